@@ -1,0 +1,412 @@
+/*
+ * CPU oracle for the CSAttention offline table build and online decode step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, written from the paper's definitions; it shares no
+ * code with the HIP library and the library never calls it.  Only the test-suite, the smoke
+ * check and the benchmark's "cpu_baseline" leg may load it.
+ *
+ * Every function cites the passage of the paper (arXiv 2604.08584) it follows.  Where the
+ * paper leaves a choice open the reading taken is stated at the function.
+ *
+ * Geometry implemented: one subspace spanning the whole head dimension, the `m` best
+ * centroids probed per query (the paper's centroid back-off of Sec. 4.4 with tau = m and a
+ * single subspace).  Everything after centroid choice (Sec. 3.3 steps 2-4) is independent of
+ * how the probed rows were chosen.
+ *
+ * Precision: the three places where floating point decides an integer are taken in fp32 with
+ * a fixed operation order, so that any implementation can reproduce them bit for bit:
+ *   - centroid-query scores and centroid-key scores: one fused-multiply-add chain over
+ *     ascending dimension, starting from +0, inputs widened from bf16;
+ *   - table scores are rounded to the grid 2^-F (round half to even) when the table is
+ *     built; with m * max|score| * 2^F < 2^24 every partial sum of at most m scores is exact
+ *     in fp32, so the per-key accumulation does not depend on the order of the additions.
+ * Attention itself (logits, softmax, weighted sum) is done in fp64.
+ *
+ * Compile with -ffp-contract=off: the only fused operations are the explicit fmaf calls.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---------------------------------------------------------------- bf16 helpers */
+
+static float bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* round-to-nearest-even fp32 -> bf16 (finite inputs) */
+static uint16_t f32_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+/* ---------------------------------------------------------------- ordering helpers */
+
+typedef struct {
+    float score;
+    int32_t idx;
+} pair_t;
+
+/* larger score first; equal scores: smaller index first (compared as real numbers, so
+ * -0 and +0 tie) */
+static int cmp_score_desc_idx_asc(const void *a, const void *b)
+{
+    const pair_t *x = (const pair_t *)a, *y = (const pair_t *)b;
+    if (x->score > y->score) return -1;
+    if (x->score < y->score) return 1;
+    if (x->idx < y->idx) return -1;
+    if (x->idx > y->idx) return 1;
+    return 0;
+}
+
+static int cmp_i32_asc(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* fp32 inner product as one fma chain over ascending dimension, from +0 */
+static float dot_chain_bf16(const uint16_t *a, const uint16_t *b, int d)
+{
+    float acc = 0.0f;
+    for (int t = 0; t < d; ++t)
+        acc = fmaf(bf16_to_f32(a[t]), bf16_to_f32(b[t]), acc);
+    return acc;
+}
+
+/* ---------------------------------------------------------------- dense attention */
+
+/*
+ * Sec. 2.1: a = softmax(q K^T / sqrt(d)), o = a V, over rows [0, n) of K and V.
+ * Also the plain definition that the sparse path must reduce to when nothing is pruned.
+ */
+void oracle_dense_attention(const uint16_t *q, const uint16_t *K, const uint16_t *V,
+                            int64_t n, int d, float *out)
+{
+    double *logit = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    double mx = -INFINITY;
+    for (int64_t i = 0; i < n; ++i) {
+        double s = 0.0;
+        for (int t = 0; t < d; ++t)
+            s += (double)bf16_to_f32(q[t]) * (double)bf16_to_f32(K[i * d + t]);
+        logit[i] = s / sqrt((double)d);
+        if (logit[i] > mx) mx = logit[i];
+    }
+    double *o = (double *)calloc((size_t)d, sizeof(double));
+    double den = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double p = exp(logit[i] - mx);
+        den += p;
+        for (int t = 0; t < d; ++t) o[t] += p * (double)bf16_to_f32(V[i * d + t]);
+    }
+    for (int t = 0; t < d; ++t) out[t] = n > 0 ? (float)(o[t] / den) : 0.0f;
+    free(o);
+    free(logit);
+}
+
+/*
+ * Sec. 3.3 step 4 ("only these K keys are used in attention") with Sec. 2.1's formula: the
+ * same softmax attention, restricted to the listed rows.  An empty list gives a zero output.
+ */
+static void attention_over(const uint16_t *q, const uint16_t *K, const uint16_t *V,
+                           const int32_t *ids, int64_t n_ids, int d, float *out)
+{
+    double *logit = (double *)malloc(sizeof(double) * (size_t)(n_ids > 0 ? n_ids : 1));
+    double mx = -INFINITY;
+    for (int64_t a = 0; a < n_ids; ++a) {
+        const uint16_t *kr = K + (int64_t)ids[a] * d;
+        double s = 0.0;
+        for (int t = 0; t < d; ++t)
+            s += (double)bf16_to_f32(q[t]) * (double)bf16_to_f32(kr[t]);
+        logit[a] = s / sqrt((double)d);
+        if (logit[a] > mx) mx = logit[a];
+    }
+    double *o = (double *)calloc((size_t)d, sizeof(double));
+    double den = 0.0;
+    for (int64_t a = 0; a < n_ids; ++a) {
+        const uint16_t *vr = V + (int64_t)ids[a] * d;
+        double p = exp(logit[a] - mx);
+        den += p;
+        for (int t = 0; t < d; ++t) o[t] += p * (double)bf16_to_f32(vr[t]);
+    }
+    for (int t = 0; t < d; ++t) out[t] = n_ids > 0 ? (float)(o[t] / den) : 0.0f;
+    free(o);
+    free(logit);
+}
+
+/* ---------------------------------------------------------------- offline: clustering */
+
+/*
+ * Sec. 3.2 (1): cosine k-means on the l2-normalised prefill queries, unit-norm centroids,
+ * k-means++ seeding, `iters` Lloyd iterations (full batch: the mini-batch size is not given).
+ *   x      [n][d] fp32 prefill queries (any scale)
+ *   u_seed [C]    uniforms in [0,1) that drive the seeding (passed in, never drawn here)
+ *   cent   [C][d] fp32 out, unit norm
+ *   objective [iters+1] out: sum_q min_j ||q~ - c_j||^2 before each iteration and after
+ *             the last one (non-increasing for Lloyd iterations).
+ * An empty cluster keeps its centroid.  Assignment ties go to the lowest centroid.
+ */
+void oracle_kmeans(const float *x, int64_t n, int d, int C, int iters, const double *u_seed,
+                   float *cent, double *objective)
+{
+    double *xn = (double *)malloc(sizeof(double) * (size_t)n * d);
+    double *c = (double *)malloc(sizeof(double) * (size_t)C * d);
+    double *dist = (double *)malloc(sizeof(double) * (size_t)n);
+    int32_t *asg = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
+    for (int64_t i = 0; i < n; ++i) {
+        double nn = 0.0;
+        for (int t = 0; t < d; ++t) nn += (double)x[i * d + t] * x[i * d + t];
+        nn = sqrt(nn);
+        for (int t = 0; t < d; ++t) xn[i * d + t] = nn > 0 ? x[i * d + t] / nn : 0.0;
+    }
+    /* k-means++: first centre uniform, then proportional to squared distance to the
+     * nearest chosen centre */
+    int64_t first = (int64_t)(u_seed[0] * (double)n);
+    if (first >= n) first = n - 1;
+    memcpy(c, xn + first * d, sizeof(double) * d);
+    for (int64_t i = 0; i < n; ++i) dist[i] = INFINITY;
+    for (int j = 1; j <= C; ++j) {
+        /* fold centre j-1 into the nearest-centre distances */
+        double tot = 0.0;
+        for (int64_t i = 0; i < n; ++i) {
+            double s = 0.0;
+            for (int t = 0; t < d; ++t) {
+                double df = xn[i * d + t] - c[(j - 1) * d + t];
+                s += df * df;
+            }
+            if (s < dist[i]) dist[i] = s;
+            tot += dist[i];
+        }
+        if (j == C) break;
+        double target = u_seed[j] * tot, run = 0.0;
+        int64_t pick = n - 1;
+        for (int64_t i = 0; i < n; ++i) {
+            run += dist[i];
+            if (run > target) { pick = i; break; }
+        }
+        memcpy(c + (size_t)j * d, xn + pick * d, sizeof(double) * d);
+    }
+    double *sum = (double *)malloc(sizeof(double) * (size_t)C * d);
+    int64_t *cnt = (int64_t *)malloc(sizeof(int64_t) * (size_t)C);
+    for (int it = 0; it <= iters; ++it) {
+        double obj = 0.0;
+        for (int64_t i = 0; i < n; ++i) {
+            int best = 0;
+            double bc = -INFINITY;
+            for (int j = 0; j < C; ++j) {
+                double s = 0.0;
+                for (int t = 0; t < d; ++t) s += xn[i * d + t] * c[(size_t)j * d + t];
+                if (s > bc) { bc = s; best = j; }
+            }
+            asg[i] = best;
+            double dd = 0.0;
+            for (int t = 0; t < d; ++t) {
+                double df = xn[i * d + t] - c[(size_t)best * d + t];
+                dd += df * df;
+            }
+            obj += dd;
+        }
+        objective[it] = obj;
+        if (it == iters) break;
+        memset(sum, 0, sizeof(double) * (size_t)C * d);
+        memset(cnt, 0, sizeof(int64_t) * (size_t)C);
+        for (int64_t i = 0; i < n; ++i) {
+            cnt[asg[i]]++;
+            for (int t = 0; t < d; ++t) sum[(size_t)asg[i] * d + t] += xn[i * d + t];
+        }
+        for (int j = 0; j < C; ++j) {
+            double nn = 0.0;
+            for (int t = 0; t < d; ++t) nn += sum[(size_t)j * d + t] * sum[(size_t)j * d + t];
+            nn = sqrt(nn);
+            if (cnt[j] == 0 || nn == 0.0) continue;
+            for (int t = 0; t < d; ++t) c[(size_t)j * d + t] = sum[(size_t)j * d + t] / nn;
+        }
+    }
+    for (size_t e = 0; e < (size_t)C * d; ++e) cent[e] = (float)c[e];
+    free(sum); free(cnt); free(xn); free(c); free(dist); free(asg);
+}
+
+/* fp32 -> bf16 rounding of a centroid matrix, done once after clustering */
+void oracle_round_bf16(const float *x, int64_t n, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = f32_to_bf16(x[i]);
+}
+
+/* ---------------------------------------------------------------- offline: table rows */
+
+/*
+ * Sec. 3.2 (2): s_j(i) = c_j . k_i for every prefill key i (raw keys, unit centroids, as the
+ * equation is written), keep the Top-L pairs, stored sorted by score (Sec. 3.1 (iii)).
+ * Ties go to the lower key index.  Scores are rounded to the grid 2^-F before the ranking.
+ * Rows shorter than L (n_pre < L) are padded with idx = -1, score = 0.
+ *   K        [n_pre][d] bf16     cent [C][d] bf16
+ *   row_ids  [n_rows]  which centroids to build (any subset, any order)
+ *   idx_out / score_out [n_rows][L]
+ * Returns the largest |q| = |round(s * 2^F)| seen, as a double (for the exactness check
+ * m * max|q| < 2^24).
+ */
+double oracle_build_rows(const uint16_t *K, int64_t n_pre, int d, const uint16_t *cent,
+                         const int32_t *row_ids, int n_rows, int L, int F,
+                         int32_t *idx_out, float *score_out)
+{
+    double max_abs_q = 0.0;
+    const float up = ldexpf(1.0f, F), down = ldexpf(1.0f, -F);
+#pragma omp parallel for schedule(dynamic) reduction(max : max_abs_q)
+    for (int r = 0; r < n_rows; ++r) {
+        pair_t *all = (pair_t *)malloc(sizeof(pair_t) * (size_t)(n_pre > 0 ? n_pre : 1));
+        const uint16_t *c = cent + (int64_t)row_ids[r] * d;
+        for (int64_t i = 0; i < n_pre; ++i) {
+            float s = dot_chain_bf16(c, K + i * d, d);
+            float qf = rintf(s * up); /* default rounding mode: half to even */
+            if (fabs((double)qf) > max_abs_q) max_abs_q = fabs((double)qf);
+            all[i].score = qf * down;
+            all[i].idx = (int32_t)i;
+        }
+        qsort(all, (size_t)n_pre, sizeof(pair_t), cmp_score_desc_idx_asc);
+        for (int p = 0; p < L; ++p) {
+            if (p < n_pre) {
+                idx_out[(int64_t)r * L + p] = all[p].idx;
+                score_out[(int64_t)r * L + p] = all[p].score;
+            } else {
+                idx_out[(int64_t)r * L + p] = -1;
+                score_out[(int64_t)r * L + p] = 0.0f;
+            }
+        }
+        free(all);
+    }
+    return max_abs_q;
+}
+
+/* ---------------------------------------------------------------- online: decode */
+
+/*
+ * Sec. 3.3 step 1 with the back-off of Sec. 4.4: z_j = q . c_j, the m largest, ties to the
+ * lower j.  q is not normalised: a positive factor cannot change the ranking.
+ */
+void oracle_top_centroids(const uint16_t *q, const uint16_t *cent, int C, int d, int m,
+                          int32_t *rows_out, float *z_out /* [C] or NULL */)
+{
+    pair_t *z = (pair_t *)malloc(sizeof(pair_t) * (size_t)C);
+    for (int j = 0; j < C; ++j) {
+        z[j].score = dot_chain_bf16(q, cent + (int64_t)j * d, d);
+        z[j].idx = j;
+        if (z_out) z_out[j] = z[j].score;
+    }
+    qsort(z, (size_t)C, sizeof(pair_t), cmp_score_desc_idx_asc);
+    for (int r = 0; r < m; ++r) rows_out[r] = r < C ? z[r].idx : -1;
+    free(z);
+}
+
+/*
+ * Sec. 3.3 steps 2-4 for one query head, given the probed rows.
+ *   step 2: read the m rows (I_j, V_j) -> up to m*L (idx, score) pairs;
+ *   step 3: score(i) = sum over the probed rows that contain i of that row's score for i
+ *           (w_b = 1); U = the keys that occur in at least one probed row; a key that is
+ *           absent from a row gets nothing from it;
+ *   step 4: keep the min(k, |U|) members of U with the largest score, ties to the lower
+ *           index; reported in ascending index order, padded with -1.
+ * acc_out (optional, [n_pre]) receives score(i), NaN for keys outside U.
+ * Returns |U|.
+ */
+int64_t oracle_select_keys(const int32_t *tbl_idx, const float *tbl_score, int L,
+                           const int32_t *rows, int m, int64_t n_pre, int k,
+                           int32_t *sel_out, int32_t *sel_count, float *acc_out)
+{
+    float *acc = (float *)calloc((size_t)(n_pre > 0 ? n_pre : 1), sizeof(float));
+    uint8_t *seen = (uint8_t *)calloc((size_t)(n_pre > 0 ? n_pre : 1), 1);
+    for (int r = 0; r < m; ++r) {
+        if (rows[r] < 0) continue;
+        const int32_t *I = tbl_idx + (int64_t)rows[r] * L;
+        const float *S = tbl_score + (int64_t)rows[r] * L;
+        for (int p = 0; p < L; ++p) {
+            int32_t i = I[p];
+            if (i < 0) continue;
+            acc[i] += S[p];
+            seen[i] = 1;
+        }
+    }
+    int64_t nU = 0;
+    for (int64_t i = 0; i < n_pre; ++i) nU += seen[i];
+    pair_t *u = (pair_t *)malloc(sizeof(pair_t) * (size_t)(nU > 0 ? nU : 1));
+    int64_t w = 0;
+    for (int64_t i = 0; i < n_pre; ++i)
+        if (seen[i]) {
+            u[w].score = acc[i];
+            u[w].idx = (int32_t)i;
+            ++w;
+        }
+    qsort(u, (size_t)nU, sizeof(pair_t), cmp_score_desc_idx_asc);
+    int keff = (int64_t)k < nU ? k : (int)nU;
+    for (int a = 0; a < keff; ++a) sel_out[a] = u[a].idx;
+    qsort(sel_out, (size_t)keff, sizeof(int32_t), cmp_i32_asc);
+    for (int a = keff; a < k; ++a) sel_out[a] = -1;
+    *sel_count = keff;
+    if (acc_out)
+        for (int64_t i = 0; i < n_pre; ++i) acc_out[i] = seen[i] ? acc[i] : NAN;
+    free(u); free(acc); free(seen);
+    return nU;
+}
+
+/*
+ * One decode step for one query head: Sec. 3.3 steps 1-4 followed by exact attention over
+ * the selected keys plus every key appended after prefill, rows [n_pre, n) (the recent
+ * window: always attended, never competing for the k slots).
+ *   q [d], cent [C][d], K / V [>= n][d] bf16; tables [C][L].
+ *   rows_out [m], sel_out [k] (ascending, -1 padded), sel_count [1], out [d] fp32.
+ */
+void oracle_decode_head(const uint16_t *q, const uint16_t *cent, int C, int d,
+                        const int32_t *tbl_idx, const float *tbl_score, int L, int m, int k,
+                        const uint16_t *K, const uint16_t *V, int64_t n_pre, int64_t n,
+                        int32_t *rows_out, int32_t *sel_out, int32_t *sel_count, float *out)
+{
+    oracle_top_centroids(q, cent, C, d, m, rows_out, NULL);
+    oracle_select_keys(tbl_idx, tbl_score, L, rows_out, m, n_pre, k, sel_out, sel_count, NULL);
+    int64_t n_att = *sel_count + (n - n_pre);
+    int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_att > 0 ? n_att : 1));
+    for (int a = 0; a < *sel_count; ++a) ids[a] = sel_out[a];
+    for (int64_t i = n_pre; i < n; ++i) ids[*sel_count + (i - n_pre)] = (int32_t)i;
+    attention_over(q, K, V, ids, n_att, d, out);
+    free(ids);
+}
+
+/*
+ * The same step for a list of independent (sequence, query head) items, spread over
+ * `n_threads` OpenMP threads (0 = the runtime's default).  Item t uses q[t], cent[t] (its KV
+ * head's centroids), tbl_idx[t] / tbl_score[t] (its KV head's tables) and K[t] / V[t] (its KV
+ * head's cache); outputs are packed [n_items][m], [n_items][k], [n_items], [n_items][d].
+ * Returns the number of threads used.
+ */
+int oracle_decode_items(int n_items, const uint16_t *const *q, const uint16_t *const *cent,
+                        const int32_t *const *tbl_idx, const float *const *tbl_score,
+                        const uint16_t *const *K, const uint16_t *const *V, int C, int d, int L,
+                        int m, int k, int64_t n_pre, int64_t n, int32_t *rows_out,
+                        int32_t *sel_out, int32_t *sel_count, float *out, int n_threads)
+{
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+    }
+#endif
+#pragma omp parallel for schedule(dynamic)
+    for (int t = 0; t < n_items; ++t)
+        oracle_decode_head(q[t], cent[t], C, d, tbl_idx[t], tbl_score[t], L, m, k, K[t], V[t],
+                           n_pre, n, rows_out + (int64_t)t * m, sel_out + (int64_t)t * k,
+                           sel_count + t, out + (int64_t)t * d);
+    return used;
+}

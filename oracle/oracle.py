@@ -1,0 +1,157 @@
+"""ctypes loader for the CPU oracle (oracle/csa_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg.  The HIP library and its Python binding never import this module.
+
+bf16 tensors cross this boundary as numpy uint16 arrays holding the raw bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "csa_oracle.c")
+_LIB = os.path.join(_HERE, "libcsa_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no contraction: the only fused ops are explicit fmaf)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call([
+            "gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+            "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.oracle_build_rows.restype = C.c_double
+        _lib.oracle_select_keys.restype = C.c_int64
+        _lib.oracle_decode_items.restype = C.c_int
+    return _lib
+
+
+def _p(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"], "oracle arrays must be C-contiguous"
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def bf16_bits(t) -> np.ndarray:
+    """torch bf16 tensor (any device) -> numpy uint16 bit patterns (host, contiguous)."""
+    import torch
+    assert t.dtype == torch.bfloat16
+    return t.detach().contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def bits_to_f32(a: np.ndarray) -> np.ndarray:
+    return (a.astype(np.uint32) << 16).view(np.float32)
+
+
+def dense_attention(q, K, V, n):
+    d = q.shape[-1]
+    out = np.empty(d, np.float32)
+    lib().oracle_dense_attention(_p(q), _p(K), _p(V), C.c_int64(n), C.c_int(d), _p(out))
+    return out
+
+
+def kmeans(x, n_centroids, iters, u_seed):
+    x = np.ascontiguousarray(x, np.float32)
+    u_seed = np.ascontiguousarray(u_seed, np.float64)
+    assert u_seed.shape[0] >= n_centroids
+    n, d = x.shape
+    cent = np.empty((n_centroids, d), np.float32)
+    obj = np.empty(iters + 1, np.float64)
+    lib().oracle_kmeans(_p(x), C.c_int64(n), C.c_int(d), C.c_int(n_centroids), C.c_int(iters),
+                        _p(u_seed), _p(cent), _p(obj))
+    return cent, obj
+
+
+def round_bf16(x):
+    x = np.ascontiguousarray(x, np.float32)
+    out = np.empty(x.shape, np.uint16)
+    lib().oracle_round_bf16(_p(x), C.c_int64(x.size), _p(out))
+    return out
+
+
+def build_rows(K, n_pre, cent, row_ids, L, F):
+    """Rows `row_ids` of one KV head's table.  Returns (idx [r][L] i32, score [r][L] f32,
+    max|q|)."""
+    d = K.shape[-1]
+    row_ids = np.ascontiguousarray(row_ids, np.int32)
+    idx = np.empty((len(row_ids), L), np.int32)
+    score = np.empty((len(row_ids), L), np.float32)
+    mx = lib().oracle_build_rows(_p(K), C.c_int64(n_pre), C.c_int(d), _p(cent), _p(row_ids),
+                                 C.c_int(len(row_ids)), C.c_int(L), C.c_int(F), _p(idx),
+                                 _p(score))
+    return idx, score, mx
+
+
+def build_tables(K, n_pre, cent, L, F):
+    return build_rows(K, n_pre, cent, np.arange(cent.shape[0], dtype=np.int32), L, F)
+
+
+def top_centroids(q, cent, m):
+    n_c, d = cent.shape
+    rows = np.empty(m, np.int32)
+    z = np.empty(n_c, np.float32)
+    lib().oracle_top_centroids(_p(q), _p(cent), C.c_int(n_c), C.c_int(d), C.c_int(m), _p(rows),
+                               _p(z))
+    return rows, z
+
+
+def select_keys(tbl_idx, tbl_score, rows, n_pre, k):
+    """Returns (sel [k] ascending / -1 padded, count, |U|, acc [n_pre] with NaN outside U)."""
+    L = tbl_idx.shape[-1]
+    rows = np.ascontiguousarray(rows, np.int32)
+    sel = np.empty(max(k, 1), np.int32)
+    cnt = np.zeros(1, np.int32)
+    acc = np.empty(max(n_pre, 1), np.float32)
+    nU = lib().oracle_select_keys(_p(tbl_idx), _p(tbl_score), C.c_int(L), _p(rows),
+                                  C.c_int(len(rows)), C.c_int64(n_pre), C.c_int(k), _p(sel),
+                                  _p(cnt), _p(acc))
+    return sel[:k], int(cnt[0]), int(nU), acc[:n_pre]
+
+
+def decode_head(q, cent, tbl_idx, tbl_score, m, k, K, V, n_pre, n):
+    """One query head.  Returns (rows [m], sel [k], count, out [d])."""
+    n_c, d = cent.shape
+    L = tbl_idx.shape[-1]
+    rows = np.empty(m, np.int32)
+    sel = np.empty(max(k, 1), np.int32)
+    cnt = np.zeros(1, np.int32)
+    out = np.empty(d, np.float32)
+    lib().oracle_decode_head(_p(q), _p(cent), C.c_int(n_c), C.c_int(d), _p(tbl_idx),
+                             _p(tbl_score), C.c_int(L), C.c_int(m), C.c_int(k), _p(K), _p(V),
+                             C.c_int64(n_pre), C.c_int64(n), _p(rows), _p(sel), _p(cnt), _p(out))
+    return rows, sel[:k], int(cnt[0]), out
+
+
+def decode_items(items, m, k, n_pre, n, n_threads=0):
+    """items: list of dicts(q [d], cent [C][d], tbl_idx [C][L], tbl_score [C][L], K, V) whose
+    arrays stay alive for the call.  Returns (rows [n][m], sel [n][k], cnt [n], out [n][d],
+    threads_used)."""
+    n_it = len(items)
+    n_c, d = items[0]["cent"].shape
+    L = items[0]["tbl_idx"].shape[-1]
+    arr = lambda key: (C.c_void_p * n_it)(*[it[key].ctypes.data for it in items])
+    for it in items:
+        for key in ("q", "cent", "tbl_idx", "tbl_score", "K", "V"):
+            assert it[key].flags["C_CONTIGUOUS"]
+    rows = np.empty((n_it, m), np.int32)
+    sel = np.empty((n_it, max(k, 1)), np.int32)
+    cnt = np.zeros(n_it, np.int32)
+    out = np.empty((n_it, d), np.float32)
+    used = lib().oracle_decode_items(
+        C.c_int(n_it), arr("q"), arr("cent"), arr("tbl_idx"), arr("tbl_score"), arr("K"),
+        arr("V"), C.c_int(n_c), C.c_int(d), C.c_int(L), C.c_int(m), C.c_int(k),
+        C.c_int64(n_pre), C.c_int64(n), _p(rows), _p(sel), _p(cnt), _p(out), C.c_int(n_threads))
+    return rows, sel[:, :k], cnt, out, used

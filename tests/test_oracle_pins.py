@@ -1,0 +1,503 @@
+"""Pins for the CPU oracle: checks against what the paper's definitions and the mathematics
+fix, none of which call back into the oracle's own arithmetic.
+
+Each test names the mistake it is meant to catch.  The paper prints no worked numeric example;
+tests/golden/ holds a hand-worked one derived from Sec. 3.3's definitions.
+"""
+import fractions
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ helpers (independent)
+
+def to_bits(x):
+    """float array whose values are exactly representable in bf16 -> uint16 bit patterns."""
+    x = np.ascontiguousarray(x, np.float32)
+    u = x.view(np.uint32)
+    assert np.all((u & 0xFFFF) == 0), "test value not representable in bf16"
+    return (u >> 16).astype(np.uint16)
+
+
+def rand_bf16(rng, shape, scale=1.0):
+    x = (rng.standard_normal(shape) * scale).astype(np.float32)
+    u = x.view(np.uint32)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return (u >> 16).astype(np.uint16)
+
+
+def f32(bits):
+    return oracle.bits_to_f32(bits)
+
+
+def round_to_f32(fr: fractions.Fraction) -> np.float32:
+    """Correctly rounded (half to even) fp32 of an exact rational, without double rounding."""
+    if fr == 0:
+        return np.float32(0.0)
+    guess = np.float32(float(fr))
+    cands = {guess, np.nextafter(guess, np.float32(np.inf)), np.nextafter(guess, np.float32(-np.inf))}
+    best = None
+    for c in cands:
+        err = abs(fractions.Fraction(float(c)) - fr)
+        even = (int(np.float32(c).view(np.uint32)) & 1) == 0
+        key = (err, 0 if even else 1)
+        if best is None or key < best[0]:
+            best = (key, c)
+    return np.float32(best[1])
+
+
+def fma_chain_exact(a_bits, b_bits):
+    """acc <- round_fp32(a_t * b_t + acc) over ascending t, in exact rational arithmetic."""
+    acc = np.float32(0.0)
+    for x, y in zip(f32(a_bits), f32(b_bits)):
+        acc = round_to_f32(fractions.Fraction(float(x)) * fractions.Fraction(float(y))
+                           + fractions.Fraction(float(acc)))
+    return acc
+
+
+def random_tables(rng, n_rows, L, n_pre, F, qmax, fill=None):
+    """Rows of distinct key indices with grid scores, sorted (score desc, idx asc)."""
+    idx = np.full((n_rows, L), -1, np.int32)
+    score = np.zeros((n_rows, L), np.float32)
+    for r in range(n_rows):
+        n = min(L, n_pre) if fill is None else fill
+        ids = rng.choice(n_pre, size=n, replace=False).astype(np.int32)
+        q = rng.integers(-qmax, qmax + 1, size=n)
+        order = np.lexsort((ids, -q))
+        idx[r, :n] = ids[order]
+        score[r, :n] = (q[order] * 2.0 ** -F).astype(np.float32)
+    return idx, score
+
+
+def brute_select(idx, score, rows, k, F):
+    """Dictionary accumulation in exact integers, then a full sort by (-sum, index)."""
+    acc = {}
+    for r in rows:
+        for i, s in zip(idx[r], score[r]):
+            if i < 0:
+                continue
+            q = fractions.Fraction(float(s)) * 2 ** F
+            assert q.denominator == 1
+            acc[int(i)] = acc.get(int(i), 0) + int(q)
+    ranked = sorted(acc.items(), key=lambda kv: (-kv[1], kv[0]))
+    return sorted(i for i, _ in ranked[:k]), acc
+
+
+def softmax_attention_np(q_bits, K_bits, V_bits, ids):
+    q, K, V = f32(q_bits).astype(np.float64), f32(K_bits).astype(np.float64), f32(V_bits).astype(np.float64)
+    lg = K[ids] @ q / math.sqrt(q.shape[0])
+    p = np.exp(lg - lg.max())
+    return (p / p.sum()) @ V[ids]
+
+
+# ------------------------------------------------------------------ dense attention (Sec. 2.1)
+
+def test_dense_two_keys_closed_form():
+    """d = 16 so sqrt(d) = 4: logits 4/4 = 1 and 0 -> weights e/(1+e), 1/(1+e).
+    Catches a missing or wrong 1/sqrt(d), a transposed operand, a missing max subtraction."""
+    d = 16
+    q = to_bits(np.ones(d))
+    K = to_bits(np.stack([np.r_[np.ones(4), np.zeros(12)], np.zeros(d)]))
+    V = to_bits(np.stack([np.r_[2.0, np.zeros(15)], np.r_[0.0, -4.0, np.zeros(14)]]))
+    o = oracle.dense_attention(q, K, V, 2)
+    w = math.e / (1 + math.e)
+    assert o[0] == pytest.approx(2 * w, rel=1e-6)
+    assert o[1] == pytest.approx(-4 * (1 - w), rel=1e-6)
+    assert np.all(o[2:] == 0)
+
+
+def test_dense_equal_keys_is_mean_and_large_logits_do_not_overflow():
+    rng = np.random.default_rng(1)
+    d, n = 128, 37
+    q = rand_bf16(rng, d, 30.0)                       # logits of order 1e3: exp overflows
+    K = np.tile(rand_bf16(rng, d, 30.0), (n, 1))      # without the max subtraction
+    V = rand_bf16(rng, (n, d))
+    o = oracle.dense_attention(q, K, V, n)
+    np.testing.assert_allclose(o, f32(V).astype(np.float64).mean(0), rtol=1e-6, atol=1e-6)
+
+
+def test_dense_prefix_only():
+    """Only rows [0, n) may contribute (catches an off-by-one in the context length)."""
+    rng = np.random.default_rng(2)
+    d = 128
+    q, K, V = rand_bf16(rng, d), rand_bf16(rng, (50, d)), rand_bf16(rng, (50, d))
+    o = oracle.dense_attention(q, K, V, 31)
+    np.testing.assert_allclose(o, softmax_attention_np(q, K, V, np.arange(31)), rtol=1e-5, atol=1e-6)
+    assert np.all(oracle.dense_attention(q, K, V, 1) == f32(V[0]))
+
+
+# ------------------------------------------------------------------ step 1: centroid ranking
+
+def test_centroid_scores_follow_the_fma_chain():
+    """Values with heavy cancellation make the result depend on the order and on the fusing;
+    the exact-rational emulation pins ascending order, start at +0, one rounding per step."""
+    rng = np.random.default_rng(3)
+    d, n_c = 128, 6
+    q = rand_bf16(rng, d, 50.0)
+    cent = rand_bf16(rng, (n_c, d), 50.0)
+    # plant cancellations: consecutive dimensions with opposite huge products
+    qf, cf = f32(q).copy(), f32(cent).copy()
+    qf[10], qf[11] = 3.0e4, -3.0e4
+    cf[:, 10] = 2.0e4
+    cf[:, 11] = 2.0e4
+    q, cent = to_bits(rand_round(qf)), to_bits(rand_round(cf))
+    _, z = oracle.top_centroids(q, cent, 1)
+    ref = np.array([fma_chain_exact(q, cent[j]) for j in range(n_c)], np.float32)
+    assert np.array_equal(z.view(np.uint32), ref.view(np.uint32))
+    # and the order matters on this input: the reversed chain differs somewhere
+    rev = np.array([fma_chain_exact(q[::-1], cent[j][::-1]) for j in range(n_c)], np.float32)
+    assert not np.array_equal(rev.view(np.uint32), ref.view(np.uint32))
+
+
+def rand_round(x):
+    """fp32 -> nearest bf16-representable fp32."""
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.view(np.float32)
+
+
+def test_top_centroids_against_full_sort_with_ties():
+    """Small-integer data: every inner product is exact, many ties; expected ranking from
+    integer arithmetic and Python's sort.  Catches ascending/descending and tie-rule slips."""
+    rng = np.random.default_rng(4)
+    d, n_c = 128, 40
+    qv = rng.integers(-2, 3, d).astype(np.float32)
+    cv = rng.integers(-1, 2, (n_c, d)).astype(np.float32)
+    cv[7] = cv[3]; cv[21] = cv[3]                       # exact ties
+    z_int = (cv.astype(np.int64) @ qv.astype(np.int64))
+    order = sorted(range(n_c), key=lambda j: (-z_int[j], j))
+    for m in (1, 4, 17, n_c):
+        rows, z = oracle.top_centroids(to_bits(qv), to_bits(cv), m)
+        assert list(rows) == order[:m]
+        assert np.array_equal(z, z_int.astype(np.float32))
+
+
+def test_query_scale_does_not_change_the_ranking():
+    """Sec. 3.3 step 1 normalises q; a positive power-of-two factor (exact in bf16) must give
+    the same rows, which is why the normalisation is skipped."""
+    rng = np.random.default_rng(5)
+    q = rand_bf16(rng, 128)
+    cent = rand_bf16(rng, (64, 128), 0.1)
+    r1, _ = oracle.top_centroids(q, cent, 8)
+    r2, _ = oracle.top_centroids(to_bits(f32(q) * 0.25), cent, 8)
+    assert np.array_equal(r1, r2)
+
+
+# ------------------------------------------------------------------ offline rows (Sec. 3.2 (2))
+
+def test_build_rows_single_centroid_is_the_sorted_top_L():
+    """C = 1 on exact (small-integer) data: the row must be the library-sorted Top-L of c.k,
+    ties to the lower index.  Catches key/centroid transposition, wrong sort direction."""
+    rng = np.random.default_rng(6)
+    d, n, L, F = 128, 300, 32, 3
+    Kv = rng.integers(-3, 4, (n, d)).astype(np.float32)
+    c = (rng.integers(-4, 5, (1, d)) / 8.0).astype(np.float32)      # multiples of 1/8: F = 3 is exact
+    s = (Kv.astype(np.float64) @ c[0].astype(np.float64))
+    order = np.lexsort((np.arange(n), -s))[:L]
+    idx, score, mx = oracle.build_rows(to_bits(Kv), n, to_bits(c), [0], L, F)
+    assert np.array_equal(idx[0], order)
+    assert np.array_equal(score[0], s[order].astype(np.float32))
+    assert mx == np.abs(s * 8).max()
+
+
+def test_build_rows_grid_rounding_half_to_even():
+    """One-dimensional products landing exactly on half grid steps."""
+    d, F = 128, 1                                  # grid 0.5
+    Kv = np.zeros((6, d), np.float32)
+    Kv[:, 0] = [0.25, 0.75, 1.25, -0.25, -0.75, 0.5]   # x 2 -> .5 1.5 2.5 -.5 -1.5 1
+    c = np.zeros((1, d), np.float32); c[0, 0] = 1.0
+    idx, score, _ = oracle.build_rows(to_bits(Kv), 6, to_bits(c), [0], 6, F)
+    got = dict(zip(idx[0].tolist(), score[0].tolist()))
+    assert got == {0: 0.0, 1: 1.0, 2: 1.0, 3: -0.0, 4: -1.0, 5: 0.5}
+    # ranking: 1.0 (keys 1, 2), 0.5 (5), 0 (0, 3), -1 (4)
+    assert idx[0].tolist() == [1, 2, 5, 0, 3, 4]
+
+
+def test_build_rows_invariants_on_the_synthetic_mixture():
+    """Sec. 3.1 (iii): L distinct indices, sorted by score, nothing outside the row beats the
+    row's minimum; scores sit on the grid; padding when n_pre < L."""
+    rng = np.random.default_rng(7)
+    d, n, n_c, L, F = 128, 700, 5, 64, 14
+    K = rand_bf16(rng, (n, d))
+    cent = rand_bf16(rng, (n_c, d), 1 / math.sqrt(d))
+    idx, score, mx = oracle.build_tables(K, n, cent, L, F)
+    s64 = f32(K).astype(np.float64) @ f32(cent).astype(np.float64).T
+    for j in range(n_c):
+        assert len(set(idx[j].tolist())) == L and idx[j].min() >= 0 and idx[j].max() < n
+        assert np.all(np.diff(score[j]) <= 0)
+        ties = np.diff(score[j]) == 0
+        assert np.all(np.diff(idx[j])[ties] > 0)
+        assert np.all(score[j] * 2.0 ** F == np.rint(score[j] * 2.0 ** F))
+        np.testing.assert_allclose(score[j], s64[idx[j], j], atol=2.0 ** -F + 1e-4)
+        outside = np.setdiff1d(np.arange(n), idx[j])
+        assert s64[outside, j].max() <= score[j, -1] + 2.0 ** -F + 1e-4
+    assert mx == pytest.approx(np.abs(np.rint(s64 * 2 ** F)).max(), rel=1e-3)
+    idx2, score2, _ = oracle.build_rows(K, 10, cent, [2], 16, F)
+    assert sorted(idx2[0, :10].tolist()) == list(range(10))
+    assert np.all(idx2[0, 10:] == -1) and np.all(score2[0, 10:] == 0)
+
+
+def test_build_rows_subset_equals_full():
+    rng = np.random.default_rng(8)
+    K, cent = rand_bf16(rng, (200, 128)), rand_bf16(rng, (9, 128), 0.1)
+    full_i, full_s, _ = oracle.build_tables(K, 200, cent, 16, 12)
+    sub_i, sub_s, _ = oracle.build_rows(K, 200, cent, [5, 1], 16, 12)
+    assert np.array_equal(sub_i, full_i[[5, 1]]) and np.array_equal(sub_s, full_s[[5, 1]])
+
+
+# ------------------------------------------------------------------ steps 2-4: select_keys
+
+@pytest.mark.parametrize("seed", range(6))
+def test_select_brute_force_tiny(seed):
+    """Dictionary accumulation + full sort on tiny inputs with many ties (qmax small).
+    Catches: dropped rows, wrong tie rule, output order, padding, count."""
+    rng = np.random.default_rng(100 + seed)
+    n_pre, n_c, L, m, F = 64, 8, 16, 4, 4
+    idx, score = random_tables(rng, n_c, L, n_pre, F, qmax=3, fill=int(rng.integers(5, L + 1)))
+    rows = rng.choice(n_c, m, replace=False).astype(np.int32)
+    for k in (1, 7, 20, 64):
+        sel, cnt, nU, acc = oracle.select_keys(idx, score, rows, n_pre, k)
+        want, acc_ref = brute_select(idx, score, rows, k, F)
+        assert nU == len(acc_ref) <= m * L                   # |U| <= mL (App. C.2)
+        assert cnt == min(k, nU) == len(want)
+        assert sel[:cnt].tolist() == want
+        assert np.all(sel[cnt:] == -1)
+        for i in range(n_pre):
+            if i in acc_ref:
+                assert acc[i] == acc_ref[i] * 2.0 ** -F
+            else:
+                assert np.isnan(acc[i])                       # absent keys are not in U
+
+
+def test_select_order_invariance_and_exact_sums():
+    """Permuting entries inside rows and the order of the probed rows leaves the selection
+    bit-identical, and the fp32 sums equal the exact integer sums scaled back (grid rule:
+    m * max|q| < 2^24)."""
+    rng = np.random.default_rng(9)
+    n_pre, n_c, L, m, F = 5000, 12, 512, 8, 14
+    qmax = (1 << 24) // m - 1
+    idx, score = random_tables(rng, n_c, L, n_pre, F, qmax)
+    rows = rng.choice(n_c, m, replace=False).astype(np.int32)
+    sel0, cnt0, nU0, acc0 = oracle.select_keys(idx, score, rows, n_pre, 300)
+    _, acc_ref = brute_select(idx, score, rows, 300, F)
+    seen = ~np.isnan(acc0)
+    assert seen.sum() == len(acc_ref)
+    for i, v in acc_ref.items():
+        assert float(acc0[i]) == v * 2.0 ** -F
+    for trial in range(4):
+        idx2, score2 = idx.copy(), score.copy()
+        for r in range(n_c):
+            p = rng.permutation(L)
+            idx2[r], score2[r] = idx[r, p], score[r, p]
+        rows2 = rng.permutation(rows).astype(np.int32)
+        sel, cnt, nU, acc = oracle.select_keys(idx2, score2, rows2, n_pre, 300)
+        assert cnt == cnt0 and nU == nU0 and np.array_equal(sel, sel0)
+        assert np.array_equal(acc.view(np.uint32), acc0.view(np.uint32))
+
+
+def test_select_single_row_is_the_row_prefix():
+    """m = 1: score(i) is that row's score, so the selection is the first k entries of the
+    (score desc, idx asc) row, re-sorted by index."""
+    rng = np.random.default_rng(10)
+    idx, score = random_tables(rng, 3, 128, 1000, 10, qmax=20)        # heavy ties
+    for k in (1, 50, 128, 200):
+        sel, cnt, nU, _ = oracle.select_keys(idx, score, np.array([1], np.int32), 1000, k)
+        assert nU == 128 and cnt == min(k, 128)
+        assert sel[:cnt].tolist() == sorted(idx[1, :cnt].tolist())
+
+
+def test_select_budget_at_least_union_returns_union():
+    rng = np.random.default_rng(11)
+    idx, score = random_tables(rng, 6, 40, 300, 8, qmax=1000, fill=33)
+    rows = np.array([0, 2, 5], np.int32)
+    sel, cnt, nU, _ = oracle.select_keys(idx, score, rows, 300, 250)
+    U = sorted(set(idx[rows].ravel().tolist()) - {-1})
+    assert nU == len(U) == cnt and sel[:cnt].tolist() == U and np.all(sel[cnt:] == -1)
+
+
+def test_select_negative_sums_and_zero_sum_members():
+    """A key whose scores cancel to 0 is still in U and outranks negative sums; keys never
+    listed are not selectable even when every listed sum is negative."""
+    idx = np.array([[0, 1, 2, -1], [1, 3, 0, -1]], np.int32)
+    score = np.array([[1.0, 0.5, -2.0, 0], [-0.5, -1.0, -3.0, 0]], np.float32)
+    # sums: key0 = -2, key1 = 0, key2 = -2, key3 = -1 ; keys 4.. never listed
+    sel, cnt, nU, acc = oracle.select_keys(idx, score, np.array([0, 1], np.int32), 8, 3)
+    assert nU == 4 and cnt == 3 and sel.tolist() == [0, 1, 3]       # tie -2: key 0 beats key 2
+    sel, cnt, _, _ = oracle.select_keys(idx, score, np.array([0, 1], np.int32), 8, 6)
+    assert cnt == 4 and sel.tolist() == [0, 1, 2, 3, -1, -1]
+
+
+# ------------------------------------------------------------------ whole step
+
+def _dense_tables(n_pre, n_c, rng, F=10):
+    """Every key in every row (L = n_pre), arbitrary grid scores."""
+    idx = np.empty((n_c, n_pre), np.int32)
+    score = np.empty((n_c, n_pre), np.float32)
+    for j in range(n_c):
+        q = rng.integers(-500, 500, n_pre)
+        order = np.lexsort((np.arange(n_pre), -q))
+        idx[j], score[j] = order, q[order] * 2.0 ** -F
+    return idx, score
+
+
+@pytest.mark.parametrize("m", [1, 3])
+def test_decode_with_nothing_pruned_is_dense_attention(m):
+    """L = N_pre and k = N_pre: sel = all prefill keys and the output equals Sec. 2.1's dense
+    attention over [0, n) (appended keys included)."""
+    rng = np.random.default_rng(12)
+    d, n_pre, n, n_c = 128, 257, 263, 5
+    q, cent = rand_bf16(rng, d), rand_bf16(rng, (n_c, d), 0.1)
+    K, V = rand_bf16(rng, (n, d)), rand_bf16(rng, (n, d))
+    idx, score = _dense_tables(n_pre, n_c, rng)
+    rows, sel, cnt, out = oracle.decode_head(q, cent, idx, score, m, n_pre, K, V, n_pre, n)
+    assert cnt == n_pre and sel.tolist() == list(range(n_pre))
+    dense = oracle.dense_attention(q, K, V, n)
+    np.testing.assert_allclose(out, dense, rtol=0, atol=1e-6)
+    np.testing.assert_allclose(out, softmax_attention_np(q, K, V, np.arange(n)), atol=1e-6)
+
+
+def test_decode_zero_budget_attends_appended_keys_only():
+    rng = np.random.default_rng(13)
+    d, n_pre, n = 128, 100, 109
+    q, cent = rand_bf16(rng, d), rand_bf16(rng, (4, d))
+    K, V = rand_bf16(rng, (n, d)), rand_bf16(rng, (n, d))
+    idx, score = random_tables(rng, 4, 16, n_pre, 8, 100)
+    _, sel, cnt, out = oracle.decode_head(q, cent, idx, score, 2, 0, K, V, n_pre, n)
+    assert cnt == 0
+    want = oracle.dense_attention(q, np.ascontiguousarray(K[n_pre:]), np.ascontiguousarray(V[n_pre:]), n - n_pre)
+    np.testing.assert_allclose(out, want, atol=1e-6)
+    # nothing selected and nothing appended: defined as a zero output
+    _, _, cnt, out = oracle.decode_head(q, cent, idx, score, 2, 0, K, V, n_pre, n_pre)
+    assert cnt == 0 and np.all(out == 0)
+
+
+def test_decode_output_is_a_convex_combination_of_attended_values():
+    """Softmax weights are non-negative and sum to 1 (Sec. 2.1): each output coordinate lies
+    between the min and max of the attended value rows, and equals the numpy softmax over
+    exactly sel + appended."""
+    rng = np.random.default_rng(14)
+    d, n_pre, n, n_c, L, m, k = 128, 900, 905, 10, 64, 4, 40
+    q, cent = rand_bf16(rng, d), rand_bf16(rng, (n_c, d), 0.1)
+    K, V = rand_bf16(rng, (n, d)), rand_bf16(rng, (n, d))
+    idx, score = random_tables(rng, n_c, L, n_pre, 12, 5000)
+    rows, sel, cnt, out = oracle.decode_head(q, cent, idx, score, m, k, K, V, n_pre, n)
+    want_rows, _ = oracle.top_centroids(q, cent, m)
+    assert np.array_equal(rows, want_rows)
+    want_sel, _ = brute_select(idx, score, rows, k, 12)
+    assert sel[:cnt].tolist() == want_sel
+    ids = np.r_[sel[:cnt], np.arange(n_pre, n)]
+    Vf = f32(V)[ids]
+    assert np.all(out <= Vf.max(0) + 1e-6) and np.all(out >= Vf.min(0) - 1e-6)
+    np.testing.assert_allclose(out, softmax_attention_np(q, K, V, ids), atol=1e-6)
+
+
+def test_single_cluster_recall_is_one():
+    """Query-centric argument of Sec. 2.4: if every prefill query is a positive multiple of one
+    direction u and the decode query is too, one centroid (= u) with L >= k retrieves exactly
+    the true top-k of q.K.  Data are small integers so all scores are exact and tie-free
+    where it matters."""
+    rng = np.random.default_rng(15)
+    d, n, k, F = 128, 500, 25, 0
+    u = np.zeros(d, np.float32); u[5] = 1.0                      # unit direction, exact in bf16
+    Kv = rng.integers(-3, 4, (n, d)).astype(np.float32)
+    Kv[:, 5] = rng.permutation(n).astype(np.float32) - 250       # distinct integer scores (bf16-exact: |x| <= 256)
+    cent, _ = oracle.kmeans(np.outer(rng.uniform(0.5, 3, 64), u), 1, 3, np.array([0.3]))
+    cent_b = oracle.round_bf16(cent)
+    assert np.array_equal(f32(cent_b)[0], u)
+    idx, score, _ = oracle.build_tables(to_bits(Kv), n, cent_b, 64, F)
+    q = to_bits(2.0 * u)
+    V = rand_bf16(rng, (n, d))
+    _, sel, cnt, _ = oracle.decode_head(q, cent_b, idx, score, 1, k, to_bits(Kv), V, n, n)
+    truth = np.argsort(-(Kv @ (2.0 * u)), kind="stable")[:k]
+    assert cnt == k and sel.tolist() == sorted(truth.tolist())
+
+
+def test_decode_items_matches_per_head_calls():
+    rng = np.random.default_rng(16)
+    d, n_pre, n, n_c, L, m, k = 128, 400, 403, 6, 32, 3, 20
+    items, singles = [], []
+    for t in range(5):
+        it = dict(q=rand_bf16(rng, d), cent=rand_bf16(rng, (n_c, d), 0.1),
+                  K=rand_bf16(rng, (n, d)), V=rand_bf16(rng, (n, d)))
+        it["tbl_idx"], it["tbl_score"] = random_tables(rng, n_c, L, n_pre, 12, 5000)
+        items.append(it)
+        singles.append(oracle.decode_head(it["q"], it["cent"], it["tbl_idx"], it["tbl_score"],
+                                          m, k, it["K"], it["V"], n_pre, n))
+    rows, sel, cnt, out, used = oracle.decode_items(items, m, k, n_pre, n, n_threads=2)
+    assert used == 2
+    for t, (r, s, c, o) in enumerate(singles):
+        assert np.array_equal(rows[t], r) and np.array_equal(sel[t], s) and cnt[t] == c
+        assert np.array_equal(out[t], o)
+
+
+# ------------------------------------------------------------------ clustering (Sec. 3.2 (1))
+
+def test_kmeans_objective_monotone_unit_norm_and_recovers_separated_clusters():
+    rng = np.random.default_rng(17)
+    d, n_c = 16, 4
+    dirs = np.linalg.qr(rng.standard_normal((d, d)))[0][:n_c]           # orthonormal directions
+    lab = rng.integers(0, n_c, 600)
+    x = (dirs[lab] + 0.05 * rng.standard_normal((600, d))) * rng.uniform(0.5, 4.0, (600, 1))
+    cent, obj = oracle.kmeans(x, n_c, 10, rng.uniform(size=n_c))
+    assert np.all(np.diff(obj) <= 1e-9)                                  # Lloyd never increases it
+    np.testing.assert_allclose(np.linalg.norm(cent, axis=1), 1.0, atol=1e-6)
+    cos = cent @ dirs.T                                                  # each direction recovered once
+    assert sorted(cos.argmax(1).tolist()) == list(range(n_c)) and np.all(cos.max(1) > 0.99)
+    # scale invariance: clustering sees only directions
+    cent2, _ = oracle.kmeans(x * 7.0, n_c, 10, rng.uniform(size=n_c))
+    assert sorted((cent2 @ dirs.T).argmax(1).tolist()) == list(range(n_c))
+
+
+def test_kmeans_single_centroid_is_the_normalised_mean_direction():
+    rng = np.random.default_rng(18)
+    x = rng.standard_normal((200, 8)) + 3.0
+    cent, _ = oracle.kmeans(x, 1, 2, np.array([0.5]))
+    xn = x / np.linalg.norm(x, axis=1, keepdims=True)
+    want = xn.mean(0) / np.linalg.norm(xn.mean(0))
+    np.testing.assert_allclose(cent[0], want, atol=1e-6)
+
+
+def test_round_bf16_is_nearest_even():
+    x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -9, -(1.0 + 2 ** -8 + 2 ** -20)], np.float32)
+    got = f32(oracle.round_bf16(x))
+    assert got.tolist() == [1.0, 1.0, 1.0 + 2 ** -6, 1.0, -(1.0 + 2 ** -7)]
+
+
+# ------------------------------------------------------------------ hand-worked example
+
+def test_hand_worked_example():
+    """tests/golden/decode_hand_example.txt: a 6-key, 3-centroid step worked by hand from
+    Sec. 3.3 steps 1-4 and Sec. 2.1 (values in the file, with the derivation)."""
+    ex = {}
+    with open(os.path.join(GOLDEN, "decode_hand_example.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if "=" in line:
+                key, val = line.split("=", 1)
+                ex[key.strip()] = [float(v) for v in val.split()]
+    d = 16
+    def vec(pairs):
+        v = np.zeros(d, np.float32)
+        for t, x in zip(pairs[0::2], pairs[1::2]):
+            v[int(t)] = x
+        return v
+    q = to_bits(vec(ex["q"]))
+    cent = to_bits(np.stack([vec(ex[f"c{j}"]) for j in range(3)]))
+    K = to_bits(np.stack([vec(ex[f"k{i}"]) for i in range(6)]))
+    V = to_bits(np.stack([vec(ex[f"v{i}"]) for i in range(6)]))
+    idx, score, _ = oracle.build_tables(np.ascontiguousarray(K[:5]), 5, cent, 3, 1)
+    assert idx.ravel().tolist() == [int(v) for v in ex["table_idx"]]
+    assert score.ravel().tolist() == ex["table_score"]
+    rows, sel, cnt, out = oracle.decode_head(q, cent, idx, score, 2, int(ex["k"][0]), K, V, 5, 6)
+    assert rows.tolist() == [int(v) for v in ex["rows"]]
+    assert sel.tolist() == [int(v) for v in ex["sel"]]
+    w = np.array(ex["weights_num"]) ; w = np.exp(w) / np.exp(w).sum()
+    want0 = sum(wi * vi for wi, vi in zip(w, ex["attended_v0"]))
+    assert out[0] == pytest.approx(want0, rel=1e-6)
