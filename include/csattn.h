@@ -1,0 +1,175 @@
+/*
+ * csattn.h - C ABI of the CSAttention online-decode library for AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels, the per-token decode step of
+ * Centroid-Scoring Attention (arXiv 2604.08584, Sec. 3.3 and App. A "All-GPU"), the offline
+ * construction of its lookup tables (Sec. 3.2) and the append of new keys/values (Sec. 3.3 (5),
+ * first sentence).  Geometry: one subspace spanning the whole head dimension and the
+ * `n_probe` best centroids per query, i.e. the centroid back-off of Sec. 4.4 with tau = n_probe.
+ *
+ * Conventions
+ *   - Every pointer named *_dev is DEVICE memory owned by the caller; the library never
+ *     allocates or frees device memory.  Pointers without that suffix are HOST memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work on it and return without synchronising unless stated otherwise.
+ *   - All calls return CSA_OK (0) or a negative csa_status; nothing aborts or throws.
+ *   - B = batch, Hq = n_q_heads, Hkv = n_kv_heads, G = Hq/Hkv, d = head_dim (128),
+ *     C = n_centroids, L = list_len, m = n_probe, k = budget_k.  Query head h belongs to
+ *     KV head h / G.  All sequences of the batch share n_pre and n.
+ *   - bf16 = the upper 16 bits of an IEEE fp32.  Inputs must be finite.
+ *   - A ctx is not thread-safe; calls on one ctx must be issued from one thread at a time and
+ *     on streams that are ordered with respect to each other.
+ */
+#ifndef CSATTN_H
+#define CSATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct csa_ctx csa_ctx; /* opaque host object */
+
+typedef enum {
+    CSA_OK = 0,
+    CSA_ERR_ARG = -1,       /* NULL / out-of-range argument or unsupported configuration */
+    CSA_ERR_STATE = -2,     /* call out of order (e.g. decode before tables exist) */
+    CSA_ERR_CAPACITY = -3,  /* append beyond max_ctx */
+    CSA_ERR_WORKSPACE = -4, /* bound buffer smaller than csa_workspace_bytes reports */
+    CSA_ERR_HIP = -5,       /* a HIP runtime call failed (see csa_last_hip_error) */
+    CSA_ERR_RANGE = -6      /* a table score does not fit the score grid (see score_frac_bits) */
+} csa_status;
+
+typedef struct {
+    int32_t batch;       /* B  >= 1 */
+    int32_t n_q_heads;   /* Hq, multiple of n_kv_heads, G = Hq/Hkv in {1,2,4,8,16} */
+    int32_t n_kv_heads;  /* Hkv >= 1 */
+    int32_t head_dim;    /* d, must be 128 */
+    int32_t n_centroids; /* C >= 1: query-centric centroids per KV head (Sec. 3.2 (1)) */
+    int32_t list_len;    /* L in [1, 8192]: Top-L capacity per centroid (Sec. 3.1 (iii)) */
+    int32_t n_probe;     /* m in [1, min(C, 63)]: centroids probed per query (Sec. 3.3 (1), 4.4) */
+    int32_t budget_k;    /* k >= 0: keys kept by Top-K (Sec. 3.3 (4)) */
+    int32_t n_subspaces; /* must be 1 */
+    int32_t max_ctx;     /* capacity (rows) of the caller's K/V storage per sequence;
+                            multiple of page_size when paged; <= 2^24 */
+    int32_t page_size;   /* 0: contiguous K/V [B][Hkv][max_ctx][d];
+                            16: paged pools [n_pages][Hkv][16][d] + block table */
+    int32_t score_frac_bits; /* F >= 0: table scores live on the grid 2^-F;
+                                < 0: csa_build_tables picks the finest safe grid */
+    int32_t partition_keys;  /* 0 = automatic; else a power of two in [1024, 16384]: size of
+                                the key-index ranges the score accumulation is split into */
+} csa_config;
+
+/*
+ * Score grid (decides which keys are kept, so it is part of the interface): a table score s is
+ * stored as the integer q = round-half-even(s * 2^F); the accumulated score of a key
+ * (Sec. 3.3 (3), w_b = 1) is the exact integer sum of its q over the probed rows.  The library
+ * requires n_probe * max|q| < 2^24, so the same sums are also exact in fp32 in any order.
+ */
+
+/* Validates `cfg` and creates the host object.  No device work, no device allocation. */
+int csa_create(const csa_config *cfg, csa_ctx **out);
+void csa_destroy(csa_ctx *ctx);
+
+/*
+ * Sizes (bytes) of the two device buffers the caller must provide to csa_bind:
+ *   tables  - centroids + lookup tables in the library's private layout (persistent state)
+ *   scratch - per-step temporaries (contents need not survive between calls)
+ */
+int csa_workspace_bytes(const csa_ctx *ctx, size_t *tables_bytes, size_t *scratch_bytes);
+
+/*
+ * Attaches the caller's device buffers.  All must be 256-byte aligned and stay valid until
+ * csa_destroy or the next csa_bind.
+ *   k_cache_dev, v_cache_dev: bf16.  page_size = 0: [B][Hkv][max_ctx][d].
+ *                             page_size = 16: pools [n_pages][Hkv][16][d].
+ *   block_table_dev: int32 [B][max_ctx/16], logical page -> pool page (paged only, else NULL).
+ * Re-binding keeps the table state only if tables_dev is unchanged.
+ */
+int csa_bind(csa_ctx *ctx, void *tables_dev, size_t tables_bytes, void *scratch_dev,
+             size_t scratch_bytes, void *k_cache_dev, void *v_cache_dev,
+             const int32_t *block_table_dev);
+
+/*
+ * Offline table construction, Sec. 3.2 (2): for every KV head and centroid j,
+ * s_j(i) = c_j . k_i over the prefill keys i < n_pre (raw keys), rounded to the score grid, and
+ * the L best (score desc, index asc) kept.  Scores are computed in fp32 as one
+ * fused-multiply-add chain over ascending dimension starting from +0, bf16 inputs widened.
+ *   centroids_dev: bf16 [B][Hkv][C][d], unit norm (Sec. 3.2 (1); clustering is the caller's).
+ * K is read from the bound cache, rows [0, n_pre).  Sets the context length to n_pre.
+ * SYNCHRONISES `stream` before returning (it reads back an overflow flag); returns
+ * CSA_ERR_RANGE if some |q| * n_probe >= 2^24 (tables are then unusable).
+ */
+int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, void *stream);
+
+/*
+ * Tables in the canonical layout, one KV head at a time or all at once:
+ *   idx   int32 [C][L], score fp32 [C][L]; each row sorted by (score desc, idx asc)
+ *   (Sec. 3.1 (iii) "sorted by score"); unused tail slots idx = -1, score = 0.
+ * csa_export_tables writes the rows of KV head (b, g) to device buffers.
+ * csa_import_tables reads centroids bf16 [B][Hkv][C][d] and canonical tables
+ *   idx [B][Hkv][C][L], score [B][Hkv][C][L] (device), and makes them the ctx's tables; it
+ *   needs score_frac_bits >= 0, SYNCHRONISES `stream`, and returns CSA_ERR_RANGE if a score is
+ *   off the grid or too large, CSA_ERR_ARG if an index is outside [-1, n_pre).
+ */
+int csa_export_tables(const csa_ctx *ctx, int32_t b, int32_t g, int32_t *idx_dev,
+                      float *score_dev, void *stream);
+int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *idx_dev,
+                      const float *score_dev, int32_t n_pre, void *stream);
+
+/*
+ * Sec. 3.3 (5), first sentence: append one key/value row per KV head at position n, n <- n+1.
+ *   k_new_dev, v_new_dev: bf16 [B][Hkv][d].
+ * Appended keys are not inserted into the tables; every key in [n_pre, n) is attended exactly
+ * by csa_decode_step (the "recent window" of Sec. 3.3 (4), covering all decode-time keys).
+ * CSA_ERR_CAPACITY if n == max_ctx.
+ */
+int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, void *stream);
+
+/*
+ * One decode step for every (sequence, query head), Sec. 3.3 (1)-(4) + App. A:
+ *   1. z_j = q . c_j (fp32 fma chain as above); the m largest, ties to the lower j;
+ *   2. the m table rows are read;
+ *   3. scores are summed per key index; U = keys present in at least one probed row;
+ *   4. the min(k, |U|) keys of U with the largest sum, ties to the lower index;
+ *   5. out = softmax(q K_A^T / sqrt(d)) V_A over A = selected keys + all keys in [n_pre, n)
+ *      (Sec. 2.1), bf16 inputs, fp32 accumulation.  A empty -> out = 0.
+ *   q_dev   bf16 [B][Hq][d]            out_dev fp32 [B][Hq][d]
+ *   sel_idx_dev   int32 [B][Hq][k]  ascending, padded with -1   (may be NULL)
+ *   sel_count_dev int32 [B][Hq]     = min(k, |U|)               (may be NULL)
+ */
+int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
+                    int32_t *sel_count_dev, void *stream);
+
+/* Host-side counters: prefill length and current context length. */
+int csa_context_len(const csa_ctx *ctx, int32_t *n_pre, int32_t *n);
+/* Rewind / set the context length to n in [n_pre, max_ctx] (rows >= n are simply ignored). */
+int csa_set_context_len(csa_ctx *ctx, int32_t n);
+/* The grid exponent F in use (valid after build/import). */
+int csa_score_frac_bits(const csa_ctx *ctx, int32_t *frac_bits);
+/* Copies the centroid rows probed by the last csa_decode_step, int32 [B][Hq][m] (order within a
+ * head unspecified), into a device buffer.  Diagnostic for step 1. */
+int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream);
+
+/*
+ * Per-kernel timing with HIP events recorded on the caller's stream around each launch.
+ * csa_profile_enable(ctx, 1) starts collecting; csa_profile_read synchronises the recorded
+ * events, adds each stage's elapsed milliseconds into ms_sum[CSA_N_STAGES] and the number of
+ * launches into launches[CSA_N_STAGES] (either may be NULL), and clears the record.
+ * Events cost a few microseconds per stage: leave disabled when timing whole steps.
+ */
+#define CSA_N_STAGES 7
+int csa_profile_enable(csa_ctx *ctx, int32_t on);
+int csa_profile_read(csa_ctx *ctx, double *ms_sum, int64_t *launches);
+const char *csa_stage_name(int32_t stage); /* NULL if out of range */
+
+const char *csa_strerror(int status);
+/* hipError_t of the last failing HIP call on this ctx (0 if none). */
+int csa_last_hip_error(const csa_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSATTN_H */

@@ -1,0 +1,471 @@
+// C ABI of the library (include/csattn.h): host object, workspace layout, call sequencing.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/csattn.h"
+#include "kernels.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kBuildChunk = 256;  // centroids scored per build pass
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Region {
+    size_t off = 0, bytes = 0;
+};
+
+struct Layout {
+    // tables buffer
+    Region cent_t, ent, part_off;
+    size_t tables_bytes = 0;
+    // scratch buffer
+    Region z, rows, cand, cand_cnt, sel, sel_count, part, flags, qs;
+    size_t scratch_bytes = 0;
+    int P_max = 0, S_max = 0;
+    size_t cand_keys = 0;  // candidate slots per head
+};
+
+const char *kStageNames[CSA_N_STAGES] = {"score_centroids", "top_centroids", "accumulate", "select",
+                                         "attention_split", "attention_merge", "append_kv"};
+
+}  // namespace
+
+struct csa_ctx {
+    csa_config cfg;
+    Layout lay;
+    char *tables = nullptr, *scratch = nullptr;
+    void *k_cache = nullptr, *v_cache = nullptr;
+    const int32_t *block_table = nullptr;
+    bool bound = false, have_tables = false;
+    int n_pre = 0, n = 0, F = -1, R = 0, P = 0;
+    int hip_err = 0;
+    // profiling
+    bool prof = false;
+    struct Rec {
+        hipEvent_t ev[CSA_N_STAGES + 1];
+        bool used[CSA_N_STAGES + 1];
+    };
+    std::vector<Rec> recs;
+    size_t n_recs = 0;
+};
+
+namespace {
+
+int min_R(const csa_config &c) { return c.partition_keys ? c.partition_keys : 1024; }
+
+Layout make_layout(const csa_config &c)
+{
+    Layout l;
+    const size_t BG = (size_t)c.batch * c.n_kv_heads, BH = (size_t)c.batch * c.n_q_heads;
+    l.P_max = (c.max_ctx + min_R(c) - 1) / min_R(c);
+    size_t off = 0;
+    auto put = [&](Region &r, size_t bytes) {
+        r.off = off;
+        r.bytes = bytes;
+        off = align_up(off + bytes);
+    };
+    put(l.cent_t, BG * c.n_centroids * c.head_dim * 2);
+    put(l.ent, BG * c.n_centroids * c.list_len * 8);
+    put(l.part_off, BG * c.n_centroids * (size_t)(l.P_max + 1) * 4);
+    l.tables_bytes = off;
+    off = 0;
+    l.cand_keys = ((size_t)c.max_ctx + 16383) / 16384 * 16384;
+    l.S_max = csa::attention_splits(c.budget_k, c.max_ctx);
+    put(l.z, BH * c.n_centroids * 4);
+    put(l.rows, BH * c.n_probe * 4);
+    put(l.cand, BH * l.cand_keys * 8);
+    put(l.cand_cnt, BH * (size_t)l.P_max * 4);
+    put(l.sel, BH * (size_t)(c.budget_k > 0 ? c.budget_k : 1) * 4);
+    put(l.sel_count, BH * 4);
+    put(l.part, BH * (size_t)(l.S_max > 0 ? l.S_max : 1) * (c.head_dim + 2) * 4);
+    put(l.flags, 256);
+    put(l.qs, (size_t)(c.n_centroids < kBuildChunk ? c.n_centroids : kBuildChunk) * c.max_ctx * 4);
+    l.scratch_bytes = off;
+    return l;
+}
+
+bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+int validate(const csa_config &c)
+{
+    if (c.batch < 1 || c.n_kv_heads < 1 || c.n_q_heads < 1) return CSA_ERR_ARG;
+    if (c.n_q_heads % c.n_kv_heads) return CSA_ERR_ARG;
+    const int G = c.n_q_heads / c.n_kv_heads;
+    if (!(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) return CSA_ERR_ARG;
+    if (c.head_dim != 128) return CSA_ERR_ARG;
+    if (c.n_centroids < 1 || c.list_len < 1 || c.list_len > 8192) return CSA_ERR_ARG;
+    if (c.n_probe < 1 || c.n_probe > 63 || c.n_probe > c.n_centroids) return CSA_ERR_ARG;
+    if (c.budget_k < 0) return CSA_ERR_ARG;
+    if (c.n_subspaces != 1) return CSA_ERR_ARG;
+    if (c.max_ctx < 1 || c.max_ctx > (1 << 24)) return CSA_ERR_ARG;
+    if (c.page_size != 0 && c.page_size != 16) return CSA_ERR_ARG;
+    if (c.page_size && c.max_ctx % c.page_size) return CSA_ERR_ARG;
+    if (c.score_frac_bits > 30) return CSA_ERR_ARG;
+    if (c.partition_keys &&
+        (!is_pow2(c.partition_keys) || c.partition_keys < 1024 || c.partition_keys > 16384))
+        return CSA_ERR_ARG;
+    if ((int64_t)c.batch * c.n_q_heads > 65535) return CSA_ERR_ARG;  // grid.y
+    return CSA_OK;
+}
+
+int hip_fail(csa_ctx *ctx, hipError_t e)
+{
+    ctx->hip_err = (int)e;
+    return CSA_ERR_HIP;
+}
+
+int check_launch(csa_ctx *ctx)
+{
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? CSA_OK : hip_fail(ctx, e);
+}
+
+// range of key indices per accumulation workgroup: aim at >= 1024 workgroups per step
+void choose_partition(csa_ctx *ctx, int n_pre)
+{
+    const csa_config &c = ctx->cfg;
+    int R = c.partition_keys;
+    if (!R) {
+        const int heads = c.batch * c.n_q_heads;
+        const int p_target = (1024 + heads - 1) / heads;
+        R = 16384;
+        while (R > 1024 && (n_pre + R - 1) / R < p_target) R >>= 1;
+    }
+    ctx->R = R;
+    ctx->P = (n_pre + R - 1) / R;
+    if (ctx->P < 1) ctx->P = 1;
+}
+
+template <class T>
+T *at(char *base, const Region &r) { return reinterpret_cast<T *>(base + r.off); }
+
+int qmax_for(int m) { return ((1 << 24) - 1) / m; }
+
+struct Prof {
+    csa_ctx *ctx;
+    hipStream_t st;
+    csa_ctx::Rec *rec = nullptr;
+    Prof(csa_ctx *c, hipStream_t s) : ctx(c), st(s)
+    {
+        if (!ctx->prof) return;
+        if (ctx->n_recs == ctx->recs.size()) {
+            csa_ctx::Rec r;
+            for (auto &e : r.ev) hipEventCreate(&e);
+            ctx->recs.push_back(r);
+        }
+        rec = &ctx->recs[ctx->n_recs++];
+        for (auto &u : rec->used) u = false;
+    }
+    // mark the boundary before stage `i` (and after stage i-1)
+    void mark(int i)
+    {
+        if (!rec) return;
+        hipEventRecord(rec->ev[i], st);
+        rec->used[i] = true;
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+int csa_create(const csa_config *cfg, csa_ctx **out)
+{
+    if (!cfg || !out) return CSA_ERR_ARG;
+    const int v = validate(*cfg);
+    if (v != CSA_OK) return v;
+    csa_ctx *ctx = new (std::nothrow) csa_ctx();
+    if (!ctx) return CSA_ERR_ARG;
+    ctx->cfg = *cfg;
+    ctx->lay = make_layout(*cfg);
+    *out = ctx;
+    return CSA_OK;
+}
+
+void csa_destroy(csa_ctx *ctx)
+{
+    if (!ctx) return;
+    for (auto &r : ctx->recs)
+        for (auto &e : r.ev) hipEventDestroy(e);
+    delete ctx;
+}
+
+int csa_workspace_bytes(const csa_ctx *ctx, size_t *tables_bytes, size_t *scratch_bytes)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    if (tables_bytes) *tables_bytes = ctx->lay.tables_bytes;
+    if (scratch_bytes) *scratch_bytes = ctx->lay.scratch_bytes;
+    return CSA_OK;
+}
+
+int csa_bind(csa_ctx *ctx, void *tables_dev, size_t tables_bytes, void *scratch_dev,
+             size_t scratch_bytes, void *k_cache_dev, void *v_cache_dev,
+             const int32_t *block_table_dev)
+{
+    if (!ctx || !tables_dev || !scratch_dev || !k_cache_dev || !v_cache_dev) return CSA_ERR_ARG;
+    if ((ctx->cfg.page_size != 0) != (block_table_dev != nullptr)) return CSA_ERR_ARG;
+    for (const void *p : {(const void *)tables_dev, (const void *)scratch_dev,
+                          (const void *)k_cache_dev, (const void *)v_cache_dev})
+        if ((uintptr_t)p % kAlign) return CSA_ERR_ARG;
+    if (tables_bytes < ctx->lay.tables_bytes || scratch_bytes < ctx->lay.scratch_bytes)
+        return CSA_ERR_WORKSPACE;
+    if (ctx->tables != (char *)tables_dev) ctx->have_tables = false;
+    ctx->tables = (char *)tables_dev;
+    ctx->scratch = (char *)scratch_dev;
+    ctx->k_cache = k_cache_dev;
+    ctx->v_cache = v_cache_dev;
+    ctx->block_table = block_table_dev;
+    ctx->bound = true;
+    return CSA_OK;
+}
+
+int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, void *stream)
+{
+    if (!ctx || !centroids_dev) return CSA_ERR_ARG;
+    if (!ctx->bound) return CSA_ERR_STATE;
+    const csa_config &c = ctx->cfg;
+    if (n_pre < 1 || n_pre > c.max_ctx) return CSA_ERR_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const Layout &l = ctx->lay;
+    ctx->have_tables = false;
+    int32_t *flags = at<int32_t>(ctx->scratch, l.flags);
+    hipError_t e = hipMemsetAsync(flags, 0, 256, st);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+
+    int F = c.score_frac_bits;
+    if (F < 0) {
+        // finest grid with n_probe * (max|s| * 2^F + 1/2) < 2^24, |s| <= ||c|| ||k|| and
+        // ||c|| <= 1.01 for unit centroids rounded to bf16
+        csa::launch_max_key_norm(ctx->k_cache, ctx->block_table, (float *)(flags + 16), c.batch,
+                                 c.n_kv_heads, c.max_ctx, n_pre, st);
+        float nn = 0.0f;
+        e = hipMemcpyAsync(&nn, flags + 16, 4, hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return hip_fail(ctx, e);
+        const double bound = 1.01 * std::sqrt((double)nn) + 1e-30;
+        F = (int)std::floor(std::log2(((double)qmax_for(c.n_probe) - 1.0) / bound));
+        if (F > 30) F = 30;
+        if (F < 0) return CSA_ERR_RANGE;
+    }
+    choose_partition(ctx, n_pre);
+    const int BG = c.batch * c.n_kv_heads;
+    csa::launch_pack_centroids(centroids_dev, at<void>(ctx->tables, l.cent_t), BG, c.n_centroids, st);
+    int32_t *qs = at<int32_t>(ctx->scratch, l.qs);
+    char *ent = at<char>(ctx->tables, l.ent);
+    for (int b = 0; b < c.batch; ++b)
+        for (int g = 0; g < c.n_kv_heads; ++g)
+            for (int j0 = 0; j0 < c.n_centroids; j0 += kBuildChunk) {
+                const int jc = c.n_centroids - j0 < kBuildChunk ? c.n_centroids - j0 : kBuildChunk;
+                csa::launch_build_scores(ctx->k_cache, ctx->block_table, centroids_dev, qs, flags, b, g,
+                                         c.n_kv_heads, c.max_ctx, n_pre, c.n_centroids, j0, jc, F,
+                                         qmax_for(c.n_probe), st);
+                const size_t row0 = ((size_t)(b * c.n_kv_heads + g) * c.n_centroids + j0);
+                csa::launch_build_select(qs, ent + row0 * c.list_len * 8, jc, n_pre, c.list_len, st);
+            }
+    csa::launch_part_offsets(ent, at<int32_t>(ctx->tables, l.part_off), (int64_t)BG * c.n_centroids,
+                             c.list_len, ctx->R, ctx->P, ctx->P + 1, st);
+    int rc = check_launch(ctx);
+    if (rc != CSA_OK) return rc;
+    int32_t hflags = 0;
+    e = hipMemcpyAsync(&hflags, flags, 4, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    if (hflags & 1) return CSA_ERR_RANGE;
+    ctx->F = F;
+    ctx->n_pre = ctx->n = n_pre;
+    ctx->have_tables = true;
+    return CSA_OK;
+}
+
+int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *idx_dev,
+                      const float *score_dev, int32_t n_pre, void *stream)
+{
+    if (!ctx || !centroids_dev || !idx_dev || !score_dev) return CSA_ERR_ARG;
+    if (!ctx->bound) return CSA_ERR_STATE;
+    const csa_config &c = ctx->cfg;
+    if (n_pre < 1 || n_pre > c.max_ctx || c.score_frac_bits < 0) return CSA_ERR_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const Layout &l = ctx->lay;
+    ctx->have_tables = false;
+    int32_t *flags = at<int32_t>(ctx->scratch, l.flags);
+    hipError_t e = hipMemsetAsync(flags, 0, 256, st);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    choose_partition(ctx, n_pre);
+    const int BG = c.batch * c.n_kv_heads;
+    const int64_t n_rows = (int64_t)BG * c.n_centroids;
+    csa::launch_pack_centroids(centroids_dev, at<void>(ctx->tables, l.cent_t), BG, c.n_centroids, st);
+    csa::launch_import_rows(idx_dev, score_dev, at<void>(ctx->tables, l.ent), flags, n_rows, c.list_len,
+                            n_pre, c.score_frac_bits, qmax_for(c.n_probe), st);
+    csa::launch_part_offsets(at<void>(ctx->tables, l.ent), at<int32_t>(ctx->tables, l.part_off), n_rows,
+                             c.list_len, ctx->R, ctx->P, ctx->P + 1, st);
+    int rc = check_launch(ctx);
+    if (rc != CSA_OK) return rc;
+    int32_t hflags = 0;
+    e = hipMemcpyAsync(&hflags, flags, 4, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    if (hflags & 2) return CSA_ERR_ARG;
+    if (hflags & 1) return CSA_ERR_RANGE;
+    ctx->F = c.score_frac_bits;
+    ctx->n_pre = ctx->n = n_pre;
+    ctx->have_tables = true;
+    return CSA_OK;
+}
+
+int csa_export_tables(const csa_ctx *ctx, int32_t b, int32_t g, int32_t *idx_dev, float *score_dev,
+                      void *stream)
+{
+    if (!ctx || !idx_dev || !score_dev) return CSA_ERR_ARG;
+    if (!ctx->have_tables) return CSA_ERR_STATE;
+    const csa_config &c = ctx->cfg;
+    if (b < 0 || b >= c.batch || g < 0 || g >= c.n_kv_heads) return CSA_ERR_ARG;
+    const size_t row0 = (size_t)(b * c.n_kv_heads + g) * c.n_centroids;
+    csa::launch_export_rows(ctx->tables + ctx->lay.ent.off + row0 * c.list_len * 8, idx_dev, score_dev,
+                            c.n_centroids, c.list_len, ctx->F, (hipStream_t)stream);
+    return check_launch(const_cast<csa_ctx *>(ctx));
+}
+
+int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, void *stream)
+{
+    if (!ctx || !k_new_dev || !v_new_dev) return CSA_ERR_ARG;
+    if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
+    if (ctx->n >= ctx->cfg.max_ctx) return CSA_ERR_CAPACITY;
+    hipStream_t st = (hipStream_t)stream;
+    Prof prof(ctx, st);
+    prof.mark(6);
+    csa::launch_append(ctx->k_cache, ctx->v_cache, ctx->block_table, k_new_dev, v_new_dev,
+                       ctx->cfg.batch, ctx->cfg.n_kv_heads, ctx->n, ctx->cfg.max_ctx, st);
+    prof.mark(7);
+    ctx->n += 1;
+    return check_launch(ctx);
+}
+
+int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
+                    int32_t *sel_count_dev, void *stream)
+{
+    if (!ctx || !q_dev || !out_dev) return CSA_ERR_ARG;
+    if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
+    const csa_config &c = ctx->cfg;
+    const Layout &l = ctx->lay;
+    hipStream_t st = (hipStream_t)stream;
+    const int BH = c.batch * c.n_q_heads, G = c.n_q_heads / c.n_kv_heads;
+    float *z = at<float>(ctx->scratch, l.z);
+    int32_t *rows = at<int32_t>(ctx->scratch, l.rows);
+    void *cand = at<void>(ctx->scratch, l.cand);
+    int32_t *cand_cnt = at<int32_t>(ctx->scratch, l.cand_cnt);
+    int32_t *sel = sel_idx_dev ? sel_idx_dev : at<int32_t>(ctx->scratch, l.sel);
+    int32_t *sel_count = sel_count_dev ? sel_count_dev : at<int32_t>(ctx->scratch, l.sel_count);
+    float *part = at<float>(ctx->scratch, l.part);
+    const int S = csa::attention_splits(c.budget_k, ctx->n - ctx->n_pre);
+
+    Prof prof(ctx, st);
+    prof.mark(0);
+    csa::launch_score_centroids(q_dev, at<void>(ctx->tables, l.cent_t), z, c.batch, c.n_kv_heads, G,
+                                c.n_centroids, st);
+    prof.mark(1);
+    csa::launch_top_centroids(z, rows, BH, c.n_centroids, c.n_probe, st);
+    prof.mark(2);
+    csa::launch_accumulate(at<void>(ctx->tables, l.ent), at<int32_t>(ctx->tables, l.part_off), rows, cand,
+                           cand_cnt, BH, c.n_centroids, c.list_len, c.n_probe, G, ctx->R, ctx->P,
+                           ctx->P + 1, st);
+    prof.mark(3);
+    csa::launch_select(cand, cand_cnt, sel, sel_count, BH, c.budget_k, ctx->R, ctx->P, st);
+    prof.mark(4);
+    csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, part,
+                                c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ctx->n_pre, ctx->n,
+                                c.max_ctx, S, st);
+    prof.mark(5);
+    csa::launch_attention_merge(part, out_dev, BH, S, st);
+    prof.mark(6);
+    return check_launch(ctx);
+}
+
+int csa_context_len(const csa_ctx *ctx, int32_t *n_pre, int32_t *n)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    if (!ctx->have_tables) return CSA_ERR_STATE;
+    if (n_pre) *n_pre = ctx->n_pre;
+    if (n) *n = ctx->n;
+    return CSA_OK;
+}
+
+int csa_set_context_len(csa_ctx *ctx, int32_t n)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    if (!ctx->have_tables) return CSA_ERR_STATE;
+    if (n < ctx->n_pre || n > ctx->cfg.max_ctx) return CSA_ERR_ARG;
+    ctx->n = n;
+    return CSA_OK;
+}
+
+int csa_score_frac_bits(const csa_ctx *ctx, int32_t *frac_bits)
+{
+    if (!ctx || !frac_bits) return CSA_ERR_ARG;
+    if (!ctx->have_tables) return CSA_ERR_STATE;
+    *frac_bits = ctx->F;
+    return CSA_OK;
+}
+
+int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream)
+{
+    if (!ctx || !rows_dev) return CSA_ERR_ARG;
+    if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
+    const size_t bytes = (size_t)ctx->cfg.batch * ctx->cfg.n_q_heads * ctx->cfg.n_probe * 4;
+    const hipError_t e = hipMemcpyAsync(rows_dev, ctx->scratch + ctx->lay.rows.off, bytes,
+                                        hipMemcpyDeviceToDevice, (hipStream_t)stream);
+    return e == hipSuccess ? CSA_OK : hip_fail(const_cast<csa_ctx *>(ctx), e);
+}
+
+int csa_profile_enable(csa_ctx *ctx, int32_t on)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    ctx->prof = on != 0;
+    return CSA_OK;
+}
+
+int csa_profile_read(csa_ctx *ctx, double *ms_sum, int64_t *launches)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    for (size_t r = 0; r < ctx->n_recs; ++r) {
+        csa_ctx::Rec &rec = ctx->recs[r];
+        for (int i = 0; i < CSA_N_STAGES; ++i) {
+            if (!rec.used[i] || !rec.used[i + 1]) continue;
+            hipError_t e = hipEventSynchronize(rec.ev[i + 1]);
+            float ms = 0.0f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, rec.ev[i], rec.ev[i + 1]);
+            if (e != hipSuccess) return hip_fail(ctx, e);
+            if (ms_sum) ms_sum[i] += ms;
+            if (launches) launches[i] += 1;
+        }
+    }
+    ctx->n_recs = 0;
+    return CSA_OK;
+}
+
+const char *csa_stage_name(int32_t stage)
+{
+    return stage >= 0 && stage < CSA_N_STAGES ? kStageNames[stage] : nullptr;
+}
+
+const char *csa_strerror(int status)
+{
+    switch (status) {
+    case CSA_OK: return "ok";
+    case CSA_ERR_ARG: return "invalid argument or unsupported configuration";
+    case CSA_ERR_STATE: return "call out of order (bind / build tables first)";
+    case CSA_ERR_CAPACITY: return "context is at max_ctx";
+    case CSA_ERR_WORKSPACE: return "bound buffer smaller than csa_workspace_bytes reports";
+    case CSA_ERR_HIP: return "HIP runtime error";
+    case CSA_ERR_RANGE: return "table score does not fit the score grid";
+    default: return "unknown status";
+    }
+}
+
+int csa_last_hip_error(const csa_ctx *ctx) { return ctx ? ctx->hip_err : 0; }
+
+}  // extern "C"

@@ -1,0 +1,226 @@
+// Attention half of the decode step: exact softmax attention over the selected keys plus every
+// key appended since prefill (paper Sec. 2.1 restricted to the kept set, Sec. 3.3 (4), App. A
+// "standard attention over selected KV"), and the K/V append (Sec. 3.3 (5), first sentence).
+#include "common.h"
+#include "kernels.h"
+
+namespace csa {
+
+// sum over the 16 lanes of a DPP row (result in every lane of the row)
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));  // row_mirror
+    return v;
+}
+
+constexpr int kAttNT = 256;                     // 4 waves
+constexpr int kAttWaves = kAttNT / kWave;
+constexpr int kItemsPerWave = 128;              // two index registers per lane
+constexpr int kSplit = kAttWaves * kItemsPerWave;  // 512 attended keys per workgroup
+
+// ---------------------------------------------------------------------------------------------
+// Split-KV gathered attention.  Workgroup (head, s) handles attended items
+// [s*kSplit, (s+1)*kSplit) of the head, where item a < sel_count is prefill key sel[a] and item
+// a >= sel_count is appended key n_pre + (a - sel_count).  A K or V row (256 B) is read by 16
+// lanes x 16 B, so one wave load instruction fetches 4 whole rows; each 16-lane group keeps its
+// own online-softmax state for the rows it sees, merged at the end.  Logits are taken in the
+// log2 domain (q pre-scaled by log2(e)/sqrt(d)).  Output: un-normalised partial
+// (max, sum, o[128]) per (head, split).
+// grid (S, B*Hq), block 256.
+// ---------------------------------------------------------------------------------------------
+template <bool PAGED>
+__global__ __launch_bounds__(kAttNT) void k_attention_split(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc,
+    const int32_t *__restrict__ block_table, const int32_t *__restrict__ sel,
+    const int32_t *__restrict__ sel_count, float *__restrict__ part, int k, int n_pre, int n,
+    int Hq, int G, int Hkv, int max_ctx, int S, float qscale)
+{
+    __shared__ float s_m[kAttWaves], s_l[kAttWaves], s_o[kAttWaves][kHeadDim];
+    const int s = blockIdx.x, head = blockIdx.y;
+    const int b = head / Hq, g = (head % Hq) / G;
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int sub = lane >> 4, c = lane & 15;
+    const int n_sel = sel_count[head];
+    const int n_att = n_sel + (n - n_pre);
+    float *pout = part + ((size_t)head * S + s) * (kHeadDim + 2);
+    const int a0 = s * kSplit + wave * kItemsPerWave;  // first item of this wave
+
+    // this lane's 8 query dimensions, pre-scaled
+    float qv[8];
+    {
+        const uint4 w = *(const uint4 *)(q + (size_t)head * kHeadDim + c * 8);
+        qv[0] = bf16_lo(w.x) * qscale; qv[1] = bf16_hi(w.x) * qscale;
+        qv[2] = bf16_lo(w.y) * qscale; qv[3] = bf16_hi(w.y) * qscale;
+        qv[4] = bf16_lo(w.z) * qscale; qv[5] = bf16_hi(w.z) * qscale;
+        qv[6] = bf16_lo(w.w) * qscale; qv[7] = bf16_hi(w.w) * qscale;
+    }
+    // row numbers (in units of 256-byte rows of the cache / pool) of items a0+lane, a0+64+lane
+    int64_t rown[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int a = a0 + u * kWave + lane;
+        int key = 0;
+        if (a < n_sel)
+            key = sel[(size_t)head * k + a];
+        else if (a < n_att)
+            key = n_pre + (a - n_sel);
+        if (PAGED) {
+            const int page = block_table[(size_t)b * (max_ctx >> 4) + (key >> 4)];
+            rown[u] = ((int64_t)page * Hkv + g) * 16 + (key & 15);
+        } else {
+            rown[u] = ((int64_t)b * Hkv + g) * max_ctx + key;
+        }
+    }
+    float m_run = -INFINITY, l_run = 0.0f, o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.0f;
+
+    const int n_here = min(kItemsPerWave, n_att - a0);  // items of this wave (may be <= 0)
+    for (int it = 0; it * 8 < n_here; ++it) {
+        // items it*8 + sub and it*8 + 4 + sub
+        const int i0 = it * 8 + sub, i1 = i0 + 4;
+        const int64_t src = it < 8 ? rown[0] : rown[1];
+        const int64_t r0 = __shfl(src, i0 & 63, kWave), r1 = __shfl(src, i1 & 63, kWave);
+        const uint4 k0 = *(const uint4 *)(kc + r0 * kHeadDim + c * 8);
+        const uint4 k1 = *(const uint4 *)(kc + r1 * kHeadDim + c * 8);
+        const uint4 v0 = *(const uint4 *)(vc + r0 * kHeadDim + c * 8);
+        const uint4 v1 = *(const uint4 *)(vc + r1 * kHeadDim + c * 8);
+        float d0 = qv[0] * bf16_lo(k0.x), d1 = qv[0] * bf16_lo(k1.x);
+        d0 = fmaf(qv[1], bf16_hi(k0.x), d0); d1 = fmaf(qv[1], bf16_hi(k1.x), d1);
+        d0 = fmaf(qv[2], bf16_lo(k0.y), d0); d1 = fmaf(qv[2], bf16_lo(k1.y), d1);
+        d0 = fmaf(qv[3], bf16_hi(k0.y), d0); d1 = fmaf(qv[3], bf16_hi(k1.y), d1);
+        d0 = fmaf(qv[4], bf16_lo(k0.z), d0); d1 = fmaf(qv[4], bf16_lo(k1.z), d1);
+        d0 = fmaf(qv[5], bf16_hi(k0.z), d0); d1 = fmaf(qv[5], bf16_hi(k1.z), d1);
+        d0 = fmaf(qv[6], bf16_lo(k0.w), d0); d1 = fmaf(qv[6], bf16_lo(k1.w), d1);
+        d0 = fmaf(qv[7], bf16_hi(k0.w), d0); d1 = fmaf(qv[7], bf16_hi(k1.w), d1);
+        d0 = row16_sum(d0);
+        d1 = row16_sum(d1);
+        if (i0 >= n_here) d0 = -INFINITY;
+        if (i1 >= n_here) d1 = -INFINITY;
+        const float m_new = fmaxf(m_run, fmaxf(d0, d1));
+        if (m_new != -INFINITY) {  // this 16-lane group has seen at least one real item
+            const float sc = exp2f(m_run - m_new);
+            const float p0 = exp2f(d0 - m_new), p1 = exp2f(d1 - m_new);
+            l_run = l_run * sc + p0 + p1;
+            const float vf0[8] = {bf16_lo(v0.x), bf16_hi(v0.x), bf16_lo(v0.y), bf16_hi(v0.y),
+                                  bf16_lo(v0.z), bf16_hi(v0.z), bf16_lo(v0.w), bf16_hi(v0.w)};
+            const float vf1[8] = {bf16_lo(v1.x), bf16_hi(v1.x), bf16_lo(v1.y), bf16_hi(v1.y),
+                                  bf16_lo(v1.z), bf16_hi(v1.z), bf16_lo(v1.w), bf16_hi(v1.w)};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = fmaf(p1, vf1[e], fmaf(p0, vf0[e], o[e] * sc));
+            m_run = m_new;
+        }
+    }
+    // merge the four 16-lane groups of the wave (lanes c, c+16, c+32, c+48)
+#pragma unroll
+    for (int x = 16; x <= 32; x <<= 1) {
+        const float m_o = __shfl_xor(m_run, x, kWave), l_o = __shfl_xor(l_run, x, kWave);
+        const float m_new = fmaxf(m_run, m_o);
+        const float sa = m_run == -INFINITY ? 0.0f : exp2f(m_run - m_new);
+        const float sb = m_o == -INFINITY ? 0.0f : exp2f(m_o - m_new);
+        l_run = l_run * sa + l_o * sb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = o[e] * sa + __shfl_xor(o[e], x, kWave) * sb;
+        m_run = m_new;
+    }
+    if (lane < 16) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s_o[wave][c * 8 + e] = o[e];
+        if (lane == 0) { s_m[wave] = m_run; s_l[wave] = l_run; }
+    }
+    __syncthreads();
+    if (threadIdx.x < kHeadDim) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kAttWaves; ++w) M = fmaxf(M, s_m[w]);
+        float acc = 0.0f, l = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kAttWaves; ++w) {
+            const float f = s_m[w] == -INFINITY ? 0.0f : exp2f(s_m[w] - M);
+            acc += s_o[w][threadIdx.x] * f;
+            l += s_l[w] * f;
+        }
+        pout[2 + threadIdx.x] = acc;
+        if (threadIdx.x == 0) { pout[0] = M; pout[1] = l; }
+    }
+}
+
+// out[head][e] = sum_s o_s[e] 2^(m_s - M) / sum_s l_s 2^(m_s - M); no attended key -> 0.
+// grid B*Hq, block 128.
+__global__ __launch_bounds__(kHeadDim) void k_attention_merge(const float *__restrict__ part,
+                                                              float *__restrict__ out, int S)
+{
+    const float *ph = part + (size_t)blockIdx.x * S * (kHeadDim + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < S; ++s) M = fmaxf(M, ph[(size_t)s * (kHeadDim + 2)]);
+    float acc = 0.0f, l = 0.0f;
+    for (int s = 0; s < S; ++s) {
+        const float *ps = ph + (size_t)s * (kHeadDim + 2);
+        const float f = ps[0] == -INFINITY ? 0.0f : exp2f(ps[0] - M);
+        acc += ps[2 + threadIdx.x] * f;
+        l += ps[1] * f;
+    }
+    out[(size_t)blockIdx.x * kHeadDim + threadIdx.x] = l > 0.0f ? acc / l : 0.0f;
+}
+
+int attention_splits(int k, int n_appended) { return (k + n_appended + kSplit - 1) / kSplit; }
+
+void launch_attention_split(const void *q, const void *kc, const void *vc,
+                            const int32_t *block_table, const int32_t *sel,
+                            const int32_t *sel_count, float *part, int B, int Hq, int Hkv, int k,
+                            int n_pre, int n, int max_ctx, int S, hipStream_t st)
+{
+    if (S <= 0) return;
+    const float qscale = 1.4426950408889634f / sqrtf((float)kHeadDim);
+    const int G = Hq / Hkv;
+    dim3 grid(S, B * Hq), block(kAttNT);
+    if (block_table)
+        k_attention_split<true><<<grid, block, 0, st>>>(
+            (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, block_table, sel,
+            sel_count, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, qscale);
+    else
+        k_attention_split<false><<<grid, block, 0, st>>>(
+            (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, nullptr, sel,
+            sel_count, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, qscale);
+}
+
+void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st)
+{
+    k_attention_merge<<<n_heads, kHeadDim, 0, st>>>(part, out, S);
+}
+
+// K/V append: row n of every (sequence, KV head).  grid B*Hkv, block 32 (16 lanes K, 16 lanes V).
+template <bool PAGED>
+__global__ void k_append(uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
+                         const int32_t *__restrict__ block_table, const uint16_t *__restrict__ kn,
+                         const uint16_t *__restrict__ vn, int n, int Hkv, int max_ctx)
+{
+    const int bg = blockIdx.x, b = bg / Hkv, g = bg % Hkv;
+    int64_t row;
+    if (PAGED) {
+        const int page = block_table[(size_t)b * (max_ctx >> 4) + (n >> 4)];
+        row = ((int64_t)page * Hkv + g) * 16 + (n & 15);
+    } else {
+        row = (int64_t)bg * max_ctx + n;
+    }
+    const int c = threadIdx.x & 15;
+    const uint16_t *src = (threadIdx.x < 16 ? kn : vn) + (size_t)bg * kHeadDim + c * 8;
+    uint16_t *dst = (threadIdx.x < 16 ? kc : vc) + row * kHeadDim + c * 8;
+    *(uint4 *)dst = *(const uint4 *)src;
+}
+
+void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
+                   int B, int Hkv, int n, int max_ctx, hipStream_t st)
+{
+    if (block_table)
+        k_append<true><<<B * Hkv, 32, 0, st>>>((uint16_t *)kc, (uint16_t *)vc, block_table,
+                                               (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx);
+    else
+        k_append<false><<<B * Hkv, 32, 0, st>>>((uint16_t *)kc, (uint16_t *)vc, nullptr,
+                                                (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx);
+}
+
+}  // namespace csa

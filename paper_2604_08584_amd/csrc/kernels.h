@@ -1,0 +1,43 @@
+// Host-callable launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace csa {
+
+// ---- tables.hip
+void launch_pack_centroids(const void *cent, void *cent_t, int n_bg, int C, hipStream_t st);
+void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32_t *flags,
+                        int64_t n_rows, int L, int n_pre, int F, int qmax, hipStream_t st);
+void launch_export_rows(const void *ent, int32_t *idx, float *score, int n_rows, int L, int F,
+                        hipStream_t st);
+void launch_part_offsets(const void *ent, int32_t *part_off, int64_t n_rows, int L, int R, int P,
+                         int PO, hipStream_t st);
+void launch_build_scores(const void *kc, const int32_t *block_table, const void *cent, int32_t *qs,
+                         int32_t *flags, int b, int g, int Hkv, int max_ctx, int n_pre, int C,
+                         int j0, int jc, int F, int qmax, hipStream_t st);
+void launch_build_select(const int32_t *qs, void *ent, int jc, int n_pre, int L, hipStream_t st);
+void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
+                         int max_ctx, int n_pre, hipStream_t st);
+
+// ---- decode.hip
+void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
+                            int C, hipStream_t st);
+void launch_top_centroids(const float *z, int32_t *rows, int n_heads, int C, int m, hipStream_t st);
+void launch_accumulate(const void *ent, const int32_t *part_off, const int32_t *rows, void *cand,
+                       int32_t *cand_cnt, int n_heads, int C, int L, int m, int G, int R, int P,
+                       int PO, hipStream_t st);
+void launch_select(const void *cand, const int32_t *cand_cnt, int32_t *sel, int32_t *sel_count,
+                   int n_heads, int k, int R, int P, hipStream_t st);
+
+// ---- attention.hip
+int attention_splits(int k, int n_appended);
+void launch_attention_split(const void *q, const void *kc, const void *vc,
+                            const int32_t *block_table, const int32_t *sel,
+                            const int32_t *sel_count, float *part, int B, int Hq, int Hkv, int k,
+                            int n_pre, int n, int max_ctx, int S, hipStream_t st);
+void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st);
+void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
+                   int B, int Hkv, int n, int max_ctx, hipStream_t st);
+
+}  // namespace csa

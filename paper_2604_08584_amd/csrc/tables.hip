@@ -1,0 +1,375 @@
+// Offline side: lookup-table construction (paper Sec. 3.2 (2)), conversion between the canonical
+// table layout (rows sorted by score, Sec. 3.1 (iii)) and the library's private device layout
+// (rows sorted by key index + per-row offsets of every key range), centroid repacking.
+#include "common.h"
+#include "kernels.h"
+
+namespace csa {
+
+// cent [n_bg][C][128] bf16 -> cent_t [n_bg][16][C][8] bf16 (one 16-byte chunk per thread)
+__global__ void k_pack_centroids(const uint4 *__restrict__ cent, uint4 *__restrict__ cent_t, int C)
+{
+    const int bg = blockIdx.y;
+    const int e = blockIdx.x * 256 + threadIdx.x;  // = j*16 + c
+    if (e >= C * 16) return;
+    const int j = e >> 4, c = e & 15;
+    cent_t[((size_t)bg * 16 + c) * C + j] = cent[(size_t)bg * C * 16 + e];
+}
+
+void launch_pack_centroids(const void *cent, void *cent_t, int n_bg, int C, hipStream_t st)
+{
+    dim3 grid((C * 16 + 255) / 256, n_bg);
+    k_pack_centroids<<<grid, 256, 0, st>>>((const uint4 *)cent, (uint4 *)cent_t, C);
+}
+
+// in-LDS bitonic sort of NP (power of two) 64-bit keys, ascending; all threads of the block
+template <int NT>
+__device__ __forceinline__ void bitonic_sort_u64(uint64_t *s, int NP)
+{
+    for (int k2 = 2; k2 <= NP; k2 <<= 1) {
+        for (int j = k2 >> 1; j > 0; j >>= 1) {
+            __syncthreads();
+            for (int i = threadIdx.x; i < NP; i += NT) {
+                const int x = i ^ j;
+                if (x > i) {
+                    const uint64_t a = s[i], b = s[x];
+                    const bool up = (i & k2) == 0;
+                    if ((a > b) == up) { s[i] = b; s[x] = a; }
+                }
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Canonical rows -> device rows.  One workgroup per row: checks every (idx, score), converts
+// score to its grid integer q (exact or flagged), sorts by key index (unused slots last).
+// flags |= 1: score off the grid or too large; flags |= 2: index outside [-1, n_pre).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_import_rows(const int32_t *__restrict__ idx,
+                                                     const float *__restrict__ score,
+                                                     Entry *__restrict__ ent,
+                                                     int32_t *__restrict__ flags, int L, int NP,
+                                                     int n_pre, float up, int qmax)
+{
+    extern __shared__ uint64_t s_keys[];
+    const size_t row = blockIdx.x;
+    int bad = 0;
+    for (int p = threadIdx.x; p < NP; p += 256) {
+        uint64_t key = ~0ull;
+        if (p < L) {
+            const int32_t i = idx[row * L + p];
+            if (i >= n_pre || i < -1) {
+                bad |= 2;
+            } else if (i >= 0) {
+                const float qf = score[row * L + p] * up;
+                if (!(fabsf(qf) <= (float)qmax) || qf != rintf(qf)) bad |= 1;
+                const int32_t q = (int32_t)qf;
+                key = ((uint64_t)(uint32_t)i << 32) | (uint32_t)(q * 64 + 1);
+            }
+        }
+        s_keys[p] = key;
+    }
+    if (bad) atomicOr(flags, bad);
+    bitonic_sort_u64<256>(s_keys, NP);
+    for (int p = threadIdx.x; p < L; p += 256) {
+        const uint64_t key = s_keys[p];
+        Entry e;
+        if (key == ~0ull) { e.idx = -1; e.qe = 0; }
+        else { e.idx = (int32_t)(key >> 32); e.qe = (int32_t)(uint32_t)key; }
+        ent[row * L + p] = e;
+    }
+}
+
+static int next_pow2(int x) { int p = 1; while (p < x) p <<= 1; return p; }
+
+void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32_t *flags,
+                        int64_t n_rows, int L, int n_pre, int F, int qmax, hipStream_t st)
+{
+    const int NP = next_pow2(L);
+    static bool attr = false;
+    if (!attr) {
+        hipFuncSetAttribute((const void *)k_import_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8);
+        attr = true;
+    }
+    k_import_rows<<<(unsigned)n_rows, 256, (size_t)NP * 8, st>>>(idx, score, (Entry *)ent, flags, L, NP,
+                                                                 n_pre, ldexpf(1.0f, F), qmax);
+}
+
+// Device rows -> canonical rows: sort by (score desc, idx asc), unused slots last.
+__global__ __launch_bounds__(256) void k_export_rows(const Entry *__restrict__ ent,
+                                                     int32_t *__restrict__ idx,
+                                                     float *__restrict__ score, int L, int NP,
+                                                     float down)
+{
+    extern __shared__ uint64_t s_keys[];
+    const size_t row = blockIdx.x;
+    for (int p = threadIdx.x; p < NP; p += 256) {
+        uint64_t key = ~0ull;
+        if (p < L) {
+            const Entry e = ent[row * L + p];
+            if (e.idx >= 0) {
+                const int32_t q = e.qe >> kCntBits;
+                key = ((uint64_t)(~((uint32_t)q ^ 0x80000000u)) << 32) | (uint32_t)e.idx;
+            }
+        }
+        s_keys[p] = key;
+    }
+    bitonic_sort_u64<256>(s_keys, NP);
+    for (int p = threadIdx.x; p < L; p += 256) {
+        const uint64_t key = s_keys[p];
+        if (key == ~0ull) {
+            idx[row * L + p] = -1;
+            score[row * L + p] = 0.0f;
+        } else {
+            const int32_t q = (int32_t)((~(uint32_t)(key >> 32)) ^ 0x80000000u);
+            idx[row * L + p] = (int32_t)(uint32_t)key;
+            score[row * L + p] = (float)q * down;
+        }
+    }
+}
+
+void launch_export_rows(const void *ent, int32_t *idx, float *score, int n_rows, int L, int F,
+                        hipStream_t st)
+{
+    const int NP = next_pow2(L);
+    static bool attr = false;
+    if (!attr) {
+        hipFuncSetAttribute((const void *)k_export_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8);
+        attr = true;
+    }
+    k_export_rows<<<n_rows, 256, (size_t)NP * 8, st>>>((const Entry *)ent, idx, score, L, NP,
+                                                       ldexpf(1.0f, -F));
+}
+
+// part_off[row][p] = number of entries of the row with key index < p*R, p = 0..P
+// (unused slots, idx = -1, sort last and are never counted).  One thread per (row, p).
+__global__ void k_part_offsets(const Entry *__restrict__ ent, int32_t *__restrict__ part_off,
+                               int64_t n_rows, int L, int R, int PO)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n_rows * PO) return;
+    const int64_t row = t / PO;
+    const uint32_t bound = (uint32_t)(t % PO) * (uint32_t)R;
+    const Entry *r = ent + row * L;
+    int lo = 0, hi = L;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if ((uint32_t)r[mid].idx < bound) lo = mid + 1; else hi = mid;
+    }
+    part_off[t] = lo;
+}
+
+void launch_part_offsets(const void *ent, int32_t *part_off, int64_t n_rows, int L, int R, int P,
+                         int PO, hipStream_t st)
+{
+    (void)P;
+    const int64_t n = n_rows * PO;
+    k_part_offsets<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((const Entry *)ent, part_off, n_rows, L, R, PO);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Table build, part 1: grid integers q[jj][i] = round-half-even(2^F * (c_{j0+jj} . k_i)) for one
+// KV head and a chunk of centroids.  One lane per key (the key row lives in registers as 128
+// fp32), centroids staged through LDS 64 at a time and broadcast.  The inner product is one fma
+// chain over ascending dimension from +0 - the same definition as the decode-time centroid
+// scores - so the table contents are reproducible bit for bit.
+// grid ceil(n_pre/256), block 256.
+// ---------------------------------------------------------------------------------------------
+constexpr int kBuildTile = 64;
+
+template <bool PAGED>
+__global__ __launch_bounds__(256) void k_build_scores(const uint16_t *__restrict__ kc,
+                                                      const int32_t *__restrict__ block_table,
+                                                      const uint16_t *__restrict__ cent,
+                                                      int32_t *__restrict__ qs,
+                                                      int32_t *__restrict__ flags, int b, int g,
+                                                      int Hkv, int max_ctx, int n_pre, int C, int j0,
+                                                      int jc, float up, int qmax)
+{
+    __shared__ uint4 s_c[kBuildTile][kHeadDim / 8];
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int ic = i < n_pre ? i : n_pre - 1;  // clamp: tail lanes compute a duplicate, store nothing
+    int64_t row;
+    if (PAGED) {
+        const int page = block_table[(size_t)b * (max_ctx >> 4) + (ic >> 4)];
+        row = ((int64_t)page * Hkv + g) * 16 + (ic & 15);
+    } else {
+        row = ((int64_t)b * Hkv + g) * max_ctx + ic;
+    }
+    float kf[kHeadDim];
+    {
+        const uint4 *kr = (const uint4 *)(kc + row * kHeadDim);
+#pragma unroll
+        for (int c = 0; c < kHeadDim / 8; ++c) {
+            const uint4 w = kr[c];
+            kf[c * 8 + 0] = bf16_lo(w.x); kf[c * 8 + 1] = bf16_hi(w.x);
+            kf[c * 8 + 2] = bf16_lo(w.y); kf[c * 8 + 3] = bf16_hi(w.y);
+            kf[c * 8 + 4] = bf16_lo(w.z); kf[c * 8 + 5] = bf16_hi(w.z);
+            kf[c * 8 + 6] = bf16_lo(w.w); kf[c * 8 + 7] = bf16_hi(w.w);
+        }
+    }
+    const uint4 *cg = (const uint4 *)(cent + (((size_t)b * Hkv + g) * C + j0) * kHeadDim);
+    int bad = 0;
+    for (int t0 = 0; t0 < jc; t0 += kBuildTile) {
+        const int nt = min(kBuildTile, jc - t0);
+        __syncthreads();
+        for (int e = threadIdx.x; e < nt * (kHeadDim / 8); e += 256)
+            s_c[e / (kHeadDim / 8)][e % (kHeadDim / 8)] = cg[(size_t)t0 * (kHeadDim / 8) + e];
+        __syncthreads();
+        for (int jj = 0; jj < nt; ++jj) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int c = 0; c < kHeadDim / 8; ++c) {
+                const uint4 w = s_c[jj][c];
+                acc = __builtin_fmaf(bf16_lo(w.x), kf[c * 8 + 0], acc);
+                acc = __builtin_fmaf(bf16_hi(w.x), kf[c * 8 + 1], acc);
+                acc = __builtin_fmaf(bf16_lo(w.y), kf[c * 8 + 2], acc);
+                acc = __builtin_fmaf(bf16_hi(w.y), kf[c * 8 + 3], acc);
+                acc = __builtin_fmaf(bf16_lo(w.z), kf[c * 8 + 4], acc);
+                acc = __builtin_fmaf(bf16_hi(w.z), kf[c * 8 + 5], acc);
+                acc = __builtin_fmaf(bf16_lo(w.w), kf[c * 8 + 6], acc);
+                acc = __builtin_fmaf(bf16_hi(w.w), kf[c * 8 + 7], acc);
+            }
+            const float qf = rintf(acc * up);
+            if (!(fabsf(qf) <= (float)qmax)) bad = 1;
+            if (i < n_pre) qs[(size_t)(t0 + jj) * n_pre + i] = (int32_t)qf;
+        }
+    }
+    if (bad) atomicOr(flags, 1);
+}
+
+void launch_build_scores(const void *kc, const int32_t *block_table, const void *cent, int32_t *qs,
+                         int32_t *flags, int b, int g, int Hkv, int max_ctx, int n_pre, int C,
+                         int j0, int jc, int F, int qmax, hipStream_t st)
+{
+    const int grid = (n_pre + 255) / 256;
+    if (block_table)
+        k_build_scores<true><<<grid, 256, 0, st>>>((const uint16_t *)kc, block_table, (const uint16_t *)cent, qs,
+                                                   flags, b, g, Hkv, max_ctx, n_pre, C, j0, jc, ldexpf(1.0f, F), qmax);
+    else
+        k_build_scores<false><<<grid, 256, 0, st>>>((const uint16_t *)kc, nullptr, (const uint16_t *)cent, qs,
+                                                    flags, b, g, Hkv, max_ctx, n_pre, C, j0, jc, ldexpf(1.0f, F), qmax);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Table build, part 2: Top-L of one row of grid integers (largest first, ties to the lower key
+// index, Sec. 3.2 (2) "keep Top-L pairs"), written directly in the device layout (ascending key
+// index).  Radix threshold search, then each wave walks a contiguous range of keys in order and
+// compacts the winners with ballots; a wave's output offset and its share of the threshold
+// ties follow from per-wave counts.
+// grid = rows of the chunk, block 1024.  ent points at the chunk's first row.
+// ---------------------------------------------------------------------------------------------
+constexpr int kBsNT = 1024;
+constexpr int kBsWaves = kBsNT / kWave;
+
+__global__ __launch_bounds__(kBsNT) void k_build_select(const int32_t *__restrict__ qs,
+                                                        Entry *__restrict__ ent, int n_pre, int L)
+{
+    __shared__ uint32_t s_hist[256 + kBsWaves + 4];
+    __shared__ int s_gt[kBsWaves], s_eq[kBsWaves];
+    const int32_t *qr = qs + (size_t)blockIdx.x * n_pre;
+    Entry *out = ent + (size_t)blockIdx.x * L;
+    const int want = min(L, n_pre);
+    uint32_t T = 0;
+    int need = 0;
+    if (n_pre > L) {
+        T = block_radix_threshold<kBsNT, 8, 4>(
+            [&](auto fn) {
+                for (int i = threadIdx.x; i < n_pre; i += kBsNT) fn((uint32_t)qr[i] ^ 0x80000000u);
+            },
+            want, s_hist, need);
+    }
+    const int wave = threadIdx.x / kWave, lane = lane_id();
+    const int per_wave = ((n_pre + kBsWaves - 1) / kBsWaves + kWave - 1) / kWave * kWave;
+    const int lo = min(n_pre, wave * per_wave), hi = min(n_pre, lo + per_wave);
+    int n_gt = 0, n_eq = 0;
+    for (int i0 = lo; i0 < hi; i0 += kWave) {
+        const int i = i0 + lane;
+        const uint32_t key = i < hi ? ((uint32_t)qr[i] ^ 0x80000000u) : 0u;
+        n_gt += __popcll(__ballot(i < hi && key > T));
+        n_eq += __popcll(__ballot(i < hi && key == T && n_pre > L));
+    }
+    if (lane == 0) { s_gt[wave] = n_gt; s_eq[wave] = n_eq; }
+    __syncthreads();
+    int pos = 0, ties_before = 0;
+    for (int w = 0; w < wave; ++w) {
+        const int e = s_eq[w];
+        pos += s_gt[w] + max(0, min(e, need - ties_before));
+        ties_before += e;
+    }
+    int tie_rank = ties_before;
+    for (int i0 = lo; i0 < hi; i0 += kWave) {
+        const int i = i0 + lane;
+        const int32_t q = i < hi ? qr[i] : 0;
+        const uint32_t key = (uint32_t)q ^ 0x80000000u;
+        const bool gt = i < hi && key > T;
+        const bool eq = i < hi && key == T && n_pre > L;
+        const uint64_t eq_mask = __ballot(eq);
+        const bool take = gt || (eq && tie_rank + mbcnt(eq_mask) < need);
+        const uint64_t take_mask = __ballot(take);
+        if (take) {
+            Entry e;
+            e.idx = i;
+            e.qe = q * 64 + 1;
+            out[pos + mbcnt(take_mask)] = e;
+        }
+        pos += __popcll(take_mask);
+        tie_rank += __popcll(eq_mask);
+    }
+    for (int p = want + threadIdx.x; p < L; p += kBsNT) {
+        Entry e;
+        e.idx = -1;
+        e.qe = 0;
+        out[p] = e;
+    }
+}
+
+void launch_build_select(const int32_t *qs, void *ent, int jc, int n_pre, int L, hipStream_t st)
+{
+    k_build_select<<<jc, kBsNT, 0, st>>>(qs, (Entry *)ent, n_pre, L);
+}
+
+// max over prefill keys of ||k||^2, as the bit pattern of a non-negative fp32 (atomicMax on
+// int).  Used to pick the score grid.  out must be zeroed.
+template <bool PAGED>
+__global__ void k_max_key_norm(const uint16_t *__restrict__ kc, const int32_t *__restrict__ block_table,
+                               int *__restrict__ out, int Hkv, int max_ctx, int n_pre, int64_t total)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float nn = 0.0f;
+    if (t < total) {
+        const int i = (int)(t % n_pre);
+        const int bg = (int)(t / n_pre), b = bg / Hkv, g = bg % Hkv;
+        int64_t row;
+        if (PAGED) {
+            const int page = block_table[(size_t)b * (max_ctx >> 4) + (i >> 4)];
+            row = ((int64_t)page * Hkv + g) * 16 + (i & 15);
+        } else {
+            row = (int64_t)bg * max_ctx + i;
+        }
+        const uint4 *kr = (const uint4 *)(kc + row * kHeadDim);
+        for (int c = 0; c < kHeadDim / 8; ++c) {
+            const uint4 w = kr[c];
+            const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                                bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+            for (int e = 0; e < 8; ++e) nn = fmaf(f[e], f[e], nn);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) nn = fmaxf(nn, __shfl_xor(nn, o, kWave));
+    if (lane_id() == 0) atomicMax(out, __float_as_int(nn));
+}
+
+void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
+                         int max_ctx, int n_pre, hipStream_t st)
+{
+    const int64_t total = (int64_t)B * Hkv * n_pre;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (block_table)
+        k_max_key_norm<true><<<grid, 256, 0, st>>>((const uint16_t *)kc, block_table, (int *)out, Hkv, max_ctx, n_pre, total);
+    else
+        k_max_key_norm<false><<<grid, 256, 0, st>>>((const uint16_t *)kc, nullptr, (int *)out, Hkv, max_ctx, n_pre, total);
+}
+
+}  // namespace csa

@@ -1,0 +1,133 @@
+"""Glue shared by the GPU parity tests: runs the HIP library (through the C ABI binding) and the
+CPU oracle on the same bytes and compares them.  Holds no arithmetic of the method."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import oracle
+from paper_2604_08584_amd import binding
+from paper_2604_08584_amd.workload import Workload, make_inputs, paginate
+
+TOL_OUT = 2e-2   # max-abs tolerance on attention outputs (bf16 inputs, fp32 accumulation)
+
+
+def cfg_kwargs(w: Workload, F: int, partition_keys: int = 0):
+    return dict(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, n_centroids=w.C,
+                list_len=w.L, n_probe=w.m, budget_k=w.k, max_ctx=w.max_ctx, page_size=w.page_size,
+                score_frac_bits=F, partition_keys=partition_keys)
+
+
+class Case:
+    """One workload instantiated on the GPU, with host copies for the oracle."""
+
+    def __init__(self, w: Workload, seed=0, F=14, partition_keys=0, gen_device="cpu",
+                 kmeans_sample=None):
+        self.w, self.F = w, F
+        inp = make_inputs(w, seed=seed, device=gen_device, kmeans_sample=kmeans_sample)
+        self.inp = {k: v.cuda() for k, v in inp.items()}
+        # logical (contiguous) host copies for the oracle; appended rows are filled in as we go
+        self.K_host = oracle.bf16_bits(inp["k_cache"])
+        self.V_host = oracle.bf16_bits(inp["v_cache"])
+        self.cent_host = oracle.bf16_bits(inp["centroids"])
+        if w.page_size:
+            self.k_store, self.block_table = paginate(self.inp["k_cache"], w.page_size, seed, w.name)
+            self.v_store, _ = paginate(self.inp["v_cache"], w.page_size, seed, w.name, self.block_table)
+        else:
+            self.k_store, self.v_store, self.block_table = self.inp["k_cache"], self.inp["v_cache"], None
+        self.ctx = binding.Context(self.k_store, self.v_store, self.block_table,
+                                   **cfg_kwargs(w, F, partition_keys))
+        self.tables = {}   # (b, g) -> (idx, score) numpy, canonical
+        self.t = 0         # appended so far
+
+    # ---- tables
+    def build_on_gpu(self):
+        self.ctx.build_tables(self.inp["centroids"], self.w.n_pre)
+        self.F = binding.csa_score_frac_bits(self.ctx.ctx)
+
+    def export(self, b, g):
+        if (b, g) not in self.tables:
+            idx, score = self.ctx.export_tables(b, g)
+            self.tables[(b, g)] = (idx.cpu().numpy(), score.cpu().numpy())
+        return self.tables[(b, g)]
+
+    def oracle_tables(self, b, g, rows=None):
+        K = np.ascontiguousarray(self.K_host[b, g, :self.w.n_pre])
+        if rows is None:
+            return oracle.build_tables(K, self.w.n_pre, self.cent_host[b, g], self.w.L, self.F)
+        return oracle.build_rows(K, self.w.n_pre, self.cent_host[b, g], rows, self.w.L, self.F)
+
+    def import_tables(self, idx, score):
+        """idx/score: numpy [B][Hkv][C][L] canonical."""
+        w = self.w
+        for b in range(w.batch):
+            for g in range(w.n_kv_heads):
+                self.tables[(b, g)] = (np.ascontiguousarray(idx[b, g]), np.ascontiguousarray(score[b, g]))
+        self.ctx.import_tables(self.inp["centroids"], torch.from_numpy(idx).cuda(),
+                               torch.from_numpy(score).cuda(), w.n_pre)
+
+    def import_oracle_tables(self):
+        w = self.w
+        idx = np.empty((w.batch, w.n_kv_heads, w.C, w.L), np.int32)
+        score = np.empty((w.batch, w.n_kv_heads, w.C, w.L), np.float32)
+        for b in range(w.batch):
+            for g in range(w.n_kv_heads):
+                idx[b, g], score[b, g], _ = self.oracle_tables(b, g)
+        self.import_tables(idx, score)
+
+    # ---- steps
+    def append(self, count=1):
+        for _ in range(count):
+            kn, vn = self.inp["k_new"][self.t], self.inp["v_new"][self.t]
+            self.ctx.append_kv(kn, vn)
+            pos = self.w.n_pre + self.t
+            self.K_host[:, :, pos] = oracle.bf16_bits(kn)
+            self.V_host[:, :, pos] = oracle.bf16_bits(vn)
+            self.t += 1
+
+    def decode(self, step):
+        q = self.inp["q_steps"][step]
+        out, sel, cnt = self.ctx.decode_step(q)
+        rows = self.ctx.probed_rows()
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), sel.cpu().numpy(), cnt.cpu().numpy(), rows.cpu().numpy()
+
+    def oracle_decode(self, step, heads):
+        """heads: list of (b, h).  Uses the tables exported from / imported into the GPU."""
+        w = self.w
+        qh = oracle.bf16_bits(self.inp["q_steps"][step])
+        n = w.n_pre + self.t
+        items = []
+        for b, h in heads:
+            g = h // w.group
+            idx, score = self.export(b, g)
+            items.append(dict(q=np.ascontiguousarray(qh[b, h]), cent=self.cent_host[b, g], tbl_idx=idx,
+                              tbl_score=score, K=self.K_host[b, g], V=self.V_host[b, g]))
+        rows, sel, cnt, out, _ = oracle.decode_items(items, w.m, w.k, w.n_pre, n)
+        return rows, sel, cnt, out
+
+    def check_step(self, step, heads=None):
+        """Decode on both sides, compare; returns the max-abs output error."""
+        w = self.w
+        if heads is None:
+            heads = [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
+        out, sel, cnt, rows = self.decode(step)
+        o_rows, o_sel, o_cnt, o_out = self.oracle_decode(step, heads)
+        worst = 0.0
+        for t, (b, h) in enumerate(heads):
+            tag = f"{w.name} step {step} head ({b},{h})"
+            assert sorted(rows[b, h].tolist()) == sorted(o_rows[t].tolist()), f"{tag}: probed rows differ"
+            assert cnt[b, h] == o_cnt[t], f"{tag}: count {cnt[b, h]} != {o_cnt[t]}"
+            if w.k:
+                assert np.array_equal(sel[b, h][:w.k], o_sel[t]), f"{tag}: selected indices differ"
+            err = float(np.abs(out[b, h] - o_out[t]).max())
+            assert np.isfinite(out[b, h]).all() and err <= TOL_OUT, f"{tag}: |out - oracle| = {err}"
+            worst = max(worst, err)
+        return worst
+
+
+def small(name="small", **kw) -> Workload:
+    base = dict(name=name, batch=1, n_q_heads=4, n_kv_heads=1, head_dim=128, n_pre=3000, n_comp=16,
+                C=48, L=200, m=5, k=150, steps=2, pre_appended=0, page_size=0, kmeans_iters=3)
+    base.update(kw)
+    return Workload(**base)

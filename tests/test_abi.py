@@ -1,0 +1,64 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol include/csattn.h
+declares, and validates arguments on the host (no compute, no GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_08584_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "csattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(csa_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = C.CDLL(binding.LIB_PATH)
+    names = declared_symbols()
+    assert len(names) >= 18
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTED) == names
+
+
+GOOD = dict(batch=1, n_q_heads=4, n_kv_heads=1, n_centroids=64, list_len=256, n_probe=4,
+            budget_k=205, max_ctx=4096)
+
+
+def test_create_validates_configuration():
+    ctx = binding.csa_create(**GOOD)
+    tb, sb = binding.csa_workspace_bytes(ctx)
+    assert tb >= 64 * 256 * 8 + 64 * 128 * 2 and sb > 0
+    binding.csa_destroy(ctx)
+    for bad in (dict(head_dim=64), dict(n_probe=0), dict(n_probe=64), dict(n_probe=65, n_centroids=100),
+                dict(n_q_heads=3), dict(n_subspaces=8), dict(list_len=0), dict(list_len=10000),
+                dict(page_size=8), dict(page_size=16, max_ctx=4100), dict(budget_k=-1),
+                dict(partition_keys=3000), dict(max_ctx=0), dict(batch=0)):
+        with pytest.raises(binding.CsaError) as e:
+            binding.csa_create(**{**GOOD, **bad})
+        assert e.value.status == binding.CSA_ERR_ARG, bad
+
+
+def test_calls_out_of_order_are_refused_on_the_host():
+    lib = binding.lib()
+    ctx = binding.csa_create(**GOOD)
+    assert lib.csa_decode_step(ctx, C.c_void_p(256), C.c_void_p(256), None, None, None) == binding.CSA_ERR_STATE
+    assert lib.csa_append_kv(ctx, C.c_void_p(256), C.c_void_p(256), None) == binding.CSA_ERR_STATE
+    assert lib.csa_build_tables(ctx, C.c_void_p(256), 4096, None) == binding.CSA_ERR_STATE
+    assert lib.csa_context_len(ctx, None, None) == binding.CSA_ERR_STATE
+    # bind: misaligned / missing / too-small buffers
+    assert lib.csa_bind(ctx, C.c_void_p(256), 1 << 40, C.c_void_p(256), 1 << 40, C.c_void_p(256),
+                        C.c_void_p(8), None) == binding.CSA_ERR_ARG
+    assert lib.csa_bind(ctx, C.c_void_p(256), 16, C.c_void_p(256), 1 << 40, C.c_void_p(256),
+                        C.c_void_p(256), None) == binding.CSA_ERR_WORKSPACE
+    assert lib.csa_bind(ctx, C.c_void_p(256), 1 << 40, C.c_void_p(256), 1 << 40, C.c_void_p(256),
+                        C.c_void_p(256), C.c_void_p(256)) == binding.CSA_ERR_ARG  # block table without paging
+    assert lib.csa_decode_step(None, None, None, None, None, None) == binding.CSA_ERR_ARG
+    binding.csa_destroy(ctx)
+    assert lib.csa_strerror(binding.CSA_ERR_RANGE).decode().startswith("table score")
+    assert lib.csa_stage_name(0).decode() == "score_centroids" and lib.csa_stage_name(99) is None

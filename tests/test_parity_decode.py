@@ -1,0 +1,217 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle on the same seeded
+inputs.  Selected indices, counts and probed rows must match exactly; attention outputs within
+2e-2 max-abs (bf16 inputs, fp32 accumulation on the GPU, fp64 in the oracle)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_08584_amd import binding
+from paper_2604_08584_amd.workload import CONFIGS
+
+from harness import Case, small
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg0_build_matches_oracle_bit_for_bit_and_decodes():
+    """BASELINE config 0: tables built on the GPU equal the oracle's tables exactly (same fma
+    chain, same grid, same tie rule), then one decode step matches."""
+    case = Case(CONFIGS["cfg0"], F=14)
+    case.build_on_gpu()
+    idx, score = case.export(0, 0)
+    o_idx, o_score, mx = case.oracle_tables(0, 0)
+    assert mx * case.w.m < 2 ** 24
+    assert np.array_equal(idx, o_idx)
+    assert np.array_equal(score, o_score)
+    err = case.check_step(0)
+    print("cfg0 max |out - oracle| =", err)
+
+
+def test_cfg0_automatic_grid():
+    """score_frac_bits < 0: the library picks F itself; the tables then equal the oracle's at
+    that F and F is the finest grid its bound allows."""
+    case = Case(CONFIGS["cfg0"], F=-1)
+    case.build_on_gpu()
+    assert 8 <= case.F <= 22
+    idx, score = case.export(0, 0)
+    o_idx, o_score, mx = case.oracle_tables(0, 0)
+    assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
+    assert mx * case.w.m < 2 ** 24 and mx * case.w.m * 8 > 2 ** 24   # within 3 bits of the limit
+    case.check_step(0)
+
+
+@pytest.mark.parametrize("G,part", [(1, 0), (2, 1024), (4, 2048), (8, 1024)])
+def test_ragged_shapes_import_and_build(G, part):
+    """Sizes that are not multiples of any tile (n_pre = 5003, C = 100, L = 300, m = 7, k = 333),
+    several key ranges, appended keys crossing the 8-item iteration and wave boundaries."""
+    w = small(f"ragged{G}", n_q_heads=2 * G, n_kv_heads=2, n_pre=5003, C=100, L=300, m=7, k=333,
+              steps=4, pre_appended=0)
+    case = Case(w, seed=G, F=13, partition_keys=part)
+    case.import_oracle_tables()
+    case.check_step(0)
+    case.append(1)
+    case.check_step(1)
+    case.append(2)
+    case.check_step(2)
+    # tables built on the GPU agree with the imported oracle tables
+    case2 = Case(w, seed=G, F=13, partition_keys=part)
+    case2.build_on_gpu()
+    for g in range(2):
+        idx, score = case2.export(0, g)
+        assert np.array_equal(idx, case.tables[(0, g)][0])
+        assert np.array_equal(score, case.tables[(0, g)][1])
+
+
+def _tie_heavy_tables(w, rng, qmax, fill):
+    idx = np.full((w.batch, w.n_kv_heads, w.C, w.L), -1, np.int32)
+    score = np.zeros((w.batch, w.n_kv_heads, w.C, w.L), np.float32)
+    for b in range(w.batch):
+        for g in range(w.n_kv_heads):
+            for j in range(w.C):
+                n = int(rng.integers(fill[0], fill[1] + 1))
+                ids = rng.choice(w.n_pre, n, replace=False).astype(np.int32)
+                q = rng.integers(-qmax, qmax + 1, n)
+                order = np.lexsort((ids, -q))
+                idx[b, g, j, :n] = ids[order]
+                score[b, g, j, :n] = q[order] * 2.0 ** -10
+    return idx, score
+
+
+@pytest.mark.parametrize("k", [1, 64, 700, 5000])
+def test_tie_breaking_with_few_distinct_sums(k):
+    """Tables with integer scores in [-2, 2]: the k-th sum is shared by hundreds of keys, so the
+    result is decided by the lowest-index rule, across key ranges and bitmap words; partially
+    filled rows (unused slots) are skipped."""
+    w = small("ties", n_q_heads=4, n_kv_heads=2, n_pre=9000, C=20, L=400, m=6, k=k, steps=1)
+    case = Case(w, seed=7, F=10, partition_keys=1024)
+    idx, score = _tie_heavy_tables(w, np.random.default_rng(k), 2, (250, 400))
+    case.import_tables(idx, score)
+    case.check_step(0)
+
+
+def test_budget_larger_than_union_and_rows_longer_than_prefill():
+    """k > |U| -> count = |U|, padding with -1; L > n_pre -> rows padded with unused slots."""
+    w = small("pad", n_pre=150, C=6, L=256, m=2, k=400, steps=2)
+    case = Case(w, seed=3, F=12)
+    case.build_on_gpu()
+    idx, score = case.export(0, 0)
+    o_idx, o_score, _ = case.oracle_tables(0, 0)
+    assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
+    assert (idx[:, 150:] == -1).all()
+    out, sel, cnt, rows = case.decode(0)
+    assert (cnt == 150).all() and (sel[..., 150:] == -1).all()
+    assert (sel[0, 0, :150] == np.arange(150)).all()
+    case.check_step(0)
+
+
+def test_zero_budget_and_empty_attention():
+    w = small("k0", k=0, steps=3)
+    case = Case(w, seed=4, F=12)
+    case.import_oracle_tables()
+    out, sel, cnt, rows = case.decode(0)
+    assert (cnt == 0).all() and (out == 0).all()          # nothing selected, nothing appended
+    case.append(3)
+    case.check_step(1)                                    # dense attention over the 3 appended keys
+
+
+@pytest.mark.parametrize("m", [1, 12])
+def test_single_probe_and_probe_all(m):
+    w = small(f"m{m}", C=12, m=m, L=128, k=100, steps=1)
+    case = Case(w, seed=5, F=12)
+    case.import_oracle_tables()
+    case.check_step(0)
+
+
+def test_many_appended_keys_fill_several_splits():
+    """600 appended keys + k = 150: the attended set spans two 512-item splits with a ragged tail."""
+    w = small("long_tail", steps=1, pre_appended=600)
+    case = Case(w, seed=6, F=12)
+    case.import_oracle_tables()
+    case.append(600)
+    case.check_step(600)
+
+
+def test_paged_cache_matches_contiguous_and_oracle():
+    """16-token pages in shuffled physical order (config 3's storage), appends crossing a page
+    boundary; the build reads K through the block table."""
+    w = small("paged", batch=2, n_q_heads=4, n_kv_heads=2, n_pre=2000, C=40, L=128, m=4, k=100,
+              steps=3, pre_appended=20, page_size=16)
+    case = Case(w, seed=8, F=12)
+    assert not torch.equal(case.k_store.view(-1)[:4096], case.inp["k_cache"].view(-1)[:4096])
+    case.build_on_gpu()
+    for b in range(2):
+        for g in range(2):
+            idx, score = case.export(b, g)
+            o_idx, o_score, _ = case.oracle_tables(b, g)
+            assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
+    case.append(20)
+    for step in range(3):
+        case.check_step(20 + step)
+        case.append(1)
+
+
+def test_repeated_steps_are_deterministic():
+    w = small("det", n_q_heads=8, n_kv_heads=2, steps=1, pre_appended=9)
+    case = Case(w, seed=9, F=12, partition_keys=1024)
+    case.import_oracle_tables()
+    case.append(9)
+    first = case.decode(9)
+    for _ in range(3):
+        again = case.decode(9)
+        for a, b in zip(first, again):
+            if a is first[3]:
+                assert np.array_equal(np.sort(a, -1), np.sort(b, -1))
+            else:
+                assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+
+
+def test_device_side_errors_are_reported():
+    w = small("err", n_pre=500, C=8, L=64, m=2, k=10, steps=1)
+    case = Case(w, seed=10, F=12)
+    idx = np.full((1, 1, 8, 64), -1, np.int32)
+    score = np.zeros((1, 1, 8, 64), np.float32)
+    idx[0, 0, :, 0] = 3
+    score[0, 0, :, 0] = 0.3                                   # not a multiple of 2^-12
+    with pytest.raises(binding.CsaError) as e:
+        case.import_tables(idx, score)
+    assert e.value.status == binding.CSA_ERR_RANGE
+    score[0, 0, :, 0] = 2.0 ** 23                             # on the grid, far too large
+    with pytest.raises(binding.CsaError) as e:
+        case.import_tables(idx, score)
+    assert e.value.status == binding.CSA_ERR_RANGE
+    score[:] = 0
+    idx[0, 0, 1, 5] = 500                                     # key index == n_pre
+    with pytest.raises(binding.CsaError) as e:
+        case.import_tables(idx, score)
+    assert e.value.status == binding.CSA_ERR_ARG
+    with pytest.raises(binding.CsaError) as e:                # tables invalid after a failed import
+        case.decode(0)
+    assert e.value.status == binding.CSA_ERR_STATE
+    idx[0, 0, 1, 5] = 499
+    case.import_tables(idx, score)
+    n_free = w.max_ctx - w.n_pre
+    for t in range(n_free):
+        case.ctx.append_kv(case.inp["k_new"][0], case.inp["v_new"][0])
+    with pytest.raises(binding.CsaError) as e:
+        case.ctx.append_kv(case.inp["k_new"][0], case.inp["v_new"][0])
+    assert e.value.status == binding.CSA_ERR_CAPACITY
+    assert binding.csa_context_len(case.ctx.ctx) == (500, w.max_ctx)
+
+
+def test_profile_counters_cover_every_stage():
+    w = small("prof", steps=2, pre_appended=0)
+    case = Case(w, seed=11, F=12)
+    case.import_oracle_tables()
+    binding.csa_profile_enable(case.ctx.ctx, True)
+    case.decode(0)
+    case.append(1)
+    case.decode(1)
+    prof = binding.csa_profile_read(case.ctx.ctx)
+    binding.csa_profile_enable(case.ctx.ctx, False)
+    assert prof["append_kv"][1] == 1
+    for name in ("score_centroids", "top_centroids", "accumulate", "select", "attention_split",
+                 "attention_merge"):
+        assert prof[name][1] == 2 and prof[name][0] > 0
+    assert all(v == (0.0, 0) for v in binding.csa_profile_read(case.ctx.ctx).values())
