@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the CSAttention decode step on one MI355X.
+
+A "step" is one pass of the whole hot path through the C-ABI library - csa_decode_step
+(centroid scoring, row gather + score accumulation, Top-K, gathered attention) followed by
+csa_append_kv - over one batch of synthetic input that is already resident in HBM.  Every step
+uses a fresh query, so the 256 MiB last-level cache cannot replay the previous step.
+
+Prints ONE JSON line (see README for the fields).  One GPU only.
+"""
+from __future__ import annotations
+
+import argparse
+import dataclasses
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="cfg4", help="cfg1..cfg4 of BASELINE.json")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--partition-keys", type=int, default=0)
+    ap.add_argument("--kmeans-sample", type=int, default=0,
+                    help="cap on pooled prefill queries seen by the centroid synthesis (0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+            f"--gpus {args.gpus} is not supported. The path shards over (sequence, KV head) "
+            "with no exchange; see DESIGN.md.")
+        sys.exit(2)
+
+    import torch
+    from paper_2604_08584_amd import binding
+    from paper_2604_08584_amd.workload import (CONFIGS, algorithmic_bytes_per_head, make_inputs,
+                                                 paginate)
+    binding.lib()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = "cuda"
+    base = CONFIGS[args.config]
+    K, W = args.steps, args.warmup
+    w = dataclasses.replace(base, steps=max(K, W, 1))
+    B, Hq, Hkv, G = w.batch, w.n_q_heads, w.n_kv_heads, w.group
+    log(f"[bench] workload {w.name}: B={B} Hq={Hq} Hkv={Hkv} N_pre={w.n_pre} C={w.C} L={w.L} "
+        f"m={w.m} k={w.k} pre_appended={w.pre_appended} page={w.page_size} steps={K} warmup={W}")
+
+    t0 = time.time()
+    inp = make_inputs(w, seed=args.seed, device=dev,
+                      kmeans_sample=args.kmeans_sample or None)
+    torch.cuda.synchronize()
+    log(f"[bench] synthetic inputs + centroids: {time.time() - t0:.1f} s")
+    if w.page_size:
+        k_store, bt = paginate(inp["k_cache"], w.page_size, args.seed, w.name)
+        v_store, _ = paginate(inp["v_cache"], w.page_size, args.seed, w.name, bt)
+    else:
+        k_store, v_store, bt = inp["k_cache"], inp["v_cache"], None
+    ctx = binding.Context(k_store, v_store, bt, batch=B, n_q_heads=Hq, n_kv_heads=Hkv,
+                          n_centroids=w.C, list_len=w.L, n_probe=w.m, budget_k=w.k,
+                          max_ctx=w.max_ctx, page_size=w.page_size, score_frac_bits=-1,
+                          partition_keys=args.partition_keys)
+    t0 = time.time()
+    ctx.build_tables(inp["centroids"], w.n_pre)
+    torch.cuda.synchronize()
+    t_build = time.time() - t0
+    log(f"[bench] csa_build_tables: {t_build:.2f} s (F = {binding.csa_score_frac_bits(ctx.ctx)})")
+
+    q_steps, k_new, v_new = inp["q_steps"], inp["k_new"], inp["v_new"]
+
+    def reset():
+        binding.csa_set_context_len(ctx.ctx, w.n_pre)
+        for t in range(w.pre_appended):
+            ctx.append_kv(k_new[t], v_new[t])
+
+    def run(n_steps):
+        for s in range(n_steps):
+            t = w.pre_appended + s
+            ctx.decode_step(q_steps[t])
+            ctx.append_kv(k_new[t], v_new[t])
+
+    # ---- warm-up, then the timed region (exactly K steps)
+    reset()
+    run(W)
+    reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(K)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    us_per_step = elapsed / K * 1e6
+    sel_mean = float(ctx.sel_count.float().mean().item())
+
+    # ---- second pass over the same K steps with per-kernel HIP events
+    reset()
+    binding.csa_profile_enable(ctx.ctx, True)
+    run(K)
+    torch.cuda.synchronize()
+    prof = binding.csa_profile_read(ctx.ctx)
+    binding.csa_profile_enable(ctx.ctx, False)
+    stage_us = {name: (ms / max(n, 1) * 1e3) for name, (ms, n) in prof.items()}
+
+    # ---- algorithmic bytes (per step, mean appended count over the timed steps)
+    t_mean = w.pre_appended + (K - 1) / 2.0
+    per_head = algorithmic_bytes_per_head(w, t_mean)
+    step_bytes = B * Hq * sum(per_head.values())
+    # dominant kernel = the gathered attention: K and V rows, q, the selected indices
+    att_bytes = B * Hq * (per_head["kv_rows"] + w.head_dim * 2 + w.k * 4)
+    att_us = stage_us["attention_split"]
+    achieved = att_bytes / (att_us * 1e-6) / 1e9
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", f"attention_split_{w.name}_hbm_traffic.txt")
+    if os.path.exists(tf):
+        mt = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(tf).read())
+        traffic = float(mt.group(1)) if mt else None
+    roofline = dict(kernel="k_attention_split", bound="hbm", achieved=round(achieved, 1),
+                    peak=PEAK_HBM_GBPS, unit="GB/s", frac=round(achieved / PEAK_HBM_GBPS, 4),
+                    traffic=traffic, algorithmic_bytes_per_launch=int(att_bytes),
+                    avg_launch_us=round(att_us, 2),
+                    measured="HIP events around each launch, second pass over the same steps")
+
+    result = {
+        "metric": "decode-step latency (µs) and achieved HBM GB/s at 128K ctx, 95% sparsity",
+        "value": round(us_per_step, 2),
+        "unit": "us/step",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(us_per_step / 1e3, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 K/V/q/centroids, int32 table scores, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
+                   "head_dim": w.head_dim, "n_pre": w.n_pre, "C": w.C, "L": w.L, "m": w.m,
+                   "k": w.k, "pre_appended": w.pre_appended, "page_size": w.page_size,
+                   "sparsity": round(1 - w.k / w.n_pre, 4), "mean_selected": sel_mean},
+        "tokens_per_s": round(B / (us_per_step * 1e-6), 1),
+        "step_algorithmic_bytes": int(step_bytes),
+        "step_hbm_gbps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
+        "step_frac_of_peak": round(step_bytes / (us_per_step * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
+        "stage_us": {k_: round(v, 2) for k_, v in stage_us.items()},
+        "build_tables_s": round(t_build, 2),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(ctx, w, inp, args.cpu_seconds)
+    print(json.dumps(result, ensure_ascii=False), flush=True)
+
+
+def cpu_baseline(ctx, w, inp, budget_s):
+    """The oracle, as it stands, on the host cores: the first decode step of the run (context =
+    N_pre + pre_appended) for the query heads of the first KV heads, scaled to the whole batch."""
+    import numpy as np
+    from oracle import oracle
+    from paper_2604_08584_amd import binding
+    n_groups = max(1, min(w.batch * w.n_kv_heads, 16 // w.group))
+    t = w.pre_appended
+    n = w.n_pre + t
+    qh = oracle.bf16_bits(inp["q_steps"][t])
+    items = []
+    for s in range(n_groups):
+        b, g = divmod(s, w.n_kv_heads)
+        idx, score = ctx.export_tables(b, g)
+        idx, score = idx.cpu().numpy(), score.cpu().numpy()
+        K = oracle.bf16_bits(inp["k_cache"][b, g])
+        V = oracle.bf16_bits(inp["v_cache"][b, g])
+        # rows [n_pre, n) of the logical cache: the keys appended before the first step
+        K[w.n_pre:n] = oracle.bf16_bits(inp["k_new"][:t, b, g])
+        V[w.n_pre:n] = oracle.bf16_bits(inp["v_new"][:t, b, g])
+        cent = oracle.bf16_bits(inp["centroids"][b, g])
+        for h in range(g * w.group, (g + 1) * w.group):
+            items.append(dict(q=np.ascontiguousarray(qh[b, h]), cent=cent, tbl_idx=idx,
+                              tbl_score=score, K=K, V=V))
+    oracle.decode_items(items[:1], w.m, w.k, w.n_pre, n)  # page the library in
+    reps, spent, used = 0, 0.0, 1
+    while spent < budget_s and reps < 50:
+        t0 = time.perf_counter()
+        *_, used = oracle.decode_items(items, w.m, w.k, w.n_pre, n, n_threads=0)
+        spent += time.perf_counter() - t0
+        reps += 1
+    per_head_s = spent / reps / len(items)
+    us_step = per_head_s * w.batch * w.n_q_heads * 1e6
+    return dict(value=round(us_step, 1), unit="us/step", cores=int(used), kind="oracle",
+                sample=f"{len(items)} of {w.batch * w.n_q_heads} (sequence, query head) items of the "
+                       f"first step, {reps} repetitions, all {used} host threads, scaled by "
+                       f"{w.batch * w.n_q_heads}/{len(items)}",
+                host_cpus=os.cpu_count())
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,73 @@
+"""GPU parity at the benchmark's full sizes (configs 1-4), in the launch configuration bench.py
+times (automatic key-range size, automatic score grid).  The oracle recomputes sampled table
+rows and sampled (sequence, head) decode steps one by one; the decode comparison always runs on
+the tables the GPU built (exported), so it is exact.  Centroid synthesis is shortened (fewer
+Lloyd iterations on a sample of the prefill queries): centroids are inputs to both sides."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2604_08584_amd.workload import CONFIGS
+
+from harness import Case
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def _check_rows(case, b, g, rows):
+    idx, score = case.export(b, g)
+    o_idx, o_score, mx = case.oracle_tables(b, g, rows)
+    assert mx * case.w.m < 2 ** 24
+    assert np.array_equal(idx[rows], o_idx), f"table rows {rows} of ({b},{g}) differ"
+    assert np.array_equal(score[rows], o_score)
+    # row invariants at full size: distinct, in range, sorted by score
+    assert all(len(set(r.tolist())) == case.w.L for r in idx[rows])
+    assert (np.diff(score[rows], axis=1) <= 0).all()
+
+
+def _light(name, steps, **kw):
+    return dataclasses.replace(CONFIGS[name], kmeans_iters=3, steps=steps, **kw)
+
+
+def test_cfg1_full_size():
+    w = _light("cfg1", 1)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=16 * w.C)
+    case.build_on_gpu()
+    _check_rows(case, 0, 3, [0, 511, 1023])
+    heads = [(0, h) for h in (0, 1, 2, 3, 12, 13, 30, 31)]
+    print("cfg1 err", case.check_step(0, heads))
+
+
+def test_cfg2_full_size_with_appends():
+    w = _light("cfg2", 4)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=16 * w.C)
+    case.build_on_gpu()
+    _check_rows(case, 0, 5, [7, 2047])
+    heads = [(0, h) for h in (0, 3, 20, 21, 22, 23)]
+    for step in range(3):
+        print("cfg2 step", step, "err", case.check_step(step, heads))
+        case.append(1)
+
+
+def test_cfg3_paged_batch():
+    w = _light("cfg3", 2)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=16 * w.C)
+    case.build_on_gpu()
+    _check_rows(case, 9, 2, [5, 1000])
+    case.append(w.pre_appended)
+    heads = [(0, 0), (0, 31), (9, 8), (9, 9), (15, 4), (15, 31)]
+    print("cfg3 err", case.check_step(w.pre_appended, heads))
+    case.append(1)
+    print("cfg3 err", case.check_step(w.pre_appended + 1, heads))
+
+
+def test_cfg4_70b_shape():
+    w = _light("cfg4", 3)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=8 * w.C)
+    case.build_on_gpu()
+    _check_rows(case, 7, 7, [4095])
+    heads = [(0, 0), (0, 7), (3, 40), (7, 56), (7, 63)]
+    for step in range(2):
+        print("cfg4 step", step, "err", case.check_step(step, heads))
+        case.append(1)
