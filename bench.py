@@ -189,7 +189,7 @@ def cpu_baseline(ctx, w, inp, budget_s):
                               tbl_score=score, K=K, V=V))
     oracle.decode_items(items[:1], w.m, w.k, w.n_pre, n)  # page the library in
     reps, spent, used = 0, 0.0, 1
-    while spent < budget_s and reps < 50:
+    while spent < budget_s and reps < 100000:
         t0 = time.perf_counter()
         *_, used = oracle.decode_items(items, w.m, w.k, w.n_pre, n, n_threads=0)
         spent += time.perf_counter() - t0

@@ -11,7 +11,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcsattn.so")
+LIB_PATH = os.environ.get("CSATTN_LIB", os.path.join(_HERE, "libcsattn.so"))
 
 CSA_OK = 0
 CSA_ERR_ARG, CSA_ERR_STATE, CSA_ERR_CAPACITY = -1, -2, -3

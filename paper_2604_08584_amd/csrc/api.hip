@@ -24,7 +24,7 @@ struct Layout {
     Region cent_t, ent, part_off;
     size_t tables_bytes = 0;
     // scratch buffer
-    Region z, rows, cand, cand_cnt, sel, sel_count, part, flags, qs;
+    Region z, rows, spans, cand, cand_cnt, hist, sel, sel_count, part, flags, qs;
     size_t scratch_bytes = 0;
     int P_max = 0, S_max = 0;
     size_t cand_keys = 0;  // candidate slots per head
@@ -43,6 +43,8 @@ struct csa_ctx {
     const int32_t *block_table = nullptr;
     bool bound = false, have_tables = false;
     int n_pre = 0, n = 0, F = -1, R = 0, P = 0;
+    uint32_t key_lo = 0;  // coarse histogram: 512 bins of 2^key_sh keys starting at key_lo
+    int key_sh = 0;
     int hip_err = 0;
     // profiling
     bool prof = false;
@@ -78,8 +80,10 @@ Layout make_layout(const csa_config &c)
     l.S_max = csa::attention_splits(c.budget_k, c.max_ctx);
     put(l.z, BH * c.n_centroids * 4);
     put(l.rows, BH * c.n_probe * 4);
+    put(l.spans, BH * (size_t)l.P_max * c.n_probe * 8);
     put(l.cand, BH * l.cand_keys * 8);
-    put(l.cand_cnt, BH * (size_t)l.P_max * 4);
+    put(l.cand_cnt, BH * (size_t)l.P_max * 4);  // candidates per (head, key range)
+    put(l.hist, BH * 512 * 4);  // per head: coarse histogram of accumulated scores
     put(l.sel, BH * (size_t)(c.budget_k > 0 ? c.budget_k : 1) * 4);
     put(l.sel_count, BH * 4);
     put(l.part, BH * (size_t)(l.S_max > 0 ? l.S_max : 1) * (c.head_dim + 2) * 4);
@@ -125,17 +129,20 @@ int check_launch(csa_ctx *ctx)
     return e == hipSuccess ? CSA_OK : hip_fail(ctx, e);
 }
 
-// range of key indices per accumulation workgroup: aim at >= 1024 workgroups per step
+// range of key indices per accumulation workgroup
 void choose_partition(csa_ctx *ctx, int n_pre)
 {
     const csa_config &c = ctx->cfg;
     int R = c.partition_keys;
     if (!R) {
+        // the accumulation kernel runs R/16 threads per key range, so the wave count does not
+        // depend on R; larger ranges amortise per-row work, but at least ~512 workgroups are wanted
         const int heads = c.batch * c.n_q_heads;
-        const int p_target = (1024 + heads - 1) / heads;
+        const int p_target = (512 + heads - 1) / heads;
         R = 16384;
         while (R > 1024 && (n_pre + R - 1) / R < p_target) R >>= 1;
     }
+    while ((n_pre + R - 1) / R > 2048 && R < 16384) R <<= 1;  // at most 2048 key ranges per head
     ctx->R = R;
     ctx->P = (n_pre + R - 1) / R;
     if (ctx->P < 1) ctx->P = 1;
@@ -146,6 +153,17 @@ T *at(char *base, const Region &r) { return reinterpret_cast<T *>(base + r.off);
 
 int qmax_for(int m) { return ((1 << 24) - 1) / m; }
 
+// The accumulated key of any key index is 2^24 + (sum of <= m table integers), so it lies within
+// m * max|q| of 2^24: 512 equal bins over that span.
+void set_key_range(csa_ctx *ctx, int qabs_max)
+{
+    const uint32_t span = (uint32_t)ctx->cfg.n_probe * (uint32_t)qabs_max;  // < 2^24
+    ctx->key_lo = (1u << 24) - span;
+    int sh = 0;
+    while (((2u * span) >> sh) >= 512u) ++sh;
+    ctx->key_sh = sh;
+}
+
 struct Prof {
     csa_ctx *ctx;
     hipStream_t st;
@@ -155,7 +173,7 @@ struct Prof {
         if (!ctx->prof) return;
         if (ctx->n_recs == ctx->recs.size()) {
             csa_ctx::Rec r;
-            for (auto &e : r.ev) hipEventCreate(&e);
+            for (auto &e : r.ev) (void)hipEventCreate(&e);
             ctx->recs.push_back(r);
         }
         rec = &ctx->recs[ctx->n_recs++];
@@ -165,7 +183,7 @@ struct Prof {
     void mark(int i)
     {
         if (!rec) return;
-        hipEventRecord(rec->ev[i], st);
+        (void)hipEventRecord(rec->ev[i], st);
         rec->used[i] = true;
     }
 };
@@ -191,7 +209,7 @@ void csa_destroy(csa_ctx *ctx)
 {
     if (!ctx) return;
     for (auto &r : ctx->recs)
-        for (auto &e : r.ev) hipEventDestroy(e);
+        for (auto &e : r.ev) (void)hipEventDestroy(e);
     delete ctx;
 }
 
@@ -271,11 +289,12 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
                              c.list_len, ctx->R, ctx->P, ctx->P + 1, st);
     int rc = check_launch(ctx);
     if (rc != CSA_OK) return rc;
-    int32_t hflags = 0;
-    e = hipMemcpyAsync(&hflags, flags, 4, hipMemcpyDeviceToHost, st);
+    int32_t hflags[2] = {0, 0};
+    e = hipMemcpyAsync(hflags, flags, 8, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) return hip_fail(ctx, e);
-    if (hflags & 1) return CSA_ERR_RANGE;
+    if (hflags[0] & 1) return CSA_ERR_RANGE;
+    set_key_range(ctx, hflags[1]);
     ctx->F = F;
     ctx->n_pre = ctx->n = n_pre;
     ctx->have_tables = true;
@@ -305,12 +324,13 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
                              c.list_len, ctx->R, ctx->P, ctx->P + 1, st);
     int rc = check_launch(ctx);
     if (rc != CSA_OK) return rc;
-    int32_t hflags = 0;
-    e = hipMemcpyAsync(&hflags, flags, 4, hipMemcpyDeviceToHost, st);
+    int32_t hflags[2] = {0, 0};
+    e = hipMemcpyAsync(hflags, flags, 8, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) return hip_fail(ctx, e);
-    if (hflags & 2) return CSA_ERR_ARG;
-    if (hflags & 1) return CSA_ERR_RANGE;
+    if (hflags[0] & 2) return CSA_ERR_ARG;
+    if (hflags[0] & 1) return CSA_ERR_RANGE;
+    set_key_range(ctx, hflags[1]);
     ctx->F = c.score_frac_bits;
     ctx->n_pre = ctx->n = n_pre;
     ctx->have_tables = true;
@@ -356,7 +376,8 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     const int BH = c.batch * c.n_q_heads, G = c.n_q_heads / c.n_kv_heads;
     float *z = at<float>(ctx->scratch, l.z);
     int32_t *rows = at<int32_t>(ctx->scratch, l.rows);
-    void *cand = at<void>(ctx->scratch, l.cand);
+    uint32_t *cand_key = at<uint32_t>(ctx->scratch, l.cand);
+    int32_t *cand_idx = reinterpret_cast<int32_t *>(cand_key + (size_t)BH * l.cand_keys);
     int32_t *cand_cnt = at<int32_t>(ctx->scratch, l.cand_cnt);
     int32_t *sel = sel_idx_dev ? sel_idx_dev : at<int32_t>(ctx->scratch, l.sel);
     int32_t *sel_count = sel_count_dev ? sel_count_dev : at<int32_t>(ctx->scratch, l.sel_count);
@@ -368,13 +389,17 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     csa::launch_score_centroids(q_dev, at<void>(ctx->tables, l.cent_t), z, c.batch, c.n_kv_heads, G,
                                 c.n_centroids, st);
     prof.mark(1);
-    csa::launch_top_centroids(z, rows, BH, c.n_centroids, c.n_probe, st);
+    void *spans = at<void>(ctx->scratch, l.spans);
+    uint32_t *hist = at<uint32_t>(ctx->scratch, l.hist);
+    csa::launch_top_centroids(z, rows, at<int32_t>(ctx->tables, l.part_off), spans, hist, BH,
+                              c.n_centroids, c.n_probe, G, ctx->P, st);
     prof.mark(2);
-    csa::launch_accumulate(at<void>(ctx->tables, l.ent), at<int32_t>(ctx->tables, l.part_off), rows, cand,
-                           cand_cnt, BH, c.n_centroids, c.list_len, c.n_probe, G, ctx->R, ctx->P,
-                           ctx->P + 1, st);
+    csa::launch_accumulate(at<void>(ctx->tables, l.ent), rows, spans, cand_key, cand_idx, cand_cnt, hist, BH,
+                           c.n_centroids, c.list_len, c.n_probe, G, ctx->R, ctx->P, l.cand_keys,
+                           ctx->key_lo, ctx->key_sh, st);
     prof.mark(3);
-    csa::launch_select(cand, cand_cnt, sel, sel_count, BH, c.budget_k, ctx->R, ctx->P, st);
+    csa::launch_select(cand_key, cand_idx, cand_cnt, sel, sel_count, hist, BH, c.budget_k, ctx->R, ctx->P,
+                       l.cand_keys, ctx->key_lo, ctx->key_sh, st);
     prof.mark(4);
     csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, part,
                                 c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ctx->n_pre, ctx->n,

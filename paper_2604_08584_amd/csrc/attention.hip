@@ -67,6 +67,7 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
             key = sel[(size_t)head * k + a];
         else if (a < n_att)
             key = n_pre + (a - n_sel);
+        if ((unsigned)key >= (unsigned)n) key = 0;  // never form an address from a bad index
         if (PAGED) {
             const int page = block_table[(size_t)b * (max_ctx >> 4) + (key >> 4)];
             rown[u] = ((int64_t)page * Hkv + g) * 16 + (key & 15);
@@ -148,20 +149,42 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
     }
 }
 
+// Merge of the S split partials of a head (a separate launch: publishing partials to a "last
+// workgroup" inside the split kernel needs device-scope fences in every workgroup, which cost far
+// more on this multi-die part than one small launch).
 // out[head][e] = sum_s o_s[e] 2^(m_s - M) / sum_s l_s 2^(m_s - M); no attended key -> 0.
 // grid B*Hq, block 128.
 __global__ __launch_bounds__(kHeadDim) void k_attention_merge(const float *__restrict__ part,
                                                               float *__restrict__ out, int S)
 {
+    __shared__ float s_f[kHeadDim];  // per-split scale (S <= 128 per pass)
+    __shared__ float s_red[2];
     const float *ph = part + (size_t)blockIdx.x * S * (kHeadDim + 2);
-    float M = -INFINITY;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, ph[(size_t)s * (kHeadDim + 2)]);
-    float acc = 0.0f, l = 0.0f;
-    for (int s = 0; s < S; ++s) {
-        const float *ps = ph + (size_t)s * (kHeadDim + 2);
-        const float f = ps[0] == -INFINITY ? 0.0f : exp2f(ps[0] - M);
-        acc += ps[2 + threadIdx.x] * f;
-        l += ps[1] * f;
+    float acc = 0.0f, l = 0.0f, M = -INFINITY;
+    for (int s0 = 0; s0 < S; s0 += kHeadDim) {
+        const int s = s0 + threadIdx.x;
+        const float ms = s < S ? ph[(size_t)s * (kHeadDim + 2)] : -INFINITY;
+        const float ls = s < S ? ph[(size_t)s * (kHeadDim + 2) + 1] : 0.0f;
+        float mx = ms;
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
+        __syncthreads();
+        if (lane_id() == 0) s_red[threadIdx.x / kWave] = mx;
+        __syncthreads();
+        const float M_new = fmaxf(M, fmaxf(s_red[0], s_red[1]));
+        const float rescale = M == -INFINITY ? 0.0f : exp2f(M - M_new);
+        acc *= rescale;
+        l *= rescale;
+        M = M_new;
+        s_f[threadIdx.x] = ms == -INFINITY ? 0.0f : exp2f(ms - M);
+        float lw = ls * s_f[threadIdx.x];
+        for (int o = 32; o > 0; o >>= 1) lw += __shfl_xor(lw, o, kWave);
+        __syncthreads();
+        if (lane_id() == 0) s_red[threadIdx.x / kWave] = lw;
+        __syncthreads();
+        l += s_red[0] + s_red[1];
+        const int ns = min(kHeadDim, S - s0);
+        for (int t = 0; t < ns; ++t)
+            acc += ph[(size_t)(s0 + t) * (kHeadDim + 2) + 2 + threadIdx.x] * s_f[t];
     }
     out[(size_t)blockIdx.x * kHeadDim + threadIdx.x] = l > 0.0f ? acc / l : 0.0f;
 }

@@ -73,47 +73,93 @@ __device__ __forceinline__ int block_excl_scan(int v, int *s_tmp, int &total)
     return off + incl - v;
 }
 
-// Radix threshold search over n keys (visited through `for_each(fn)`, which must call
-// fn(key) once per element, from any thread).  Finds T such that
-//   count(key > T) < want <= count(key >= T)            (requires 1 <= want <= n)
+// Wave-aggregated histogram increment: lanes that hit the same bin as the first pending lane
+// are counted with one LDS atomic (keys cluster heavily in the leading digits); after two such
+// rounds the remaining lanes fall back to one atomic each.
+__device__ __forceinline__ void hist_add(uint32_t *hist, uint32_t bin, bool active)
+{
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+        if (active) {  // exec = the pending lanes
+            const uint32_t lb = (uint32_t)__builtin_amdgcn_readfirstlane((int)bin);
+            const bool same = bin == lb;
+            const uint64_t mask = __ballot(same);
+            if (same) {
+                if (mbcnt(mask) == 0) atomicAdd(&hist[lb], (uint32_t)__popcll(mask));
+                active = false;
+            }
+        }
+    }
+    if (active) atomicAdd(&hist[bin], 1u);
+}
+
+// Given a histogram of NB bins in LDS, finds the bin in which the `want`-th largest element
+// falls when bins are walked from the top: returns that bin, `above` = number of elements in
+// higher bins (above < want <= above + hist[bin]).  All NT threads must call; NB % NT == 0 or
+// NT >= NB.  s_aux: NT/64 + 2 uint32 of LDS.  Ends with a barrier (hist may be reused after).
+template <int NT, int NB>
+__device__ __forceinline__ int block_pick_bin(const uint32_t *s_hist, int want, uint32_t *s_aux,
+                                              int &above)
+{
+    constexpr int BPT = NB >= NT ? NB / NT : 1;  // bins per owning thread
+    static_assert(NB >= NT ? NB % NT == 0 : true, "bins must divide evenly");
+    uint32_t *s_res = s_aux + NT / kWave;
+    // thread t owns bins NB-1-t*BPT downwards; inclusive scan from the top bin
+    int v = 0;
+    const int top = NB - 1 - (int)threadIdx.x * BPT;
+    if (top >= 0)
+#pragma unroll
+        for (int u = 0; u < BPT; ++u) v += (int)s_hist[top - u];
+    int incl = wave_incl_scan(v);
+    if (lane_id() == kWave - 1) s_aux[threadIdx.x / kWave] = (uint32_t)incl;
+    __syncthreads();
+    int off = 0;
+    for (int i = 0; i < (int)(threadIdx.x / kWave); ++i) off += (int)s_aux[i];
+    incl += off;
+    int excl = incl - v;
+    if (top >= 0 && excl < want && want <= incl) {
+#pragma unroll
+        for (int u = 0; u < BPT; ++u) {
+            const int h = (int)s_hist[top - u];
+            if (excl < want && want <= excl + h) {
+                s_res[0] = (uint32_t)(top - u);
+                s_res[1] = (uint32_t)excl;
+            }
+            excl += h;
+        }
+    }
+    __syncthreads();
+    const int bin = (int)s_res[0];
+    above = (int)s_res[1];
+    __syncthreads();
+    return bin;
+}
+
+// Radix threshold search over a set of keys visited through `for_each(fn)`, which must call
+// fn(key, valid) from every thread (valid = false for padding).
+// Finds T such that   count(key > T) < want <= count(key >= T)     (requires 1 <= want <= n).
 // Returns T; `need` = want - count(key > T) = how many keys equal to T are still wanted.
-// Keys must be < 2^(RB*PASSES).  s_hist: (1<<RB) + NT/64 + 4 uint32 of LDS.  NT >= (1<<RB).
+// Keys must be < 2^(RB*PASSES).  s_hist: 2^RB + NT/64 + 2 uint32 of LDS.
 template <int NT, int RB, int PASSES, class ForEach>
 __device__ __forceinline__ uint32_t block_radix_threshold(ForEach for_each, int want,
                                                           uint32_t *s_hist, int &need)
 {
     constexpr int NB = 1 << RB;
-    static_assert(NT >= NB, "one thread per histogram bin");
-    uint32_t *s_aux = s_hist + NB;  // [NT/64] wave totals, then [2] result
-    uint32_t *s_res = s_aux + NT / kWave;
     uint32_t prefix = 0, pmask = 0;
     int remaining = want;
     for (int pass = 0; pass < PASSES; ++pass) {
         const int shift = RB * (PASSES - 1 - pass);
         for (int i = threadIdx.x; i < NB; i += NT) s_hist[i] = 0;
         __syncthreads();
-        for_each([&](uint32_t key) {
-            if ((key & pmask) == prefix) atomicAdd(&s_hist[(key >> shift) & (NB - 1)], 1u);
+        for_each([&](uint32_t key, bool valid) {
+            hist_add(s_hist, (key >> shift) & (NB - 1), valid && (key & pmask) == prefix);
         });
         __syncthreads();
-        // thread t owns bin NB-1-t; inclusive scan from the top bin downwards
-        int v = threadIdx.x < NB ? (int)s_hist[NB - 1 - threadIdx.x] : 0;
-        int incl = wave_incl_scan(v);
-        if (lane_id() == kWave - 1) s_aux[threadIdx.x / kWave] = (uint32_t)incl;
-        __syncthreads();
-        int off = 0;
-        for (int i = 0; i < (int)(threadIdx.x / kWave); ++i) off += (int)s_aux[i];
-        incl += off;
-        const int excl = incl - v;
-        if (threadIdx.x < NB && excl < remaining && remaining <= incl) {
-            s_res[0] = (uint32_t)(NB - 1 - threadIdx.x);
-            s_res[1] = (uint32_t)excl;
-        }
-        __syncthreads();
-        prefix |= s_res[0] << shift;
+        int above;
+        const int bin = block_pick_bin<NT, NB>(s_hist, remaining, s_hist + NB, above);
+        prefix |= (uint32_t)bin << shift;
         pmask |= (uint32_t)(NB - 1) << shift;
-        remaining -= (int)s_res[1];
-        __syncthreads();
+        remaining -= above;
     }
     need = remaining;
     return prefix;

@@ -23,12 +23,15 @@ void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out,
 // ---- decode.hip
 void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
                             int C, hipStream_t st);
-void launch_top_centroids(const float *z, int32_t *rows, int n_heads, int C, int m, hipStream_t st);
-void launch_accumulate(const void *ent, const int32_t *part_off, const int32_t *rows, void *cand,
-                       int32_t *cand_cnt, int n_heads, int C, int L, int m, int G, int R, int P,
-                       int PO, hipStream_t st);
-void launch_select(const void *cand, const int32_t *cand_cnt, int32_t *sel, int32_t *sel_count,
-                   int n_heads, int k, int R, int P, hipStream_t st);
+void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, void *spans,
+                          uint32_t *hist_g, int n_heads, int C, int m, int G, int P, hipStream_t st);
+void launch_accumulate(const void *ent, const int32_t *rows, const void *spans, uint32_t *cand_key,
+                       int32_t *cand_idx, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
+                       int L, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
+                       int key_sh, hipStream_t st);
+void launch_select(const uint32_t *cand_key, const int32_t *cand_idx, const int32_t *seg_cnt,
+                   int32_t *sel, int32_t *sel_count, const uint32_t *hist_g, int n_heads, int k, int R,
+                   int P, size_t cand_stride, uint32_t key_lo, int key_sh, hipStream_t st);
 
 // ---- attention.hip
 int attention_splits(int k, int n_appended);

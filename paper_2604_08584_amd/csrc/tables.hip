@@ -45,7 +45,8 @@ __device__ __forceinline__ void bitonic_sort_u64(uint64_t *s, int NP)
 // ---------------------------------------------------------------------------------------------
 // Canonical rows -> device rows.  One workgroup per row: checks every (idx, score), converts
 // score to its grid integer q (exact or flagged), sorts by key index (unused slots last).
-// flags |= 1: score off the grid or too large; flags |= 2: index outside [-1, n_pre).
+// flags[0] |= 1: score off the grid or too large; |= 2: index outside [-1, n_pre).
+// flags[1] = max |q| over all entries (atomicMax).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_import_rows(const int32_t *__restrict__ idx,
                                                      const float *__restrict__ score,
@@ -55,7 +56,7 @@ __global__ __launch_bounds__(256) void k_import_rows(const int32_t *__restrict__
 {
     extern __shared__ uint64_t s_keys[];
     const size_t row = blockIdx.x;
-    int bad = 0;
+    int bad = 0, qabs = 0;
     for (int p = threadIdx.x; p < NP; p += 256) {
         uint64_t key = ~0ull;
         if (p < L) {
@@ -66,12 +67,15 @@ __global__ __launch_bounds__(256) void k_import_rows(const int32_t *__restrict__
                 const float qf = score[row * L + p] * up;
                 if (!(fabsf(qf) <= (float)qmax) || qf != rintf(qf)) bad |= 1;
                 const int32_t q = (int32_t)qf;
+                qabs = max(qabs, abs(q));
                 key = ((uint64_t)(uint32_t)i << 32) | (uint32_t)(q * 64 + 1);
             }
         }
         s_keys[p] = key;
     }
     if (bad) atomicOr(flags, bad);
+    for (int o = 32; o > 0; o >>= 1) qabs = max(qabs, __shfl_xor(qabs, o, kWave));
+    if (lane_id() == 0 && !bad) atomicMax(flags + 1, qabs);
     bitonic_sort_u64<256>(s_keys, NP);
     for (int p = threadIdx.x; p < L; p += 256) {
         const uint64_t key = s_keys[p];
@@ -90,7 +94,7 @@ void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32
     const int NP = next_pow2(L);
     static bool attr = false;
     if (!attr) {
-        hipFuncSetAttribute((const void *)k_import_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8);
+        (void)hipFuncSetAttribute((const void *)k_import_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8);
         attr = true;
     }
     k_import_rows<<<(unsigned)n_rows, 256, (size_t)NP * 8, st>>>(idx, score, (Entry *)ent, flags, L, NP,
@@ -136,7 +140,7 @@ void launch_export_rows(const void *ent, int32_t *idx, float *score, int n_rows,
     const int NP = next_pow2(L);
     static bool attr = false;
     if (!attr) {
-        hipFuncSetAttribute((const void *)k_export_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8);
+        (void)hipFuncSetAttribute((const void *)k_export_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8);
         attr = true;
     }
     k_export_rows<<<n_rows, 256, (size_t)NP * 8, st>>>((const Entry *)ent, idx, score, L, NP,
@@ -212,6 +216,7 @@ __global__ __launch_bounds__(256) void k_build_scores(const uint16_t *__restrict
     }
     const uint4 *cg = (const uint4 *)(cent + (((size_t)b * Hkv + g) * C + j0) * kHeadDim);
     int bad = 0;
+    float qabs = 0.0f;
     for (int t0 = 0; t0 < jc; t0 += kBuildTile) {
         const int nt = min(kBuildTile, jc - t0);
         __syncthreads();
@@ -234,10 +239,14 @@ __global__ __launch_bounds__(256) void k_build_scores(const uint16_t *__restrict
             }
             const float qf = rintf(acc * up);
             if (!(fabsf(qf) <= (float)qmax)) bad = 1;
+            qabs = fmaxf(qabs, fabsf(qf));
             if (i < n_pre) qs[(size_t)(t0 + jj) * n_pre + i] = (int32_t)qf;
         }
     }
     if (bad) atomicOr(flags, 1);
+    for (int o = 32; o > 0; o >>= 1) qabs = fmaxf(qabs, __shfl_xor(qabs, o, kWave));
+    if (lane_id() == 0 && !bad) atomicMax(flags + 1, (int)qabs);  // max |q| (a bound: every score of the
+                                                                  // chunk counts, kept or not)
 }
 
 void launch_build_scores(const void *kc, const int32_t *block_table, const void *cent, int32_t *qs,
@@ -277,7 +286,10 @@ __global__ __launch_bounds__(kBsNT) void k_build_select(const int32_t *__restric
     if (n_pre > L) {
         T = block_radix_threshold<kBsNT, 8, 4>(
             [&](auto fn) {
-                for (int i = threadIdx.x; i < n_pre; i += kBsNT) fn((uint32_t)qr[i] ^ 0x80000000u);
+                for (int i0 = 0; i0 < n_pre; i0 += kBsNT) {
+                    const int i = i0 + threadIdx.x;
+                    fn(i < n_pre ? ((uint32_t)qr[i] ^ 0x80000000u) : 0u, i < n_pre);
+                }
             },
             want, s_hist, need);
     }
