@@ -128,27 +128,35 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
             }
         }
     };
-    if (m <= kTopNT / 4) {
+    if (m <= kTopNT / 4 && C >= kTopNT) {  // every lane holds at least one value
         // ---- fast path
         uint32_t best = 0;  // orderable(z) of a finite z is never 0
         visit([&](int, uint32_t key, bool valid) { if (valid && key > best) best = key; });
-        s_hist[threadIdx.x] = best;
-        __syncthreads();
-        int rank = 0;  // number of thread maxima ahead of mine (ties: lower thread first)
+        // a lower bound on the m-th largest value overall: in each wave the r-th largest of the
+        // 64 lane maxima, r = ceil(m / waves) (found by r rounds of max-and-remove); the smallest
+        // of these over the waves has at least m values at or above it
         {
-            const uint4 *h4 = (const uint4 *)s_hist;
-            const int me = threadIdx.x;
-#pragma unroll 8
-            for (int t4 = 0; t4 < kTopNT / 4; ++t4) {
-                const uint4 o = h4[t4];
-                rank += (o.x > best) || (o.x == best && 4 * t4 + 0 < me);
-                rank += (o.y > best) || (o.y == best && 4 * t4 + 1 < me);
-                rank += (o.z > best) || (o.z == best && 4 * t4 + 2 < me);
-                rank += (o.w > best) || (o.w == best && 4 * t4 + 3 < me);
+            constexpr int NWT = kTopNT / kWave;
+            const int r = (m + NWT - 1) / NWT;  // <= 16 of the 64 lane maxima; NWT * r >= m
+            uint64_t cur = ((uint64_t)best << 32) | (uint32_t)~threadIdx.x;  // distinct per lane
+            uint64_t wmax = 0ull;
+            for (int round = 0; round < r; ++round) {
+                wmax = cur;
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) {
+                    const uint64_t t = __shfl_xor(wmax, o, kWave);
+                    wmax = t > wmax ? t : wmax;
+                }
+                if (cur == wmax) cur = 0ull;  // remove the winner
+            }
+            if (lane_id() == 0) s_hist[threadIdx.x / kWave] = (uint32_t)(wmax >> 32);
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                uint32_t bnd = 0xFFFFFFFFu;
+                for (int w = 0; w < NWT; ++w) bnd = min(bnd, s_hist[w]);
+                s_bound = bnd;
             }
         }
-        const int n_valid_threads = C < kTopNT ? C : kTopNT;  // threads that hold a value
-        if (rank == (m < n_valid_threads ? m : n_valid_threads) - 1) s_bound = best;
         __syncthreads();
         const uint32_t bound = s_bound;
         visit([&](int j, uint32_t key, bool valid) {
@@ -159,7 +167,7 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
         });
         __syncthreads();
         const int nc = s_slot;
-        if (nc <= kTopCand) {
+        if (nc <= kTopCand && nc >= m) {  // (nc >= m always holds; checked so that no row is ever left unset)
             if (threadIdx.x == 0) s_ck[nc] = 0;  // pad to an even count (0 beats nothing)
             __syncthreads();
             const ulonglong2 *c2 = (const ulonglong2 *)s_ck;
@@ -225,12 +233,12 @@ void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off
 // a key absent from every probed row is not a candidate even if all sums are negative).
 // The kernel is bound by instruction issue as much as by HBM, so the per-entry and per-slot
 // paths are kept minimal: a wave owns whole rows (row constants are scalar), keeps eight
-// 512-byte loads in flight per lane group, and the sparse accumulator array is first compacted
+// 512-byte loads in flight (two rows at a time), and the sparse accumulator array is first compacted
 // into LDS; only the dense survivors are turned into (sum + 2^24, index), counted into the
 // head's coarse histogram and written out, in segment p of the head's candidate arrays.
 // grid (P, B*Hq), block NT = R/16, dynamic LDS R*4 bytes.
 // ---------------------------------------------------------------------------------------------
-constexpr int kAccUnroll = 8;
+constexpr int kAccUnroll = 4;
 
 template <int NT>
 __global__ __launch_bounds__(NT, 8) void k_accumulate(const Entry *__restrict__ ent,
@@ -266,21 +274,31 @@ __global__ __launch_bounds__(NT, 8) void k_accumulate(const Entry *__restrict__ 
     }
     __syncthreads();
     const int base = p * R;
-    for (int r = wave; r < m; r += NW) {
-        const int lo = __builtin_amdgcn_readfirstlane(s_lo[r]);
-        const int hi = __builtin_amdgcn_readfirstlane(s_hi[r]);
-        const Entry *rp = ent + ((size_t)bg * C + __builtin_amdgcn_readfirstlane(s_row[r])) * L;
-        for (int e0 = lo; e0 < hi; e0 += kWave * kAccUnroll) {
-            Entry v[kAccUnroll];
+    // two rows per wave at a time, kAccUnroll 512-byte loads in flight for each
+    for (int r = wave; r < m; r += 2 * NW) {
+        const int r2 = r + NW < m ? r + NW : r;
+        const int lo_a = __builtin_amdgcn_readfirstlane(s_lo[r]);
+        const int hi_a = __builtin_amdgcn_readfirstlane(s_hi[r]);
+        const int lo_b = __builtin_amdgcn_readfirstlane(s_lo[r2]);
+        const int hi_b = r2 != r ? __builtin_amdgcn_readfirstlane(s_hi[r2]) : lo_b;  // empty if no 2nd row
+        const Entry *rp_a = ent + ((size_t)bg * C + __builtin_amdgcn_readfirstlane(s_row[r])) * L;
+        const Entry *rp_b = ent + ((size_t)bg * C + __builtin_amdgcn_readfirstlane(s_row[r2])) * L;
+        for (int ea = lo_a, eb = lo_b; ea < hi_a || eb < hi_b;
+             ea += kWave * kAccUnroll, eb += kWave * kAccUnroll) {
+            Entry va[kAccUnroll], vb[kAccUnroll];
 #pragma unroll
             for (int u = 0; u < kAccUnroll; ++u) {
-                const int e = e0 + u * kWave + lane;
-                v[u].idx = -1;
-                if (e < hi) v[u] = rp[e];
+                const int xa = ea + u * kWave + lane, xb = eb + u * kWave + lane;
+                va[u].idx = -1;
+                vb[u].idx = -1;
+                if (xa < hi_a) va[u] = rp_a[xa];
+                if (xb < hi_b) vb[u] = rp_b[xb];
             }
 #pragma unroll
-            for (int u = 0; u < kAccUnroll; ++u)
-                if (v[u].idx >= 0) atomicAdd(&s_acc[v[u].idx - base], v[u].qe);
+            for (int u = 0; u < kAccUnroll; ++u) {
+                if (va[u].idx >= 0) atomicAdd(&s_acc[va[u].idx - base], va[u].qe);
+                if (vb[u].idx >= 0) atomicAdd(&s_acc[vb[u].idx - base], vb[u].qe);
+            }
         }
     }
     __syncthreads();
@@ -299,7 +317,7 @@ __global__ __launch_bounds__(NT, 8) void k_accumulate(const Entry *__restrict__ 
     uint2 *s_stage = (uint2 *)s_acc;  // R/2 (accumulator, local slot) pairs at a time
     constexpr int half = R / 2;
     for (int w0 = 0; w0 < total; w0 += half) {
-        if (w0) __syncthreads();  // previous window copied out
+        if (w0) __syncthreads();  // previous window consumed
         int q = pos - w0;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -323,7 +341,10 @@ __global__ __launch_bounds__(NT, 8) void k_accumulate(const Entry *__restrict__ 
         }
     }
     if (threadIdx.x == 0) seg_cnt[(size_t)head * P + p] = total;
-    __syncthreads();  // histogram complete
+    // histogram complete once every wave's LDS atomics have landed: wait for LDS traffic only
+    // (a full __syncthreads would also wait for the candidate stores above)
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), vmcnt / expcnt untouched
+    __builtin_amdgcn_s_barrier();
     for (int e = threadIdx.x; e < kCoarseBins; e += NT) {
         const uint32_t c = s_h[e];
         if (c) atomicAdd(&hist_g[(size_t)head * kCoarseBins + e], c);
@@ -418,28 +439,31 @@ __global__ __launch_bounds__(kSelNT, 8) void k_select(const uint32_t *__restrict
     for (int a = k_eff + threadIdx.x; a < k; a += kSelNT) out[a] = -1;
     if (k_eff == 0) return;
 
-    // stream(fn): fn(slot, key, valid) over the candidates of every segment.  A wave walks whole
-    // segments, four consecutive slots per lane and load, up to four loads in flight; fn may use
-    // wave-level operations only (trip counts differ between waves).
+    // stream(fn): fn(key, key_index, valid) over the candidates of every segment.  A wave walks
+    // whole segments, four consecutive slots per lane and load, keys and indices both read with
+    // full-width loads issued up front (a dependent index load per winner would serialise the
+    // walk); fn may use wave-level operations only (trip counts differ between waves).
     auto stream = [&](auto fn) {
         for (int p = wave; p < P; p += NW) {
             const int c = s_cnt[p];
             const int s0 = p * R;
             for (int e0 = 0; e0 < c; e0 += kWave * 16) {
                 uint4 kk[4];
+                int4 ii[4];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
                     const int e = e0 + (x * kWave + lane) * 4;
                     kk[x] = e < c ? *(const uint4 *)(hk + s0 + e) : make_uint4(0, 0, 0, 0);
+                    ii[x] = e < c ? *(const int4 *)(hi_ + s0 + e) : make_int4(0, 0, 0, 0);
                 }
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
                     const int e = e0 + (x * kWave + lane) * 4;
                     if (e0 + x * kWave * 4 < c) {  // wave-uniform
-                        fn(s0 + e + 0, kk[x].x, e + 0 < c);
-                        fn(s0 + e + 1, kk[x].y, e + 1 < c);
-                        fn(s0 + e + 2, kk[x].z, e + 2 < c);
-                        fn(s0 + e + 3, kk[x].w, e + 3 < c);
+                        fn(kk[x].x, ii[x].x, e + 0 < c);
+                        fn(kk[x].y, ii[x].y, e + 1 < c);
+                        fn(kk[x].z, ii[x].z, e + 2 < c);
+                        fn(kk[x].w, ii[x].w, e + 3 < c);
                     }
                 }
             }
@@ -468,7 +492,7 @@ __global__ __launch_bounds__(kSelNT, 8) void k_select(const uint32_t *__restrict
                 while (((hi - lo) >> sh) >= 512u) ++sh;
                 for (int i = threadIdx.x; i < 512; i += kSelNT) s_hist[i] = 0;
                 __syncthreads();
-                stream([&](int, uint32_t key, bool valid) {
+                stream([&](uint32_t key, int, bool valid) {
                     const bool in = valid && key >= lo && key <= hi;
                     hist_add(s_hist, in ? (key - lo) >> sh : 0u, in);
                 });
@@ -489,16 +513,16 @@ __global__ __launch_bounds__(kSelNT, 8) void k_select(const uint32_t *__restrict
                 // gather the contenders (key - lo < 2^sh <= 2^16) with their key indices; with a
                 // single bitmap chunk, keys above the bin are sure winners and are marked now
                 __syncthreads();
-                stream([&](int slot, uint32_t key, bool valid) {
+                stream([&](uint32_t key, int key_index, bool valid) {
                     const bool in = valid && key >= lo && key <= hi;
                     const uint64_t mask = __ballot(in);
                     if (mask) {
                         int wbase = 0;
                         if (mbcnt(mask) == 0 && in) wbase = atomicAdd(&s_n, __popcll(mask));
-                        wbase = __shfl(wbase, __ffsll((unsigned long long)mask) - 1, kWave);
-                        if (in) s_ck[wbase + mbcnt(mask)] = make_uint2(key - lo, (uint32_t)hi_[slot]);
+                        wbase = __builtin_amdgcn_readlane(wbase, __ffsll((unsigned long long)mask) - 1);
+                        if (in) s_ck[wbase + mbcnt(mask)] = make_uint2(key - lo, (uint32_t)key_index);
                     }
-                    if (single && valid && key > hi) mark(s_gt, hi_[slot], 0);
+                    if (single && valid && key > hi) mark(s_gt, key_index, 0);
                 });
                 __syncthreads();
                 const int nc = s_n;
@@ -539,8 +563,8 @@ __global__ __launch_bounds__(kSelNT, 8) void k_select(const uint32_t *__restrict
                 }
             }
             __syncthreads();
-            stream([&](int slot, uint32_t key, bool valid) {
-                if (valid && key >= T) mark(key > T ? s_gt : s_eq, hi_[slot], c0);
+            stream([&](uint32_t key, int key_index, bool valid) {
+                if (valid && key >= T) mark(key > T ? s_gt : s_eq, key_index, c0);
             });
         }
         marked = false;
