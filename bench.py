@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--kmeans-sample", type=int, default=0,
                     help="cap on pooled prefill queries seen by the centroid synthesis (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device-to-device copies before the timed region, "
+                         "so that a counter run has a kernel of known HBM traffic to scale by")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -93,6 +96,14 @@ def main():
             t = w.pre_appended + s
             ctx.decode_step(q_steps[t])
             ctx.append_kv(k_new[t], v_new[t])
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- warm-up, then the timed region (exactly K steps)
     reset()

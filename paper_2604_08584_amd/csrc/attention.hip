@@ -16,6 +16,7 @@ __device__ __forceinline__ float row16_sum(float v)
     return v;
 }
 
+constexpr int kXcd = 8;                          // accelerator dies, each with a private L2
 constexpr int kAttNT = 256;                     // 4 waves
 constexpr int kAttWaves = kAttNT / kWave;
 constexpr int kItemsPerWave = 128;              // two index registers per lane
@@ -29,17 +30,25 @@ constexpr int kSplit = kAttWaves * kItemsPerWave;  // 512 attended keys per work
 // own online-softmax state for the rows it sees, merged at the end.  Logits are taken in the
 // log2 domain (q pre-scaled by log2(e)/sqrt(d)).  Output: un-normalised partial
 // (max, sum, o[128]) per (head, split).
-// grid (S, B*Hq), block 256.
+// grid ceil8(B*Hkv*S) * G workgroups (1-D, see the id mapping below), block 256.
 // ---------------------------------------------------------------------------------------------
 template <bool PAGED>
 __global__ __launch_bounds__(kAttNT) void k_attention_split(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc,
     const int32_t *__restrict__ block_table, const int32_t *__restrict__ sel,
     const int32_t *__restrict__ sel_count, float *__restrict__ part, int k, int n_pre, int n,
-    int Hq, int G, int Hkv, int max_ctx, int S, float qscale)
+    int Hq, int G, int Hkv, int max_ctx, int S, int n_units, float qscale)
 {
     __shared__ float s_m[kAttWaves], s_l[kAttWaves], s_o[kAttWaves][kHeadDim];
-    const int s = blockIdx.x, head = blockIdx.y;
+    // XCD-aware order: the chip deals consecutive workgroup ids round-robin to its 8 XCDs (each
+    // with its own L2).  The G query heads of a KV head select overlapping keys, so the G
+    // workgroups that handle the same split of the same KV head get ids 8 apart: same XCD, same
+    // moment, and a K/V row fetched for one head is an L2 hit for the others.
+    const int id = blockIdx.x;
+    const int unit = (id / (kXcd * G)) * kXcd + id % kXcd;  // (KV head, split) pair
+    if (unit >= n_units) return;                            // grid padded to a multiple of 8 * G
+    const int s = unit % S;
+    const int head = (unit / S) * G + (id % (kXcd * G)) / kXcd;
     const int b = head / Hq, g = (head % Hq) / G;
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int sub = lane >> 4, c = lane & 15;
@@ -199,15 +208,16 @@ void launch_attention_split(const void *q, const void *kc, const void *vc,
     if (S <= 0) return;
     const float qscale = 1.4426950408889634f / sqrtf((float)kHeadDim);
     const int G = Hq / Hkv;
-    dim3 grid(S, B * Hq), block(kAttNT);
+    const int n_units = B * Hkv * S;
+    dim3 grid((n_units + kXcd - 1) / kXcd * kXcd * G), block(kAttNT);
     if (block_table)
         k_attention_split<true><<<grid, block, 0, st>>>(
             (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, block_table, sel,
-            sel_count, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, qscale);
+            sel_count, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, n_units, qscale);
     else
         k_attention_split<false><<<grid, block, 0, st>>>(
             (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, nullptr, sel,
-            sel_count, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, qscale);
+            sel_count, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, n_units, qscale);
 }
 
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st)

@@ -241,7 +241,7 @@ void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off
 constexpr int kAccUnroll = 4;
 
 template <int NT>
-__global__ __launch_bounds__(NT, 8) void k_accumulate(const Entry *__restrict__ ent,
+__global__ __launch_bounds__(NT) void k_accumulate(const Entry *__restrict__ ent,
                                                    const int32_t *__restrict__ rows,
                                                    const int2 *__restrict__ spans,
                                                    uint32_t *__restrict__ cand_key,
@@ -398,7 +398,7 @@ constexpr int kChunk = 131072;                      // key indices per bitmap ch
 constexpr int kChunkWords = kChunk / 32;            // 4096 words
 constexpr int kWordsPerThread = kChunkWords / kSelNT;  // 4 consecutive words per thread
 
-__global__ __launch_bounds__(kSelNT, 8) void k_select(const uint32_t *__restrict__ cand_key,
+__global__ __launch_bounds__(kSelNT) void k_select(const uint32_t *__restrict__ cand_key,
                                                    const int32_t *__restrict__ cand_idx,
                                                    const int32_t *__restrict__ seg_cnt,
                                                    int32_t *__restrict__ sel,
