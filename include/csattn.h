@@ -66,7 +66,8 @@ typedef struct {
  * Score grid (decides which keys are kept, so it is part of the interface): a table score s is
  * stored as the integer q = round-half-even(s * 2^F); the accumulated score of a key
  * (Sec. 3.3 (3), w_b = 1) is the exact integer sum of its q over the probed rows.  The library
- * requires n_probe * max|q| < 2^24, so the same sums are also exact in fp32 in any order.
+ * requires n_probe * max|q| < 2^24, so the same sums are also exact in fp32 in any order, and
+ * max|q| < 2^19 (a table entry is kept in 32 bits on the device: 20 bits of q, 12 index bits).
  */
 
 /* Validates `cfg` and creates the host object.  No device work, no device allocation. */
@@ -100,7 +101,7 @@ int csa_bind(csa_ctx *ctx, void *tables_dev, size_t tables_bytes, void *scratch_
  *   centroids_dev: bf16 [B][Hkv][C][d], unit norm (Sec. 3.2 (1); clustering is the caller's).
  * K is read from the bound cache, rows [0, n_pre).  Sets the context length to n_pre.
  * SYNCHRONISES `stream` before returning (it reads back an overflow flag); returns
- * CSA_ERR_RANGE if some |q| * n_probe >= 2^24 (tables are then unusable).
+ * CSA_ERR_RANGE if some |q| * n_probe >= 2^24 or |q| >= 2^19 (tables are then unusable).
  */
 int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, void *stream);
 
@@ -160,7 +161,7 @@ int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream);
  * launches into launches[CSA_N_STAGES] (either may be NULL), and clears the record.
  * Events cost a few microseconds per stage: leave disabled when timing whole steps.
  */
-#define CSA_N_STAGES 7
+#define CSA_N_STAGES 8
 int csa_profile_enable(csa_ctx *ctx, int32_t on);
 int csa_profile_read(csa_ctx *ctx, double *ms_sum, int64_t *launches);
 const char *csa_stage_name(int32_t stage); /* NULL if out of range */

@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("CSATTN_LIB", os.path.join(_HERE, "libcsattn.so"))
 CSA_OK = 0
 CSA_ERR_ARG, CSA_ERR_STATE, CSA_ERR_CAPACITY = -1, -2, -3
 CSA_ERR_WORKSPACE, CSA_ERR_HIP, CSA_ERR_RANGE = -4, -5, -6
-CSA_N_STAGES = 7
+CSA_N_STAGES = 8
 
 
 class csa_config(C.Structure):

@@ -24,14 +24,15 @@ struct Layout {
     Region cent_t, ent, part_off;
     size_t tables_bytes = 0;
     // scratch buffer
-    Region z, rows, spans, cand, cand_cnt, hist, sel, sel_count, part, flags, qs;
+    Region z, rows, spans, cand, cand_bits, cand_cnt, seg_par, thr, hist, sel, sel_count, part, flags, qs;
     size_t scratch_bytes = 0;
-    int P_max = 0, S_max = 0;
+    int P_max = 0, PO_max = 0, S_max = 0, Ls = 0;
     size_t cand_keys = 0;  // candidate slots per head
 };
 
-const char *kStageNames[CSA_N_STAGES] = {"score_centroids", "top_centroids", "accumulate", "select",
-                                         "attention_split", "attention_merge", "append_kv"};
+const char *kStageNames[CSA_N_STAGES] = {"score_centroids", "top_centroids",   "accumulate", "select_threshold",
+                                         "select_emit",     "attention_split", "attention_merge", "append_kv"};
+constexpr int kUnit = 4096;  // key indices per block of a packed table row (see common.h)
 
 }  // namespace
 
@@ -43,6 +44,7 @@ struct csa_ctx {
     const int32_t *block_table = nullptr;
     bool bound = false, have_tables = false;
     int n_pre = 0, n = 0, F = -1, R = 0, P = 0;
+    int Q = 0, nsub = 0, PO = 0;  // block size min(R, 4096), blocks per range, offsets per row
     uint32_t key_lo = 0;  // coarse histogram: 512 bins of 2^key_sh keys starting at key_lo
     int key_sh = 0;
     int hip_err = 0;
@@ -65,6 +67,9 @@ Layout make_layout(const csa_config &c)
     Layout l;
     const size_t BG = (size_t)c.batch * c.n_kv_heads, BH = (size_t)c.batch * c.n_q_heads;
     l.P_max = (c.max_ctx + min_R(c) - 1) / min_R(c);
+    const int q_min = min_R(c) < kUnit ? min_R(c) : kUnit;
+    l.PO_max = (c.max_ctx + q_min - 1) / q_min + 5;  // >= P * nsub + 1 for every admissible R
+    l.Ls = (c.list_len + 3) / 4 * 4;                 // row stride: 16-byte aligned rows
     size_t off = 0;
     auto put = [&](Region &r, size_t bytes) {
         r.off = off;
@@ -72,17 +77,20 @@ Layout make_layout(const csa_config &c)
         off = align_up(off + bytes);
     };
     put(l.cent_t, BG * c.n_centroids * c.head_dim * 2);
-    put(l.ent, BG * c.n_centroids * c.list_len * 8);
-    put(l.part_off, BG * c.n_centroids * (size_t)(l.P_max + 1) * 4);
+    put(l.ent, BG * c.n_centroids * (size_t)l.Ls * 4);
+    put(l.part_off, BG * c.n_centroids * (size_t)l.PO_max * 4);
     l.tables_bytes = off;
     off = 0;
     l.cand_keys = ((size_t)c.max_ctx + 16383) / 16384 * 16384;
     l.S_max = csa::attention_splits(c.budget_k, c.max_ctx);
     put(l.z, BH * c.n_centroids * 4);
     put(l.rows, BH * c.n_probe * 4);
-    put(l.spans, BH * (size_t)l.P_max * c.n_probe * 8);
-    put(l.cand, BH * l.cand_keys * 8);
+    put(l.spans, BH * (size_t)c.n_probe * 2 * l.PO_max * 4);  // P * (nsub + 1) <= 2 * PO offsets per row
+    put(l.cand, BH * l.cand_keys * 4);       // candidate keys, R slots per (head, key range)
+    put(l.cand_bits, BH * l.cand_keys / 8);  // presence bitmap over the key indices
     put(l.cand_cnt, BH * (size_t)l.P_max * 4);  // candidates per (head, key range)
+    put(l.seg_par, BH * (size_t)l.P_max * 8);   // (output offset, ties allowed) per (head, key range)
+    put(l.thr, BH * 4);                         // Top-K threshold per head
     put(l.hist, BH * 512 * 4);  // per head: coarse histogram of accumulated scores
     put(l.sel, BH * (size_t)(c.budget_k > 0 ? c.budget_k : 1) * 4);
     put(l.sel_count, BH * 4);
@@ -147,12 +155,20 @@ void choose_partition(csa_ctx *ctx, int n_pre)
     ctx->R = R;
     ctx->P = (n_pre + R - 1) / R;
     if (ctx->P < 1) ctx->P = 1;
+    ctx->Q = R < kUnit ? R : kUnit;
+    ctx->nsub = R / ctx->Q;
+    ctx->PO = ctx->P * ctx->nsub + 1;
 }
 
 template <class T>
 T *at(char *base, const Region &r) { return reinterpret_cast<T *>(base + r.off); }
 
-int qmax_for(int m) { return ((1 << 24) - 1) / m; }
+// largest admissible |q|: m sums stay below 2^24 and q fits the 20-bit field of a packed entry
+int qmax_for(int m)
+{
+    const int a = ((1 << 24) - 1) / m, b = (1 << 19) - 1;
+    return a < b ? a : b;
+}
 
 // The accumulated key of any key index is 2^24 + (sum of <= m table integers), so it lies within
 // m * max|q| of 2^24: 512 equal bins over that span.
@@ -272,10 +288,12 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
         if (F < 0) return CSA_ERR_RANGE;
     }
     choose_partition(ctx, n_pre);
+    if (ctx->PO > l.PO_max || ctx->P > l.P_max) return CSA_ERR_WORKSPACE;  // (cannot happen: see make_layout)
     const int BG = c.batch * c.n_kv_heads;
     csa::launch_pack_centroids(centroids_dev, at<void>(ctx->tables, l.cent_t), BG, c.n_centroids, st);
     int32_t *qs = at<int32_t>(ctx->scratch, l.qs);
     char *ent = at<char>(ctx->tables, l.ent);
+    int32_t *part_off = at<int32_t>(ctx->tables, l.part_off);
     for (int b = 0; b < c.batch; ++b)
         for (int g = 0; g < c.n_kv_heads; ++g)
             for (int j0 = 0; j0 < c.n_centroids; j0 += kBuildChunk) {
@@ -284,10 +302,9 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
                                          c.n_kv_heads, c.max_ctx, n_pre, c.n_centroids, j0, jc, F,
                                          qmax_for(c.n_probe), st);
                 const size_t row0 = ((size_t)(b * c.n_kv_heads + g) * c.n_centroids + j0);
-                csa::launch_build_select(qs, ent + row0 * c.list_len * 8, jc, n_pre, c.list_len, st);
+                csa::launch_build_select(qs, ent + row0 * l.Ls * 4, part_off + row0 * ctx->PO, jc, n_pre,
+                                         c.list_len, l.Ls, ctx->Q, ctx->PO, st);
             }
-    csa::launch_part_offsets(ent, at<int32_t>(ctx->tables, l.part_off), (int64_t)BG * c.n_centroids,
-                             c.list_len, ctx->R, ctx->P, ctx->P + 1, st);
     int rc = check_launch(ctx);
     if (rc != CSA_OK) return rc;
     int32_t hflags[2] = {0, 0};
@@ -316,13 +333,13 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
     hipError_t e = hipMemsetAsync(flags, 0, 256, st);
     if (e != hipSuccess) return hip_fail(ctx, e);
     choose_partition(ctx, n_pre);
+    if (ctx->PO > l.PO_max || ctx->P > l.P_max) return CSA_ERR_WORKSPACE;  // (cannot happen: see make_layout)
     const int BG = c.batch * c.n_kv_heads;
     const int64_t n_rows = (int64_t)BG * c.n_centroids;
     csa::launch_pack_centroids(centroids_dev, at<void>(ctx->tables, l.cent_t), BG, c.n_centroids, st);
-    csa::launch_import_rows(idx_dev, score_dev, at<void>(ctx->tables, l.ent), flags, n_rows, c.list_len,
-                            n_pre, c.score_frac_bits, qmax_for(c.n_probe), st);
-    csa::launch_part_offsets(at<void>(ctx->tables, l.ent), at<int32_t>(ctx->tables, l.part_off), n_rows,
-                             c.list_len, ctx->R, ctx->P, ctx->P + 1, st);
+    csa::launch_import_rows(idx_dev, score_dev, at<void>(ctx->tables, l.ent), at<int32_t>(ctx->tables, l.part_off),
+                            flags, n_rows, c.list_len, l.Ls, n_pre, c.score_frac_bits, qmax_for(c.n_probe),
+                            ctx->Q, ctx->PO, st);
     int rc = check_launch(ctx);
     if (rc != CSA_OK) return rc;
     int32_t hflags[2] = {0, 0};
@@ -346,8 +363,10 @@ int csa_export_tables(const csa_ctx *ctx, int32_t b, int32_t g, int32_t *idx_dev
     const csa_config &c = ctx->cfg;
     if (b < 0 || b >= c.batch || g < 0 || g >= c.n_kv_heads) return CSA_ERR_ARG;
     const size_t row0 = (size_t)(b * c.n_kv_heads + g) * c.n_centroids;
-    csa::launch_export_rows(ctx->tables + ctx->lay.ent.off + row0 * c.list_len * 8, idx_dev, score_dev,
-                            c.n_centroids, c.list_len, ctx->F, (hipStream_t)stream);
+    const int32_t *part_off = reinterpret_cast<const int32_t *>(ctx->tables + ctx->lay.part_off.off);
+    csa::launch_export_rows(ctx->tables + ctx->lay.ent.off + row0 * ctx->lay.Ls * 4, part_off + row0 * ctx->PO,
+                            idx_dev, score_dev, c.n_centroids, c.list_len, ctx->lay.Ls, ctx->F, ctx->Q,
+                            ctx->PO, (hipStream_t)stream);
     return check_launch(const_cast<csa_ctx *>(ctx));
 }
 
@@ -358,10 +377,10 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
     if (ctx->n >= ctx->cfg.max_ctx) return CSA_ERR_CAPACITY;
     hipStream_t st = (hipStream_t)stream;
     Prof prof(ctx, st);
-    prof.mark(6);
+    prof.mark(7);
     csa::launch_append(ctx->k_cache, ctx->v_cache, ctx->block_table, k_new_dev, v_new_dev,
                        ctx->cfg.batch, ctx->cfg.n_kv_heads, ctx->n, ctx->cfg.max_ctx, st);
-    prof.mark(7);
+    prof.mark(8);
     ctx->n += 1;
     return check_launch(ctx);
 }
@@ -378,8 +397,10 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     float *z = at<float>(ctx->scratch, l.z);
     int32_t *rows = at<int32_t>(ctx->scratch, l.rows);
     uint32_t *cand_key = at<uint32_t>(ctx->scratch, l.cand);
-    int32_t *cand_idx = reinterpret_cast<int32_t *>(cand_key + (size_t)BH * l.cand_keys);
+    uint32_t *cand_bits = at<uint32_t>(ctx->scratch, l.cand_bits);
     int32_t *cand_cnt = at<int32_t>(ctx->scratch, l.cand_cnt);
+    void *seg_par = at<void>(ctx->scratch, l.seg_par);
+    uint32_t *thr = at<uint32_t>(ctx->scratch, l.thr);
     int32_t *sel = sel_idx_dev ? sel_idx_dev : at<int32_t>(ctx->scratch, l.sel);
     int32_t *sel_count = sel_count_dev ? sel_count_dev : at<int32_t>(ctx->scratch, l.sel_count);
     float *part = at<float>(ctx->scratch, l.part);
@@ -390,24 +411,27 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     csa::launch_score_centroids(q_dev, at<void>(ctx->tables, l.cent_t), z, c.batch, c.n_kv_heads, G,
                                 c.n_centroids, st);
     prof.mark(1);
-    void *spans = at<void>(ctx->scratch, l.spans);
+    int32_t *spans = at<int32_t>(ctx->scratch, l.spans);
     uint32_t *hist = at<uint32_t>(ctx->scratch, l.hist);
     csa::launch_top_centroids(z, rows, at<int32_t>(ctx->tables, l.part_off), spans, hist, BH,
-                              c.n_centroids, c.n_probe, G, ctx->P, st);
+                              c.n_centroids, c.n_probe, G, ctx->P, ctx->nsub, ctx->PO, st);
     prof.mark(2);
-    csa::launch_accumulate(at<void>(ctx->tables, l.ent), rows, spans, cand_key, cand_idx, cand_cnt, hist, BH,
-                           c.n_centroids, c.list_len, c.n_probe, G, ctx->R, ctx->P, l.cand_keys,
-                           ctx->key_lo, ctx->key_sh, st);
+    csa::launch_accumulate(at<void>(ctx->tables, l.ent), rows, spans, cand_key, cand_bits, cand_cnt, hist, BH,
+                           c.n_centroids, l.Ls, c.n_probe, G, ctx->R, ctx->P, l.cand_keys, ctx->key_lo,
+                           ctx->key_sh, st);
     prof.mark(3);
-    csa::launch_select(cand_key, cand_idx, cand_cnt, sel, sel_count, hist, BH, c.budget_k, ctx->R, ctx->P,
-                       l.cand_keys, ctx->key_lo, ctx->key_sh, st);
+    csa::launch_threshold(cand_key, cand_cnt, sel, sel_count, thr, seg_par, hist, BH, c.budget_k, ctx->R,
+                          ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, st);
     prof.mark(4);
+    csa::launch_emit(cand_key, cand_bits, cand_cnt, thr, seg_par, sel, BH, c.budget_k, ctx->R, ctx->P,
+                     l.cand_keys, st);
+    prof.mark(5);
     csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, part,
                                 c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ctx->n_pre, ctx->n,
                                 c.max_ctx, S, st);
-    prof.mark(5);
-    csa::launch_attention_merge(part, out_dev, BH, S, st);
     prof.mark(6);
+    csa::launch_attention_merge(part, out_dev, BH, S, st);
+    prof.mark(7);
     return check_launch(ctx);
 }
 

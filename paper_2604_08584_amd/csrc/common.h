@@ -12,15 +12,20 @@ constexpr int kHeadDim = 128;
 constexpr int kCntBits = 6;
 constexpr int32_t kKeyBias = 1 << 24;  // accumulated |sum q| < 2^24  ->  key in (0, 2^25)
 
-struct __align__(8) Entry {
-    int32_t idx;  // key index, -1 = unused slot
-    int32_t qe;   // q * 64 + 1
-};
+// A table entry in device memory is one 32-bit word: the grid integer q (signed, kQBits bits) above
+// the low kUnitBits bits of the key index.  Rows are sorted by key index, and the per-row offsets
+// of every block of kUnit (or fewer) key indices tell which block an entry belongs to, so the high
+// bits of the index need not be stored.
+constexpr int kUnitBits = 12;
+constexpr int kUnit = 1 << kUnitBits;
+constexpr int kQBits = 32 - kUnitBits;
+constexpr int32_t kQLimit = (1 << (kQBits - 1)) - 1;  // |q| <= kQLimit
 
-struct __align__(8) Cand {
-    int32_t idx;
-    uint32_t key;  // (sum of q) + kKeyBias
-};
+__device__ __forceinline__ uint32_t pack_entry(int32_t idx, int32_t q)
+{
+    return ((uint32_t)q << kUnitBits) | ((uint32_t)idx & (uint32_t)(kUnit - 1));
+}
+__device__ __forceinline__ int32_t entry_q(uint32_t e) { return (int32_t)e >> kUnitBits; }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
@@ -71,6 +76,43 @@ __device__ __forceinline__ int block_excl_scan(int v, int *s_tmp, int &total)
     __syncthreads();
     total = tot;
     return off + incl - v;
+}
+
+// The same for four 16-bit counters packed in a 64-bit word (every running total must stay
+// below 65536): one scan, four prefix sums.
+template <int NT>
+__device__ __forceinline__ unsigned long long block_excl_scan_4x16(unsigned long long v,
+                                                                    unsigned long long *s_tmp,
+                                                                    unsigned long long &total)
+{
+    constexpr int NW = NT / kWave;
+    const int w = threadIdx.x / kWave;
+    unsigned long long incl = v;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const unsigned long long t = __shfl_up(incl, o, kWave);
+        if (lane_id() >= o) incl += t;
+    }
+    if (lane_id() == kWave - 1) s_tmp[w] = incl;
+    __syncthreads();
+    unsigned long long off = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const unsigned long long t = s_tmp[i];
+        if (i < w) off += t;
+        tot += t;
+    }
+    __syncthreads();
+    total = tot;
+    return off + incl - v;
+}
+
+// sum over the wave, result in every lane
+__device__ __forceinline__ int wave_sum(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
 }
 
 // Wave-aggregated histogram increment: lanes that hit the same bin as the first pending lane

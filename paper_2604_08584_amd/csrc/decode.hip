@@ -76,8 +76,9 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
 // values >= that bound are candidates; they are ranked against each other by (z desc, j asc) and
 // ranks < m are written in rank order.  If there are too many candidates (many equal values) a
 // radix threshold search with an ordered tie pick does the job instead.
-// Also clears the head's coarse score histogram and looks up, for every key range p, the slice
-// [lo, hi) of each probed row, so that the accumulation kernel starts with one coalesced read.
+// Also clears the head's coarse score histogram and looks up, for every key range p, the
+// nsub + 1 offsets that cut the slice of each probed row into its blocks, so that the
+// accumulation kernel starts with one coalesced read.
 // grid B*Hq, block 256.
 // ---------------------------------------------------------------------------------------------
 constexpr int kTopNT = 256;
@@ -88,9 +89,9 @@ constexpr int kTopCand = 1024;  // candidate capacity of the fast path
 __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restrict__ z,
                                                           int32_t *__restrict__ rows,
                                                           const int32_t *__restrict__ part_off,
-                                                          int2 *__restrict__ spans,
+                                                          int32_t *__restrict__ spans,
                                                           uint32_t *__restrict__ hist_g, int C,
-                                                          int m, int G, int P)
+                                                          int m, int G, int P, int nsub, int PO)
 {
     __shared__ int32_t s_rows[64];
     __shared__ __align__(16) uint32_t s_hist[256 + kTopNT / kWave + 4];
@@ -206,141 +207,159 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
     });
     }
 publish:
-    // the probed rows, and for every key range p the slice [lo, hi) of each probed row
+    // the probed rows, and for every key range p the nsub + 1 block offsets of each probed row
     __syncthreads();
     if (threadIdx.x < m) out[threadIdx.x] = s_rows[threadIdx.x];
     const int bg = blockIdx.x / G;
-    int2 *sp = spans + (size_t)blockIdx.x * P * m;
-    for (int t = threadIdx.x; t < P * m; t += kTopNT) {
-        const int p = t / m, r = t - p * m;
-        const int32_t *po = part_off + ((size_t)bg * C + s_rows[r]) * (P + 1);
-        sp[t] = make_int2(po[p], po[p + 1]);
+    const int nb = nsub + 1;
+    int32_t *sp = spans + (size_t)blockIdx.x * P * m * nb;
+    for (int t = threadIdx.x; t < P * m * nb; t += kTopNT) {
+        const int s = t % nb, pr = t / nb;
+        const int p = pr / m, r = pr - p * m;
+        sp[t] = part_off[((size_t)bg * C + s_rows[r]) * PO + p * nsub + s];
     }
 }
 
-void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, void *spans,
-                          uint32_t *hist_g, int n_heads, int C, int m, int G, int P, hipStream_t st)
+void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, int32_t *spans,
+                          uint32_t *hist_g, int n_heads, int C, int m, int G, int P, int nsub, int PO,
+                          hipStream_t st)
 {
-    k_top_centroids<<<n_heads, kTopNT, 0, st>>>(z, rows, part_off, (int2 *)spans, hist_g, C, m, G, P);
+    k_top_centroids<<<n_heads, kTopNT, 0, st>>>(z, rows, part_off, spans, hist_g, C, m, G, P, nsub, PO);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Steps 2+3: gather the m probed rows and sum scores per key (Sec. 3.3 (2)-(3), w_b = 1).
-// Rows are stored sorted by key index with per-row offsets of every key range of R keys, so
+// Rows are stored sorted by key index with per-row offsets of every block of key indices, so
 // workgroup (head, p) reads only the slices of its range [p*R, (p+1)*R) - every table byte is
 // read once - and keeps R direct-addressed integer accumulators in LDS.  Each entry adds
 // q*64 + 1: exact integer sums, order-free, and "seen" == accumulator != 0 (U of Sec. 3.3 (3):
 // a key absent from every probed row is not a candidate even if all sums are negative).
-// The kernel is bound by instruction issue as much as by HBM, so the per-entry and per-slot
-// paths are kept minimal: a wave owns whole rows (row constants are scalar), keeps eight
-// 512-byte loads in flight (two rows at a time), and the sparse accumulator array is first compacted
-// into LDS; only the dense survivors are turned into (sum + 2^24, index), counted into the
-// head's coarse histogram and written out, in segment p of the head's candidate arrays.
+// A wave owns whole rows (row constants are scalar) and keeps the slices of four rows in
+// flight, 32 bytes (8 packed entries) per lane.  What leaves the workgroup is the range's
+// presence bitmap (one bit per key index) and the keys sum + 2^24 of the present indices in
+// ascending index order - the index of a candidate is implied by its rank in the bitmap - plus
+// the head's coarse histogram of those keys.
 // grid (P, B*Hq), block NT = R/16, dynamic LDS R*4 bytes.
 // ---------------------------------------------------------------------------------------------
-constexpr int kAccUnroll = 4;
+constexpr int kAccRows = 4;  // rows in flight per wave
 
 template <int NT>
-__global__ __launch_bounds__(NT) void k_accumulate(const Entry *__restrict__ ent,
+__global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ ent,
                                                    const int32_t *__restrict__ rows,
-                                                   const int2 *__restrict__ spans,
+                                                   const int32_t *__restrict__ spans,
                                                    uint32_t *__restrict__ cand_key,
-                                                   int32_t *__restrict__ cand_idx,
+                                                   uint32_t *__restrict__ cand_bits,
                                                    int32_t *__restrict__ seg_cnt,
-                                                   uint32_t *__restrict__ hist_g, int C, int L,
+                                                   uint32_t *__restrict__ hist_g, int C, int Ls,
                                                    int m, int G, int P, size_t cand_stride,
                                                    uint32_t key_lo, int key_sh)
 {
     constexpr int NW = NT / kWave;
     constexpr int R = NT * 16;
+    constexpr int NSUB = R > kUnit ? R / kUnit : 1;  // blocks of a range (1, 2 or 4)
+    constexpr int NB = NSUB + 1;
     extern __shared__ __align__(16) int32_t s_acc[];  // [R]
-    __shared__ int32_t s_lo[64], s_hi[64], s_row[64];
+    __shared__ int32_t s_b[64 * NB], s_row[64];
     __shared__ uint32_t s_h[kCoarseBins];
-    __shared__ int s_scan[NW + 1];
+    __shared__ unsigned long long s_scan[NW + 1];
     const int p = blockIdx.x, head = blockIdx.y;
     const int bg = head / G;
     const int wave = threadIdx.x / kWave, lane = lane_id();
-    if (threadIdx.x < m) {
-        const int2 sp = spans[((size_t)head * P + p) * m + threadIdx.x];
-        s_row[threadIdx.x] = rows[(size_t)head * m + threadIdx.x];
-        s_lo[threadIdx.x] = sp.x;
-        s_hi[threadIdx.x] = sp.y;
-    }
     {
+        const int32_t *sp = spans + ((size_t)head * P + p) * m * NB;
+        for (int e = threadIdx.x; e < m * NB; e += NT) s_b[e] = sp[e];
+        if (threadIdx.x < m) s_row[threadIdx.x] = rows[(size_t)head * m + threadIdx.x];
         int4 *z4 = (int4 *)s_acc;
 #pragma unroll
         for (int u = 0; u < 4; ++u) z4[u * NT + threadIdx.x] = make_int4(0, 0, 0, 0);
         for (int e = threadIdx.x; e < kCoarseBins; e += NT) s_h[e] = 0;
     }
     __syncthreads();
-    const int base = p * R;
-    // two rows per wave at a time, kAccUnroll 512-byte loads in flight for each
-    for (int r = wave; r < m; r += 2 * NW) {
-        const int r2 = r + NW < m ? r + NW : r;
-        const int lo_a = __builtin_amdgcn_readfirstlane(s_lo[r]);
-        const int hi_a = __builtin_amdgcn_readfirstlane(s_hi[r]);
-        const int lo_b = __builtin_amdgcn_readfirstlane(s_lo[r2]);
-        const int hi_b = r2 != r ? __builtin_amdgcn_readfirstlane(s_hi[r2]) : lo_b;  // empty if no 2nd row
-        const Entry *rp_a = ent + ((size_t)bg * C + __builtin_amdgcn_readfirstlane(s_row[r])) * L;
-        const Entry *rp_b = ent + ((size_t)bg * C + __builtin_amdgcn_readfirstlane(s_row[r2])) * L;
-        for (int ea = lo_a, eb = lo_b; ea < hi_a || eb < hi_b;
-             ea += kWave * kAccUnroll, eb += kWave * kAccUnroll) {
-            Entry va[kAccUnroll], vb[kAccUnroll];
+    // slot of an entry = (its block within the range) * kUnit + (low index bits) - off0
+    const int off0 = (p * R) & (kUnit - 1);  // non-zero only for ranges smaller than a block
+    for (int r0 = wave; r0 < m; r0 += kAccRows * NW) {
+        int lo[kAccRows], hi[kAccRows], b1[kAccRows], b2[kAccRows], b3[kAccRows];
+        const uint32_t *rp[kAccRows];
+        int longest = 0;
 #pragma unroll
-            for (int u = 0; u < kAccUnroll; ++u) {
-                const int xa = ea + u * kWave + lane, xb = eb + u * kWave + lane;
-                va[u].idx = -1;
-                vb[u].idx = -1;
-                if (xa < hi_a) va[u] = rp_a[xa];
-                if (xb < hi_b) vb[u] = rp_b[xb];
+        for (int j = 0; j < kAccRows; ++j) {
+            const int r = r0 + j * NW;
+            const bool on = r < m;
+            const int rr = on ? r : r0;
+            lo[j] = __builtin_amdgcn_readfirstlane(s_b[rr * NB]);
+            hi[j] = on ? __builtin_amdgcn_readfirstlane(s_b[rr * NB + NSUB]) : lo[j];  // empty if no such row
+            b1[j] = NSUB > 1 ? __builtin_amdgcn_readfirstlane(s_b[rr * NB + 1]) : 0x7FFFFFFF;
+            b2[j] = NSUB > 2 ? __builtin_amdgcn_readfirstlane(s_b[rr * NB + 2]) : 0x7FFFFFFF;
+            b3[j] = NSUB > 2 ? __builtin_amdgcn_readfirstlane(s_b[rr * NB + 3]) : 0x7FFFFFFF;
+            rp[j] = ent + ((size_t)bg * C + __builtin_amdgcn_readfirstlane(s_row[rr])) * Ls;
+            lo[j] = min(lo[j], hi[j]);
+            longest = max(longest, hi[j] - (lo[j] & ~3));
+        }
+        for (int it = 0; it * (kWave * 8) < longest; ++it) {
+            uint4 va[kAccRows], vb[kAccRows];
+#pragma unroll
+            for (int j = 0; j < kAccRows; ++j) {
+                const int x = (lo[j] & ~3) + it * (kWave * 8) + lane * 8;
+                va[j] = x < hi[j] ? *(const uint4 *)(rp[j] + x) : make_uint4(0, 0, 0, 0);
+                vb[j] = x + 4 < hi[j] ? *(const uint4 *)(rp[j] + x + 4) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
-            for (int u = 0; u < kAccUnroll; ++u) {
-                if (va[u].idx >= 0) atomicAdd(&s_acc[va[u].idx - base], va[u].qe);
-                if (vb[u].idx >= 0) atomicAdd(&s_acc[vb[u].idx - base], vb[u].qe);
+            for (int j = 0; j < kAccRows; ++j) {
+                const int x = (lo[j] & ~3) + it * (kWave * 8) + lane * 8;
+                const uint32_t ev[8] = {va[j].x, va[j].y, va[j].z, va[j].w, vb[j].x, vb[j].y, vb[j].z, vb[j].w};
+                const uint32_t len = (uint32_t)(hi[j] - lo[j]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int pos = x + e;
+                    if ((uint32_t)(pos - lo[j]) < len) {
+                        int slot = (int)(ev[e] & (uint32_t)(kUnit - 1)) - off0;
+                        if (NSUB > 1) slot += (pos >= b1[j]) ? kUnit : 0;
+                        if (NSUB > 2) slot += ((pos >= b2[j]) ? kUnit : 0) + ((pos >= b3[j]) ? kUnit : 0);
+                        const int32_t val = entry_q(ev[e]) * (1 << kCntBits) + 1;
+                        if ((unsigned)slot < (unsigned)R) atomicAdd(&s_acc[slot], val);
+                    }
+                }
             }
         }
     }
     __syncthreads();
-    // sparse -> dense: thread t owns the 16 slots 4*(u*NT + t) .. +3, u < 4 (128-bit LDS reads)
+    // thread t owns the slot groups 4*(u*NT + t) .. +3, u < 4 (128-bit LDS reads); walking
+    // (u, t, slot) in this order is walking the key indices in ascending order
     int4 a[4];
-    int mine = 0;
+    uint32_t nib[4];
+    unsigned long long packed = 0;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         a[u] = ((const int4 *)s_acc)[u * NT + threadIdx.x];
-        mine += (a[u].x != 0) + (a[u].y != 0) + (a[u].z != 0) + (a[u].w != 0);
+        nib[u] = (a[u].x != 0 ? 1u : 0u) | (a[u].y != 0 ? 2u : 0u) | (a[u].z != 0 ? 4u : 0u) |
+                 (a[u].w != 0 ? 8u : 0u);
+        packed |= (unsigned long long)__popc(nib[u]) << (16 * u);
     }
-    int total;
-    const int pos = block_excl_scan<NT>(mine, s_scan, total);  // (barriers: all slots are in registers)
+    unsigned long long tot4;
+    const unsigned long long pre4 = block_excl_scan_4x16<NT>(packed, s_scan, tot4);
     uint32_t *dk = cand_key + (size_t)head * cand_stride + (size_t)p * R;
-    int32_t *di = cand_idx + (size_t)head * cand_stride + (size_t)p * R;
-    uint2 *s_stage = (uint2 *)s_acc;  // R/2 (accumulator, local slot) pairs at a time
-    constexpr int half = R / 2;
-    for (int w0 = 0; w0 < total; w0 += half) {
-        if (w0) __syncthreads();  // previous window consumed
-        int q = pos - w0;
+    uint32_t *db = cand_bits + ((size_t)head * cand_stride + (size_t)p * R) / 32;
+    int group_base = 0;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int slot = 4 * (u * NT + threadIdx.x);
-            const int av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
+    for (int u = 0; u < 4; ++u) {
+        int rank = group_base + (int)((pre4 >> (16 * u)) & 0xFFFFu);
+        const int av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
 #pragma unroll
-            for (int x = 0; x < 4; ++x)
-                if (av[x] != 0) {
-                    if ((unsigned)q < (unsigned)half) s_stage[q] = make_uint2((uint32_t)av[x], (uint32_t)(slot + x));
-                    ++q;
-                }
-        }
-        __syncthreads();
-        const int n_here = min(half, total - w0);
-        for (int i = threadIdx.x; i < n_here; i += NT) {
-            const uint2 c = s_stage[i];
-            const uint32_t key = (uint32_t)(((int32_t)c.x >> kCntBits) + kKeyBias);
-            dk[w0 + i] = key;
-            di[w0 + i] = base + (int32_t)c.y;
-            atomicAdd(&s_h[(key - key_lo) >> key_sh], 1u);
-        }
+        for (int x = 0; x < 4; ++x)
+            if (av[x] != 0) {
+                const uint32_t key = (uint32_t)((av[x] >> kCntBits) + kKeyBias);
+                dk[rank++] = key;
+                atomicAdd(&s_h[(key - key_lo) >> key_sh], 1u);
+            }
+        // eight neighbouring lanes hold the 32 bits of one bitmap word
+        uint32_t w = nib[u] << (4 * (lane & 7));
+        w |= __shfl_xor(w, 1, kWave);
+        w |= __shfl_xor(w, 2, kWave);
+        w |= __shfl_xor(w, 4, kWave);
+        if ((lane & 7) == 0) db[(u * NT + (int)threadIdx.x) >> 3] = w;
+        group_base += (int)((tot4 >> (16 * u)) & 0xFFFFu);
     }
-    if (threadIdx.x == 0) seg_cnt[(size_t)head * P + p] = total;
+    if (threadIdx.x == 0) seg_cnt[(size_t)head * P + p] = group_base;
     // histogram complete once every wave's LDS atomics have landed: wait for LDS traffic only
     // (a full __syncthreads would also wait for the candidate stores above)
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), vmcnt / expcnt untouched
@@ -351,9 +370,9 @@ __global__ __launch_bounds__(NT) void k_accumulate(const Entry *__restrict__ ent
     }
 }
 
-void launch_accumulate(const void *ent, const int32_t *rows, const void *spans, uint32_t *cand_key,
-                       int32_t *cand_idx, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
-                       int L, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
+void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *spans, uint32_t *cand_key,
+                       uint32_t *cand_bits, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
+                       int Ls, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
                        int key_sh, hipStream_t st)
 {
     dim3 grid(P, n_heads);
@@ -363,10 +382,10 @@ void launch_accumulate(const void *ent, const int32_t *rows, const void *spans, 
                                   16384 * 4);
         attr = true;
     }
-#define CSA_ACC(NT_)                                                                             \
-    k_accumulate<NT_><<<grid, NT_, (size_t)R * 4, st>>>((const Entry *)ent, rows, (const int2 *)spans, \
-                                                        cand_key, cand_idx, seg_cnt, hist_g, C, L, m, \
-                                                        G, P, cand_stride, key_lo, key_sh)
+#define CSA_ACC(NT_)                                                                              \
+    k_accumulate<NT_><<<grid, NT_, (size_t)R * 4, st>>>((const uint32_t *)ent, rows, spans, cand_key, \
+                                                        cand_bits, seg_cnt, hist_g, C, Ls, m, G, P,  \
+                                                        cand_stride, key_lo, key_sh)
     switch (R) {
     case 1024: CSA_ACC(64); break;
     case 2048: CSA_ACC(128); break;
@@ -378,111 +397,100 @@ void launch_accumulate(const void *ent, const int32_t *rows, const void *spans, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 4: Top-K over the candidates of one head (Sec. 3.3 (4)): the min(k, |U|) largest sums,
-// ties to the lower key index, written in ascending index order and padded with -1.
-// Threshold search by range refinement: the live key range [lo, hi] is cut into <= 512 equal
-// bins and a histogram of the candidate keys over them is taken (the first one arrives
-// ready-made from the accumulation kernel, a further one costs a streaming pass and is rarely
-// needed); the bin holding the k-th largest becomes the new range; once it holds few enough
-// keys they are gathered into LDS (with their indices) and finished there with a radix search.
-// Winners are marked in two LDS bitmaps over the key indices ("above threshold", "equal to
-// threshold"), the lowest-index ties still needed are kept, and the set bits are emitted in
-// ascending order.  When all key indices fit one bitmap chunk (n <= 131072) the gather pass
-// marks the sure winners on the fly, so the candidates are streamed exactly once.
+// Step 4, first half: the Top-K threshold of one head (Sec. 3.3 (4)): the key T such that the
+// min(k, |U|) winners are every candidate with key > T plus the `need` lowest-index candidates
+// with key == T.  Range refinement: the live key range [lo, hi] is cut into <= 512 equal bins
+// and a histogram of the candidate keys over them is taken (the first one arrives ready-made
+// from the accumulation kernel; a further one costs a streaming pass and is rarely needed); the
+// bin holding the k-th largest becomes the new range; once it holds few enough keys they are
+// gathered into LDS (tagged with their key range) and finished there with a radix search.  The
+// same streaming pass counts, per key range p, the candidates above the bin, so that the
+// kernel can hand every range its output offset and its share of the threshold ties:
+//   seg_par[head][p] = (first output slot of range p, ties range p may keep), thr[head] = T.
+// Nothing selected (k = 0 or no candidate): T = 0xFFFFFFFF.  Everything selected: T = 0.
 // grid B*Hq, block 1024.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSelNT = 1024;
-constexpr int kSelCap = 4096;                       // contenders finished in LDS
-constexpr int kSelMaxP = 2048;                      // key ranges (segments) per head
-constexpr int kChunk = 131072;                      // key indices per bitmap chunk
-constexpr int kChunkWords = kChunk / 32;            // 4096 words
-constexpr int kWordsPerThread = kChunkWords / kSelNT;  // 4 consecutive words per thread
+constexpr int kThrNT = 1024;
+constexpr int kSelCap = 4096;   // contenders finished in LDS
+constexpr int kSelMaxP = 2048;  // key ranges (segments) per head
+constexpr int kSegBits = 11;    // a contender is (key - lo) << kSegBits | p
+static_assert((1 << kSegBits) >= kSelMaxP, "segment tag too narrow");
 
-__global__ __launch_bounds__(kSelNT) void k_select(const uint32_t *__restrict__ cand_key,
-                                                   const int32_t *__restrict__ cand_idx,
-                                                   const int32_t *__restrict__ seg_cnt,
-                                                   int32_t *__restrict__ sel,
-                                                   int32_t *__restrict__ sel_count,
-                                                   const uint32_t *__restrict__ hist_g, int k, int R,
-                                                   int P, size_t cand_stride, uint32_t key_lo,
-                                                   int key_sh)
+__global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict__ cand_key,
+                                                      const int32_t *__restrict__ seg_cnt,
+                                                      int32_t *__restrict__ sel,
+                                                      int32_t *__restrict__ sel_count,
+                                                      uint32_t *__restrict__ thr,
+                                                      int2 *__restrict__ seg_par,
+                                                      const uint32_t *__restrict__ hist_g, int k,
+                                                      int R, int P, size_t cand_stride,
+                                                      uint32_t key_lo, int key_sh)
 {
-    constexpr int NW = kSelNT / kWave;
-    __shared__ uint32_t s_hist[512 + kSelNT / kWave + 2];
-    __shared__ int s_scan[kSelNT / kWave + 1];
-    __shared__ __align__(16) uint32_t s_gt[kChunkWords], s_eq[kChunkWords];
-    __shared__ uint2 s_ck[kSelCap];  // contenders: (key - lo, key index)
-    __shared__ int32_t s_cnt[kSelMaxP];
+    constexpr int NW = kThrNT / kWave;
+    __shared__ uint32_t s_hist[512 + kThrNT / kWave + 2];
+    __shared__ int s_scan[kThrNT / kWave + 1];
+    __shared__ uint32_t s_ck[kSelCap];
+    __shared__ int32_t s_cnt[kSelMaxP], s_gt[kSelMaxP], s_eq[kSelMaxP];
     __shared__ int s_n;
     const int head = blockIdx.x;
     const uint32_t *hk = cand_key + (size_t)head * cand_stride;
-    const int32_t *hi_ = cand_idx + (size_t)head * cand_stride;
     int32_t *out = sel + (size_t)head * k;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     // segment counts; |U| = their sum
     int part = 0;
-    for (int p = threadIdx.x; p < P; p += kSelNT) {
-        const int c = seg_cnt[(size_t)head * P + p];
+    for (int p = threadIdx.x; p < kSelMaxP; p += kThrNT) {
+        const int c = p < P ? min(seg_cnt[(size_t)head * P + p], R) : 0;
         s_cnt[p] = c;
+        s_gt[p] = 0;
+        s_eq[p] = 0;
         part += c;
     }
     if (threadIdx.x == 0) s_n = 0;
-#pragma unroll
-    for (int u = 0; u < kWordsPerThread; ++u) {
-        s_gt[u * kSelNT + threadIdx.x] = 0;
-        s_eq[u * kSelNT + threadIdx.x] = 0;
-    }
     int n_total;
-    block_excl_scan<kSelNT>(part, s_scan, n_total);  // (its barriers also publish the LDS writes)
+    block_excl_scan<kThrNT>(part, s_scan, n_total);  // (its barriers also publish the LDS writes)
     const int k_eff = n_total < k ? n_total : k;
     if (threadIdx.x == 0) sel_count[head] = k_eff;
-    for (int a = k_eff + threadIdx.x; a < k; a += kSelNT) out[a] = -1;
-    if (k_eff == 0) return;
+    for (int a = k_eff + threadIdx.x; a < k; a += kThrNT) out[a] = -1;
 
-    // stream(fn): fn(key, key_index, valid) over the candidates of every segment.  A wave walks
-    // whole segments, four consecutive slots per lane and load, keys and indices both read with
-    // full-width loads issued up front (a dependent index load per winner would serialise the
-    // walk); fn may use wave-level operations only (trip counts differ between waves).
-    auto stream = [&](auto fn) {
+    // stream(fn, seg_end): fn(key, p) over the candidate keys of every segment p (key = 0 for
+    // padding - a real key is never 0), then seg_end(p).  A wave walks whole segments, four
+    // consecutive keys per lane and load; both callbacks may use wave-level operations only.
+    auto stream = [&](auto fn, auto seg_end) {
         for (int p = wave; p < P; p += NW) {
             const int c = s_cnt[p];
             const int s0 = p * R;
             for (int e0 = 0; e0 < c; e0 += kWave * 16) {
                 uint4 kk[4];
-                int4 ii[4];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
                     const int e = e0 + (x * kWave + lane) * 4;
                     kk[x] = e < c ? *(const uint4 *)(hk + s0 + e) : make_uint4(0, 0, 0, 0);
-                    ii[x] = e < c ? *(const int4 *)(hi_ + s0 + e) : make_int4(0, 0, 0, 0);
+                    if (e + 1 >= c) kk[x].y = 0;
+                    if (e + 2 >= c) kk[x].z = 0;
+                    if (e + 3 >= c) kk[x].w = 0;
                 }
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
-                    const int e = e0 + (x * kWave + lane) * 4;
-                    if (e0 + x * kWave * 4 < c) {  // wave-uniform
-                        fn(kk[x].x, ii[x].x, e + 0 < c);
-                        fn(kk[x].y, ii[x].y, e + 1 < c);
-                        fn(kk[x].z, ii[x].z, e + 2 < c);
-                        fn(kk[x].w, ii[x].w, e + 3 < c);
-                    }
+                    fn(kk[x].x, p);
+                    fn(kk[x].y, p);
+                    fn(kk[x].z, p);
+                    fn(kk[x].w, p);
                 }
             }
+            seg_end(p);
         }
     };
-    auto mark = [&](uint32_t *bitmap, int key_index, int c0) {
-        const int rel = key_index - c0;
-        if ((unsigned)rel < (unsigned)kChunk) atomicOr(&bitmap[rel >> 5], 1u << (rel & 31));
-    };
 
-    const bool single = P * R <= kChunk;  // one bitmap chunk covers every key index
-    bool marked = false;                  // bitmaps of chunk 0 already hold the final marks
-    uint32_t T = 0;  // keys are > 0, so T = 0 selects everything when k >= |U|
+    uint32_t T = 0xFFFFFFFFu;
     int need = 0;
-    if (n_total > k) {
+    if (k_eff > 0 && n_total <= k) {
+        T = 0;  // every candidate wins
+        for (int p = threadIdx.x; p < P; p += kThrNT) s_gt[p] = s_cnt[p];
+    } else if (k_eff > 0) {
         // first round: the head's coarse histogram, filled by the accumulation kernel
         uint32_t lo = key_lo, hi = key_lo + ((uint32_t)kCoarseBins << key_sh) - 1u;
         int sh = key_sh;
-        for (int i = threadIdx.x; i < kCoarseBins; i += kSelNT)
+        for (int i = threadIdx.x; i < kCoarseBins; i += kThrNT)
             s_hist[i] = hist_g[(size_t)head * kCoarseBins + i];
         __syncthreads();
         int want = k;
@@ -490,132 +498,189 @@ __global__ __launch_bounds__(kSelNT) void k_select(const uint32_t *__restrict__ 
             if (!have_hist) {
                 sh = 0;
                 while (((hi - lo) >> sh) >= 512u) ++sh;
-                for (int i = threadIdx.x; i < 512; i += kSelNT) s_hist[i] = 0;
+                for (int i = threadIdx.x; i < 512; i += kThrNT) s_hist[i] = 0;
                 __syncthreads();
-                stream([&](uint32_t key, int, bool valid) {
-                    const bool in = valid && key >= lo && key <= hi;
-                    hist_add(s_hist, in ? (key - lo) >> sh : 0u, in);
-                });
+                stream([&](uint32_t key, int) {
+                           const bool in = key >= lo && key <= hi;
+                           hist_add(s_hist, in ? (key - lo) >> sh : 0u, in);
+                       },
+                       [&](int) {});
                 __syncthreads();
             }
             int above;
-            const int bin = block_pick_bin<kSelNT, 512>(s_hist, want, s_hist + 512, above);
+            const int bin = block_pick_bin<kThrNT, 512>(s_hist, want, s_hist + 512, above);
             const int in_bin = (int)s_hist[bin];
             want -= above;
             lo += (uint32_t)bin << sh;
             hi = min(hi, lo + ((1u << sh) - 1u));
-            if (sh == 0) {  // the bin is a single key value
+            if (sh == 0) {
+                // the bin is a single key value: count, per range, the keys above and equal to it
                 T = lo;
                 need = want;
+                int n_gt = 0, n_eq = 0;
+                stream([&](uint32_t key, int) {
+                           n_gt += key > T ? 1 : 0;
+                           n_eq += key == T ? 1 : 0;
+                       },
+                       [&](int p) {
+                           n_gt = wave_sum(n_gt);
+                           n_eq = wave_sum(n_eq);
+                           if (lane == 0) {
+                               s_gt[p] = n_gt;
+                               s_eq[p] = n_eq;
+                           }
+                           n_gt = 0;
+                           n_eq = 0;
+                       });
                 break;
             }
             if (in_bin <= kSelCap) {
-                // gather the contenders (key - lo < 2^sh <= 2^16) with their key indices; with a
-                // single bitmap chunk, keys above the bin are sure winners and are marked now
+                // gather the contenders (key - lo < 2^sh <= 2^16), tagged with their range; count per
+                // range the keys above the bin (sure winners)
                 __syncthreads();
-                stream([&](uint32_t key, int key_index, bool valid) {
-                    const bool in = valid && key >= lo && key <= hi;
-                    const uint64_t mask = __ballot(in);
-                    if (mask) {
-                        int wbase = 0;
-                        if (mbcnt(mask) == 0 && in) wbase = atomicAdd(&s_n, __popcll(mask));
-                        wbase = __builtin_amdgcn_readlane(wbase, __ffsll((unsigned long long)mask) - 1);
-                        if (in) s_ck[wbase + mbcnt(mask)] = make_uint2(key - lo, (uint32_t)key_index);
-                    }
-                    if (single && valid && key > hi) mark(s_gt, key_index, 0);
-                });
+                int n_gt = 0;
+                stream([&](uint32_t key, int p) {
+                           n_gt += key > hi ? 1 : 0;
+                           const bool in = key >= lo && key <= hi;
+                           const uint64_t mask = __ballot(in);
+                           if (mask) {
+                               int wbase = 0;
+                               if (in && mbcnt(mask) == 0) wbase = atomicAdd(&s_n, __popcll(mask));
+                               wbase = __builtin_amdgcn_readlane(wbase, __ffsll((unsigned long long)mask) - 1);
+                               const int o = wbase + mbcnt(mask);
+                               if (in && o < kSelCap) s_ck[o] = ((key - lo) << kSegBits) | (uint32_t)p;
+                           }
+                       },
+                       [&](int p) {
+                           n_gt = wave_sum(n_gt);
+                           if (lane == 0) s_gt[p] = n_gt;
+                           n_gt = 0;
+                       });
                 __syncthreads();
-                const int nc = s_n;
-                const uint32_t Tl = block_radix_threshold<kSelNT, 8, 2>(
+                const int nc = min(s_n, kSelCap);
+                const uint32_t Tl = block_radix_threshold<kThrNT, 8, 2>(
                     [&](auto fn) {
-                        for (int a0 = 0; a0 < nc; a0 += kSelNT) {
+                        for (int a0 = 0; a0 < nc; a0 += kThrNT) {
                             const int a = a0 + threadIdx.x;
-                            fn(a < nc ? s_ck[a].x : 0u, a < nc);
+                            fn(a < nc ? s_ck[a] >> kSegBits : 0u, a < nc);
                         }
                     },
                     want, s_hist, need);
                 T = lo + Tl;
-                if (single) {
-                    for (int a = threadIdx.x; a < nc; a += kSelNT) {
-                        const uint2 c = s_ck[a];
-                        if (c.x > Tl)
-                            mark(s_gt, (int)c.y, 0);
-                        else if (c.x == Tl)
-                            mark(s_eq, (int)c.y, 0);
-                    }
-                    marked = true;
+                for (int a = threadIdx.x; a < nc; a += kThrNT) {
+                    const uint32_t c = s_ck[a];
+                    const uint32_t kk = c >> kSegBits;
+                    const int p = (int)(c & ((1u << kSegBits) - 1u));
+                    if (kk > Tl)
+                        atomicAdd(&s_gt[p], 1);
+                    else if (kk == Tl)
+                        atomicAdd(&s_eq[p], 1);
                 }
                 break;
             }
             __syncthreads();  // s_hist[bin] was read above; the next round clears the histogram
         }
     }
+    __syncthreads();
+    // per range: its share of the ties (lowest ranges first) and its first output slot
+    static_assert(kSelMaxP == 2 * kThrNT, "two ranges per thread");
+    const int p0 = 2 * (int)threadIdx.x, p1 = p0 + 1;
+    const int e0 = s_eq[p0], e1 = s_eq[p1];
+    int dummy;
+    const int ties_before = block_excl_scan<kThrNT>(e0 + e1, s_scan, dummy);
+    const int al0 = max(0, min(e0, need - ties_before));
+    const int al1 = max(0, min(e1, need - ties_before - e0));
+    const int take0 = s_gt[p0] + al0, take1 = s_gt[p1] + al1;
+    const int off = block_excl_scan<kThrNT>(take0 + take1, s_scan, dummy);
+    if (p0 < P) seg_par[(size_t)head * P + p0] = make_int2(off, al0);
+    if (p1 < P) seg_par[(size_t)head * P + p1] = make_int2(off + take0, al1);
+    if (threadIdx.x == 0) thr[head] = T;
+}
 
-    // ordered emission, kChunk key indices at a time
-    int n_out = 0;
-    for (int c0 = 0; c0 < P * R; c0 += kChunk) {
-        if (!marked) {
-            if (c0) {
-#pragma unroll
-                for (int u = 0; u < kWordsPerThread; ++u) {
-                    s_gt[u * kSelNT + threadIdx.x] = 0;
-                    s_eq[u * kSelNT + threadIdx.x] = 0;
-                }
-            }
-            __syncthreads();
-            stream([&](uint32_t key, int key_index, bool valid) {
-                if (valid && key >= T) mark(key > T ? s_gt : s_eq, key_index, c0);
-            });
-        }
-        marked = false;
-        __syncthreads();
-        // keep the lowest-index `need` ties; thread t owns words [4t, 4t+4)
-        uint32_t eq[kWordsPerThread], bits[kWordsPerThread];
-        int n_eq = 0;
-        {
-            const uint4 e4 = ((const uint4 *)s_eq)[threadIdx.x];
-            eq[0] = e4.x; eq[1] = e4.y; eq[2] = e4.z; eq[3] = e4.w;
-            n_eq = __popc(e4.x) + __popc(e4.y) + __popc(e4.z) + __popc(e4.w);
-        }
-        int tie_total;
-        int allow = need - block_excl_scan<kSelNT>(n_eq, s_scan, tie_total);
-        int n_bits = 0;
-        const uint4 g4 = ((const uint4 *)s_gt)[threadIdx.x];
-        const uint32_t gt[kWordsPerThread] = {g4.x, g4.y, g4.z, g4.w};
-#pragma unroll
-        for (int u = 0; u < kWordsPerThread; ++u) {
-            uint32_t e = eq[u];
-            if (allow <= 0)
-                e = 0;
-            else
-                while (__popc(e) > allow) e &= ~(0x80000000u >> __clz(e));  // drop the highest bit
-            allow -= __popc(e);
-            bits[u] = gt[u] | e;
-            n_bits += __popc(bits[u]);
-        }
-        need = max(0, need - tie_total);
-        int take_total;
-        int pos = block_excl_scan<kSelNT>(n_bits, s_scan, take_total) + n_out;
-#pragma unroll
-        for (int u = 0; u < kWordsPerThread; ++u) {
-            uint32_t b = bits[u];
-            const int kbase = c0 + (threadIdx.x * kWordsPerThread + u) * 32;
-            while (b) {
-                out[pos++] = kbase + __ffs(b) - 1;
-                b &= b - 1;
-            }
-        }
-        n_out += take_total;
-        __syncthreads();
+void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t *sel, int32_t *sel_count,
+                      uint32_t *thr, void *seg_par, const uint32_t *hist_g, int n_heads, int k, int R,
+                      int P, size_t cand_stride, uint32_t key_lo, int key_sh, hipStream_t st)
+{
+    k_threshold<<<n_heads, kThrNT, 0, st>>>(cand_key, seg_cnt, sel, sel_count, thr, (int2 *)seg_par, hist_g,
+                                            k, R, P, cand_stride, key_lo, key_sh);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Step 4, second half: range p of a head writes its winners - candidates with key > T plus its
+// allowed number of lowest-index candidates with key == T - as ascending key indices, starting
+// at its output slot.  The candidates' keys are staged in LDS; thread t owns bitmap word t (32
+// key indices) and finds its keys by the rank of its bits.
+// grid (P, B*Hq), block NT = max(64, R/32), dynamic LDS R*4 bytes.
+// ---------------------------------------------------------------------------------------------
+template <int NT>
+__global__ __launch_bounds__(NT) void k_emit(const uint32_t *__restrict__ cand_key,
+                                             const uint32_t *__restrict__ cand_bits,
+                                             const int32_t *__restrict__ seg_cnt,
+                                             const uint32_t *__restrict__ thr,
+                                             const int2 *__restrict__ seg_par,
+                                             int32_t *__restrict__ sel, int k, int R, int P,
+                                             size_t cand_stride)
+{
+    extern __shared__ __align__(16) uint32_t s_key[];  // [R]
+    __shared__ int s_scan[NT / kWave + 1];
+    const int p = blockIdx.x, head = blockIdx.y;
+    const int c = min(seg_cnt[(size_t)head * P + p], R);
+    const uint32_t T = thr[head];
+    if (c <= 0 || T == 0xFFFFFFFFu) return;  // (uniform over the workgroup)
+    const int2 par = seg_par[(size_t)head * P + p];
+    const size_t seg0 = (size_t)head * cand_stride + (size_t)p * R;
+    for (int i = threadIdx.x * 4; i < c; i += NT * 4)  // the segment has R slots, R % 4 == 0
+        *(uint4 *)(s_key + i) = *(const uint4 *)(cand_key + seg0 + i);
+    const int W = R / 32;
+    const uint32_t word = (int)threadIdx.x < W ? cand_bits[seg0 / 32 + threadIdx.x] : 0u;
+    int total;
+    int rank = block_excl_scan<NT>(__popc(word), s_scan, total);  // (its barriers publish s_key)
+    uint32_t gt = 0, eq = 0;
+    for (uint32_t b = word; b; b &= b - 1) {
+        const uint32_t bit = b & (0u - b);
+        const uint32_t key = rank < c ? s_key[rank] : 0u;
+        ++rank;
+        if (key > T) gt |= bit;
+        else if (key == T) eq |= bit;
+    }
+    // keep the lowest-index ties this range is allowed
+    int allow = par.y - block_excl_scan<NT>(__popc(eq), s_scan, total);
+    if (allow <= 0)
+        eq = 0;
+    else
+        while (__popc(eq) > allow) eq &= ~(0x80000000u >> __clz(eq));  // drop the highest bit
+    uint32_t bits = gt | eq;
+    int pos = par.x + block_excl_scan<NT>(__popc(bits), s_scan, total);
+    int32_t *out = sel + (size_t)head * k;
+    const int kbase = p * R + (int)threadIdx.x * 32;
+    for (; bits; bits &= bits - 1) {
+        if (pos < k) out[pos] = kbase + __ffs(bits) - 1;
+        ++pos;
     }
 }
 
-void launch_select(const uint32_t *cand_key, const int32_t *cand_idx, const int32_t *seg_cnt,
-                   int32_t *sel, int32_t *sel_count, const uint32_t *hist_g, int n_heads, int k, int R,
-                   int P, size_t cand_stride, uint32_t key_lo, int key_sh, hipStream_t st)
+void launch_emit(const uint32_t *cand_key, const uint32_t *cand_bits, const int32_t *seg_cnt,
+                 const uint32_t *thr, const void *seg_par, int32_t *sel, int n_heads, int k, int R, int P,
+                 size_t cand_stride, hipStream_t st)
 {
-    k_select<<<n_heads, kSelNT, 0, st>>>(cand_key, cand_idx, seg_cnt, sel, sel_count, hist_g, k, R, P,
-                                         cand_stride, key_lo, key_sh);
+    if (k <= 0) return;
+    dim3 grid(P, n_heads);
+    static bool attr = false;
+    if (!attr) {
+        (void)hipFuncSetAttribute((const void *)k_emit<512>, hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4);
+        attr = true;
+    }
+#define CSA_EMIT(NT_)                                                                              \
+    k_emit<NT_><<<grid, NT_, (size_t)R * 4, st>>>(cand_key, cand_bits, seg_cnt, thr, (const int2 *)seg_par, \
+                                                  sel, k, R, P, cand_stride)
+    switch (R) {
+    case 1024: CSA_EMIT(64); break;
+    case 2048: CSA_EMIT(64); break;
+    case 4096: CSA_EMIT(128); break;
+    case 8192: CSA_EMIT(256); break;
+    default: CSA_EMIT(512); break;  // 16384
+    }
+#undef CSA_EMIT
 }
 
 }  // namespace csa

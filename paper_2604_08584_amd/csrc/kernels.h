@@ -7,31 +7,35 @@ namespace csa {
 
 // ---- tables.hip
 void launch_pack_centroids(const void *cent, void *cent_t, int n_bg, int C, hipStream_t st);
-void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32_t *flags,
-                        int64_t n_rows, int L, int n_pre, int F, int qmax, hipStream_t st);
-void launch_export_rows(const void *ent, int32_t *idx, float *score, int n_rows, int L, int F,
-                        hipStream_t st);
-void launch_part_offsets(const void *ent, int32_t *part_off, int64_t n_rows, int L, int R, int P,
-                         int PO, hipStream_t st);
+void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32_t *part_off,
+                        int32_t *flags, int64_t n_rows, int L, int Ls, int n_pre, int F, int qmax,
+                        int Q, int PO, hipStream_t st);
+void launch_export_rows(const void *ent, const int32_t *part_off, int32_t *idx, float *score,
+                        int n_rows, int L, int Ls, int F, int Q, int PO, hipStream_t st);
 void launch_build_scores(const void *kc, const int32_t *block_table, const void *cent, int32_t *qs,
                          int32_t *flags, int b, int g, int Hkv, int max_ctx, int n_pre, int C,
                          int j0, int jc, int F, int qmax, hipStream_t st);
-void launch_build_select(const int32_t *qs, void *ent, int jc, int n_pre, int L, hipStream_t st);
+void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc, int n_pre, int L,
+                         int Ls, int Q, int PO, hipStream_t st);
 void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
                          int max_ctx, int n_pre, hipStream_t st);
 
 // ---- decode.hip
 void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
                             int C, hipStream_t st);
-void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, void *spans,
-                          uint32_t *hist_g, int n_heads, int C, int m, int G, int P, hipStream_t st);
-void launch_accumulate(const void *ent, const int32_t *rows, const void *spans, uint32_t *cand_key,
-                       int32_t *cand_idx, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
-                       int L, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
+void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, int32_t *spans,
+                          uint32_t *hist_g, int n_heads, int C, int m, int G, int P, int nsub, int PO,
+                          hipStream_t st);
+void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *spans, uint32_t *cand_key,
+                       uint32_t *cand_bits, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
+                       int Ls, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
                        int key_sh, hipStream_t st);
-void launch_select(const uint32_t *cand_key, const int32_t *cand_idx, const int32_t *seg_cnt,
-                   int32_t *sel, int32_t *sel_count, const uint32_t *hist_g, int n_heads, int k, int R,
-                   int P, size_t cand_stride, uint32_t key_lo, int key_sh, hipStream_t st);
+void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t *sel, int32_t *sel_count,
+                      uint32_t *thr, void *seg_par, const uint32_t *hist_g, int n_heads, int k, int R,
+                      int P, size_t cand_stride, uint32_t key_lo, int key_sh, hipStream_t st);
+void launch_emit(const uint32_t *cand_key, const uint32_t *cand_bits, const int32_t *seg_cnt,
+                 const uint32_t *thr, const void *seg_par, int32_t *sel, int n_heads, int k, int R, int P,
+                 size_t cand_stride, hipStream_t st);
 
 // ---- attention.hip
 int attention_splits(int k, int n_appended);

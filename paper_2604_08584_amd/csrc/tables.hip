@@ -42,17 +42,33 @@ __device__ __forceinline__ void bitonic_sort_u64(uint64_t *s, int NP)
     __syncthreads();
 }
 
+// first position in the ascending array a[0, n) whose value is >= bound
+template <class T>
+__device__ __forceinline__ int lower_bound_pos(const T *a, int n, T bound)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid] < bound) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Canonical rows -> device rows.  One workgroup per row: checks every (idx, score), converts
-// score to its grid integer q (exact or flagged), sorts by key index (unused slots last).
+// score to its grid integer q (exact or flagged), sorts by key index, writes packed entries
+// (row stride Ls, unused slots zero) and the row's offsets part_off[u] = number of entries with
+// key index < u * Q, u < PO.
 // flags[0] |= 1: score off the grid or too large; |= 2: index outside [-1, n_pre).
 // flags[1] = max |q| over all entries (atomicMax).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_import_rows(const int32_t *__restrict__ idx,
                                                      const float *__restrict__ score,
-                                                     Entry *__restrict__ ent,
-                                                     int32_t *__restrict__ flags, int L, int NP,
-                                                     int n_pre, float up, int qmax)
+                                                     uint32_t *__restrict__ ent,
+                                                     int32_t *__restrict__ part_off,
+                                                     int32_t *__restrict__ flags, int L, int Ls,
+                                                     int NP, int n_pre, float up, int qmax, int Q,
+                                                     int PO)
 {
     extern __shared__ uint64_t s_keys[];
     const size_t row = blockIdx.x;
@@ -66,9 +82,9 @@ __global__ __launch_bounds__(256) void k_import_rows(const int32_t *__restrict__
             } else if (i >= 0) {
                 const float qf = score[row * L + p] * up;
                 if (!(fabsf(qf) <= (float)qmax) || qf != rintf(qf)) bad |= 1;
-                const int32_t q = (int32_t)qf;
+                const int32_t q = bad ? 0 : (int32_t)qf;
                 qabs = max(qabs, abs(q));
-                key = ((uint64_t)(uint32_t)i << 32) | (uint32_t)(q * 64 + 1);
+                key = ((uint64_t)(uint32_t)i << 32) | (uint32_t)q;
             }
         }
         s_keys[p] = key;
@@ -77,19 +93,19 @@ __global__ __launch_bounds__(256) void k_import_rows(const int32_t *__restrict__
     for (int o = 32; o > 0; o >>= 1) qabs = max(qabs, __shfl_xor(qabs, o, kWave));
     if (lane_id() == 0 && !bad) atomicMax(flags + 1, qabs);
     bitonic_sort_u64<256>(s_keys, NP);
-    for (int p = threadIdx.x; p < L; p += 256) {
-        const uint64_t key = s_keys[p];
-        Entry e;
-        if (key == ~0ull) { e.idx = -1; e.qe = 0; }
-        else { e.idx = (int32_t)(key >> 32); e.qe = (int32_t)(uint32_t)key; }
-        ent[row * L + p] = e;
+    for (int p = threadIdx.x; p < Ls; p += 256) {
+        const uint64_t key = p < NP ? s_keys[p] : ~0ull;
+        ent[row * Ls + p] = key == ~0ull ? 0u : pack_entry((int32_t)(key >> 32), (int32_t)(uint32_t)key);
     }
+    for (int u = threadIdx.x; u < PO; u += 256)
+        part_off[row * PO + u] = lower_bound_pos<uint64_t>(s_keys, NP, (uint64_t)u * (uint64_t)Q << 32);
 }
 
 static int next_pow2(int x) { int p = 1; while (p < x) p <<= 1; return p; }
 
-void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32_t *flags,
-                        int64_t n_rows, int L, int n_pre, int F, int qmax, hipStream_t st)
+void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32_t *part_off,
+                        int32_t *flags, int64_t n_rows, int L, int Ls, int n_pre, int F, int qmax,
+                        int Q, int PO, hipStream_t st)
 {
     const int NP = next_pow2(L);
     static bool attr = false;
@@ -97,26 +113,35 @@ void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32
         (void)hipFuncSetAttribute((const void *)k_import_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8);
         attr = true;
     }
-    k_import_rows<<<(unsigned)n_rows, 256, (size_t)NP * 8, st>>>(idx, score, (Entry *)ent, flags, L, NP,
-                                                                 n_pre, ldexpf(1.0f, F), qmax);
+    k_import_rows<<<(unsigned)n_rows, 256, (size_t)NP * 8, st>>>(idx, score, (uint32_t *)ent, part_off, flags,
+                                                                 L, Ls, NP, n_pre, ldexpf(1.0f, F), qmax, Q, PO);
 }
 
-// Device rows -> canonical rows: sort by (score desc, idx asc), unused slots last.
-__global__ __launch_bounds__(256) void k_export_rows(const Entry *__restrict__ ent,
+// Device rows -> canonical rows: sort by (score desc, idx asc), unused slots last.  The block of
+// an entry (hence the high bits of its key index) follows from its position and the row offsets.
+__global__ __launch_bounds__(256) void k_export_rows(const uint32_t *__restrict__ ent,
+                                                     const int32_t *__restrict__ part_off,
                                                      int32_t *__restrict__ idx,
-                                                     float *__restrict__ score, int L, int NP,
-                                                     float down)
+                                                     float *__restrict__ score, int L, int Ls, int NP,
+                                                     float down, int Q, int PO)
 {
     extern __shared__ uint64_t s_keys[];
     const size_t row = blockIdx.x;
+    const int32_t *po = part_off + row * PO;
+    const int count = po[PO - 1];
     for (int p = threadIdx.x; p < NP; p += 256) {
         uint64_t key = ~0ull;
-        if (p < L) {
-            const Entry e = ent[row * L + p];
-            if (e.idx >= 0) {
-                const int32_t q = e.qe >> kCntBits;
-                key = ((uint64_t)(~((uint32_t)q ^ 0x80000000u)) << 32) | (uint32_t)e.idx;
+        if (p < count && p < L) {
+            const uint32_t e = ent[row * Ls + p];
+            // block u: the last one whose first entry is at or before p
+            int lo = 0, hi = PO - 1;  // po[lo] <= p < po[hi]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (po[mid] <= p) lo = mid; else hi = mid;
             }
+            const uint32_t i = (((uint32_t)lo * (uint32_t)Q) & ~(uint32_t)(kUnit - 1)) | (e & (uint32_t)(kUnit - 1));
+            const int32_t q = entry_q(e);
+            key = ((uint64_t)(~((uint32_t)q ^ 0x80000000u)) << 32) | i;
         }
         s_keys[p] = key;
     }
@@ -134,8 +159,8 @@ __global__ __launch_bounds__(256) void k_export_rows(const Entry *__restrict__ e
     }
 }
 
-void launch_export_rows(const void *ent, int32_t *idx, float *score, int n_rows, int L, int F,
-                        hipStream_t st)
+void launch_export_rows(const void *ent, const int32_t *part_off, int32_t *idx, float *score,
+                        int n_rows, int L, int Ls, int F, int Q, int PO, hipStream_t st)
 {
     const int NP = next_pow2(L);
     static bool attr = false;
@@ -143,34 +168,8 @@ void launch_export_rows(const void *ent, int32_t *idx, float *score, int n_rows,
         (void)hipFuncSetAttribute((const void *)k_export_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8);
         attr = true;
     }
-    k_export_rows<<<n_rows, 256, (size_t)NP * 8, st>>>((const Entry *)ent, idx, score, L, NP,
-                                                       ldexpf(1.0f, -F));
-}
-
-// part_off[row][p] = number of entries of the row with key index < p*R, p = 0..P
-// (unused slots, idx = -1, sort last and are never counted).  One thread per (row, p).
-__global__ void k_part_offsets(const Entry *__restrict__ ent, int32_t *__restrict__ part_off,
-                               int64_t n_rows, int L, int R, int PO)
-{
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= n_rows * PO) return;
-    const int64_t row = t / PO;
-    const uint32_t bound = (uint32_t)(t % PO) * (uint32_t)R;
-    const Entry *r = ent + row * L;
-    int lo = 0, hi = L;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if ((uint32_t)r[mid].idx < bound) lo = mid + 1; else hi = mid;
-    }
-    part_off[t] = lo;
-}
-
-void launch_part_offsets(const void *ent, int32_t *part_off, int64_t n_rows, int L, int R, int P,
-                         int PO, hipStream_t st)
-{
-    (void)P;
-    const int64_t n = n_rows * PO;
-    k_part_offsets<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((const Entry *)ent, part_off, n_rows, L, R, PO);
+    k_export_rows<<<n_rows, 256, (size_t)NP * 8, st>>>((const uint32_t *)ent, part_off, idx, score, L, Ls, NP,
+                                                       ldexpf(1.0f, -F), Q, PO);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -264,22 +263,28 @@ void launch_build_scores(const void *kc, const int32_t *block_table, const void 
 
 // ---------------------------------------------------------------------------------------------
 // Table build, part 2: Top-L of one row of grid integers (largest first, ties to the lower key
-// index, Sec. 3.2 (2) "keep Top-L pairs"), written directly in the device layout (ascending key
-// index).  Radix threshold search, then each wave walks a contiguous range of keys in order and
-// compacts the winners with ballots; a wave's output offset and its share of the threshold
-// ties follow from per-wave counts.
-// grid = rows of the chunk, block 1024.  ent points at the chunk's first row.
+// index, Sec. 3.2 (2) "keep Top-L pairs"), written directly in the device layout (packed entries
+// in ascending key index, row stride Ls) together with the row's block offsets.  Radix threshold
+// search, then each wave walks a contiguous range of keys in order and compacts the winners with
+// ballots; a wave's output offset and its share of the threshold ties follow from per-wave
+// counts.  The winners' key indices are also kept in LDS so that the offsets
+// part_off[u] = number of entries with key index < u * Q can be looked up afterwards.
+// grid = rows of the chunk, block 1024.  ent / part_off point at the chunk's first row.
 // ---------------------------------------------------------------------------------------------
 constexpr int kBsNT = 1024;
 constexpr int kBsWaves = kBsNT / kWave;
+constexpr int kMaxL = 8192;
 
 __global__ __launch_bounds__(kBsNT) void k_build_select(const int32_t *__restrict__ qs,
-                                                        Entry *__restrict__ ent, int n_pre, int L)
+                                                        uint32_t *__restrict__ ent,
+                                                        int32_t *__restrict__ part_off, int n_pre,
+                                                        int L, int Ls, int Q, int PO)
 {
     __shared__ uint32_t s_hist[256 + kBsWaves + 4];
     __shared__ int s_gt[kBsWaves], s_eq[kBsWaves];
+    __shared__ int32_t s_idx[kMaxL];
     const int32_t *qr = qs + (size_t)blockIdx.x * n_pre;
-    Entry *out = ent + (size_t)blockIdx.x * L;
+    uint32_t *out = ent + (size_t)blockIdx.x * Ls;
     const int want = min(L, n_pre);
     uint32_t T = 0;
     int need = 0;
@@ -322,25 +327,28 @@ __global__ __launch_bounds__(kBsNT) void k_build_select(const int32_t *__restric
         const bool take = gt || (eq && tie_rank + mbcnt(eq_mask) < need);
         const uint64_t take_mask = __ballot(take);
         if (take) {
-            Entry e;
-            e.idx = i;
-            e.qe = q * 64 + 1;
-            out[pos + mbcnt(take_mask)] = e;
+            const int o = pos + mbcnt(take_mask);
+            if (o < want) {  // (always: the counts above add up to `want`)
+                out[o] = pack_entry(i, q);
+                s_idx[o] = i;
+            }
         }
         pos += __popcll(take_mask);
         tie_rank += __popcll(eq_mask);
     }
-    for (int p = want + threadIdx.x; p < L; p += kBsNT) {
-        Entry e;
-        e.idx = -1;
-        e.qe = 0;
-        out[p] = e;
+    for (int p = want + threadIdx.x; p < Ls; p += kBsNT) out[p] = 0u;
+    __syncthreads();
+    int32_t *po = part_off + (size_t)blockIdx.x * PO;
+    for (int u = threadIdx.x; u < PO; u += kBsNT) {
+        const int64_t bound = (int64_t)u * Q;
+        po[u] = bound >= n_pre ? want : lower_bound_pos<int32_t>(s_idx, want, (int32_t)bound);
     }
 }
 
-void launch_build_select(const int32_t *qs, void *ent, int jc, int n_pre, int L, hipStream_t st)
+void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc, int n_pre, int L,
+                         int Ls, int Q, int PO, hipStream_t st)
 {
-    k_build_select<<<jc, kBsNT, 0, st>>>(qs, (Entry *)ent, n_pre, L);
+    k_build_select<<<jc, kBsNT, 0, st>>>(qs, (uint32_t *)ent, part_off, n_pre, L, Ls, Q, PO);
 }
 
 // max over prefill keys of ||k||^2, as the bit pattern of a non-negative fp32 (atomicMax on

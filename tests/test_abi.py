@@ -33,7 +33,7 @@ GOOD = dict(batch=1, n_q_heads=4, n_kv_heads=1, n_centroids=64, list_len=256, n_
 def test_create_validates_configuration():
     ctx = binding.csa_create(**GOOD)
     tb, sb = binding.csa_workspace_bytes(ctx)
-    assert tb >= 64 * 256 * 8 + 64 * 128 * 2 and sb > 0
+    assert tb >= 64 * 256 * 4 + 64 * 128 * 2 and sb > 0     # 4-byte packed entries + bf16 centroids
     binding.csa_destroy(ctx)
     for bad in (dict(head_dim=64), dict(n_probe=0), dict(n_probe=64), dict(n_probe=65, n_centroids=100),
                 dict(n_q_heads=3), dict(n_subspaces=8), dict(list_len=0), dict(list_len=10000),

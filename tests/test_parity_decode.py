@@ -38,7 +38,8 @@ def test_cfg0_automatic_grid():
     idx, score = case.export(0, 0)
     o_idx, o_score, mx = case.oracle_tables(0, 0)
     assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
-    assert mx * case.w.m < 2 ** 24 and mx * case.w.m * 8 > 2 ** 24   # within 3 bits of the limit
+    limit = min(2 ** 24 / case.w.m, 2 ** 19)      # exact sums of m scores; 20-bit packed entries
+    assert mx < limit and mx * 8 > limit          # within 3 bits of the limit
     case.check_step(0)
 
 
@@ -64,6 +65,23 @@ def test_ragged_shapes_import_and_build(G, part):
         assert np.array_equal(score, case.tables[(0, g)][1])
 
 
+@pytest.mark.parametrize("part", [4096, 8192, 16384])
+def test_key_ranges_spanning_several_index_blocks(part):
+    """Key ranges of 1, 2 and 4 blocks of 4096 key indices (a packed table entry keeps only the low
+    12 index bits; the block follows from the entry's position), ragged last range."""
+    w = small(f"blocks{part}", n_q_heads=4, n_kv_heads=2, n_pre=20011, C=30, L=700, m=9, k=1500,
+              steps=2)
+    case = Case(w, seed=part, F=13, partition_keys=part)
+    case.build_on_gpu()
+    for g in range(2):
+        idx, score = case.export(0, g)
+        o_idx, o_score, _ = case.oracle_tables(0, g)
+        assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
+    case.check_step(0)
+    case.append(1)
+    case.check_step(1)
+
+
 def _tie_heavy_tables(w, rng, qmax, fill):
     idx = np.full((w.batch, w.n_kv_heads, w.C, w.L), -1, np.int32)
     score = np.zeros((w.batch, w.n_kv_heads, w.C, w.L), np.float32)
@@ -79,13 +97,14 @@ def _tie_heavy_tables(w, rng, qmax, fill):
     return idx, score
 
 
-@pytest.mark.parametrize("k", [1, 64, 700, 5000])
-def test_tie_breaking_with_few_distinct_sums(k):
+@pytest.mark.parametrize("k,part", [(1, 1024), (64, 1024), (700, 1024), (5000, 1024), (700, 8192),
+                                    (3000, 16384)])
+def test_tie_breaking_with_few_distinct_sums(k, part):
     """Tables with integer scores in [-2, 2]: the k-th sum is shared by hundreds of keys, so the
     result is decided by the lowest-index rule, across key ranges and bitmap words; partially
     filled rows (unused slots) are skipped."""
     w = small("ties", n_q_heads=4, n_kv_heads=2, n_pre=9000, C=20, L=400, m=6, k=k, steps=1)
-    case = Case(w, seed=7, F=10, partition_keys=1024)
+    case = Case(w, seed=7, F=10, partition_keys=part)
     idx, score = _tie_heavy_tables(w, np.random.default_rng(k), 2, (250, 400))
     case.import_tables(idx, score)
     case.check_step(0)
@@ -211,7 +230,7 @@ def test_profile_counters_cover_every_stage():
     prof = binding.csa_profile_read(case.ctx.ctx)
     binding.csa_profile_enable(case.ctx.ctx, False)
     assert prof["append_kv"][1] == 1
-    for name in ("score_centroids", "top_centroids", "accumulate", "select", "attention_split",
+    for name in ("score_centroids", "top_centroids", "accumulate", "select_threshold", "select_emit", "attention_split",
                  "attention_merge"):
         assert prof[name][1] == 2 and prof[name][0] > 0
     assert all(v == (0.0, 0) for v in binding.csa_profile_read(case.ctx.ctx).values())
