@@ -67,7 +67,7 @@ typedef struct {
  * stored as the integer q = round-half-even(s * 2^F); the accumulated score of a key
  * (Sec. 3.3 (3), w_b = 1) is the exact integer sum of its q over the probed rows.  The library
  * requires n_probe * max|q| < 2^24, so the same sums are also exact in fp32 in any order, and
- * max|q| < 2^19 (a table entry is kept in 32 bits on the device: 20 bits of q, 12 index bits).
+ * max|q| < 2^18 (a table entry is kept in 32 bits on the device: 19 bits of q, 13 index bits).
  */
 
 /* Validates `cfg` and creates the host object.  No device work, no device allocation. */
@@ -101,7 +101,7 @@ int csa_bind(csa_ctx *ctx, void *tables_dev, size_t tables_bytes, void *scratch_
  *   centroids_dev: bf16 [B][Hkv][C][d], unit norm (Sec. 3.2 (1); clustering is the caller's).
  * K is read from the bound cache, rows [0, n_pre).  Sets the context length to n_pre.
  * SYNCHRONISES `stream` before returning (it reads back an overflow flag); returns
- * CSA_ERR_RANGE if some |q| * n_probe >= 2^24 or |q| >= 2^19 (tables are then unusable).
+ * CSA_ERR_RANGE if some |q| * n_probe >= 2^24 or |q| >= 2^18 (tables are then unusable).
  */
 int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, void *stream);
 

@@ -32,7 +32,7 @@ struct Layout {
 
 const char *kStageNames[CSA_N_STAGES] = {"score_centroids", "top_centroids",   "accumulate", "select_threshold",
                                          "select_emit",     "attention_split", "attention_merge", "append_kv"};
-constexpr int kUnit = 4096;  // key indices per block of a packed table row (see common.h)
+using csa::kUnit;
 
 }  // namespace
 
@@ -44,7 +44,7 @@ struct csa_ctx {
     const int32_t *block_table = nullptr;
     bool bound = false, have_tables = false;
     int n_pre = 0, n = 0, F = -1, R = 0, P = 0;
-    int Q = 0, nsub = 0, PO = 0;  // block size min(R, 4096), blocks per range, offsets per row
+    int Q = 0, nsub = 0, PO = 0;  // block size min(R, kUnit), blocks per range, offsets per row
     uint32_t key_lo = 0;  // coarse histogram: 512 bins of 2^key_sh keys starting at key_lo
     int key_sh = 0;
     int hip_err = 0;
@@ -163,10 +163,10 @@ void choose_partition(csa_ctx *ctx, int n_pre)
 template <class T>
 T *at(char *base, const Region &r) { return reinterpret_cast<T *>(base + r.off); }
 
-// largest admissible |q|: m sums stay below 2^24 and q fits the 20-bit field of a packed entry
+// largest admissible |q|: m sums stay below 2^24 and q fits its field of a packed entry
 int qmax_for(int m)
 {
-    const int a = ((1 << 24) - 1) / m, b = (1 << 19) - 1;
+    const int a = ((1 << 24) - 1) / m, b = csa::kQLimit;
     return a < b ? a : b;
 }
 

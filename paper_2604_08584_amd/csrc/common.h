@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "kernels.h"
+
 namespace csa {
 
 constexpr int kWave = 64;
@@ -11,15 +13,6 @@ constexpr int kHeadDim = 128;
 // (sum of q) * 64 + (number of probed rows that list it); non-zero iff the key was seen.
 constexpr int kCntBits = 6;
 constexpr int32_t kKeyBias = 1 << 24;  // accumulated |sum q| < 2^24  ->  key in (0, 2^25)
-
-// A table entry in device memory is one 32-bit word: the grid integer q (signed, kQBits bits) above
-// the low kUnitBits bits of the key index.  Rows are sorted by key index, and the per-row offsets
-// of every block of kUnit (or fewer) key indices tell which block an entry belongs to, so the high
-// bits of the index need not be stored.
-constexpr int kUnitBits = 12;
-constexpr int kUnit = 1 << kUnitBits;
-constexpr int kQBits = 32 - kUnitBits;
-constexpr int32_t kQLimit = (1 << (kQBits - 1)) - 1;  // |q| <= kQLimit
 
 __device__ __forceinline__ uint32_t pack_entry(int32_t idx, int32_t q)
 {

@@ -235,7 +235,8 @@ void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off
 // q*64 + 1: exact integer sums, order-free, and "seen" == accumulator != 0 (U of Sec. 3.3 (3):
 // a key absent from every probed row is not a candidate even if all sums are negative).
 // A wave owns whole rows (row constants are scalar) and keeps the slices of four rows in
-// flight, 32 bytes (8 packed entries) per lane.  What leaves the workgroup is the range's
+// flight, 32 bytes (8 packed entries) per lane.  The kernel is bound by instruction issue, so the
+// per-entry and per-slot paths are kept minimal.  What leaves the workgroup is the range's
 // presence bitmap (one bit per key index) and the keys sum + 2^24 of the present indices in
 // ascending index order - the index of a candidate is implied by its rank in the bitmap - plus
 // the head's coarse histogram of those keys.
@@ -339,6 +340,9 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     const unsigned long long pre4 = block_excl_scan_4x16<NT>(packed, s_scan, tot4);
     uint32_t *dk = cand_key + (size_t)head * cand_stride + (size_t)p * R;
     uint32_t *db = cand_bits + ((size_t)head * cand_stride + (size_t)p * R) / 32;
+    // sparse -> dense through LDS (every accumulator is in registers by now, so the array is free):
+    // the non-zero accumulators land at their rank, the per-slot work stays minimal
+    int32_t *s_dense = s_acc;
     int group_base = 0;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -346,11 +350,7 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
         const int av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
 #pragma unroll
         for (int x = 0; x < 4; ++x)
-            if (av[x] != 0) {
-                const uint32_t key = (uint32_t)((av[x] >> kCntBits) + kKeyBias);
-                dk[rank++] = key;
-                atomicAdd(&s_h[(key - key_lo) >> key_sh], 1u);
-            }
+            if (av[x] != 0) s_dense[rank++] = av[x];
         // eight neighbouring lanes hold the 32 bits of one bitmap word
         uint32_t w = nib[u] << (4 * (lane & 7));
         w |= __shfl_xor(w, 1, kWave);
@@ -358,6 +358,12 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
         w |= __shfl_xor(w, 4, kWave);
         if ((lane & 7) == 0) db[(u * NT + (int)threadIdx.x) >> 3] = w;
         group_base += (int)((tot4 >> (16 * u)) & 0xFFFFu);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < group_base; i += NT) {
+        const uint32_t key = (uint32_t)((s_dense[i] >> kCntBits) + kKeyBias);
+        dk[i] = key;
+        atomicAdd(&s_h[(key - key_lo) >> key_sh], 1u);
     }
     if (threadIdx.x == 0) seg_cnt[(size_t)head * P + p] = group_base;
     // histogram complete once every wave's LDS atomics have landed: wait for LDS traffic only
@@ -436,7 +442,10 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
     const uint32_t *hk = cand_key + (size_t)head * cand_stride;
     int32_t *out = sel + (size_t)head * k;
     const int wave = threadIdx.x / kWave, lane = lane_id();
-    // segment counts; |U| = their sum
+    // The kernel is a chain of memory latencies, so everything that can be requested before the
+    // first wait is: the segment counts, the coarse histogram, and - speculatively - the first
+    // 2 x 1024 key slots of the segment this wave walks first (slots past the segment's count
+    // hold stale keys and are masked once the count is known).
     int part = 0;
     for (int p = threadIdx.x; p < kSelMaxP; p += kThrNT) {
         const int c = p < P ? min(seg_cnt[(size_t)head * P + p], R) : 0;
@@ -445,37 +454,61 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
         s_eq[p] = 0;
         part += c;
     }
+    const uint32_t my_hist = threadIdx.x < kCoarseBins ? hist_g[(size_t)head * kCoarseBins + threadIdx.x] : 0u;
+    uint32_t pre0[16], pre1[16];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int e = (x * kWave + lane) * 4;
+        uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+        if (wave < P) {
+            v0 = *(const uint4 *)(hk + (size_t)wave * R + e);                                   // e + 3 < 1024 <= R
+            if (e + kWave * 16 < R) v1 = *(const uint4 *)(hk + (size_t)wave * R + e + kWave * 16);
+        }
+        pre0[4 * x] = v0.x; pre0[4 * x + 1] = v0.y; pre0[4 * x + 2] = v0.z; pre0[4 * x + 3] = v0.w;
+        pre1[4 * x] = v1.x; pre1[4 * x + 1] = v1.y; pre1[4 * x + 2] = v1.z; pre1[4 * x + 3] = v1.w;
+    }
     if (threadIdx.x == 0) s_n = 0;
     int n_total;
     block_excl_scan<kThrNT>(part, s_scan, n_total);  // (its barriers also publish the LDS writes)
     const int k_eff = n_total < k ? n_total : k;
     if (threadIdx.x == 0) sel_count[head] = k_eff;
     for (int a = k_eff + threadIdx.x; a < k; a += kThrNT) out[a] = -1;
+    {
+        const int c = wave < P ? s_cnt[wave] : 0;
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = (x * kWave + lane) * 4 + j;
+                if (e >= c) pre0[4 * x + j] = 0u;
+                if (e + kWave * 16 >= c) pre1[4 * x + j] = 0u;
+            }
+    }
 
-    // stream(fn, seg_end): fn(key, p) over the candidate keys of every segment p (key = 0 for
-    // padding - a real key is never 0), then seg_end(p).  A wave walks whole segments, four
-    // consecutive keys per lane and load; both callbacks may use wave-level operations only.
-    auto stream = [&](auto fn, auto seg_end) {
+    // stream(chunk, seg_end): chunk(keys, p) for every 16 x 64 candidate keys of every segment p
+    // (keys[] = this lane's 16; 0 = padding - a real key is never 0), then seg_end(p).  A wave
+    // walks whole segments, four consecutive keys per lane and load; both callbacks may use
+    // wave-level operations only.
+    auto stream = [&](auto chunk, auto seg_end) {
         for (int p = wave; p < P; p += NW) {
             const int c = s_cnt[p];
-            const int s0 = p * R;
             for (int e0 = 0; e0 < c; e0 += kWave * 16) {
-                uint4 kk[4];
+                uint32_t cur[16];
+                if (p == wave && e0 < 2 * kWave * 16) {  // (wave-uniform)
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const int e = e0 + (x * kWave + lane) * 4;
-                    kk[x] = e < c ? *(const uint4 *)(hk + s0 + e) : make_uint4(0, 0, 0, 0);
-                    if (e + 1 >= c) kk[x].y = 0;
-                    if (e + 2 >= c) kk[x].z = 0;
-                    if (e + 3 >= c) kk[x].w = 0;
-                }
+                    for (int i = 0; i < 16; ++i) cur[i] = e0 == 0 ? pre0[i] : pre1[i];
+                } else {
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    fn(kk[x].x, p);
-                    fn(kk[x].y, p);
-                    fn(kk[x].z, p);
-                    fn(kk[x].w, p);
+                    for (int x = 0; x < 4; ++x) {
+                        const int e = e0 + (x * kWave + lane) * 4;
+                        const uint4 v = e < c ? *(const uint4 *)(hk + (size_t)p * R + e) : make_uint4(0, 0, 0, 0);
+                        cur[4 * x + 0] = v.x;
+                        cur[4 * x + 1] = e + 1 < c ? v.y : 0u;
+                        cur[4 * x + 2] = e + 2 < c ? v.z : 0u;
+                        cur[4 * x + 3] = e + 3 < c ? v.w : 0u;
+                    }
                 }
+                chunk(cur, p);
             }
             seg_end(p);
         }
@@ -490,8 +523,8 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
         // first round: the head's coarse histogram, filled by the accumulation kernel
         uint32_t lo = key_lo, hi = key_lo + ((uint32_t)kCoarseBins << key_sh) - 1u;
         int sh = key_sh;
-        for (int i = threadIdx.x; i < kCoarseBins; i += kThrNT)
-            s_hist[i] = hist_g[(size_t)head * kCoarseBins + i];
+        static_assert(kCoarseBins <= kThrNT, "one bin per thread");
+        if (threadIdx.x < kCoarseBins) s_hist[threadIdx.x] = my_hist;
         __syncthreads();
         int want = k;
         for (bool have_hist = true;; have_hist = false) {
@@ -500,9 +533,12 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
                 while (((hi - lo) >> sh) >= 512u) ++sh;
                 for (int i = threadIdx.x; i < 512; i += kThrNT) s_hist[i] = 0;
                 __syncthreads();
-                stream([&](uint32_t key, int) {
-                           const bool in = key >= lo && key <= hi;
-                           hist_add(s_hist, in ? (key - lo) >> sh : 0u, in);
+                stream([&](const uint32_t (&keys)[16], int) {
+#pragma unroll
+                           for (int i = 0; i < 16; ++i) {
+                               const bool in = keys[i] >= lo && keys[i] <= hi;
+                               hist_add(s_hist, in ? (keys[i] - lo) >> sh : 0u, in);
+                           }
                        },
                        [&](int) {});
                 __syncthreads();
@@ -518,9 +554,12 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
                 T = lo;
                 need = want;
                 int n_gt = 0, n_eq = 0;
-                stream([&](uint32_t key, int) {
-                           n_gt += key > T ? 1 : 0;
-                           n_eq += key == T ? 1 : 0;
+                stream([&](const uint32_t (&keys)[16], int) {
+#pragma unroll
+                           for (int i = 0; i < 16; ++i) {
+                               n_gt += keys[i] > T ? 1 : 0;
+                               n_eq += keys[i] == T ? 1 : 0;
+                           }
                        },
                        [&](int p) {
                            n_gt = wave_sum(n_gt);
@@ -539,16 +578,26 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
                 // range the keys above the bin (sure winners)
                 __syncthreads();
                 int n_gt = 0;
-                stream([&](uint32_t key, int p) {
-                           n_gt += key > hi ? 1 : 0;
-                           const bool in = key >= lo && key <= hi;
-                           const uint64_t mask = __ballot(in);
-                           if (mask) {
+                stream([&](const uint32_t (&keys)[16], int p) {
+                           // one LDS atomic per wave and chunk reserves room for all its contenders
+                           int n_in = 0;
+#pragma unroll
+                           for (int i = 0; i < 16; ++i) {
+                               n_gt += keys[i] > hi ? 1 : 0;
+                               n_in += keys[i] >= lo && keys[i] <= hi ? 1 : 0;
+                           }
+                           const int incl = wave_incl_scan(n_in);
+                           const int n_wave = __builtin_amdgcn_readlane(incl, kWave - 1);
+                           if (n_wave) {
                                int wbase = 0;
-                               if (in && mbcnt(mask) == 0) wbase = atomicAdd(&s_n, __popcll(mask));
-                               wbase = __builtin_amdgcn_readlane(wbase, __ffsll((unsigned long long)mask) - 1);
-                               const int o = wbase + mbcnt(mask);
-                               if (in && o < kSelCap) s_ck[o] = ((key - lo) << kSegBits) | (uint32_t)p;
+                               if (lane == 0) wbase = atomicAdd(&s_n, n_wave);
+                               int o = __builtin_amdgcn_readfirstlane(wbase) + incl - n_in;
+#pragma unroll
+                               for (int i = 0; i < 16; ++i)
+                                   if (keys[i] >= lo && keys[i] <= hi) {
+                                       if (o < kSelCap) s_ck[o] = ((keys[i] - lo) << kSegBits) | (uint32_t)p;
+                                       ++o;
+                                   }
                            }
                        },
                        [&](int p) {
@@ -608,10 +657,14 @@ void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t 
 // ---------------------------------------------------------------------------------------------
 // Step 4, second half: range p of a head writes its winners - candidates with key > T plus its
 // allowed number of lowest-index candidates with key == T - as ascending key indices, starting
-// at its output slot.  The candidates' keys are staged in LDS; thread t owns bitmap word t (32
-// key indices) and finds its keys by the rank of its bits.
-// grid (P, B*Hq), block NT = max(64, R/32), dynamic LDS R*4 bytes.
+// at its output slot.  Thread t owns bitmap word t (32 key indices) and finds its keys by the
+// rank of its bits; the keys are staged in LDS, kEmitStage at a time (one round unless the
+// range is unusually dense).  Every independent load is issued before the first wait: the
+// kernel is a chain of latencies, not of bytes.
+// grid (P, B*Hq), block NT = max(64, R/32).
 // ---------------------------------------------------------------------------------------------
+constexpr int kEmitStage = 2048;
+
 template <int NT>
 __global__ __launch_bounds__(NT) void k_emit(const uint32_t *__restrict__ cand_key,
                                              const uint32_t *__restrict__ cand_bits,
@@ -621,34 +674,49 @@ __global__ __launch_bounds__(NT) void k_emit(const uint32_t *__restrict__ cand_k
                                              int32_t *__restrict__ sel, int k, int R, int P,
                                              size_t cand_stride)
 {
-    extern __shared__ __align__(16) uint32_t s_key[];  // [R]
+    __shared__ __align__(16) uint32_t s_key[kEmitStage];
     __shared__ int s_scan[NT / kWave + 1];
     const int p = blockIdx.x, head = blockIdx.y;
-    const int c = min(seg_cnt[(size_t)head * P + p], R);
-    const uint32_t T = thr[head];
-    if (c <= 0 || T == 0xFFFFFFFFu) return;  // (uniform over the workgroup)
-    const int2 par = seg_par[(size_t)head * P + p];
     const size_t seg0 = (size_t)head * cand_stride + (size_t)p * R;
-    for (int i = threadIdx.x * 4; i < c; i += NT * 4)  // the segment has R slots, R % 4 == 0
-        *(uint4 *)(s_key + i) = *(const uint4 *)(cand_key + seg0 + i);
+    const int n_stage = R < kEmitStage ? R : kEmitStage;  // slots [0, n_stage) exist in every segment
     const int W = R / 32;
     const uint32_t word = (int)threadIdx.x < W ? cand_bits[seg0 / 32 + threadIdx.x] : 0u;
+    for (int i = threadIdx.x * 4; i < n_stage; i += NT * 4)
+        *(uint4 *)(s_key + i) = *(const uint4 *)(cand_key + seg0 + i);
+    const int c = min(seg_cnt[(size_t)head * P + p], R);
+    const uint32_t T = thr[head];
+    const int2 par = seg_par[(size_t)head * P + p];
+    if (c <= 0 || T == 0xFFFFFFFFu) return;  // (uniform over the workgroup)
     int total;
-    int rank = block_excl_scan<NT>(__popc(word), s_scan, total);  // (its barriers publish s_key)
+    const int rank = block_excl_scan<NT>(__popc(word), s_scan, total);  // (its barriers publish s_key)
     uint32_t gt = 0, eq = 0;
-    for (uint32_t b = word; b; b &= b - 1) {
-        const uint32_t bit = b & (0u - b);
-        const uint32_t key = rank < c ? s_key[rank] : 0u;
-        ++rank;
-        if (key > T) gt |= bit;
-        else if (key == T) eq |= bit;
+    for (int base = 0; base < c; base += kEmitStage) {
+        if (base) {
+            __syncthreads();
+            for (int i = threadIdx.x * 4; i < kEmitStage && base + i < c; i += NT * 4)
+                *(uint4 *)(s_key + i) = *(const uint4 *)(cand_key + seg0 + base + i);
+            __syncthreads();
+        }
+        int r = rank - base;
+        for (uint32_t b = word; b; b &= b - 1, ++r) {
+            if ((unsigned)r < (unsigned)kEmitStage) {
+                const uint32_t bit = b & (0u - b);
+                const uint32_t key = s_key[r];
+                if (key > T) gt |= bit;
+                else if (key == T) eq |= bit;
+            }
+        }
     }
     // keep the lowest-index ties this range is allowed
-    int allow = par.y - block_excl_scan<NT>(__popc(eq), s_scan, total);
-    if (allow <= 0)
+    if (par.y <= 0) {
         eq = 0;
-    else
-        while (__popc(eq) > allow) eq &= ~(0x80000000u >> __clz(eq));  // drop the highest bit
+    } else {
+        const int allow = par.y - block_excl_scan<NT>(__popc(eq), s_scan, total);
+        if (allow <= 0)
+            eq = 0;
+        else
+            while (__popc(eq) > allow) eq &= ~(0x80000000u >> __clz(eq));  // drop the highest bit
+    }
     uint32_t bits = gt | eq;
     int pos = par.x + block_excl_scan<NT>(__popc(bits), s_scan, total);
     int32_t *out = sel + (size_t)head * k;
@@ -665,14 +733,9 @@ void launch_emit(const uint32_t *cand_key, const uint32_t *cand_bits, const int3
 {
     if (k <= 0) return;
     dim3 grid(P, n_heads);
-    static bool attr = false;
-    if (!attr) {
-        (void)hipFuncSetAttribute((const void *)k_emit<512>, hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4);
-        attr = true;
-    }
-#define CSA_EMIT(NT_)                                                                              \
-    k_emit<NT_><<<grid, NT_, (size_t)R * 4, st>>>(cand_key, cand_bits, seg_cnt, thr, (const int2 *)seg_par, \
-                                                  sel, k, R, P, cand_stride)
+#define CSA_EMIT(NT_)                                                                                \
+    k_emit<NT_><<<grid, NT_, 0, st>>>(cand_key, cand_bits, seg_cnt, thr, (const int2 *)seg_par, sel, k, R, P, \
+                                      cand_stride)
     switch (R) {
     case 1024: CSA_EMIT(64); break;
     case 2048: CSA_EMIT(64); break;

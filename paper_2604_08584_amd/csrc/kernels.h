@@ -5,6 +5,15 @@
 
 namespace csa {
 
+// A table entry in device memory is one 32-bit word: the grid integer q (signed, kQBits bits) above
+// the low kUnitBits bits of the key index.  Rows are sorted by key index, and the per-row offsets
+// of every block of kUnit (or fewer) key indices tell which block an entry belongs to, so the high
+// bits of the index need not be stored.
+constexpr int kUnitBits = 13;
+constexpr int kUnit = 1 << kUnitBits;
+constexpr int kQBits = 32 - kUnitBits;
+constexpr int32_t kQLimit = (1 << (kQBits - 1)) - 1;  // |q| <= kQLimit
+
 // ---- tables.hip
 void launch_pack_centroids(const void *cent, void *cent_t, int n_bg, int C, hipStream_t st);
 void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32_t *part_off,

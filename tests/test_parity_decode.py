@@ -38,7 +38,7 @@ def test_cfg0_automatic_grid():
     idx, score = case.export(0, 0)
     o_idx, o_score, mx = case.oracle_tables(0, 0)
     assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
-    limit = min(2 ** 24 / case.w.m, 2 ** 19)      # exact sums of m scores; 20-bit packed entries
+    limit = min(2 ** 24 / case.w.m, 2 ** 18)      # exact sums of m scores; 19-bit packed scores
     assert mx < limit and mx * 8 > limit          # within 3 bits of the limit
     case.check_step(0)
 
@@ -67,8 +67,8 @@ def test_ragged_shapes_import_and_build(G, part):
 
 @pytest.mark.parametrize("part", [4096, 8192, 16384])
 def test_key_ranges_spanning_several_index_blocks(part):
-    """Key ranges of 1, 2 and 4 blocks of 4096 key indices (a packed table entry keeps only the low
-    12 index bits; the block follows from the entry's position), ragged last range."""
+    """Key ranges of half a block, one block and two blocks of 8192 key indices (a packed table entry
+    keeps only the low 13 index bits; the block follows from the entry's position), ragged last range."""
     w = small(f"blocks{part}", n_q_heads=4, n_kv_heads=2, n_pre=20011, C=30, L=700, m=9, k=1500,
               steps=2)
     case = Case(w, seed=part, F=13, partition_keys=part)
