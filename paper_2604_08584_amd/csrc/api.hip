@@ -82,7 +82,7 @@ Layout make_layout(const csa_config &c)
     l.tables_bytes = off;
     off = 0;
     l.cand_keys = ((size_t)c.max_ctx + 16383) / 16384 * 16384;
-    l.S_max = csa::attention_splits(c.budget_k, c.max_ctx);
+    l.S_max = csa::attention_splits(c.budget_k, l.P_max, c.max_ctx);
     put(l.z, BH * c.n_centroids * 4);
     put(l.rows, BH * c.n_probe * 4);
     put(l.spans, BH * (size_t)c.n_probe * 2 * l.PO_max * 4);  // P * (nsub + 1) <= 2 * PO offsets per row
@@ -404,7 +404,7 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     int32_t *sel = sel_idx_dev ? sel_idx_dev : at<int32_t>(ctx->scratch, l.sel);
     int32_t *sel_count = sel_count_dev ? sel_count_dev : at<int32_t>(ctx->scratch, l.sel_count);
     float *part = at<float>(ctx->scratch, l.part);
-    const int S = csa::attention_splits(c.budget_k, ctx->n - ctx->n_pre);
+    const int S = csa::attention_splits(c.budget_k, ctx->P, ctx->n - ctx->n_pre);
 
     Prof prof(ctx, st);
     prof.mark(0);
@@ -426,9 +426,9 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     csa::launch_emit(cand_key, cand_bits, cand_cnt, thr, seg_par, sel, BH, c.budget_k, ctx->R, ctx->P,
                      l.cand_keys, st);
     prof.mark(5);
-    csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, part,
-                                c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ctx->n_pre, ctx->n,
-                                c.max_ctx, S, st);
+    csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, seg_par,
+                                part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ctx->n_pre, ctx->n,
+                                c.max_ctx, S, ctx->P, st);
     prof.mark(6);
     csa::launch_attention_merge(part, out_dev, BH, S, st);
     prof.mark(7);

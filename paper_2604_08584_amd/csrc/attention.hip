@@ -23,12 +23,15 @@ constexpr int kItemsPerWave = 128;              // two index registers per lane
 constexpr int kSplit = kAttWaves * kItemsPerWave;  // 512 attended keys per workgroup
 
 // ---------------------------------------------------------------------------------------------
-// Split-KV gathered attention.  Workgroup (head, s) handles attended items
-// [s*kSplit, (s+1)*kSplit) of the head, where item a < sel_count is prefill key sel[a] and item
-// a >= sel_count is appended key n_pre + (a - sel_count).  A K or V row (256 B) is read by 16
-// lanes x 16 B, so one wave load instruction fetches 4 whole rows; each 16-lane group keeps its
-// own online-softmax state for the rows it sees, merged at the end.  Logits are taken in the
-// log2 domain (q pre-scaled by log2(e)/sqrt(d)).  Output: un-normalised partial
+// Split-KV gathered attention.  The attended keys of a head are cut the way the search half cut
+// them: split s < P_sel holds the selected keys whose index lies in key range s (their slice of
+// the head's ascending `sel` list starts at seg_par[head][s].x), split s >= P_sel holds a run of
+// kSplit keys appended since prefill.  Cutting by key range rather than by rank means the G query
+// heads of a KV head walk the same stretch of K/V in the same split, so a row picked by several of
+// them is fetched from HBM once and hits in L2 for the others.  A K or V row (256 B) is read by
+// 16 lanes x 16 B, so one wave load instruction fetches 4 whole rows; each 16-lane group keeps
+// its own online-softmax state for the rows it sees, merged at the end.  Logits are taken in
+// the log2 domain (q pre-scaled by log2(e)/sqrt(d)).  Output: un-normalised partial
 // (max, sum, o[128]) per (head, split).
 // grid ceil8(B*Hkv*S) * G workgroups (1-D, see the id mapping below), block 256.
 // ---------------------------------------------------------------------------------------------
@@ -36,14 +39,14 @@ template <bool PAGED>
 __global__ __launch_bounds__(kAttNT) void k_attention_split(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc,
     const int32_t *__restrict__ block_table, const int32_t *__restrict__ sel,
-    const int32_t *__restrict__ sel_count, float *__restrict__ part, int k, int n_pre, int n,
-    int Hq, int G, int Hkv, int max_ctx, int S, int n_units, float qscale)
+    const int32_t *__restrict__ sel_count, const int2 *__restrict__ seg_par,
+    float *__restrict__ part, int k, int n_pre, int n, int Hq, int G, int Hkv, int max_ctx, int S,
+    int P, int P_sel, int n_units, float qscale)
 {
     __shared__ float s_m[kAttWaves], s_l[kAttWaves], s_o[kAttWaves][kHeadDim];
     // XCD-aware order: the chip deals consecutive workgroup ids round-robin to its 8 XCDs (each
-    // with its own L2).  The G query heads of a KV head select overlapping keys, so the G
-    // workgroups that handle the same split of the same KV head get ids 8 apart: same XCD, same
-    // moment, and a K/V row fetched for one head is an L2 hit for the others.
+    // with its own L2).  The G workgroups that handle the same split of the same KV head get ids
+    // 8 apart: same XCD, same moment.
     const int id = blockIdx.x;
     const int unit = (id / (kXcd * G)) * kXcd + id % kXcd;  // (KV head, split) pair
     if (unit >= n_units) return;                            // grid padded to a multiple of 8 * G
@@ -52,10 +55,19 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
     const int b = head / Hq, g = (head % Hq) / G;
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int sub = lane >> 4, c = lane & 15;
-    const int n_sel = sel_count[head];
-    const int n_att = n_sel + (n - n_pre);
     float *pout = part + ((size_t)head * S + s) * (kHeadDim + 2);
-    const int a0 = s * kSplit + wave * kItemsPerWave;  // first item of this wave
+    // this workgroup's items: [first, first + count) of the head's sel list, or of the appended keys
+    const bool from_sel = s < P_sel;
+    int first, count;
+    if (from_sel) {
+        const int n_sel = min(sel_count[head], k);
+        first = min(seg_par[(size_t)head * P + s].x, n_sel);
+        const int end = s + 1 < P ? min(seg_par[(size_t)head * P + s + 1].x, n_sel) : n_sel;
+        count = max(end - first, 0);
+    } else {
+        first = n_pre + (s - P_sel) * kSplit;
+        count = max(min(kSplit, n - first), 0);
+    }
 
     // this lane's 8 query dimensions, pre-scaled
     float qv[8];
@@ -66,62 +78,87 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
         qv[4] = bf16_lo(w.z) * qscale; qv[5] = bf16_hi(w.z) * qscale;
         qv[6] = bf16_lo(w.w) * qscale; qv[7] = bf16_hi(w.w) * qscale;
     }
-    // row numbers (in units of 256-byte rows of the cache / pool) of items a0+lane, a0+64+lane
-    int64_t rown[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int a = a0 + u * kWave + lane;
-        int key = 0;
-        if (a < n_sel)
-            key = sel[(size_t)head * k + a];
-        else if (a < n_att)
-            key = n_pre + (a - n_sel);
-        if ((unsigned)key >= (unsigned)n) key = 0;  // never form an address from a bad index
-        if (PAGED) {
-            const int page = block_table[(size_t)b * (max_ctx >> 4) + (key >> 4)];
-            rown[u] = ((int64_t)page * Hkv + g) * 16 + (key & 15);
-        } else {
-            rown[u] = ((int64_t)b * Hkv + g) * max_ctx + key;
-        }
-    }
     float m_run = -INFINITY, l_run = 0.0f, o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = 0.0f;
 
-    const int n_here = min(kItemsPerWave, n_att - a0);  // items of this wave (may be <= 0)
-    for (int it = 0; it * 8 < n_here; ++it) {
-        // items it*8 + sub and it*8 + 4 + sub
-        const int i0 = it * 8 + sub, i1 = i0 + 4;
-        const int64_t src = it < 8 ? rown[0] : rown[1];
-        const int64_t r0 = __shfl(src, i0 & 63, kWave), r1 = __shfl(src, i1 & 63, kWave);
-        const uint4 k0 = *(const uint4 *)(kc + r0 * kHeadDim + c * 8);
-        const uint4 k1 = *(const uint4 *)(kc + r1 * kHeadDim + c * 8);
-        const uint4 v0 = *(const uint4 *)(vc + r0 * kHeadDim + c * 8);
-        const uint4 v1 = *(const uint4 *)(vc + r1 * kHeadDim + c * 8);
-        float d0 = qv[0] * bf16_lo(k0.x), d1 = qv[0] * bf16_lo(k1.x);
-        d0 = fmaf(qv[1], bf16_hi(k0.x), d0); d1 = fmaf(qv[1], bf16_hi(k1.x), d1);
-        d0 = fmaf(qv[2], bf16_lo(k0.y), d0); d1 = fmaf(qv[2], bf16_lo(k1.y), d1);
-        d0 = fmaf(qv[3], bf16_hi(k0.y), d0); d1 = fmaf(qv[3], bf16_hi(k1.y), d1);
-        d0 = fmaf(qv[4], bf16_lo(k0.z), d0); d1 = fmaf(qv[4], bf16_lo(k1.z), d1);
-        d0 = fmaf(qv[5], bf16_hi(k0.z), d0); d1 = fmaf(qv[5], bf16_hi(k1.z), d1);
-        d0 = fmaf(qv[6], bf16_lo(k0.w), d0); d1 = fmaf(qv[6], bf16_lo(k1.w), d1);
-        d0 = fmaf(qv[7], bf16_hi(k0.w), d0); d1 = fmaf(qv[7], bf16_hi(k1.w), d1);
-        d0 = row16_sum(d0);
-        d1 = row16_sum(d1);
-        if (i0 >= n_here) d0 = -INFINITY;
-        if (i1 >= n_here) d1 = -INFINITY;
-        const float m_new = fmaxf(m_run, fmaxf(d0, d1));
-        if (m_new != -INFINITY) {  // this 16-lane group has seen at least one real item
-            const float sc = exp2f(m_run - m_new);
-            const float p0 = exp2f(d0 - m_new), p1 = exp2f(d1 - m_new);
-            l_run = l_run * sc + p0 + p1;
-            const float vf0[8] = {bf16_lo(v0.x), bf16_hi(v0.x), bf16_lo(v0.y), bf16_hi(v0.y),
-                                  bf16_lo(v0.z), bf16_hi(v0.z), bf16_lo(v0.w), bf16_hi(v0.w)};
-            const float vf1[8] = {bf16_lo(v1.x), bf16_hi(v1.x), bf16_lo(v1.y), bf16_hi(v1.y),
-                                  bf16_lo(v1.z), bf16_hi(v1.z), bf16_lo(v1.w), bf16_hi(v1.w)};
+    // kSplit items per pass over the workgroup (one pass unless a key range is unusually popular).
+    // The four waves interleave: group j of 8 consecutive items belongs to wave j % 4, so the
+    // workgroup moves through its (ascending) keys as one front - and the workgroups of the other
+    // heads of the KV head, started at the same moment on the same XCD, move with it.
+    for (int base = 0; base < count; base += kSplit) {
+        const int rem = count - base;             // items left for the workgroup
+        if (wave * 8 >= rem) break;               // nothing for this wave (wave-uniform)
+        // this wave's slot t < 128 is item base + ((t / 8) * 4 + wave) * 8 + t % 8; a prefix of
+        // the slots is valid.  Row numbers (in units of 256-byte rows of the cache / pool) of slots
+        // lane and 64 + lane:
+        int64_t rown[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = fmaf(p1, vf1[e], fmaf(p0, vf0[e], o[e] * sc));
-            m_run = m_new;
+        for (int u = 0; u < 2; ++u) {
+            const int t = u * kWave + lane;
+            const int a = ((t >> 3) * kAttWaves + wave) * 8 + (t & 7);
+            int key = 0;
+            if (a < rem) key = from_sel ? sel[(size_t)head * k + first + base + a] : first + base + a;
+            if ((unsigned)key >= (unsigned)n) key = 0;  // never form an address from a bad index
+            if (PAGED) {
+                const int page = block_table[(size_t)b * (max_ctx >> 4) + (key >> 4)];
+                rown[u] = ((int64_t)page * Hkv + g) * 16 + (key & 15);
+            } else {
+                rown[u] = ((int64_t)b * Hkv + g) * max_ctx + key;
+            }
+        }
+        // valid slots of this wave: full groups of 8 plus the ragged last one
+        int n_here = 0;
+        {
+            const int groups = (rem + 7) / 8;                              // groups of the workgroup
+            const int mine = (groups - wave + kAttWaves - 1) / kAttWaves;  // groups of this wave (>= 1)
+            const int last = ((mine - 1) * kAttWaves + wave) * 8;          // first item of its last group
+            n_here = min(kItemsPerWave, (mine - 1) * 8 + min(8, rem - last));
+        }
+        // rows of iteration `it`: items it*8 + sub and it*8 + 4 + sub; the next iteration's rows are
+        // requested before this one's are used, so that eight row loads per lane group stay in flight
+        auto fetch = [&](int it, uint4 &k0, uint4 &k1, uint4 &v0, uint4 &v1) {
+            const int i0 = it * 8 + sub, i1 = i0 + 4;
+            const int64_t src = it < 8 ? rown[0] : rown[1];
+            const int64_t r0 = __shfl(src, i0 & 63, kWave), r1 = __shfl(src, i1 & 63, kWave);
+            k0 = *(const uint4 *)(kc + r0 * kHeadDim + c * 8);
+            k1 = *(const uint4 *)(kc + r1 * kHeadDim + c * 8);
+            v0 = *(const uint4 *)(vc + r0 * kHeadDim + c * 8);
+            v1 = *(const uint4 *)(vc + r1 * kHeadDim + c * 8);
+        };
+        uint4 k0, k1, v0, v1, nk0, nk1, nv0, nv1;
+        fetch(0, k0, k1, v0, v1);
+        for (int it = 0; it * 8 < n_here; ++it) {
+            const int i0 = it * 8 + sub, i1 = i0 + 4;
+            // (unconditional, so that the wait below can leave exactly these four loads in flight;
+            // after the last iteration it re-requests the rows just used, which hit in cache)
+            fetch((it + 1) * 8 < n_here ? it + 1 : it, nk0, nk1, nv0, nv1);
+            float d0 = qv[0] * bf16_lo(k0.x), d1 = qv[0] * bf16_lo(k1.x);
+            d0 = fmaf(qv[1], bf16_hi(k0.x), d0); d1 = fmaf(qv[1], bf16_hi(k1.x), d1);
+            d0 = fmaf(qv[2], bf16_lo(k0.y), d0); d1 = fmaf(qv[2], bf16_lo(k1.y), d1);
+            d0 = fmaf(qv[3], bf16_hi(k0.y), d0); d1 = fmaf(qv[3], bf16_hi(k1.y), d1);
+            d0 = fmaf(qv[4], bf16_lo(k0.z), d0); d1 = fmaf(qv[4], bf16_lo(k1.z), d1);
+            d0 = fmaf(qv[5], bf16_hi(k0.z), d0); d1 = fmaf(qv[5], bf16_hi(k1.z), d1);
+            d0 = fmaf(qv[6], bf16_lo(k0.w), d0); d1 = fmaf(qv[6], bf16_lo(k1.w), d1);
+            d0 = fmaf(qv[7], bf16_hi(k0.w), d0); d1 = fmaf(qv[7], bf16_hi(k1.w), d1);
+            d0 = row16_sum(d0);
+            d1 = row16_sum(d1);
+            if (i0 >= n_here) d0 = -INFINITY;
+            if (i1 >= n_here) d1 = -INFINITY;
+            const float m_new = fmaxf(m_run, fmaxf(d0, d1));
+            if (m_new != -INFINITY) {  // this 16-lane group has seen at least one real item
+                const float sc = exp2f(m_run - m_new);
+                const float p0 = exp2f(d0 - m_new), p1 = exp2f(d1 - m_new);
+                l_run = l_run * sc + p0 + p1;
+                const float vf0[8] = {bf16_lo(v0.x), bf16_hi(v0.x), bf16_lo(v0.y), bf16_hi(v0.y),
+                                      bf16_lo(v0.z), bf16_hi(v0.z), bf16_lo(v0.w), bf16_hi(v0.w)};
+                const float vf1[8] = {bf16_lo(v1.x), bf16_hi(v1.x), bf16_lo(v1.y), bf16_hi(v1.y),
+                                      bf16_lo(v1.z), bf16_hi(v1.z), bf16_lo(v1.w), bf16_hi(v1.w)};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = fmaf(p1, vf1[e], fmaf(p0, vf0[e], o[e] * sc));
+                m_run = m_new;
+            }
+            k0 = nk0; k1 = nk1; v0 = nv0; v1 = nv1;
         }
     }
     // merge the four 16-lane groups of the wave (lanes c, c+16, c+32, c+48)
@@ -198,26 +235,35 @@ __global__ __launch_bounds__(kHeadDim) void k_attention_merge(const float *__res
     out[(size_t)blockIdx.x * kHeadDim + threadIdx.x] = l > 0.0f ? acc / l : 0.0f;
 }
 
-int attention_splits(int k, int n_appended) { return (k + n_appended + kSplit - 1) / kSplit; }
+// number of splits: one per key range for the selected keys (none when k = 0), one per kSplit
+// appended keys
+int attention_splits(int k, int P, int n_appended)
+{
+    return (k > 0 ? P : 0) + (n_appended + kSplit - 1) / kSplit;
+}
 
 void launch_attention_split(const void *q, const void *kc, const void *vc,
                             const int32_t *block_table, const int32_t *sel,
-                            const int32_t *sel_count, float *part, int B, int Hq, int Hkv, int k,
-                            int n_pre, int n, int max_ctx, int S, hipStream_t st)
+                            const int32_t *sel_count, const void *seg_par, float *part, int B, int Hq,
+                            int Hkv, int k, int n_pre, int n, int max_ctx, int S, int P,
+                            hipStream_t st)
 {
     if (S <= 0) return;
     const float qscale = 1.4426950408889634f / sqrtf((float)kHeadDim);
     const int G = Hq / Hkv;
     const int n_units = B * Hkv * S;
+    const int P_sel = k > 0 ? P : 0;
     dim3 grid((n_units + kXcd - 1) / kXcd * kXcd * G), block(kAttNT);
     if (block_table)
         k_attention_split<true><<<grid, block, 0, st>>>(
             (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, block_table, sel,
-            sel_count, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, n_units, qscale);
+            sel_count, (const int2 *)seg_par, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, P, P_sel,
+            n_units, qscale);
     else
         k_attention_split<false><<<grid, block, 0, st>>>(
             (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, nullptr, sel,
-            sel_count, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, n_units, qscale);
+            sel_count, (const int2 *)seg_par, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, P, P_sel,
+            n_units, qscale);
 }
 
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st)
