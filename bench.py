@@ -38,6 +38,11 @@ def main():
     ap.add_argument("--partition-keys", type=int, default=0)
     ap.add_argument("--kmeans-sample", type=int, default=0,
                     help="cap on pooled prefill queries seen by the centroid synthesis (0 = all)")
+    ap.add_argument("--search-period", type=int, default=1,
+                    help="schedule 'keep ratio + search period': search every P-th step, reuse the "
+                         "index set in between (csa_decode_step_reuse)")
+    ap.add_argument("--keep-ratio", type=float, default=0.0,
+                    help="budget k = round(ratio * N_pre) instead of the config's (0 = config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies before the timed region, "
@@ -60,6 +65,9 @@ def main():
     base = CONFIGS[args.config]
     K, W = args.steps, args.warmup
     w = dataclasses.replace(base, steps=max(K, W, 1))
+    if args.keep_ratio > 0:
+        w = dataclasses.replace(w, k=int(round(args.keep_ratio * w.n_pre)))
+    period = max(1, args.search_period)
     B, Hq, Hkv, G = w.batch, w.n_q_heads, w.n_kv_heads, w.group
     log(f"[bench] workload {w.name}: B={B} Hq={Hq} Hkv={Hkv} N_pre={w.n_pre} C={w.C} L={w.L} "
         f"m={w.m} k={w.k} pre_appended={w.pre_appended} page={w.page_size} steps={K} warmup={W}")
@@ -94,7 +102,10 @@ def main():
     def run(n_steps):
         for s in range(n_steps):
             t = w.pre_appended + s
-            ctx.decode_step(q_steps[t])
+            if s % period == 0:
+                ctx.decode_step(q_steps[t])
+            else:
+                ctx.decode_step_reuse(q_steps[t])
             ctx.append_kv(k_new[t], v_new[t])
 
     if args.copy_calibration:
@@ -124,19 +135,22 @@ def main():
     torch.cuda.synchronize()
     prof = binding.csa_profile_read(ctx.ctx)
     binding.csa_profile_enable(ctx.ctx, False)
-    stage_us = {name: (ms / max(n, 1) * 1e3) for name, (ms, n) in prof.items()}
+    # per launch of each kernel (search kernels run on every period-th step only)
+    stage_us = {name: (ms / max(n, 1) * 1e3) for name, (ms, n) in prof.items() if n > 0}
 
     # ---- algorithmic bytes (per step, mean appended count over the timed steps)
     t_mean = w.pre_appended + (K - 1) / 2.0
     per_head = algorithmic_bytes_per_head(w, t_mean)
-    step_bytes = B * Hq * sum(per_head.values())
+    n_search = (K + period - 1) // period
+    step_bytes = B * Hq * ((per_head["centroids"] + per_head["table_rows"]) * n_search / K
+                           + per_head["kv_rows"] + per_head["io"])
     # dominant kernel = the gathered attention: K and V rows, q, the selected indices
     att_bytes = B * Hq * (per_head["kv_rows"] + w.head_dim * 2 + w.k * 4)
     att_us = stage_us["attention_split"]
     achieved = att_bytes / (att_us * 1e-6) / 1e9
     traffic = None
     tf = os.path.join(ROOT, "profiles", f"attention_split_{w.name}_hbm_traffic.txt")
-    if os.path.exists(tf):
+    if os.path.exists(tf) and period == 1 and args.keep_ratio == 0:
         mt = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(tf).read())
         traffic = float(mt.group(1)) if mt else None
     roofline = dict(kernel="k_attention_split", bound="hbm", achieved=round(achieved, 1),
@@ -159,7 +173,8 @@ def main():
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": w.head_dim, "n_pre": w.n_pre, "C": w.C, "L": w.L, "m": w.m,
                    "k": w.k, "pre_appended": w.pre_appended, "page_size": w.page_size,
-                   "sparsity": round(1 - w.k / w.n_pre, 4), "mean_selected": sel_mean},
+                   "sparsity": round(1 - w.k / w.n_pre, 4), "mean_selected": sel_mean,
+                   "search_period": period},
         "tokens_per_s": round(B / (us_per_step * 1e-6), 1),
         "step_algorithmic_bytes": int(step_bytes),
         "step_hbm_gbps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),

@@ -144,6 +144,22 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
 int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
                     int32_t *sel_count_dev, void *stream);
 
+/*
+ * A decode step inside a search period (App. "Schedules evaluation" and the complexity appendix:
+ * with search period P the index set of the last searching step is reused for the next P-1
+ * steps, e.g. the schedules 0.15-step-4 and 0.20-step-8): no centroid scoring, no table access,
+ * no Top-K - step 5 of csa_decode_step over the given index set plus all keys in [n_pre, n),
+ * with the current query.
+ *   sel_idx_dev   int32 [B][Hq][k]  ascending, distinct, each < n_pre, padded with -1 (input)
+ *   sel_count_dev int32 [B][Hq]     entries used per head, <= k                        (input)
+ * Both NULL: the index set written by the last csa_decode_step on this ctx (whether into the
+ * caller's buffers or into the scratch buffer, which must then be untouched since);
+ * CSA_ERR_STATE if there was none since the tables were built.  An unsorted list is not
+ * detected: keys may then be attended twice or not at all (never an invalid address).
+ */
+int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev,
+                          const int32_t *sel_idx_dev, const int32_t *sel_count_dev, void *stream);
+
 /* Host-side counters: prefill length and current context length. */
 int csa_context_len(const csa_ctx *ctx, int32_t *n_pre, int32_t *n);
 /* Rewind / set the context length to n in [n_pre, max_ctx] (rows >= n are simply ignored). */
@@ -161,7 +177,7 @@ int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream);
  * launches into launches[CSA_N_STAGES] (either may be NULL), and clears the record.
  * Events cost a few microseconds per stage: leave disabled when timing whole steps.
  */
-#define CSA_N_STAGES 8
+#define CSA_N_STAGES 9
 int csa_profile_enable(csa_ctx *ctx, int32_t on);
 int csa_profile_read(csa_ctx *ctx, double *ms_sum, int64_t *launches);
 const char *csa_stage_name(int32_t stage); /* NULL if out of range */

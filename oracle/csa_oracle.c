@@ -382,6 +382,25 @@ void oracle_decode_head(const uint16_t *q, const uint16_t *cent, int C, int d,
 }
 
 /*
+ * A decode step inside a search period (App. "Schedules" / complexity appendix: with search
+ * period P the index set found by the last searching step is reused for the next P-1 steps):
+ * no centroid scoring, no table access - exact attention over the given index set plus every
+ * key appended after prefill, rows [n_pre, n), with the current query.
+ *   sel [count]: prefill key indices (any order, distinct), each < n_pre.
+ */
+void oracle_attend_selected(const uint16_t *q, const uint16_t *K, const uint16_t *V,
+                            const int32_t *sel, int count, int64_t n_pre, int64_t n, int d,
+                            float *out)
+{
+    int64_t n_att = count + (n - n_pre);
+    int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_att > 0 ? n_att : 1));
+    for (int a = 0; a < count; ++a) ids[a] = sel[a];
+    for (int64_t i = n_pre; i < n; ++i) ids[count + (i - n_pre)] = (int32_t)i;
+    attention_over(q, K, V, ids, n_att, d, out);
+    free(ids);
+}
+
+/*
  * The same step for a list of independent (sequence, query head) items, spread over
  * `n_threads` OpenMP threads (0 = the runtime's default).  Item t uses q[t], cent[t] (its KV
  * head's centroids), tbl_idx[t] / tbl_score[t] (its KV head's tables) and K[t] / V[t] (its KV

@@ -135,6 +135,16 @@ def decode_head(q, cent, tbl_idx, tbl_score, m, k, K, V, n_pre, n):
     return rows, sel[:k], int(cnt[0]), out
 
 
+def attend_selected(q, K, V, sel, n_pre, n):
+    """Attention of q over the prefill keys listed in `sel` plus the appended keys [n_pre, n)."""
+    d = q.shape[-1]
+    sel = np.ascontiguousarray(sel, np.int32)
+    out = np.empty(d, np.float32)
+    lib().oracle_attend_selected(_p(q), _p(K), _p(V), _p(sel), C.c_int(len(sel)), C.c_int64(n_pre),
+                                 C.c_int64(n), C.c_int(d), _p(out))
+    return out
+
+
 def decode_items(items, m, k, n_pre, n, n_threads=0):
     """items: list of dicts(q [d], cent [C][d], tbl_idx [C][L], tbl_score [C][L], K, V) whose
     arrays stay alive for the call.  Returns (rows [n][m], sel [n][k], cnt [n], out [n][d],

@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("CSATTN_LIB", os.path.join(_HERE, "libcsattn.so"))
 CSA_OK = 0
 CSA_ERR_ARG, CSA_ERR_STATE, CSA_ERR_CAPACITY = -1, -2, -3
 CSA_ERR_WORKSPACE, CSA_ERR_HIP, CSA_ERR_RANGE = -4, -5, -6
-CSA_N_STAGES = 8
+CSA_N_STAGES = 9
 
 
 class csa_config(C.Structure):
@@ -49,6 +49,7 @@ def lib() -> C.CDLL:
         "csa_import_tables": (C.c_int, [vp, vp, vp, vp, i32, vp]),
         "csa_append_kv": (C.c_int, [vp, vp, vp, vp]),
         "csa_decode_step": (C.c_int, [vp, vp, vp, vp, vp, vp]),
+        "csa_decode_step_reuse": (C.c_int, [vp, vp, vp, vp, vp, vp]),
         "csa_context_len": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
         "csa_set_context_len": (C.c_int, [vp, i32]),
         "csa_score_frac_bits": (C.c_int, [vp, C.POINTER(i32)]),
@@ -68,6 +69,7 @@ def lib() -> C.CDLL:
 
 EXPORTED = ("csa_create", "csa_destroy", "csa_workspace_bytes", "csa_bind", "csa_build_tables",
             "csa_export_tables", "csa_import_tables", "csa_append_kv", "csa_decode_step",
+            "csa_decode_step_reuse",
             "csa_context_len", "csa_set_context_len", "csa_score_frac_bits",
             "csa_last_probed_rows", "csa_profile_enable", "csa_profile_read", "csa_stage_name",
             "csa_strerror", "csa_last_hip_error")
@@ -145,6 +147,11 @@ def csa_decode_step(ctx, q, out, sel_idx=None, sel_count=None):
            "csa_decode_step")
 
 
+def csa_decode_step_reuse(ctx, q, out, sel_idx=None, sel_count=None):
+    _check(lib().csa_decode_step_reuse(ctx, _ptr(q), _ptr(out), _ptr(sel_idx), _ptr(sel_count), _stream()),
+           "csa_decode_step_reuse")
+
+
 def csa_context_len(ctx):
     a, b = C.c_int32(), C.c_int32()
     _check(lib().csa_context_len(ctx, C.byref(a), C.byref(b)), "csa_context_len")
@@ -211,6 +218,10 @@ class Context:
     def decode_step(self, q):
         csa_decode_step(self.ctx, q, self.out, self.sel, self.sel_count)
         return self.out, self.sel, self.sel_count
+
+    def decode_step_reuse(self, q, sel=None, sel_count=None):
+        csa_decode_step_reuse(self.ctx, q, self.out, sel, sel_count)
+        return self.out
 
     def append_kv(self, k_new, v_new):
         csa_append_kv(self.ctx, k_new, v_new)

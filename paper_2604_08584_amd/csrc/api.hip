@@ -30,8 +30,9 @@ struct Layout {
     size_t cand_keys = 0;  // candidate slots per head
 };
 
-const char *kStageNames[CSA_N_STAGES] = {"score_centroids", "top_centroids",   "accumulate", "select_threshold",
-                                         "select_emit",     "attention_split", "attention_merge", "append_kv"};
+const char *kStageNames[CSA_N_STAGES] = {"score_centroids", "top_centroids",   "accumulate",      "select_threshold",
+                                         "select_emit",     "attention_split", "attention_merge", "append_kv",
+                                         "range_offsets"};
 using csa::kUnit;
 
 }  // namespace
@@ -51,9 +52,11 @@ struct csa_ctx {
     // profiling
     bool prof = false;
     struct Rec {
-        hipEvent_t ev[CSA_N_STAGES + 1];
-        bool used[CSA_N_STAGES + 1];
+        hipEvent_t ev[CSA_N_STAGES + 1];  // stage i runs between ev[i] and ev[i + 1]
+        bool done[CSA_N_STAGES];          // both events of stage i were recorded in this call
     };
+    // the index set of the last searching step (reused by csa_decode_step_reuse)
+    const int32_t *last_sel = nullptr, *last_sel_count = nullptr;
     std::vector<Rec> recs;
     size_t n_recs = 0;
 };
@@ -194,14 +197,20 @@ struct Prof {
             ctx->recs.push_back(r);
         }
         rec = &ctx->recs[ctx->n_recs++];
-        for (auto &u : rec->used) u = false;
+        for (auto &u : rec->done) u = false;
     }
     // mark the boundary before stage `i` (and after stage i-1)
     void mark(int i)
     {
         if (!rec) return;
         (void)hipEventRecord(rec->ev[i], st);
-        rec->used[i] = true;
+    }
+    // mark the end of stage `i` (= the boundary before stage i+1)
+    void end(int i)
+    {
+        if (!rec) return;
+        (void)hipEventRecord(rec->ev[i + 1], st);
+        rec->done[i] = true;
     }
 };
 
@@ -255,6 +264,7 @@ int csa_bind(csa_ctx *ctx, void *tables_dev, size_t tables_bytes, void *scratch_
     ctx->k_cache = k_cache_dev;
     ctx->v_cache = v_cache_dev;
     ctx->block_table = block_table_dev;
+    ctx->last_sel = ctx->last_sel_count = nullptr;
     ctx->bound = true;
     return CSA_OK;
 }
@@ -268,6 +278,7 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
     hipStream_t st = (hipStream_t)stream;
     const Layout &l = ctx->lay;
     ctx->have_tables = false;
+    ctx->last_sel = ctx->last_sel_count = nullptr;
     int32_t *flags = at<int32_t>(ctx->scratch, l.flags);
     hipError_t e = hipMemsetAsync(flags, 0, 256, st);
     if (e != hipSuccess) return hip_fail(ctx, e);
@@ -329,6 +340,7 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
     hipStream_t st = (hipStream_t)stream;
     const Layout &l = ctx->lay;
     ctx->have_tables = false;
+    ctx->last_sel = ctx->last_sel_count = nullptr;
     int32_t *flags = at<int32_t>(ctx->scratch, l.flags);
     hipError_t e = hipMemsetAsync(flags, 0, 256, st);
     if (e != hipSuccess) return hip_fail(ctx, e);
@@ -380,7 +392,7 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
     prof.mark(7);
     csa::launch_append(ctx->k_cache, ctx->v_cache, ctx->block_table, k_new_dev, v_new_dev,
                        ctx->cfg.batch, ctx->cfg.n_kv_heads, ctx->n, ctx->cfg.max_ctx, st);
-    prof.mark(8);
+    prof.end(7);
     ctx->n += 1;
     return check_launch(ctx);
 }
@@ -410,28 +422,60 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     prof.mark(0);
     csa::launch_score_centroids(q_dev, at<void>(ctx->tables, l.cent_t), z, c.batch, c.n_kv_heads, G,
                                 c.n_centroids, st);
-    prof.mark(1);
+    prof.end(0);
     int32_t *spans = at<int32_t>(ctx->scratch, l.spans);
     uint32_t *hist = at<uint32_t>(ctx->scratch, l.hist);
     csa::launch_top_centroids(z, rows, at<int32_t>(ctx->tables, l.part_off), spans, hist, BH,
                               c.n_centroids, c.n_probe, G, ctx->P, ctx->nsub, ctx->PO, st);
-    prof.mark(2);
+    prof.end(1);
     csa::launch_accumulate(at<void>(ctx->tables, l.ent), rows, spans, cand_key, cand_bits, cand_cnt, hist, BH,
                            c.n_centroids, l.Ls, c.n_probe, G, ctx->R, ctx->P, l.cand_keys, ctx->key_lo,
                            ctx->key_sh, st);
-    prof.mark(3);
+    prof.end(2);
     csa::launch_threshold(cand_key, cand_cnt, sel, sel_count, thr, seg_par, hist, BH, c.budget_k, ctx->R,
                           ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, st);
-    prof.mark(4);
+    prof.end(3);
     csa::launch_emit(cand_key, cand_bits, cand_cnt, thr, seg_par, sel, BH, c.budget_k, ctx->R, ctx->P,
                      l.cand_keys, st);
+    prof.end(4);
+    csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, seg_par,
+                                part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ctx->n_pre, ctx->n,
+                                c.max_ctx, S, ctx->P, st);
+    prof.end(5);
+    csa::launch_attention_merge(part, out_dev, BH, S, st);
+    prof.end(6);
+    ctx->last_sel = sel;
+    ctx->last_sel_count = sel_count;
+    return check_launch(ctx);
+}
+
+int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *sel_idx_dev,
+                          const int32_t *sel_count_dev, void *stream)
+{
+    if (!ctx || !q_dev || !out_dev) return CSA_ERR_ARG;
+    if ((sel_idx_dev == nullptr) != (sel_count_dev == nullptr)) return CSA_ERR_ARG;
+    if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
+    const int32_t *sel = sel_idx_dev ? sel_idx_dev : ctx->last_sel;
+    const int32_t *sel_count = sel_count_dev ? sel_count_dev : ctx->last_sel_count;
+    if (!sel || !sel_count) return CSA_ERR_STATE;  // no searching step yet
+    const csa_config &c = ctx->cfg;
+    const Layout &l = ctx->lay;
+    hipStream_t st = (hipStream_t)stream;
+    const int BH = c.batch * c.n_q_heads;
+    void *seg_par = at<void>(ctx->scratch, l.seg_par);
+    float *part = at<float>(ctx->scratch, l.part);
+    const int S = csa::attention_splits(c.budget_k, ctx->P, ctx->n - ctx->n_pre);
+    Prof prof(ctx, st);
+    prof.mark(8);
+    csa::launch_range_offsets(sel, sel_count, seg_par, BH, c.budget_k, ctx->R, ctx->P, st);
+    prof.end(8);
     prof.mark(5);
     csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, seg_par,
                                 part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ctx->n_pre, ctx->n,
                                 c.max_ctx, S, ctx->P, st);
-    prof.mark(6);
+    prof.end(5);
     csa::launch_attention_merge(part, out_dev, BH, S, st);
-    prof.mark(7);
+    prof.end(6);
     return check_launch(ctx);
 }
 
@@ -484,7 +528,7 @@ int csa_profile_read(csa_ctx *ctx, double *ms_sum, int64_t *launches)
     for (size_t r = 0; r < ctx->n_recs; ++r) {
         csa_ctx::Rec &rec = ctx->recs[r];
         for (int i = 0; i < CSA_N_STAGES; ++i) {
-            if (!rec.used[i] || !rec.used[i + 1]) continue;
+            if (!rec.done[i]) continue;
             hipError_t e = hipEventSynchronize(rec.ev[i + 1]);
             float ms = 0.0f;
             if (e == hipSuccess) e = hipEventElapsedTime(&ms, rec.ev[i], rec.ev[i + 1]);

@@ -195,6 +195,34 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
     }
 }
 
+// Where the key ranges start in an ascending index list (a search-period step reuses an index set
+// instead of searching, so the per-range output offsets of the Top-K kernels do not exist):
+// seg_par[head][p].x = number of listed indices below p*R.  One thread per range, binary search.
+// grid B*Hq, block 256.
+__global__ void k_range_offsets(const int32_t *__restrict__ sel, const int32_t *__restrict__ sel_count,
+                                int2 *__restrict__ seg_par, int k, int R, int P)
+{
+    const int head = blockIdx.x;
+    const int n_sel = max(0, min(sel_count[head], k));
+    const int32_t *list = sel + (size_t)head * k;
+    for (int p = threadIdx.x; p < P; p += blockDim.x) {
+        const int64_t bound = (int64_t)p * R;
+        int lo = 0, hi = n_sel;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (list[mid] < bound) lo = mid + 1; else hi = mid;
+        }
+        seg_par[(size_t)head * P + p] = make_int2(lo, 0);
+    }
+}
+
+void launch_range_offsets(const int32_t *sel, const int32_t *sel_count, void *seg_par, int n_heads, int k,
+                          int R, int P, hipStream_t st)
+{
+    if (k <= 0) return;
+    k_range_offsets<<<n_heads, 256, 0, st>>>(sel, sel_count, (int2 *)seg_par, k, R, P);
+}
+
 // Merge of the S split partials of a head (a separate launch: publishing partials to a "last
 // workgroup" inside the split kernel needs device-scope fences in every workgroup, which cost far
 // more on this multi-die part than one small launch).

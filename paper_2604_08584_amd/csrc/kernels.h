@@ -53,6 +53,8 @@ void launch_attention_split(const void *q, const void *kc, const void *vc,
                             const int32_t *sel_count, const void *seg_par, float *part, int B, int Hq,
                             int Hkv, int k, int n_pre, int n, int max_ctx, int S, int P,
                             hipStream_t st);
+void launch_range_offsets(const int32_t *sel, const int32_t *sel_count, void *seg_par, int n_heads, int k,
+                          int R, int P, hipStream_t st);
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st);
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
                    int B, int Hkv, int n, int max_ctx, hipStream_t st);

@@ -126,6 +126,32 @@ class Case:
         return worst
 
 
+    def check_reuse_step(self, step, sel, cnt, heads=None, pass_buffers=False):
+        """A search-period step: attention of step `step`'s query over the index set (sel, cnt) of
+        an earlier searching step plus everything appended so far; compared with the oracle."""
+        w = self.w
+        if heads is None:
+            heads = [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
+        q = self.inp["q_steps"][step]
+        if pass_buffers:
+            out = self.ctx.decode_step_reuse(q, torch.from_numpy(sel).cuda(), torch.from_numpy(cnt).cuda())
+        else:
+            out = self.ctx.decode_step_reuse(q)
+        torch.cuda.synchronize()
+        out = out.cpu().numpy()
+        qh = oracle.bf16_bits(q)
+        n = w.n_pre + self.t
+        worst = 0.0
+        for b, h in heads:
+            g = h // w.group
+            want = oracle.attend_selected(np.ascontiguousarray(qh[b, h]), self.K_host[b, g], self.V_host[b, g],
+                                          sel[b, h][:cnt[b, h]], w.n_pre, n)
+            err = float(np.abs(out[b, h] - want).max())
+            assert np.isfinite(out[b, h]).all() and err <= TOL_OUT, f"{w.name} reuse step {step} head ({b},{h}): {err}"
+            worst = max(worst, err)
+        return worst
+
+
 def small(name="small", **kw) -> Workload:
     base = dict(name=name, batch=1, n_q_heads=4, n_kv_heads=1, head_dim=128, n_pre=3000, n_comp=16,
                 C=48, L=200, m=5, k=150, steps=2, pre_appended=0, page_size=0, kmeans_iters=3)

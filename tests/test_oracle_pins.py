@@ -398,6 +398,27 @@ def test_decode_output_is_a_convex_combination_of_attended_values():
     np.testing.assert_allclose(out, softmax_attention_np(q, K, V, ids), atol=1e-6)
 
 
+def test_reuse_step_attends_the_given_set_plus_appended_keys():
+    """A step inside a search period (complexity appendix: the index set is reused for P-1 steps):
+    with every prefill key listed it is dense attention; the order of the list is irrelevant; one
+    listed key and nothing appended returns that key's value row; an index at or beyond n_pre that
+    is not appended yet never enters (catches attending [0, n) instead of sel + [n_pre, n))."""
+    rng = np.random.default_rng(21)
+    d, n_pre, n = 128, 300, 307
+    q, K, V = rand_bf16(rng, d), rand_bf16(rng, (n + 5, d)), rand_bf16(rng, (n + 5, d))
+    full = oracle.attend_selected(q, K, V, np.arange(n_pre), n_pre, n)
+    np.testing.assert_allclose(full, oracle.dense_attention(q, K, V, n), atol=1e-6)
+    sel = rng.choice(n_pre, 40, replace=False).astype(np.int32)
+    a = oracle.attend_selected(q, K, V, np.sort(sel), n_pre, n)
+    b = oracle.attend_selected(q, K, V, sel, n_pre, n)
+    np.testing.assert_allclose(a, b, atol=1e-6)
+    np.testing.assert_allclose(a, softmax_attention_np(q, K, V, np.r_[sel, np.arange(n_pre, n)]), atol=1e-6)
+    one = oracle.attend_selected(q, K, V, np.array([17], np.int32), n_pre, n_pre)
+    assert np.array_equal(one, f32(V[17]))
+    none = oracle.attend_selected(q, K, V, np.zeros(0, np.int32), n_pre, n_pre)
+    assert np.all(none == 0)
+
+
 def test_single_cluster_recall_is_one():
     """Query-centric argument of Sec. 2.4: if every prefill query is a positive multiple of one
     direction u and the decode query is too, one centroid (= u) with L >= k retrieves exactly

@@ -171,6 +171,34 @@ def test_paged_cache_matches_contiguous_and_oracle():
         case.append(1)
 
 
+@pytest.mark.parametrize("paged", [False, True])
+def test_search_period_steps_reuse_the_index_set(paged):
+    """Schedule with search period 4: step 0 searches, steps 1-3 reuse its index set for their own
+    queries while keys keep being appended (they are always attended), step 4 searches again.
+    Both ways of naming the index set (the library's own copy / caller's buffers) are checked."""
+    w = small("period", batch=2, n_q_heads=8, n_kv_heads=2, n_pre=6000, C=40, L=300, m=6, k=500,
+              steps=6, page_size=16 if paged else 0)
+    case = Case(w, seed=12, F=12, partition_keys=2048)
+    case.import_oracle_tables()
+    with pytest.raises(binding.CsaError) as e:          # nothing to reuse yet
+        case.ctx.decode_step_reuse(case.inp["q_steps"][0])
+    assert e.value.status == binding.CSA_ERR_STATE
+    case.check_step(0)
+    _, sel, cnt, _ = case.decode(0)
+    for step in (1, 2, 3):
+        case.append(1)
+        case.check_reuse_step(step, sel, cnt, pass_buffers=(step == 2))
+    case.append(1)
+    case.check_step(4)
+    # a caller-made ascending list (not a search result) is attended as given
+    mine = np.full_like(sel, -1)
+    mine[..., :7] = np.array([0, 5, 2047, 2048, 4095, 4096, 5999], np.int32)
+    mcnt = np.full_like(cnt, 7)
+    case.check_reuse_step(5, mine, mcnt, pass_buffers=True)
+    # an empty list leaves the appended keys only
+    case.check_reuse_step(5, mine, np.zeros_like(cnt), pass_buffers=True)
+
+
 def test_repeated_steps_are_deterministic():
     w = small("det", n_q_heads=8, n_kv_heads=2, steps=1, pre_appended=9)
     case = Case(w, seed=9, F=12, partition_keys=1024)
