@@ -8,10 +8,13 @@
  * Every function cites the passage of the paper (arXiv 2604.08584) it follows.  Where the
  * paper leaves a choice open the reading taken is stated at the function.
  *
- * Geometry implemented: one subspace spanning the whole head dimension, the `m` best
- * centroids probed per query (the paper's centroid back-off of Sec. 4.4 with tau = m and a
- * single subspace).  Everything after centroid choice (Sec. 3.3 steps 2-4) is independent of
- * how the probed rows were chosen.
+ * Geometry implemented: the head dimension is cut uniformly into S subspaces of d/S dimensions
+ * (Sec. 3.1 (i)); each subspace has its own C centroids and its own C table rows; a query
+ * probes the tau best centroids of every subspace (Sec. 3.3 (1) for tau = 1, the centroid
+ * back-off of Sec. 4.4 for tau > 1), M = S * tau rows in all.  S = 1 is the single-subspace
+ * geometry of the benchmark configurations; S = 8, tau = 1 is the paper's default.  Row r of a
+ * KV head's table belongs to subspace r / C and centroid r % C.  Everything after centroid
+ * choice (Sec. 3.3 steps 2-4) is independent of how the probed rows were chosen.
  *
  * Precision: the three places where floating point decides an integer are taken in fp32 with
  * a fixed operation order, so that any implementation can reproduce them bit for bit:
@@ -247,28 +250,31 @@ void oracle_round_bf16(const float *x, int64_t n, uint16_t *out)
 /* ---------------------------------------------------------------- offline: table rows */
 
 /*
- * Sec. 3.2 (2): s_j(i) = c_j . k_i for every prefill key i (raw keys, unit centroids, as the
- * equation is written), keep the Top-L pairs, stored sorted by score (Sec. 3.1 (iii)).
- * Ties go to the lower key index.  Scores are rounded to the grid 2^-F before the ranking.
- * Rows shorter than L (n_pre < L) are padded with idx = -1, score = 0.
- *   K        [n_pre][d] bf16     cent [C][d] bf16
- *   row_ids  [n_rows]  which centroids to build (any subset, any order)
+ * Sec. 3.2 (2): s_j^(b)(i) = c_j^(b) . k_i^(b) for every prefill key i (raw key sub-vectors, unit
+ * centroids, as the equation is written), keep the Top-L pairs, stored sorted by score
+ * (Sec. 3.1 (iii)).  Ties go to the lower key index.  Scores are rounded to the grid 2^-F before
+ * the ranking.  Rows shorter than L (n_pre < L) are padded with idx = -1, score = 0.
+ *   K        [n_pre][d] bf16
+ *   cent     [S][C][d/S] bf16 (S = n_sub subspaces, dimensions [b*d/S, (b+1)*d/S) of the head)
+ *   row_ids  [n_rows]  which rows to build (row = b*C + j; any subset, any order)
  *   idx_out / score_out [n_rows][L]
  * Returns the largest |q| = |round(s * 2^F)| seen, as a double (for the exactness check
- * m * max|q| < 2^24).
+ * M * max|q| < 2^24).
  */
-double oracle_build_rows(const uint16_t *K, int64_t n_pre, int d, const uint16_t *cent,
-                         const int32_t *row_ids, int n_rows, int L, int F,
+double oracle_build_rows(const uint16_t *K, int64_t n_pre, int d, int n_sub, int C,
+                         const uint16_t *cent, const int32_t *row_ids, int n_rows, int L, int F,
                          int32_t *idx_out, float *score_out)
 {
     double max_abs_q = 0.0;
     const float up = ldexpf(1.0f, F), down = ldexpf(1.0f, -F);
+    const int db = d / n_sub;
 #pragma omp parallel for schedule(dynamic) reduction(max : max_abs_q)
     for (int r = 0; r < n_rows; ++r) {
         pair_t *all = (pair_t *)malloc(sizeof(pair_t) * (size_t)(n_pre > 0 ? n_pre : 1));
-        const uint16_t *c = cent + (int64_t)row_ids[r] * d;
+        const int b = row_ids[r] / C;
+        const uint16_t *c = cent + (int64_t)row_ids[r] * db;
         for (int64_t i = 0; i < n_pre; ++i) {
-            float s = dot_chain_bf16(c, K + i * d, d);
+            float s = dot_chain_bf16(c, K + i * d + (int64_t)b * db, db);
             float qf = rintf(s * up); /* default rounding mode: half to even */
             if (fabs((double)qf) > max_abs_q) max_abs_q = fabs((double)qf);
             all[i].score = qf * down;
@@ -292,20 +298,26 @@ double oracle_build_rows(const uint16_t *K, int64_t n_pre, int d, const uint16_t
 /* ---------------------------------------------------------------- online: decode */
 
 /*
- * Sec. 3.3 step 1 with the back-off of Sec. 4.4: z_j = q . c_j, the m largest, ties to the
- * lower j.  q is not normalised: a positive factor cannot change the ranking.
+ * Sec. 3.3 step 1 with the back-off of Sec. 4.4: in every subspace b, z_j = q^(b) . c_j^(b), the
+ * tau largest, ties to the lower j.  q is not normalised: a positive factor per subspace cannot
+ * change that subspace's ranking.
+ *   cent [S][C][d/S]; rows_out [S*tau]: subspace-major, best first, as table rows b*C + j;
+ *   z_out [S][C] or NULL.
  */
-void oracle_top_centroids(const uint16_t *q, const uint16_t *cent, int C, int d, int m,
-                          int32_t *rows_out, float *z_out /* [C] or NULL */)
+void oracle_top_centroids(const uint16_t *q, const uint16_t *cent, int n_sub, int C, int d, int tau,
+                          int32_t *rows_out, float *z_out)
 {
+    const int db = d / n_sub;
     pair_t *z = (pair_t *)malloc(sizeof(pair_t) * (size_t)C);
-    for (int j = 0; j < C; ++j) {
-        z[j].score = dot_chain_bf16(q, cent + (int64_t)j * d, d);
-        z[j].idx = j;
-        if (z_out) z_out[j] = z[j].score;
+    for (int b = 0; b < n_sub; ++b) {
+        for (int j = 0; j < C; ++j) {
+            z[j].score = dot_chain_bf16(q + b * db, cent + ((int64_t)b * C + j) * db, db);
+            z[j].idx = j;
+            if (z_out) z_out[(int64_t)b * C + j] = z[j].score;
+        }
+        qsort(z, (size_t)C, sizeof(pair_t), cmp_score_desc_idx_asc);
+        for (int r = 0; r < tau; ++r) rows_out[b * tau + r] = r < C ? b * C + z[r].idx : -1;
     }
-    qsort(z, (size_t)C, sizeof(pair_t), cmp_score_desc_idx_asc);
-    for (int r = 0; r < m; ++r) rows_out[r] = r < C ? z[r].idx : -1;
     free(z);
 }
 
@@ -363,15 +375,16 @@ int64_t oracle_select_keys(const int32_t *tbl_idx, const float *tbl_score, int L
  * One decode step for one query head: Sec. 3.3 steps 1-4 followed by exact attention over
  * the selected keys plus every key appended after prefill, rows [n_pre, n) (the recent
  * window: always attended, never competing for the k slots).
- *   q [d], cent [C][d], K / V [>= n][d] bf16; tables [C][L].
- *   rows_out [m], sel_out [k] (ascending, -1 padded), sel_count [1], out [d] fp32.
+ *   q [d], cent [S][C][d/S], K / V [>= n][d] bf16; tables [S*C][L]; tau probes per subspace.
+ *   rows_out [S*tau], sel_out [k] (ascending, -1 padded), sel_count [1], out [d] fp32.
  */
-void oracle_decode_head(const uint16_t *q, const uint16_t *cent, int C, int d,
-                        const int32_t *tbl_idx, const float *tbl_score, int L, int m, int k,
+void oracle_decode_head(const uint16_t *q, const uint16_t *cent, int n_sub, int C, int d,
+                        const int32_t *tbl_idx, const float *tbl_score, int L, int tau, int k,
                         const uint16_t *K, const uint16_t *V, int64_t n_pre, int64_t n,
                         int32_t *rows_out, int32_t *sel_out, int32_t *sel_count, float *out)
 {
-    oracle_top_centroids(q, cent, C, d, m, rows_out, NULL);
+    const int m = n_sub * tau;
+    oracle_top_centroids(q, cent, n_sub, C, d, tau, rows_out, NULL);
     oracle_select_keys(tbl_idx, tbl_score, L, rows_out, m, n_pre, k, sel_out, sel_count, NULL);
     int64_t n_att = *sel_count + (n - n_pre);
     int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_att > 0 ? n_att : 1));
@@ -404,16 +417,17 @@ void oracle_attend_selected(const uint16_t *q, const uint16_t *K, const uint16_t
  * The same step for a list of independent (sequence, query head) items, spread over
  * `n_threads` OpenMP threads (0 = the runtime's default).  Item t uses q[t], cent[t] (its KV
  * head's centroids), tbl_idx[t] / tbl_score[t] (its KV head's tables) and K[t] / V[t] (its KV
- * head's cache); outputs are packed [n_items][m], [n_items][k], [n_items], [n_items][d].
+ * head's cache); outputs are packed [n_items][S*tau], [n_items][k], [n_items], [n_items][d].
  * Returns the number of threads used.
  */
 int oracle_decode_items(int n_items, const uint16_t *const *q, const uint16_t *const *cent,
                         const int32_t *const *tbl_idx, const float *const *tbl_score,
-                        const uint16_t *const *K, const uint16_t *const *V, int C, int d, int L,
-                        int m, int k, int64_t n_pre, int64_t n, int32_t *rows_out,
+                        const uint16_t *const *K, const uint16_t *const *V, int n_sub, int C, int d,
+                        int L, int tau, int k, int64_t n_pre, int64_t n, int32_t *rows_out,
                         int32_t *sel_out, int32_t *sel_count, float *out, int n_threads)
 {
     int used = 1;
+    const int m = n_sub * tau;
 #ifdef _OPENMP
     if (n_threads > 0) omp_set_num_threads(n_threads);
 #pragma omp parallel
@@ -424,8 +438,8 @@ int oracle_decode_items(int n_items, const uint16_t *const *q, const uint16_t *c
 #endif
 #pragma omp parallel for schedule(dynamic)
     for (int t = 0; t < n_items; ++t)
-        oracle_decode_head(q[t], cent[t], C, d, tbl_idx[t], tbl_score[t], L, m, k, K[t], V[t],
-                           n_pre, n, rows_out + (int64_t)t * m, sel_out + (int64_t)t * k,
+        oracle_decode_head(q[t], cent[t], n_sub, C, d, tbl_idx[t], tbl_score[t], L, tau, k, K[t],
+                           V[t], n_pre, n, rows_out + (int64_t)t * m, sel_out + (int64_t)t * k,
                            sel_count + t, out + (int64_t)t * d);
     return used;
 }

@@ -82,29 +82,39 @@ def round_bf16(x):
     return out
 
 
+def _geometry(cent):
+    """cent: [C][d] (one subspace) or [S][C][d/S].  Returns (cent as given, S, C, d)."""
+    if cent.ndim == 2:
+        return 1, cent.shape[0], cent.shape[1]
+    return cent.shape[0], cent.shape[1], cent.shape[0] * cent.shape[2]
+
+
 def build_rows(K, n_pre, cent, row_ids, L, F):
-    """Rows `row_ids` of one KV head's table.  Returns (idx [r][L] i32, score [r][L] f32,
-    max|q|)."""
-    d = K.shape[-1]
+    """Rows `row_ids` (row = subspace * C + centroid) of one KV head's table; cent [C][d] or
+    [S][C][d/S].  Returns (idx [r][L] i32, score [r][L] f32, max|q|)."""
+    S, n_c, d = _geometry(cent)
+    assert K.shape[-1] == d
     row_ids = np.ascontiguousarray(row_ids, np.int32)
     idx = np.empty((len(row_ids), L), np.int32)
     score = np.empty((len(row_ids), L), np.float32)
-    mx = lib().oracle_build_rows(_p(K), C.c_int64(n_pre), C.c_int(d), _p(cent), _p(row_ids),
-                                 C.c_int(len(row_ids)), C.c_int(L), C.c_int(F), _p(idx),
+    mx = lib().oracle_build_rows(_p(K), C.c_int64(n_pre), C.c_int(d), C.c_int(S), C.c_int(n_c), _p(cent),
+                                 _p(row_ids), C.c_int(len(row_ids)), C.c_int(L), C.c_int(F), _p(idx),
                                  _p(score))
     return idx, score, mx
 
 
 def build_tables(K, n_pre, cent, L, F):
-    return build_rows(K, n_pre, cent, np.arange(cent.shape[0], dtype=np.int32), L, F)
+    S, n_c, _ = _geometry(cent)
+    return build_rows(K, n_pre, cent, np.arange(S * n_c, dtype=np.int32), L, F)
 
 
-def top_centroids(q, cent, m):
-    n_c, d = cent.shape
-    rows = np.empty(m, np.int32)
-    z = np.empty(n_c, np.float32)
-    lib().oracle_top_centroids(_p(q), _p(cent), C.c_int(n_c), C.c_int(d), C.c_int(m), _p(rows),
-                               _p(z))
+def top_centroids(q, cent, tau):
+    """The tau best centroids of every subspace as table rows [S*tau], and z [S*C]."""
+    S, n_c, d = _geometry(cent)
+    rows = np.empty(S * tau, np.int32)
+    z = np.empty(S * n_c, np.float32)
+    lib().oracle_top_centroids(_p(q), _p(cent), C.c_int(S), C.c_int(n_c), C.c_int(d), C.c_int(tau),
+                               _p(rows), _p(z))
     return rows, z
 
 
@@ -121,16 +131,16 @@ def select_keys(tbl_idx, tbl_score, rows, n_pre, k):
     return sel[:k], int(cnt[0]), int(nU), acc[:n_pre]
 
 
-def decode_head(q, cent, tbl_idx, tbl_score, m, k, K, V, n_pre, n):
-    """One query head.  Returns (rows [m], sel [k], count, out [d])."""
-    n_c, d = cent.shape
+def decode_head(q, cent, tbl_idx, tbl_score, tau, k, K, V, n_pre, n):
+    """One query head, tau probes per subspace.  Returns (rows [S*tau], sel [k], count, out [d])."""
+    S, n_c, d = _geometry(cent)
     L = tbl_idx.shape[-1]
-    rows = np.empty(m, np.int32)
+    rows = np.empty(S * tau, np.int32)
     sel = np.empty(max(k, 1), np.int32)
     cnt = np.zeros(1, np.int32)
     out = np.empty(d, np.float32)
-    lib().oracle_decode_head(_p(q), _p(cent), C.c_int(n_c), C.c_int(d), _p(tbl_idx),
-                             _p(tbl_score), C.c_int(L), C.c_int(m), C.c_int(k), _p(K), _p(V),
+    lib().oracle_decode_head(_p(q), _p(cent), C.c_int(S), C.c_int(n_c), C.c_int(d), _p(tbl_idx),
+                             _p(tbl_score), C.c_int(L), C.c_int(tau), C.c_int(k), _p(K), _p(V),
                              C.c_int64(n_pre), C.c_int64(n), _p(rows), _p(sel), _p(cnt), _p(out))
     return rows, sel[:k], int(cnt[0]), out
 
@@ -145,23 +155,23 @@ def attend_selected(q, K, V, sel, n_pre, n):
     return out
 
 
-def decode_items(items, m, k, n_pre, n, n_threads=0):
-    """items: list of dicts(q [d], cent [C][d], tbl_idx [C][L], tbl_score [C][L], K, V) whose
-    arrays stay alive for the call.  Returns (rows [n][m], sel [n][k], cnt [n], out [n][d],
-    threads_used)."""
+def decode_items(items, tau, k, n_pre, n, n_threads=0):
+    """items: list of dicts(q [d], cent [C][d] or [S][C][d/S], tbl_idx [S*C][L], tbl_score, K, V)
+    whose arrays stay alive for the call.  Returns (rows [n][S*tau], sel [n][k], cnt [n],
+    out [n][d], threads_used)."""
     n_it = len(items)
-    n_c, d = items[0]["cent"].shape
+    S, n_c, d = _geometry(items[0]["cent"])
     L = items[0]["tbl_idx"].shape[-1]
     arr = lambda key: (C.c_void_p * n_it)(*[it[key].ctypes.data for it in items])
     for it in items:
         for key in ("q", "cent", "tbl_idx", "tbl_score", "K", "V"):
             assert it[key].flags["C_CONTIGUOUS"]
-    rows = np.empty((n_it, m), np.int32)
+    rows = np.empty((n_it, S * tau), np.int32)
     sel = np.empty((n_it, max(k, 1)), np.int32)
     cnt = np.zeros(n_it, np.int32)
     out = np.empty((n_it, d), np.float32)
     used = lib().oracle_decode_items(
         C.c_int(n_it), arr("q"), arr("cent"), arr("tbl_idx"), arr("tbl_score"), arr("K"),
-        arr("V"), C.c_int(n_c), C.c_int(d), C.c_int(L), C.c_int(m), C.c_int(k),
+        arr("V"), C.c_int(S), C.c_int(n_c), C.c_int(d), C.c_int(L), C.c_int(tau), C.c_int(k),
         C.c_int64(n_pre), C.c_int64(n), _p(rows), _p(sel), _p(cnt), _p(out), C.c_int(n_threads))
     return rows, sel[:, :k], cnt, out, used

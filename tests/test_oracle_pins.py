@@ -190,6 +190,107 @@ def test_query_scale_does_not_change_the_ranking():
     assert np.array_equal(r1, r2)
 
 
+# ------------------------------------------------------------------ subspaces (Sec. 3.1, 3.3 (1))
+
+def test_subspace_scores_are_partial_inner_products_of_the_matching_slices():
+    """S = 4: z^(b)_j must be the fma chain over dimensions [32b, 32b+32) of q against centroid
+    (b, j) - pinned with the exact-rational emulation - and the subspace partials of one vector
+    add up to the full inner product (Sec. 3.1).  Catches a wrong slice offset or stride."""
+    rng = np.random.default_rng(30)
+    S, n_c, d = 4, 5, 128
+    db = d // S
+    q = rand_bf16(rng, d, 3.0)
+    cent = rand_bf16(rng, (S, n_c, db), 3.0)
+    _, z = oracle.top_centroids(q, cent, 1)
+    z = z.reshape(S, n_c)
+    for b in range(S):
+        ref = np.array([fma_chain_exact(q[b * db:(b + 1) * db], cent[b, j]) for j in range(n_c)], np.float32)
+        assert np.array_equal(z[b].view(np.uint32), ref.view(np.uint32))
+    # decomposition: a "centroid" made of the slices of one vector c gives sum_b z^(b) = q . c
+    c_full = rand_bf16(rng, d, 3.0)
+    _, zc = oracle.top_centroids(q, np.ascontiguousarray(c_full.reshape(S, 1, db)), 1)
+    full = float(f32(q).astype(np.float64) @ f32(c_full).astype(np.float64))
+    assert float(zc.astype(np.float64).sum()) == pytest.approx(full, rel=1e-5, abs=1e-4)
+
+
+def test_subspace_probes_are_the_best_tau_of_every_subspace():
+    """Small-integer data (exact products, many ties): rows = for every subspace the tau best
+    centroids by (score desc, j asc), as table rows b*C + j, subspace-major."""
+    rng = np.random.default_rng(31)
+    S, n_c, d = 8, 12, 128
+    db = d // S
+    qv = rng.integers(-2, 3, d).astype(np.float32)
+    cv = rng.integers(-1, 2, (S, n_c, db)).astype(np.float32)
+    cv[2, 5] = cv[2, 1]; cv[2, 9] = cv[2, 1]           # exact ties inside a subspace
+    for tau in (1, 2, 3, n_c):
+        rows, _ = oracle.top_centroids(to_bits(qv), to_bits(cv), tau)
+        want = []
+        for b in range(S):
+            zi = cv[b].astype(np.int64) @ qv[b * db:(b + 1) * db].astype(np.int64)
+            want += [b * n_c + j for j in sorted(range(n_c), key=lambda j: (-zi[j], j))[:tau]]
+        assert list(rows) == want
+
+
+def test_subspace_rows_score_the_matching_key_slice():
+    """Keys that vanish outside subspace 2: every row of another subspace scores 0 for every key
+    (its Top-L is then the L lowest indices), and row (2, j) is the sorted Top-L of
+    c^(2)_j . k^(2)_i.  Catches scoring a key slice against the wrong subspace's centroid."""
+    rng = np.random.default_rng(32)
+    S, n_c, d, n, L, F = 4, 3, 128, 200, 16, 2
+    db = d // S
+    Kv = np.zeros((n, d), np.float32)
+    Kv[:, 2 * db:3 * db] = rng.integers(-3, 4, (n, db))
+    cv = rng.integers(-2, 3, (S, n_c, db)).astype(np.float32)
+    idx, score, _ = oracle.build_tables(to_bits(Kv), n, to_bits(cv), L, F)
+    for b in range(S):
+        for j in range(n_c):
+            r = b * n_c + j
+            if b != 2:
+                assert idx[r].tolist() == list(range(L)) and np.all(score[r] == 0)
+            else:
+                sc = Kv[:, 2 * db:3 * db].astype(np.int64) @ cv[2, j].astype(np.int64)
+                order = sorted(range(n), key=lambda i: (-sc[i], i))[:L]
+                assert idx[r].tolist() == order
+                assert np.array_equal(score[r], sc[order].astype(np.float32))
+
+
+@pytest.mark.parametrize("S", [2, 8, 16])
+def test_subspace_sums_retrieve_the_true_top_k_when_centroids_equal_the_query(S):
+    """Sec. 3.1 / App. C.2: q.k = sum_b q^(b).k^(b).  With one centroid per subspace equal to the
+    query's own slice, every key in every row (L = N) and integer data (all products exact, on any
+    grid), the accumulated score of key i IS q.k_i, so the selection must be the brute-force
+    Top-k of q.K with ties to the lower index."""
+    rng = np.random.default_rng(33 + S)
+    d, n, k, F = 128, 150, 20, 1
+    db = d // S
+    qv = rng.integers(-2, 3, d).astype(np.float32)
+    Kv = rng.integers(-2, 3, (n, d)).astype(np.float32)
+    Kv[40] = Kv[7]; Kv[90] = Kv[7]                       # exact score ties
+    cent = to_bits(np.ascontiguousarray(qv.reshape(S, 1, db)))
+    K, V = to_bits(Kv), rand_bf16(rng, (n, d))
+    idx, score, _ = oracle.build_tables(K, n, cent, n, F)
+    rows, sel, cnt, out = oracle.decode_head(to_bits(qv), cent, idx, score, 1, k, K, V, n, n)
+    assert list(rows) == list(range(S))
+    full = Kv.astype(np.int64) @ qv.astype(np.int64)
+    want = sorted(sorted(range(n), key=lambda i: (-full[i], i))[:k])
+    assert cnt == k and sel.tolist() == want
+    np.testing.assert_allclose(out, softmax_attention_np(to_bits(qv), K, V, np.array(want)), atol=1e-6)
+
+
+def test_one_subspace_given_as_3d_equals_the_2d_form():
+    rng = np.random.default_rng(34)
+    d, n, n_c, L = 128, 120, 6, 24
+    q, cent = rand_bf16(rng, d), rand_bf16(rng, (n_c, d), 0.1)
+    K, V = rand_bf16(rng, (n, d)), rand_bf16(rng, (n, d))
+    i2, s2, _ = oracle.build_tables(K, n, cent, L, 10)
+    i3, s3, _ = oracle.build_tables(K, n, cent.reshape(1, n_c, d), L, 10)
+    assert np.array_equal(i2, i3) and np.array_equal(s2, s3)
+    a = oracle.decode_head(q, cent, i2, s2, 3, 30, K, V, n, n)
+    b = oracle.decode_head(q, cent.reshape(1, n_c, d), i2, s2, 3, 30, K, V, n, n)
+    for x, y in zip(a, b):
+        assert np.array_equal(np.asarray(x), np.asarray(y))
+
+
 # ------------------------------------------------------------------ offline rows (Sec. 3.2 (2))
 
 def test_build_rows_single_centroid_is_the_sorted_top_L():
