@@ -33,7 +33,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="cfg4", help="cfg1..cfg4 of BASELINE.json")
+    ap.add_argument("--config", default="cfg4",
+                    help="cfg1..cfg4 of BASELINE.json, or paper_s8 (the paper's default geometry)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--partition-keys", type=int, default=0)
     ap.add_argument("--kmeans-sample", type=int, default=0,
@@ -85,7 +86,7 @@ def main():
     ctx = binding.Context(k_store, v_store, bt, batch=B, n_q_heads=Hq, n_kv_heads=Hkv,
                           n_centroids=w.C, list_len=w.L, n_probe=w.m, budget_k=w.k,
                           max_ctx=w.max_ctx, page_size=w.page_size, score_frac_bits=-1,
-                          partition_keys=args.partition_keys)
+                          partition_keys=args.partition_keys, n_subspaces=w.n_sub)
     t0 = time.time()
     ctx.build_tables(inp["centroids"], w.n_pre)
     torch.cuda.synchronize()
@@ -171,7 +172,7 @@ def main():
         "dtype": "bf16 K/V/q/centroids, int32 table scores, fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
-                   "head_dim": w.head_dim, "n_pre": w.n_pre, "C": w.C, "L": w.L, "m": w.m,
+                   "head_dim": w.head_dim, "n_pre": w.n_pre, "subspaces": w.n_sub, "C": w.C, "L": w.L, "m": w.m,
                    "k": w.k, "pre_appended": w.pre_appended, "page_size": w.page_size,
                    "sparsity": round(1 - w.k / w.n_pre, 4), "mean_selected": sel_mean,
                    "search_period": period},

@@ -4,8 +4,12 @@
  * The library implements, as hand-written HIP kernels, the per-token decode step of
  * Centroid-Scoring Attention (arXiv 2604.08584, Sec. 3.3 and App. A "All-GPU"), the offline
  * construction of its lookup tables (Sec. 3.2) and the append of new keys/values (Sec. 3.3 (5),
- * first sentence).  Geometry: one subspace spanning the whole head dimension and the
- * `n_probe` best centroids per query, i.e. the centroid back-off of Sec. 4.4 with tau = n_probe.
+ * first sentence).  Geometry (Sec. 3.1 (i)): the head dimension is cut uniformly into
+ * S = n_subspaces subspaces, each with its own C centroids and C table rows; a query probes the
+ * tau = n_probe best centroids of every subspace (Sec. 3.3 (1) for tau = 1, the centroid back-off
+ * of Sec. 4.4 for tau > 1), M = S * tau rows in all.  S = 8, tau = 1 is the paper's default;
+ * S = 1 is a single subspace spanning the whole head dimension.  Table row r of a KV head belongs
+ * to subspace r / C and centroid r % C.
  *
  * Conventions
  *   - Every pointer named *_dev is DEVICE memory owned by the caller; the library never
@@ -14,8 +18,8 @@
  *     work on it and return without synchronising unless stated otherwise.
  *   - All calls return CSA_OK (0) or a negative csa_status; nothing aborts or throws.
  *   - B = batch, Hq = n_q_heads, Hkv = n_kv_heads, G = Hq/Hkv, d = head_dim (128),
- *     C = n_centroids, L = list_len, m = n_probe, k = budget_k.  Query head h belongs to
- *     KV head h / G.  All sequences of the batch share n_pre and n.
+ *     S = n_subspaces, C = n_centroids, L = list_len, tau = n_probe, M = S * tau, k = budget_k.
+ *     Query head h belongs to KV head h / G.  All sequences of the batch share n_pre and n.
  *   - bf16 = the upper 16 bits of an IEEE fp32.  Inputs must be finite.
  *   - A ctx is not thread-safe; calls on one ctx must be issued from one thread at a time and
  *     on streams that are ordered with respect to each other.
@@ -47,11 +51,12 @@ typedef struct {
     int32_t n_q_heads;   /* Hq, multiple of n_kv_heads, G = Hq/Hkv in {1,2,4,8,16} */
     int32_t n_kv_heads;  /* Hkv >= 1 */
     int32_t head_dim;    /* d, must be 128 */
-    int32_t n_centroids; /* C >= 1: query-centric centroids per KV head (Sec. 3.2 (1)) */
+    int32_t n_centroids; /* C >= 1: query-centric centroids per KV head and subspace (Sec. 3.2 (1)) */
     int32_t list_len;    /* L in [1, 8192]: Top-L capacity per centroid (Sec. 3.1 (iii)) */
-    int32_t n_probe;     /* m in [1, min(C, 63)]: centroids probed per query (Sec. 3.3 (1), 4.4) */
+    int32_t n_probe;     /* tau in [1, C], S * tau <= 63: centroids probed per subspace
+                            (Sec. 3.3 (1), 4.4) */
     int32_t budget_k;    /* k >= 0: keys kept by Top-K (Sec. 3.3 (4)) */
-    int32_t n_subspaces; /* must be 1 */
+    int32_t n_subspaces; /* S in {1, 2, 4, 8, 16}: uniform split, 128 / S dimensions each */
     int32_t max_ctx;     /* capacity (rows) of the caller's K/V storage per sequence;
                             multiple of page_size when paged; <= 2^24 */
     int32_t page_size;   /* 0: contiguous K/V [B][Hkv][max_ctx][d];
@@ -66,7 +71,7 @@ typedef struct {
  * Score grid (decides which keys are kept, so it is part of the interface): a table score s is
  * stored as the integer q = round-half-even(s * 2^F); the accumulated score of a key
  * (Sec. 3.3 (3), w_b = 1) is the exact integer sum of its q over the probed rows.  The library
- * requires n_probe * max|q| < 2^24, so the same sums are also exact in fp32 in any order, and
+ * requires M * max|q| < 2^24, so the same sums are also exact in fp32 in any order, and
  * max|q| < 2^18 (a table entry is kept in 32 bits on the device: 19 bits of q, 13 index bits).
  */
 
@@ -94,24 +99,25 @@ int csa_bind(csa_ctx *ctx, void *tables_dev, size_t tables_bytes, void *scratch_
              const int32_t *block_table_dev);
 
 /*
- * Offline table construction, Sec. 3.2 (2): for every KV head and centroid j,
- * s_j(i) = c_j . k_i over the prefill keys i < n_pre (raw keys), rounded to the score grid, and
- * the L best (score desc, index asc) kept.  Scores are computed in fp32 as one
- * fused-multiply-add chain over ascending dimension starting from +0, bf16 inputs widened.
- *   centroids_dev: bf16 [B][Hkv][C][d], unit norm (Sec. 3.2 (1); clustering is the caller's).
+ * Offline table construction, Sec. 3.2 (2): for every KV head, subspace b and centroid j,
+ * s_j(i) = c_j^(b) . k_i^(b) over the prefill keys i < n_pre (raw key sub-vectors), rounded to the
+ * score grid, and the L best (score desc, index asc) kept.  Scores are computed in fp32 as one
+ * fused-multiply-add chain over the subspace's dimensions in ascending order starting from +0,
+ * bf16 inputs widened.
+ *   centroids_dev: bf16 [B][Hkv][S][C][d/S], unit norm (Sec. 3.2 (1); clustering is the caller's).
  * K is read from the bound cache, rows [0, n_pre).  Sets the context length to n_pre.
  * SYNCHRONISES `stream` before returning (it reads back an overflow flag); returns
- * CSA_ERR_RANGE if some |q| * n_probe >= 2^24 or |q| >= 2^18 (tables are then unusable).
+ * CSA_ERR_RANGE if some |q| * M >= 2^24 or |q| >= 2^18 (tables are then unusable).
  */
 int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, void *stream);
 
 /*
  * Tables in the canonical layout, one KV head at a time or all at once:
- *   idx   int32 [C][L], score fp32 [C][L]; each row sorted by (score desc, idx asc)
+ *   idx   int32 [S*C][L], score fp32 [S*C][L]; each row sorted by (score desc, idx asc)
  *   (Sec. 3.1 (iii) "sorted by score"); unused tail slots idx = -1, score = 0.
  * csa_export_tables writes the rows of KV head (b, g) to device buffers.
- * csa_import_tables reads centroids bf16 [B][Hkv][C][d] and canonical tables
- *   idx [B][Hkv][C][L], score [B][Hkv][C][L] (device), and makes them the ctx's tables; it
+ * csa_import_tables reads centroids bf16 [B][Hkv][S][C][d/S] and canonical tables
+ *   idx [B][Hkv][S*C][L], score [B][Hkv][S*C][L] (device), and makes them the ctx's tables; it
  *   needs score_frac_bits >= 0, SYNCHRONISES `stream`, and returns CSA_ERR_RANGE if a score is
  *   off the grid or too large, CSA_ERR_ARG if an index is outside [-1, n_pre).
  */
@@ -131,8 +137,9 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
 
 /*
  * One decode step for every (sequence, query head), Sec. 3.3 (1)-(4) + App. A:
- *   1. z_j = q . c_j (fp32 fma chain as above); the m largest, ties to the lower j;
- *   2. the m table rows are read;
+ *   1. in every subspace b, z_j = q^(b) . c_j^(b) (fp32 fma chain as above); the tau largest, ties
+ *      to the lower j;
+ *   2. the M = S * tau table rows are read;
  *   3. scores are summed per key index; U = keys present in at least one probed row;
  *   4. the min(k, |U|) keys of U with the largest sum, ties to the lower index;
  *   5. out = softmax(q K_A^T / sqrt(d)) V_A over A = selected keys + all keys in [n_pre, n)
@@ -166,8 +173,9 @@ int csa_context_len(const csa_ctx *ctx, int32_t *n_pre, int32_t *n);
 int csa_set_context_len(csa_ctx *ctx, int32_t n);
 /* The grid exponent F in use (valid after build/import). */
 int csa_score_frac_bits(const csa_ctx *ctx, int32_t *frac_bits);
-/* Copies the centroid rows probed by the last csa_decode_step, int32 [B][Hq][m] (order within a
- * head unspecified), into a device buffer.  Diagnostic for step 1. */
+/* Copies the table rows (b * C + j) probed by the last csa_decode_step, int32 [B][Hq][S*tau]
+ * (subspace-major; order within a subspace unspecified), into a device buffer.  Diagnostic for
+ * step 1. */
 int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream);
 
 /*

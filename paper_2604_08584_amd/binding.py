@@ -209,7 +209,7 @@ class Context:
         csa_import_tables(self.ctx, centroids, idx, score, n_pre)
 
     def export_tables(self, b, g):
-        C_, L = self.cfg["n_centroids"], self.cfg["list_len"]
+        C_, L = self.cfg["n_centroids"] * self.cfg.get("n_subspaces", 1), self.cfg["list_len"]
         idx = torch.empty(C_, L, dtype=torch.int32, device=self.out.device)
         score = torch.empty(C_, L, dtype=torch.float32, device=self.out.device)
         csa_export_tables(self.ctx, b, g, idx, score)
@@ -227,7 +227,8 @@ class Context:
         csa_append_kv(self.ctx, k_new, v_new)
 
     def probed_rows(self):
-        rows = torch.empty(self.cfg["batch"], self.cfg["n_q_heads"], self.cfg["n_probe"],
+        rows = torch.empty(self.cfg["batch"], self.cfg["n_q_heads"],
+                           self.cfg["n_probe"] * self.cfg.get("n_subspaces", 1),
                            dtype=torch.int32, device=self.out.device)
         csa_last_probed_rows(self.ctx, rows)
         return rows

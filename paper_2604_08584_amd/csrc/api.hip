@@ -69,6 +69,8 @@ Layout make_layout(const csa_config &c)
 {
     Layout l;
     const size_t BG = (size_t)c.batch * c.n_kv_heads, BH = (size_t)c.batch * c.n_q_heads;
+    const size_t Ct = (size_t)c.n_subspaces * c.n_centroids;  // table rows per KV head
+    const size_t M = (size_t)c.n_subspaces * c.n_probe;       // rows probed per query
     l.P_max = (c.max_ctx + min_R(c) - 1) / min_R(c);
     const int q_min = min_R(c) < kUnit ? min_R(c) : kUnit;
     l.PO_max = (c.max_ctx + q_min - 1) / q_min + 5;  // >= P * nsub + 1 for every admissible R
@@ -80,15 +82,15 @@ Layout make_layout(const csa_config &c)
         off = align_up(off + bytes);
     };
     put(l.cent_t, BG * c.n_centroids * c.head_dim * 2);
-    put(l.ent, BG * c.n_centroids * (size_t)l.Ls * 4);
-    put(l.part_off, BG * c.n_centroids * (size_t)l.PO_max * 4);
+    put(l.ent, BG * Ct * (size_t)l.Ls * 4);
+    put(l.part_off, BG * Ct * (size_t)l.PO_max * 4);
     l.tables_bytes = off;
     off = 0;
     l.cand_keys = ((size_t)c.max_ctx + 16383) / 16384 * 16384;
     l.S_max = csa::attention_splits(c.budget_k, l.P_max, c.max_ctx);
-    put(l.z, BH * c.n_centroids * 4);
-    put(l.rows, BH * c.n_probe * 4);
-    put(l.spans, BH * (size_t)c.n_probe * 2 * l.PO_max * 4);  // P * (nsub + 1) <= 2 * PO offsets per row
+    put(l.z, BH * Ct * 4);
+    put(l.rows, BH * M * 4);
+    put(l.spans, BH * M * 2 * l.PO_max * 4);  // P * (nsub + 1) <= 2 * PO offsets per row
     put(l.cand, BH * l.cand_keys * 4);       // candidate keys, R slots per (head, key range)
     put(l.cand_bits, BH * l.cand_keys / 8);  // presence bitmap over the key indices
     put(l.cand_cnt, BH * (size_t)l.P_max * 4);  // candidates per (head, key range)
@@ -114,9 +116,11 @@ int validate(const csa_config &c)
     if (!(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) return CSA_ERR_ARG;
     if (c.head_dim != 128) return CSA_ERR_ARG;
     if (c.n_centroids < 1 || c.list_len < 1 || c.list_len > 8192) return CSA_ERR_ARG;
-    if (c.n_probe < 1 || c.n_probe > 63 || c.n_probe > c.n_centroids) return CSA_ERR_ARG;
+    const int S = c.n_subspaces;
+    if (!(S == 1 || S == 2 || S == 4 || S == 8 || S == 16)) return CSA_ERR_ARG;
+    if (c.n_probe < 1 || c.n_probe > c.n_centroids || (int64_t)S * c.n_probe > 63) return CSA_ERR_ARG;
     if (c.budget_k < 0) return CSA_ERR_ARG;
-    if (c.n_subspaces != 1) return CSA_ERR_ARG;
+    if ((int64_t)S * c.n_centroids > (1 << 24)) return CSA_ERR_ARG;
     if (c.max_ctx < 1 || c.max_ctx > (1 << 24)) return CSA_ERR_ARG;
     if (c.page_size != 0 && c.page_size != 16) return CSA_ERR_ARG;
     if (c.page_size && c.max_ctx % c.page_size) return CSA_ERR_ARG;
@@ -125,6 +129,7 @@ int validate(const csa_config &c)
         (!is_pow2(c.partition_keys) || c.partition_keys < 1024 || c.partition_keys > 16384))
         return CSA_ERR_ARG;
     if ((int64_t)c.batch * c.n_q_heads > 65535) return CSA_ERR_ARG;  // grid.y
+    if ((int64_t)c.batch * c.n_kv_heads > 65535) return CSA_ERR_ARG;  // grid.z
     return CSA_OK;
 }
 
@@ -177,7 +182,7 @@ int qmax_for(int m)
 // m * max|q| of 2^24: 512 equal bins over that span.
 void set_key_range(csa_ctx *ctx, int qabs_max)
 {
-    const uint32_t span = (uint32_t)ctx->cfg.n_probe * (uint32_t)qabs_max;  // < 2^24
+    const uint32_t span = (uint32_t)(ctx->cfg.n_probe * ctx->cfg.n_subspaces) * (uint32_t)qabs_max;  // < 2^24
     ctx->key_lo = (1u << 24) - span;
     int sh = 0;
     while (((2u * span) >> sh) >= 512u) ++sh;
@@ -288,34 +293,37 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
         // finest grid with n_probe * (max|s| * 2^F + 1/2) < 2^24, |s| <= ||c|| ||k|| and
         // ||c|| <= 1.01 for unit centroids rounded to bf16
         csa::launch_max_key_norm(ctx->k_cache, ctx->block_table, (float *)(flags + 16), c.batch,
-                                 c.n_kv_heads, c.max_ctx, n_pre, st);
+                                 c.n_kv_heads, c.max_ctx, n_pre, c.n_subspaces, st);
         float nn = 0.0f;
         e = hipMemcpyAsync(&nn, flags + 16, 4, hipMemcpyDeviceToHost, st);
         if (e == hipSuccess) e = hipStreamSynchronize(st);
         if (e != hipSuccess) return hip_fail(ctx, e);
         const double bound = 1.01 * std::sqrt((double)nn) + 1e-30;
-        F = (int)std::floor(std::log2(((double)qmax_for(c.n_probe) - 1.0) / bound));
+        F = (int)std::floor(std::log2(((double)qmax_for(c.n_probe * c.n_subspaces) - 1.0) / bound));
         if (F > 30) F = 30;
         if (F < 0) return CSA_ERR_RANGE;
     }
     choose_partition(ctx, n_pre);
     if (ctx->PO > l.PO_max || ctx->P > l.P_max) return CSA_ERR_WORKSPACE;  // (cannot happen: see make_layout)
     const int BG = c.batch * c.n_kv_heads;
-    csa::launch_pack_centroids(centroids_dev, at<void>(ctx->tables, l.cent_t), BG, c.n_centroids, st);
+    const int S = c.n_subspaces, db = c.head_dim / S, M = S * c.n_probe;
+    csa::launch_pack_centroids(centroids_dev, at<void>(ctx->tables, l.cent_t), BG, c.n_centroids, S, st);
     int32_t *qs = at<int32_t>(ctx->scratch, l.qs);
     char *ent = at<char>(ctx->tables, l.ent);
     int32_t *part_off = at<int32_t>(ctx->tables, l.part_off);
+    const uint16_t *cent = (const uint16_t *)centroids_dev;
     for (int b = 0; b < c.batch; ++b)
         for (int g = 0; g < c.n_kv_heads; ++g)
-            for (int j0 = 0; j0 < c.n_centroids; j0 += kBuildChunk) {
-                const int jc = c.n_centroids - j0 < kBuildChunk ? c.n_centroids - j0 : kBuildChunk;
-                csa::launch_build_scores(ctx->k_cache, ctx->block_table, centroids_dev, qs, flags, b, g,
-                                         c.n_kv_heads, c.max_ctx, n_pre, c.n_centroids, j0, jc, F,
-                                         qmax_for(c.n_probe), st);
-                const size_t row0 = ((size_t)(b * c.n_kv_heads + g) * c.n_centroids + j0);
-                csa::launch_build_select(qs, ent + row0 * l.Ls * 4, part_off + row0 * ctx->PO, jc, n_pre,
-                                         c.list_len, l.Ls, ctx->Q, ctx->PO, st);
-            }
+            for (int sub = 0; sub < S; ++sub)
+                for (int j0 = 0; j0 < c.n_centroids; j0 += kBuildChunk) {
+                    const int jc = c.n_centroids - j0 < kBuildChunk ? c.n_centroids - j0 : kBuildChunk;
+                    // table row of centroid (sub, j0) of KV head (b, g); its centroid vector
+                    const size_t row0 = ((size_t)(b * c.n_kv_heads + g) * S + sub) * c.n_centroids + j0;
+                    csa::launch_build_scores(ctx->k_cache, ctx->block_table, cent + row0 * db, qs, flags, b, g,
+                                             c.n_kv_heads, c.max_ctx, n_pre, S, sub, jc, F, qmax_for(M), st);
+                    csa::launch_build_select(qs, ent + row0 * l.Ls * 4, part_off + row0 * ctx->PO, jc, n_pre,
+                                             c.list_len, l.Ls, ctx->Q, ctx->PO, st);
+                }
     int rc = check_launch(ctx);
     if (rc != CSA_OK) return rc;
     int32_t hflags[2] = {0, 0};
@@ -347,11 +355,12 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
     choose_partition(ctx, n_pre);
     if (ctx->PO > l.PO_max || ctx->P > l.P_max) return CSA_ERR_WORKSPACE;  // (cannot happen: see make_layout)
     const int BG = c.batch * c.n_kv_heads;
-    const int64_t n_rows = (int64_t)BG * c.n_centroids;
-    csa::launch_pack_centroids(centroids_dev, at<void>(ctx->tables, l.cent_t), BG, c.n_centroids, st);
+    const int64_t n_rows = (int64_t)BG * c.n_subspaces * c.n_centroids;
+    csa::launch_pack_centroids(centroids_dev, at<void>(ctx->tables, l.cent_t), BG, c.n_centroids,
+                               c.n_subspaces, st);
     csa::launch_import_rows(idx_dev, score_dev, at<void>(ctx->tables, l.ent), at<int32_t>(ctx->tables, l.part_off),
-                            flags, n_rows, c.list_len, l.Ls, n_pre, c.score_frac_bits, qmax_for(c.n_probe),
-                            ctx->Q, ctx->PO, st);
+                            flags, n_rows, c.list_len, l.Ls, n_pre, c.score_frac_bits,
+                            qmax_for(c.n_probe * c.n_subspaces), ctx->Q, ctx->PO, st);
     int rc = check_launch(ctx);
     if (rc != CSA_OK) return rc;
     int32_t hflags[2] = {0, 0};
@@ -374,10 +383,11 @@ int csa_export_tables(const csa_ctx *ctx, int32_t b, int32_t g, int32_t *idx_dev
     if (!ctx->have_tables) return CSA_ERR_STATE;
     const csa_config &c = ctx->cfg;
     if (b < 0 || b >= c.batch || g < 0 || g >= c.n_kv_heads) return CSA_ERR_ARG;
-    const size_t row0 = (size_t)(b * c.n_kv_heads + g) * c.n_centroids;
+    const int Ct = c.n_subspaces * c.n_centroids;
+    const size_t row0 = (size_t)(b * c.n_kv_heads + g) * Ct;
     const int32_t *part_off = reinterpret_cast<const int32_t *>(ctx->tables + ctx->lay.part_off.off);
     csa::launch_export_rows(ctx->tables + ctx->lay.ent.off + row0 * ctx->lay.Ls * 4, part_off + row0 * ctx->PO,
-                            idx_dev, score_dev, c.n_centroids, c.list_len, ctx->lay.Ls, ctx->F, ctx->Q,
+                            idx_dev, score_dev, Ct, c.list_len, ctx->lay.Ls, ctx->F, ctx->Q,
                             ctx->PO, (hipStream_t)stream);
     return check_launch(const_cast<csa_ctx *>(ctx));
 }
@@ -406,6 +416,7 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     const Layout &l = ctx->lay;
     hipStream_t st = (hipStream_t)stream;
     const int BH = c.batch * c.n_q_heads, G = c.n_q_heads / c.n_kv_heads;
+    const int S_sub = c.n_subspaces, Ct = S_sub * c.n_centroids, M = S_sub * c.n_probe;
     float *z = at<float>(ctx->scratch, l.z);
     int32_t *rows = at<int32_t>(ctx->scratch, l.rows);
     uint32_t *cand_key = at<uint32_t>(ctx->scratch, l.cand);
@@ -421,16 +432,15 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     Prof prof(ctx, st);
     prof.mark(0);
     csa::launch_score_centroids(q_dev, at<void>(ctx->tables, l.cent_t), z, c.batch, c.n_kv_heads, G,
-                                c.n_centroids, st);
+                                c.n_centroids, S_sub, st);
     prof.end(0);
     int32_t *spans = at<int32_t>(ctx->scratch, l.spans);
     uint32_t *hist = at<uint32_t>(ctx->scratch, l.hist);
     csa::launch_top_centroids(z, rows, at<int32_t>(ctx->tables, l.part_off), spans, hist, BH,
-                              c.n_centroids, c.n_probe, G, ctx->P, ctx->nsub, ctx->PO, st);
+                              c.n_centroids, S_sub, c.n_probe, G, ctx->P, ctx->nsub, ctx->PO, st);
     prof.end(1);
     csa::launch_accumulate(at<void>(ctx->tables, l.ent), rows, spans, cand_key, cand_bits, cand_cnt, hist, BH,
-                           c.n_centroids, l.Ls, c.n_probe, G, ctx->R, ctx->P, l.cand_keys, ctx->key_lo,
-                           ctx->key_sh, st);
+                           Ct, l.Ls, M, G, ctx->R, ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, st);
     prof.end(2);
     csa::launch_threshold(cand_key, cand_cnt, sel, sel_count, thr, seg_par, hist, BH, c.budget_k, ctx->R,
                           ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, st);
@@ -509,7 +519,7 @@ int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream)
 {
     if (!ctx || !rows_dev) return CSA_ERR_ARG;
     if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
-    const size_t bytes = (size_t)ctx->cfg.batch * ctx->cfg.n_q_heads * ctx->cfg.n_probe * 4;
+    const size_t bytes = (size_t)ctx->cfg.batch * ctx->cfg.n_q_heads * ctx->cfg.n_probe * ctx->cfg.n_subspaces * 4;
     const hipError_t e = hipMemcpyAsync(rows_dev, ctx->scratch + ctx->lay.rows.off, bytes,
                                         hipMemcpyDeviceToDevice, (hipStream_t)stream);
     return e == hipSuccess ? CSA_OK : hip_fail(const_cast<csa_ctx *>(ctx), e);

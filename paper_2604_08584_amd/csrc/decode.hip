@@ -54,32 +54,96 @@ __global__ __launch_bounds__(256) void k_score_centroids(const uint16_t *__restr
     }
 }
 
-void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
-                            int C, hipStream_t st)
+// The same for S > 1 subspaces of db = 128/S dimensions (Sec. 3.1 (i), 3.3 (1)): lane j of block
+// (x, s, bg) scores centroid (s, j) against dimensions [s*db, (s+1)*db) of the G queries.
+// cent_t is [bg][S][db/8][C][8]; z is [b][h][S][C].
+// grid (ceil(C/256), S, B*Hkv), block 256.
+template <int GH>
+__global__ __launch_bounds__(256) void k_score_centroids_sub(const uint16_t *__restrict__ q,
+                                                             const uint4 *__restrict__ cent_t,
+                                                             float *__restrict__ z, int C, int G, int S)
 {
-    dim3 grid((C + 255) / 256, B * Hkv), block(256);
+    __shared__ float s_q[GH][kHeadDim / 2];
+    const int sub = blockIdx.y, bg = blockIdx.z;
+    const int db = kHeadDim / S, nch = db / 8;  // nch <= 8
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const uint4 *ct = cent_t + ((size_t)bg * S + sub) * nch * C;
+    uint4 wv[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) wv[c] = (c < nch && j < C) ? ct[(size_t)c * C + j] : make_uint4(0, 0, 0, 0);
+    for (int h0 = 0; h0 < G; h0 += GH) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < GH * db; e += 256) {
+            const int hh = e / db, t = e % db;
+            s_q[hh][t] = __uint_as_float((uint32_t)q[((size_t)bg * G + h0 + hh) * kHeadDim + sub * db + t] << 16);
+        }
+        __syncthreads();
+        if (j < C) {
+            float acc[GH];
+#pragma unroll
+            for (int hh = 0; hh < GH; ++hh) acc[hh] = 0.0f;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                if (c < nch) {
+                    const uint4 w = wv[c];
+                    const float cf[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                                         bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+#pragma unroll
+                        for (int hh = 0; hh < GH; ++hh)
+                            acc[hh] = __builtin_fmaf(s_q[hh][c * 8 + e], cf[e], acc[hh]);
+                }
+            }
+#pragma unroll
+            for (int hh = 0; hh < GH; ++hh)
+                z[(((size_t)bg * G + h0 + hh) * S + sub) * C + j] = acc[hh] + 0.0f;  // -0 -> +0
+        }
+    }
+}
+
+void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
+                            int C, int S, hipStream_t st)
+{
+    dim3 block(256);
+    if (S == 1) {
+        dim3 grid((C + 255) / 256, B * Hkv);
+        if (G % 8 == 0)
+            k_score_centroids<8><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
+        else if (G % 4 == 0)
+            k_score_centroids<4><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
+        else if (G % 2 == 0)
+            k_score_centroids<2><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
+        else
+            k_score_centroids<1><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
+        return;
+    }
+    dim3 grid((C + 255) / 256, S, B * Hkv);
     if (G % 8 == 0)
-        k_score_centroids<8><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
+        k_score_centroids_sub<8><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, S);
     else if (G % 4 == 0)
-        k_score_centroids<4><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
+        k_score_centroids_sub<4><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, S);
     else if (G % 2 == 0)
-        k_score_centroids<2><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
+        k_score_centroids_sub<2><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, S);
     else
-        k_score_centroids<1><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
+        k_score_centroids_sub<1><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, S);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 1b: the m centroids with the largest z, ties to the lower index (Sec. 3.3 (1) with the
-// top-tau back-off of Sec. 4.4), on the order-preserving integer image of z.
+// Step 1b: in one subspace of one head, the m = tau centroids with the largest z, ties to the
+// lower index (Sec. 3.3 (1) with the top-tau back-off of Sec. 4.4), on the order-preserving
+// integer image of z; they become table rows sub*C + j, slots [sub*tau, (sub+1)*tau) of the head's
+// M = S*tau probed rows.
 // Fast path (m small against C): every thread takes the maximum of its own slice; the m-th
 // largest of the 256 thread maxima is a lower bound on the m-th largest overall, so only the few
 // values >= that bound are candidates; they are ranked against each other by (z desc, j asc) and
 // ranks < m are written in rank order.  If there are too many candidates (many equal values) a
-// radix threshold search with an ordered tie pick does the job instead.
+// radix threshold search with an ordered tie pick does the job instead.  With C <= 256 every
+// thread holds one value and simply counts the values that beat it.
 // Also clears the head's coarse score histogram and looks up, for every key range p, the
 // nsub + 1 offsets that cut the slice of each probed row into its blocks, so that the
 // accumulation kernel starts with one coalesced read.
-// grid B*Hq, block 256.
+// grid B*Hq*S, block 256.
 // ---------------------------------------------------------------------------------------------
 constexpr int kTopNT = 256;
 constexpr int kCoarseBins = 512;  // per-head histogram of accumulated scores, filled by k_accumulate
@@ -91,8 +155,10 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
                                                           const int32_t *__restrict__ part_off,
                                                           int32_t *__restrict__ spans,
                                                           uint32_t *__restrict__ hist_g, int C,
-                                                          int m, int G, int P, int nsub, int PO)
+                                                          int S, int m, int G, int P, int nsub, int PO)
 {
+    const int head = blockIdx.x / S, sub = blockIdx.x - head * S;
+    const int M = S * m;
     __shared__ int32_t s_rows[64];
     __shared__ __align__(16) uint32_t s_hist[256 + kTopNT / kWave + 4];
     __shared__ int s_scan[kTopNT / kWave + 1];
@@ -100,9 +166,10 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
     __shared__ int s_slot;
     __shared__ uint32_t s_bound;
     const float *zh = z + (size_t)blockIdx.x * C;
-    int32_t *out = rows + (size_t)blockIdx.x * m;
+    int32_t *out = rows + (size_t)head * M + sub * m;
     if (threadIdx.x == 0) s_slot = 0;
-    for (int i = threadIdx.x; i < kCoarseBins; i += kTopNT) hist_g[(size_t)blockIdx.x * kCoarseBins + i] = 0;
+    if (sub == 0)
+        for (int i = threadIdx.x; i < kCoarseBins; i += kTopNT) hist_g[(size_t)head * kCoarseBins + i] = 0;
     const bool in_regs = C <= kTopNT * kTopReg;
     uint32_t kreg[kTopReg];
     if (in_regs) {
@@ -129,6 +196,23 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
             }
         }
     };
+    if (C <= kTopNT) {
+        // ---- few centroids: one value per thread, rank = number of values that beat it
+        const uint64_t mine = threadIdx.x < C ? (((uint64_t)kreg[0] << 32) | (uint32_t)~threadIdx.x) : 0ull;
+        s_ck[threadIdx.x] = mine;  // (key << 32) | ~j: larger = better, distinct; 0 beats nothing
+        __syncthreads();
+        if ((int)threadIdx.x < C) {
+            const ulonglong2 *c2 = (const ulonglong2 *)s_ck;
+            int r = 0;
+#pragma unroll 4
+            for (int t2 = 0; t2 < kTopNT / 2; ++t2) {
+                const ulonglong2 o = c2[t2];
+                r += (o.x > mine) + (o.y > mine);
+            }
+            if (r < m) s_rows[r] = (int32_t)threadIdx.x;
+        }
+        goto publish;
+    }
     if (m <= kTopNT / 4 && C >= kTopNT) {  // every lane holds at least one value
         // ---- fast path
         uint32_t best = 0;  // orderable(z) of a finite z is never 0
@@ -209,22 +293,24 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
 publish:
     // the probed rows, and for every key range p the nsub + 1 block offsets of each probed row
     __syncthreads();
-    if (threadIdx.x < m) out[threadIdx.x] = s_rows[threadIdx.x];
-    const int bg = blockIdx.x / G;
+    if ((int)threadIdx.x < m) out[threadIdx.x] = sub * C + s_rows[threadIdx.x];
+    const int bg = head / G;
     const int nb = nsub + 1;
-    int32_t *sp = spans + (size_t)blockIdx.x * P * m * nb;
+    int32_t *sp = spans + (size_t)head * P * M * nb;
     for (int t = threadIdx.x; t < P * m * nb; t += kTopNT) {
-        const int s = t % nb, pr = t / nb;
+        const int x = t % nb, pr = t / nb;
         const int p = pr / m, r = pr - p * m;
-        sp[t] = part_off[((size_t)bg * C + s_rows[r]) * PO + p * nsub + s];
+        sp[((size_t)p * M + sub * m + r) * nb + x] =
+            part_off[((size_t)bg * S * C + (size_t)sub * C + s_rows[r]) * PO + p * nsub + x];
     }
 }
 
 void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, int32_t *spans,
-                          uint32_t *hist_g, int n_heads, int C, int m, int G, int P, int nsub, int PO,
-                          hipStream_t st)
+                          uint32_t *hist_g, int n_heads, int C, int S, int tau, int G, int P, int nsub,
+                          int PO, hipStream_t st)
 {
-    k_top_centroids<<<n_heads, kTopNT, 0, st>>>(z, rows, part_off, spans, hist_g, C, m, G, P, nsub, PO);
+    k_top_centroids<<<n_heads * S, kTopNT, 0, st>>>(z, rows, part_off, spans, hist_g, C, S, tau, G, P, nsub,
+                                                    PO);
 }
 
 // ---------------------------------------------------------------------------------------------

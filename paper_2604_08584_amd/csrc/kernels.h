@@ -15,26 +15,26 @@ constexpr int kQBits = 32 - kUnitBits;
 constexpr int32_t kQLimit = (1 << (kQBits - 1)) - 1;  // |q| <= kQLimit
 
 // ---- tables.hip
-void launch_pack_centroids(const void *cent, void *cent_t, int n_bg, int C, hipStream_t st);
+void launch_pack_centroids(const void *cent, void *cent_t, int n_bg, int C, int S, hipStream_t st);
 void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32_t *part_off,
                         int32_t *flags, int64_t n_rows, int L, int Ls, int n_pre, int F, int qmax,
                         int Q, int PO, hipStream_t st);
 void launch_export_rows(const void *ent, const int32_t *part_off, int32_t *idx, float *score,
                         int n_rows, int L, int Ls, int F, int Q, int PO, hipStream_t st);
 void launch_build_scores(const void *kc, const int32_t *block_table, const void *cent, int32_t *qs,
-                         int32_t *flags, int b, int g, int Hkv, int max_ctx, int n_pre, int C,
-                         int j0, int jc, int F, int qmax, hipStream_t st);
+                         int32_t *flags, int b, int g, int Hkv, int max_ctx, int n_pre, int S, int sub,
+                         int jc, int F, int qmax, hipStream_t st);
 void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc, int n_pre, int L,
                          int Ls, int Q, int PO, hipStream_t st);
 void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
-                         int max_ctx, int n_pre, hipStream_t st);
+                         int max_ctx, int n_pre, int S, hipStream_t st);
 
 // ---- decode.hip
 void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
-                            int C, hipStream_t st);
+                            int C, int S, hipStream_t st);
 void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, int32_t *spans,
-                          uint32_t *hist_g, int n_heads, int C, int m, int G, int P, int nsub, int PO,
-                          hipStream_t st);
+                          uint32_t *hist_g, int n_heads, int C, int S, int tau, int G, int P, int nsub,
+                          int PO, hipStream_t st);
 void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *spans, uint32_t *cand_key,
                        uint32_t *cand_bits, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
                        int Ls, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,

@@ -6,20 +6,23 @@
 
 namespace csa {
 
-// cent [n_bg][C][128] bf16 -> cent_t [n_bg][16][C][8] bf16 (one 16-byte chunk per thread)
-__global__ void k_pack_centroids(const uint4 *__restrict__ cent, uint4 *__restrict__ cent_t, int C)
+// cent [n_bg][S][C][db] bf16 -> cent_t [n_bg][S][db/8][C][8] bf16 (one 16-byte chunk per thread;
+// db = 128 / S dimensions per subspace)
+__global__ void k_pack_centroids(const uint4 *__restrict__ cent, uint4 *__restrict__ cent_t, int C, int S)
 {
     const int bg = blockIdx.y;
-    const int e = blockIdx.x * 256 + threadIdx.x;  // = j*16 + c
+    const int e = blockIdx.x * 256 + threadIdx.x;  // = ((s * C) + j) * nch + c
     if (e >= C * 16) return;
-    const int j = e >> 4, c = e & 15;
-    cent_t[((size_t)bg * 16 + c) * C + j] = cent[(size_t)bg * C * 16 + e];
+    const int nch = 16 / S;
+    const int c = e % nch, sj = e / nch;
+    const int s = sj / C, j = sj - s * C;
+    cent_t[(((size_t)bg * S + s) * nch + c) * C + j] = cent[(size_t)bg * C * 16 + e];
 }
 
-void launch_pack_centroids(const void *cent, void *cent_t, int n_bg, int C, hipStream_t st)
+void launch_pack_centroids(const void *cent, void *cent_t, int n_bg, int C, int S, hipStream_t st)
 {
     dim3 grid((C * 16 + 255) / 256, n_bg);
-    k_pack_centroids<<<grid, 256, 0, st>>>((const uint4 *)cent, (uint4 *)cent_t, C);
+    k_pack_centroids<<<grid, 256, 0, st>>>((const uint4 *)cent, (uint4 *)cent_t, C, S);
 }
 
 // in-LDS bitonic sort of NP (power of two) 64-bit keys, ascending; all threads of the block
@@ -173,25 +176,27 @@ void launch_export_rows(const void *ent, const int32_t *part_off, int32_t *idx, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Table build, part 1: grid integers q[jj][i] = round-half-even(2^F * (c_{j0+jj} . k_i)) for one
-// KV head and a chunk of centroids.  One lane per key (the key row lives in registers as 128
-// fp32), centroids staged through LDS 64 at a time and broadcast.  The inner product is one fma
-// chain over ascending dimension from +0 - the same definition as the decode-time centroid
-// scores - so the table contents are reproducible bit for bit.
-// grid ceil(n_pre/256), block 256.
+// Table build, part 1: grid integers q[jj][i] = round-half-even(2^F * (c . k_i^(s))) for one KV
+// head, one subspace s (dimensions [s*DB, (s+1)*DB) of the head) and a chunk of that subspace's
+// centroids (Sec. 3.2 (2)).  One lane per key (its sub-vector lives in registers as DB fp32),
+// centroids staged through LDS 64 at a time and broadcast.  The inner product is one fma chain
+// over ascending dimension from +0 - the same definition as the decode-time centroid scores - so
+// the table contents are reproducible bit for bit.
+// grid ceil(n_pre/256), block 256.  cent points at the chunk's first centroid ([jc][DB] bf16).
 // ---------------------------------------------------------------------------------------------
 constexpr int kBuildTile = 64;
 
-template <bool PAGED>
+template <bool PAGED, int DB>
 __global__ __launch_bounds__(256) void k_build_scores(const uint16_t *__restrict__ kc,
                                                       const int32_t *__restrict__ block_table,
                                                       const uint16_t *__restrict__ cent,
                                                       int32_t *__restrict__ qs,
                                                       int32_t *__restrict__ flags, int b, int g,
-                                                      int Hkv, int max_ctx, int n_pre, int C, int j0,
+                                                      int Hkv, int max_ctx, int n_pre, int sub,
                                                       int jc, float up, int qmax)
 {
-    __shared__ uint4 s_c[kBuildTile][kHeadDim / 8];
+    constexpr int NCH = DB / 8;
+    __shared__ uint4 s_c[kBuildTile][NCH];
     const int i = blockIdx.x * 256 + threadIdx.x;
     const int ic = i < n_pre ? i : n_pre - 1;  // clamp: tail lanes compute a duplicate, store nothing
     int64_t row;
@@ -201,11 +206,11 @@ __global__ __launch_bounds__(256) void k_build_scores(const uint16_t *__restrict
     } else {
         row = ((int64_t)b * Hkv + g) * max_ctx + ic;
     }
-    float kf[kHeadDim];
+    float kf[DB];
     {
-        const uint4 *kr = (const uint4 *)(kc + row * kHeadDim);
+        const uint4 *kr = (const uint4 *)(kc + row * kHeadDim + sub * DB);
 #pragma unroll
-        for (int c = 0; c < kHeadDim / 8; ++c) {
+        for (int c = 0; c < NCH; ++c) {
             const uint4 w = kr[c];
             kf[c * 8 + 0] = bf16_lo(w.x); kf[c * 8 + 1] = bf16_hi(w.x);
             kf[c * 8 + 2] = bf16_lo(w.y); kf[c * 8 + 3] = bf16_hi(w.y);
@@ -213,19 +218,19 @@ __global__ __launch_bounds__(256) void k_build_scores(const uint16_t *__restrict
             kf[c * 8 + 6] = bf16_lo(w.w); kf[c * 8 + 7] = bf16_hi(w.w);
         }
     }
-    const uint4 *cg = (const uint4 *)(cent + (((size_t)b * Hkv + g) * C + j0) * kHeadDim);
+    const uint4 *cg = (const uint4 *)cent;
     int bad = 0;
     float qabs = 0.0f;
     for (int t0 = 0; t0 < jc; t0 += kBuildTile) {
         const int nt = min(kBuildTile, jc - t0);
         __syncthreads();
-        for (int e = threadIdx.x; e < nt * (kHeadDim / 8); e += 256)
-            s_c[e / (kHeadDim / 8)][e % (kHeadDim / 8)] = cg[(size_t)t0 * (kHeadDim / 8) + e];
+        for (int e = threadIdx.x; e < nt * NCH; e += 256)
+            s_c[e / NCH][e % NCH] = cg[(size_t)t0 * NCH + e];
         __syncthreads();
         for (int jj = 0; jj < nt; ++jj) {
             float acc = 0.0f;
 #pragma unroll
-            for (int c = 0; c < kHeadDim / 8; ++c) {
+            for (int c = 0; c < NCH; ++c) {
                 const uint4 w = s_c[jj][c];
                 acc = __builtin_fmaf(bf16_lo(w.x), kf[c * 8 + 0], acc);
                 acc = __builtin_fmaf(bf16_hi(w.x), kf[c * 8 + 1], acc);
@@ -239,7 +244,7 @@ __global__ __launch_bounds__(256) void k_build_scores(const uint16_t *__restrict
             const float qf = rintf(acc * up);
             if (!(fabsf(qf) <= (float)qmax)) bad = 1;
             qabs = fmaxf(qabs, fabsf(qf));
-            if (i < n_pre) qs[(size_t)(t0 + jj) * n_pre + i] = (int32_t)qf;
+            if (i < n_pre) qs[(size_t)(t0 + jj) * n_pre + i] = bad ? 0 : (int32_t)qf;
         }
     }
     if (bad) atomicOr(flags, 1);
@@ -248,17 +253,35 @@ __global__ __launch_bounds__(256) void k_build_scores(const uint16_t *__restrict
                                                                   // chunk counts, kept or not)
 }
 
-void launch_build_scores(const void *kc, const int32_t *block_table, const void *cent, int32_t *qs,
-                         int32_t *flags, int b, int g, int Hkv, int max_ctx, int n_pre, int C,
-                         int j0, int jc, int F, int qmax, hipStream_t st)
+template <int DB>
+static void launch_build_scores_db(const void *kc, const int32_t *block_table, const void *cent,
+                                   int32_t *qs, int32_t *flags, int b, int g, int Hkv, int max_ctx,
+                                   int n_pre, int sub, int jc, int F, int qmax, hipStream_t st)
 {
     const int grid = (n_pre + 255) / 256;
     if (block_table)
-        k_build_scores<true><<<grid, 256, 0, st>>>((const uint16_t *)kc, block_table, (const uint16_t *)cent, qs,
-                                                   flags, b, g, Hkv, max_ctx, n_pre, C, j0, jc, ldexpf(1.0f, F), qmax);
+        k_build_scores<true, DB><<<grid, 256, 0, st>>>((const uint16_t *)kc, block_table, (const uint16_t *)cent,
+                                                       qs, flags, b, g, Hkv, max_ctx, n_pre, sub, jc,
+                                                       ldexpf(1.0f, F), qmax);
     else
-        k_build_scores<false><<<grid, 256, 0, st>>>((const uint16_t *)kc, nullptr, (const uint16_t *)cent, qs,
-                                                    flags, b, g, Hkv, max_ctx, n_pre, C, j0, jc, ldexpf(1.0f, F), qmax);
+        k_build_scores<false, DB><<<grid, 256, 0, st>>>((const uint16_t *)kc, nullptr, (const uint16_t *)cent, qs,
+                                                        flags, b, g, Hkv, max_ctx, n_pre, sub, jc,
+                                                        ldexpf(1.0f, F), qmax);
+}
+
+void launch_build_scores(const void *kc, const int32_t *block_table, const void *cent, int32_t *qs,
+                         int32_t *flags, int b, int g, int Hkv, int max_ctx, int n_pre, int S, int sub,
+                         int jc, int F, int qmax, hipStream_t st)
+{
+#define CSA_BS(DB_) launch_build_scores_db<DB_>(kc, block_table, cent, qs, flags, b, g, Hkv, max_ctx, n_pre, sub, jc, F, qmax, st)
+    switch (S) {
+    case 1: CSA_BS(128); break;
+    case 2: CSA_BS(64); break;
+    case 4: CSA_BS(32); break;
+    case 8: CSA_BS(16); break;
+    default: CSA_BS(8); break;  // 16
+    }
+#undef CSA_BS
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -351,14 +374,16 @@ void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc
     k_build_select<<<jc, kBsNT, 0, st>>>(qs, (uint32_t *)ent, part_off, n_pre, L, Ls, Q, PO);
 }
 
-// max over prefill keys of ||k||^2, as the bit pattern of a non-negative fp32 (atomicMax on
-// int).  Used to pick the score grid.  out must be zeroed.
+// max over prefill keys and subspaces of ||k^(s)||^2 (nch 16-byte chunks per subspace), as the bit
+// pattern of a non-negative fp32 (atomicMax on int).  Used to pick the score grid.  out must be
+// zeroed.
 template <bool PAGED>
 __global__ void k_max_key_norm(const uint16_t *__restrict__ kc, const int32_t *__restrict__ block_table,
-                               int *__restrict__ out, int Hkv, int max_ctx, int n_pre, int64_t total)
+                               int *__restrict__ out, int Hkv, int max_ctx, int n_pre, int64_t total,
+                               int nch)
 {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    float nn = 0.0f;
+    float best = 0.0f;
     if (t < total) {
         const int i = (int)(t % n_pre);
         const int bg = (int)(t / n_pre), b = bg / Hkv, g = bg % Hkv;
@@ -370,26 +395,31 @@ __global__ void k_max_key_norm(const uint16_t *__restrict__ kc, const int32_t *_
             row = (int64_t)bg * max_ctx + i;
         }
         const uint4 *kr = (const uint4 *)(kc + row * kHeadDim);
+        float nn = 0.0f;
         for (int c = 0; c < kHeadDim / 8; ++c) {
             const uint4 w = kr[c];
             const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
                                 bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
             for (int e = 0; e < 8; ++e) nn = fmaf(f[e], f[e], nn);
+            if ((c + 1) % nch == 0) {
+                best = fmaxf(best, nn);
+                nn = 0.0f;
+            }
         }
     }
-    for (int o = 32; o > 0; o >>= 1) nn = fmaxf(nn, __shfl_xor(nn, o, kWave));
-    if (lane_id() == 0) atomicMax(out, __float_as_int(nn));
+    for (int o = 32; o > 0; o >>= 1) best = fmaxf(best, __shfl_xor(best, o, kWave));
+    if (lane_id() == 0) atomicMax(out, __float_as_int(best));
 }
 
 void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
-                         int max_ctx, int n_pre, hipStream_t st)
+                         int max_ctx, int n_pre, int S, hipStream_t st)
 {
     const int64_t total = (int64_t)B * Hkv * n_pre;
     const unsigned grid = (unsigned)((total + 255) / 256);
     if (block_table)
-        k_max_key_norm<true><<<grid, 256, 0, st>>>((const uint16_t *)kc, block_table, (int *)out, Hkv, max_ctx, n_pre, total);
+        k_max_key_norm<true><<<grid, 256, 0, st>>>((const uint16_t *)kc, block_table, (int *)out, Hkv, max_ctx, n_pre, total, 16 / S);
     else
-        k_max_key_norm<false><<<grid, 256, 0, st>>>((const uint16_t *)kc, nullptr, (int *)out, Hkv, max_ctx, n_pre, total);
+        k_max_key_norm<false><<<grid, 256, 0, st>>>((const uint16_t *)kc, nullptr, (int *)out, Hkv, max_ctx, n_pre, total, 16 / S);
 }
 
 }  // namespace csa

@@ -18,10 +18,11 @@ Recipe (per sequence b, KV head g), all draws from a torch.Generator seeded with
 * prefill query     q = mu_c + 0.5 * eps + u (same means as the keys)  (stream "Qpre")
 * value i           independent mixture of the same form, own means    (streams "v_means", "V")
 * decode query / appended key / appended value: fresh draws of the three forms above
-* centroids         spherical k-means over the pooled, l2-normalised prefill queries of the G
-                    query heads of the group; random-sample initialisation; `kmeans_iters`
-                    full-batch Lloyd iterations; an empty cluster keeps its centroid; rounded
-                    to bf16 once at the end.
+* centroids         per subspace (a uniform slice of the head dimension): spherical k-means over
+                    the pooled, l2-normalised sub-vectors of the prefill queries of the G query
+                    heads of the group; random-sample initialisation; `kmeans_iters` full-batch
+                    Lloyd iterations; an empty cluster keeps its centroid; rounded to bf16 once
+                    at the end.
 """
 from __future__ import annotations
 
@@ -50,6 +51,7 @@ class Workload:
     pre_appended: int   # keys appended before the first timed step
     page_size: int      # 0 = contiguous K/V, 16 = paged
     kmeans_iters: int = 20
+    n_sub: int = 1      # subspaces S (uniform split of the head dimension); C, m are per subspace
 
     @property
     def group(self) -> int:
@@ -69,6 +71,9 @@ CONFIGS: Dict[str, Workload] = {
     "cfg2": Workload("cfg2", 1, 32, 8, 128, 131072, 256, 2048, 4096, 32, 6554, 64, 0, 0),
     "cfg3": Workload("cfg3", 16, 32, 8, 128, 65536, 256, 1024, 4096, 16, 3277, 1, 256, 16),
     "cfg4": Workload("cfg4", 8, 64, 8, 128, 131072, 512, 4096, 4096, 32, 6554, 256, 0, 0),
+    # the paper's default geometry (Table "hyperparameters": 8 subspaces, one probe each, C = 128
+    # centroids per subspace, L = 0.1 N_pre, K = 0.05 N) on the 8B-shaped layer, batch 8
+    "paper_s8": Workload("paper_s8", 8, 32, 8, 128, 65536, 256, 128, 6554, 1, 3277, 64, 0, 0, n_sub=8),
 }
 
 _STREAMS = ("k_means", "v_means", "offset", "K", "V", "Qpre", "kmeans_init",
@@ -131,7 +136,8 @@ def make_inputs(cfg: Workload, seed: int = 0, device: str = "cpu",
 
     Returns (bf16 unless noted):
       k_cache, v_cache [B][Hkv][max_ctx][d]  rows [0, n_pre) filled, the rest zero
-      centroids        [B][Hkv][C][d]        unit norm before the bf16 rounding
+      centroids        [B][Hkv][C][d], or [B][Hkv][S][C][d/S] when cfg.n_sub = S > 1;
+                                             unit norm before the bf16 rounding
       q_steps          [T][B][Hq][d]         one decode query per head per step
       k_new, v_new     [T][B][Hkv][d]        the pair appended at each step
     with T = pre_appended + steps.  `kmeans_sample` caps the number of pooled prefill queries
@@ -143,7 +149,9 @@ def make_inputs(cfg: Workload, seed: int = 0, device: str = "cpu",
     bf = torch.bfloat16
     k_cache = torch.zeros(B, Hkv, cfg.max_ctx, d, dtype=bf, device=dev)
     v_cache = torch.zeros(B, Hkv, cfg.max_ctx, d, dtype=bf, device=dev)
-    centroids = torch.empty(B, Hkv, cfg.C, d, dtype=bf, device=dev)
+    S = cfg.n_sub
+    db = d // S
+    centroids = torch.empty(B, Hkv, S, cfg.C, db, dtype=bf, device=dev)
     q_steps = torch.empty(T, B, Hq, d, dtype=bf, device=dev)
     k_new = torch.empty(T, B, Hkv, d, dtype=bf, device=dev)
     v_new = torch.empty(T, B, Hkv, d, dtype=bf, device=dev)
@@ -162,13 +170,18 @@ def make_inputs(cfg: Workload, seed: int = 0, device: str = "cpu",
                 n_pool = min(n_pool, kmeans_sample)
             # prefill queries are bf16 tensors in a model; round before clustering
             qpre = _mixture(k_means, n_pool, G_("Qpre"), shift=u).to(bf).float()
-            cent = spherical_kmeans(qpre, cfg.C, cfg.kmeans_iters, G_("kmeans_init"))
-            centroids[b, g] = cent.to(bf)
+            g_init = G_("kmeans_init")
+            for sub in range(S):
+                cent = spherical_kmeans(qpre[:, sub * db:(sub + 1) * db].contiguous(), cfg.C,
+                                        cfg.kmeans_iters, g_init)
+                centroids[b, g, sub] = cent.to(bf)
             del qpre
             q_steps[:, b, g * G:(g + 1) * G] = _mixture(
                 k_means, T * G, G_("decode_q"), shift=u).to(bf).view(T, G, d)
             k_new[:, b, g] = _mixture(k_means, T, G_("append_k")).to(bf)
             v_new[:, b, g] = _mixture(v_means, T, G_("append_v")).to(bf)
+    if S == 1:
+        centroids = centroids.view(B, Hkv, cfg.C, d)
     return dict(k_cache=k_cache, v_cache=v_cache, centroids=centroids,
                 q_steps=q_steps, k_new=k_new, v_new=v_new)
 
@@ -201,8 +214,8 @@ def algorithmic_bytes_per_head(cfg: Workload, t: float) -> Dict[str, float]:
     8-byte entries, 2*(k+t) K/V rows, and q / out / sel."""
     d = cfg.head_dim
     return dict(
-        centroids=cfg.C * d * 2 / cfg.group,
-        table_rows=cfg.m * cfg.L * 8,
+        centroids=cfg.C * d * 2 / cfg.group,             # S subspaces x C centroids x d/S dimensions
+        table_rows=cfg.n_sub * cfg.m * cfg.L * 8,
         kv_rows=2 * (cfg.k + t) * d * 2,
         io=d * 2 + d * 4 + cfg.k * 4,
     )

@@ -15,7 +15,7 @@ TOL_OUT = 2e-2   # max-abs tolerance on attention outputs (bf16 inputs, fp32 acc
 def cfg_kwargs(w: Workload, F: int, partition_keys: int = 0):
     return dict(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, n_centroids=w.C,
                 list_len=w.L, n_probe=w.m, budget_k=w.k, max_ctx=w.max_ctx, page_size=w.page_size,
-                score_frac_bits=F, partition_keys=partition_keys)
+                score_frac_bits=F, partition_keys=partition_keys, n_subspaces=w.n_sub)
 
 
 class Case:
@@ -68,8 +68,8 @@ class Case:
 
     def import_oracle_tables(self):
         w = self.w
-        idx = np.empty((w.batch, w.n_kv_heads, w.C, w.L), np.int32)
-        score = np.empty((w.batch, w.n_kv_heads, w.C, w.L), np.float32)
+        idx = np.empty((w.batch, w.n_kv_heads, w.n_sub * w.C, w.L), np.int32)
+        score = np.empty((w.batch, w.n_kv_heads, w.n_sub * w.C, w.L), np.float32)
         for b in range(w.batch):
             for g in range(w.n_kv_heads):
                 idx[b, g], score[b, g], _ = self.oracle_tables(b, g)

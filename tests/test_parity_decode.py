@@ -82,6 +82,47 @@ def test_key_ranges_spanning_several_index_blocks(part):
     case.check_step(1)
 
 
+@pytest.mark.parametrize("S,tau,C", [(2, 3, 300), (8, 1, 37), (8, 2, 64), (16, 3, 20), (4, 2, 600)])
+def test_subspace_geometry(S, tau, C):
+    """S uniform subspaces with tau probes each (S = 8, tau = 1 is the paper's default; tau > 1 its
+    centroid back-off): tables built on the GPU equal the oracle's bit for bit, probed rows, selected
+    indices and outputs match over two steps with an append in between."""
+    w = small(f"sub{S}x{tau}", n_q_heads=8, n_kv_heads=2, n_pre=5003, C=C, L=200, m=tau, k=333,
+              steps=2, n_sub=S)
+    case = Case(w, seed=S * 10 + tau, F=13, partition_keys=2048)
+    case.build_on_gpu()
+    for g in range(2):
+        idx, score = case.export(0, g)
+        o_idx, o_score, mx = case.oracle_tables(0, g)
+        assert mx * S * tau < 2 ** 24
+        assert idx.shape == (S * C, 200)
+        assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
+    case.check_step(0)
+    case.append(1)
+    case.check_step(1)
+    # the import path carries the same tables
+    case2 = Case(w, seed=S * 10 + tau, F=13, partition_keys=1024)
+    case2.import_oracle_tables()
+    case2.check_step(0)
+
+
+def test_subspace_geometry_automatic_grid_uses_subvector_norms():
+    """With S = 8 the scores are inner products of 16-dimensional sub-vectors, so the automatic
+    grid is finer than the one a whole-vector norm bound would allow."""
+    w = small("sub_auto", n_q_heads=4, n_kv_heads=1, n_pre=3000, C=32, L=128, m=1, k=100, steps=1, n_sub=8)
+    case = Case(w, seed=3, F=-1)
+    case.build_on_gpu()
+    w1 = small("sub_auto1", n_q_heads=4, n_kv_heads=1, n_pre=3000, C=32, L=128, m=8, k=100, steps=1)
+    case1 = Case(w1, seed=3, F=-1)
+    case1.build_on_gpu()
+    assert case.F > case1.F
+    idx, score = case.export(0, 0)
+    o_idx, o_score, mx = case.oracle_tables(0, 0)
+    assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
+    assert mx * 8 < 2 ** 24 and mx < 2 ** 18
+    case.check_step(0)
+
+
 def _tie_heavy_tables(w, rng, qmax, fill):
     idx = np.full((w.batch, w.n_kv_heads, w.C, w.L), -1, np.int32)
     score = np.zeros((w.batch, w.n_kv_heads, w.C, w.L), np.float32)

@@ -18,7 +18,7 @@ pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 def _check_rows(case, b, g, rows):
     idx, score = case.export(b, g)
     o_idx, o_score, mx = case.oracle_tables(b, g, rows)
-    assert mx * case.w.m < 2 ** 24
+    assert mx * case.w.m * case.w.n_sub < 2 ** 24
     assert np.array_equal(idx[rows], o_idx), f"table rows {rows} of ({b},{g}) differ"
     assert np.array_equal(score[rows], o_score)
     # row invariants at full size: distinct, in range, sorted by score
@@ -70,4 +70,18 @@ def test_cfg4_70b_shape():
     heads = [(0, 0), (0, 7), (3, 40), (7, 56), (7, 63)]
     for step in range(2):
         print("cfg4 step", step, "err", case.check_step(step, heads))
+        case.append(1)
+
+
+def test_paper_default_geometry_full_size():
+    """The paper's default geometry (8 subspaces, one probe each, C = 128, L = 0.1 N_pre,
+    k = 0.05 N_pre) at 64K context, batch 8: sampled table rows of several subspaces and sampled
+    heads over two steps."""
+    w = _light("paper_s8", 2)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=64 * w.C)
+    case.build_on_gpu()
+    _check_rows(case, 3, 5, [0, 127, 128 * 3 + 17, 128 * 7 + 127])
+    heads = [(0, 0), (0, 3), (3, 20), (7, 28), (7, 31)]
+    for step in range(2):
+        print("paper_s8 step", step, "err", case.check_step(step, heads))
         case.append(1)
