@@ -295,6 +295,48 @@ double oracle_build_rows(const uint16_t *K, int64_t n_pre, int d, int n_sub, int
     return max_abs_q;
 }
 
+/* ---------------------------------------------------------------- online: streaming updates */
+
+/*
+ * Sec. 3.3 (5): after a new key k_S (index idx_new, larger than every index in the tables) has
+ * been appended, score it against every centroid of every subspace, score = c_j^(b) . k_S^(b)
+ * (same fma chain and grid as the table build), and try-insert it into that centroid's
+ * fixed-capacity Top-L list: a list with a free slot takes it; a full list takes it only if it
+ * beats the list's minimum, which is evicted (an equal score does not beat it: the older key has
+ * the lower index).  Lists stay sorted by (score desc, idx asc); capacity L never changes.
+ *   tbl_idx / tbl_score [S*C][L] in place.  Returns the largest |q| of the new key's scores.
+ */
+double oracle_try_insert(int32_t *tbl_idx, float *tbl_score, int L, const uint16_t *cent,
+                         int n_sub, int C, int d, const uint16_t *k_new, int32_t idx_new, int F)
+{
+    const float up = ldexpf(1.0f, F), down = ldexpf(1.0f, -F);
+    const int db = d / n_sub;
+    double max_abs_q = 0.0;
+    for (int r = 0; r < n_sub * C; ++r) {
+        int32_t *I = tbl_idx + (int64_t)r * L;
+        float *S = tbl_score + (int64_t)r * L;
+        const int b = r / C;
+        float qf = rintf(dot_chain_bf16(cent + (int64_t)r * db, k_new + b * db, db) * up);
+        if (fabs((double)qf) > max_abs_q) max_abs_q = fabs((double)qf);
+        float sc = qf * down;
+        int cnt = 0;
+        while (cnt < L && I[cnt] >= 0) ++cnt;
+        if (cnt == L) {
+            if (!(sc > S[L - 1])) continue; /* does not beat the minimum */
+            cnt = L - 1;                    /* evict it */
+        }
+        int p = cnt; /* slide larger-index-or-smaller-score entries one slot down */
+        while (p > 0 && S[p - 1] < sc) {
+            I[p] = I[p - 1];
+            S[p] = S[p - 1];
+            --p;
+        }
+        I[p] = idx_new;
+        S[p] = sc;
+    }
+    return max_abs_q;
+}
+
 /* ---------------------------------------------------------------- online: decode */
 
 /*
@@ -329,6 +371,8 @@ void oracle_top_centroids(const uint16_t *q, const uint16_t *cent, int n_sub, in
  *           absent from a row gets nothing from it;
  *   step 4: keep the min(k, |U|) members of U with the largest score, ties to the lower
  *           index; reported in ascending index order, padded with -1.
+ * Only key indices below n_pre are candidates: entries at or above it (keys of the always-attended
+ * recent window, which streaming updates may have put into the tables) are skipped.
  * acc_out (optional, [n_pre]) receives score(i), NaN for keys outside U.
  * Returns |U|.
  */
@@ -344,7 +388,7 @@ int64_t oracle_select_keys(const int32_t *tbl_idx, const float *tbl_score, int L
         const float *S = tbl_score + (int64_t)rows[r] * L;
         for (int p = 0; p < L; ++p) {
             int32_t i = I[p];
-            if (i < 0) continue;
+            if (i < 0 || i >= n_pre) continue;
             acc[i] += S[p];
             seen[i] = 1;
         }
@@ -373,8 +417,10 @@ int64_t oracle_select_keys(const int32_t *tbl_idx, const float *tbl_score, int L
 
 /*
  * One decode step for one query head: Sec. 3.3 steps 1-4 followed by exact attention over
- * the selected keys plus every key appended after prefill, rows [n_pre, n) (the recent
- * window: always attended, never competing for the k slots).
+ * the selected keys plus the recent window, rows [n_pre, n): always attended, never competing
+ * for the k slots.  Without streaming updates the window is every key appended after prefill and
+ * n_pre is the prefill length; with them (Sec. 3.3 (5)) older appended keys compete through the
+ * tables and the caller passes n_pre = max(0, n - R), the start of the last R positions.
  *   q [d], cent [S][C][d/S], K / V [>= n][d] bf16; tables [S*C][L]; tau probes per subspace.
  *   rows_out [S*tau], sel_out [k] (ascending, -1 padded), sel_count [1], out [d] fp32.
  */

@@ -37,6 +37,7 @@ def lib():
         _lib.oracle_build_rows.restype = C.c_double
         _lib.oracle_select_keys.restype = C.c_int64
         _lib.oracle_decode_items.restype = C.c_int
+        _lib.oracle_try_insert.restype = C.c_double
     return _lib
 
 
@@ -143,6 +144,17 @@ def decode_head(q, cent, tbl_idx, tbl_score, tau, k, K, V, n_pre, n):
                              _p(tbl_score), C.c_int(L), C.c_int(tau), C.c_int(k), _p(K), _p(V),
                              C.c_int64(n_pre), C.c_int64(n), _p(rows), _p(sel), _p(cnt), _p(out))
     return rows, sel[:k], int(cnt[0]), out
+
+
+def try_insert(tbl_idx, tbl_score, cent, k_new, idx_new, F):
+    """Streaming update of one KV head's tables [S*C][L] (in place) with the key appended at index
+    idx_new.  Returns the largest |q| among the new key's scores."""
+    S, n_c, d = _geometry(cent)
+    assert tbl_idx.flags["C_CONTIGUOUS"] and tbl_score.flags["C_CONTIGUOUS"]
+    assert tbl_idx.shape[0] == S * n_c
+    return lib().oracle_try_insert(_p(tbl_idx), _p(tbl_score), C.c_int(tbl_idx.shape[-1]), _p(cent),
+                                   C.c_int(S), C.c_int(n_c), C.c_int(d), _p(k_new), C.c_int32(idx_new),
+                                   C.c_int(F))
 
 
 def attend_selected(q, K, V, sel, n_pre, n):

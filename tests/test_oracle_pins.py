@@ -520,6 +520,58 @@ def test_reuse_step_attends_the_given_set_plus_appended_keys():
     assert np.all(none == 0)
 
 
+# ------------------------------------------------------------------ streaming updates (Sec. 3.3 (5))
+
+@pytest.mark.parametrize("S,L", [(1, 40), (4, 40), (2, 400)])
+def test_try_insert_stream_equals_a_build_over_all_keys(S, L):
+    """Top-L of a growing set is order-independent: tables built over the first 300 keys and then
+    updated with keys 300..339 one at a time must equal tables built over all 340 keys at once
+    (L = 400: lists with free slots just grow).  Small-integer keys give many equal scores, so the
+    rule "an equal score does not evict" is exercised.  Catches a wrong eviction test, a wrong
+    insert position, scoring the wrong key slice."""
+    rng = np.random.default_rng(40 + S)
+    d, n0, n1, n_c, F = 128, 300, 340, 5, 2
+    Kv = rng.integers(-2, 3, (n1, d)).astype(np.float32)
+    cv = rng.integers(-1, 2, (S, n_c, d // S)).astype(np.float32)
+    K, cent = to_bits(Kv), to_bits(cv)
+    idx, score, _ = oracle.build_tables(np.ascontiguousarray(K[:n0]), n0, cent, L, F)
+    for i in range(n0, n1):
+        oracle.try_insert(idx, score, cent, K[i], i, F)
+    want_idx, want_score, _ = oracle.build_tables(K, n1, cent, L, F)
+    assert np.array_equal(idx, want_idx) and np.array_equal(score, want_score)
+
+
+def test_try_insert_on_real_valued_scores_keeps_rows_sorted_and_bounded():
+    rng = np.random.default_rng(44)
+    d, n0, n1, n_c, L, F = 128, 500, 560, 7, 64, 10
+    K, cent = rand_bf16(rng, (n1, d)), rand_bf16(rng, (n_c, d), 0.1)
+    idx, score, _ = oracle.build_tables(np.ascontiguousarray(K[:n0]), n0, cent, L, F)
+    for i in range(n0, n1):
+        oracle.try_insert(idx, score, cent, K[i], i, F)
+    want_idx, want_score, _ = oracle.build_tables(K, n1, cent, L, F)
+    assert np.array_equal(idx, want_idx) and np.array_equal(score, want_score)
+    assert (np.diff(score, axis=1) <= 0).all() and all(len(set(r.tolist())) == L for r in idx)
+
+
+def test_decode_with_a_recent_window_excludes_it_from_the_candidates():
+    """Streaming mode: keys at or after the window start are attended unconditionally and must
+    not be selected as well (they would be counted twice).  Tables contain window keys."""
+    rng = np.random.default_rng(45)
+    d, n, n_c, L, m, k, F, win = 128, 400, 6, 80, 3, 50, 12, 32
+    q, cent = rand_bf16(rng, d), rand_bf16(rng, (n_c, d), 0.1)
+    K, V = rand_bf16(rng, (n, d)), rand_bf16(rng, (n, d))
+    idx, score = random_tables(rng, n_c, L, n, F, 5000)     # indices anywhere in [0, n)
+    ws = n - win
+    rows, sel, cnt, out = oracle.decode_head(q, cent, idx, score, m, k, K, V, ws, n)
+    assert (idx[rows] >= ws).any()                            # the case is exercised
+    masked_idx = np.where(idx >= ws, -1, idx)
+    want_sel, _ = brute_select(masked_idx, score, rows, k, F)
+    assert sel[:cnt].tolist() == want_sel and all(i < ws for i in want_sel)
+    ids = np.r_[sel[:cnt], np.arange(ws, n)]
+    assert len(set(ids.tolist())) == len(ids)
+    np.testing.assert_allclose(out, softmax_attention_np(q, K, V, ids), atol=1e-6)
+
+
 def test_single_cluster_recall_is_one():
     """Query-centric argument of Sec. 2.4: if every prefill query is a positive multiple of one
     direction u and the decode query is too, one centroid (= u) with L >= k retrieves exactly
