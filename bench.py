@@ -44,6 +44,9 @@ def main():
                          "index set in between (csa_decode_step_reuse)")
     ap.add_argument("--keep-ratio", type=float, default=0.0,
                     help="budget k = round(ratio * N_pre) instead of the config's (0 = config)")
+    ap.add_argument("--stream-window", type=int, default=0,
+                    help="R > 0: streaming updates - csa_append_kv try-inserts every new key into the "
+                         "tables and only the last R positions are attended unconditionally")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies before the timed region, "
@@ -65,7 +68,11 @@ def main():
     dev = "cuda"
     base = CONFIGS[args.config]
     K, W = args.steps, args.warmup
-    w = dataclasses.replace(base, steps=max(K, W, 1))
+    streaming = args.stream_window > 0
+    # with streaming updates the tables keep the appended keys, so the context cannot be rewound
+    # after the warm-up: the timed steps simply continue from there
+    K_prof = min(K, 16) if streaming else K   # steps of the per-kernel event pass
+    w = dataclasses.replace(base, steps=(W + K + K_prof) if streaming else max(K, W, 1))
     if args.keep_ratio > 0:
         w = dataclasses.replace(w, k=int(round(args.keep_ratio * w.n_pre)))
     period = max(1, args.search_period)
@@ -86,7 +93,8 @@ def main():
     ctx = binding.Context(k_store, v_store, bt, batch=B, n_q_heads=Hq, n_kv_heads=Hkv,
                           n_centroids=w.C, list_len=w.L, n_probe=w.m, budget_k=w.k,
                           max_ctx=w.max_ctx, page_size=w.page_size, score_frac_bits=-1,
-                          partition_keys=args.partition_keys, n_subspaces=w.n_sub)
+                          partition_keys=args.partition_keys, n_subspaces=w.n_sub,
+                          stream_window=args.stream_window)
     t0 = time.time()
     ctx.build_tables(inp["centroids"], w.n_pre)
     torch.cuda.synchronize()
@@ -95,13 +103,23 @@ def main():
 
     q_steps, k_new, v_new = inp["q_steps"], inp["k_new"], inp["v_new"]
 
+    done = [0]   # decode steps taken since the last rewind
+
     def reset():
+        if streaming:   # never rewinds; only the keys appended before the first step are due once
+            if binding.csa_context_len(ctx.ctx)[1] == w.n_pre:
+                for t in range(w.pre_appended):
+                    ctx.append_kv(k_new[t], v_new[t])
+            return
+        done[0] = 0
         binding.csa_set_context_len(ctx.ctx, w.n_pre)
         for t in range(w.pre_appended):
             ctx.append_kv(k_new[t], v_new[t])
 
     def run(n_steps):
-        for s in range(n_steps):
+        first = done[0]
+        done[0] += n_steps
+        for s in range(first, first + n_steps):
             t = w.pre_appended + s
             if s % period == 0:
                 ctx.decode_step(q_steps[t])
@@ -129,10 +147,11 @@ def main():
     us_per_step = elapsed / K * 1e6
     sel_mean = float(ctx.sel_count.float().mean().item())
 
-    # ---- second pass over the same K steps with per-kernel HIP events
+    # ---- second pass with per-kernel HIP events: over the same K steps, or - with streaming
+    # updates, where steps cannot be replayed - over the next K_prof steps
     reset()
     binding.csa_profile_enable(ctx.ctx, True)
-    run(K)
+    run(K_prof)
     torch.cuda.synchronize()
     prof = binding.csa_profile_read(ctx.ctx)
     binding.csa_profile_enable(ctx.ctx, False)
@@ -140,7 +159,8 @@ def main():
     stage_us = {name: (ms / max(n, 1) * 1e3) for name, (ms, n) in prof.items() if n > 0}
 
     # ---- algorithmic bytes (per step, mean appended count over the timed steps)
-    t_mean = w.pre_appended + (K - 1) / 2.0
+    # keys attended unconditionally: all appended ones, or the recent window
+    t_mean = float(args.stream_window) if streaming else w.pre_appended + (K - 1) / 2.0
     per_head = algorithmic_bytes_per_head(w, t_mean)
     n_search = (K + period - 1) // period
     step_bytes = B * Hq * ((per_head["centroids"] + per_head["table_rows"]) * n_search / K
@@ -185,7 +205,10 @@ def main():
         "roofline": roofline,
     }
 
-    if not args.no_cpu_baseline:
+    if streaming:
+        result["config"]["stream_window"] = args.stream_window
+        binding.csa_streaming_status(ctx.ctx)
+    if not args.no_cpu_baseline and not streaming:
         result["cpu_baseline"] = cpu_baseline(ctx, w, inp, args.cpu_seconds)
     print(json.dumps(result, ensure_ascii=False), flush=True)
 

@@ -65,6 +65,10 @@ typedef struct {
                                 < 0: csa_build_tables picks the finest safe grid */
     int32_t partition_keys;  /* 0 = automatic; else a power of two in [1024, 16384]: size of
                                 the key-index ranges the score accumulation is split into */
+    int32_t stream_window;   /* 0: appended keys never enter the tables and are all attended;
+                                R > 0: streaming updates (Sec. 3.3 (5)) - csa_append_kv try-inserts
+                                each new key into the Top-L lists and only the last R positions
+                                (the recent window of Sec. 3.3 (4)) are attended unconditionally */
 } csa_config;
 
 /*
@@ -127,10 +131,18 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
                       const float *score_dev, int32_t n_pre, void *stream);
 
 /*
- * Sec. 3.3 (5), first sentence: append one key/value row per KV head at position n, n <- n+1.
+ * Sec. 3.3 (5): append one key/value row per KV head at position n, n <- n+1.
  *   k_new_dev, v_new_dev: bf16 [B][Hkv][d].
- * Appended keys are not inserted into the tables; every key in [n_pre, n) is attended exactly
- * by csa_decode_step (the "recent window" of Sec. 3.3 (4), covering all decode-time keys).
+ * stream_window = 0: appended keys are not inserted into the tables; every key in [n_pre, n) is
+ * attended exactly by csa_decode_step (the "recent window" of Sec. 3.3 (4), covering all
+ * decode-time keys).
+ * stream_window = R > 0: the new key is also scored against every centroid of every subspace
+ * (same fma chain and grid as the table build) and try-inserted into that centroid's
+ * fixed-capacity list: a list with a free slot takes it, a full list takes it only if its score
+ * beats the list's minimum (an equal score does not), which is evicted.  csa_decode_step then
+ * attends the selected keys plus the last R positions [max(0, n - R), n); keys in that window
+ * are not candidates of the Top-K.  A score outside the grid range is clamped (see
+ * csa_streaming_status).
  * CSA_ERR_CAPACITY if n == max_ctx.
  */
 int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, void *stream);
@@ -167,9 +179,14 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
 int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev,
                           const int32_t *sel_idx_dev, const int32_t *sel_count_dev, void *stream);
 
+/* Streaming updates only: SYNCHRONISES `stream` and returns CSA_ERR_RANGE if a streamed key's
+ * score did not fit the score grid since the tables were built (it was clamped), else CSA_OK. */
+int csa_streaming_status(csa_ctx *ctx, void *stream);
+
 /* Host-side counters: prefill length and current context length. */
 int csa_context_len(const csa_ctx *ctx, int32_t *n_pre, int32_t *n);
-/* Rewind / set the context length to n in [n_pre, max_ctx] (rows >= n are simply ignored). */
+/* Rewind / set the context length to n in [n_pre, max_ctx] (rows >= n are simply ignored).
+ * With streaming updates the tables hold the appended keys: CSA_ERR_STATE unless n is unchanged. */
 int csa_set_context_len(csa_ctx *ctx, int32_t n);
 /* The grid exponent F in use (valid after build/import). */
 int csa_score_frac_bits(const csa_ctx *ctx, int32_t *frac_bits);
@@ -185,7 +202,7 @@ int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream);
  * launches into launches[CSA_N_STAGES] (either may be NULL), and clears the record.
  * Events cost a few microseconds per stage: leave disabled when timing whole steps.
  */
-#define CSA_N_STAGES 9
+#define CSA_N_STAGES 10
 int csa_profile_enable(csa_ctx *ctx, int32_t on);
 int csa_profile_read(csa_ctx *ctx, double *ms_sum, int64_t *launches);
 const char *csa_stage_name(int32_t stage); /* NULL if out of range */

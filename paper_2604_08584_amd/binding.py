@@ -16,13 +16,14 @@ LIB_PATH = os.environ.get("CSATTN_LIB", os.path.join(_HERE, "libcsattn.so"))
 CSA_OK = 0
 CSA_ERR_ARG, CSA_ERR_STATE, CSA_ERR_CAPACITY = -1, -2, -3
 CSA_ERR_WORKSPACE, CSA_ERR_HIP, CSA_ERR_RANGE = -4, -5, -6
-CSA_N_STAGES = 9
+CSA_N_STAGES = 10
 
 
 class csa_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "n_centroids", "list_len", "n_probe",
-        "budget_k", "n_subspaces", "max_ctx", "page_size", "score_frac_bits", "partition_keys")]
+        "budget_k", "n_subspaces", "max_ctx", "page_size", "score_frac_bits", "partition_keys",
+        "stream_window")]
 
 
 _lib = None
@@ -50,6 +51,7 @@ def lib() -> C.CDLL:
         "csa_append_kv": (C.c_int, [vp, vp, vp, vp]),
         "csa_decode_step": (C.c_int, [vp, vp, vp, vp, vp, vp]),
         "csa_decode_step_reuse": (C.c_int, [vp, vp, vp, vp, vp, vp]),
+        "csa_streaming_status": (C.c_int, [vp, vp]),
         "csa_context_len": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
         "csa_set_context_len": (C.c_int, [vp, i32]),
         "csa_score_frac_bits": (C.c_int, [vp, C.POINTER(i32)]),
@@ -69,7 +71,7 @@ def lib() -> C.CDLL:
 
 EXPORTED = ("csa_create", "csa_destroy", "csa_workspace_bytes", "csa_bind", "csa_build_tables",
             "csa_export_tables", "csa_import_tables", "csa_append_kv", "csa_decode_step",
-            "csa_decode_step_reuse",
+            "csa_decode_step_reuse", "csa_streaming_status",
             "csa_context_len", "csa_set_context_len", "csa_score_frac_bits",
             "csa_last_probed_rows", "csa_profile_enable", "csa_profile_read", "csa_stage_name",
             "csa_strerror", "csa_last_hip_error")
@@ -100,7 +102,8 @@ def _stream():
 # ---- the C entry points, one to one -------------------------------------------------------
 
 def csa_create(**cfg) -> C.c_void_p:
-    c = csa_config(n_subspaces=1, head_dim=128, page_size=0, score_frac_bits=-1, partition_keys=0)
+    c = csa_config(n_subspaces=1, head_dim=128, page_size=0, score_frac_bits=-1, partition_keys=0,
+                   stream_window=0)
     for key, val in cfg.items():
         setattr(c, key, val)
     ctx = C.c_void_p()
@@ -150,6 +153,10 @@ def csa_decode_step(ctx, q, out, sel_idx=None, sel_count=None):
 def csa_decode_step_reuse(ctx, q, out, sel_idx=None, sel_count=None):
     _check(lib().csa_decode_step_reuse(ctx, _ptr(q), _ptr(out), _ptr(sel_idx), _ptr(sel_count), _stream()),
            "csa_decode_step_reuse")
+
+
+def csa_streaming_status(ctx):
+    _check(lib().csa_streaming_status(ctx, _stream()), "csa_streaming_status")
 
 
 def csa_context_len(ctx):

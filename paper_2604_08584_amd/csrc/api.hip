@@ -21,10 +21,11 @@ struct Region {
 
 struct Layout {
     // tables buffer
-    Region cent_t, ent, part_off;
+    Region cent_t, ent, part_off, row_cnt, row_min;  // (the last two: streaming updates only)
     size_t tables_bytes = 0;
     // scratch buffer
     Region z, rows, spans, cand, cand_bits, cand_cnt, seg_par, thr, hist, sel, sel_count, part, flags, qs;
+    Region queue_n, queue;  // rows waiting for the streaming insertion
     size_t scratch_bytes = 0;
     int P_max = 0, PO_max = 0, S_max = 0, Ls = 0;
     size_t cand_keys = 0;  // candidate slots per head
@@ -32,7 +33,7 @@ struct Layout {
 
 const char *kStageNames[CSA_N_STAGES] = {"score_centroids", "top_centroids",   "accumulate",      "select_threshold",
                                          "select_emit",     "attention_split", "attention_merge", "append_kv",
-                                         "range_offsets"};
+                                         "range_offsets",   "stream_insert"};
 using csa::kUnit;
 
 }  // namespace
@@ -84,6 +85,10 @@ Layout make_layout(const csa_config &c)
     put(l.cent_t, BG * c.n_centroids * c.head_dim * 2);
     put(l.ent, BG * Ct * (size_t)l.Ls * 4);
     put(l.part_off, BG * Ct * (size_t)l.PO_max * 4);
+    if (c.stream_window > 0) {
+        put(l.row_cnt, BG * Ct * 4);
+        put(l.row_min, BG * Ct * 4);
+    }
     l.tables_bytes = off;
     off = 0;
     l.cand_keys = ((size_t)c.max_ctx + 16383) / 16384 * 16384;
@@ -102,6 +107,10 @@ Layout make_layout(const csa_config &c)
     put(l.part, BH * (size_t)(l.S_max > 0 ? l.S_max : 1) * (c.head_dim + 2) * 4);
     put(l.flags, 256);
     put(l.qs, (size_t)(c.n_centroids < kBuildChunk ? c.n_centroids : kBuildChunk) * c.max_ctx * 4);
+    if (c.stream_window > 0) {
+        put(l.queue_n, 256);
+        put(l.queue, BG * Ct * 16);
+    }
     l.scratch_bytes = off;
     return l;
 }
@@ -130,6 +139,7 @@ int validate(const csa_config &c)
         return CSA_ERR_ARG;
     if ((int64_t)c.batch * c.n_q_heads > 65535) return CSA_ERR_ARG;  // grid.y
     if ((int64_t)c.batch * c.n_kv_heads > 65535) return CSA_ERR_ARG;  // grid.z
+    if (c.stream_window < 0) return CSA_ERR_ARG;
     return CSA_OK;
 }
 
@@ -149,6 +159,7 @@ int check_launch(csa_ctx *ctx)
 void choose_partition(csa_ctx *ctx, int n_pre)
 {
     const csa_config &c = ctx->cfg;
+    if (c.stream_window > 0) n_pre = c.max_ctx;  // appended keys enter the tables: cover every index
     int R = c.partition_keys;
     if (!R) {
         // the accumulation kernel runs R/16 threads per key range, so the wave count does not
@@ -182,11 +193,20 @@ int qmax_for(int m)
 // m * max|q| of 2^24: 512 equal bins over that span.
 void set_key_range(csa_ctx *ctx, int qabs_max)
 {
+    // scores of keys inserted later are only known to respect the admissible maximum
+    if (ctx->cfg.stream_window > 0) qabs_max = qmax_for(ctx->cfg.n_probe * ctx->cfg.n_subspaces);
     const uint32_t span = (uint32_t)(ctx->cfg.n_probe * ctx->cfg.n_subspaces) * (uint32_t)qabs_max;  // < 2^24
     ctx->key_lo = (1u << 24) - span;
     int sh = 0;
     while (((2u * span) >> sh) >= 512u) ++sh;
     ctx->key_sh = sh;
+}
+
+int window_start(const csa_ctx *ctx)
+{
+    if (ctx->cfg.stream_window <= 0) return ctx->n_pre;
+    const int ws = ctx->n - ctx->cfg.stream_window;
+    return ws > 0 ? ws : 0;
 }
 
 struct Prof {
@@ -332,6 +352,9 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
     if (e != hipSuccess) return hip_fail(ctx, e);
     if (hflags[0] & 1) return CSA_ERR_RANGE;
     set_key_range(ctx, hflags[1]);
+    if (c.stream_window > 0)
+        csa::launch_row_stats(ent, part_off, at<int32_t>(ctx->tables, l.row_cnt), at<int32_t>(ctx->tables, l.row_min),
+                              (int64_t)BG * S * c.n_centroids, l.Ls, ctx->PO, st);
     ctx->F = F;
     ctx->n_pre = ctx->n = n_pre;
     ctx->have_tables = true;
@@ -370,6 +393,10 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
     if (hflags[0] & 2) return CSA_ERR_ARG;
     if (hflags[0] & 1) return CSA_ERR_RANGE;
     set_key_range(ctx, hflags[1]);
+    if (c.stream_window > 0)
+        csa::launch_row_stats(at<void>(ctx->tables, l.ent), at<int32_t>(ctx->tables, l.part_off),
+                              at<int32_t>(ctx->tables, l.row_cnt), at<int32_t>(ctx->tables, l.row_min), n_rows, l.Ls,
+                              ctx->PO, st);
     ctx->F = c.score_frac_bits;
     ctx->n_pre = ctx->n = n_pre;
     ctx->have_tables = true;
@@ -399,10 +426,24 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
     if (ctx->n >= ctx->cfg.max_ctx) return CSA_ERR_CAPACITY;
     hipStream_t st = (hipStream_t)stream;
     Prof prof(ctx, st);
+    const csa_config &c = ctx->cfg;
+    const Layout &l = ctx->lay;
+    const bool streaming = c.stream_window > 0;
     prof.mark(7);
-    csa::launch_append(ctx->k_cache, ctx->v_cache, ctx->block_table, k_new_dev, v_new_dev,
-                       ctx->cfg.batch, ctx->cfg.n_kv_heads, ctx->n, ctx->cfg.max_ctx, st);
+    csa::launch_append(ctx->k_cache, ctx->v_cache, ctx->block_table, k_new_dev, v_new_dev, c.batch,
+                       c.n_kv_heads, ctx->n, c.max_ctx,
+                       streaming ? at<int32_t>(ctx->scratch, l.queue_n) : nullptr, st);
     prof.end(7);
+    if (streaming) {
+        prof.mark(9);
+        csa::launch_insert(k_new_dev, at<void>(ctx->tables, l.cent_t), at<void>(ctx->tables, l.ent),
+                           at<int32_t>(ctx->tables, l.part_off), at<int32_t>(ctx->tables, l.row_cnt),
+                           at<int32_t>(ctx->tables, l.row_min), at<int32_t>(ctx->scratch, l.queue_n),
+                           at<void>(ctx->scratch, l.queue), at<int32_t>(ctx->scratch, l.flags), c.batch,
+                           c.n_kv_heads, c.n_centroids, c.n_subspaces, c.list_len, l.Ls, ctx->Q, ctx->PO, ctx->F,
+                           qmax_for(c.n_probe * c.n_subspaces), ctx->n, st);
+        prof.end(9);
+    }
     ctx->n += 1;
     return check_launch(ctx);
 }
@@ -427,7 +468,10 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     int32_t *sel = sel_idx_dev ? sel_idx_dev : at<int32_t>(ctx->scratch, l.sel);
     int32_t *sel_count = sel_count_dev ? sel_count_dev : at<int32_t>(ctx->scratch, l.sel_count);
     float *part = at<float>(ctx->scratch, l.part);
-    const int S = csa::attention_splits(c.budget_k, ctx->P, ctx->n - ctx->n_pre);
+    // the always-attended recent window [ws, n): every appended key, or - with streaming updates -
+    // the last stream_window positions (older appended keys compete through the tables)
+    const int ws = window_start(ctx);
+    const int S = csa::attention_splits(c.budget_k, ctx->P, ctx->n - ws);
 
     Prof prof(ctx, st);
     prof.mark(0);
@@ -440,7 +484,7 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
                               c.n_centroids, S_sub, c.n_probe, G, ctx->P, ctx->nsub, ctx->PO, st);
     prof.end(1);
     csa::launch_accumulate(at<void>(ctx->tables, l.ent), rows, spans, cand_key, cand_bits, cand_cnt, hist, BH,
-                           Ct, l.Ls, M, G, ctx->R, ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, st);
+                           Ct, l.Ls, M, G, ctx->R, ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, ws, st);
     prof.end(2);
     csa::launch_threshold(cand_key, cand_cnt, sel, sel_count, thr, seg_par, hist, BH, c.budget_k, ctx->R,
                           ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, st);
@@ -449,7 +493,7 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
                      l.cand_keys, st);
     prof.end(4);
     csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, seg_par,
-                                part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ctx->n_pre, ctx->n,
+                                part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ws, ctx->n,
                                 c.max_ctx, S, ctx->P, st);
     prof.end(5);
     csa::launch_attention_merge(part, out_dev, BH, S, st);
@@ -474,19 +518,33 @@ int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev, const
     const int BH = c.batch * c.n_q_heads;
     void *seg_par = at<void>(ctx->scratch, l.seg_par);
     float *part = at<float>(ctx->scratch, l.part);
-    const int S = csa::attention_splits(c.budget_k, ctx->P, ctx->n - ctx->n_pre);
+    const int ws = window_start(ctx);
+    const int S = csa::attention_splits(c.budget_k, ctx->P, ctx->n - ws);
     Prof prof(ctx, st);
     prof.mark(8);
     csa::launch_range_offsets(sel, sel_count, seg_par, BH, c.budget_k, ctx->R, ctx->P, st);
     prof.end(8);
     prof.mark(5);
     csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, seg_par,
-                                part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ctx->n_pre, ctx->n,
+                                part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ws, ctx->n,
                                 c.max_ctx, S, ctx->P, st);
     prof.end(5);
     csa::launch_attention_merge(part, out_dev, BH, S, st);
     prof.end(6);
     return check_launch(ctx);
+}
+
+int csa_streaming_status(csa_ctx *ctx, void *stream)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
+    if (ctx->cfg.stream_window <= 0) return CSA_OK;
+    int32_t flag = 0;
+    hipError_t e = hipMemcpyAsync(&flag, at<int32_t>(ctx->scratch, ctx->lay.flags) + 2, 4, hipMemcpyDeviceToHost,
+                                  (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return flag ? CSA_ERR_RANGE : CSA_OK;
 }
 
 int csa_context_len(const csa_ctx *ctx, int32_t *n_pre, int32_t *n)
@@ -503,6 +561,7 @@ int csa_set_context_len(csa_ctx *ctx, int32_t n)
     if (!ctx) return CSA_ERR_ARG;
     if (!ctx->have_tables) return CSA_ERR_STATE;
     if (n < ctx->n_pre || n > ctx->cfg.max_ctx) return CSA_ERR_ARG;
+    if (ctx->cfg.stream_window > 0 && n != ctx->n) return CSA_ERR_STATE;  // the tables hold the appended keys
     ctx->n = n;
     return CSA_OK;
 }

@@ -300,12 +300,16 @@ void launch_attention_merge(const float *part, float *out, int n_heads, int S, h
 }
 
 // K/V append: row n of every (sequence, KV head).  grid B*Hkv, block 32 (16 lanes K, 16 lanes V).
+// zero_me (optional): a counter the following kernels start from zero (the insertion queue of the
+// streaming update), cleared here instead of with a memset node.
 template <bool PAGED>
 __global__ void k_append(uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
                          const int32_t *__restrict__ block_table, const uint16_t *__restrict__ kn,
-                         const uint16_t *__restrict__ vn, int n, int Hkv, int max_ctx)
+                         const uint16_t *__restrict__ vn, int n, int Hkv, int max_ctx,
+                         int32_t *__restrict__ zero_me)
 {
     const int bg = blockIdx.x, b = bg / Hkv, g = bg % Hkv;
+    if (zero_me && bg == 0 && threadIdx.x == 0) *zero_me = 0;
     int64_t row;
     if (PAGED) {
         const int page = block_table[(size_t)b * (max_ctx >> 4) + (n >> 4)];
@@ -320,14 +324,16 @@ __global__ void k_append(uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
 }
 
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
-                   int B, int Hkv, int n, int max_ctx, hipStream_t st)
+                   int B, int Hkv, int n, int max_ctx, int32_t *zero_me, hipStream_t st)
 {
     if (block_table)
         k_append<true><<<B * Hkv, 32, 0, st>>>((uint16_t *)kc, (uint16_t *)vc, block_table,
-                                               (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx);
+                                               (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx,
+                                               zero_me);
     else
         k_append<false><<<B * Hkv, 32, 0, st>>>((uint16_t *)kc, (uint16_t *)vc, nullptr,
-                                                (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx);
+                                                (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx,
+                                                zero_me);
 }
 
 }  // namespace csa

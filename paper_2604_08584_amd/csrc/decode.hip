@@ -339,7 +339,7 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
                                                    int32_t *__restrict__ seg_cnt,
                                                    uint32_t *__restrict__ hist_g, int C, int Ls,
                                                    int m, int G, int P, size_t cand_stride,
-                                                   uint32_t key_lo, int key_sh)
+                                                   uint32_t key_lo, int key_sh, int excl_from)
 {
     constexpr int NW = NT / kWave;
     constexpr int R = NT * 16;
@@ -415,9 +415,19 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     int4 a[4];
     uint32_t nib[4];
     unsigned long long packed = 0;
+    // key indices at or above excl_from (the always-attended recent window, which streaming updates
+    // may have put into the tables) are not candidates; only the last range(s) can hold any
+    const bool has_excl = p * R + R > excl_from;  // (uniform over the workgroup)
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         a[u] = ((const int4 *)s_acc)[u * NT + threadIdx.x];
+        if (has_excl) {
+            const int i0 = p * R + 4 * (u * NT + (int)threadIdx.x);
+            if (i0 + 0 >= excl_from) a[u].x = 0;
+            if (i0 + 1 >= excl_from) a[u].y = 0;
+            if (i0 + 2 >= excl_from) a[u].z = 0;
+            if (i0 + 3 >= excl_from) a[u].w = 0;
+        }
         nib[u] = (a[u].x != 0 ? 1u : 0u) | (a[u].y != 0 ? 2u : 0u) | (a[u].z != 0 ? 4u : 0u) |
                  (a[u].w != 0 ? 8u : 0u);
         packed |= (unsigned long long)__popc(nib[u]) << (16 * u);
@@ -465,7 +475,7 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
 void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *spans, uint32_t *cand_key,
                        uint32_t *cand_bits, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
                        int Ls, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
-                       int key_sh, hipStream_t st)
+                       int key_sh, int excl_from, hipStream_t st)
 {
     dim3 grid(P, n_heads);
     static bool attr = false;
@@ -477,7 +487,7 @@ void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *span
 #define CSA_ACC(NT_)                                                                              \
     k_accumulate<NT_><<<grid, NT_, (size_t)R * 4, st>>>((const uint32_t *)ent, rows, spans, cand_key, \
                                                         cand_bits, seg_cnt, hist_g, C, Ls, m, G, P,  \
-                                                        cand_stride, key_lo, key_sh)
+                                                        cand_stride, key_lo, key_sh, excl_from)
     switch (R) {
     case 1024: CSA_ACC(64); break;
     case 2048: CSA_ACC(128); break;

@@ -26,6 +26,11 @@ void launch_build_scores(const void *kc, const int32_t *block_table, const void 
                          int jc, int F, int qmax, hipStream_t st);
 void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc, int n_pre, int L,
                          int Ls, int Q, int PO, hipStream_t st);
+void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt, int32_t *row_min,
+                      int64_t n_rows, int Ls, int PO, hipStream_t st);
+void launch_insert(const void *k_new, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
+                   int32_t *row_min, int32_t *queue_n, void *queue, int32_t *flags, int B, int Hkv, int C,
+                   int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st);
 void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
                          int max_ctx, int n_pre, int S, hipStream_t st);
 
@@ -38,7 +43,7 @@ void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off
 void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *spans, uint32_t *cand_key,
                        uint32_t *cand_bits, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
                        int Ls, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
-                       int key_sh, hipStream_t st);
+                       int key_sh, int excl_from, hipStream_t st);
 void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t *sel, int32_t *sel_count,
                       uint32_t *thr, void *seg_par, const uint32_t *hist_g, int n_heads, int k, int R,
                       int P, size_t cand_stride, uint32_t key_lo, int key_sh, hipStream_t st);
@@ -57,6 +62,6 @@ void launch_range_offsets(const int32_t *sel, const int32_t *sel_count, void *se
                           int R, int P, hipStream_t st);
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st);
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
-                   int B, int Hkv, int n, int max_ctx, hipStream_t st);
+                   int B, int Hkv, int n, int max_ctx, int32_t *zero_me, hipStream_t st);
 
 }  // namespace csa

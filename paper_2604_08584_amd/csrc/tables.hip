@@ -374,6 +374,204 @@ void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc
     k_build_select<<<jc, kBsNT, 0, st>>>(qs, (uint32_t *)ent, part_off, n_pre, L, Ls, Q, PO);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Streaming updates (Sec. 3.3 (5)): per-row state, try test, insertion.
+// ---------------------------------------------------------------------------------------------
+
+// row_cnt[row] = valid entries of the row, row_min[row] = their smallest q (INT_MAX if none).
+// One wave per row.  grid ceil(n_rows / 4), block 256.
+__global__ __launch_bounds__(256) void k_row_stats(const uint32_t *__restrict__ ent,
+                                                   const int32_t *__restrict__ part_off,
+                                                   int32_t *__restrict__ row_cnt,
+                                                   int32_t *__restrict__ row_min, int64_t n_rows,
+                                                   int Ls, int PO)
+{
+    const int64_t row = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave;
+    if (row >= n_rows) return;
+    const int cnt = part_off[row * PO + PO - 1];
+    int mn = 0x7FFFFFFF;
+    for (int p = lane_id(); p < cnt; p += kWave) mn = min(mn, entry_q(ent[row * Ls + p]));
+    for (int o = 32; o > 0; o >>= 1) mn = min(mn, __shfl_xor(mn, o, kWave));
+    if (lane_id() == 0) {
+        row_cnt[row] = cnt;
+        row_min[row] = mn;
+    }
+}
+
+void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt, int32_t *row_min,
+                      int64_t n_rows, int Ls, int PO, hipStream_t st)
+{
+    k_row_stats<<<(unsigned)((n_rows + 3) / 4), 256, 0, st>>>((const uint32_t *)ent, part_off, row_cnt, row_min,
+                                                              n_rows, Ls, PO);
+}
+
+// Try test: lane j of block (x, s, bg) scores the new key of KV head bg against centroid (s, j)
+// - the fma chain and grid of the table build - and, if the row has a free slot or the score beats
+// the row minimum, queues (row, q) for insertion.  A score outside the grid range is clamped and
+// reported in flags[2].  cent_t is [bg][S][db/8][C][8]; k_new is [bg][128] bf16.
+// grid (ceil(C/256), S, B*Hkv), block 256.
+__global__ __launch_bounds__(256) void k_insert_scan(const uint16_t *__restrict__ k_new,
+                                                     const uint4 *__restrict__ cent_t,
+                                                     const int32_t *__restrict__ row_cnt,
+                                                     const int32_t *__restrict__ row_min,
+                                                     int32_t *__restrict__ queue_n,
+                                                     int4 *__restrict__ queue,
+                                                     int32_t *__restrict__ flags, int C, int S, int L,
+                                                     float up, int qmax)
+{
+    __shared__ float s_k[kHeadDim];
+    const int sub = blockIdx.y, bg = blockIdx.z;
+    const int db = kHeadDim / S, nch = db / 8;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (threadIdx.x < db)
+        s_k[threadIdx.x] = __uint_as_float((uint32_t)k_new[(size_t)bg * kHeadDim + sub * db + threadIdx.x] << 16);
+    __syncthreads();
+    const bool live = j < C;
+    const int jc = live ? j : C - 1;  // (tail lanes compute a duplicate and queue nothing)
+    const uint4 *ct = cent_t + ((size_t)bg * S + sub) * nch * C;
+    const int64_t row = ((int64_t)bg * S + sub) * C + jc;
+    const int cnt = row_cnt[row], mn = row_min[row];
+    uint4 wv[kHeadDim / 8];  // every load is requested before the first use
+#pragma unroll
+    for (int c = 0; c < kHeadDim / 8; ++c) wv[c] = c < nch ? ct[(size_t)c * C + jc] : make_uint4(0, 0, 0, 0);
+    float acc = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kHeadDim / 8; ++c) {
+        if (c < nch) {
+            const uint4 w = wv[c];
+            const float cf[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                                 bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(cf[e], s_k[c * 8 + e], acc);
+        }
+    }
+    float qf = rintf(acc * up);
+    if (!(fabsf(qf) <= (float)qmax)) {
+        atomicOr(flags + 2, 1);
+        qf = qf > 0.0f ? (float)qmax : -(float)qmax;  // (a NaN cannot occur: inputs are finite)
+    }
+    const int q = (int)qf;
+    // one counter update per wave
+    const bool take = live && (cnt < L || q > mn);
+    const uint64_t mask = __ballot(take);
+    if (mask) {
+        int base = 0;
+        if (lane_id() == __ffsll((unsigned long long)mask) - 1) base = atomicAdd(queue_n, __popcll(mask));
+        base = __builtin_amdgcn_readlane(base, __ffsll((unsigned long long)mask) - 1);
+        if (take) queue[base + mbcnt(mask)] = make_int4((int)row, q, cnt, mn);  // (the row's state travels along)
+    }
+}
+
+// Insertion: one workgroup per queued row.  The new key has the largest index so far, so in the
+// device layout (ascending key index) it goes to the end of the row; a full row first loses its
+// minimum - the entry with the smallest q, among equals the one with the largest index, i.e. the
+// last of them - and the entries behind it move up one slot.  The row's block offsets, count and
+// minimum are brought up to date.
+// grid: any (workgroups stride over the queue), block 256, dynamic LDS Ls * 4 bytes.
+__global__ __launch_bounds__(256) void k_insert_rows(uint32_t *__restrict__ ent,
+                                                     int32_t *__restrict__ part_off,
+                                                     int32_t *__restrict__ row_cnt,
+                                                     int32_t *__restrict__ row_min,
+                                                     const int32_t *__restrict__ queue_n,
+                                                     const int4 *__restrict__ queue, int L, int Ls,
+                                                     int Q, int PO, int idx_new)
+{
+    extern __shared__ uint32_t s_row[];
+    __shared__ int s_red[4];
+    const int n_items = *queue_n;
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int4 it = queue[item];
+        const int64_t row = it.x;
+        const int q_new = it.y, cnt = it.z;
+        uint32_t *re = ent + row * Ls;
+        int32_t *po = part_off + row * PO;
+        const uint32_t e_new = pack_entry(idx_new, q_new);
+        if (cnt < L) {
+            if (threadIdx.x == 0) {
+                re[cnt] = e_new;
+                row_cnt[row] = cnt + 1;
+                row_min[row] = min(it.w, q_new);
+            }
+            for (int u = threadIdx.x; u < PO; u += 256)
+                if ((int64_t)u * Q > idx_new) po[u] += 1;
+            continue;  // (uniform over the workgroup)
+        }
+        const int mn = it.w;
+        __syncthreads();  // the previous item's LDS reads are done
+        // the row, 16 bytes per lane and load (Ls is a multiple of 4; slots >= L hold zeros)
+        int pmin = -1;
+        for (int p4 = threadIdx.x; p4 * 4 < L; p4 += 256) {
+            const uint4 v = *(const uint4 *)(re + p4 * 4);
+            *(uint4 *)(s_row + p4 * 4) = v;
+            const uint32_t ev[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (p4 * 4 + i < L && entry_q(ev[i]) == mn) pmin = p4 * 4 + i;  // (ascending: the last match stays)
+        }
+        for (int o = 32; o > 0; o >>= 1) pmin = max(pmin, __shfl_xor(pmin, o, kWave));
+        if (lane_id() == 0) s_red[threadIdx.x / kWave] = pmin;
+        __syncthreads();
+        pmin = max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3]));
+        if (pmin < 0) continue;  // (cannot happen: row_min is the minimum of a full row)
+        // the evicted entry's block = the number of block boundaries u >= 1 at or before pmin
+        // (offsets are non-decreasing); counted in parallel: one round of loads, no dependent chain
+        int n_le = 0;
+        for (int u = 1 + threadIdx.x; u < PO; u += 256) n_le += po[u] <= pmin ? 1 : 0;
+        n_le = wave_sum(n_le);
+        __syncthreads();  // s_red was read by every thread
+        if (lane_id() == 0) s_red[threadIdx.x / kWave] = n_le;
+        __syncthreads();
+        const int ue = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+        // entries behind the evicted one move up a slot, the new entry takes the last slot
+        int new_min = q_new;
+        for (int p4 = threadIdx.x; p4 * 4 < L; p4 += 256) {
+            uint32_t ov[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int p = p4 * 4 + i;
+                uint32_t e = 0u;
+                if (p < L) {
+                    e = p < pmin ? s_row[p] : (p + 1 < L ? s_row[p + 1] : e_new);
+                    new_min = min(new_min, entry_q(e));
+                }
+                ov[i] = e;
+            }
+            if (p4 * 4 + 3 >= pmin) *(uint4 *)(re + p4 * 4) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
+        }
+        for (int o = 32; o > 0; o >>= 1) new_min = min(new_min, __shfl_xor(new_min, o, kWave));
+        __syncthreads();  // s_red was read by every thread
+        if (lane_id() == 0) s_red[threadIdx.x / kWave] = new_min;
+        __syncthreads();
+        if (threadIdx.x == 0) row_min[row] = min(min(s_red[0], s_red[1]), min(s_red[2], s_red[3]));
+        // offsets: one entry fewer before every block after the evicted one's, one more before
+        // every block that starts above the new index
+        for (int u = threadIdx.x; u < PO; u += 256) {
+            const int d = ((int64_t)u * Q > idx_new ? 1 : 0) - (u > ue ? 1 : 0);
+            if (d) po[u] += d;
+        }
+    }
+}
+
+void launch_insert(const void *k_new, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
+                   int32_t *row_min, int32_t *queue_n, void *queue, int32_t *flags, int B, int Hkv, int C,
+                   int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st)
+{
+    static bool attr = false;
+    if (!attr) {
+        (void)hipFuncSetAttribute((const void *)k_insert_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 4);
+        attr = true;
+    }
+    dim3 grid((C + 255) / 256, S, B * Hkv);
+    k_insert_scan<<<grid, 256, 0, st>>>((const uint16_t *)k_new, (const uint4 *)cent_t, row_cnt, row_min, queue_n,
+                                        (int4 *)queue, flags, C, S, L, ldexpf(1.0f, F), qmax);
+    // the queue length is only known on the device: enough workgroups for one row each in the
+    // usual case (a few percent of the rows take a new key), striding when there are more
+    const int64_t n_rows = (int64_t)B * Hkv * S * C;
+    const unsigned wgs = (unsigned)(n_rows < 16384 ? n_rows : 16384);
+    k_insert_rows<<<wgs, 256, (size_t)Ls * 4, st>>>((uint32_t *)ent, part_off, row_cnt, row_min, queue_n,
+                                                    (const int4 *)queue, L, Ls, Q, PO, idx_new);
+}
+
 // max over prefill keys and subspaces of ||k^(s)||^2 (nch 16-byte chunks per subspace), as the bit
 // pattern of a non-negative fp32 (atomicMax on int).  Used to pick the score grid.  out must be
 // zeroed.

@@ -12,8 +12,8 @@ from paper_2604_08584_amd.workload import Workload, make_inputs, paginate
 TOL_OUT = 2e-2   # max-abs tolerance on attention outputs (bf16 inputs, fp32 accumulation)
 
 
-def cfg_kwargs(w: Workload, F: int, partition_keys: int = 0):
-    return dict(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, n_centroids=w.C,
+def cfg_kwargs(w: Workload, F: int, partition_keys: int = 0, stream_window: int = 0):
+    return dict(stream_window=stream_window, batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, n_centroids=w.C,
                 list_len=w.L, n_probe=w.m, budget_k=w.k, max_ctx=w.max_ctx, page_size=w.page_size,
                 score_frac_bits=F, partition_keys=partition_keys, n_subspaces=w.n_sub)
 
@@ -22,8 +22,9 @@ class Case:
     """One workload instantiated on the GPU, with host copies for the oracle."""
 
     def __init__(self, w: Workload, seed=0, F=14, partition_keys=0, gen_device="cpu",
-                 kmeans_sample=None):
+                 kmeans_sample=None, stream_window=0):
         self.w, self.F = w, F
+        self.stream_window = stream_window   # > 0: appended keys are try-inserted into the tables
         inp = make_inputs(w, seed=seed, device=gen_device, kmeans_sample=kmeans_sample)
         self.inp = {k: v.cuda() for k, v in inp.items()}
         # logical (contiguous) host copies for the oracle; appended rows are filled in as we go
@@ -36,7 +37,7 @@ class Case:
         else:
             self.k_store, self.v_store, self.block_table = self.inp["k_cache"], self.inp["v_cache"], None
         self.ctx = binding.Context(self.k_store, self.v_store, self.block_table,
-                                   **cfg_kwargs(w, F, partition_keys))
+                                   **cfg_kwargs(w, F, partition_keys, stream_window))
         self.tables = {}   # (b, g) -> (idx, score) numpy, canonical
         self.t = 0         # appended so far
 
@@ -76,14 +77,40 @@ class Case:
         self.import_tables(idx, score)
 
     # ---- steps
-    def append(self, count=1):
+    def append(self, count=1, groups=None):
+        """Appends on the GPU and mirrors it on the host; with streaming updates the oracle's
+        try-insert is applied to the host copies of the tables of `groups` (default: all (b, g);
+        those tables must have been exported before the first append)."""
+        w = self.w
         for _ in range(count):
             kn, vn = self.inp["k_new"][self.t], self.inp["v_new"][self.t]
             self.ctx.append_kv(kn, vn)
-            pos = self.w.n_pre + self.t
-            self.K_host[:, :, pos] = oracle.bf16_bits(kn)
+            pos = w.n_pre + self.t
+            kb = oracle.bf16_bits(kn)
+            self.K_host[:, :, pos] = kb
             self.V_host[:, :, pos] = oracle.bf16_bits(vn)
+            if self.stream_window:
+                for (b, g) in (groups if groups is not None else
+                               [(b, g) for b in range(w.batch) for g in range(w.n_kv_heads)]):
+                    idx, score = self.tables[(b, g)]
+                    oracle.try_insert(idx, score, self.cent_host[b, g], np.ascontiguousarray(kb[b, g]), pos, self.F)
             self.t += 1
+
+    def export_all(self):
+        for b in range(self.w.batch):
+            for g in range(self.w.n_kv_heads):
+                self.export(b, g)
+
+    def check_tables(self, b, g):
+        """The GPU's tables (exported now) against the host copy kept up to date by the oracle."""
+        idx, score = self.ctx.export_tables(b, g)
+        want_idx, want_score = self.tables[(b, g)]
+        assert np.array_equal(idx.cpu().numpy(), want_idx), f"table indices of ({b},{g}) differ"
+        assert np.array_equal(score.cpu().numpy(), want_score), f"table scores of ({b},{g}) differ"
+
+    def window_start(self):
+        n = self.w.n_pre + self.t
+        return max(0, n - self.stream_window) if self.stream_window else self.w.n_pre
 
     def decode(self, step):
         q = self.inp["q_steps"][step]
@@ -103,7 +130,7 @@ class Case:
             idx, score = self.export(b, g)
             items.append(dict(q=np.ascontiguousarray(qh[b, h]), cent=self.cent_host[b, g], tbl_idx=idx,
                               tbl_score=score, K=self.K_host[b, g], V=self.V_host[b, g]))
-        rows, sel, cnt, out, _ = oracle.decode_items(items, w.m, w.k, w.n_pre, n)
+        rows, sel, cnt, out, _ = oracle.decode_items(items, w.m, w.k, self.window_start(), n)
         return rows, sel, cnt, out
 
     def check_step(self, step, heads=None):
@@ -145,7 +172,7 @@ class Case:
         for b, h in heads:
             g = h // w.group
             want = oracle.attend_selected(np.ascontiguousarray(qh[b, h]), self.K_host[b, g], self.V_host[b, g],
-                                          sel[b, h][:cnt[b, h]], w.n_pre, n)
+                                          sel[b, h][:cnt[b, h]], self.window_start(), n)
             err = float(np.abs(out[b, h] - want).max())
             assert np.isfinite(out[b, h]).all() and err <= TOL_OUT, f"{w.name} reuse step {step} head ({b},{h}): {err}"
             worst = max(worst, err)

@@ -240,6 +240,49 @@ def test_search_period_steps_reuse_the_index_set(paged):
     case.check_reuse_step(5, mine, np.zeros_like(cnt), pass_buffers=True)
 
 
+@pytest.mark.parametrize("S,L,part,paged", [(1, 200, 1024, False), (4, 96, 2048, True), (1, 700, 8192, False)])
+def test_streaming_updates_try_insert_and_recent_window(S, L, part, paged):
+    """stream_window = 8: every appended key is try-inserted into the Top-L lists on the GPU and,
+    by the oracle, into the host copy; after 1, 9 and 30 appends the exported tables are identical
+    and decode steps (window = last 8 positions, excluded from the Top-K candidates) match.  L = 700
+    with n_pre = 600 starts from lists with free slots; the other cases evict."""
+    n_pre = 600 if L == 700 else 3000
+    w = small(f"stream{S}", n_q_heads=4, n_kv_heads=2, n_pre=n_pre, C=24, L=L, m=2, k=150, steps=32,
+              n_sub=S, page_size=16 if paged else 0)
+    case = Case(w, seed=20 + S, F=12, partition_keys=part, stream_window=8)
+    case.build_on_gpu()
+    case.export_all()
+    for g in range(2):
+        o_idx, o_score, _ = case.oracle_tables(0, g)
+        assert np.array_equal(case.tables[(0, g)][0], o_idx) and np.array_equal(case.tables[(0, g)][1], o_score)
+    case.check_step(0)
+    done = 0
+    for upto in (1, 9, 30):
+        case.append(upto - done)
+        done = upto
+        for g in range(2):
+            case.check_tables(0, g)
+        case.check_step(upto)
+    binding.csa_streaming_status(case.ctx.ctx)                 # no score left the grid
+    # the newest keys really are in the tables, and rewinding is refused
+    assert (case.tables[(0, 0)][0] >= w.n_pre).any()
+    with pytest.raises(binding.CsaError) as e:
+        binding.csa_set_context_len(case.ctx.ctx, w.n_pre)
+    assert e.value.status == binding.CSA_ERR_STATE
+
+
+def test_streaming_updates_report_scores_that_leave_the_grid():
+    w = small("stream_ovf", n_q_heads=4, n_kv_heads=1, n_pre=500, C=8, L=64, m=2, k=50, steps=2)
+    case = Case(w, seed=31, F=-1, stream_window=4)
+    case.build_on_gpu()
+    binding.csa_streaming_status(case.ctx.ctx)
+    huge = (case.inp["k_new"][0].float() * 64).to(torch.bfloat16)   # far outside the prefill keys' norms
+    case.ctx.append_kv(huge, case.inp["v_new"][0])
+    with pytest.raises(binding.CsaError) as e:
+        binding.csa_streaming_status(case.ctx.ctx)
+    assert e.value.status == binding.CSA_ERR_RANGE
+
+
 def test_repeated_steps_are_deterministic():
     w = small("det", n_q_heads=8, n_kv_heads=2, steps=1, pre_appended=9)
     case = Case(w, seed=9, F=12, partition_keys=1024)

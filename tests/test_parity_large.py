@@ -85,3 +85,21 @@ def test_paper_default_geometry_full_size():
     for step in range(2):
         print("paper_s8 step", step, "err", case.check_step(step, heads))
         case.append(1)
+
+
+def test_cfg2_streaming_updates_full_size():
+    """Config 2's shape with streaming updates (recent window R = 32): 40 appended keys are
+    try-inserted on the GPU and by the oracle into KV head 5's tables; tables and sampled decode
+    steps (before the window is full, and after keys have left it) must match."""
+    w = _light("cfg2", 41)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=16 * w.C, stream_window=32)
+    case.build_on_gpu()
+    case.export(0, 5)
+    heads = [(0, 20), (0, 21), (0, 23)]
+    print("stream step 0 err", case.check_step(0, heads))
+    for upto in (3, 40):
+        case.append(upto - case.t, groups=[(0, 5)])
+        case.check_tables(0, 5)
+        print("stream step", upto, "err", case.check_step(upto, heads))
+    idx = case.tables[(0, 5)][0]
+    print("rows holding appended keys:", int((idx >= w.n_pre).any(axis=1).sum()), "of", idx.shape[0])
