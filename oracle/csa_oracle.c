@@ -241,6 +241,94 @@ void oracle_kmeans(const float *x, int64_t n, int d, int C, int iters, const dou
     free(sum); free(cnt); free(xn); free(c); free(dist); free(asg);
 }
 
+/*
+ * The same clustering with the centroids held in bf16 between the steps - the form in which
+ * the tables' build consumes them - split into its two parts so that each can be checked on its
+ * own: k-means++ seeding (every seed is a normalised data point, rounded to bf16; the next one is
+ * drawn with probability proportional to the squared distance to the nearest seed so far, from the
+ * uniform u_seed[j]) and one Lloyd step (cosine assignment against the bf16 centroids, ties to
+ * the lowest centroid; centroid <- mean of its normalised members, re-normalised, rounded to
+ * bf16; an empty cluster keeps its centroid).
+ *   x [n][d] fp32 (any scale), cent bf16 [C][d].
+ *   oracle_kmeans_step also returns, per point, its assignment and the gap between its best and
+ *   second-best cosine (how close the decision was), and the mean best cosine.
+ */
+void oracle_kmeans_seed(const float *x, int64_t n, int d, int C, const double *u_seed, uint16_t *cent)
+{
+    double *xn = (double *)malloc(sizeof(double) * (size_t)d);
+    double *dist = (double *)malloc(sizeof(double) * (size_t)n);
+    for (int64_t i = 0; i < n; ++i) dist[i] = INFINITY;
+    int64_t pick = (int64_t)(u_seed[0] * (double)n);
+    if (pick >= n) pick = n - 1;
+    for (int j = 0; j < C; ++j) {
+        /* seed j = the normalised point `pick`, rounded to bf16 */
+        double nn = 0.0;
+        for (int t = 0; t < d; ++t) nn += (double)x[pick * d + t] * x[pick * d + t];
+        nn = sqrt(nn);
+        for (int t = 0; t < d; ++t) cent[(int64_t)j * d + t] = f32_to_bf16(nn > 0 ? (float)(x[pick * d + t] / nn) : 0.0f);
+        if (j + 1 == C) break;
+        /* fold it into the nearest-seed distances, draw the next one */
+        double tot = 0.0;
+        for (int64_t i = 0; i < n; ++i) {
+            double ni = 0.0, s = 0.0;
+            for (int t = 0; t < d; ++t) ni += (double)x[i * d + t] * x[i * d + t];
+            ni = sqrt(ni);
+            for (int t = 0; t < d; ++t) {
+                double df = (ni > 0 ? x[i * d + t] / ni : 0.0) - (double)bf16_to_f32(cent[(int64_t)j * d + t]);
+                s += df * df;
+            }
+            if (s < dist[i]) dist[i] = s;
+            tot += dist[i];
+        }
+        double target = u_seed[j + 1] * tot, run = 0.0;
+        pick = n - 1;
+        for (int64_t i = 0; i < n; ++i) {
+            run += dist[i];
+            if (run > target) { pick = i; break; }
+        }
+    }
+    free(xn); free(dist);
+}
+
+double oracle_kmeans_step(const float *x, int64_t n, int d, int C, const uint16_t *cent_in,
+                          uint16_t *cent_out, int32_t *assign, double *gap)
+{
+    double *sum = (double *)calloc((size_t)C * d, sizeof(double));
+    int64_t *cnt = (int64_t *)calloc((size_t)C, sizeof(int64_t));
+    double *xn = (double *)malloc(sizeof(double) * (size_t)d);
+    double cos_sum = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double nn = 0.0;
+        for (int t = 0; t < d; ++t) nn += (double)x[i * d + t] * x[i * d + t];
+        nn = sqrt(nn);
+        for (int t = 0; t < d; ++t) xn[t] = nn > 0 ? x[i * d + t] / nn : 0.0;
+        int best = 0;
+        double b1 = -INFINITY, b2 = -INFINITY;
+        for (int j = 0; j < C; ++j) {
+            double s = 0.0;
+            for (int t = 0; t < d; ++t) s += xn[t] * (double)bf16_to_f32(cent_in[(int64_t)j * d + t]);
+            if (s > b1) { b2 = b1; b1 = s; best = j; }
+            else if (s > b2) b2 = s;
+        }
+        assign[i] = best;
+        if (gap) gap[i] = b1 - b2;
+        cos_sum += b1;
+        cnt[best]++;
+        for (int t = 0; t < d; ++t) sum[(int64_t)best * d + t] += xn[t];
+    }
+    for (int j = 0; j < C; ++j) {
+        double nn = 0.0;
+        for (int t = 0; t < d; ++t) nn += sum[(int64_t)j * d + t] * sum[(int64_t)j * d + t];
+        nn = sqrt(nn);
+        for (int t = 0; t < d; ++t)
+            cent_out[(int64_t)j * d + t] = (cnt[j] == 0 || nn == 0.0)
+                                               ? cent_in[(int64_t)j * d + t]
+                                               : f32_to_bf16((float)(sum[(int64_t)j * d + t] / nn));
+    }
+    free(sum); free(cnt); free(xn);
+    return n > 0 ? cos_sum / (double)n : 0.0;
+}
+
 /* fp32 -> bf16 rounding of a centroid matrix, done once after clustering */
 void oracle_round_bf16(const float *x, int64_t n, uint16_t *out)
 {

@@ -38,6 +38,7 @@ def lib():
         _lib.oracle_select_keys.restype = C.c_int64
         _lib.oracle_decode_items.restype = C.c_int
         _lib.oracle_try_insert.restype = C.c_double
+        _lib.oracle_kmeans_step.restype = C.c_double
     return _lib
 
 
@@ -74,6 +75,31 @@ def kmeans(x, n_centroids, iters, u_seed):
     lib().oracle_kmeans(_p(x), C.c_int64(n), C.c_int(d), C.c_int(n_centroids), C.c_int(iters),
                         _p(u_seed), _p(cent), _p(obj))
     return cent, obj
+
+
+def kmeans_seed(x, n_centroids, u_seed):
+    """k-means++ seeds (bf16 bit patterns [C][d]) of the rows of x [n][d] fp32."""
+    x = np.ascontiguousarray(x, np.float32)
+    u_seed = np.ascontiguousarray(u_seed, np.float64)
+    assert u_seed.shape[0] >= n_centroids
+    n, d = x.shape
+    cent = np.empty((n_centroids, d), np.uint16)
+    lib().oracle_kmeans_seed(_p(x), C.c_int64(n), C.c_int(d), C.c_int(n_centroids), _p(u_seed), _p(cent))
+    return cent
+
+
+def kmeans_step(x, cent):
+    """One Lloyd step from bf16 centroids.  Returns (new bf16 centroids, assignment [n], top-2 cosine
+    gap [n], mean best cosine)."""
+    x = np.ascontiguousarray(x, np.float32)
+    n, d = x.shape
+    n_c = cent.shape[0]
+    out = np.empty((n_c, d), np.uint16)
+    asg = np.empty(n, np.int32)
+    gap = np.empty(n, np.float64)
+    mc = lib().oracle_kmeans_step(_p(x), C.c_int64(n), C.c_int(d), C.c_int(n_c), _p(cent), _p(out), _p(asg),
+                                  _p(gap))
+    return out, asg, gap, mc
 
 
 def round_bf16(x):

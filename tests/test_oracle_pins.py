@@ -629,6 +629,41 @@ def test_kmeans_objective_monotone_unit_norm_and_recovers_separated_clusters():
     assert sorted((cent2 @ dirs.T).argmax(1).tolist()) == list(range(n_c))
 
 
+def test_kmeans_in_bf16_steps_seeds_are_data_points_and_a_step_is_the_mean_direction():
+    """The two-part form the GPU path is checked against.  Seeds: each is a normalised data point
+    (rounded to bf16); with two tight, far-apart groups and the first seed in one of them, the D^2
+    draw must land in the other for any u that is not astronomically small.  Step: on four
+    well-separated directions the assignment is the obvious one, the new centroid of a cluster is
+    the bf16-rounded direction of the sum of its normalised members, an empty cluster keeps its
+    centroid, and a second step does not lower the mean cosine."""
+    rng = np.random.default_rng(50)
+    d = 32
+    a, b = np.eye(d, dtype=np.float32)[0], np.eye(d, dtype=np.float32)[5]
+    x = np.r_[[a * s for s in rng.uniform(1, 3, 20)], [b * s for s in rng.uniform(1, 3, 20)]].astype(np.float32)
+    x += 1e-3 * rng.standard_normal(x.shape).astype(np.float32)
+    for u1 in (1e-4, 0.3, 0.999):
+        seeds = f32(oracle.kmeans_seed(x, 2, np.array([0.1, u1])))       # first seed: a point of group a
+        assert abs(seeds[0, 0]) > 0.99 and abs(seeds[1, 5]) > 0.99
+    xn = x / np.linalg.norm(x, axis=1, keepdims=True)
+    seeds = oracle.kmeans_seed(x, 2, np.array([0.6, 0.5]))                # first seed: a point of group b
+    assert any(np.array_equal(f32(seeds[0]), rand_round(r)) for r in xn[20:])
+    # one step on 4 directions + an unused fifth centroid
+    dirs = np.eye(d, dtype=np.float32)[[1, 7, 12, 30]]
+    pts = np.concatenate([dirs[c] * rng.uniform(0.5, 2, (25, 1)) + 0.05 * rng.standard_normal((25, d))
+                          for c in range(4)]).astype(np.float32)
+    cent0 = to_bits(np.r_[dirs, -np.ones((1, d), np.float32) * 0.125])
+    cent1, asg, gap, mc = oracle.kmeans_step(pts, cent0)
+    assert asg.tolist() == sum([[c] * 25 for c in range(4)], [])
+    pn = pts.astype(np.float64) / np.linalg.norm(pts.astype(np.float64), axis=1, keepdims=True)
+    for c in range(4):
+        m = pn[25 * c:25 * c + 25].sum(0)
+        assert np.array_equal(f32(cent1[c]), rand_round((m / np.linalg.norm(m)).astype(np.float32)))
+    assert np.array_equal(cent1[4], cent0[4]) and (gap > 0).all()
+    assert mc == pytest.approx(float(np.mean([pn[i] @ f32(cent0[asg[i]]) for i in range(100)])), rel=1e-9)
+    _, _, _, mc2 = oracle.kmeans_step(pts, cent1)
+    assert mc2 >= mc - 1e-9
+
+
 def test_kmeans_single_centroid_is_the_normalised_mean_direction():
     rng = np.random.default_rng(18)
     x = rng.standard_normal((200, 8)) + 3.0
