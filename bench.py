@@ -47,6 +47,11 @@ def main():
     ap.add_argument("--stream-window", type=int, default=0,
                     help="R > 0: streaming updates - csa_append_kv try-inserts every new key into the "
                          "tables and only the last R positions are attended unconditionally")
+    ap.add_argument("--cluster", action="store_true",
+                    help="measure the offline query clustering (csa_cluster_queries) of ONE sequence of "
+                         "the config instead of the decode step: seeding + Lloyd steps, and the "
+                         "assignment kernel against the bf16 matrix-core peak")
+    ap.add_argument("--cluster-iters", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies before the timed region, "
@@ -67,6 +72,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = "cuda"
     base = CONFIGS[args.config]
+    if args.cluster:
+        return cluster_bench(args, base)
     K, W = args.steps, args.warmup
     streaming = args.stream_window > 0
     # with streaming updates the tables keep the appended keys, so the context cannot be rewound
@@ -211,6 +218,58 @@ def main():
     if not args.no_cpu_baseline and not streaming:
         result["cpu_baseline"] = cpu_baseline(ctx, w, inp, args.cpu_seconds)
     print(json.dumps(result, ensure_ascii=False), flush=True)
+
+
+def cluster_bench(args, w):
+    """Offline clustering of one sequence's prefill queries (Sec. 3.2 (1)): k-means++ seeding plus
+    `--cluster-iters` Lloyd steps for every KV head and subspace.  Prints one JSON line."""
+    import numpy as np
+    import torch
+    from paper_2604_08584_amd import binding
+    from paper_2604_08584_amd.workload import _gen, _mixture, stream_seed
+    Hq, Hkv, G, S, C, d = w.n_q_heads, w.n_kv_heads, w.group, w.n_sub, w.C, w.head_dim
+    iters = args.cluster_iters
+    q = torch.empty(1, Hq, w.n_pre, d, dtype=torch.bfloat16, device="cuda")
+    for g in range(Hkv):     # the workload's prefill-query recipe (same means as the keys, shifted)
+        gen = lambda st: _gen(q.device, stream_seed(args.seed, w.name, 0, g, st))
+        means = torch.randn(w.n_comp, d, generator=gen("k_means"), device="cuda")
+        u = torch.randn(d, generator=gen("offset"), device="cuda")
+        u = 3.0 * u / u.norm()
+        q[0, g * G:(g + 1) * G] = _mixture(means, G * w.n_pre, gen("Qpre"), shift=u).to(torch.bfloat16).view(G, w.n_pre, d)
+    ctx = binding.csa_create(batch=1, n_q_heads=Hq, n_kv_heads=Hkv, n_centroids=C, list_len=w.L, n_probe=w.m,
+                             budget_k=w.k, max_ctx=w.max_ctx, n_subspaces=S)
+    work = torch.empty(binding.csa_cluster_workspace_bytes(ctx, w.n_pre), dtype=torch.uint8, device="cuda")
+    cent = torch.empty(1, Hkv, S, C, d // S, dtype=torch.bfloat16, device="cuda")
+    mean_cos = torch.zeros(1, Hkv, S, max(iters, 1), device="cuda")
+    useed = np.random.default_rng(args.seed).uniform(size=(1, Hkv, S, C)).astype(np.float32)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    binding.csa_cluster_queries(ctx, q, w.n_pre, 0, useed, None, cent, None, None, work)   # seeding only
+    torch.cuda.synchronize()
+    t_seed = time.perf_counter() - t0
+    seeds = cent.clone()
+    t0 = time.perf_counter()
+    binding.csa_cluster_queries(ctx, q, w.n_pre, iters, None, seeds, cent, mean_cos, None, work)
+    torch.cuda.synchronize()
+    t_lloyd = time.perf_counter() - t0
+    n_pool = G * w.n_pre
+    flops = 2.0 * n_pool * C * (d // S) * Hkv * S * iters          # the assignment contraction
+    mc = mean_cos.mean(dim=(0, 1, 2)).cpu().numpy()
+    binding.csa_destroy(ctx)
+    peak = 2500.0
+    print(json.dumps({
+        "metric": "offline query clustering of one sequence (s): k-means++ seeding + Lloyd steps",
+        "value": round(t_seed + t_lloyd, 4), "unit": "s", "n_gpus": 1, "higher_is_better": False,
+        "dtype": "bf16 operands, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "n_pre": w.n_pre, "subspaces": S,
+                   "C": C, "iters": iters, "points_per_problem": n_pool},
+        "seeding_s": round(t_seed, 4), "lloyd_s": round(t_lloyd, 4),
+        "mean_cos_first_last": [round(float(mc[0]), 4), round(float(mc[-1]), 4)],
+        "roofline": {"kernel": "k_km_assign (+ k_km_finish)", "bound": "mfma",
+                     "achieved": round(flops / t_lloyd / 1e12, 2), "peak": peak, "unit": "TFLOP/s",
+                     "frac": round(flops / t_lloyd / 1e12 / peak, 4), "traffic": None,
+                     "measured": "wall clock over all Lloyd steps of all problems, synchronised"},
+    }), flush=True)
 
 
 def cpu_baseline(ctx, w, inp, budget_s):

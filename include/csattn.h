@@ -116,6 +116,35 @@ int csa_bind(csa_ctx *ctx, void *tables_dev, size_t tables_bytes, void *scratch_
 int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, void *stream);
 
 /*
+ * Query-centric centroids, Sec. 3.2 (1): for every KV head and subspace, cosine k-means over the
+ * l2-normalised prefill query sub-vectors of the G query heads of the group ("per KV-head group",
+ * Sec. 4.4), k-means++ seeding, `iters` Lloyd steps over all points (the paper's mini-batch size is
+ * not stated; the full batch is used).  Centroids are unit vectors held in bf16 between the steps:
+ * each step assigns every point to the centroid of largest inner product (bf16 operands on the
+ * matrix cores, fp32 accumulation; ties to the lower centroid) and replaces a centroid by the
+ * re-normalised sum of its normalised members, rounded to bf16 (an empty cluster keeps its
+ * centroid).  The member sums are added with fp32 atomics, so the last bit of a centroid may differ
+ * between runs.
+ *   q_pre_dev          bf16 [B][Hq][n_pre][d]: the prefill queries.
+ *   u_seed             HOST fp32 [B][Hkv][S][C], uniforms in [0, 1) that drive the seeding: point
+ *                      floor(u_0 * n) first, then each next seed is the first point whose running
+ *                      sum of squared distances to the nearest seed so far exceeds u_j * total.
+ *                      NULL if init_centroids_dev is given.
+ *   init_centroids_dev bf16 [B][Hkv][S][C][d/S] starting centroids instead of the seeding, or NULL.
+ *   centroids_out_dev  bf16 [B][Hkv][S][C][d/S]: the input csa_build_tables expects.
+ *   mean_cos_dev       fp32 [B][Hkv][S][max(iters,1)]: mean cosine of the points to their assigned
+ *                      centroid in each step's assignment (non-decreasing up to rounding); or NULL.
+ *   assign_dev         int32 [B][Hkv][S][G*n_pre]: assignments of the last step; or NULL.
+ *   work_dev           scratch of csa_cluster_workspace_bytes bytes, 256-byte aligned.
+ * Needs no bound buffers and no tables.  Enqueues on `stream`; does not synchronise.
+ */
+int csa_cluster_workspace_bytes(const csa_ctx *ctx, int32_t n_pre, size_t *bytes);
+int csa_cluster_queries(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters,
+                        const float *u_seed, const void *init_centroids_dev, void *centroids_out_dev,
+                        float *mean_cos_dev, int32_t *assign_dev, void *work_dev, size_t work_bytes,
+                        void *stream);
+
+/*
  * Tables in the canonical layout, one KV head at a time or all at once:
  *   idx   int32 [S*C][L], score fp32 [S*C][L]; each row sorted by (score desc, idx asc)
  *   (Sec. 3.1 (iii) "sorted by score"); unused tail slots idx = -1, score = 0.

@@ -46,6 +46,8 @@ def lib() -> C.CDLL:
         "csa_workspace_bytes": (C.c_int, [vp, C.POINTER(sz), C.POINTER(sz)]),
         "csa_bind": (C.c_int, [vp, vp, sz, vp, sz, vp, vp, vp]),
         "csa_build_tables": (C.c_int, [vp, vp, i32, vp]),
+        "csa_cluster_workspace_bytes": (C.c_int, [vp, i32, C.POINTER(sz)]),
+        "csa_cluster_queries": (C.c_int, [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]),
         "csa_export_tables": (C.c_int, [vp, i32, i32, vp, vp, vp]),
         "csa_import_tables": (C.c_int, [vp, vp, vp, vp, i32, vp]),
         "csa_append_kv": (C.c_int, [vp, vp, vp, vp]),
@@ -70,6 +72,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTED = ("csa_create", "csa_destroy", "csa_workspace_bytes", "csa_bind", "csa_build_tables",
+            "csa_cluster_workspace_bytes", "csa_cluster_queries",
             "csa_export_tables", "csa_import_tables", "csa_append_kv", "csa_decode_step",
             "csa_decode_step_reuse", "csa_streaming_status",
             "csa_context_len", "csa_set_context_len", "csa_score_frac_bits",
@@ -129,6 +132,28 @@ def csa_bind(ctx, tables, scratch, k_cache, v_cache, block_table=None):
 
 def csa_build_tables(ctx, centroids, n_pre):
     _check(lib().csa_build_tables(ctx, _ptr(centroids), n_pre, _stream()), "csa_build_tables")
+
+
+def csa_cluster_workspace_bytes(ctx, n_pre) -> int:
+    b = C.c_size_t()
+    _check(lib().csa_cluster_workspace_bytes(ctx, n_pre, C.byref(b)), "csa_cluster_workspace_bytes")
+    return b.value
+
+
+def csa_cluster_queries(ctx, q_pre, n_pre, iters, u_seed, init_centroids, centroids_out, mean_cos=None,
+                        assign=None, work=None):
+    """u_seed: host numpy float32 array (or None when init_centroids is given)."""
+    import numpy as np
+    if work is None:
+        work = torch.empty(csa_cluster_workspace_bytes(ctx, n_pre), dtype=torch.uint8, device=q_pre.device)
+    useed_p = None
+    if u_seed is not None:
+        u_seed = np.ascontiguousarray(u_seed, np.float32)
+        useed_p = u_seed.ctypes.data_as(C.c_void_p)
+    _check(lib().csa_cluster_queries(ctx, _ptr(q_pre), n_pre, iters, useed_p, _ptr(init_centroids),
+                                     _ptr(centroids_out), _ptr(mean_cos), _ptr(assign), _ptr(work),
+                                     work.numel(), _stream()), "csa_cluster_queries")
+    torch.cuda.current_stream().synchronize()   # u_seed (host memory) and work stay alive until here
 
 
 def csa_export_tables(ctx, b, g, idx_out, score_out):

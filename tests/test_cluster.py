@@ -1,0 +1,147 @@
+"""GPU parity of the offline query clustering (paper Sec. 3.2 (1)): the library's k-means++ seeding
+and Lloyd steps (assignment on the matrix cores) against the oracle's two-part bf16 form.
+
+Where floating point decides an integer (an assignment, a seed draw) both sides are compared on
+what is unique: assignments may differ only where the oracle's own decision gap is at rounding
+level; centroids of clusters with identical members may differ by one bf16 step (fp32 atomics vs
+fp64 sums); seeds must be data points and follow the D^2 weighting."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2604_08584_amd import binding
+
+from harness import Case, small
+
+pytestmark = pytest.mark.gpu
+
+
+def _queries(B, Hq, n_pre, n_comp, seed, spread=0.5):
+    """Mixture-of-Gaussians prefill queries [B][Hq][n_pre][128] bf16 (data synthesis only)."""
+    g = torch.Generator().manual_seed(seed)
+    means = torch.randn(n_comp, 128, generator=g)
+    comp = torch.randint(0, n_comp, (B, Hq, n_pre), generator=g)
+    x = means[comp] + spread * torch.randn(B, Hq, n_pre, 128, generator=g)
+    return x.to(torch.bfloat16)
+
+
+def _ctx(B, Hq, Hkv, C, S):
+    return binding.csa_create(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, n_centroids=C, list_len=64, n_probe=1,
+                              budget_k=10, max_ctx=4096, n_subspaces=S)
+
+
+def _pool(q_bits, b, g, G, sub, db):
+    """Pooled sub-vectors of KV head (b, g) as fp32 [G*n_pre][db]."""
+    x = oracle.bits_to_f32(q_bits[b, g * G:(g + 1) * G])          # [G][n_pre][128]
+    return np.ascontiguousarray(x.reshape(-1, 128)[:, sub * db:(sub + 1) * db])
+
+
+@pytest.mark.parametrize("S,C", [(1, 37), (4, 64), (16, 20), (8, 130)])
+def test_lloyd_step_matches_the_oracle(S, C):
+    B, Hq, Hkv, n_pre = 2, 4, 2, 700
+    G, db = Hq // Hkv, 128 // S
+    q = _queries(B, Hq, n_pre, 12, 100 + S)
+    rng = np.random.default_rng(S)
+    init = rng.standard_normal((B, Hkv, S, C, db)).astype(np.float32)
+    init /= np.linalg.norm(init, axis=-1, keepdims=True)
+    init_t = torch.from_numpy(init).to(torch.bfloat16).cuda()
+    ctx = _ctx(B, Hq, Hkv, C, S)
+    out = torch.empty_like(init_t)
+    mean_cos = torch.zeros(B, Hkv, S, 1, device="cuda")
+    assign = torch.empty(B, Hkv, S, G * n_pre, dtype=torch.int32, device="cuda")
+    binding.csa_cluster_queries(ctx, q.cuda(), n_pre, 1, None, init_t, out, mean_cos, assign)
+    binding.csa_destroy(ctx)
+    q_bits, init_bits, out_bits = oracle.bf16_bits(q), oracle.bf16_bits(init_t), oracle.bf16_bits(out)
+    assign, mean_cos = assign.cpu().numpy(), mean_cos.cpu().numpy()
+    n_diff = 0
+    for b in range(B):
+        for g in range(Hkv):
+            for s in range(S):
+                x = _pool(q_bits, b, g, G, s, db)
+                want, asg, gap, mc = oracle.kmeans_step(x, init_bits[b, g, s])
+                diff = np.nonzero(assign[b, g, s] != asg)[0]
+                n_diff += len(diff)
+                assert (gap[diff] < 1e-5).all(), f"assignments differ where the decision was clear: {gap[diff]}"
+                assert mean_cos[b, g, s, 0] == pytest.approx(mc, abs=1e-4)
+                got_f, want_f = oracle.bits_to_f32(out_bits[b, g, s]), oracle.bits_to_f32(want)
+                touched = set(assign[b, g, s][diff].tolist()) | set(asg[diff].tolist())
+                for j in range(C):
+                    if j in touched:
+                        continue
+                    np.testing.assert_allclose(got_f[j], want_f[j], rtol=2.0 ** -7, atol=1e-6,
+                                               err_msg=f"centroid {j} of ({b},{g},{s})")
+                np.testing.assert_allclose(np.linalg.norm(got_f.astype(np.float64), axis=1), 1.0, atol=1e-2)
+    assert n_diff <= 2
+
+
+def test_seeds_are_data_points_drawn_by_squared_distance():
+    """8 tight groups of 150 points and C = 8: D^2 sampling lands in a new group at (almost) every
+    draw, every seed is one of the normalised points rounded to bf16, the first seed is point
+    floor(u_0 n), and the whole seed set matches the oracle's (fp64) draw."""
+    B, Hq, Hkv, n_pre, C = 1, 2, 1, 600, 8
+    g = torch.Generator().manual_seed(7)
+    dirs = torch.nn.functional.normalize(torch.randn(8, 128, generator=g), dim=1)
+    comp = torch.arange(B * Hq * n_pre).view(B, Hq, n_pre) % 8
+    x = (dirs[comp] * (1 + torch.rand(B, Hq, n_pre, 1, generator=g)) +
+         0.01 * torch.randn(B, Hq, n_pre, 128, generator=g)).to(torch.bfloat16)
+    u = np.random.default_rng(1).uniform(size=(B, Hkv, 1, C)).astype(np.float32)
+    ctx = _ctx(B, Hq, Hkv, C, 1)
+    out = torch.empty(B, Hkv, 1, C, 128, dtype=torch.bfloat16, device="cuda")
+    binding.csa_cluster_queries(ctx, x.cuda(), n_pre, 0, u, None, out)
+    binding.csa_destroy(ctx)
+    seeds = oracle.bits_to_f32(oracle.bf16_bits(out))[0, 0, 0]
+    pool = _pool(oracle.bf16_bits(x), 0, 0, 2, 0, 128)
+    pn = pool / np.linalg.norm(pool, axis=1, keepdims=True)
+    pn_bf16 = oracle.bits_to_f32(oracle.round_bf16(pn.astype(np.float32)))
+    which = [int(np.argmax(pn @ s)) for s in seeds]
+    for s, i in zip(seeds, which):
+        assert np.abs(pn_bf16[i] - s).max() <= 2.0 ** -8          # a data point (fp32 vs fp64 normalisation)
+    assert which[0] == int(np.float64(u[0, 0, 0, 0]) * len(pool))
+    groups = {int(np.argmax(dirs.numpy() @ s)) for s in seeds}
+    assert len(groups) >= 7
+    want = oracle.bits_to_f32(oracle.kmeans_seed(pool, C, u[0, 0, 0].astype(np.float64)))
+    same = sum(int(np.abs(want[j] - seeds[j]).max() <= 2.0 ** -8) for j in range(C))
+    assert same >= C - 1, f"only {same} of {C} seeds equal the oracle's"
+
+
+def test_full_clustering_improves_monotonically_and_matches_the_oracle_quality():
+    B, Hq, Hkv, n_pre, C, S, iters = 1, 4, 1, 1500, 24, 2, 6
+    q = _queries(B, Hq, n_pre, 20, 5)
+    u = np.random.default_rng(2).uniform(size=(B, Hkv, S, C)).astype(np.float32)
+    ctx = _ctx(B, Hq, Hkv, C, S)
+    out = torch.empty(B, Hkv, S, C, 128 // S, dtype=torch.bfloat16, device="cuda")
+    mean_cos = torch.zeros(B, Hkv, S, iters, device="cuda")
+    binding.csa_cluster_queries(ctx, q.cuda(), n_pre, iters, u, None, out, mean_cos)
+    binding.csa_destroy(ctx)
+    mean_cos = mean_cos.cpu().numpy()
+    q_bits = oracle.bf16_bits(q)
+    for s in range(S):
+        mc = mean_cos[0, 0, s]
+        assert (np.diff(mc) >= -1e-4).all(), mc
+        x = _pool(q_bits, 0, 0, 4, s, 64)
+        cent = oracle.kmeans_seed(x, C, u[0, 0, s].astype(np.float64))
+        for _ in range(iters):
+            cent, _, _, o_mc = oracle.kmeans_step(x, cent)
+        assert mc[-1] >= o_mc - 0.01, (mc[-1], o_mc)
+        _, _, _, final = oracle.kmeans_step(x, oracle.bf16_bits(out)[0, 0, s])
+        assert final >= o_mc - 0.01
+
+
+def test_clustered_centroids_feed_the_table_build_and_decode():
+    """Prefill queries -> csa_cluster_queries -> csa_build_tables -> decode, all on the GPU; the
+    oracle rebuilds the tables from the same centroids and checks a step."""
+    w = small("e2e", n_q_heads=4, n_kv_heads=2, n_pre=2500, C=32, L=128, m=2, k=120, steps=1, n_sub=4)
+    case = Case(w, seed=77, F=12)
+    q = _queries(1, 4, w.n_pre, 16, 9).cuda()
+    u = np.random.default_rng(3).uniform(size=(1, 2, 4, 32)).astype(np.float32)
+    cent = torch.empty(1, 2, 4, 32, 32, dtype=torch.bfloat16, device="cuda")
+    binding.csa_cluster_queries(case.ctx.ctx, q, w.n_pre, 4, u, None, cent)
+    case.inp["centroids"] = cent
+    case.cent_host = oracle.bf16_bits(cent)
+    case.build_on_gpu()
+    for g in range(2):
+        idx, score = case.export(0, g)
+        o_idx, o_score, _ = case.oracle_tables(0, g)
+        assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
+    case.check_step(0)
