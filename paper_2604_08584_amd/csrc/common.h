@@ -39,13 +39,17 @@ __device__ __forceinline__ int mbcnt(uint64_t mask)
                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves (no LDS traffic):
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of row 0 / 2 is broadcast
+// into row 1 / 3, then lane 31 into the upper half.
 __device__ __forceinline__ int wave_incl_scan(int v)
 {
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        int t = __shfl_up(v, o, kWave);
-        if (lane_id() >= o) v += t;
-    }
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2, 3
     return v;
 }
 
@@ -80,12 +84,10 @@ __device__ __forceinline__ unsigned long long block_excl_scan_4x16(unsigned long
 {
     constexpr int NW = NT / kWave;
     const int w = threadIdx.x / kWave;
-    unsigned long long incl = v;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const unsigned long long t = __shfl_up(incl, o, kWave);
-        if (lane_id() >= o) incl += t;
-    }
+    // (no field overflows, so the two 32-bit halves scan independently)
+    const unsigned long long incl =
+        ((unsigned long long)(uint32_t)wave_incl_scan((int)(uint32_t)(v >> 32)) << 32) |
+        (uint32_t)wave_incl_scan((int)(uint32_t)v);
     if (lane_id() == kWave - 1) s_tmp[w] = incl;
     __syncthreads();
     unsigned long long off = 0, tot = 0;
@@ -103,9 +105,7 @@ __device__ __forceinline__ unsigned long long block_excl_scan_4x16(unsigned long
 // sum over the wave, result in every lane
 __device__ __forceinline__ int wave_sum(int v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
+    return __builtin_amdgcn_readlane(wave_incl_scan(v), kWave - 1);
 }
 
 // Wave-aggregated histogram increment: lanes that hit the same bin as the first pending lane

@@ -760,6 +760,7 @@ void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t 
 // grid (P, B*Hq), block NT = max(64, R/32).
 // ---------------------------------------------------------------------------------------------
 constexpr int kEmitStage = 2048;
+constexpr int kEmitPre = 12;  // keys of a bitmap word fetched up front
 
 template <int NT>
 __global__ __launch_bounds__(NT) void k_emit(const uint32_t *__restrict__ cand_key,
@@ -777,8 +778,20 @@ __global__ __launch_bounds__(NT) void k_emit(const uint32_t *__restrict__ cand_k
     const int n_stage = R < kEmitStage ? R : kEmitStage;  // slots [0, n_stage) exist in every segment
     const int W = R / 32;
     const uint32_t word = (int)threadIdx.x < W ? cand_bits[seg0 / 32 + threadIdx.x] : 0u;
-    for (int i = threadIdx.x * 4; i < n_stage; i += NT * 4)
-        *(uint4 *)(s_key + i) = *(const uint4 *)(cand_key + seg0 + i);
+    {
+        constexpr int ITER = kEmitStage / (NT * 4);  // every load is requested before the first is stored
+        uint4 v[ITER];
+#pragma unroll
+        for (int u = 0; u < ITER; ++u) {
+            const int i = (u * NT + (int)threadIdx.x) * 4;
+            v[u] = i < n_stage ? *(const uint4 *)(cand_key + seg0 + i) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < ITER; ++u) {
+            const int i = (u * NT + (int)threadIdx.x) * 4;
+            if (i < n_stage) *(uint4 *)(s_key + i) = v[u];
+        }
+    }
     const int c = min(seg_cnt[(size_t)head * P + p], R);
     const uint32_t T = thr[head];
     const int2 par = seg_par[(size_t)head * P + p];
@@ -793,8 +806,27 @@ __global__ __launch_bounds__(NT) void k_emit(const uint32_t *__restrict__ cand_k
                 *(uint4 *)(s_key + i) = *(const uint4 *)(cand_key + seg0 + base + i);
             __syncthreads();
         }
-        int r = rank - base;
-        for (uint32_t b = word; b; b &= b - 1, ++r) {
+        // the word's keys sit at consecutive ranks: fetch the first kEmitPre of them with independent
+        // LDS reads before any is used (a bit-by-bit walk would pay one LDS round trip per key)
+        const int r0 = rank - base;
+        uint32_t kreg[kEmitPre];
+#pragma unroll
+        for (int i = 0; i < kEmitPre; ++i)
+            kreg[i] = (unsigned)(r0 + i) < (unsigned)kEmitStage ? s_key[r0 + i] : 0u;
+        uint32_t b = word;
+#pragma unroll
+        for (int i = 0; i < kEmitPre; ++i) {
+            if (b) {
+                if ((unsigned)(r0 + i) < (unsigned)kEmitStage) {
+                    const uint32_t bit = b & (0u - b);
+                    if (kreg[i] > T) gt |= bit;
+                    else if (kreg[i] == T) eq |= bit;
+                }
+                b &= b - 1;
+            }
+        }
+        int r = r0 + kEmitPre;
+        for (; b; b &= b - 1, ++r) {  // (rare: more than kEmitPre candidates in 32 key indices)
             if ((unsigned)r < (unsigned)kEmitStage) {
                 const uint32_t bit = b & (0u - b);
                 const uint32_t key = s_key[r];
