@@ -6,7 +6,7 @@ A "step" is one pass of the whole hot path through the C-ABI library - csa_decod
 csa_append_kv - over one batch of synthetic input that is already resident in HBM.  Every step
 uses a fresh query, so the 256 MiB last-level cache cannot replay the previous step.
 
-Prints ONE JSON line (see README for the fields).  One GPU only.
+Prints ONE JSON line.  One GPU only.
 """
 from __future__ import annotations
 
@@ -34,7 +34,7 @@ def main():
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="cfg4",
-                    help="cfg1..cfg4 of BASELINE.json, or paper_s8 (the paper's default geometry)")
+                    help="benchmark configuration cfg1..cfg4, or paper_s8 (the paper's default geometry)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--partition-keys", type=int, default=0)
     ap.add_argument("--kmeans-sample", type=int, default=0,
@@ -61,7 +61,7 @@ def main():
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
             f"--gpus {args.gpus} is not supported. The path shards over (sequence, KV head) "
-            "with no exchange; see DESIGN.md.")
+            "with no exchange between GPUs.")
         sys.exit(2)
 
     import torch

@@ -64,7 +64,8 @@ class Workload:
         return (n + page - 1) // page * page
 
 
-# benchmark configs 0-4.
+# The five benchmark configurations (0 = tiny, 1 = 8B-shaped 32K, 2 = 8B-shaped 128K batch 1,
+# 3 = paged batch 16 at 64K, 4 = 70B-shaped 128K batch 8).
 CONFIGS: Dict[str, Workload] = {
     "cfg0": Workload("cfg0", 1, 4, 1, 128, 4096, 32, 64, 256, 4, 205, 1, 0, 0),
     "cfg1": Workload("cfg1", 1, 32, 8, 128, 32768, 256, 1024, 2048, 16, 1638, 1, 0, 0),

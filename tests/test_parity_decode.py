@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 
 def test_cfg0_build_matches_oracle_bit_for_bit_and_decodes():
-    """BASELINE config 0: tables built on the GPU equal the oracle's tables exactly (same fma
+    """Benchmark configuration 0: tables built on the GPU equal the oracle's tables exactly (same fma
     chain, same grid, same tie rule), then one decode step matches."""
     case = Case(CONFIGS["cfg0"], F=14)
     case.build_on_gpu()

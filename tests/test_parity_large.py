@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes (configs 1-4), in the launch configuration bench.py
+"""GPU parity at the full sizes of benchmark configurations 1-4, in the launch configuration bench.py
 times (automatic key-range size, automatic score grid).  The oracle recomputes sampled table
 rows and sampled (sequence, head) decode steps one by one; the decode comparison always runs on
 the tables the GPU built (exported), so it is exact.  Centroid synthesis is shortened (fewer
