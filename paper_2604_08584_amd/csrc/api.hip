@@ -531,12 +531,21 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     csa::launch_threshold(cand_key, cand_cnt, sel, sel_count, thr, seg_par, hist, BH, c.budget_k, ctx->R,
                           ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, st);
     prof.end(3);
-    csa::launch_emit(cand_key, cand_bits, cand_cnt, thr, seg_par, sel, BH, c.budget_k, ctx->R, ctx->P,
-                     l.cand_keys, st);
-    prof.end(4);
+    // the second half of the Top-K runs in the prologue of the attention workgroups when a key
+    // range has one bitmap word per attention thread and the launch is small (it then saves a
+    // launch, 4 us of 76 at batch 1); with thousands of workgroups the prologue's latency delays
+    // every workgroup's K/V stream and a kernel of its own measured 9 us of 420 faster
+    const bool fused = c.budget_k > 0 && csa::attention_can_emit(ctx->R) && (int64_t)BH * S <= 2048;
+    if (!fused) {
+        csa::launch_emit(cand_key, cand_bits, cand_cnt, thr, seg_par, sel, BH, c.budget_k, ctx->R, ctx->P,
+                         l.cand_keys, st);
+        prof.end(4);
+    }
+    prof.mark(5);
     csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, seg_par,
                                 part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ws, ctx->n,
-                                c.max_ctx, S, ctx->P, st);
+                                c.max_ctx, S, ctx->P, fused ? cand_key : nullptr, cand_bits, cand_cnt, thr,
+                                ctx->R, l.cand_keys, st);
     prof.end(5);
     csa::launch_attention_merge(part, out_dev, BH, S, st);
     prof.end(6);
@@ -567,9 +576,10 @@ int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev, const
     csa::launch_range_offsets(sel, sel_count, seg_par, BH, c.budget_k, ctx->R, ctx->P, st);
     prof.end(8);
     prof.mark(5);
-    csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, seg_par,
-                                part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ws, ctx->n,
-                                c.max_ctx, S, ctx->P, st);
+    csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table,
+                                const_cast<int32_t *>(sel), sel_count, seg_par, part, c.batch, c.n_q_heads,
+                                c.n_kv_heads, c.budget_k, ws, ctx->n, c.max_ctx, S, ctx->P, nullptr, nullptr,
+                                nullptr, nullptr, ctx->R, l.cand_keys, st);
     prof.end(5);
     csa::launch_attention_merge(part, out_dev, BH, S, st);
     prof.end(6);

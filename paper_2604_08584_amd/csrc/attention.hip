@@ -33,17 +33,32 @@ constexpr int kSplit = kAttWaves * kItemsPerWave;  // 512 attended keys per work
 // its own online-softmax state for the rows it sees, merged at the end.  Logits are taken in
 // the log2 domain (q pre-scaled by log2(e)/sqrt(d)).  Output: un-normalised partial
 // (max, sum, o[128]) per (head, split).
+// EMIT: the workgroup of a key range first finishes the Top-K for that range itself (second half of
+// Sec. 3.3 (4): compare the range's candidates with the head's threshold, write the winners'
+// indices into `sel`) and then attends what it wrote - possible when a range has one bitmap word
+// per thread (R = 8192); it saves a launch, and this latency-bound piece runs while other
+// workgroups stream K/V.  Otherwise `sel` is read as given (Top-K done by a kernel before, or a
+// reused / caller-made index set).
 // grid ceil8(B*Hkv*S) * G workgroups (1-D, see the id mapping below), block 256.
 // ---------------------------------------------------------------------------------------------
-template <bool PAGED>
+struct EmitArgs {  // what the prologue of an EMIT launch needs (see emit_range)
+    const uint32_t *cand_key, *cand_bits, *thr;
+    const int32_t *seg_cnt;
+    int R;
+    size_t cand_stride;
+};
+
+template <bool PAGED, bool EMIT>
 __global__ __launch_bounds__(kAttNT) void k_attention_split(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc,
-    const int32_t *__restrict__ block_table, const int32_t *__restrict__ sel,
+    const int32_t *__restrict__ block_table, int32_t *__restrict__ sel,
     const int32_t *__restrict__ sel_count, const int2 *__restrict__ seg_par,
     float *__restrict__ part, int k, int n_pre, int n, int Hq, int G, int Hkv, int max_ctx, int S,
-    int P, int P_sel, int n_units, float qscale)
+    int P, int P_sel, int n_units, float qscale, EmitArgs ea)
 {
     __shared__ float s_m[kAttWaves], s_l[kAttWaves], s_o[kAttWaves][kHeadDim];
+    __shared__ __align__(16) uint32_t s_key[EMIT ? kEmitStage : 4];
+    __shared__ int s_scan[kAttWaves + 1];
     // XCD-aware order: the chip deals consecutive workgroup ids round-robin to its 8 XCDs (each
     // with its own L2).  The G workgroups that handle the same split of the same KV head get ids
     // 8 apart: same XCD, same moment.
@@ -59,7 +74,12 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
     // this workgroup's items: [first, first + count) of the head's sel list, or of the appended keys
     const bool from_sel = s < P_sel;
     int first, count;
-    if (from_sel) {
+    if (from_sel && EMIT) {
+        count = emit_range<kAttNT>(ea.cand_key, ea.cand_bits, ea.seg_cnt, ea.thr, seg_par, sel, k, ea.R, P,
+                                   ea.cand_stride, head, s, s_key, s_scan, first);
+        count = max(0, min(count, k - first));
+        __syncthreads();  // the indices just written are read back below by other threads
+    } else if (from_sel) {
         const int n_sel = min(sel_count[head], k);
         first = min(seg_par[(size_t)head * P + s].x, n_sel);
         const int end = s + 1 < P ? min(seg_par[(size_t)head * P + s + 1].x, n_sel) : n_sel;
@@ -271,28 +291,33 @@ int attention_splits(int k, int P, int n_appended)
 }
 
 void launch_attention_split(const void *q, const void *kc, const void *vc,
-                            const int32_t *block_table, const int32_t *sel,
-                            const int32_t *sel_count, const void *seg_par, float *part, int B, int Hq,
-                            int Hkv, int k, int n_pre, int n, int max_ctx, int S, int P,
-                            hipStream_t st)
+                            const int32_t *block_table, int32_t *sel, const int32_t *sel_count,
+                            const void *seg_par, float *part, int B, int Hq, int Hkv, int k, int n_pre,
+                            int n, int max_ctx, int S, int P, const uint32_t *cand_key,
+                            const uint32_t *cand_bits, const int32_t *seg_cnt, const uint32_t *thr, int R,
+                            size_t cand_stride, hipStream_t st)
 {
     if (S <= 0) return;
     const float qscale = 1.4426950408889634f / sqrtf((float)kHeadDim);
     const int G = Hq / Hkv;
     const int n_units = B * Hkv * S;
     const int P_sel = k > 0 ? P : 0;
+    const bool emit = cand_key != nullptr;  // (the caller has checked attention_can_emit(R))
+    const EmitArgs ea{cand_key, cand_bits, thr, seg_cnt, R, cand_stride};
     dim3 grid((n_units + kXcd - 1) / kXcd * kXcd * G), block(kAttNT);
-    if (block_table)
-        k_attention_split<true><<<grid, block, 0, st>>>(
-            (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, block_table, sel,
-            sel_count, (const int2 *)seg_par, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, P, P_sel,
-            n_units, qscale);
-    else
-        k_attention_split<false><<<grid, block, 0, st>>>(
-            (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, nullptr, sel,
-            sel_count, (const int2 *)seg_par, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, P, P_sel,
-            n_units, qscale);
+#define CSA_ATT(PAGED_, EMIT_)                                                                            \
+    k_attention_split<PAGED_, EMIT_><<<grid, block, 0, st>>>(                                             \
+        (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, block_table, sel, sel_count,     \
+        (const int2 *)seg_par, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, P, P_sel, n_units, qscale, ea)
+    if (block_table) {
+        if (emit) CSA_ATT(true, true); else CSA_ATT(true, false);
+    } else {
+        if (emit) CSA_ATT(false, true); else CSA_ATT(false, false);
+    }
+#undef CSA_ATT
 }
+
+bool attention_can_emit(int R) { return R == 32 * kAttNT; }
 
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st)
 {

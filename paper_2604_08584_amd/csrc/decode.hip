@@ -751,17 +751,10 @@ void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 4, second half: range p of a head writes its winners - candidates with key > T plus its
-// allowed number of lowest-index candidates with key == T - as ascending key indices, starting
-// at its output slot.  Thread t owns bitmap word t (32 key indices) and finds its keys by the
-// rank of its bits; the keys are staged in LDS, kEmitStage at a time (one round unless the
-// range is unusually dense).  Every independent load is issued before the first wait: the
-// kernel is a chain of latencies, not of bytes.
+// Step 4, second half as a kernel of its own (see emit_range in common.h): used when the gathered
+// attention cannot do it in its prologue.
 // grid (P, B*Hq), block NT = max(64, R/32).
 // ---------------------------------------------------------------------------------------------
-constexpr int kEmitStage = 2048;
-constexpr int kEmitPre = 12;  // keys of a bitmap word fetched up front
-
 template <int NT>
 __global__ __launch_bounds__(NT) void k_emit(const uint32_t *__restrict__ cand_key,
                                              const uint32_t *__restrict__ cand_bits,
@@ -773,86 +766,9 @@ __global__ __launch_bounds__(NT) void k_emit(const uint32_t *__restrict__ cand_k
 {
     __shared__ __align__(16) uint32_t s_key[kEmitStage];
     __shared__ int s_scan[NT / kWave + 1];
-    const int p = blockIdx.x, head = blockIdx.y;
-    const size_t seg0 = (size_t)head * cand_stride + (size_t)p * R;
-    const int n_stage = R < kEmitStage ? R : kEmitStage;  // slots [0, n_stage) exist in every segment
-    const int W = R / 32;
-    const uint32_t word = (int)threadIdx.x < W ? cand_bits[seg0 / 32 + threadIdx.x] : 0u;
-    {
-        constexpr int ITER = kEmitStage / (NT * 4);  // every load is requested before the first is stored
-        uint4 v[ITER];
-#pragma unroll
-        for (int u = 0; u < ITER; ++u) {
-            const int i = (u * NT + (int)threadIdx.x) * 4;
-            v[u] = i < n_stage ? *(const uint4 *)(cand_key + seg0 + i) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < ITER; ++u) {
-            const int i = (u * NT + (int)threadIdx.x) * 4;
-            if (i < n_stage) *(uint4 *)(s_key + i) = v[u];
-        }
-    }
-    const int c = min(seg_cnt[(size_t)head * P + p], R);
-    const uint32_t T = thr[head];
-    const int2 par = seg_par[(size_t)head * P + p];
-    if (c <= 0 || T == 0xFFFFFFFFu) return;  // (uniform over the workgroup)
-    int total;
-    const int rank = block_excl_scan<NT>(__popc(word), s_scan, total);  // (its barriers publish s_key)
-    uint32_t gt = 0, eq = 0;
-    for (int base = 0; base < c; base += kEmitStage) {
-        if (base) {
-            __syncthreads();
-            for (int i = threadIdx.x * 4; i < kEmitStage && base + i < c; i += NT * 4)
-                *(uint4 *)(s_key + i) = *(const uint4 *)(cand_key + seg0 + base + i);
-            __syncthreads();
-        }
-        // the word's keys sit at consecutive ranks: fetch the first kEmitPre of them with independent
-        // LDS reads before any is used (a bit-by-bit walk would pay one LDS round trip per key)
-        const int r0 = rank - base;
-        uint32_t kreg[kEmitPre];
-#pragma unroll
-        for (int i = 0; i < kEmitPre; ++i)
-            kreg[i] = (unsigned)(r0 + i) < (unsigned)kEmitStage ? s_key[r0 + i] : 0u;
-        uint32_t b = word;
-#pragma unroll
-        for (int i = 0; i < kEmitPre; ++i) {
-            if (b) {
-                if ((unsigned)(r0 + i) < (unsigned)kEmitStage) {
-                    const uint32_t bit = b & (0u - b);
-                    if (kreg[i] > T) gt |= bit;
-                    else if (kreg[i] == T) eq |= bit;
-                }
-                b &= b - 1;
-            }
-        }
-        int r = r0 + kEmitPre;
-        for (; b; b &= b - 1, ++r) {  // (rare: more than kEmitPre candidates in 32 key indices)
-            if ((unsigned)r < (unsigned)kEmitStage) {
-                const uint32_t bit = b & (0u - b);
-                const uint32_t key = s_key[r];
-                if (key > T) gt |= bit;
-                else if (key == T) eq |= bit;
-            }
-        }
-    }
-    // keep the lowest-index ties this range is allowed
-    if (par.y <= 0) {
-        eq = 0;
-    } else {
-        const int allow = par.y - block_excl_scan<NT>(__popc(eq), s_scan, total);
-        if (allow <= 0)
-            eq = 0;
-        else
-            while (__popc(eq) > allow) eq &= ~(0x80000000u >> __clz(eq));  // drop the highest bit
-    }
-    uint32_t bits = gt | eq;
-    int pos = par.x + block_excl_scan<NT>(__popc(bits), s_scan, total);
-    int32_t *out = sel + (size_t)head * k;
-    const int kbase = p * R + (int)threadIdx.x * 32;
-    for (; bits; bits &= bits - 1) {
-        if (pos < k) out[pos] = kbase + __ffs(bits) - 1;
-        ++pos;
-    }
+    int first;
+    (void)emit_range<NT>(cand_key, cand_bits, seg_cnt, thr, seg_par, sel, k, R, P, cand_stride, blockIdx.y,
+                         blockIdx.x, s_key, s_scan, first);
 }
 
 void launch_emit(const uint32_t *cand_key, const uint32_t *cand_bits, const int32_t *seg_cnt,

@@ -59,11 +59,15 @@ void launch_emit(const uint32_t *cand_key, const uint32_t *cand_bits, const int3
 
 // ---- attention.hip
 int attention_splits(int k, int P, int n_appended);
+// cand_key != NULL: the kernel also does the second half of the Top-K for its key range (needs
+// attention_can_emit(R)); else `sel` is read as given.
 void launch_attention_split(const void *q, const void *kc, const void *vc,
-                            const int32_t *block_table, const int32_t *sel,
-                            const int32_t *sel_count, const void *seg_par, float *part, int B, int Hq,
-                            int Hkv, int k, int n_pre, int n, int max_ctx, int S, int P,
-                            hipStream_t st);
+                            const int32_t *block_table, int32_t *sel, const int32_t *sel_count,
+                            const void *seg_par, float *part, int B, int Hq, int Hkv, int k, int n_pre,
+                            int n, int max_ctx, int S, int P, const uint32_t *cand_key,
+                            const uint32_t *cand_bits, const int32_t *seg_cnt, const uint32_t *thr, int R,
+                            size_t cand_stride, hipStream_t st);
+bool attention_can_emit(int R);
 void launch_range_offsets(const int32_t *sel, const int32_t *sel_count, void *seg_par, int n_heads, int k,
                           int R, int P, hipStream_t st);
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st);
