@@ -512,12 +512,12 @@ void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *span
 // Nothing selected (k = 0 or no candidate): T = 0xFFFFFFFF.  Everything selected: T = 0.
 // grid B*Hq, block 1024.
 // ---------------------------------------------------------------------------------------------
-constexpr int kThrNT = 1024;
 constexpr int kSelCap = 4096;   // contenders finished in LDS
 constexpr int kSelMaxP = 2048;  // key ranges (segments) per head
 constexpr int kSegBits = 11;    // a contender is (key - lo) << kSegBits | p
 static_assert((1 << kSegBits) >= kSelMaxP, "segment tag too narrow");
 
+template <int kThrNT>
 __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict__ cand_key,
                                                       const int32_t *__restrict__ seg_cnt,
                                                       int32_t *__restrict__ sel,
@@ -540,8 +540,9 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
     const int wave = threadIdx.x / kWave, lane = lane_id();
     // The kernel is a chain of memory latencies, so everything that can be requested before the
     // first wait is: the segment counts, the coarse histogram, and - speculatively - the first
-    // 2 x 1024 key slots of the segment this wave walks first (slots past the segment's count
-    // hold stale keys and are masked once the count is known).
+    // 1024 key slots of the segment this wave walks first (slots past the segment's count hold
+    // stale keys and are masked once the count is known).  Later chunks are requested one ahead.
+    // (Holding more keys in registers would cost the second workgroup per CU.)
     int part = 0;
     for (int p = threadIdx.x; p < kSelMaxP; p += kThrNT) {
         const int c = p < P ? min(seg_cnt[(size_t)head * P + p], R) : 0;
@@ -551,17 +552,13 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
         part += c;
     }
     const uint32_t my_hist = threadIdx.x < kCoarseBins ? hist_g[(size_t)head * kCoarseBins + threadIdx.x] : 0u;
-    uint32_t pre0[16], pre1[16];
+    uint32_t pre0[16];
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         const int e = (x * kWave + lane) * 4;
-        uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
-        if (wave < P) {
-            v0 = *(const uint4 *)(hk + (size_t)wave * R + e);                                   // e + 3 < 1024 <= R
-            if (e + kWave * 16 < R) v1 = *(const uint4 *)(hk + (size_t)wave * R + e + kWave * 16);
-        }
+        uint4 v0 = make_uint4(0, 0, 0, 0);
+        if (wave < P) v0 = *(const uint4 *)(hk + (size_t)wave * R + e);  // e + 3 < 1024 <= R
         pre0[4 * x] = v0.x; pre0[4 * x + 1] = v0.y; pre0[4 * x + 2] = v0.z; pre0[4 * x + 3] = v0.w;
-        pre1[4 * x] = v1.x; pre1[4 * x + 1] = v1.y; pre1[4 * x + 2] = v1.z; pre1[4 * x + 3] = v1.w;
     }
     if (threadIdx.x == 0) s_n = 0;
     int n_total;
@@ -577,7 +574,6 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
             for (int j = 0; j < 4; ++j) {
                 const int e = (x * kWave + lane) * 4 + j;
                 if (e >= c) pre0[4 * x + j] = 0u;
-                if (e + kWave * 16 >= c) pre1[4 * x + j] = 0u;
             }
     }
 
@@ -586,25 +582,34 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
     // walks whole segments, four consecutive keys per lane and load; both callbacks may use
     // wave-level operations only.
     auto stream = [&](auto chunk, auto seg_end) {
+        auto fetch = [&](uint32_t (&dst)[16], int p, int c, int e0) {
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int e = e0 + (x * kWave + lane) * 4;
+                const uint4 v = e < c ? *(const uint4 *)(hk + (size_t)p * R + e) : make_uint4(0, 0, 0, 0);
+                dst[4 * x + 0] = v.x;
+                dst[4 * x + 1] = e + 1 < c ? v.y : 0u;
+                dst[4 * x + 2] = e + 2 < c ? v.z : 0u;
+                dst[4 * x + 3] = e + 3 < c ? v.w : 0u;
+            }
+        };
         for (int p = wave; p < P; p += NW) {
             const int c = s_cnt[p];
+            uint32_t cur[16], nxt[16];
+            if (p == wave) {  // (wave-uniform)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) cur[i] = pre0[i];
+            } else if (c > 0) {
+                fetch(cur, p, c, 0);
+            }
             for (int e0 = 0; e0 < c; e0 += kWave * 16) {
-                uint32_t cur[16];
-                if (p == wave && e0 < 2 * kWave * 16) {  // (wave-uniform)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) cur[i] = e0 == 0 ? pre0[i] : pre1[i];
-                } else {
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const int e = e0 + (x * kWave + lane) * 4;
-                        const uint4 v = e < c ? *(const uint4 *)(hk + (size_t)p * R + e) : make_uint4(0, 0, 0, 0);
-                        cur[4 * x + 0] = v.x;
-                        cur[4 * x + 1] = e + 1 < c ? v.y : 0u;
-                        cur[4 * x + 2] = e + 2 < c ? v.z : 0u;
-                        cur[4 * x + 3] = e + 3 < c ? v.w : 0u;
-                    }
-                }
+                const bool more = e0 + kWave * 16 < c;
+                if (more) fetch(nxt, p, c, e0 + kWave * 16);  // in flight while this chunk is worked on
                 chunk(cur, p);
+                if (more) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) cur[i] = nxt[i];
+                }
             }
             seg_end(p);
         }
@@ -727,18 +732,29 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
         }
     }
     __syncthreads();
-    // per range: its share of the ties (lowest ranges first) and its first output slot
-    static_assert(kSelMaxP == 2 * kThrNT, "two ranges per thread");
-    const int p0 = 2 * (int)threadIdx.x, p1 = p0 + 1;
-    const int e0 = s_eq[p0], e1 = s_eq[p1];
+    // per range: its share of the ties (lowest ranges first) and its first output slot; thread t
+    // owns the kSelMaxP / NT consecutive ranges starting at t * kSelMaxP / NT
+    constexpr int RPT = kSelMaxP / kThrNT;
+    const int p0 = RPT * (int)threadIdx.x;
+    int e_mine = 0;
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) e_mine += s_eq[p0 + i];
     int dummy;
-    const int ties_before = block_excl_scan<kThrNT>(e0 + e1, s_scan, dummy);
-    const int al0 = max(0, min(e0, need - ties_before));
-    const int al1 = max(0, min(e1, need - ties_before - e0));
-    const int take0 = s_gt[p0] + al0, take1 = s_gt[p1] + al1;
-    const int off = block_excl_scan<kThrNT>(take0 + take1, s_scan, dummy);
-    if (p0 < P) seg_par[(size_t)head * P + p0] = make_int2(off, al0);
-    if (p1 < P) seg_par[(size_t)head * P + p1] = make_int2(off + take0, al1);
+    int ties_before = block_excl_scan<kThrNT>(e_mine, s_scan, dummy);
+    int al[RPT], take_mine = 0;
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const int e = s_eq[p0 + i];
+        al[i] = max(0, min(e, need - ties_before));
+        ties_before += e;
+        take_mine += s_gt[p0 + i] + al[i];
+    }
+    int off = block_excl_scan<kThrNT>(take_mine, s_scan, dummy);
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        if (p0 + i < P) seg_par[(size_t)head * P + p0 + i] = make_int2(off, al[i]);
+        off += s_gt[p0 + i] + al[i];
+    }
     if (threadIdx.x == 0) thr[head] = T;
 }
 
@@ -746,8 +762,15 @@ void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t 
                       uint32_t *thr, void *seg_par, const uint32_t *hist_g, int n_heads, int k, int R,
                       int P, size_t cand_stride, uint32_t key_lo, int key_sh, hipStream_t st)
 {
-    k_threshold<<<n_heads, kThrNT, 0, st>>>(cand_key, seg_cnt, sel, sel_count, thr, (int2 *)seg_par, hist_g,
-                                            k, R, P, cand_stride, key_lo, key_sh);
+    // A 1024-thread workgroup (one wave per key range at 16 ranges) has the shorter latency, but its
+    // registers allow one workgroup per CU; with more heads than CUs, 512-thread workgroups - two
+    // per CU - run all heads at once instead of in two rounds.
+    if (n_heads > 256)
+        k_threshold<512><<<n_heads, 512, 0, st>>>(cand_key, seg_cnt, sel, sel_count, thr, (int2 *)seg_par, hist_g,
+                                                  k, R, P, cand_stride, key_lo, key_sh);
+    else
+        k_threshold<1024><<<n_heads, 1024, 0, st>>>(cand_key, seg_cnt, sel, sel_count, thr, (int2 *)seg_par,
+                                                    hist_g, k, R, P, cand_stride, key_lo, key_sh);
 }
 
 // ---------------------------------------------------------------------------------------------
