@@ -283,6 +283,45 @@ def test_streaming_updates_report_scores_that_leave_the_grid():
     assert e.value.status == binding.CSA_ERR_RANGE
 
 
+def test_maximum_list_length_and_probe_count():
+    """L = 8192 (the largest list: whole-row sorts and the build's index copy fill their LDS) with
+    rows shorter and longer than the prefill, and M = 63 probed rows (the most the 6-bit occurrence
+    count of an accumulator allows)."""
+    w = small("maxL", n_q_heads=2, n_kv_heads=1, n_pre=9000, C=5, L=8192, m=3, k=4000, steps=1)
+    case = Case(w, seed=40, F=12, partition_keys=4096)
+    case.build_on_gpu()
+    idx, score = case.export(0, 0)
+    o_idx, o_score, _ = case.oracle_tables(0, 0)
+    assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
+    case.check_step(0)
+    case2 = Case(w, seed=40, F=12)
+    case2.import_tables(idx[None, None], score[None, None])
+    case2.check_step(0)
+    w = small("maxM", n_q_heads=16, n_kv_heads=1, n_pre=2000, C=64, L=100, m=63, k=900, steps=1)   # G = 16
+    case = Case(w, seed=41, F=10)
+    case.import_oracle_tables()
+    case.check_step(0)
+
+
+def test_result_does_not_depend_on_the_key_range_size():
+    """The key-range size is a launch parameter, not part of the method: the selections of the same
+    inputs are bit-identical for every admissible size, the outputs equal up to fp32 summation order."""
+    w = small("ranges", n_q_heads=4, n_kv_heads=2, n_pre=20000, C=30, L=500, m=6, k=900, steps=1, pre_appended=3)
+    ref = None
+    for part in (1024, 2048, 4096, 8192, 16384):
+        case = Case(w, seed=42, F=12, partition_keys=part)
+        case.build_on_gpu()
+        case.append(3)
+        out, sel, cnt, _ = case.decode(3)
+        if ref is None:
+            ref = (out, sel, cnt)
+            case.check_step(3)
+        else:
+            assert np.array_equal(sel, ref[1]) and np.array_equal(cnt, ref[2])
+            # (outputs: the attention splits follow the key ranges, so fp32 summation order differs)
+            np.testing.assert_allclose(out, ref[0], rtol=0, atol=1e-5)
+
+
 def test_repeated_steps_are_deterministic():
     w = small("det", n_q_heads=8, n_kv_heads=2, steps=1, pre_appended=9)
     case = Case(w, seed=9, F=12, partition_keys=1024)
