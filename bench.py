@@ -274,26 +274,34 @@ def cluster_bench(args, w):
 
 def cpu_baseline(ctx, w, inp, budget_s):
     """The oracle, as it stands, on the host cores: the first decode step of the run (context =
-    N_pre + pre_appended) for the query heads of the first KV heads, scaled to the whole batch."""
+    N_pre + pre_appended) for the query heads of the first KV heads, scaled to the whole batch.
+    The oracle reads tables it builds itself (the rows its sampled heads probe, at the grid the
+    library reports); building them is set-up and not timed, like the GPU's build."""
     import numpy as np
     from oracle import oracle
     from paper_2604_08584_amd import binding
     n_groups = max(1, min(w.batch * w.n_kv_heads, 16 // w.group))
     t = w.pre_appended
     n = w.n_pre + t
+    F = binding.csa_score_frac_bits(ctx.ctx)
     qh = oracle.bf16_bits(inp["q_steps"][t])
     items = []
     for s in range(n_groups):
         b, g = divmod(s, w.n_kv_heads)
-        idx, score = ctx.export_tables(b, g)
-        idx, score = idx.cpu().numpy(), score.cpu().numpy()
         K = oracle.bf16_bits(inp["k_cache"][b, g])
         V = oracle.bf16_bits(inp["v_cache"][b, g])
         # rows [n_pre, n) of the logical cache: the keys appended before the first step
         K[w.n_pre:n] = oracle.bf16_bits(inp["k_new"][:t, b, g])
         V[w.n_pre:n] = oracle.bf16_bits(inp["v_new"][:t, b, g])
         cent = oracle.bf16_bits(inp["centroids"][b, g])
-        for h in range(g * w.group, (g + 1) * w.group):
+        heads = range(g * w.group, (g + 1) * w.group)
+        probed = np.unique(np.concatenate(
+            [oracle.top_centroids(np.ascontiguousarray(qh[b, h]), cent, w.m)[0] for h in heads]))
+        idx = np.full((w.n_sub * w.C, w.L), -1, np.int32)
+        score = np.zeros((w.n_sub * w.C, w.L), np.float32)
+        idx[probed], score[probed], _ = oracle.build_rows(np.ascontiguousarray(K[:w.n_pre]), w.n_pre, cent,
+                                                          probed, w.L, F)
+        for h in heads:
             items.append(dict(q=np.ascontiguousarray(qh[b, h]), cent=cent, tbl_idx=idx,
                               tbl_score=score, K=K, V=V))
     oracle.decode_items(items[:1], w.m, w.k, w.n_pre, n)  # page the library in

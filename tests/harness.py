@@ -1,5 +1,9 @@
 """Glue shared by the GPU parity tests: runs the HIP library (through the C ABI binding) and the
-CPU oracle on the same bytes and compares them.  Holds no arithmetic of the method."""
+CPU oracle on the same bytes and compares them.  Holds no arithmetic of the method.
+
+Nothing the oracle consumes comes from the GPU: its tables are the ones it builds itself from
+the same K and centroids (only the rows a step probes, at full size), or arrays a test made up
+and handed to both sides; tables exported from the GPU are only ever compared."""
 from __future__ import annotations
 
 import numpy as np
@@ -38,7 +42,8 @@ class Case:
             self.k_store, self.v_store, self.block_table = self.inp["k_cache"], self.inp["v_cache"], None
         self.ctx = binding.Context(self.k_store, self.v_store, self.block_table,
                                    **cfg_kwargs(w, F, partition_keys, stream_window))
-        self.tables = {}   # (b, g) -> (idx, score) numpy, canonical
+        # the oracle's own tables: (b, g) -> [idx [S*C][L], score [S*C][L], row-is-filled [S*C]]
+        self.otab = {}
         self.t = 0         # appended so far
 
     # ---- tables
@@ -47,10 +52,26 @@ class Case:
         self.F = binding.csa_score_frac_bits(self.ctx.ctx)
 
     def export(self, b, g):
-        if (b, g) not in self.tables:
-            idx, score = self.ctx.export_tables(b, g)
-            self.tables[(b, g)] = (idx.cpu().numpy(), score.cpu().numpy())
-        return self.tables[(b, g)]
+        """The GPU's tables of KV head (b, g), canonical layout (for comparison only)."""
+        idx, score = self.ctx.export_tables(b, g)
+        return idx.cpu().numpy(), score.cpu().numpy()
+
+    def oracle_rows(self, b, g, rows=None):
+        """The oracle's tables of KV head (b, g) with (at least) `rows` filled in by the oracle's own
+        build over the prefill keys (None = every row).  Returns (idx, score) [S*C][L]."""
+        w = self.w
+        n_rows = w.n_sub * w.C
+        if (b, g) not in self.otab:
+            self.otab[(b, g)] = [np.full((n_rows, w.L), -1, np.int32), np.zeros((n_rows, w.L), np.float32),
+                                 np.zeros(n_rows, bool)]
+        idx, score, have = self.otab[(b, g)]
+        want = np.arange(n_rows) if rows is None else np.unique(np.asarray(rows))
+        todo = want[~have[want]]
+        if len(todo):
+            i, s, _ = self.oracle_tables(b, g, todo)
+            idx[todo], score[todo] = i, s
+            have[todo] = True
+        return idx, score
 
     def oracle_tables(self, b, g, rows=None):
         K = np.ascontiguousarray(self.K_host[b, g, :self.w.n_pre])
@@ -63,7 +84,8 @@ class Case:
         w = self.w
         for b in range(w.batch):
             for g in range(w.n_kv_heads):
-                self.tables[(b, g)] = (np.ascontiguousarray(idx[b, g]), np.ascontiguousarray(score[b, g]))
+                self.otab[(b, g)] = [np.ascontiguousarray(idx[b, g]), np.ascontiguousarray(score[b, g]),
+                                     np.ones(idx.shape[2], bool)]
         self.ctx.import_tables(self.inp["centroids"], torch.from_numpy(idx).cuda(),
                                torch.from_numpy(score).cuda(), w.n_pre)
 
@@ -79,8 +101,8 @@ class Case:
     # ---- steps
     def append(self, count=1, groups=None):
         """Appends on the GPU and mirrors it on the host; with streaming updates the oracle's
-        try-insert is applied to the host copies of the tables of `groups` (default: all (b, g);
-        those tables must have been exported before the first append)."""
+        try-insert is applied to the oracle's tables of `groups` (default: all (b, g)), which are
+        built in full first."""
         w = self.w
         for _ in range(count):
             kn, vn = self.inp["k_new"][self.t], self.inp["v_new"][self.t]
@@ -92,21 +114,16 @@ class Case:
             if self.stream_window:
                 for (b, g) in (groups if groups is not None else
                                [(b, g) for b in range(w.batch) for g in range(w.n_kv_heads)]):
-                    idx, score = self.tables[(b, g)]
+                    idx, score = self.oracle_rows(b, g)
                     oracle.try_insert(idx, score, self.cent_host[b, g], np.ascontiguousarray(kb[b, g]), pos, self.F)
             self.t += 1
 
-    def export_all(self):
-        for b in range(self.w.batch):
-            for g in range(self.w.n_kv_heads):
-                self.export(b, g)
-
     def check_tables(self, b, g):
-        """The GPU's tables (exported now) against the host copy kept up to date by the oracle."""
-        idx, score = self.ctx.export_tables(b, g)
-        want_idx, want_score = self.tables[(b, g)]
-        assert np.array_equal(idx.cpu().numpy(), want_idx), f"table indices of ({b},{g}) differ"
-        assert np.array_equal(score.cpu().numpy(), want_score), f"table scores of ({b},{g}) differ"
+        """The GPU's tables (exported now) against the oracle's (built, and kept up to date, by it)."""
+        idx, score = self.export(b, g)
+        want_idx, want_score = self.oracle_rows(b, g)
+        assert np.array_equal(idx, want_idx), f"table indices of ({b},{g}) differ"
+        assert np.array_equal(score, want_score), f"table scores of ({b},{g}) differ"
 
     def window_start(self):
         n = self.w.n_pre + self.t
@@ -120,18 +137,34 @@ class Case:
         return out.cpu().numpy(), sel.cpu().numpy(), cnt.cpu().numpy(), rows.cpu().numpy()
 
     def oracle_decode(self, step, heads):
-        """heads: list of (b, h).  Uses the tables exported from / imported into the GPU."""
+        """heads: list of (b, h).  The oracle probes its own centroids and reads its own tables: the
+        rows a head probes are built by the oracle on demand (all rows once streaming updates or an
+        import have made the tables complete)."""
         w = self.w
         qh = oracle.bf16_bits(self.inp["q_steps"][step])
         n = w.n_pre + self.t
         items = []
         for b, h in heads:
             g = h // w.group
-            idx, score = self.export(b, g)
+            probed, _ = oracle.top_centroids(np.ascontiguousarray(qh[b, h]), self.cent_host[b, g], w.m)
+            idx, score = self.oracle_rows(b, g, probed)
             items.append(dict(q=np.ascontiguousarray(qh[b, h]), cent=self.cent_host[b, g], tbl_idx=idx,
                               tbl_score=score, K=self.K_host[b, g], V=self.V_host[b, g]))
         rows, sel, cnt, out, _ = oracle.decode_items(items, w.m, w.k, self.window_start(), n)
         return rows, sel, cnt, out
+
+    def oracle_index_set(self, step):
+        """The oracle's index set of every head for `step` as the arrays decode_step returns:
+        sel [B][Hq][k] int32 (ascending, -1 padded) and cnt [B][Hq] int32."""
+        w = self.w
+        heads = [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
+        _, o_sel, o_cnt, _ = self.oracle_decode(step, heads)
+        sel = np.full((w.batch, w.n_q_heads, w.k), -1, np.int32)
+        cnt = np.zeros((w.batch, w.n_q_heads), np.int32)
+        for t, (b, h) in enumerate(heads):
+            cnt[b, h] = o_cnt[t]
+            sel[b, h, :o_cnt[t]] = np.asarray(o_sel[t])[:o_cnt[t]]
+        return sel, cnt
 
     def check_step(self, step, heads=None):
         """Decode on both sides, compare; returns the max-abs output error."""

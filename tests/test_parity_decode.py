@@ -61,8 +61,8 @@ def test_ragged_shapes_import_and_build(G, part):
     case2.build_on_gpu()
     for g in range(2):
         idx, score = case2.export(0, g)
-        assert np.array_equal(idx, case.tables[(0, g)][0])
-        assert np.array_equal(score, case.tables[(0, g)][1])
+        assert np.array_equal(idx, case.oracle_rows(0, g)[0])
+        assert np.array_equal(score, case.oracle_rows(0, g)[1])
 
 
 @pytest.mark.parametrize("part", [4096, 8192, 16384])
@@ -224,8 +224,8 @@ def test_search_period_steps_reuse_the_index_set(paged):
     with pytest.raises(binding.CsaError) as e:          # nothing to reuse yet
         case.ctx.decode_step_reuse(case.inp["q_steps"][0])
     assert e.value.status == binding.CSA_ERR_STATE
-    case.check_step(0)
-    _, sel, cnt, _ = case.decode(0)
+    case.check_step(0)                                  # leaves the library holding step 0's index set
+    sel, cnt = case.oracle_index_set(0)                 # the oracle's own copy of it (checked equal above)
     for step in (1, 2, 3):
         case.append(1)
         case.check_reuse_step(step, sel, cnt, pass_buffers=(step == 2))
@@ -251,10 +251,8 @@ def test_streaming_updates_try_insert_and_recent_window(S, L, part, paged):
               n_sub=S, page_size=16 if paged else 0)
     case = Case(w, seed=20 + S, F=12, partition_keys=part, stream_window=8)
     case.build_on_gpu()
-    case.export_all()
     for g in range(2):
-        o_idx, o_score, _ = case.oracle_tables(0, g)
-        assert np.array_equal(case.tables[(0, g)][0], o_idx) and np.array_equal(case.tables[(0, g)][1], o_score)
+        case.check_tables(0, g)
     case.check_step(0)
     done = 0
     for upto in (1, 9, 30):
@@ -265,7 +263,7 @@ def test_streaming_updates_try_insert_and_recent_window(S, L, part, paged):
         case.check_step(upto)
     binding.csa_streaming_status(case.ctx.ctx)                 # no score left the grid
     # the newest keys really are in the tables, and rewinding is refused
-    assert (case.tables[(0, 0)][0] >= w.n_pre).any()
+    assert (case.oracle_rows(0, 0)[0] >= w.n_pre).any()
     with pytest.raises(binding.CsaError) as e:
         binding.csa_set_context_len(case.ctx.ctx, w.n_pre)
     assert e.value.status == binding.CSA_ERR_STATE
@@ -295,7 +293,7 @@ def test_maximum_list_length_and_probe_count():
     assert np.array_equal(idx, o_idx) and np.array_equal(score, o_score)
     case.check_step(0)
     case2 = Case(w, seed=40, F=12)
-    case2.import_tables(idx[None, None], score[None, None])
+    case2.import_tables(o_idx[None, None], o_score[None, None])
     case2.check_step(0)
     w = small("maxM", n_q_heads=16, n_kv_heads=1, n_pre=2000, C=64, L=100, m=63, k=900, steps=1)   # G = 16
     case = Case(w, seed=41, F=10)
