@@ -154,6 +154,22 @@ def main():
     us_per_step = elapsed / K * 1e6
     sel_mean = float(ctx.sel_count.float().mean().item())
 
+    # ---- per-step latency spread: an event pair around every step of one more pass (the library
+    # launches on torch's current stream, so torch events bracket its kernels); streaming runs,
+    # which cannot replay their steps, skip it
+    step_pct = None
+    if not streaming:
+        reset()
+        torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+        marks[0].record()
+        for i in range(K):
+            run(1)
+            marks[i + 1].record()
+        torch.cuda.synchronize()
+        per = sorted(marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(K))
+        step_pct = {f"p{q_}": round(per[min(K - 1, int(q_ / 100.0 * K))], 2) for q_ in (50, 90, 99)}
+
     # ---- second pass with per-kernel HIP events: over the same K steps, or - with streaming
     # updates, where steps cannot be replayed - over the next K_prof steps
     reset()
@@ -207,6 +223,7 @@ def main():
         "step_algorithmic_bytes": int(step_bytes),
         "step_hbm_gbps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
         "step_frac_of_peak": round(step_bytes / (us_per_step * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
+        "step_us_percentiles": step_pct,
         "stage_us": {k_: round(v, 2) for k_, v in stage_us.items()},
         "build_tables_s": round(t_build, 2),
         "roofline": roofline,
@@ -305,18 +322,34 @@ def cpu_baseline(ctx, w, inp, budget_s):
             items.append(dict(q=np.ascontiguousarray(qh[b, h]), cent=cent, tbl_idx=idx,
                               tbl_score=score, K=K, V=V))
     oracle.decode_items(items[:1], w.m, w.k, w.n_pre, n)  # page the library in
-    reps, spent, used = 0, 0.0, 1
-    while spent < budget_s and reps < 100000:
+
+    def timed(its, n_threads, budget):
+        reps, spent, used = 0, 0.0, 1
+        while spent < budget and reps < 100000:
+            t0 = time.perf_counter()
+            *_, used = oracle.decode_items(its, w.m, w.k, w.n_pre, n, n_threads=n_threads)
+            spent += time.perf_counter() - t0
+            reps += 1
+        return spent / reps / len(its), reps, int(used)
+
+    scale = w.batch * w.n_q_heads
+    per_head_s, reps, used = timed(items, 0, 0.6 * budget_s)            # all host threads
+    one_head_s, _, _ = timed(items[:2], 1, 0.2 * budget_s)               # one thread
+    # dense attention over the whole context (Sec. 3.1, the definition the method approximates) on one
+    # thread, for the dense-to-sparse ratio on the same cores
+    it = items[0]
+    reps_d, spent_d = 0, 0.0
+    while spent_d < 0.2 * budget_s and reps_d < 1000:
         t0 = time.perf_counter()
-        *_, used = oracle.decode_items(items, w.m, w.k, w.n_pre, n, n_threads=0)
-        spent += time.perf_counter() - t0
-        reps += 1
-    per_head_s = spent / reps / len(items)
-    us_step = per_head_s * w.batch * w.n_q_heads * 1e6
-    return dict(value=round(us_step, 1), unit="us/step", cores=int(used), kind="oracle",
-                sample=f"{len(items)} of {w.batch * w.n_q_heads} (sequence, query head) items of the "
+        oracle.dense_attention(it["q"], it["K"], it["V"], n)
+        spent_d += time.perf_counter() - t0
+        reps_d += 1
+    return dict(value=round(per_head_s * scale * 1e6, 1), unit="us/step", cores=used, kind="oracle",
+                sample=f"{len(items)} of {scale} (sequence, query head) items of the "
                        f"first step, {reps} repetitions, all {used} host threads, scaled by "
-                       f"{w.batch * w.n_q_heads}/{len(items)}",
+                       f"{scale}/{len(items)}",
+                single_thread_us_step=round(one_head_s * scale * 1e6, 1),
+                dense_attention_single_thread_us_step=round(spent_d / reps_d * scale * 1e6, 1),
                 host_cpus=os.cpu_count())
 
 
