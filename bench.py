@@ -149,6 +149,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(K)
+    issued = time.perf_counter() - t0       # host time to enqueue the K steps (no waiting)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     us_per_step = elapsed / K * 1e6
@@ -224,6 +225,7 @@ def main():
         "step_hbm_gbps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
         "step_frac_of_peak": round(step_bytes / (us_per_step * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
         "step_us_percentiles": step_pct,
+        "host_issue_us_per_step": round(issued / K * 1e6, 2),
         "stage_us": {k_: round(v, 2) for k_, v in stage_us.items()},
         "build_tables_s": round(t_build, 2),
         "roofline": roofline,

@@ -108,6 +108,21 @@ __device__ __forceinline__ int wave_sum(int v)
     return __builtin_amdgcn_readlane(wave_incl_scan(v), kWave - 1);
 }
 
+// largest value over the wave, result in every lane (the same moves as the scan; a lane that
+// receives nothing keeps its value: 0 is the identity)
+__device__ __forceinline__ uint32_t wave_max(uint32_t v)
+{
+    int x = (int)v;
+    auto mx = [](int a, int b) { return (int)max((uint32_t)a, (uint32_t)b); };
+    x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true));
+    x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true));
+    x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true));
+    x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true));
+    x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false));
+    x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false));
+    return (uint32_t)__builtin_amdgcn_readlane(x, kWave - 1);
+}
+
 // Wave-aggregated histogram increment: lanes that hit the same bin as the first pending lane
 // are counted with one LDS atomic (keys cluster heavily in the leading digits); after two such
 // rounds the remaining lanes fall back to one atomic each.

@@ -223,18 +223,13 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
         {
             constexpr int NWT = kTopNT / kWave;
             const int r = (m + NWT - 1) / NWT;  // <= 16 of the 64 lane maxima; NWT * r >= m
-            uint64_t cur = ((uint64_t)best << 32) | (uint32_t)~threadIdx.x;  // distinct per lane
-            uint64_t wmax = 0ull;
+            uint32_t cur = best, wmax = 0u;
             for (int round = 0; round < r; ++round) {
-                wmax = cur;
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) {
-                    const uint64_t t = __shfl_xor(wmax, o, kWave);
-                    wmax = t > wmax ? t : wmax;
-                }
-                if (cur == wmax) cur = 0ull;  // remove the winner
+                wmax = wave_max(cur);
+                const uint64_t holders = __ballot(cur == wmax);
+                if (lane_id() == __ffsll((unsigned long long)holders) - 1) cur = 0u;  // remove one winner
             }
-            if (lane_id() == 0) s_hist[threadIdx.x / kWave] = (uint32_t)(wmax >> 32);
+            if (lane_id() == 0) s_hist[threadIdx.x / kWave] = wmax;
             __syncthreads();
             if (threadIdx.x == 0) {
                 uint32_t bnd = 0xFFFFFFFFu;
@@ -297,11 +292,21 @@ publish:
     const int bg = head / G;
     const int nb = nsub + 1;
     int32_t *sp = spans + (size_t)head * P * M * nb;
-    for (int t = threadIdx.x; t < P * m * nb; t += kTopNT) {
-        const int x = t % nb, pr = t / nb;
-        const int p = pr / m, r = pr - p * m;
-        sp[((size_t)p * M + sub * m + r) * nb + x] =
-            part_off[((size_t)bg * S * C + (size_t)sub * C + s_rows[r]) * PO + p * nsub + x];
+    // (four independent loads in flight per thread before the first store)
+    for (int t0 = threadIdx.x; t0 < P * m * nb; t0 += 4 * kTopNT) {
+        int32_t v[4];
+        size_t dst[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = min(t0 + u * kTopNT, P * m * nb - 1);
+            const int x = t % nb, pr = t / nb;
+            const int p = pr / m, r = pr - p * m;
+            dst[u] = ((size_t)p * M + sub * m + r) * nb + x;
+            v[u] = part_off[((size_t)bg * S * C + (size_t)sub * C + s_rows[r]) * PO + p * nsub + x];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (t0 + u * kTopNT < P * m * nb) sp[dst[u]] = v[u];
     }
 }
 
@@ -537,7 +542,7 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
     const int head = blockIdx.x;
     const uint32_t *hk = cand_key + (size_t)head * cand_stride;
     int32_t *out = sel + (size_t)head * k;
-    const int wave = threadIdx.x / kWave, lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();  // (scalar)
     // The kernel is a chain of memory latencies, so everything that can be requested before the
     // first wait is: the segment counts, the coarse histogram, and - speculatively - the first
     // 1024 key slots of the segment this wave walks first (slots past the segment's count hold
@@ -567,7 +572,7 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
     if (threadIdx.x == 0) sel_count[head] = k_eff;
     for (int a = k_eff + threadIdx.x; a < k; a += kThrNT) out[a] = -1;
     {
-        const int c = wave < P ? s_cnt[wave] : 0;
+        const int c = wave < P ? __builtin_amdgcn_readfirstlane(s_cnt[wave]) : 0;
 #pragma unroll
         for (int x = 0; x < 4; ++x)
 #pragma unroll
@@ -594,7 +599,7 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
             }
         };
         for (int p = wave; p < P; p += NW) {
-            const int c = s_cnt[p];
+            const int c = __builtin_amdgcn_readfirstlane(s_cnt[p]);  // (scalar loop bounds)
             uint32_t cur[16], nxt[16];
             if (p == wave) {  // (wave-uniform)
 #pragma unroll
@@ -678,31 +683,35 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
                 // gather the contenders (key - lo < 2^sh <= 2^16), tagged with their range; count per
                 // range the keys above the bin (sure winners)
                 __syncthreads();
-                int n_gt = 0;
+                // (counts are taken with wave votes: they live in scalar registers and cost one
+                // vector compare per key; the rare contenders are placed vote by vote)
+                int n_gt = 0;  // wave-uniform
+                const uint32_t width = hi - lo;
                 stream([&](const uint32_t (&keys)[16], int p) {
-                           // one LDS atomic per wave and chunk reserves room for all its contenders
+                           unsigned long long in[16];
                            int n_in = 0;
 #pragma unroll
                            for (int i = 0; i < 16; ++i) {
-                               n_gt += keys[i] > hi ? 1 : 0;
-                               n_in += keys[i] >= lo && keys[i] <= hi ? 1 : 0;
+                               n_gt += __popcll(__ballot(keys[i] > hi));
+                               in[i] = __ballot(keys[i] - lo <= width);
+                               n_in += __popcll(in[i]);
                            }
-                           const int incl = wave_incl_scan(n_in);
-                           const int n_wave = __builtin_amdgcn_readlane(incl, kWave - 1);
-                           if (n_wave) {
-                               int wbase = 0;
-                               if (lane == 0) wbase = atomicAdd(&s_n, n_wave);
-                               int o = __builtin_amdgcn_readfirstlane(wbase) + incl - n_in;
+                           if (n_in) {
+                               // one LDS atomic per wave and chunk reserves room for all its contenders
+                               int o = 0;
+                               if (lane == 0) o = atomicAdd(&s_n, n_in);
+                               o = __builtin_amdgcn_readfirstlane(o);
 #pragma unroll
                                for (int i = 0; i < 16; ++i)
-                                   if (keys[i] >= lo && keys[i] <= hi) {
-                                       if (o < kSelCap) s_ck[o] = ((keys[i] - lo) << kSegBits) | (uint32_t)p;
-                                       ++o;
+                                   if (in[i]) {  // (wave-uniform)
+                                       const int mine = o + mbcnt(in[i]);
+                                       if (keys[i] - lo <= width && mine < kSelCap)
+                                           s_ck[mine] = ((keys[i] - lo) << kSegBits) | (uint32_t)p;
+                                       o += __popcll(in[i]);
                                    }
                            }
                        },
                        [&](int p) {
-                           n_gt = wave_sum(n_gt);
                            if (lane == 0) s_gt[p] = n_gt;
                            n_gt = 0;
                        });
