@@ -24,7 +24,7 @@ struct Layout {
     Region cent_t, ent, part_off, row_cnt, row_min;  // (the last two: streaming updates only)
     size_t tables_bytes = 0;
     // scratch buffer
-    Region z, rows, spans, cand, cand_bits, cand_cnt, seg_par, thr, hist, sel, sel_count, part, flags, qs;
+    Region z, rows, spans, cand, bin_off, cand_cnt, seg_par, seg_run, thr, sel, sel_count, part, flags, qs;
     Region queue_n, queue;  // rows waiting for the streaming insertion
     size_t scratch_bytes = 0;
     int P_max = 0, PO_max = 0, S_max = 0, Ls = 0;
@@ -97,11 +97,10 @@ Layout make_layout(const csa_config &c)
     put(l.rows, BH * M * 4);
     put(l.spans, BH * M * 2 * l.PO_max * 4);  // P * (nsub + 1) <= 2 * PO offsets per row
     put(l.cand, BH * l.cand_keys * 4);       // candidate keys, R slots per (head, key range)
-    put(l.cand_bits, BH * l.cand_keys / 8);  // presence bitmap over the key indices
     put(l.cand_cnt, BH * (size_t)l.P_max * 4);  // candidates per (head, key range)
     put(l.seg_par, BH * (size_t)l.P_max * 8);   // (output offset, ties allowed) per (head, key range)
+    put(l.seg_run, BH * (size_t)l.P_max * 8);   // candidates of the threshold's bin per (head, key range)
     put(l.thr, BH * 4);                         // Top-K threshold per head
-    put(l.hist, BH * 512 * 4);  // per head: coarse histogram of accumulated scores
     put(l.sel, BH * (size_t)(c.budget_k > 0 ? c.budget_k : 1) * 4);
     put(l.sel_count, BH * 4);
     put(l.part, BH * (size_t)(l.S_max > 0 ? l.S_max : 1) * (c.head_dim + 2) * 4);
@@ -111,6 +110,7 @@ Layout make_layout(const csa_config &c)
         put(l.queue_n, 256);
         put(l.queue, BG * Ct * 16);
     }
+    put(l.bin_off, BH * (size_t)l.P_max * 512 * 2);  // start of every coarse score bin per (head, key range)
     l.scratch_bytes = off;
     return l;
 }
@@ -503,9 +503,10 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     float *z = at<float>(ctx->scratch, l.z);
     int32_t *rows = at<int32_t>(ctx->scratch, l.rows);
     uint32_t *cand_key = at<uint32_t>(ctx->scratch, l.cand);
-    uint32_t *cand_bits = at<uint32_t>(ctx->scratch, l.cand_bits);
+    uint16_t *bin_off = at<uint16_t>(ctx->scratch, l.bin_off);
     int32_t *cand_cnt = at<int32_t>(ctx->scratch, l.cand_cnt);
     void *seg_par = at<void>(ctx->scratch, l.seg_par);
+    void *seg_run = at<void>(ctx->scratch, l.seg_run);
     uint32_t *thr = at<uint32_t>(ctx->scratch, l.thr);
     int32_t *sel = sel_idx_dev ? sel_idx_dev : at<int32_t>(ctx->scratch, l.sel);
     int32_t *sel_count = sel_count_dev ? sel_count_dev : at<int32_t>(ctx->scratch, l.sel_count);
@@ -521,15 +522,14 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
                                 c.n_centroids, S_sub, st);
     prof.end(0);
     int32_t *spans = at<int32_t>(ctx->scratch, l.spans);
-    uint32_t *hist = at<uint32_t>(ctx->scratch, l.hist);
-    csa::launch_top_centroids(z, rows, at<int32_t>(ctx->tables, l.part_off), spans, hist, BH,
+    csa::launch_top_centroids(z, rows, at<int32_t>(ctx->tables, l.part_off), spans, BH,
                               c.n_centroids, S_sub, c.n_probe, G, ctx->P, ctx->nsub, ctx->PO, st);
     prof.end(1);
-    csa::launch_accumulate(at<void>(ctx->tables, l.ent), rows, spans, cand_key, cand_bits, cand_cnt, hist, BH,
+    csa::launch_accumulate(at<void>(ctx->tables, l.ent), rows, spans, cand_key, bin_off, cand_cnt, BH,
                            Ct, l.Ls, M, G, ctx->R, ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, ws, st);
     prof.end(2);
-    csa::launch_threshold(cand_key, cand_cnt, sel, sel_count, thr, seg_par, hist, BH, c.budget_k, ctx->R,
-                          ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, st);
+    csa::launch_threshold(cand_key, cand_cnt, bin_off, sel, sel_count, thr, seg_par, seg_run, BH, c.budget_k,
+                          ctx->R, ctx->P, l.cand_keys, ctx->key_sh, st);
     prof.end(3);
     // the second half of the Top-K runs in the prologue of the attention workgroups when a key
     // range has one bitmap word per attention thread and the launch is small (it then saves a
@@ -537,14 +537,14 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
     // every workgroup's K/V stream and a kernel of its own measured 9 us of 420 faster
     const bool fused = c.budget_k > 0 && csa::attention_can_emit(ctx->R) && (int64_t)BH * S <= 2048;
     if (!fused) {
-        csa::launch_emit(cand_key, cand_bits, cand_cnt, thr, seg_par, sel, BH, c.budget_k, ctx->R, ctx->P,
+        csa::launch_emit(cand_key, seg_run, cand_cnt, thr, seg_par, sel, BH, c.budget_k, ctx->R, ctx->P,
                          l.cand_keys, st);
         prof.end(4);
     }
     prof.mark(5);
     csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, seg_par,
                                 part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ws, ctx->n,
-                                c.max_ctx, S, ctx->P, fused ? cand_key : nullptr, cand_bits, cand_cnt, thr,
+                                c.max_ctx, S, ctx->P, fused ? cand_key : nullptr, seg_run, cand_cnt, thr,
                                 ctx->R, l.cand_keys, st);
     prof.end(5);
     csa::launch_attention_merge(part, out_dev, BH, S, st);

@@ -42,7 +42,8 @@ constexpr int kSplit = kAttWaves * kItemsPerWave;  // 512 attended keys per work
 // grid ceil8(B*Hkv*S) * G workgroups (1-D, see the id mapping below), block 256.
 // ---------------------------------------------------------------------------------------------
 struct EmitArgs {  // what the prologue of an EMIT launch needs (see emit_range)
-    const uint32_t *cand_key, *cand_bits, *thr;
+    const uint32_t *cand_key, *thr;
+    const int2 *seg_run;
     const int32_t *seg_cnt;
     int R;
     size_t cand_stride;
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
     int P, int P_sel, int n_units, float qscale, EmitArgs ea)
 {
     __shared__ float s_m[kAttWaves], s_l[kAttWaves], s_o[kAttWaves][kHeadDim];
-    __shared__ __align__(16) uint32_t s_key[EMIT ? kEmitStage : 4];
+    __shared__ uint32_t s_bits[EMIT ? 2 * kAttNT : 4];  // winners' and ties' bitmaps of the key range
     __shared__ int s_scan[kAttWaves + 1];
     // XCD-aware order: the chip deals consecutive workgroup ids round-robin to its 8 XCDs (each
     // with its own L2).  The G workgroups that handle the same split of the same KV head get ids
@@ -75,8 +76,8 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
     const bool from_sel = s < P_sel;
     int first, count;
     if (from_sel && EMIT) {
-        count = emit_range<kAttNT>(ea.cand_key, ea.cand_bits, ea.seg_cnt, ea.thr, seg_par, sel, k, ea.R, P,
-                                   ea.cand_stride, head, s, s_key, s_scan, first);
+        count = emit_range<kAttNT>(ea.cand_key, ea.seg_run, ea.seg_cnt, ea.thr, seg_par, sel, k, ea.R, P,
+                                   ea.cand_stride, head, s, s_bits, s_scan, first);
         count = max(0, min(count, k - first));
         __syncthreads();  // the indices just written are read back below by other threads
     } else if (from_sel) {
@@ -294,7 +295,7 @@ void launch_attention_split(const void *q, const void *kc, const void *vc,
                             const int32_t *block_table, int32_t *sel, const int32_t *sel_count,
                             const void *seg_par, float *part, int B, int Hq, int Hkv, int k, int n_pre,
                             int n, int max_ctx, int S, int P, const uint32_t *cand_key,
-                            const uint32_t *cand_bits, const int32_t *seg_cnt, const uint32_t *thr, int R,
+                            const void *seg_run, const int32_t *seg_cnt, const uint32_t *thr, int R,
                             size_t cand_stride, hipStream_t st)
 {
     if (S <= 0) return;
@@ -303,7 +304,7 @@ void launch_attention_split(const void *q, const void *kc, const void *vc,
     const int n_units = B * Hkv * S;
     const int P_sel = k > 0 ? P : 0;
     const bool emit = cand_key != nullptr;  // (the caller has checked attention_can_emit(R))
-    const EmitArgs ea{cand_key, cand_bits, thr, seg_cnt, R, cand_stride};
+    const EmitArgs ea{cand_key, thr, (const int2 *)seg_run, seg_cnt, R, cand_stride};
     dim3 grid((n_units + kXcd - 1) / kXcd * kXcd * G), block(kAttNT);
 #define CSA_ATT(PAGED_, EMIT_)                                                                            \
     k_attention_split<PAGED_, EMIT_><<<grid, block, 0, st>>>(                                             \

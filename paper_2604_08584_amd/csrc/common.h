@@ -217,90 +217,80 @@ __device__ __forceinline__ uint32_t block_radix_threshold(ForEach for_each, int 
 
 
 // ---------------------------------------------------------------------------------------------
+// Candidate words.  The accumulation kernel leaves the candidates of (head, key range) grouped by
+// coarse bin of their accumulated score, best bin first: word = (score bits below the bin) <<
+// kIdxBits | key index within the range, with the start offset of every bin in bin_off[.][512]
+// (uint16; bin 512 would start at the range's candidate count).  The head's threshold is
+// B << kThrShift | T: candidates of bins before B are selected, of bin B those whose score bits
+// exceed T plus some whose bits equal T.
+// ---------------------------------------------------------------------------------------------
+constexpr int kCoarseBins = 512;
+constexpr int kIdxBits = 14;   // key index within a range of <= 16384 keys
+constexpr int kThrShift = 22;  // score bits within a bin: < 2^18
+
+// ---------------------------------------------------------------------------------------------
 // Top-K, second half (paper Sec. 3.3 (4)) for key range p of one head: the range writes its winners
-// - candidates with key > T plus its allowed number of lowest-index candidates with key == T - as
-// ascending key indices into sel[head], starting at its output slot.  Thread t owns bitmap word t
-// (32 key indices) and finds its keys by the rank of its bits; the keys are staged in LDS,
-// kEmitStage at a time (one round unless the range is unusually dense).  Every independent load
-// is issued before the first wait: the work is a chain of latencies, not of bytes.
-// All NT >= R/32 threads of the workgroup must call.  s_key: kEmitStage words, s_scan: NT/64 + 1.
+// - its candidates in bins better than the threshold's, those of the threshold's bin above the
+// threshold, plus its allowed number of lowest-index candidates equal to it - as ascending key
+// indices into sel[head], starting at its output slot.  The winners (a prefix of the range's
+// candidate words and part of one bin's run) set their bits in an LDS bitmap over the range; thread
+// t then owns bitmap word t and writes its indices at the rank of its bits.  The first words are
+// requested before the threshold is known: they are almost always the ones needed.
+// All NT >= R/32 threads of the workgroup must call.  s_bits: 2 * R/32 words, s_scan: NT/64 + 1.
 // Returns the number of winners written (uniform); `first` = the range's first output slot.
 // Ends with every thread past the last barrier but NOT with a barrier after the global writes.
 // ---------------------------------------------------------------------------------------------
-constexpr int kEmitStage = 2048;
-constexpr int kEmitPre = 12;  // keys of a bitmap word fetched up front
+constexpr int kEmitPre = 2;  // candidate words per thread requested up front
 
 template <int NT>
 __device__ __forceinline__ int emit_range(const uint32_t *__restrict__ cand_key,
-                                          const uint32_t *__restrict__ cand_bits,
+                                          const int2 *__restrict__ seg_run,
                                           const int32_t *__restrict__ seg_cnt,
                                           const uint32_t *__restrict__ thr,
                                           const int2 *__restrict__ seg_par, int32_t *__restrict__ sel,
                                           int k, int R, int P, size_t cand_stride, int head, int p,
-                                          uint32_t *s_key, int *s_scan, int &first)
+                                          uint32_t *s_bits, int *s_scan, int &first)
 {
-    const size_t seg0 = (size_t)head * cand_stride + (size_t)p * R;
-    const int n_stage = R < kEmitStage ? R : kEmitStage;  // slots [0, n_stage) exist in every segment
+    const uint32_t *dk = cand_key + (size_t)head * cand_stride + (size_t)p * R;
     const int W = R / 32;
-    const uint32_t word = (int)threadIdx.x < W ? cand_bits[seg0 / 32 + threadIdx.x] : 0u;
-    {
-        constexpr int ITER = kEmitStage / (NT * 4);  // every load is requested before the first is stored
-        uint4 v[ITER];
+    uint32_t *s_tie = s_bits + W;
+    uint32_t pre[kEmitPre];
 #pragma unroll
-        for (int u = 0; u < ITER; ++u) {
-            const int i = (u * NT + (int)threadIdx.x) * 4;
-            v[u] = i < n_stage ? *(const uint4 *)(cand_key + seg0 + i) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < ITER; ++u) {
-            const int i = (u * NT + (int)threadIdx.x) * 4;
-            if (i < n_stage) *(uint4 *)(s_key + i) = v[u];
-        }
+    for (int u = 0; u < kEmitPre; ++u) {
+        const int i = u * NT + (int)threadIdx.x;
+        pre[u] = i < R ? dk[i] : 0u;  // (slots past the count hold stale words; masked below)
     }
     const int c = min(seg_cnt[(size_t)head * P + p], R);
     const uint32_t T = thr[head];
     const int2 par = seg_par[(size_t)head * P + p];
+    const int2 run = seg_run[(size_t)head * P + p];  // (holds stale values when nothing is selected)
     first = par.x;
     if (c <= 0 || T == 0xFFFFFFFFu) return 0;  // (uniform over the workgroup)
-    int total;
-    const int rank = block_excl_scan<NT>(__popc(word), s_scan, total);  // (its barriers publish s_key)
-    uint32_t gt = 0, eq = 0;
-    for (int base = 0; base < c; base += kEmitStage) {
-        if (base) {
-            __syncthreads();
-            for (int i = threadIdx.x * 4; i < kEmitStage && base + i < c; i += NT * 4)
-                *(uint4 *)(s_key + i) = *(const uint4 *)(cand_key + seg0 + base + i);
-            __syncthreads();
-        }
-        // the word's keys sit at consecutive ranks: fetch the first kEmitPre of them with independent
-        // LDS reads before any is used (a bit-by-bit walk would pay one LDS round trip per key)
-        const int r0 = rank - base;
-        uint32_t kreg[kEmitPre];
-#pragma unroll
-        for (int i = 0; i < kEmitPre; ++i)
-            kreg[i] = (unsigned)(r0 + i) < (unsigned)kEmitStage ? s_key[r0 + i] : 0u;
-        uint32_t b = word;
-#pragma unroll
-        for (int i = 0; i < kEmitPre; ++i) {
-            if (b) {
-                if ((unsigned)(r0 + i) < (unsigned)kEmitStage) {
-                    const uint32_t bit = b & (0u - b);
-                    if (kreg[i] > T) gt |= bit;
-                    else if (kreg[i] == T) eq |= bit;
-                }
-                b &= b - 1;
-            }
-        }
-        int r = r0 + kEmitPre;
-        for (; b; b &= b - 1, ++r) {  // (rare: more than kEmitPre candidates in 32 key indices)
-            if ((unsigned)r < (unsigned)kEmitStage) {
-                const uint32_t bit = b & (0u - b);
-                const uint32_t key = s_key[r];
-                if (key > T) gt |= bit;
-                else if (key == T) eq |= bit;
-            }
-        }
+    const uint32_t Tl = T & ((1u << kThrShift) - 1u);
+    const int o0 = min(run.x, c);  // winners without a look: [0, o0)
+    const int o1 = min(run.y, c);  // the threshold's bin: [o0, o1)
+    if ((int)threadIdx.x < W) {
+        s_bits[threadIdx.x] = 0;
+        s_tie[threadIdx.x] = 0;
     }
+    __syncthreads();
+    auto place = [&](int i, uint32_t w) {
+        if (i < o1) {
+            const uint32_t idx = w & ((1u << kIdxBits) - 1u), bit = 1u << (idx & 31);
+            const uint32_t sc = w >> kIdxBits;
+            if (i < o0 || sc > Tl)
+                atomicOr(&s_bits[idx >> 5], bit);
+            else if (sc == Tl)
+                atomicOr(&s_tie[idx >> 5], bit);
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < kEmitPre; ++u) place(u * NT + (int)threadIdx.x, pre[u]);
+    for (int i = kEmitPre * NT + (int)threadIdx.x; i < o1; i += NT) place(i, dk[i]);
+    __syncthreads();
+    uint32_t bits = (int)threadIdx.x < W ? s_bits[threadIdx.x] : 0u;
+    uint32_t eq = (int)threadIdx.x < W ? s_tie[threadIdx.x] : 0u;
+    int total;
     // keep the lowest-index ties this range is allowed
     if (par.y <= 0) {
         eq = 0;
@@ -311,7 +301,7 @@ __device__ __forceinline__ int emit_range(const uint32_t *__restrict__ cand_key,
         else
             while (__popc(eq) > allow) eq &= ~(0x80000000u >> __clz(eq));  // drop the highest bit
     }
-    uint32_t bits = gt | eq;
+    bits |= eq;
     int pos = par.x + block_excl_scan<NT>(__popc(bits), s_scan, total);
     int32_t *out = sel + (size_t)head * k;
     const int kbase = p * R + (int)threadIdx.x * 32;

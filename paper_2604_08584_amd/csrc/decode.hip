@@ -146,16 +146,14 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
 // grid B*Hq*S, block 256.
 // ---------------------------------------------------------------------------------------------
 constexpr int kTopNT = 256;
-constexpr int kCoarseBins = 512;  // per-head histogram of accumulated scores, filled by k_accumulate
 constexpr int kTopReg = 16;     // keys per thread held in registers
 constexpr int kTopCand = 1024;  // candidate capacity of the fast path
 
 __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restrict__ z,
                                                           int32_t *__restrict__ rows,
                                                           const int32_t *__restrict__ part_off,
-                                                          int32_t *__restrict__ spans,
-                                                          uint32_t *__restrict__ hist_g, int C,
-                                                          int S, int m, int G, int P, int nsub, int PO)
+                                                          int32_t *__restrict__ spans, int C, int S,
+                                                          int m, int G, int P, int nsub, int PO)
 {
     const int head = blockIdx.x / S, sub = blockIdx.x - head * S;
     const int M = S * m;
@@ -168,8 +166,6 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
     const float *zh = z + (size_t)blockIdx.x * C;
     int32_t *out = rows + (size_t)head * M + sub * m;
     if (threadIdx.x == 0) s_slot = 0;
-    if (sub == 0)
-        for (int i = threadIdx.x; i < kCoarseBins; i += kTopNT) hist_g[(size_t)head * kCoarseBins + i] = 0;
     const bool in_regs = C <= kTopNT * kTopReg;
     uint32_t kreg[kTopReg];
     if (in_regs) {
@@ -311,11 +307,9 @@ publish:
 }
 
 void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, int32_t *spans,
-                          uint32_t *hist_g, int n_heads, int C, int S, int tau, int G, int P, int nsub,
-                          int PO, hipStream_t st)
+                          int n_heads, int C, int S, int tau, int G, int P, int nsub, int PO, hipStream_t st)
 {
-    k_top_centroids<<<n_heads * S, kTopNT, 0, st>>>(z, rows, part_off, spans, hist_g, C, S, tau, G, P, nsub,
-                                                    PO);
+    k_top_centroids<<<n_heads * S, kTopNT, 0, st>>>(z, rows, part_off, spans, C, S, tau, G, P, nsub, PO);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -340,9 +334,8 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
                                                    const int32_t *__restrict__ rows,
                                                    const int32_t *__restrict__ spans,
                                                    uint32_t *__restrict__ cand_key,
-                                                   uint32_t *__restrict__ cand_bits,
-                                                   int32_t *__restrict__ seg_cnt,
-                                                   uint32_t *__restrict__ hist_g, int C, int Ls,
+                                                   uint16_t *__restrict__ bin_off,
+                                                   int32_t *__restrict__ seg_cnt, int C, int Ls,
                                                    int m, int G, int P, size_t cand_stride,
                                                    uint32_t key_lo, int key_sh, int excl_from)
 {
@@ -352,8 +345,8 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     constexpr int NB = NSUB + 1;
     extern __shared__ __align__(16) int32_t s_acc[];  // [R]
     __shared__ int32_t s_b[64 * NB], s_row[64];
-    __shared__ uint32_t s_h[kCoarseBins];
-    __shared__ unsigned long long s_scan[NW + 1];
+    __shared__ uint32_t s_h[kCoarseBins], s_pos[kCoarseBins];
+    __shared__ int s_scan[NW + 1];
     const int p = blockIdx.x, head = blockIdx.y;
     const int bg = head / G;
     const int wave = threadIdx.x / kWave, lane = lane_id();
@@ -415,11 +408,8 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
         }
     }
     __syncthreads();
-    // thread t owns the slot groups 4*(u*NT + t) .. +3, u < 4 (128-bit LDS reads); walking
-    // (u, t, slot) in this order is walking the key indices in ascending order
+    // thread t owns the slot groups 4*(u*NT + t) .. +3, u < 4 (128-bit LDS reads)
     int4 a[4];
-    uint32_t nib[4];
-    unsigned long long packed = 0;
     // key indices at or above excl_from (the always-attended recent window, which streaming updates
     // may have put into the tables) are not candidates; only the last range(s) can hold any
     const bool has_excl = p * R + R > excl_from;  // (uniform over the workgroup)
@@ -433,52 +423,68 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
             if (i0 + 2 >= excl_from) a[u].z = 0;
             if (i0 + 3 >= excl_from) a[u].w = 0;
         }
-        nib[u] = (a[u].x != 0 ? 1u : 0u) | (a[u].y != 0 ? 2u : 0u) | (a[u].z != 0 ? 4u : 0u) |
-                 (a[u].w != 0 ? 8u : 0u);
-        packed |= (unsigned long long)__popc(nib[u]) << (16 * u);
     }
-    unsigned long long tot4;
-    const unsigned long long pre4 = block_excl_scan_4x16<NT>(packed, s_scan, tot4);
-    uint32_t *dk = cand_key + (size_t)head * cand_stride + (size_t)p * R;
-    uint32_t *db = cand_bits + ((size_t)head * cand_stride + (size_t)p * R) / 32;
-    // sparse -> dense through LDS (every accumulator is in registers by now, so the array is free):
-    // the non-zero accumulators land at their rank, the per-slot work stays minimal
-    int32_t *s_dense = s_acc;
-    int group_base = 0;
+    // The candidates leave grouped by coarse bin of their accumulated score, best bin first (a
+    // counting sort through LDS): word = (score bits below the bin) << kIdxBits | slot in the range.
+    // The Top-K threshold then needs the per-range bin offsets and the one bin it falls in, and a
+    // range's winners are a prefix of its candidates plus part of that bin.
+    // pass 1: occupancy of the bins (reversed: bin 0 holds the largest scores)
+    const uint32_t low_mask = (1u << key_sh) - 1u;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        int rank = group_base + (int)((pre4 >> (16 * u)) & 0xFFFFu);
         const int av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
 #pragma unroll
         for (int x = 0; x < 4; ++x)
-            if (av[x] != 0) s_dense[rank++] = av[x];
-        // eight neighbouring lanes hold the 32 bits of one bitmap word
-        uint32_t w = nib[u] << (4 * (lane & 7));
-        w |= __shfl_xor(w, 1, kWave);
-        w |= __shfl_xor(w, 2, kWave);
-        w |= __shfl_xor(w, 4, kWave);
-        if ((lane & 7) == 0) db[(u * NT + (int)threadIdx.x) >> 3] = w;
-        group_base += (int)((tot4 >> (16 * u)) & 0xFFFFu);
+            if (av[x] != 0) {
+                const uint32_t d = (uint32_t)((av[x] >> kCntBits) + kKeyBias) - key_lo;
+                atomicAdd(&s_h[(kCoarseBins - 1) - (d >> key_sh)], 1u);
+            }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < group_base; i += NT) {
-        const uint32_t key = (uint32_t)((s_dense[i] >> kCntBits) + kKeyBias);
-        dk[i] = key;
-        atomicAdd(&s_h[(key - key_lo) >> key_sh], 1u);
+    // exclusive scan over the bins: where each bin's run starts (kept in LDS as the running write
+    // position of the bin, and written out for the selection kernels)
+    constexpr int BPT = NT >= kCoarseBins ? 1 : kCoarseBins / NT;  // bins per owning thread
+    const bool owner = (int)threadIdx.x * BPT < kCoarseBins;
+    int cnt[BPT], mine = 0;
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+        cnt[j] = owner ? (int)s_h[threadIdx.x * BPT + j] : 0;
+        mine += cnt[j];
     }
-    if (threadIdx.x == 0) seg_cnt[(size_t)head * P + p] = group_base;
-    // histogram complete once every wave's LDS atomics have landed: wait for LDS traffic only
-    // (a full __syncthreads would also wait for the candidate stores above)
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), vmcnt / expcnt untouched
-    __builtin_amdgcn_s_barrier();
-    for (int e = threadIdx.x; e < kCoarseBins; e += NT) {
-        const uint32_t c = s_h[e];
-        if (c) atomicAdd(&hist_g[(size_t)head * kCoarseBins + e], c);
+    int total;
+    int start = block_excl_scan<NT>(mine, (int *)s_scan, total);
+    uint16_t *bo = bin_off + ((size_t)head * P + p) * kCoarseBins;
+    if (owner) {
+#pragma unroll
+        for (int j = 0; j < BPT; ++j) {
+            s_pos[threadIdx.x * BPT + j] = (uint32_t)start;
+            bo[threadIdx.x * BPT + j] = (uint16_t)start;
+            start += cnt[j];
+        }
     }
+    __syncthreads();
+    // pass 2: every candidate takes the next position of its bin (every accumulator is in
+    // registers by now, so the accumulator array is free to hold the sorted words)
+    uint32_t *s_out = (uint32_t *)s_acc;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+            if (av[x] != 0) {
+                const uint32_t d = (uint32_t)((av[x] >> kCntBits) + kKeyBias) - key_lo;
+                const uint32_t at = atomicAdd(&s_pos[(kCoarseBins - 1) - (d >> key_sh)], 1u);
+                s_out[at] = ((d & low_mask) << kIdxBits) | (uint32_t)(4 * (u * NT + (int)threadIdx.x) + x);
+            }
+    }
+    __syncthreads();
+    uint32_t *dk = cand_key + (size_t)head * cand_stride + (size_t)p * R;
+    for (int i = threadIdx.x; i < total; i += NT) dk[i] = s_out[i];
+    if (threadIdx.x == 0) seg_cnt[(size_t)head * P + p] = total;
 }
 
 void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *spans, uint32_t *cand_key,
-                       uint32_t *cand_bits, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
+                       uint16_t *bin_off, int32_t *seg_cnt, int n_heads, int C,
                        int Ls, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
                        int key_sh, int excl_from, hipStream_t st)
 {
@@ -491,7 +497,7 @@ void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *span
     }
 #define CSA_ACC(NT_)                                                                              \
     k_accumulate<NT_><<<grid, NT_, (size_t)R * 4, st>>>((const uint32_t *)ent, rows, spans, cand_key, \
-                                                        cand_bits, seg_cnt, hist_g, C, Ls, m, G, P,  \
+                                                        bin_off, seg_cnt, C, Ls, m, G, P,  \
                                                         cand_stride, key_lo, key_sh, excl_from)
     switch (R) {
     case 1024: CSA_ACC(64); break;
@@ -504,50 +510,55 @@ void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *span
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 4, first half: the Top-K threshold of one head (Sec. 3.3 (4)): the key T such that the
-// min(k, |U|) winners are every candidate with key > T plus the `need` lowest-index candidates
-// with key == T.  Range refinement: the live key range [lo, hi] is cut into <= 512 equal bins
-// and a histogram of the candidate keys over them is taken (the first one arrives ready-made
-// from the accumulation kernel; a further one costs a streaming pass and is rarely needed); the
-// bin holding the k-th largest becomes the new range; once it holds few enough keys they are
-// gathered into LDS (tagged with their key range) and finished there with a radix search.  The
-// same streaming pass counts, per key range p, the candidates above the bin, so that the
-// kernel can hand every range its output offset and its share of the threshold ties:
-//   seg_par[head][p] = (first output slot of range p, ties range p may keep), thr[head] = T.
-// Nothing selected (k = 0 or no candidate): T = 0xFFFFFFFF.  Everything selected: T = 0.
-// grid B*Hq, block 1024.
+// Step 4, first half: the Top-K threshold of one head (Sec. 3.3 (4)).  The accumulation kernel
+// left every key range's candidates grouped by coarse score bin (best first) with the bins' start
+// offsets, so the head's histogram is a sum of offset differences, the bin B holding the k-th
+// largest score follows from it, and everything in better bins is selected without being looked
+// at.  Only the candidates of bin B (a run per key range) are read: their scores within the bin
+// are searched for the value T such that the winners are every candidate above T plus the `need`
+// lowest-index candidates equal to T - in LDS by a radix search when the bin holds few enough,
+// else by refining the range with histogram passes over the runs first.  Output:
+//   thr[head] = B << kThrShift | T   (0xFFFFFFFF: nothing selected; B = 512: every candidate),
+//   seg_par[head][p] = (first output slot of range p, ties range p may keep).
+// grid B*Hq, block NT.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSelCap = 4096;   // contenders finished in LDS
 constexpr int kSelMaxP = 2048;  // key ranges (segments) per head
-constexpr int kSegBits = 11;    // a contender is (key - lo) << kSegBits | p
+constexpr int kSegBits = 11;    // a contender is (score within the bin) << kSegBits | p
 static_assert((1 << kSegBits) >= kSelMaxP, "segment tag too narrow");
 
 template <int kThrNT>
 __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict__ cand_key,
                                                       const int32_t *__restrict__ seg_cnt,
+                                                      const uint16_t *__restrict__ bin_off,
                                                       int32_t *__restrict__ sel,
                                                       int32_t *__restrict__ sel_count,
                                                       uint32_t *__restrict__ thr,
                                                       int2 *__restrict__ seg_par,
-                                                      const uint32_t *__restrict__ hist_g, int k,
-                                                      int R, int P, size_t cand_stride,
-                                                      uint32_t key_lo, int key_sh)
+                                                      int2 *__restrict__ seg_run, int k, int R, int P,
+                                                      size_t cand_stride, int key_sh)
 {
     constexpr int NW = kThrNT / kWave;
     __shared__ uint32_t s_hist[512 + kThrNT / kWave + 2];
     __shared__ int s_scan[kThrNT / kWave + 1];
     __shared__ uint32_t s_ck[kSelCap];
     __shared__ int32_t s_cnt[kSelMaxP], s_gt[kSelMaxP], s_eq[kSelMaxP];
+    __shared__ uint16_t s_beg[kSelMaxP], s_end[kSelMaxP];  // the run of bin B in every range
     __shared__ int s_n;
+    static_assert(kCoarseBins == 512 && kCoarseBins <= kThrNT, "one bin per thread");
     const int head = blockIdx.x;
     const uint32_t *hk = cand_key + (size_t)head * cand_stride;
+    const uint16_t *bo = bin_off + (size_t)head * P * kCoarseBins;
     int32_t *out = sel + (size_t)head * k;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();  // (scalar)
-    // The kernel is a chain of memory latencies, so everything that can be requested before the
-    // first wait is: the segment counts, the coarse histogram, and - speculatively - the first
-    // 1024 key slots of the segment this wave walks first (slots past the segment's count hold
-    // stale keys and are masked once the count is known).  Later chunks are requested one ahead.
-    // (Holding more keys in registers would cost the second workgroup per CU.)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
+    // the head's histogram, bin j = sum over the ranges of (start of bin j+1) - (start of bin j):
+    // a wave reads a range's 512 offsets with one 16-byte load per lane (lane = eight consecutive
+    // bins); the first two ranges of every wave are requested before anything is waited for
+    static_assert(kCoarseBins == 8 * kWave, "one 16-byte load per lane covers a range's offsets");
+    auto hist_load = [&](int p) {
+        return p < P ? *(const uint4 *)(bo + (size_t)p * kCoarseBins + lane * 8) : make_uint4(0, 0, 0, 0);
+    };
+    const uint4 hpre0 = hist_load(wave), hpre1 = hist_load(wave + NW);
     int part = 0;
     for (int p = threadIdx.x; p < kSelMaxP; p += kThrNT) {
         const int c = p < P ? min(seg_cnt[(size_t)head * P + p], R) : 0;
@@ -556,165 +567,85 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
         s_eq[p] = 0;
         part += c;
     }
-    const uint32_t my_hist = threadIdx.x < kCoarseBins ? hist_g[(size_t)head * kCoarseBins + threadIdx.x] : 0u;
-    uint32_t pre0[16];
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        const int e = (x * kWave + lane) * 4;
-        uint4 v0 = make_uint4(0, 0, 0, 0);
-        if (wave < P) v0 = *(const uint4 *)(hk + (size_t)wave * R + e);  // e + 3 < 1024 <= R
-        pre0[4 * x] = v0.x; pre0[4 * x + 1] = v0.y; pre0[4 * x + 2] = v0.z; pre0[4 * x + 3] = v0.w;
-    }
+    for (int i = threadIdx.x; i < 512; i += kThrNT) s_hist[i] = 0;  // (walked top = best by block_pick_bin)
     if (threadIdx.x == 0) s_n = 0;
     int n_total;
     block_excl_scan<kThrNT>(part, s_scan, n_total);  // (its barriers also publish the LDS writes)
     const int k_eff = n_total < k ? n_total : k;
     if (threadIdx.x == 0) sel_count[head] = k_eff;
     for (int a = k_eff + threadIdx.x; a < k; a += kThrNT) out[a] = -1;
-    {
-        const int c = wave < P ? __builtin_amdgcn_readfirstlane(s_cnt[wave]) : 0;
-#pragma unroll
-        for (int x = 0; x < 4; ++x)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int e = (x * kWave + lane) * 4 + j;
-                if (e >= c) pre0[4 * x + j] = 0u;
-            }
-    }
-
-    // stream(chunk, seg_end): chunk(keys, p) for every 16 x 64 candidate keys of every segment p
-    // (keys[] = this lane's 16; 0 = padding - a real key is never 0), then seg_end(p).  A wave
-    // walks whole segments, four consecutive keys per lane and load; both callbacks may use
-    // wave-level operations only.
-    auto stream = [&](auto chunk, auto seg_end) {
-        auto fetch = [&](uint32_t (&dst)[16], int p, int c, int e0) {
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int e = e0 + (x * kWave + lane) * 4;
-                const uint4 v = e < c ? *(const uint4 *)(hk + (size_t)p * R + e) : make_uint4(0, 0, 0, 0);
-                dst[4 * x + 0] = v.x;
-                dst[4 * x + 1] = e + 1 < c ? v.y : 0u;
-                dst[4 * x + 2] = e + 2 < c ? v.z : 0u;
-                dst[4 * x + 3] = e + 3 < c ? v.w : 0u;
-            }
-        };
-        for (int p = wave; p < P; p += NW) {
-            const int c = __builtin_amdgcn_readfirstlane(s_cnt[p]);  // (scalar loop bounds)
-            uint32_t cur[16], nxt[16];
-            if (p == wave) {  // (wave-uniform)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) cur[i] = pre0[i];
-            } else if (c > 0) {
-                fetch(cur, p, c, 0);
-            }
-            for (int e0 = 0; e0 < c; e0 += kWave * 16) {
-                const bool more = e0 + kWave * 16 < c;
-                if (more) fetch(nxt, p, c, e0 + kWave * 16);  // in flight while this chunk is worked on
-                chunk(cur, p);
-                if (more) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) cur[i] = nxt[i];
-                }
-            }
-            seg_end(p);
-        }
-    };
 
     uint32_t T = 0xFFFFFFFFu;
     int need = 0;
     if (k_eff > 0 && n_total <= k) {
-        T = 0;  // every candidate wins
-        for (int p = threadIdx.x; p < P; p += kThrNT) s_gt[p] = s_cnt[p];
+        T = (uint32_t)kCoarseBins << kThrShift;  // every candidate wins
+        for (int p = threadIdx.x; p < P; p += kThrNT) {
+            s_gt[p] = s_cnt[p];
+            s_beg[p] = s_end[p] = (uint16_t)s_cnt[p];
+        }
     } else if (k_eff > 0) {
-        // first round: the head's coarse histogram, filled by the accumulation kernel
-        uint32_t lo = key_lo, hi = key_lo + ((uint32_t)kCoarseBins << key_sh) - 1u;
-        int sh = key_sh;
-        static_assert(kCoarseBins <= kThrNT, "one bin per thread");
-        if (threadIdx.x < kCoarseBins) s_hist[threadIdx.x] = my_hist;
+        for (int p = wave, it = 0; p < P; p += NW, ++it) {
+            const uint4 v = it == 0 ? hpre0 : it == 1 ? hpre1 : hist_load(p);
+            // start of the bin after this lane's eight: the next lane's first, or the range's count
+            uint32_t nxt = (uint32_t)__shfl_down((int)(v.x & 0xFFFFu), 1, kWave);
+            if (lane == kWave - 1) nxt = (uint32_t)s_cnt[p];
+            const uint32_t o[9] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16, v.z & 0xFFFFu,
+                                   v.z >> 16, v.w & 0xFFFFu, v.w >> 16, nxt};
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (o[i + 1] > o[i]) atomicAdd(&s_hist[(kCoarseBins - 1) - (lane * 8 + i)], o[i + 1] - o[i]);
+        }
         __syncthreads();
-        int want = k;
-        for (bool have_hist = true;; have_hist = false) {
-            if (!have_hist) {
-                sh = 0;
-                while (((hi - lo) >> sh) >= 512u) ++sh;
-                for (int i = threadIdx.x; i < 512; i += kThrNT) s_hist[i] = 0;
-                __syncthreads();
-                stream([&](const uint32_t (&keys)[16], int) {
-#pragma unroll
-                           for (int i = 0; i < 16; ++i) {
-                               const bool in = keys[i] >= lo && keys[i] <= hi;
-                               hist_add(s_hist, in ? (keys[i] - lo) >> sh : 0u, in);
-                           }
-                       },
-                       [&](int) {});
-                __syncthreads();
+        int above;
+        const int top_bin = block_pick_bin<kThrNT, 512>(s_hist, k, s_hist + 512, above);
+        const int B = (kCoarseBins - 1) - top_bin;  // as the accumulation kernel numbers the bins
+        int in_bin = (int)s_hist[top_bin];
+        int want = k - above;  // how many of bin B's candidates are selected (>= 1)
+        for (int p = threadIdx.x; p < P; p += kThrNT) {
+            const int c = s_cnt[p];
+            const int b0 = c > 0 ? (int)bo[(size_t)p * kCoarseBins + B] : 0;
+            const int b1 = c > 0 ? (B + 1 < kCoarseBins ? (int)bo[(size_t)p * kCoarseBins + B + 1] : c) : 0;
+            s_beg[p] = (uint16_t)b0;
+            s_end[p] = (uint16_t)b1;
+            s_gt[p] = b0;  // every candidate of a better bin
+        }
+        __syncthreads();
+        // runs(fn, seg_end): fn(score within the bin, valid, p) for the candidates of bin B of every
+        // range p (a wave walks whole runs, one candidate per lane and round), then seg_end(p)
+        auto runs = [&](auto fn, auto seg_end) {
+            for (int p = wave; p < P; p += NW) {
+                const int b0 = __builtin_amdgcn_readfirstlane((int)s_beg[p]);
+                const int b1 = __builtin_amdgcn_readfirstlane((int)s_end[p]);
+                for (int e0 = b0; e0 < b1; e0 += kWave) {
+                    const bool valid = e0 + lane < b1;
+                    const uint32_t w = valid ? hk[(size_t)p * R + e0 + lane] : 0u;
+                    fn(w >> kIdxBits, valid, p);
+                }
+                seg_end(p);
             }
-            int above;
-            const int bin = block_pick_bin<kThrNT, 512>(s_hist, want, s_hist + 512, above);
-            const int in_bin = (int)s_hist[bin];
-            want -= above;
-            lo += (uint32_t)bin << sh;
-            hi = min(hi, lo + ((1u << sh) - 1u));
-            if (sh == 0) {
-                // the bin is a single key value: count, per range, the keys above and equal to it
-                T = lo;
-                need = want;
-                int n_gt = 0, n_eq = 0;
-                stream([&](const uint32_t (&keys)[16], int) {
-#pragma unroll
-                           for (int i = 0; i < 16; ++i) {
-                               n_gt += keys[i] > T ? 1 : 0;
-                               n_eq += keys[i] == T ? 1 : 0;
-                           }
-                       },
-                       [&](int p) {
-                           n_gt = wave_sum(n_gt);
-                           n_eq = wave_sum(n_eq);
-                           if (lane == 0) {
-                               s_gt[p] = n_gt;
-                               s_eq[p] = n_eq;
-                           }
-                           n_gt = 0;
-                           n_eq = 0;
-                       });
-                break;
-            }
+        };
+        // the live score range [lo, hi] within the bin, narrowed until few enough candidates remain
+        uint32_t lo = 0, hi = (1u << key_sh) - 1u;
+        for (;;) {
             if (in_bin <= kSelCap) {
-                // gather the contenders (key - lo < 2^sh <= 2^16), tagged with their range; count per
-                // range the keys above the bin (sure winners)
-                __syncthreads();
-                // (counts are taken with wave votes: they live in scalar registers and cost one
-                // vector compare per key; the rare contenders are placed vote by vote)
-                int n_gt = 0;  // wave-uniform
-                const uint32_t width = hi - lo;
-                stream([&](const uint32_t (&keys)[16], int p) {
-                           unsigned long long in[16];
-                           int n_in = 0;
-#pragma unroll
-                           for (int i = 0; i < 16; ++i) {
-                               n_gt += __popcll(__ballot(keys[i] > hi));
-                               in[i] = __ballot(keys[i] - lo <= width);
-                               n_in += __popcll(in[i]);
-                           }
-                           if (n_in) {
-                               // one LDS atomic per wave and chunk reserves room for all its contenders
-                               int o = 0;
-                               if (lane == 0) o = atomicAdd(&s_n, n_in);
-                               o = __builtin_amdgcn_readfirstlane(o);
-#pragma unroll
-                               for (int i = 0; i < 16; ++i)
-                                   if (in[i]) {  // (wave-uniform)
-                                       const int mine = o + mbcnt(in[i]);
-                                       if (keys[i] - lo <= width && mine < kSelCap)
-                                           s_ck[mine] = ((keys[i] - lo) << kSegBits) | (uint32_t)p;
-                                       o += __popcll(in[i]);
-                                   }
-                           }
-                       },
-                       [&](int p) {
-                           if (lane == 0) s_gt[p] = n_gt;
-                           n_gt = 0;
-                       });
+                // gather the contenders, tagged with their range; candidates above the live range are
+                // sure winners of their range
+                int n_gt = 0;  // (wave-uniform)
+                runs([&](uint32_t key, bool valid, int p) {
+                         n_gt += __popcll(__ballot(valid && key > hi));
+                         const bool in = valid && key >= lo && key <= hi;
+                         const unsigned long long m = __ballot(in);
+                         if (m) {
+                             int o = 0;
+                             if (lane == 0) o = atomicAdd(&s_n, __popcll(m));
+                             o = __builtin_amdgcn_readfirstlane(o) + mbcnt(m);
+                             if (in && o < kSelCap) s_ck[o] = ((key - lo) << kSegBits) | (uint32_t)p;
+                         }
+                     },
+                     [&](int p) {
+                         if (lane == 0 && n_gt) s_gt[p] += n_gt;
+                         n_gt = 0;
+                     });
                 __syncthreads();
                 const int nc = min(s_n, kSelCap);
                 const uint32_t Tl = block_radix_threshold<kThrNT, 8, 2>(
@@ -725,7 +656,7 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
                         }
                     },
                     want, s_hist, need);
-                T = lo + Tl;
+                T = ((uint32_t)B << kThrShift) | (lo + Tl);
                 for (int a = threadIdx.x; a < nc; a += kThrNT) {
                     const uint32_t c = s_ck[a];
                     const uint32_t kk = c >> kSegBits;
@@ -737,7 +668,43 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
                 }
                 break;
             }
-            __syncthreads();  // s_hist[bin] was read above; the next round clears the histogram
+            if (lo == hi) {
+                // a single score value: count, per range, the candidates above and equal to it
+                T = ((uint32_t)B << kThrShift) | lo;
+                need = want;
+                int n_gt = 0, n_eq = 0;
+                runs([&](uint32_t key, bool valid, int) {
+                         n_gt += __popcll(__ballot(valid && key > lo));
+                         n_eq += __popcll(__ballot(valid && key == lo));
+                     },
+                     [&](int p) {
+                         if (lane == 0) {
+                             s_gt[p] += n_gt;
+                             s_eq[p] = n_eq;
+                         }
+                         n_gt = 0;
+                         n_eq = 0;
+                     });
+                break;
+            }
+            // too many: histogram of the live range over <= 512 equal bins, keep the bin with the
+            // want-th largest
+            int sh = 0;
+            while (((hi - lo) >> sh) >= 512u) ++sh;
+            __syncthreads();
+            for (int i = threadIdx.x; i < 512; i += kThrNT) s_hist[i] = 0;
+            __syncthreads();
+            runs([&](uint32_t key, bool valid, int) {
+                     const bool in = valid && key >= lo && key <= hi;
+                     hist_add(s_hist, in ? (key - lo) >> sh : 0u, in);
+                 },
+                 [&](int) {});
+            __syncthreads();
+            const int bin = block_pick_bin<kThrNT, 512>(s_hist, want, s_hist + 512, above);
+            in_bin = (int)s_hist[bin];
+            want -= above;
+            lo += (uint32_t)bin << sh;
+            hi = min(hi, lo + ((1u << sh) - 1u));
         }
     }
     __syncthreads();
@@ -761,25 +728,29 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
     int off = block_excl_scan<kThrNT>(take_mine, s_scan, dummy);
 #pragma unroll
     for (int i = 0; i < RPT; ++i) {
-        if (p0 + i < P) seg_par[(size_t)head * P + p0 + i] = make_int2(off, al[i]);
+        if (p0 + i < P) {
+            seg_par[(size_t)head * P + p0 + i] = make_int2(off, al[i]);
+            if (T != 0xFFFFFFFFu)
+                seg_run[(size_t)head * P + p0 + i] = make_int2((int)s_beg[p0 + i], (int)s_end[p0 + i]);
+        }
         off += s_gt[p0 + i] + al[i];
     }
     if (threadIdx.x == 0) thr[head] = T;
 }
 
-void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t *sel, int32_t *sel_count,
-                      uint32_t *thr, void *seg_par, const uint32_t *hist_g, int n_heads, int k, int R,
-                      int P, size_t cand_stride, uint32_t key_lo, int key_sh, hipStream_t st)
+void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, const uint16_t *bin_off, int32_t *sel,
+                      int32_t *sel_count, uint32_t *thr, void *seg_par, void *seg_run, int n_heads, int k,
+                      int R, int P, size_t cand_stride, int key_sh, hipStream_t st)
 {
-    // A 1024-thread workgroup (one wave per key range at 16 ranges) has the shorter latency, but its
-    // registers allow one workgroup per CU; with more heads than CUs, 512-thread workgroups - two
-    // per CU - run all heads at once instead of in two rounds.
+    // two 512-thread workgroups fit a CU: with more heads than CUs all heads run at once
     if (n_heads > 256)
-        k_threshold<512><<<n_heads, 512, 0, st>>>(cand_key, seg_cnt, sel, sel_count, thr, (int2 *)seg_par, hist_g,
-                                                  k, R, P, cand_stride, key_lo, key_sh);
+        k_threshold<512><<<n_heads, 512, 0, st>>>(cand_key, seg_cnt, bin_off, sel, sel_count, thr,
+                                                  (int2 *)seg_par, (int2 *)seg_run, k, R, P, cand_stride,
+                                                  key_sh);
     else
-        k_threshold<1024><<<n_heads, 1024, 0, st>>>(cand_key, seg_cnt, sel, sel_count, thr, (int2 *)seg_par,
-                                                    hist_g, k, R, P, cand_stride, key_lo, key_sh);
+        k_threshold<1024><<<n_heads, 1024, 0, st>>>(cand_key, seg_cnt, bin_off, sel, sel_count, thr,
+                                                    (int2 *)seg_par, (int2 *)seg_run, k, R, P, cand_stride,
+                                                    key_sh);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -789,28 +760,28 @@ void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t 
 // ---------------------------------------------------------------------------------------------
 template <int NT>
 __global__ __launch_bounds__(NT) void k_emit(const uint32_t *__restrict__ cand_key,
-                                             const uint32_t *__restrict__ cand_bits,
+                                             const int2 *__restrict__ seg_run,
                                              const int32_t *__restrict__ seg_cnt,
                                              const uint32_t *__restrict__ thr,
                                              const int2 *__restrict__ seg_par,
                                              int32_t *__restrict__ sel, int k, int R, int P,
                                              size_t cand_stride)
 {
-    __shared__ __align__(16) uint32_t s_key[kEmitStage];
+    __shared__ uint32_t s_bits[2 * NT];  // NT >= R/32 words each for the winners and the ties
     __shared__ int s_scan[NT / kWave + 1];
     int first;
-    (void)emit_range<NT>(cand_key, cand_bits, seg_cnt, thr, seg_par, sel, k, R, P, cand_stride, blockIdx.y,
-                         blockIdx.x, s_key, s_scan, first);
+    (void)emit_range<NT>(cand_key, seg_run, seg_cnt, thr, seg_par, sel, k, R, P, cand_stride, blockIdx.y,
+                         blockIdx.x, s_bits, s_scan, first);
 }
 
-void launch_emit(const uint32_t *cand_key, const uint32_t *cand_bits, const int32_t *seg_cnt,
+void launch_emit(const uint32_t *cand_key, const void *seg_run, const int32_t *seg_cnt,
                  const uint32_t *thr, const void *seg_par, int32_t *sel, int n_heads, int k, int R, int P,
                  size_t cand_stride, hipStream_t st)
 {
     if (k <= 0) return;
     dim3 grid(P, n_heads);
-#define CSA_EMIT(NT_)                                                                                \
-    k_emit<NT_><<<grid, NT_, 0, st>>>(cand_key, cand_bits, seg_cnt, thr, (const int2 *)seg_par, sel, k, R, P, \
+#define CSA_EMIT(NT_)                                                                               \
+    k_emit<NT_><<<grid, NT_, 0, st>>>(cand_key, (const int2 *)seg_run, seg_cnt, thr, (const int2 *)seg_par, sel, k, R, P, \
                                       cand_stride)
     switch (R) {
     case 1024: CSA_EMIT(64); break;

@@ -44,16 +44,18 @@ int cluster_problem(const void *q_group, int n_pre, int n_pool, int S, int sub, 
 void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
                             int C, int S, hipStream_t st);
 void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, int32_t *spans,
-                          uint32_t *hist_g, int n_heads, int C, int S, int tau, int G, int P, int nsub,
-                          int PO, hipStream_t st);
+                          int n_heads, int C, int S, int tau, int G, int P, int nsub, int PO, hipStream_t st);
+// candidates of (head, key range): cand_key (words grouped by coarse score bin, best first),
+// bin_off[.][512] (start of every bin), seg_cnt (how many)
 void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *spans, uint32_t *cand_key,
-                       uint32_t *cand_bits, int32_t *seg_cnt, uint32_t *hist_g, int n_heads, int C,
+                       uint16_t *bin_off, int32_t *seg_cnt, int n_heads, int C,
                        int Ls, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
                        int key_sh, int excl_from, hipStream_t st);
-void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, int32_t *sel, int32_t *sel_count,
-                      uint32_t *thr, void *seg_par, const uint32_t *hist_g, int n_heads, int k, int R,
-                      int P, size_t cand_stride, uint32_t key_lo, int key_sh, hipStream_t st);
-void launch_emit(const uint32_t *cand_key, const uint32_t *cand_bits, const int32_t *seg_cnt,
+// seg_run[head][p] = where the threshold's bin starts and ends among the candidates of range p
+void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, const uint16_t *bin_off, int32_t *sel,
+                      int32_t *sel_count, uint32_t *thr, void *seg_par, void *seg_run, int n_heads, int k,
+                      int R, int P, size_t cand_stride, int key_sh, hipStream_t st);
+void launch_emit(const uint32_t *cand_key, const void *seg_run, const int32_t *seg_cnt,
                  const uint32_t *thr, const void *seg_par, int32_t *sel, int n_heads, int k, int R, int P,
                  size_t cand_stride, hipStream_t st);
 
@@ -65,7 +67,7 @@ void launch_attention_split(const void *q, const void *kc, const void *vc,
                             const int32_t *block_table, int32_t *sel, const int32_t *sel_count,
                             const void *seg_par, float *part, int B, int Hq, int Hkv, int k, int n_pre,
                             int n, int max_ctx, int S, int P, const uint32_t *cand_key,
-                            const uint32_t *cand_bits, const int32_t *seg_cnt, const uint32_t *thr, int R,
+                            const void *seg_run, const int32_t *seg_cnt, const uint32_t *thr, int R,
                             size_t cand_stride, hipStream_t st);
 bool attention_can_emit(int R);
 void launch_range_offsets(const int32_t *sel, const int32_t *sel_count, void *seg_par, int n_heads, int k,
