@@ -57,6 +57,8 @@ def main():
                     help="also run three plain 1 GiB device-to-device copies before the timed region, "
                          "so that a counter run has a kernel of known HBM traffic to scale by")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--two-calls", action="store_true",
+                    help="csa_decode_step then csa_append_kv instead of the one-call csa_decode_step_append")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
@@ -128,11 +130,16 @@ def main():
         done[0] += n_steps
         for s in range(first, first + n_steps):
             t = w.pre_appended + s
-            if s % period == 0:
-                ctx.decode_step(q_steps[t])
+            if args.two_calls:
+                if s % period == 0:
+                    ctx.decode_step(q_steps[t])
+                else:
+                    ctx.decode_step_reuse(q_steps[t])
+                ctx.append_kv(k_new[t], v_new[t])
+            elif s % period == 0:
+                ctx.decode_step_append(q_steps[t], k_new[t], v_new[t])
             else:
-                ctx.decode_step_reuse(q_steps[t])
-            ctx.append_kv(k_new[t], v_new[t])
+                ctx.decode_step_reuse_append(q_steps[t], k_new[t], v_new[t])
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -219,7 +226,8 @@ def main():
                    "head_dim": w.head_dim, "n_pre": w.n_pre, "subspaces": w.n_sub, "C": w.C, "L": w.L, "m": w.m,
                    "k": w.k, "pre_appended": w.pre_appended, "page_size": w.page_size,
                    "sparsity": round(1 - w.k / w.n_pre, 4), "mean_selected": sel_mean,
-                   "search_period": period},
+                   "search_period": period,
+                   "calls_per_step": "csa_decode_step + csa_append_kv" if args.two_calls else "csa_decode_step_append"},
         "tokens_per_s": round(B / (us_per_step * 1e-6), 1),
         "step_algorithmic_bytes": int(step_bytes),
         "step_hbm_gbps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),

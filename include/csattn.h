@@ -208,6 +208,18 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
 int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev,
                           const int32_t *sel_idx_dev, const int32_t *sel_count_dev, void *stream);
 
+/*
+ * A whole decode iteration in one call: the step on the current context - csa_decode_step
+ * (reuse = 0) or csa_decode_step_reuse (reuse != 0; sel_idx_dev / sel_count_dev are then inputs
+ * or both NULL) - followed by csa_append_kv(k_new_dev, v_new_dev), Sec. 3.3 (1)-(5).  Same
+ * results, same argument meaning and same errors as the two calls in that order; the append rides
+ * in the step's last launch, which saves one kernel launch per iteration.  CSA_ERR_CAPACITY (and
+ * nothing enqueued) when the context is full.
+ */
+int csa_decode_step_append(csa_ctx *ctx, const void *q_dev, const void *k_new_dev, const void *v_new_dev,
+                           float *out_dev, int32_t *sel_idx_dev, int32_t *sel_count_dev, int32_t reuse,
+                           void *stream);
+
 /* Streaming updates only: SYNCHRONISES `stream` and returns CSA_ERR_RANGE if a streamed key's
  * score did not fit the score grid since the tables were built (it was clamped), else CSA_OK. */
 int csa_streaming_status(csa_ctx *ctx, void *stream);

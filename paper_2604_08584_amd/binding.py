@@ -53,6 +53,7 @@ def lib() -> C.CDLL:
         "csa_append_kv": (C.c_int, [vp, vp, vp, vp]),
         "csa_decode_step": (C.c_int, [vp, vp, vp, vp, vp, vp]),
         "csa_decode_step_reuse": (C.c_int, [vp, vp, vp, vp, vp, vp]),
+        "csa_decode_step_append": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, i32, vp]),
         "csa_streaming_status": (C.c_int, [vp, vp]),
         "csa_context_len": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
         "csa_set_context_len": (C.c_int, [vp, i32]),
@@ -74,7 +75,7 @@ def lib() -> C.CDLL:
 EXPORTED = ("csa_create", "csa_destroy", "csa_workspace_bytes", "csa_bind", "csa_build_tables",
             "csa_cluster_workspace_bytes", "csa_cluster_queries",
             "csa_export_tables", "csa_import_tables", "csa_append_kv", "csa_decode_step",
-            "csa_decode_step_reuse", "csa_streaming_status",
+            "csa_decode_step_reuse", "csa_decode_step_append", "csa_streaming_status",
             "csa_context_len", "csa_set_context_len", "csa_score_frac_bits",
             "csa_last_probed_rows", "csa_profile_enable", "csa_profile_read", "csa_stage_name",
             "csa_strerror", "csa_last_hip_error")
@@ -180,6 +181,12 @@ def csa_decode_step_reuse(ctx, q, out, sel_idx=None, sel_count=None):
            "csa_decode_step_reuse")
 
 
+def csa_decode_step_append(ctx, q, k_new, v_new, out, sel_idx=None, sel_count=None, reuse=False):
+    _check(lib().csa_decode_step_append(ctx, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _ptr(sel_idx),
+                                        _ptr(sel_count), int(bool(reuse)), _stream()),
+           "csa_decode_step_append")
+
+
 def csa_streaming_status(ctx):
     _check(lib().csa_streaming_status(ctx, _stream()), "csa_streaming_status")
 
@@ -257,6 +264,16 @@ class Context:
 
     def append_kv(self, k_new, v_new):
         csa_append_kv(self.ctx, k_new, v_new)
+
+    def decode_step_append(self, q, k_new, v_new):
+        """decode_step followed by append_kv, in one call."""
+        csa_decode_step_append(self.ctx, q, k_new, v_new, self.out, self.sel, self.sel_count, False)
+        return self.out, self.sel, self.sel_count
+
+    def decode_step_reuse_append(self, q, k_new, v_new, sel=None, sel_count=None):
+        """decode_step_reuse followed by append_kv, in one call."""
+        csa_decode_step_append(self.ctx, q, k_new, v_new, self.out, sel, sel_count, True)
+        return self.out
 
     def probed_rows(self):
         rows = torch.empty(self.cfg["batch"], self.cfg["n_q_heads"],

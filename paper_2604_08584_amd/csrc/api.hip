@@ -461,6 +461,46 @@ int csa_export_tables(const csa_ctx *ctx, int32_t b, int32_t g, int32_t *idx_dev
     return check_launch(const_cast<csa_ctx *>(ctx));
 }
 
+namespace {
+
+// streaming update of the tables with the key just appended at position ctx->n (Sec. 3.3 (5))
+void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, hipStream_t st)
+{
+    const csa_config &c = ctx->cfg;
+    const Layout &l = ctx->lay;
+    prof.mark(9);
+    csa::launch_insert(k_new_dev, at<void>(ctx->tables, l.cent_t), at<void>(ctx->tables, l.ent),
+                       at<int32_t>(ctx->tables, l.part_off), at<int32_t>(ctx->tables, l.row_cnt),
+                       at<int32_t>(ctx->tables, l.row_min), at<int32_t>(ctx->scratch, l.queue_n),
+                       at<void>(ctx->scratch, l.queue), at<int32_t>(ctx->scratch, l.flags), c.batch,
+                       c.n_kv_heads, c.n_centroids, c.n_subspaces, c.list_len, l.Ls, ctx->Q, ctx->PO, ctx->F,
+                       qmax_for(c.n_probe * c.n_subspaces), ctx->n, st);
+    prof.end(9);
+}
+
+// the split merge that ends a step; with k_new/v_new also the append of row n (same launch) and,
+// with streaming updates, the try-insert
+void finish_step(csa_ctx *ctx, Prof &prof, const float *part, float *out_dev, int S, const void *k_new_dev,
+                 const void *v_new_dev, hipStream_t st)
+{
+    const csa_config &c = ctx->cfg;
+    const int BH = c.batch * c.n_q_heads;
+    if (!k_new_dev) {
+        csa::launch_attention_merge(part, out_dev, BH, S, st);
+        prof.end(6);
+        return;
+    }
+    const bool streaming = c.stream_window > 0;
+    csa::launch_attention_merge_append(part, out_dev, BH, S, ctx->k_cache, ctx->v_cache, ctx->block_table,
+                                       k_new_dev, v_new_dev, c.batch, c.n_kv_heads, ctx->n, c.max_ctx,
+                                       streaming ? at<int32_t>(ctx->scratch, ctx->lay.queue_n) : nullptr, st);
+    prof.end(6);
+    if (streaming) run_insert(ctx, prof, k_new_dev, st);
+    ctx->n += 1;
+}
+
+}  // namespace
+
 int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, void *stream)
 {
     if (!ctx || !k_new_dev || !v_new_dev) return CSA_ERR_ARG;
@@ -476,25 +516,19 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
                        c.n_kv_heads, ctx->n, c.max_ctx,
                        streaming ? at<int32_t>(ctx->scratch, l.queue_n) : nullptr, st);
     prof.end(7);
-    if (streaming) {
-        prof.mark(9);
-        csa::launch_insert(k_new_dev, at<void>(ctx->tables, l.cent_t), at<void>(ctx->tables, l.ent),
-                           at<int32_t>(ctx->tables, l.part_off), at<int32_t>(ctx->tables, l.row_cnt),
-                           at<int32_t>(ctx->tables, l.row_min), at<int32_t>(ctx->scratch, l.queue_n),
-                           at<void>(ctx->scratch, l.queue), at<int32_t>(ctx->scratch, l.flags), c.batch,
-                           c.n_kv_heads, c.n_centroids, c.n_subspaces, c.list_len, l.Ls, ctx->Q, ctx->PO, ctx->F,
-                           qmax_for(c.n_probe * c.n_subspaces), ctx->n, st);
-        prof.end(9);
-    }
+    if (streaming) run_insert(ctx, prof, k_new_dev, st);
     ctx->n += 1;
     return check_launch(ctx);
 }
 
-int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
-                    int32_t *sel_count_dev, void *stream)
+namespace {
+
+int search_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
+                int32_t *sel_count_dev, const void *k_new_dev, const void *v_new_dev, void *stream)
 {
     if (!ctx || !q_dev || !out_dev) return CSA_ERR_ARG;
     if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
+    if (k_new_dev && ctx->n >= ctx->cfg.max_ctx) return CSA_ERR_CAPACITY;
     const csa_config &c = ctx->cfg;
     const Layout &l = ctx->lay;
     hipStream_t st = (hipStream_t)stream;
@@ -547,19 +581,19 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
                                 c.max_ctx, S, ctx->P, fused ? cand_key : nullptr, seg_run, cand_cnt, thr,
                                 ctx->R, l.cand_keys, st);
     prof.end(5);
-    csa::launch_attention_merge(part, out_dev, BH, S, st);
-    prof.end(6);
+    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, st);
     ctx->last_sel = sel;
     ctx->last_sel_count = sel_count;
     return check_launch(ctx);
 }
 
-int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *sel_idx_dev,
-                          const int32_t *sel_count_dev, void *stream)
+int reuse_step(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *sel_idx_dev,
+               const int32_t *sel_count_dev, const void *k_new_dev, const void *v_new_dev, void *stream)
 {
     if (!ctx || !q_dev || !out_dev) return CSA_ERR_ARG;
     if ((sel_idx_dev == nullptr) != (sel_count_dev == nullptr)) return CSA_ERR_ARG;
     if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
+    if (k_new_dev && ctx->n >= ctx->cfg.max_ctx) return CSA_ERR_CAPACITY;
     const int32_t *sel = sel_idx_dev ? sel_idx_dev : ctx->last_sel;
     const int32_t *sel_count = sel_count_dev ? sel_count_dev : ctx->last_sel_count;
     if (!sel || !sel_count) return CSA_ERR_STATE;  // no searching step yet
@@ -581,9 +615,31 @@ int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev, const
                                 c.n_kv_heads, c.budget_k, ws, ctx->n, c.max_ctx, S, ctx->P, nullptr, nullptr,
                                 nullptr, nullptr, ctx->R, l.cand_keys, st);
     prof.end(5);
-    csa::launch_attention_merge(part, out_dev, BH, S, st);
-    prof.end(6);
+    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, st);
     return check_launch(ctx);
+}
+
+}  // namespace
+
+int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
+                    int32_t *sel_count_dev, void *stream)
+{
+    return search_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, stream);
+}
+
+int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *sel_idx_dev,
+                          const int32_t *sel_count_dev, void *stream)
+{
+    return reuse_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, stream);
+}
+
+int csa_decode_step_append(csa_ctx *ctx, const void *q_dev, const void *k_new_dev, const void *v_new_dev,
+                           float *out_dev, int32_t *sel_idx_dev, int32_t *sel_count_dev, int32_t reuse,
+                           void *stream)
+{
+    if (!k_new_dev || !v_new_dev) return CSA_ERR_ARG;
+    return reuse ? reuse_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev, v_new_dev, stream)
+                 : search_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev, v_new_dev, stream);
 }
 
 int csa_streaming_status(csa_ctx *ctx, void *stream)

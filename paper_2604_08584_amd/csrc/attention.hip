@@ -249,11 +249,46 @@ void launch_range_offsets(const int32_t *sel, const int32_t *sel_count, void *se
 // more on this multi-die part than one small launch).
 // out[head][e] = sum_s o_s[e] 2^(m_s - M) / sum_s l_s 2^(m_s - M); no attended key -> 0.
 // grid B*Hq, block 128.
+// APPEND: B*Hkv further workgroups write row n of K and V (Sec. 3.3 (5)) - the append that follows
+// a step, folded into this launch (the attention kernel, which has finished, never read row n).
+struct AppendArgs {
+    uint16_t *kc, *vc;
+    const int32_t *block_table;
+    const uint16_t *kn, *vn;
+    int n, Hkv, max_ctx;
+    int32_t *zero_me;
+};
+
+template <bool PAGED>
+__device__ __forceinline__ void append_row(const AppendArgs &a, int bg, int t)
+{
+    // row n of (sequence, KV head) bg: 16 lanes copy K, 16 lanes V, 16 bytes each
+    const int b = bg / a.Hkv, g = bg % a.Hkv;
+    if (a.zero_me && bg == 0 && t == 0) *a.zero_me = 0;
+    int64_t row;
+    if (PAGED) {
+        const int page = a.block_table[(size_t)b * (a.max_ctx >> 4) + (a.n >> 4)];
+        row = ((int64_t)page * a.Hkv + g) * 16 + (a.n & 15);
+    } else {
+        row = (int64_t)bg * a.max_ctx + a.n;
+    }
+    const int c = t & 15;
+    const uint16_t *src = (t < 16 ? a.kn : a.vn) + (size_t)bg * kHeadDim + c * 8;
+    uint16_t *dst = (t < 16 ? a.kc : a.vc) + row * kHeadDim + c * 8;
+    *(uint4 *)dst = *(const uint4 *)src;
+}
+
+template <int APPEND>  // 0: merge only, 1: + append (contiguous cache), 2: + append (paged cache)
 __global__ __launch_bounds__(kHeadDim) void k_attention_merge(const float *__restrict__ part,
-                                                              float *__restrict__ out, int S)
+                                                              float *__restrict__ out, int S,
+                                                              int n_heads, AppendArgs ap)
 {
     __shared__ float s_f[kHeadDim];  // per-split scale (S <= 128 per pass)
     __shared__ float s_red[2];
+    if (APPEND && (int)blockIdx.x >= n_heads) {  // (uniform over the workgroup)
+        if (threadIdx.x < 32) append_row<APPEND == 2>(ap, (int)blockIdx.x - n_heads, (int)threadIdx.x);
+        return;
+    }
     const float *ph = part + (size_t)blockIdx.x * S * (kHeadDim + 2);
     float acc = 0.0f, l = 0.0f, M = -INFINITY;
     for (int s0 = 0; s0 < S; s0 += kHeadDim) {
@@ -322,7 +357,19 @@ bool attention_can_emit(int R) { return R == 32 * kAttNT; }
 
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st)
 {
-    k_attention_merge<<<n_heads, kHeadDim, 0, st>>>(part, out, S);
+    k_attention_merge<0><<<n_heads, kHeadDim, 0, st>>>(part, out, S, n_heads, AppendArgs{});
+}
+
+void launch_attention_merge_append(const float *part, float *out, int n_heads, int S, void *kc, void *vc,
+                                   const int32_t *block_table, const void *kn, const void *vn, int B,
+                                   int Hkv, int n, int max_ctx, int32_t *zero_me, hipStream_t st)
+{
+    const AppendArgs ap{(uint16_t *)kc, (uint16_t *)vc, block_table, (const uint16_t *)kn,
+                        (const uint16_t *)vn, n, Hkv, max_ctx, zero_me};
+    if (block_table)
+        k_attention_merge<2><<<n_heads + B * Hkv, kHeadDim, 0, st>>>(part, out, S, n_heads, ap);
+    else
+        k_attention_merge<1><<<n_heads + B * Hkv, kHeadDim, 0, st>>>(part, out, S, n_heads, ap);
 }
 
 // K/V append: row n of every (sequence, KV head).  grid B*Hkv, block 32 (16 lanes K, 16 lanes V).
@@ -334,19 +381,8 @@ __global__ void k_append(uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
                          const uint16_t *__restrict__ vn, int n, int Hkv, int max_ctx,
                          int32_t *__restrict__ zero_me)
 {
-    const int bg = blockIdx.x, b = bg / Hkv, g = bg % Hkv;
-    if (zero_me && bg == 0 && threadIdx.x == 0) *zero_me = 0;
-    int64_t row;
-    if (PAGED) {
-        const int page = block_table[(size_t)b * (max_ctx >> 4) + (n >> 4)];
-        row = ((int64_t)page * Hkv + g) * 16 + (n & 15);
-    } else {
-        row = (int64_t)bg * max_ctx + n;
-    }
-    const int c = threadIdx.x & 15;
-    const uint16_t *src = (threadIdx.x < 16 ? kn : vn) + (size_t)bg * kHeadDim + c * 8;
-    uint16_t *dst = (threadIdx.x < 16 ? kc : vc) + row * kHeadDim + c * 8;
-    *(uint4 *)dst = *(const uint4 *)src;
+    append_row<PAGED>(AppendArgs{kc, vc, block_table, kn, vn, n, Hkv, max_ctx, zero_me}, (int)blockIdx.x,
+                      (int)threadIdx.x);
 }
 
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,

@@ -73,6 +73,10 @@ bool attention_can_emit(int R);
 void launch_range_offsets(const int32_t *sel, const int32_t *sel_count, void *seg_par, int n_heads, int k,
                           int R, int P, hipStream_t st);
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st);
+// the merge, and in the same launch the append of row n (arguments as launch_append)
+void launch_attention_merge_append(const float *part, float *out, int n_heads, int S, void *kc, void *vc,
+                                   const int32_t *block_table, const void *kn, const void *vn, int B,
+                                   int Hkv, int n, int max_ctx, int32_t *zero_me, hipStream_t st);
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
                    int B, int Hkv, int n, int max_ctx, int32_t *zero_me, hipStream_t st);
 

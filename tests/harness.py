@@ -107,16 +107,22 @@ class Case:
         for _ in range(count):
             kn, vn = self.inp["k_new"][self.t], self.inp["v_new"][self.t]
             self.ctx.append_kv(kn, vn)
-            pos = w.n_pre + self.t
-            kb = oracle.bf16_bits(kn)
-            self.K_host[:, :, pos] = kb
-            self.V_host[:, :, pos] = oracle.bf16_bits(vn)
-            if self.stream_window:
-                for (b, g) in (groups if groups is not None else
-                               [(b, g) for b in range(w.batch) for g in range(w.n_kv_heads)]):
-                    idx, score = self.oracle_rows(b, g)
-                    oracle.try_insert(idx, score, self.cent_host[b, g], np.ascontiguousarray(kb[b, g]), pos, self.F)
-            self.t += 1
+            self._mirror_append(groups)
+
+    def _mirror_append(self, groups=None):
+        """The host side of one append: K/V rows, and the oracle's try-insert with streaming updates."""
+        w = self.w
+        kn, vn = self.inp["k_new"][self.t], self.inp["v_new"][self.t]
+        pos = w.n_pre + self.t
+        kb = oracle.bf16_bits(kn)
+        self.K_host[:, :, pos] = kb
+        self.V_host[:, :, pos] = oracle.bf16_bits(vn)
+        if self.stream_window:
+            for (b, g) in (groups if groups is not None else
+                           [(b, g) for b in range(w.batch) for g in range(w.n_kv_heads)]):
+                idx, score = self.oracle_rows(b, g)
+                oracle.try_insert(idx, score, self.cent_host[b, g], np.ascontiguousarray(kb[b, g]), pos, self.F)
+        self.t += 1
 
     def check_tables(self, b, g):
         """The GPU's tables (exported now) against the oracle's (built, and kept up to date, by it)."""
@@ -132,6 +138,14 @@ class Case:
     def decode(self, step):
         q = self.inp["q_steps"][step]
         out, sel, cnt = self.ctx.decode_step(q)
+        rows = self.ctx.probed_rows()
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), sel.cpu().numpy(), cnt.cpu().numpy(), rows.cpu().numpy()
+
+    def decode_append(self, step):
+        """The fused call: decode step `step`, then the append of the next K/V row (one call)."""
+        q = self.inp["q_steps"][step]
+        out, sel, cnt = self.ctx.decode_step_append(q, self.inp["k_new"][self.t], self.inp["v_new"][self.t])
         rows = self.ctx.probed_rows()
         torch.cuda.synchronize()
         return out.cpu().numpy(), sel.cpu().numpy(), cnt.cpu().numpy(), rows.cpu().numpy()
@@ -166,13 +180,19 @@ class Case:
             sel[b, h, :o_cnt[t]] = np.asarray(o_sel[t])[:o_cnt[t]]
         return sel, cnt
 
-    def check_step(self, step, heads=None):
-        """Decode on both sides, compare; returns the max-abs output error."""
+    def check_step(self, step, heads=None, fused_append=False, groups=None):
+        """Decode on both sides, compare; returns the max-abs output error.  fused_append: the GPU
+        side uses the one-call form that also appends the next K/V row (the oracle decodes on the
+        context before that append, then the host mirrors it)."""
         w = self.w
         if heads is None:
             heads = [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
-        out, sel, cnt, rows = self.decode(step)
         o_rows, o_sel, o_cnt, o_out = self.oracle_decode(step, heads)
+        if fused_append:
+            out, sel, cnt, rows = self.decode_append(step)
+            self._mirror_append(groups)
+        else:
+            out, sel, cnt, rows = self.decode(step)
         worst = 0.0
         for t, (b, h) in enumerate(heads):
             tag = f"{w.name} step {step} head ({b},{h})"

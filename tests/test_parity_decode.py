@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import oracle
 from paper_2604_08584_amd import binding
 from paper_2604_08584_amd.workload import CONFIGS
 
@@ -267,6 +268,52 @@ def test_streaming_updates_try_insert_and_recent_window(S, L, part, paged):
     with pytest.raises(binding.CsaError) as e:
         binding.csa_set_context_len(case.ctx.ctx, w.n_pre)
     assert e.value.status == binding.CSA_ERR_STATE
+
+
+@pytest.mark.parametrize("paged,stream_window", [(False, 0), (True, 0), (False, 6), (True, 6)])
+def test_one_call_iteration_equals_step_then_append(paged, stream_window):
+    """csa_decode_step_append = csa_decode_step (or the reuse step) followed by csa_append_kv: every
+    step's outputs match the oracle on the context before the append, the appended rows are attended
+    by the following steps, the tables follow the appends when streaming updates are on, a reuse
+    step can be the fused one too, and a full context is refused with nothing changed."""
+    w = small("onecall", batch=2, n_q_heads=4, n_kv_heads=2, n_pre=2504, C=32, L=150, m=4, k=200, steps=8,
+              page_size=16 if paged else 0)
+    assert w.max_ctx == w.n_pre + 8
+    case = Case(w, seed=50, F=12, partition_keys=1024, stream_window=stream_window)
+    case.build_on_gpu()
+    for step in range(5):
+        case.check_step(step, fused_append=True)
+    assert binding.csa_context_len(case.ctx.ctx) == (w.n_pre, w.n_pre + 5)
+    if stream_window:
+        for b in range(2):
+            for g in range(2):
+                case.check_tables(b, g)
+        binding.csa_streaming_status(case.ctx.ctx)
+    # a reuse step in the one-call form: the oracle's index set of a searching step on this context
+    case.check_step(5)
+    sel, cnt = case.oracle_index_set(5)
+    q = case.inp["q_steps"][6]
+    out = case.ctx.decode_step_reuse_append(q, case.inp["k_new"][case.t], case.inp["v_new"][case.t],
+                                            torch.from_numpy(sel).cuda(), torch.from_numpy(cnt).cuda())
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    qh, n = oracle.bf16_bits(q), w.n_pre + case.t
+    for b in range(2):
+        for h in range(4):
+            want = oracle.attend_selected(np.ascontiguousarray(qh[b, h]), case.K_host[b, h // 2], case.V_host[b, h // 2],
+                                          sel[b, h][:cnt[b, h]], case.window_start(), n)
+            assert np.abs(out[b, h] - want).max() <= 2e-2
+    case._mirror_append()
+    case.check_step(6, fused_append=True)               # attends the rows appended by the one-call steps
+    case.check_step(7, fused_append=True)
+    assert binding.csa_context_len(case.ctx.ctx)[1] == w.max_ctx
+    before = case.ctx.out.clone()
+    with pytest.raises(binding.CsaError) as e:          # full: refused before anything is enqueued
+        case.ctx.decode_step_append(case.inp["q_steps"][7], case.inp["k_new"][7], case.inp["v_new"][7])
+    assert e.value.status == binding.CSA_ERR_CAPACITY
+    torch.cuda.synchronize()
+    assert torch.equal(before, case.ctx.out) and binding.csa_context_len(case.ctx.ctx)[1] == w.max_ctx
+    case.check_step(7)                                   # the plain step still works on the full context
 
 
 def test_streaming_updates_report_scores_that_leave_the_grid():
