@@ -362,10 +362,12 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     __syncthreads();
     // slot of an entry = (its block within the range) * kUnit + (low index bits) - off0
     const int off0 = (p * R) & (kUnit - 1);  // non-zero only for ranges smaller than a block
+    constexpr int kChunk = kWave * 4;  // entries of one round of 16-byte loads
     for (int r0 = wave; r0 < m; r0 += kAccRows * NW) {
         int lo[kAccRows], hi[kAccRows], b1[kAccRows], b2[kAccRows], b3[kAccRows];
+        int n_wide[kAccRows], n_tail[kAccRows];
         const uint32_t *rp[kAccRows];
-        int longest = 0;
+        int rounds = 0;
 #pragma unroll
         for (int j = 0; j < kAccRows; ++j) {
             const int r = r0 + j * NW;
@@ -378,34 +380,49 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
             b3[j] = NSUB > 2 ? __builtin_amdgcn_readfirstlane(s_b[rr * NB + 3]) : 0x7FFFFFFF;
             rp[j] = ent + ((size_t)bg * C + __builtin_amdgcn_readfirstlane(s_row[rr])) * Ls;
             lo[j] = min(lo[j], hi[j]);
-            longest = max(longest, hi[j] - (lo[j] & ~3));
+            // the slice from its 16-byte boundary: rounds of 16 bytes per lane, and - when what is
+            // left after them fits one entry per lane - one such round instead of a mostly idle wide
+            // one (a slice of a 1/P share of a row is typically a little over one wide round)
+            const int n = hi[j] - (lo[j] & ~3);
+            const int left = n % kChunk;
+            n_wide[j] = n / kChunk + (left > kWave ? 1 : 0);
+            n_tail[j] = left > kWave ? 0 : left;
+            rounds = max(rounds, n_wide[j]);
         }
-        for (int it = 0; it * (kWave * 8) < longest; ++it) {
-            uint4 va[kAccRows], vb[kAccRows];
+        auto add = [&](uint32_t e, int pos, int j) {
+            if ((uint32_t)(pos - lo[j]) < (uint32_t)(hi[j] - lo[j])) {
+                int slot = (int)(e & (uint32_t)(kUnit - 1)) - off0;
+                if (NSUB > 1) slot += (pos >= b1[j]) ? kUnit : 0;
+                if (NSUB > 2) slot += ((pos >= b2[j]) ? kUnit : 0) + ((pos >= b3[j]) ? kUnit : 0);
+                const int32_t val = entry_q(e) * (1 << kCntBits) + 1;
+                if ((unsigned)slot < (unsigned)R) atomicAdd(&s_acc[slot], val);
+            }
+        };
+        uint32_t vt[kAccRows];  // the one-per-lane leftovers: requested first, used last
+#pragma unroll
+        for (int j = 0; j < kAccRows; ++j)
+            vt[j] = lane < n_tail[j] ? rp[j][(lo[j] & ~3) + n_wide[j] * kChunk + lane] : 0u;
+        for (int it = 0; it < rounds; ++it) {
+            uint4 va[kAccRows];
 #pragma unroll
             for (int j = 0; j < kAccRows; ++j) {
-                const int x = (lo[j] & ~3) + it * (kWave * 8) + lane * 8;
-                va[j] = x < hi[j] ? *(const uint4 *)(rp[j] + x) : make_uint4(0, 0, 0, 0);
-                vb[j] = x + 4 < hi[j] ? *(const uint4 *)(rp[j] + x + 4) : make_uint4(0, 0, 0, 0);
+                const int x = (lo[j] & ~3) + it * kChunk + lane * 4;
+                va[j] = it < n_wide[j] && x < hi[j] ? *(const uint4 *)(rp[j] + x) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int j = 0; j < kAccRows; ++j) {
-                const int x = (lo[j] & ~3) + it * (kWave * 8) + lane * 8;
-                const uint32_t ev[8] = {va[j].x, va[j].y, va[j].z, va[j].w, vb[j].x, vb[j].y, vb[j].z, vb[j].w};
-                const uint32_t len = (uint32_t)(hi[j] - lo[j]);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int pos = x + e;
-                    if ((uint32_t)(pos - lo[j]) < len) {
-                        int slot = (int)(ev[e] & (uint32_t)(kUnit - 1)) - off0;
-                        if (NSUB > 1) slot += (pos >= b1[j]) ? kUnit : 0;
-                        if (NSUB > 2) slot += ((pos >= b2[j]) ? kUnit : 0) + ((pos >= b3[j]) ? kUnit : 0);
-                        const int32_t val = entry_q(ev[e]) * (1 << kCntBits) + 1;
-                        if ((unsigned)slot < (unsigned)R) atomicAdd(&s_acc[slot], val);
-                    }
+                const int x = (lo[j] & ~3) + it * kChunk + lane * 4;
+                if (it < n_wide[j]) {  // (scalar)
+                    add(va[j].x, x, j);
+                    add(va[j].y, x + 1, j);
+                    add(va[j].z, x + 2, j);
+                    add(va[j].w, x + 3, j);
                 }
             }
         }
+#pragma unroll
+        for (int j = 0; j < kAccRows; ++j)
+            if (lane < n_tail[j]) add(vt[j], (lo[j] & ~3) + n_wide[j] * kChunk + lane, j);
     }
     __syncthreads();
     // thread t owns the slot groups 4*(u*NT + t) .. +3, u < 4 (128-bit LDS reads)
