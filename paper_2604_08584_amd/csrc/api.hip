@@ -47,7 +47,7 @@ struct csa_ctx {
     bool bound = false, have_tables = false;
     int n_pre = 0, n = 0, F = -1, R = 0, P = 0;
     int Q = 0, nsub = 0, PO = 0;  // block size min(R, kUnit), blocks per range, offsets per row
-    uint32_t key_lo = 0;  // coarse histogram: 512 bins of 2^key_sh keys starting at key_lo
+    uint32_t key_lo = 0;  // coarse score bins of the candidates: 512 bins of 2^key_sh keys starting at key_lo
     int key_sh = 0;
     int hip_err = 0;
     // profiling
@@ -567,8 +567,8 @@ int search_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_id
     prof.end(3);
     // the second half of the Top-K runs in the prologue of the attention workgroups when a key
     // range has one bitmap word per attention thread and the launch is small (it then saves a
-    // launch, 4 us of 76 at batch 1); with thousands of workgroups the prologue's latency delays
-    // every workgroup's K/V stream and a kernel of its own measured 9 us of 420 faster
+    // launch, 4 us of 66 at batch 1); with thousands of workgroups the prologue's latency delays
+    // every workgroup's K/V stream and a kernel of its own measured 7 us of 390 faster
     const bool fused = c.budget_k > 0 && csa::attention_can_emit(ctx->R) && (int64_t)BH * S <= 2048;
     if (!fused) {
         csa::launch_emit(cand_key, seg_run, cand_cnt, thr, seg_par, sel, BH, c.budget_k, ctx->R, ctx->P,

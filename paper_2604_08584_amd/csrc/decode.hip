@@ -140,7 +140,7 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
 // ranks < m are written in rank order.  If there are too many candidates (many equal values) a
 // radix threshold search with an ordered tie pick does the job instead.  With C <= 256 every
 // thread holds one value and simply counts the values that beat it.
-// Also clears the head's coarse score histogram and looks up, for every key range p, the
+// Also looks up, for every key range p, the
 // nsub + 1 offsets that cut the slice of each probed row into its blocks, so that the
 // accumulation kernel starts with one coalesced read.
 // grid B*Hq*S, block 256.
@@ -320,11 +320,11 @@ void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off
 // q*64 + 1: exact integer sums, order-free, and "seen" == accumulator != 0 (U of Sec. 3.3 (3):
 // a key absent from every probed row is not a candidate even if all sums are negative).
 // A wave owns whole rows (row constants are scalar) and keeps the slices of four rows in
-// flight, 32 bytes (8 packed entries) per lane.  The kernel is bound by instruction issue, so the
-// per-entry and per-slot paths are kept minimal.  What leaves the workgroup is the range's
-// presence bitmap (one bit per key index) and the keys sum + 2^24 of the present indices in
-// ascending index order - the index of a candidate is implied by its rank in the bitmap - plus
-// the head's coarse histogram of those keys.
+// flight, 16 bytes (4 packed entries) per lane and round.  The kernel is bound by instruction
+// issue and the LDS atomic rate, so the per-entry and per-slot paths are kept minimal.  What
+// leaves the workgroup are the range's candidates as 32-bit words grouped by coarse bin of
+// their sum, best bin first (a counting sort through LDS), and the start offset of every bin:
+// the selection kernels then read offsets and one bin instead of every candidate.
 // grid (P, B*Hq), block NT = R/16, dynamic LDS R*4 bytes.
 // ---------------------------------------------------------------------------------------------
 constexpr int kAccRows = 4;  // rows in flight per wave
