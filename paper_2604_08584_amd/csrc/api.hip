@@ -107,8 +107,9 @@ Layout make_layout(const csa_config &c)
     put(l.flags, 256);
     put(l.qs, (size_t)(c.n_centroids < kBuildChunk ? c.n_centroids : kBuildChunk) * c.max_ctx * 4);
     if (c.stream_window > 0) {
-        put(l.queue_n, 256);
-        put(l.queue, BG * Ct * 16);
+        const size_t n_seg = (size_t)c.n_subspaces * ((c.n_centroids + 1023) / 1024);  // queue segments per KV head
+        put(l.queue_n, BG * n_seg * 4);
+        put(l.queue, BG * n_seg * 1024 * 16);
     }
     put(l.bin_off, BH * (size_t)l.P_max * 512 * 2);  // start of every coarse score bin per (head, key range)
     l.scratch_bytes = off;
@@ -140,6 +141,8 @@ int validate(const csa_config &c)
     if ((int64_t)c.batch * c.n_q_heads > 65535) return CSA_ERR_ARG;  // grid.y
     if ((int64_t)c.batch * c.n_kv_heads > 65535) return CSA_ERR_ARG;  // grid.z
     if (c.stream_window < 0) return CSA_ERR_ARG;
+    // the streaming update queues rows in segments of 1024 centroids, at most 64 per KV head
+    if (c.stream_window > 0 && (int64_t)c.n_subspaces * ((c.n_centroids + 1023) / 1024) > 64) return CSA_ERR_ARG;
     return CSA_OK;
 }
 
@@ -492,8 +495,7 @@ void finish_step(csa_ctx *ctx, Prof &prof, const float *part, float *out_dev, in
     }
     const bool streaming = c.stream_window > 0;
     csa::launch_attention_merge_append(part, out_dev, BH, S, ctx->k_cache, ctx->v_cache, ctx->block_table,
-                                       k_new_dev, v_new_dev, c.batch, c.n_kv_heads, ctx->n, c.max_ctx,
-                                       streaming ? at<int32_t>(ctx->scratch, ctx->lay.queue_n) : nullptr, st);
+                                       k_new_dev, v_new_dev, c.batch, c.n_kv_heads, ctx->n, c.max_ctx, st);
     prof.end(6);
     if (streaming) run_insert(ctx, prof, k_new_dev, st);
     ctx->n += 1;
@@ -509,12 +511,10 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
     hipStream_t st = (hipStream_t)stream;
     Prof prof(ctx, st);
     const csa_config &c = ctx->cfg;
-    const Layout &l = ctx->lay;
     const bool streaming = c.stream_window > 0;
     prof.mark(7);
     csa::launch_append(ctx->k_cache, ctx->v_cache, ctx->block_table, k_new_dev, v_new_dev, c.batch,
-                       c.n_kv_heads, ctx->n, c.max_ctx,
-                       streaming ? at<int32_t>(ctx->scratch, l.queue_n) : nullptr, st);
+                       c.n_kv_heads, ctx->n, c.max_ctx, st);
     prof.end(7);
     if (streaming) run_insert(ctx, prof, k_new_dev, st);
     ctx->n += 1;

@@ -256,7 +256,6 @@ struct AppendArgs {
     const int32_t *block_table;
     const uint16_t *kn, *vn;
     int n, Hkv, max_ctx;
-    int32_t *zero_me;
 };
 
 template <bool PAGED>
@@ -264,7 +263,6 @@ __device__ __forceinline__ void append_row(const AppendArgs &a, int bg, int t)
 {
     // row n of (sequence, KV head) bg: 16 lanes copy K, 16 lanes V, 16 bytes each
     const int b = bg / a.Hkv, g = bg % a.Hkv;
-    if (a.zero_me && bg == 0 && t == 0) *a.zero_me = 0;
     int64_t row;
     if (PAGED) {
         const int page = a.block_table[(size_t)b * (a.max_ctx >> 4) + (a.n >> 4)];
@@ -362,10 +360,10 @@ void launch_attention_merge(const float *part, float *out, int n_heads, int S, h
 
 void launch_attention_merge_append(const float *part, float *out, int n_heads, int S, void *kc, void *vc,
                                    const int32_t *block_table, const void *kn, const void *vn, int B,
-                                   int Hkv, int n, int max_ctx, int32_t *zero_me, hipStream_t st)
+                                   int Hkv, int n, int max_ctx, hipStream_t st)
 {
     const AppendArgs ap{(uint16_t *)kc, (uint16_t *)vc, block_table, (const uint16_t *)kn,
-                        (const uint16_t *)vn, n, Hkv, max_ctx, zero_me};
+                        (const uint16_t *)vn, n, Hkv, max_ctx};
     if (block_table)
         k_attention_merge<2><<<n_heads + B * Hkv, kHeadDim, 0, st>>>(part, out, S, n_heads, ap);
     else
@@ -373,29 +371,24 @@ void launch_attention_merge_append(const float *part, float *out, int n_heads, i
 }
 
 // K/V append: row n of every (sequence, KV head).  grid B*Hkv, block 32 (16 lanes K, 16 lanes V).
-// zero_me (optional): a counter the following kernels start from zero (the insertion queue of the
-// streaming update), cleared here instead of with a memset node.
 template <bool PAGED>
 __global__ void k_append(uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
                          const int32_t *__restrict__ block_table, const uint16_t *__restrict__ kn,
-                         const uint16_t *__restrict__ vn, int n, int Hkv, int max_ctx,
-                         int32_t *__restrict__ zero_me)
+                         const uint16_t *__restrict__ vn, int n, int Hkv, int max_ctx)
 {
-    append_row<PAGED>(AppendArgs{kc, vc, block_table, kn, vn, n, Hkv, max_ctx, zero_me}, (int)blockIdx.x,
+    append_row<PAGED>(AppendArgs{kc, vc, block_table, kn, vn, n, Hkv, max_ctx}, (int)blockIdx.x,
                       (int)threadIdx.x);
 }
 
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
-                   int B, int Hkv, int n, int max_ctx, int32_t *zero_me, hipStream_t st)
+                   int B, int Hkv, int n, int max_ctx, hipStream_t st)
 {
     if (block_table)
         k_append<true><<<B * Hkv, 32, 0, st>>>((uint16_t *)kc, (uint16_t *)vc, block_table,
-                                               (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx,
-                                               zero_me);
+                                               (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx);
     else
         k_append<false><<<B * Hkv, 32, 0, st>>>((uint16_t *)kc, (uint16_t *)vc, nullptr,
-                                                (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx,
-                                                zero_me);
+                                                (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx);
 }
 
 }  // namespace csa

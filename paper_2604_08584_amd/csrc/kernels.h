@@ -76,8 +76,8 @@ void launch_attention_merge(const float *part, float *out, int n_heads, int S, h
 // the merge, and in the same launch the append of row n (arguments as launch_append)
 void launch_attention_merge_append(const float *part, float *out, int n_heads, int S, void *kc, void *vc,
                                    const int32_t *block_table, const void *kn, const void *vn, int B,
-                                   int Hkv, int n, int max_ctx, int32_t *zero_me, hipStream_t st);
+                                   int Hkv, int n, int max_ctx, hipStream_t st);
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
-                   int B, int Hkv, int n, int max_ctx, int32_t *zero_me, hipStream_t st);
+                   int B, int Hkv, int n, int max_ctx, hipStream_t st);
 
 }  // namespace csa

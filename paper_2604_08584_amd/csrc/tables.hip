@@ -409,8 +409,13 @@ void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt
 // - the fma chain and grid of the table build - and, if the row has a free slot or the score beats
 // the row minimum, queues (row, q) for insertion.  A score outside the grid range is clamped and
 // reported in flags[2].  cent_t is [bg][S][db/8][C][8]; k_new is [bg][128] bf16.
-// grid (ceil(C/256), S, B*Hkv), block 256.
-__global__ __launch_bounds__(256) void k_insert_scan(const uint16_t *__restrict__ k_new,
+// Every workgroup owns a queue segment of kScanNT slots and its count (written, not added to): no
+// global atomics - on this multi-die part thousands of returning atomics on a few addresses cost
+// more than the scan itself - and nothing to clear between steps.
+// grid (ceil(C/1024), S, B*Hkv), block 1024; segment id = (bg*S + s) * gridDim.x + x.
+constexpr int kScanNT = 1024;
+
+__global__ __launch_bounds__(kScanNT) void k_insert_scan(const uint16_t *__restrict__ k_new,
                                                      const uint4 *__restrict__ cent_t,
                                                      const int32_t *__restrict__ row_cnt,
                                                      const int32_t *__restrict__ row_min,
@@ -420,9 +425,11 @@ __global__ __launch_bounds__(256) void k_insert_scan(const uint16_t *__restrict_
                                                      float up, int qmax)
 {
     __shared__ float s_k[kHeadDim];
+    __shared__ int s_n;
     const int sub = blockIdx.y, bg = blockIdx.z;
     const int db = kHeadDim / S, nch = db / 8;
-    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int j = blockIdx.x * kScanNT + threadIdx.x;
+    if (threadIdx.x == 0) s_n = 0;
     if (threadIdx.x < db)
         s_k[threadIdx.x] = __uint_as_float((uint32_t)k_new[(size_t)bg * kHeadDim + sub * db + threadIdx.x] << 16);
     __syncthreads();
@@ -451,103 +458,150 @@ __global__ __launch_bounds__(256) void k_insert_scan(const uint16_t *__restrict_
         qf = qf > 0.0f ? (float)qmax : -(float)qmax;  // (a NaN cannot occur: inputs are finite)
     }
     const int q = (int)qf;
-    // one counter update per wave
+    // one LDS counter update per wave
+    const size_t seg = ((size_t)bg * S + sub) * gridDim.x + blockIdx.x;
     const bool take = live && (cnt < L || q > mn);
     const uint64_t mask = __ballot(take);
     if (mask) {
         int base = 0;
-        if (lane_id() == __ffsll((unsigned long long)mask) - 1) base = atomicAdd(queue_n, __popcll(mask));
+        if (lane_id() == __ffsll((unsigned long long)mask) - 1) base = atomicAdd(&s_n, __popcll(mask));
         base = __builtin_amdgcn_readlane(base, __ffsll((unsigned long long)mask) - 1);
-        if (take) queue[base + mbcnt(mask)] = make_int4((int)row, q, cnt, mn);  // (the row's state travels along)
+        if (take)  // (the row's state travels along)
+            queue[seg * kScanNT + base + mbcnt(mask)] = make_int4((int)row, q, cnt, mn);
     }
+    __syncthreads();
+    if (threadIdx.x == 0) queue_n[seg] = s_n;
 }
 
-// Insertion: one workgroup per queued row.  The new key has the largest index so far, so in the
-// device layout (ascending key index) it goes to the end of the row; a full row first loses its
-// minimum - the entry with the smallest q, among equals the one with the largest index, i.e. the
-// last of them - and the entries behind it move up one slot.  The row's block offsets, count and
-// minimum are brought up to date.
-// grid: any (workgroups stride over the queue), block 256, dynamic LDS Ls * 4 bytes.
-__global__ __launch_bounds__(256) void k_insert_rows(uint32_t *__restrict__ ent,
+// Insertion: one wave per queued row.  Rows are grouped by blocks of Q key indices (the order
+// inside a block carries no meaning: the accumulation kernel scatters by index).  The new key has
+// the largest index so far, so it belongs to the last block.  A row with a free slot takes it at
+// its end.  A full row first loses its minimum - the entry with the smallest q, among equals the
+// one with the largest key index - and the hole travels to the last block one block at a time:
+// the last entry of a block moves into the hole, which leaves the hole in front of the next block;
+// the new entry fills it in front of the last block.  That is one entry move per block instead of
+// shifting the rest of the row.  The row is read once: the evicted entry, how often the minimum
+// occurs and the smallest larger value give the new minimum.  Block offsets, count and minimum
+// are brought up to date.  The work is a chain of memory latencies, so a row gets a wave, not a
+// workgroup: four times as many rows are in flight, and nothing waits at a barrier; a wave is tied
+// to a queue slot (segment s, slots w, w + W, ...), so the segment's count and the slot's content
+// are requested together.  One wave per workgroup: a wave without work (most segments hold fewer
+// rows than they have waves) gives its place up at once.
+// grid (W, n_seg, B*Hkv), block 64.
+constexpr int kInsPo = 512;    // block offsets of a row kept in LDS (per wave) when they fit
+constexpr int kInsLoads = 8;   // 16-byte loads per lane in flight
+
+__global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ ent,
                                                      int32_t *__restrict__ part_off,
                                                      int32_t *__restrict__ row_cnt,
                                                      int32_t *__restrict__ row_min,
                                                      const int32_t *__restrict__ queue_n,
-                                                     const int4 *__restrict__ queue, int L, int Ls,
-                                                     int Q, int PO, int idx_new)
+                                                     const int4 *__restrict__ queue, int n_seg, int L,
+                                                     int Ls, int Q, int PO, int idx_new)
 {
-    extern __shared__ uint32_t s_row[];
-    __shared__ int s_red[4];
-    const int n_items = *queue_n;
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-        const int4 it = queue[item];
+    __shared__ int32_t s_po[kInsPo];
+    const int lane = lane_id();
+    const size_t seg = (size_t)blockIdx.z * n_seg + blockIdx.y;
+    const int4 *qseg = queue + seg * kScanNT;
+    const int first = blockIdx.x;
+    const int4 it0 = qseg[first < kScanNT ? first : 0];  // (a stale slot when the segment holds fewer)
+    const int n_items = queue_n[seg];
+    const int u_new = idx_new / Q;  // the new key's block
+    const bool po_lds = PO <= kInsPo;
+    for (int item = first; item < n_items; item += gridDim.x) {
+        const int4 it = item == first ? it0 : qseg[item];
         const int64_t row = it.x;
-        const int q_new = it.y, cnt = it.z;
+        const int q_new = it.y, cnt = it.z, mn = it.w;
         uint32_t *re = ent + row * Ls;
         int32_t *po = part_off + row * PO;
         const uint32_t e_new = pack_entry(idx_new, q_new);
-        if (cnt < L) {
-            if (threadIdx.x == 0) {
+        if (cnt < L) {  // (uniform over the wave)
+            if (lane == 0) {
                 re[cnt] = e_new;
                 row_cnt[row] = cnt + 1;
-                row_min[row] = min(it.w, q_new);
+                row_min[row] = min(mn, q_new);
             }
-            for (int u = threadIdx.x; u < PO; u += 256)
+            for (int u = lane; u < PO; u += kWave)
                 if ((int64_t)u * Q > idx_new) po[u] += 1;
-            continue;  // (uniform over the workgroup)
+            continue;
         }
-        const int mn = it.w;
-        __syncthreads();  // the previous item's LDS reads are done
-        // the row, 16 bytes per lane and load (Ls is a multiple of 4; slots >= L hold zeros)
-        int pmin = -1;
-        for (int p4 = threadIdx.x; p4 * 4 < L; p4 += 256) {
-            const uint4 v = *(const uint4 *)(re + p4 * 4);
-            *(uint4 *)(s_row + p4 * 4) = v;
-            const uint32_t ev[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (p4 * 4 + i < L && entry_q(ev[i]) == mn) pmin = p4 * 4 + i;  // (ascending: the last match stays)
-        }
-        for (int o = 32; o > 0; o >>= 1) pmin = max(pmin, __shfl_xor(pmin, o, kWave));
-        if (lane_id() == 0) s_red[threadIdx.x / kWave] = pmin;
-        __syncthreads();
-        pmin = max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3]));
-        if (pmin < 0) continue;  // (cannot happen: row_min is the minimum of a full row)
-        // the evicted entry's block = the number of block boundaries u >= 1 at or before pmin
-        // (offsets are non-decreasing); counted in parallel: one round of loads, no dependent chain
-        int n_le = 0;
-        for (int u = 1 + threadIdx.x; u < PO; u += 256) n_le += po[u] <= pmin ? 1 : 0;
-        n_le = wave_sum(n_le);
-        __syncthreads();  // s_red was read by every thread
-        if (lane_id() == 0) s_red[threadIdx.x / kWave] = n_le;
-        __syncthreads();
-        const int ue = s_red[0] + s_red[1] + s_red[2] + s_red[3];
-        // entries behind the evicted one move up a slot, the new entry takes the last slot
-        int new_min = q_new;
-        for (int p4 = threadIdx.x; p4 * 4 < L; p4 += 256) {
-            uint32_t ov[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int p = p4 * 4 + i;
-                uint32_t e = 0u;
-                if (p < L) {
-                    e = p < pmin ? s_row[p] : (p + 1 < L ? s_row[p + 1] : e_new);
-                    new_min = min(new_min, entry_q(e));
-                }
-                ov[i] = e;
+        if (po_lds)
+            for (int u = lane; u < PO; u += kWave) s_po[u] = po[u];
+        const int32_t *pol = po_lds ? s_po : po;  // the offsets as they are before this insertion
+        // block of position p: the last u with pol[u] <= p (offsets are non-decreasing)
+        auto block_of = [&](int p) {
+            int lo = 0, hi = PO - 1;  // pol[lo] <= p < pol[hi]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (pol[mid] <= p) lo = mid; else hi = mid;
             }
-            if (p4 * 4 + 3 >= pmin) *(uint4 *)(re + p4 * 4) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
+            return lo;
+        };
+        // one pass over the row, 2048 entries (eight 16-byte loads per lane) at a time; slots >= L
+        // hold zeros (Ls is a multiple of 4)
+        unsigned long long best = 0ull;  // the entry to evict as (key index + 1, position): larger wins
+        int n_min = 0, min2 = 0x7FFFFFFF;  // occurrences of the minimum, smallest value above it
+        for (int base = 0; base < L; base += kWave * 4 * kInsLoads) {
+            uint4 v[kInsLoads];
+#pragma unroll
+            for (int u = 0; u < kInsLoads; ++u) {
+                const int p = base + (u * kWave + lane) * 4;
+                v[u] = p < L ? *(const uint4 *)(re + p) : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < kInsLoads; ++u) {
+                const uint32_t ev[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int p = base + (u * kWave + lane) * 4 + i;
+                    if (p < L) {
+                        const int q = entry_q(ev[i]);
+                        if (q == mn) {
+                            ++n_min;
+                            const uint32_t idx = (((uint32_t)block_of(p) * (uint32_t)Q) & ~(uint32_t)(kUnit - 1)) |
+                                                 (ev[i] & (uint32_t)(kUnit - 1));
+                            const unsigned long long cand = ((unsigned long long)(idx + 1u) << 32) | (uint32_t)p;
+                            best = cand > best ? cand : best;
+                        } else {
+                            min2 = min(min2, q);
+                        }
+                    }
+                }
+            }
         }
-        for (int o = 32; o > 0; o >>= 1) new_min = min(new_min, __shfl_xor(new_min, o, kWave));
-        __syncthreads();  // s_red was read by every thread
-        if (lane_id() == 0) s_red[threadIdx.x / kWave] = new_min;
-        __syncthreads();
-        if (threadIdx.x == 0) row_min[row] = min(min(s_red[0], s_red[1]), min(s_red[2], s_red[3]));
-        // offsets: one entry fewer before every block after the evicted one's, one more before
-        // every block that starts above the new index
-        for (int u = threadIdx.x; u < PO; u += 256) {
-            const int d = ((int64_t)u * Q > idx_new ? 1 : 0) - (u > ue ? 1 : 0);
-            if (d) po[u] += d;
+        for (int o = 32; o > 0; o >>= 1) {
+            const unsigned long long t = __shfl_xor(best, o, kWave);
+            best = t > best ? t : best;
+            min2 = min(min2, __shfl_xor(min2, o, kWave));
+        }
+        n_min = wave_sum(n_min);
+        if (best == 0ull) continue;  // (cannot happen: row_min is the minimum of a full row)
+        const int pe = (int)(uint32_t)best;
+        const int ue = block_of(pe);
+        // the hole's way: block w in [ue, u_new) gives its last entry (at pol[w+1] - 1) to the hole
+        // (at pe in block ue, else in front of block w at pol[w] - 1); all reads of a round of 64
+        // blocks first, then its writes - the source of one move is the target of the next
+        for (int w0 = ue; w0 < u_new; w0 += kWave) {  // (uniform bounds)
+            const int w = w0 + lane;
+            const bool on = w < u_new;
+            int src = 0, dst = 0;
+            uint32_t val = 0u;
+            if (on) {
+                src = pol[w + 1] - 1;
+                // (without the LDS copy, the first block of a later round already has its lowered offset)
+                dst = w == ue ? pe : (!po_lds && w == w0 ? pol[w] : pol[w] - 1);
+                val = re[src];
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the reads have returned
+            if (on && src != dst) re[dst] = val;
+            if (on) po[w + 1] = src;  // one entry fewer before block w + 1
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // (the next round reads what this one wrote)
+        }
+        if (lane == 0) {
+            // the new entry: in place of the evicted one if that sat in the last block, else in the
+            // hole now in front of the last block
+            re[ue == u_new ? pe : (po_lds ? s_po[u_new] - 1 : po[u_new])] = e_new;
+            row_min[row] = min(q_new, n_min >= 2 ? mn : min2);
         }
     }
 }
@@ -556,20 +610,16 @@ void launch_insert(const void *k_new, const void *cent_t, void *ent, int32_t *pa
                    int32_t *row_min, int32_t *queue_n, void *queue, int32_t *flags, int B, int Hkv, int C,
                    int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st)
 {
-    static bool attr = false;
-    if (!attr) {
-        (void)hipFuncSetAttribute((const void *)k_insert_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 4);
-        attr = true;
-    }
-    dim3 grid((C + 255) / 256, S, B * Hkv);
-    k_insert_scan<<<grid, 256, 0, st>>>((const uint16_t *)k_new, (const uint4 *)cent_t, row_cnt, row_min, queue_n,
-                                        (int4 *)queue, flags, C, S, L, ldexpf(1.0f, F), qmax);
-    // the queue length is only known on the device: enough workgroups for one row each in the
-    // usual case (a few percent of the rows take a new key), striding when there are more
-    const int64_t n_rows = (int64_t)B * Hkv * S * C;
-    const unsigned wgs = (unsigned)(n_rows < 16384 ? n_rows : 16384);
-    k_insert_rows<<<wgs, 256, (size_t)Ls * 4, st>>>((uint32_t *)ent, part_off, row_cnt, row_min, queue_n,
-                                                    (const int4 *)queue, L, Ls, Q, PO, idx_new);
+    const int nx = (C + kScanNT - 1) / kScanNT, n_seg = S * nx;  // (n_seg <= 64: checked at create)
+    dim3 grid(nx, S, B * Hkv);
+    k_insert_scan<<<grid, kScanNT, 0, st>>>((const uint16_t *)k_new, (const uint4 *)cent_t, row_cnt, row_min, queue_n,
+                                            (int4 *)queue, flags, C, S, L, ldexpf(1.0f, F), qmax);
+    // the queue lengths are only known on the device: enough waves for one row each in the usual
+    // case (a few percent of the rows take a new key), striding when there are more
+    const int per_seg = C < kScanNT ? C : kScanNT;  // rows behind a segment
+    const int waves = per_seg / 8 < 1 ? 1 : per_seg / 8;  // one wave per 8 rows (about 3 % take a key, unevenly)
+    k_insert_rows<<<dim3(waves, n_seg, B * Hkv), kWave, 0, st>>>((uint32_t *)ent, part_off, row_cnt, row_min, queue_n,
+                                                      (const int4 *)queue, n_seg, L, Ls, Q, PO, idx_new);
 }
 
 // max over prefill keys and subspaces of ||k^(s)||^2 (nch 16-byte chunks per subspace), as the bit
