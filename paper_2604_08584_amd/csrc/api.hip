@@ -21,7 +21,7 @@ struct Region {
 
 struct Layout {
     // tables buffer
-    Region cent_t, ent, part_off, row_cnt, row_min;  // (the last two: streaming updates only)
+    Region cent_t, ent, part_off, row_cnt, row_min, blk_min;  // (the last three: streaming updates only)
     size_t tables_bytes = 0;
     // scratch buffer
     Region z, rows, spans, cand, bin_off, cand_cnt, seg_par, seg_run, thr, sel, sel_count, part, flags, qs;
@@ -88,6 +88,7 @@ Layout make_layout(const csa_config &c)
     if (c.stream_window > 0) {
         put(l.row_cnt, BG * Ct * 4);
         put(l.row_min, BG * Ct * 4);
+        put(l.blk_min, BG * Ct * (size_t)l.PO_max * 4);  // per block of a row: its smallest score
     }
     l.tables_bytes = off;
     off = 0;
@@ -357,6 +358,7 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
     set_key_range(ctx, hflags[1]);
     if (c.stream_window > 0)
         csa::launch_row_stats(ent, part_off, at<int32_t>(ctx->tables, l.row_cnt), at<int32_t>(ctx->tables, l.row_min),
+                              at<int32_t>(ctx->tables, l.blk_min),
                               (int64_t)BG * S * c.n_centroids, l.Ls, ctx->PO, st);
     ctx->F = F;
     ctx->n_pre = ctx->n = n_pre;
@@ -440,8 +442,8 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
     set_key_range(ctx, hflags[1]);
     if (c.stream_window > 0)
         csa::launch_row_stats(at<void>(ctx->tables, l.ent), at<int32_t>(ctx->tables, l.part_off),
-                              at<int32_t>(ctx->tables, l.row_cnt), at<int32_t>(ctx->tables, l.row_min), n_rows, l.Ls,
-                              ctx->PO, st);
+                              at<int32_t>(ctx->tables, l.row_cnt), at<int32_t>(ctx->tables, l.row_min),
+                              at<int32_t>(ctx->tables, l.blk_min), n_rows, l.Ls, ctx->PO, st);
     ctx->F = c.score_frac_bits;
     ctx->n_pre = ctx->n = n_pre;
     ctx->have_tables = true;
@@ -474,7 +476,8 @@ void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, hipStream_t st)
     prof.mark(9);
     csa::launch_insert(k_new_dev, at<void>(ctx->tables, l.cent_t), at<void>(ctx->tables, l.ent),
                        at<int32_t>(ctx->tables, l.part_off), at<int32_t>(ctx->tables, l.row_cnt),
-                       at<int32_t>(ctx->tables, l.row_min), at<int32_t>(ctx->scratch, l.queue_n),
+                       at<int32_t>(ctx->tables, l.row_min), at<int32_t>(ctx->tables, l.blk_min),
+                       at<int32_t>(ctx->scratch, l.queue_n),
                        at<void>(ctx->scratch, l.queue), at<int32_t>(ctx->scratch, l.flags), c.batch,
                        c.n_kv_heads, c.n_centroids, c.n_subspaces, c.list_len, l.Ls, ctx->Q, ctx->PO, ctx->F,
                        qmax_for(c.n_probe * c.n_subspaces), ctx->n, st);

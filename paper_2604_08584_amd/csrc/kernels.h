@@ -26,10 +26,10 @@ void launch_build_scores(const void *kc, const int32_t *block_table, const void 
                          int jc, int F, int qmax, hipStream_t st);
 void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc, int n_pre, int L,
                          int Ls, int Q, int PO, hipStream_t st);
-void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt, int32_t *row_min,
+void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt, int32_t *row_min, int32_t *blk_min,
                       int64_t n_rows, int Ls, int PO, hipStream_t st);
 void launch_insert(const void *k_new, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
-                   int32_t *row_min, int32_t *queue_n, void *queue, int32_t *flags, int B, int Hkv, int C,
+                   int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *flags, int B, int Hkv, int C,
                    int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st);
 void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
                          int max_ctx, int n_pre, int S, hipStream_t st);

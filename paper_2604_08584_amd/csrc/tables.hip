@@ -378,31 +378,40 @@ void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc
 // Streaming updates (Sec. 3.3 (5)): per-row state, try test, insertion.
 // ---------------------------------------------------------------------------------------------
 
-// row_cnt[row] = valid entries of the row, row_min[row] = their smallest q (INT_MAX if none).
+// row_cnt[row] = valid entries of the row, row_min[row] = their smallest q (INT_MAX if none),
+// blk_min[row][u] = the smallest q within block u of the row (INT_MAX for an empty block): an
+// insertion then reads the one block that holds the minimum instead of the whole row.
 // One wave per row.  grid ceil(n_rows / 4), block 256.
 __global__ __launch_bounds__(256) void k_row_stats(const uint32_t *__restrict__ ent,
                                                    const int32_t *__restrict__ part_off,
                                                    int32_t *__restrict__ row_cnt,
-                                                   int32_t *__restrict__ row_min, int64_t n_rows,
+                                                   int32_t *__restrict__ row_min,
+                                                   int32_t *__restrict__ blk_min, int64_t n_rows,
                                                    int Ls, int PO)
 {
     const int64_t row = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave;
     if (row >= n_rows) return;
-    const int cnt = part_off[row * PO + PO - 1];
-    int mn = 0x7FFFFFFF;
-    for (int p = lane_id(); p < cnt; p += kWave) mn = min(mn, entry_q(ent[row * Ls + p]));
-    for (int o = 32; o > 0; o >>= 1) mn = min(mn, __shfl_xor(mn, o, kWave));
+    const int32_t *po = part_off + row * PO;
+    int all = 0x7FFFFFFF;
+    for (int u = 0; u + 1 < PO; ++u) {
+        const int b0 = po[u], b1 = po[u + 1];
+        int mn = 0x7FFFFFFF;
+        for (int p = b0 + lane_id(); p < b1; p += kWave) mn = min(mn, entry_q(ent[row * Ls + p]));
+        for (int o = 32; o > 0; o >>= 1) mn = min(mn, __shfl_xor(mn, o, kWave));
+        if (lane_id() == 0) blk_min[row * PO + u] = mn;
+        all = min(all, mn);
+    }
     if (lane_id() == 0) {
-        row_cnt[row] = cnt;
-        row_min[row] = mn;
+        row_cnt[row] = po[PO - 1];
+        row_min[row] = all;
     }
 }
 
 void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt, int32_t *row_min,
-                      int64_t n_rows, int Ls, int PO, hipStream_t st)
+                      int32_t *blk_min, int64_t n_rows, int Ls, int PO, hipStream_t st)
 {
     k_row_stats<<<(unsigned)((n_rows + 3) / 4), 256, 0, st>>>((const uint32_t *)ent, part_off, row_cnt, row_min,
-                                                              n_rows, Ls, PO);
+                                                              blk_min, n_rows, Ls, PO);
 }
 
 // Try test: lane j of block (x, s, bg) scores the new key of KV head bg against centroid (s, j)
@@ -477,27 +486,27 @@ __global__ __launch_bounds__(kScanNT) void k_insert_scan(const uint16_t *__restr
 // inside a block carries no meaning: the accumulation kernel scatters by index).  The new key has
 // the largest index so far, so it belongs to the last block.  A row with a free slot takes it at
 // its end.  A full row first loses its minimum - the entry with the smallest q, among equals the
-// one with the largest key index - and the hole travels to the last block one block at a time:
-// the last entry of a block moves into the hole, which leaves the hole in front of the next block;
-// the new entry fills it in front of the last block.  That is one entry move per block instead of
-// shifting the rest of the row.  The row is read once: the evicted entry, how often the minimum
-// occurs and the smallest larger value give the new minimum.  Block offsets, count and minimum
-// are brought up to date.  The work is a chain of memory latencies, so a row gets a wave, not a
-// workgroup: four times as many rows are in flight, and nothing waits at a barrier; a wave is tied
-// to a queue slot (segment s, slots w, w + W, ...), so the segment's count and the slot's content
-// are requested together.  One wave per workgroup: a wave without work (most segments hold fewer
-// rows than they have waves) gives its place up at once.
+// one with the largest key index, found by reading only the block whose recorded minimum it is -
+// and the hole travels to the last block one block at a time: the last entry of a block moves into
+// the hole, which leaves the hole in front of the next block; the new entry fills it in front of
+// the last block.  That is one entry move per block instead of shifting the rest of the row, and
+// about 1/P of the row read instead of all of it.  Block offsets, block minima, count and row
+// minimum are brought up to date.  The work is a chain of memory latencies, so a row gets a
+// wave, not a workgroup, nothing waits at a barrier, and a wave is tied to a queue slot (segment
+// s, slots w, w + W, ...), so the segment's count and the slot's content are requested together.
+// One wave per workgroup: a wave without work (most segments hold fewer rows than they have
+// waves) gives its place up at once.
 // grid (W, n_seg, B*Hkv), block 64.
-constexpr int kInsPo = 512;    // block offsets of a row kept in LDS (per wave) when they fit
-constexpr int kInsLoads = 8;   // 16-byte loads per lane in flight
+constexpr int kInsPo = 1024;  // block offsets and minima of a row kept in LDS when they fit
 
 __global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ ent,
-                                                     int32_t *__restrict__ part_off,
-                                                     int32_t *__restrict__ row_cnt,
-                                                     int32_t *__restrict__ row_min,
-                                                     const int32_t *__restrict__ queue_n,
-                                                     const int4 *__restrict__ queue, int n_seg, int L,
-                                                     int Ls, int Q, int PO, int idx_new)
+                                                       int32_t *__restrict__ part_off,
+                                                       int32_t *__restrict__ row_cnt,
+                                                       int32_t *__restrict__ row_min,
+                                                       int32_t *__restrict__ blk_min,
+                                                       const int32_t *__restrict__ queue_n,
+                                                       const int4 *__restrict__ queue, int n_seg, int L,
+                                                       int Ls, int Q, int PO, int idx_new)
 {
     __shared__ int32_t s_po[kInsPo];
     const int lane = lane_id();
@@ -514,12 +523,14 @@ __global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ en
         const int q_new = it.y, cnt = it.z, mn = it.w;
         uint32_t *re = ent + row * Ls;
         int32_t *po = part_off + row * PO;
+        int32_t *bm = blk_min + row * PO;
         const uint32_t e_new = pack_entry(idx_new, q_new);
         if (cnt < L) {  // (uniform over the wave)
             if (lane == 0) {
                 re[cnt] = e_new;
                 row_cnt[row] = cnt + 1;
                 row_min[row] = min(mn, q_new);
+                bm[u_new] = min(bm[u_new], q_new);
             }
             for (int u = lane; u < PO; u += kWave)
                 if ((int64_t)u * Q > idx_new) po[u] += 1;
@@ -528,45 +539,37 @@ __global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ en
         if (po_lds)
             for (int u = lane; u < PO; u += kWave) s_po[u] = po[u];
         const int32_t *pol = po_lds ? s_po : po;  // the offsets as they are before this insertion
-        // block of position p: the last u with pol[u] <= p (offsets are non-decreasing)
-        auto block_of = [&](int p) {
-            int lo = 0, hi = PO - 1;  // pol[lo] <= p < pol[hi]
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (pol[mid] <= p) lo = mid; else hi = mid;
+        // the block that holds the entry to evict: the last one whose minimum is the row minimum;
+        // the smallest of the other blocks' minima goes into the new row minimum
+        int ue = -1, others = 0x7FFFFFFF;
+        for (int u0 = 0; u0 + 1 < PO; u0 += kWave) {
+            const int u = u0 + lane;
+            const int v = u + 1 < PO ? bm[u] : 0x7FFFFFFF;
+            const unsigned long long hit = __ballot(v == mn);
+            if (hit) {
+                if (ue >= 0) others = min(others, mn);  // (an earlier block also holds the minimum)
+                ue = u0 + 63 - __clzll(hit);
             }
-            return lo;
-        };
-        // one pass over the row, 2048 entries (eight 16-byte loads per lane) at a time; slots >= L
-        // hold zeros (Ls is a multiple of 4)
-        unsigned long long best = 0ull;  // the entry to evict as (key index + 1, position): larger wins
-        int n_min = 0, min2 = 0x7FFFFFFF;  // occurrences of the minimum, smallest value above it
-        for (int base = 0; base < L; base += kWave * 4 * kInsLoads) {
-            uint4 v[kInsLoads];
-#pragma unroll
-            for (int u = 0; u < kInsLoads; ++u) {
-                const int p = base + (u * kWave + lane) * 4;
-                v[u] = p < L ? *(const uint4 *)(re + p) : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int u = 0; u < kInsLoads; ++u) {
-                const uint32_t ev[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int p = base + (u * kWave + lane) * 4 + i;
-                    if (p < L) {
-                        const int q = entry_q(ev[i]);
-                        if (q == mn) {
-                            ++n_min;
-                            const uint32_t idx = (((uint32_t)block_of(p) * (uint32_t)Q) & ~(uint32_t)(kUnit - 1)) |
-                                                 (ev[i] & (uint32_t)(kUnit - 1));
-                            const unsigned long long cand = ((unsigned long long)(idx + 1u) << 32) | (uint32_t)p;
-                            best = cand > best ? cand : best;
-                        } else {
-                            min2 = min(min2, q);
-                        }
-                    }
-                }
+            int o = (v == mn && u == ue) ? 0x7FFFFFFF : v;
+            for (int d = 32; d > 0; d >>= 1) o = min(o, __shfl_xor(o, d, kWave));
+            others = min(others, o);
+        }
+        if (ue < 0) continue;  // (cannot happen: row_min is the minimum of a full row)
+        // that block: the evicted entry (q == mn, largest index = largest low index bits within a
+        // block) and the smallest q of what stays in the block
+        const int b0 = pol[ue], b1 = pol[ue + 1];
+        unsigned long long best = 0ull;  // (low index bits + 1, position): larger wins
+        int n_min = 0, min2 = 0x7FFFFFFF;
+        for (int p = b0 + lane; p < b1; p += kWave) {
+            const uint32_t e = re[p];
+            const int q = entry_q(e);
+            if (q == mn) {
+                ++n_min;
+                const unsigned long long cand =
+                    ((unsigned long long)((e & (uint32_t)(kUnit - 1)) + 1u) << 32) | (uint32_t)p;
+                best = cand > best ? cand : best;
+            } else {
+                min2 = min(min2, q);
             }
         }
         for (int o = 32; o > 0; o >>= 1) {
@@ -575,9 +578,9 @@ __global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ en
             min2 = min(min2, __shfl_xor(min2, o, kWave));
         }
         n_min = wave_sum(n_min);
-        if (best == 0ull) continue;  // (cannot happen: row_min is the minimum of a full row)
+        if (best == 0ull) continue;  // (cannot happen: the block's minimum is recorded as mn)
         const int pe = (int)(uint32_t)best;
-        const int ue = block_of(pe);
+        const int blk_left = n_min >= 2 ? mn : min2;  // the block's minimum without the evicted entry
         // the hole's way: block w in [ue, u_new) gives its last entry (at pol[w+1] - 1) to the hole
         // (at pe in block ue, else in front of block w at pol[w] - 1); all reads of a round of 64
         // blocks first, then its writes - the source of one move is the target of the next
@@ -601,13 +604,22 @@ __global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ en
             // the new entry: in place of the evicted one if that sat in the last block, else in the
             // hole now in front of the last block
             re[ue == u_new ? pe : (po_lds ? s_po[u_new] - 1 : po[u_new])] = e_new;
-            row_min[row] = min(q_new, n_min >= 2 ? mn : min2);
+            int last_min;  // the last block's minimum with the new entry
+            if (ue == u_new) {
+                last_min = min(blk_left, q_new);
+            } else {
+                bm[ue] = blk_left;
+                last_min = min(bm[u_new], q_new);
+            }
+            bm[u_new] = last_min;
+            // (`others` counted block u_new with its old minimum when it is not the evicted one's)
+            row_min[row] = min(min(others, blk_left), q_new);
         }
     }
 }
 
 void launch_insert(const void *k_new, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
-                   int32_t *row_min, int32_t *queue_n, void *queue, int32_t *flags, int B, int Hkv, int C,
+                   int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *flags, int B, int Hkv, int C,
                    int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st)
 {
     const int nx = (C + kScanNT - 1) / kScanNT, n_seg = S * nx;  // (n_seg <= 64: checked at create)
@@ -618,7 +630,7 @@ void launch_insert(const void *k_new, const void *cent_t, void *ent, int32_t *pa
     // case (a few percent of the rows take a new key), striding when there are more
     const int per_seg = C < kScanNT ? C : kScanNT;  // rows behind a segment
     const int waves = per_seg / 8 < 1 ? 1 : per_seg / 8;  // one wave per 8 rows (about 3 % take a key, unevenly)
-    k_insert_rows<<<dim3(waves, n_seg, B * Hkv), kWave, 0, st>>>((uint32_t *)ent, part_off, row_cnt, row_min, queue_n,
+    k_insert_rows<<<dim3(waves, n_seg, B * Hkv), kWave, 0, st>>>((uint32_t *)ent, part_off, row_cnt, row_min, blk_min, queue_n,
                                                       (const int4 *)queue, n_seg, L, Ls, Q, PO, idx_new);
 }
 
