@@ -316,6 +316,25 @@ def test_one_call_iteration_equals_step_then_append(paged, stream_window):
     case.check_step(7)                                   # the plain step still works on the full context
 
 
+@pytest.mark.parametrize("n_pre,C,steps", [(70000, 8, 12), (1100000, 64, 40)])
+def test_streaming_updates_with_many_blocks_per_row(n_pre, C, steps):
+    """Key ranges of 1024 over 70K and 1.1M keys: a row is cut into 69 and 1075 blocks, so an
+    eviction's hole travels over more than one round of 64 blocks, and (1.1M) the row's offsets no
+    longer fit the on-chip copy.  Lists of the maximum length so that a fair share of the appended
+    keys enters some list; tables and steps are compared after every few appends."""
+    w = small(f"blocks{n_pre}", n_q_heads=2, n_kv_heads=1, n_pre=n_pre, n_comp=8, C=C, L=8192, m=2, k=100,
+              steps=steps)
+    case = Case(w, seed=60, F=11, partition_keys=1024, stream_window=4, gen_device="cuda")
+    case.build_on_gpu()
+    case.check_tables(0, 0)
+    for upto in (1, steps // 2, steps):
+        case.append(upto - case.t)
+        case.check_tables(0, 0)
+        case.check_step(upto - 1)
+    binding.csa_streaming_status(case.ctx.ctx)
+    assert (case.oracle_rows(0, 0)[0] >= w.n_pre).sum() >= 3
+
+
 def test_streaming_updates_report_scores_that_leave_the_grid():
     w = small("stream_ovf", n_q_heads=4, n_kv_heads=1, n_pre=500, C=8, L=64, m=2, k=50, steps=2)
     case = Case(w, seed=31, F=-1, stream_window=4)
