@@ -23,6 +23,10 @@
  *   - bf16 = the upper 16 bits of an IEEE fp32.  Inputs must be finite.
  *   - A ctx is not thread-safe; calls on one ctx must be issued from one thread at a time and
  *     on streams that are ordered with respect to each other.
+ *   - csa_decode_step and csa_decode_step_reuse only launch kernels on `stream` (no allocation,
+ *     no synchronisation, no memset or copy nodes), so they may be captured into a HIP graph and
+ *     replayed while the context length stays as captured; calls that append bake the position
+ *     into their launches and are not replayable.
  */
 #ifndef CSATTN_H
 #define CSATTN_H

@@ -401,6 +401,44 @@ def test_repeated_steps_are_deterministic():
                 assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
 
 
+@pytest.mark.parametrize("R,paged", [(8192, False), (1024, True)])
+def test_decode_step_is_capturable_in_a_hip_graph(R, paged):
+    """A serving loop can capture csa_decode_step (every launch goes to the caller's stream, nothing
+    allocates, nothing synchronises, no memset nodes): the graph is replayed with new queries in the
+    captured buffer, with eager steps and synchronisations between the replays, and every replay
+    matches the oracle and the eager result bit for bit.  (R = 8192 with a small launch takes the path
+    that finishes the Top-K inside the attention kernel, R = 1024 the separate kernel.)"""
+    w = small("graph", batch=2, n_q_heads=4, n_kv_heads=2, n_pre=9000, C=40, L=400, m=4, k=300, steps=4,
+              pre_appended=3, page_size=16 if paged else 0)
+    case = Case(w, seed=70, F=12, partition_keys=R)
+    case.import_oracle_tables()
+    case.append(3)
+    q_static = case.inp["q_steps"][3].clone()
+    case.ctx.decode_step(q_static)                       # warm-up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()                           # (default priority)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            case.ctx.decode_step(q_static)
+    torch.cuda.synchronize()
+    heads = [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
+    for step in (3, 4, 5, 3):
+        q_static.copy_(case.inp["q_steps"][step])
+        graph.replay()
+        torch.cuda.synchronize()
+        out = case.ctx.out.cpu().numpy().copy()
+        sel = case.ctx.sel.cpu().numpy().copy()
+        cnt = case.ctx.sel_count.cpu().numpy().copy()
+        e_out, e_sel, e_cnt, _ = case.decode(step)      # eager work between the replays
+        assert np.array_equal(out.view(np.uint8), e_out.view(np.uint8))
+        assert np.array_equal(sel, e_sel) and np.array_equal(cnt, e_cnt)
+        _, o_sel, o_cnt, o_out = case.oracle_decode(step, heads)
+        for t, (b, h) in enumerate(heads):
+            assert cnt[b, h] == o_cnt[t] and np.array_equal(sel[b, h][:w.k], o_sel[t])
+            assert np.abs(out[b, h] - o_out[t]).max() <= 2e-2
+
+
 def test_device_side_errors_are_reported():
     w = small("err", n_pre=500, C=8, L=64, m=2, k=10, steps=1)
     case = Case(w, seed=10, F=12)
