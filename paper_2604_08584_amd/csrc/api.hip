@@ -563,13 +563,22 @@ int search_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_id
 
     Prof prof(ctx, st);
     prof.mark(0);
-    csa::launch_score_centroids(q_dev, at<void>(ctx->tables, l.cent_t), z, c.batch, c.n_kv_heads, G,
-                                c.n_centroids, S_sub, st);
-    prof.end(0);
     int32_t *spans = at<int32_t>(ctx->scratch, l.spans);
-    csa::launch_top_centroids(z, rows, at<int32_t>(ctx->tables, l.part_off), spans, BH,
-                              c.n_centroids, S_sub, c.n_probe, G, ctx->P, ctx->nsub, ctx->PO, st);
-    prof.end(1);
+    if (csa::score_top_fused(c.n_centroids, S_sub, c.n_probe)) {
+        // the paper's own geometry: scoring and the choice of the probed rows in one launch
+        csa::launch_score_top_sub(q_dev, at<void>(ctx->tables, l.cent_t), rows, at<int32_t>(ctx->tables, l.part_off),
+                                  spans, c.batch, c.n_kv_heads, G, c.n_centroids, S_sub, c.n_probe, ctx->P,
+                                  ctx->nsub, ctx->PO, st);
+        prof.end(0);
+        prof.mark(2);
+    } else {
+        csa::launch_score_centroids(q_dev, at<void>(ctx->tables, l.cent_t), z, c.batch, c.n_kv_heads, G,
+                                    c.n_centroids, S_sub, st);
+        prof.end(0);
+        csa::launch_top_centroids(z, rows, at<int32_t>(ctx->tables, l.part_off), spans, BH,
+                                  c.n_centroids, S_sub, c.n_probe, G, ctx->P, ctx->nsub, ctx->PO, st);
+        prof.end(1);
+    }
     csa::launch_accumulate(at<void>(ctx->tables, l.ent), rows, spans, cand_key, bin_off, cand_cnt, BH,
                            Ct, l.Ls, M, G, ctx->R, ctx->P, l.cand_keys, ctx->key_lo, ctx->key_sh, ws, st);
     prof.end(2);

@@ -102,6 +102,118 @@ __global__ __launch_bounds__(256) void k_score_centroids_sub(const uint16_t *__r
     }
 }
 
+// Steps 1a + 1b in one launch for the paper's own geometry - several subspaces with few centroids
+// each (C <= 256) and few probes per subspace (tau <= kFusedTau): the workgroup that scores
+// subspace s of a KV head holds every centroid score of that subspace for the GH query heads in
+// registers, so it also picks the tau best per head (tau rounds of "largest, ties to the lower
+// centroid, remove") and publishes the probed rows and their block offsets, as k_top_centroids
+// does.  No z array, no second launch.
+// grid (1, S, B*Hkv), block 256.
+constexpr int kFusedTau = 4;
+
+template <int GH>
+__global__ __launch_bounds__(256) void k_score_top_sub(const uint16_t *__restrict__ q,
+                                                       const uint4 *__restrict__ cent_t,
+                                                       int32_t *__restrict__ rows,
+                                                       const int32_t *__restrict__ part_off,
+                                                       int32_t *__restrict__ spans, int C, int G, int S,
+                                                       int tau, int P, int nsub, int PO)
+{
+    __shared__ float s_q[GH][kHeadDim / 2];
+    __shared__ unsigned long long s_best[256 / kWave][GH];  // per wave and head: (key, ~centroid)
+    __shared__ int32_t s_rows[GH][kFusedTau];
+    const int sub = blockIdx.y, bg = blockIdx.z;
+    const int db = kHeadDim / S, nch = db / 8;  // nch <= 8
+    const int j = threadIdx.x;
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int M = S * tau, nb = nsub + 1;
+    const uint4 *ct = cent_t + ((size_t)bg * S + sub) * nch * C;
+    uint4 wv[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) wv[c] = (c < nch && j < C) ? ct[(size_t)c * C + j] : make_uint4(0, 0, 0, 0);
+    for (int h0 = 0; h0 < G; h0 += GH) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < GH * db; e += 256) {
+            const int hh = e / db, t = e % db;
+            s_q[hh][t] = __uint_as_float((uint32_t)q[((size_t)bg * G + h0 + hh) * kHeadDim + sub * db + t] << 16);
+        }
+        __syncthreads();
+        uint32_t key[GH];  // order-preserving image of z; 0 = no centroid / already taken
+        {
+            float acc[GH];
+#pragma unroll
+            for (int hh = 0; hh < GH; ++hh) acc[hh] = 0.0f;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                if (c < nch) {
+                    const uint4 w = wv[c];
+                    const float cf[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                                         bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+#pragma unroll
+                        for (int hh = 0; hh < GH; ++hh)
+                            acc[hh] = __builtin_fmaf(s_q[hh][c * 8 + e], cf[e], acc[hh]);
+                }
+            }
+#pragma unroll
+            for (int hh = 0; hh < GH; ++hh) key[hh] = j < C ? orderable(acc[hh] + 0.0f) : 0u;  // -0 -> +0
+        }
+        for (int r = 0; r < tau; ++r) {
+#pragma unroll
+            for (int hh = 0; hh < GH; ++hh) {
+                const uint32_t wm = wave_max(key[hh]);
+                const int first = __ffsll((unsigned long long)__ballot(key[hh] == wm)) - 1;  // lowest centroid
+                if (lane == 0)
+                    s_best[wave][hh] = ((unsigned long long)wm << 32) | (uint32_t)~(uint32_t)(wave * kWave + first);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int hh = 0; hh < GH; ++hh) {
+                unsigned long long b = s_best[0][hh];
+#pragma unroll
+                for (int w = 1; w < 256 / kWave; ++w) b = max(b, s_best[w][hh]);
+                const int win = (int)~(uint32_t)b;
+                if (j == win) {
+                    key[hh] = 0u;
+                    s_rows[hh][r] = win;
+                }
+            }
+            __syncthreads();
+        }
+        // the probed rows, and for every key range p the nsub + 1 block offsets of each probed row
+        for (int t = threadIdx.x; t < GH * tau; t += 256) {
+            const int hh = t / tau, r = t - hh * tau;
+            rows[((size_t)bg * G + h0 + hh) * M + sub * tau + r] = sub * C + s_rows[hh][r];
+        }
+        for (int t = threadIdx.x; t < GH * P * tau * nb; t += 256) {
+            const int x = t % nb, pr = t / nb;
+            const int r = pr % tau, ph = pr / tau;
+            const int p = ph % P, hh = ph / P;
+            const size_t head = (size_t)bg * G + h0 + hh;
+            spans[((head * P + p) * M + sub * tau + r) * nb + x] =
+                part_off[((size_t)bg * S * C + (size_t)sub * C + s_rows[hh][r]) * PO + p * nsub + x];
+        }
+    }
+}
+
+bool score_top_fused(int C, int S, int tau) { return S > 1 && C <= 256 && tau <= kFusedTau; }
+
+void launch_score_top_sub(const void *q, const void *cent_t, int32_t *rows, const int32_t *part_off,
+                          int32_t *spans, int B, int Hkv, int G, int C, int S, int tau, int P, int nsub,
+                          int PO, hipStream_t st)
+{
+    dim3 grid(1, S, B * Hkv), block(256);
+#define CSA_ST(GH_)                                                                                    \
+    k_score_top_sub<GH_><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, rows, part_off, \
+                                                 spans, C, G, S, tau, P, nsub, PO)
+    if (G % 8 == 0) CSA_ST(8);
+    else if (G % 4 == 0) CSA_ST(4);
+    else if (G % 2 == 0) CSA_ST(2);
+    else CSA_ST(1);
+#undef CSA_ST
+}
+
 void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
                             int C, int S, hipStream_t st)
 {

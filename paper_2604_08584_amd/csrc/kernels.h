@@ -43,6 +43,11 @@ int cluster_problem(const void *q_group, int n_pre, int n_pool, int S, int sub, 
 // ---- decode.hip
 void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
                             int C, int S, hipStream_t st);
+// both of the above in one launch (several subspaces, C <= 256, few probes per subspace)
+bool score_top_fused(int C, int S, int tau);
+void launch_score_top_sub(const void *q, const void *cent_t, int32_t *rows, const int32_t *part_off,
+                          int32_t *spans, int B, int Hkv, int G, int C, int S, int tau, int P, int nsub,
+                          int PO, hipStream_t st);
 void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, int32_t *spans,
                           int n_heads, int C, int S, int tau, int G, int P, int nsub, int PO, hipStream_t st);
 // candidates of (head, key range): cand_key (words grouped by coarse score bin, best first),
