@@ -255,12 +255,12 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
 // Also looks up, for every key range p, the
 // nsub + 1 offsets that cut the slice of each probed row into its blocks, so that the
 // accumulation kernel starts with one coalesced read.
-// grid B*Hq*S, block 256.
+// grid B*Hq*S, block 256 (1024 for a small launch of long score arrays).
 // ---------------------------------------------------------------------------------------------
-constexpr int kTopNT = 256;
 constexpr int kTopReg = 16;     // keys per thread held in registers
 constexpr int kTopCand = 1024;  // candidate capacity of the fast path
 
+template <int kTopNT>
 __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restrict__ z,
                                                           int32_t *__restrict__ rows,
                                                           const int32_t *__restrict__ part_off,
@@ -421,7 +421,12 @@ publish:
 void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, int32_t *spans,
                           int n_heads, int C, int S, int tau, int G, int P, int nsub, int PO, hipStream_t st)
 {
-    k_top_centroids<<<n_heads * S, kTopNT, 0, st>>>(z, rows, part_off, spans, C, S, tau, G, P, nsub, PO);
+    // a small launch (fewer workgroups than CUs) of long score arrays: 1024 threads per head shorten
+    // every phase of this chain of latencies
+    if (n_heads * S <= 256 && C >= 1024)
+        k_top_centroids<1024><<<n_heads * S, 1024, 0, st>>>(z, rows, part_off, spans, C, S, tau, G, P, nsub, PO);
+    else
+        k_top_centroids<256><<<n_heads * S, 256, 0, st>>>(z, rows, part_off, spans, C, S, tau, G, P, nsub, PO);
 }
 
 // ---------------------------------------------------------------------------------------------
