@@ -73,9 +73,14 @@ Layout make_layout(const csa_config &c)
     const size_t BG = (size_t)c.batch * c.n_kv_heads, BH = (size_t)c.batch * c.n_q_heads;
     const size_t Ct = (size_t)c.n_subspaces * c.n_centroids;  // table rows per KV head
     const size_t M = (size_t)c.n_subspaces * c.n_probe;       // rows probed per query
+    // choose_partition widens the key ranges until a head has at most 2048 of them, so neither the
+    // ranges nor the block offsets of a row (P * nsub + 1, nsub = 2 only for ranges of 16384 keys,
+    // of which there are at most 1024) outgrow these bounds however long the context is
     l.P_max = (c.max_ctx + min_R(c) - 1) / min_R(c);
+    if (l.P_max > 2048) l.P_max = 2048;
     const int q_min = min_R(c) < kUnit ? min_R(c) : kUnit;
     l.PO_max = (c.max_ctx + q_min - 1) / q_min + 5;  // >= P * nsub + 1 for every admissible R
+    if (l.PO_max > 2048 + 5) l.PO_max = 2048 + 5;
     l.Ls = (c.list_len + 3) / 4 * 4;                 // row stride: 16-byte aligned rows
     size_t off = 0;
     auto put = [&](Region &r, size_t bytes) {

@@ -46,6 +46,25 @@ def test_create_validates_configuration():
         assert e.value.status == binding.CSA_ERR_ARG, bad
 
 
+def test_workspace_stays_proportionate_for_the_longest_context():
+    """max_ctx = 2^24 with the smallest requested key ranges: the ranges are widened until a head has
+    at most 2048 of them, and the per-range buffers are sized for that, not for max_ctx / 1024."""
+    cfg = dict(batch=1, n_q_heads=8, n_kv_heads=1, n_centroids=64, list_len=1024, n_probe=4, budget_k=1000,
+               max_ctx=1 << 24, partition_keys=1024)
+    ctx = binding.csa_create(**cfg)
+    tb, sb = binding.csa_workspace_bytes(ctx)
+    binding.csa_destroy(ctx)
+    per_head_candidates = (1 << 24) * 4                     # one 32-bit word per key index
+    per_head_ranges = 2048 * (512 * 2 + 4 + 8 + 8)          # bin offsets, count, two small records per range
+    build_scratch = 64 * (1 << 24) * 4                      # integer scores of a chunk of centroid rows
+    assert sb < 8 * (per_head_candidates + per_head_ranges) * 1.2 + build_scratch * 1.1 + (1 << 24)
+    assert tb < (64 * 1024 * 4 + 64 * 2053 * 4 + 64 * 128 * 2) * 1.1 + (1 << 20)
+    # streaming updates bound the queue segments per KV head
+    with pytest.raises(binding.CsaError) as e:
+        binding.csa_create(**{**GOOD, 'n_centroids': 70000, 'n_probe': 4, 'stream_window': 8})
+    assert e.value.status == binding.CSA_ERR_ARG
+
+
 def test_calls_out_of_order_are_refused_on_the_host():
     lib = binding.lib()
     ctx = binding.csa_create(**GOOD)
