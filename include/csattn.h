@@ -52,7 +52,7 @@ typedef enum {
 
 typedef struct {
     int32_t batch;       /* B  >= 1 */
-    int32_t n_q_heads;   /* Hq, multiple of n_kv_heads, G = Hq/Hkv in {1,2,4,8,16} */
+    int32_t n_q_heads;   /* Hq, multiple of n_kv_heads, G = Hq/Hkv <= 16 */
     int32_t n_kv_heads;  /* Hkv >= 1 */
     int32_t head_dim;    /* d, must be 128 */
     int32_t n_centroids; /* C >= 1: query-centric centroids per KV head and subspace (Sec. 3.2 (1)) */

@@ -130,7 +130,7 @@ int validate(const csa_config &c)
     if (c.batch < 1 || c.n_kv_heads < 1 || c.n_q_heads < 1) return CSA_ERR_ARG;
     if (c.n_q_heads % c.n_kv_heads) return CSA_ERR_ARG;
     const int G = c.n_q_heads / c.n_kv_heads;
-    if (!(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) return CSA_ERR_ARG;
+    if (G > 16) return CSA_ERR_ARG;
     if (c.head_dim != 128) return CSA_ERR_ARG;
     if (c.n_centroids < 1 || c.list_len < 1 || c.list_len > 8192) return CSA_ERR_ARG;
     const int S = c.n_subspaces;

@@ -197,6 +197,14 @@ __global__ __launch_bounds__(256) void k_score_top_sub(const uint16_t *__restric
     }
 }
 
+// query heads of a KV head scored per pass over its centroids: the largest divisor of G up to 8
+static int heads_per_pass(int G)
+{
+    for (int gh = 8; gh > 1; --gh)
+        if (G % gh == 0) return gh;
+    return 1;
+}
+
 bool score_top_fused(int C, int S, int tau) { return S > 1 && C <= 256 && tau <= kFusedTau; }
 
 void launch_score_top_sub(const void *q, const void *cent_t, int32_t *rows, const int32_t *part_off,
@@ -207,10 +215,16 @@ void launch_score_top_sub(const void *q, const void *cent_t, int32_t *rows, cons
 #define CSA_ST(GH_)                                                                                    \
     k_score_top_sub<GH_><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, rows, part_off, \
                                                  spans, C, G, S, tau, P, nsub, PO)
-    if (G % 8 == 0) CSA_ST(8);
-    else if (G % 4 == 0) CSA_ST(4);
-    else if (G % 2 == 0) CSA_ST(2);
-    else CSA_ST(1);
+    switch (heads_per_pass(G)) {
+    case 8: CSA_ST(8); break;
+    case 7: CSA_ST(7); break;
+    case 6: CSA_ST(6); break;
+    case 5: CSA_ST(5); break;
+    case 4: CSA_ST(4); break;
+    case 3: CSA_ST(3); break;
+    case 2: CSA_ST(2); break;
+    default: CSA_ST(1); break;
+    }
 #undef CSA_ST
 }
 
@@ -218,27 +232,38 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
                             int C, int S, hipStream_t st)
 {
     dim3 block(256);
+    const int gh = heads_per_pass(G);
     if (S == 1) {
         dim3 grid((C + 255) / 256, B * Hkv);
-        if (G % 8 == 0)
-            k_score_centroids<8><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
-        else if (G % 4 == 0)
-            k_score_centroids<4><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
-        else if (G % 2 == 0)
-            k_score_centroids<2><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
-        else
-            k_score_centroids<1><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G);
+#define CSA_SC(GH_) \
+    k_score_centroids<GH_><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G)
+        switch (gh) {
+        case 8: CSA_SC(8); break;
+        case 7: CSA_SC(7); break;
+        case 6: CSA_SC(6); break;
+        case 5: CSA_SC(5); break;
+        case 4: CSA_SC(4); break;
+        case 3: CSA_SC(3); break;
+        case 2: CSA_SC(2); break;
+        default: CSA_SC(1); break;
+        }
+#undef CSA_SC
         return;
     }
     dim3 grid((C + 255) / 256, S, B * Hkv);
-    if (G % 8 == 0)
-        k_score_centroids_sub<8><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, S);
-    else if (G % 4 == 0)
-        k_score_centroids_sub<4><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, S);
-    else if (G % 2 == 0)
-        k_score_centroids_sub<2><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, S);
-    else
-        k_score_centroids_sub<1><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, S);
+#define CSA_SC(GH_) \
+    k_score_centroids_sub<GH_><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, S)
+    switch (gh) {
+    case 8: CSA_SC(8); break;
+    case 7: CSA_SC(7); break;
+    case 6: CSA_SC(6); break;
+    case 5: CSA_SC(5); break;
+    case 4: CSA_SC(4); break;
+    case 3: CSA_SC(3); break;
+    case 2: CSA_SC(2); break;
+    default: CSA_SC(1); break;
+    }
+#undef CSA_SC
 }
 
 // ---------------------------------------------------------------------------------------------

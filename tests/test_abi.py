@@ -37,7 +37,7 @@ def test_create_validates_configuration():
     binding.csa_destroy(ctx)
     binding.csa_destroy(binding.csa_create(**{**GOOD, 'n_subspaces': 8, 'n_probe': 2}))   # the paper's geometry
     for bad in (dict(head_dim=64), dict(n_probe=0), dict(n_probe=64), dict(n_probe=65, n_centroids=100),
-                dict(n_q_heads=3), dict(n_subspaces=3), dict(n_subspaces=32), dict(n_subspaces=16, n_probe=4),
+                dict(n_q_heads=3, n_kv_heads=2), dict(n_q_heads=17), dict(n_subspaces=3), dict(n_subspaces=32), dict(n_subspaces=16, n_probe=4),
                 dict(list_len=0), dict(list_len=10000),
                 dict(page_size=8), dict(page_size=16, max_ctx=4100), dict(budget_k=-1),
                 dict(partition_keys=3000), dict(max_ctx=0), dict(batch=0)):

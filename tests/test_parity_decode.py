@@ -44,7 +44,7 @@ def test_cfg0_automatic_grid():
     case.check_step(0)
 
 
-@pytest.mark.parametrize("G,part", [(1, 0), (2, 1024), (4, 2048), (8, 1024)])
+@pytest.mark.parametrize("G,part", [(1, 0), (2, 1024), (4, 2048), (8, 1024), (3, 2048), (7, 1024), (12, 0)])
 def test_ragged_shapes_import_and_build(G, part):
     """Sizes that are not multiples of any tile (n_pre = 5003, C = 100, L = 300, m = 7, k = 333),
     several key ranges, appended keys crossing the 8-item iteration and wave boundaries."""
