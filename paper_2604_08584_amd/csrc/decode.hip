@@ -587,27 +587,32 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     // counting sort through LDS): word = (score bits below the bin) << kIdxBits | slot in the range.
     // The Top-K threshold then needs the per-range bin offsets and the one bin it falls in, and a
     // range's winners are a prefix of its candidates plus part of that bin.
-    // pass 1: occupancy of the bins (reversed: bin 0 holds the largest scores)
-    const uint32_t low_mask = (1u << key_sh) - 1u;
+    // every accumulator becomes d = (its score key) - key_lo once (kEmpty for an untouched slot): the
+    // two passes below then need a shift each
+    constexpr uint32_t kEmpty = 0xFFFFFFFFu;  // (a real d is below 2^25)
+    const int32_t rebase = kKeyBias - (int32_t)key_lo;
+    uint32_t d[16];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
 #pragma unroll
-        for (int x = 0; x < 4; ++x)
-            if (av[x] != 0) {
-                const uint32_t d = (uint32_t)((av[x] >> kCntBits) + kKeyBias) - key_lo;
-                atomicAdd(&s_h[(kCoarseBins - 1) - (d >> key_sh)], 1u);
-            }
+        for (int x = 0; x < 4; ++x) d[4 * u + x] = av[x] != 0 ? (uint32_t)((av[x] >> kCntBits) + rebase) : kEmpty;
     }
+    // pass 1: occupancy of the bins (s_h is indexed by the bin itself, the output by the reversed
+    // bin: output bin 0 holds the largest scores)
+    const uint32_t low_mask = (1u << key_sh) - 1u;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        if (d[i] != kEmpty) atomicAdd(&s_h[d[i] >> key_sh], 1u);
     __syncthreads();
-    // exclusive scan over the bins: where each bin's run starts (kept in LDS as the running write
-    // position of the bin, and written out for the selection kernels)
+    // exclusive scan over the reversed bins: where each bin's run starts (kept in LDS as the running
+    // write position of the bin, and written out for the selection kernels)
     constexpr int BPT = NT >= kCoarseBins ? 1 : kCoarseBins / NT;  // bins per owning thread
     const bool owner = (int)threadIdx.x * BPT < kCoarseBins;
     int cnt[BPT], mine = 0;
 #pragma unroll
     for (int j = 0; j < BPT; ++j) {
-        cnt[j] = owner ? (int)s_h[threadIdx.x * BPT + j] : 0;
+        cnt[j] = owner ? (int)s_h[(kCoarseBins - 1) - (threadIdx.x * BPT + j)] : 0;
         mine += cnt[j];
     }
     int total;
@@ -616,7 +621,7 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     if (owner) {
 #pragma unroll
         for (int j = 0; j < BPT; ++j) {
-            s_pos[threadIdx.x * BPT + j] = (uint32_t)start;
+            s_pos[(kCoarseBins - 1) - (threadIdx.x * BPT + j)] = (uint32_t)start;
             bo[threadIdx.x * BPT + j] = (uint16_t)start;
             start += cnt[j];
         }
@@ -626,16 +631,12 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     // registers by now, so the accumulator array is free to hold the sorted words)
     uint32_t *s_out = (uint32_t *)s_acc;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
-#pragma unroll
-        for (int x = 0; x < 4; ++x)
-            if (av[x] != 0) {
-                const uint32_t d = (uint32_t)((av[x] >> kCntBits) + kKeyBias) - key_lo;
-                const uint32_t at = atomicAdd(&s_pos[(kCoarseBins - 1) - (d >> key_sh)], 1u);
-                s_out[at] = ((d & low_mask) << kIdxBits) | (uint32_t)(4 * (u * NT + (int)threadIdx.x) + x);
-            }
-    }
+    for (int i = 0; i < 16; ++i)
+        if (d[i] != kEmpty) {
+            const uint32_t at = atomicAdd(&s_pos[d[i] >> key_sh], 1u);
+            // slot of accumulator i = 4 * ((i / 4) * NT + thread) + i % 4
+            s_out[at] = ((d[i] & low_mask) << kIdxBits) | (uint32_t)(4 * ((i >> 2) * NT + (int)threadIdx.x) + (i & 3));
+        }
     __syncthreads();
     uint32_t *dk = cand_key + (size_t)head * cand_stride + (size_t)p * R;
     for (int i = threadIdx.x; i < total; i += NT) dk[i] = s_out[i];
