@@ -174,9 +174,8 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
  * fixed-capacity list: a list with a free slot takes it, a full list takes it only if its score
  * beats the list's minimum (an equal score does not), which is evicted.  csa_decode_step then
  * attends the selected keys plus the last R positions [max(0, n - R), n); keys in that window
- * are not candidates of the Top-K.  A score outside the grid range, or larger in magnitude than
- * twice the largest key-centroid score met when the tables were built or imported, is clamped
- * (see csa_streaming_status).
+ * are not candidates of the Top-K.  A score outside the grid range is clamped (see
+ * csa_streaming_status).
  * CSA_ERR_CAPACITY if n == max_ctx.
  */
 int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, void *stream);
@@ -226,8 +225,7 @@ int csa_decode_step_append(csa_ctx *ctx, const void *q_dev, const void *k_new_de
                            void *stream);
 
 /* Streaming updates only: SYNCHRONISES `stream` and returns CSA_ERR_RANGE if a streamed key's
- * score was clamped since the tables were built (it left the score grid or exceeded twice the
- * largest score met at build / import time), else CSA_OK. */
+ * score did not fit the score grid since the tables were built (it was clamped), else CSA_OK. */
 int csa_streaming_status(csa_ctx *ctx, void *stream);
 
 /* Host-side counters: prefill length and current context length. */

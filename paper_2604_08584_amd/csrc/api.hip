@@ -49,7 +49,6 @@ struct csa_ctx {
     int Q = 0, nsub = 0, PO = 0;  // block size min(R, kUnit), blocks per range, offsets per row
     uint32_t key_lo = 0;  // coarse score bins of the candidates: 512 bins of 2^key_sh keys starting at key_lo
     int key_sh = 0;
-    int q_clamp = 0;  // largest |q| a streamed key's score may have (larger ones are clamped and reported)
     int hip_err = 0;
     // profiling
     bool prof = false;
@@ -203,15 +202,9 @@ int qmax_for(int m)
 // m * max|q| of 2^24: 512 equal bins over that span.
 void set_key_range(csa_ctx *ctx, int qabs_max)
 {
-    // scores of keys inserted later: admitted up to twice the largest score seen so far (and the
-    // grid's own limit); the try test clamps to that bound and reports it.  The tighter the span,
-    // the finer the 512 bins the candidates are sorted into.
-    ctx->q_clamp = qmax_for(ctx->cfg.n_probe * ctx->cfg.n_subspaces);
-    if (ctx->cfg.stream_window > 0) {
-        const int64_t twice = 2 * (int64_t)(qabs_max > 0 ? qabs_max : 1);
-        if (twice < ctx->q_clamp) ctx->q_clamp = (int)twice;
-        qabs_max = ctx->q_clamp;
-    }
+    // scores of keys inserted later are only known to respect the admissible maximum (a bound taken
+    // from the prefill keys would be wrong for a short prefill followed by a long generation)
+    if (ctx->cfg.stream_window > 0) qabs_max = qmax_for(ctx->cfg.n_probe * ctx->cfg.n_subspaces);
     const uint32_t span = (uint32_t)(ctx->cfg.n_probe * ctx->cfg.n_subspaces) * (uint32_t)qabs_max;  // < 2^24
     ctx->key_lo = (1u << 24) - span;
     int sh = 0;
@@ -493,7 +486,7 @@ void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, hipStream_t st)
                        at<int32_t>(ctx->scratch, l.queue_n),
                        at<void>(ctx->scratch, l.queue), at<int32_t>(ctx->scratch, l.flags), c.batch,
                        c.n_kv_heads, c.n_centroids, c.n_subspaces, c.list_len, l.Ls, ctx->Q, ctx->PO, ctx->F,
-                       ctx->q_clamp, ctx->n, st);
+                       qmax_for(c.n_probe * c.n_subspaces), ctx->n, st);
     prof.end(9);
 }
 

@@ -335,6 +335,25 @@ def test_streaming_updates_with_many_blocks_per_row(n_pre, C, steps):
     assert (case.oracle_rows(0, 0)[0] >= w.n_pre).sum() >= 3
 
 
+@pytest.mark.parametrize("n_pre,S,C", [(1, 1, 1), (2, 8, 5), (17, 2, 64)])
+def test_streaming_updates_after_a_very_short_prefill(n_pre, S, C):
+    """A prefill of one, two or seventeen keys, then generation with streaming updates: lists start
+    almost empty and fill up; appended keys score well above anything the prefill held, and none of
+    that may be clamped or reported."""
+    w = small(f"short{n_pre}", n_q_heads=6, n_kv_heads=2, n_pre=n_pre, n_comp=2, C=C, L=16, m=1, k=50, steps=24,
+              n_sub=S)
+    case = Case(w, seed=80 + n_pre, F=10, partition_keys=16384, stream_window=3)
+    case.build_on_gpu()
+    for step in range(24):
+        case.check_step(step, fused_append=(step % 2 == 0))
+        if step % 2:
+            case.append(1)
+        if step % 6 == 5:
+            for g in range(2):
+                case.check_tables(0, g)
+    binding.csa_streaming_status(case.ctx.ctx)
+
+
 def test_streaming_updates_report_scores_that_leave_the_grid():
     w = small("stream_ovf", n_q_heads=4, n_kv_heads=1, n_pre=500, C=8, L=64, m=2, k=50, steps=2)
     case = Case(w, seed=31, F=-1, stream_window=4)
