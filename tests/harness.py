@@ -206,26 +206,31 @@ class Case:
         return worst
 
 
-    def check_reuse_step(self, step, sel, cnt, heads=None, pass_buffers=False):
+    def check_reuse_step(self, step, sel, cnt, heads=None, pass_buffers=False, fused_append=False):
         """A search-period step: attention of step `step`'s query over the index set (sel, cnt) of
-        an earlier searching step plus everything appended so far; compared with the oracle."""
+        an earlier searching step plus everything appended so far; compared with the oracle.
+        fused_append: the GPU side uses the one-call form that also appends the next K/V row."""
         w = self.w
         if heads is None:
             heads = [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
         q = self.inp["q_steps"][step]
-        if pass_buffers:
-            out = self.ctx.decode_step_reuse(q, torch.from_numpy(sel).cuda(), torch.from_numpy(cnt).cuda())
+        bufs = (torch.from_numpy(sel).cuda(), torch.from_numpy(cnt).cuda()) if pass_buffers else ()
+        n = w.n_pre + self.t                      # the context this step attends to
+        start = self.window_start()
+        if fused_append:
+            out = self.ctx.decode_step_reuse_append(q, self.inp["k_new"][self.t], self.inp["v_new"][self.t], *bufs)
         else:
-            out = self.ctx.decode_step_reuse(q)
+            out = self.ctx.decode_step_reuse(q, *bufs)
         torch.cuda.synchronize()
         out = out.cpu().numpy()
+        if fused_append:
+            self._mirror_append()
         qh = oracle.bf16_bits(q)
-        n = w.n_pre + self.t
         worst = 0.0
         for b, h in heads:
             g = h // w.group
             want = oracle.attend_selected(np.ascontiguousarray(qh[b, h]), self.K_host[b, g], self.V_host[b, g],
-                                          sel[b, h][:cnt[b, h]], self.window_start(), n)
+                                          sel[b, h][:cnt[b, h]], start, n)
             err = float(np.abs(out[b, h] - want).max())
             assert np.isfinite(out[b, h]).all() and err <= TOL_OUT, f"{w.name} reuse step {step} head ({b},{h}): {err}"
             worst = max(worst, err)
