@@ -299,7 +299,7 @@ __device__ __forceinline__ int emit_range(const uint32_t *__restrict__ cand_key,
         if (allow <= 0)
             eq = 0;
         else
-            while (__popc(eq) > allow) eq &= ~(0x80000000u >> __clz(eq));  // drop the highest bit
+            while ((int)__popc(eq) > allow) eq &= ~(0x80000000u >> __clz(eq));  // drop the highest bit
     }
     bits |= eq;
     int pos = par.x + block_excl_scan<NT>(__popc(bits), s_scan, total);

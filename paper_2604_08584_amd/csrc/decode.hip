@@ -331,7 +331,7 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
     };
     if (C <= kTopNT) {
         // ---- few centroids: one value per thread, rank = number of values that beat it
-        const uint64_t mine = threadIdx.x < C ? (((uint64_t)kreg[0] << 32) | (uint32_t)~threadIdx.x) : 0ull;
+        const uint64_t mine = (int)threadIdx.x < C ? (((uint64_t)kreg[0] << 32) | (uint32_t)~threadIdx.x) : 0ull;
         s_ck[threadIdx.x] = mine;  // (key << 32) | ~j: larger = better, distinct; 0 beats nothing
         __syncthreads();
         if ((int)threadIdx.x < C) {
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     {
         const int32_t *sp = spans + ((size_t)head * P + p) * m * NB;
         for (int e = threadIdx.x; e < m * NB; e += NT) s_b[e] = sp[e];
-        if (threadIdx.x < m) s_row[threadIdx.x] = rows[(size_t)head * m + threadIdx.x];
+        if ((int)threadIdx.x < m) s_row[threadIdx.x] = rows[(size_t)head * m + threadIdx.x];
         int4 *z4 = (int4 *)s_acc;
 #pragma unroll
         for (int u = 0; u < 4; ++u) z4[u * NT + threadIdx.x] = make_int4(0, 0, 0, 0);

@@ -439,7 +439,7 @@ __global__ __launch_bounds__(kScanNT) void k_insert_scan(const uint16_t *__restr
     const int db = kHeadDim / S, nch = db / 8;
     const int j = blockIdx.x * kScanNT + threadIdx.x;
     if (threadIdx.x == 0) s_n = 0;
-    if (threadIdx.x < db)
+    if ((int)threadIdx.x < db)
         s_k[threadIdx.x] = __uint_as_float((uint32_t)k_new[(size_t)bg * kHeadDim + sub * db + threadIdx.x] << 16);
     __syncthreads();
     const bool live = j < C;
