@@ -5,6 +5,8 @@ Where floating point decides an integer (an assignment, a seed draw) both sides 
 what is unique: assignments may differ only where the oracle's own decision gap is at rounding
 level; centroids of clusters with identical members may differ by one bf16 step (fp32 atomics vs
 fp64 sums); seeds must be data points and follow the D^2 weighting."""
+import random
+
 import numpy as np
 import pytest
 import torch
@@ -37,12 +39,11 @@ def _pool(q_bits, b, g, G, sub, db):
     return np.ascontiguousarray(x.reshape(-1, 128)[:, sub * db:(sub + 1) * db])
 
 
-@pytest.mark.parametrize("S,C", [(1, 37), (4, 64), (16, 20), (8, 130)])
-def test_lloyd_step_matches_the_oracle(S, C):
-    B, Hq, Hkv, n_pre = 2, 4, 2, 700
-    G, db = Hq // Hkv, 128 // S
-    q = _queries(B, Hq, n_pre, 12, 100 + S)
-    rng = np.random.default_rng(S)
+def _check_lloyd_step(B, Hkv, G, n_pre, S, C, seed, max_diff=2):
+    """One Lloyd step from random unit centroids on both sides; returns nothing, asserts parity."""
+    Hq, db = G * Hkv, 128 // S
+    q = _queries(B, Hq, n_pre, 12, 100 + seed)
+    rng = np.random.default_rng(seed)
     init = rng.standard_normal((B, Hkv, S, C, db)).astype(np.float32)
     init /= np.linalg.norm(init, axis=-1, keepdims=True)
     init_t = torch.from_numpy(init).to(torch.bfloat16).cuda()
@@ -72,7 +73,26 @@ def test_lloyd_step_matches_the_oracle(S, C):
                     np.testing.assert_allclose(got_f[j], want_f[j], rtol=2.0 ** -7, atol=1e-6,
                                                err_msg=f"centroid {j} of ({b},{g},{s})")
                 np.testing.assert_allclose(np.linalg.norm(got_f.astype(np.float64), axis=1), 1.0, atol=1e-2)
-    assert n_diff <= 2
+    assert n_diff <= max_diff
+
+
+@pytest.mark.parametrize("S,C", [(1, 37), (4, 64), (16, 20), (8, 130)])
+def test_lloyd_step_matches_the_oracle(S, C):
+    _check_lloyd_step(B=2, Hkv=2, G=2, n_pre=700, S=S, C=C, seed=S)
+
+
+def test_lloyd_step_on_random_shapes():
+    """Pools of 1 to 24000 points and 1 to 1030 centroids around every tile edge of the assignment
+    kernel (32-point and 32-centroid MFMA tiles, 128 points per workgroup), all sub-space widths,
+    more centroids than points."""
+    rng = random.Random(5)
+    for ci in range(24):
+        S = rng.choice([1, 2, 4, 8, 16])
+        C = rng.choice([1, 2, 3, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200, 257, 600, 1030])
+        B, Hkv, G = rng.choice([1, 2]), rng.choice([1, 2]), rng.choice([1, 2, 3, 8])
+        n_pre = rng.choice([1, 5, 31, 64, 127, 128, 129, 700, 1111, 3000])
+        print(ci, dict(S=S, C=C, B=B, Hkv=Hkv, G=G, n_pre=n_pre), flush=True)
+        _check_lloyd_step(B, Hkv, G, n_pre, S, C, seed=1000 + ci, max_diff=4)
 
 
 def test_seeds_are_data_points_drawn_by_squared_distance():
