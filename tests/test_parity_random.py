@@ -29,7 +29,8 @@ def _steps_with_random_call_forms(case, rng, steps):
 @pytest.mark.parametrize("seed", [11, 12])
 def test_random_shapes(seed):
     """Odd group sizes, one to eight subspaces, centroid counts around and below the probe count,
-    coarse grids (many equal sums), every key-range size, K from 0 to beyond the candidates."""
+    coarse grids (many equal sums), every key-range size, K from 0 to beyond the candidates; tables
+    built by the library or imported from the oracle."""
     rng = random.Random(seed)
     for ci in range(24):
         S = rng.choice([1, 1, 1, 2, 4, 8])
@@ -44,8 +45,12 @@ def test_random_shapes(seed):
         stream = rng.choice([0, 0, 5])
         case = Case(w, seed=seed * 1000 + ci, F=rng.choice([3, 8, 12]),
                     partition_keys=rng.choice([0, 1024, 2048, 4096, 8192, 16384]), stream_window=stream)
-        print(ci, w, "stream", stream, flush=True)
-        case.build_on_gpu()
+        imported = rng.random() < 0.5
+        print(ci, w, "stream", stream, "imported" if imported else "built", flush=True)
+        if imported:
+            case.import_oracle_tables()     # the oracle's tables through csa_import_tables
+        else:
+            case.build_on_gpu()
         _check_all_tables(case)
         _steps_with_random_call_forms(case, rng, 4)
         if stream:
