@@ -57,6 +57,9 @@ def main():
                     help="also run three plain 1 GiB device-to-device copies before the timed region, "
                          "so that a counter run has a kernel of known HBM traffic to scale by")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--row-gather-floor", action="store_true",
+                    help="also time csa_probe_row_gather (bare fetches of K and V rows) over the distinct "
+                         "rows the last step's attention had to read, and report it as row_gather_floor")
     ap.add_argument("--two-calls", action="store_true",
                     help="csa_decode_step then csa_append_kv instead of the one-call csa_decode_step_append")
     args = ap.parse_args()
@@ -239,12 +242,47 @@ def main():
         "roofline": roofline,
     }
 
+    if args.row_gather_floor and not w.page_size:
+        result["row_gather_floor"] = row_gather_floor(ctx, w, inp, att_us)
     if streaming:
         result["config"]["stream_window"] = args.stream_window
         binding.csa_streaming_status(ctx.ctx)
     if not args.no_cpu_baseline and not streaming:
         result["cpu_baseline"] = cpu_baseline(ctx, w, inp, args.cpu_seconds)
     print(json.dumps(result, ensure_ascii=False), flush=True)
+
+
+def row_gather_floor(ctx, w, inp, att_us, reps=20):
+    """Time of fetching, and doing nothing else with, the distinct K and V rows the attention kernel
+    of the last step had to read: per (sequence, KV head) the union of its query heads' selected
+    keys and the appended keys, in ascending order."""
+    import torch
+    from paper_2604_08584_amd import binding
+    B, Hkv, G = w.batch, w.n_kv_heads, w.group
+    n = binding.csa_context_len(ctx.ctx)[1]
+    sel = ctx.sel.view(B, Hkv, G * w.k).long()
+    need = torch.zeros(B, Hkv, w.max_ctx + 1, dtype=torch.bool, device=sel.device)
+    need.scatter_(2, torch.where(sel >= 0, sel, torch.full_like(sel, w.max_ctx)), True)
+    need = need[:, :, :w.max_ctx]
+    need[:, :, w.n_pre:n] = True
+    idx = need.reshape(-1).nonzero().squeeze(1).to(torch.int32)      # row number in [B*Hkv*max_ctx)
+    check = torch.empty((idx.numel() + 63) // 64, dtype=torch.int32, device=sel.device)
+    kc, vc = inp["k_cache"].view(-1, w.head_dim), inp["v_cache"].view(-1, w.head_dim)
+    for _ in range(3):
+        binding.csa_probe_row_gather(kc, vc, idx, check)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        binding.csa_probe_row_gather(kc, vc, idx, check)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    nbytes = idx.numel() * 2 * w.head_dim * 2
+    return {"distinct_rows": int(idx.numel()), "bytes": int(nbytes), "us": round(us, 2),
+            "gbps": round(nbytes / (us * 1e-6) / 1e9, 1), "attention_split_us": round(att_us, 2),
+            "floor_over_attention": round(us / att_us, 4),
+            "what": "csa_probe_row_gather over the union of the selected and appended rows per KV head "
+                    "(last step), K and V, HIP events"}
 
 
 def cluster_bench(args, w):

@@ -710,6 +710,15 @@ int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream)
     return e == hipSuccess ? CSA_OK : hip_fail(const_cast<csa_ctx *>(ctx), e);
 }
 
+int csa_probe_row_gather(const void *k_rows_dev, const void *v_rows_dev, int64_t n_rows,
+                         const int32_t *idx_dev, int64_t n_idx, uint32_t *check_dev, void *stream)
+{
+    if (!k_rows_dev || !v_rows_dev || !idx_dev || !check_dev) return CSA_ERR_ARG;
+    if (n_rows <= 0 || n_idx < 0 || n_idx > ((int64_t)1 << 40)) return CSA_ERR_ARG;
+    csa::launch_probe_row_gather(k_rows_dev, v_rows_dev, n_rows, idx_dev, n_idx, check_dev, (hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? CSA_OK : CSA_ERR_HIP;
+}
+
 int csa_profile_enable(csa_ctx *ctx, int32_t on)
 {
     if (!ctx) return CSA_ERR_ARG;

@@ -85,4 +85,8 @@ void launch_attention_merge_append(const float *part, float *out, int n_heads, i
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
                    int B, int Hkv, int n, int max_ctx, hipStream_t st);
 
+// measurement aid: reads row idx[i] (256 bytes) of both buffers, one XOR word per 64 indices
+void launch_probe_row_gather(const void *k_rows, const void *v_rows, int64_t n_rows, const int32_t *idx,
+                             int64_t n_idx, uint32_t *check, hipStream_t st);
+
 }  // namespace csa
