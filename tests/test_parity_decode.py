@@ -534,3 +534,31 @@ def test_row_gather_probe_reads_the_rows_it_is_given():
     assert got[n_grp] == 0x5A5A5A5A                           # nothing past the last group is written
     with pytest.raises(binding.CsaError):
         binding._check(binding.lib().csa_probe_row_gather(None, None, 1, None, 0, None, None), "probe")
+
+
+def test_two_contexts_interleaved_on_two_streams():
+    """Two contexts of different shapes take turns, each on a stream of its own: nothing in the
+    library is shared between contexts, so every step still matches the oracle."""
+    wa = small("ctx_a", n_q_heads=8, n_kv_heads=2, n_pre=9000, C=64, L=300, m=4, k=500, steps=4)
+    wb = small("ctx_b", batch=2, n_q_heads=6, n_kv_heads=2, n_pre=2000, C=32, L=64, m=2, k=40, steps=4,
+               n_sub=4, page_size=16)
+    a = Case(wa, seed=1, F=12, partition_keys=1024)
+    b = Case(wb, seed=2, F=10, stream_window=3)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    with torch.cuda.stream(sa):
+        a.build_on_gpu()
+    with torch.cuda.stream(sb):
+        b.build_on_gpu()
+    for step in range(4):
+        with torch.cuda.stream(sa):
+            a.check_step(step, fused_append=(step % 2 == 0))
+            if step % 2:
+                a.append(1)
+        with torch.cuda.stream(sb):
+            b.check_step(step, fused_append=(step % 2 == 1))
+            if step % 2 == 0:
+                b.append(1)
+    with torch.cuda.stream(sb):
+        for g in range(2):
+            b.check_tables(0, g)
+            b.check_tables(1, g)
