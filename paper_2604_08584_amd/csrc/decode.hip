@@ -329,8 +329,9 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
             }
         }
     };
-    if (C <= kTopNT) {
-        // ---- few centroids: one value per thread, rank = number of values that beat it
+    if (C <= kTopNT && C <= 256) {
+        // ---- few centroids: one value per thread, rank = number of values that beat it (quadratic
+        // work: not for the 1024 values a wide workgroup could hold this way)
         const uint64_t mine = (int)threadIdx.x < C ? (((uint64_t)kreg[0] << 32) | (uint32_t)~threadIdx.x) : 0ull;
         s_ck[threadIdx.x] = mine;  // (key << 32) | ~j: larger = better, distinct; 0 beats nothing
         __syncthreads();
