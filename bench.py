@@ -242,8 +242,8 @@ def main():
         "roofline": roofline,
     }
 
-    if args.row_gather_floor and not w.page_size:
-        result["row_gather_floor"] = row_gather_floor(ctx, w, inp, att_us)
+    if args.row_gather_floor:
+        result["row_gather_floor"] = row_gather_floor(ctx, w, k_store, v_store, bt, att_us)
     if streaming:
         result["config"]["stream_window"] = args.stream_window
         binding.csa_streaming_status(ctx.ctx)
@@ -252,7 +252,7 @@ def main():
     print(json.dumps(result, ensure_ascii=False), flush=True)
 
 
-def row_gather_floor(ctx, w, inp, att_us, reps=20):
+def row_gather_floor(ctx, w, k_store, v_store, bt, att_us, reps=20):
     """Time of fetching, and doing nothing else with, the distinct K and V rows the attention kernel
     of the last step had to read: per (sequence, KV head) the union of its query heads' selected
     keys and the appended keys, in ascending order."""
@@ -265,9 +265,14 @@ def row_gather_floor(ctx, w, inp, att_us, reps=20):
     need.scatter_(2, torch.where(sel >= 0, sel, torch.full_like(sel, w.max_ctx)), True)
     need = need[:, :, :w.max_ctx]
     need[:, :, w.n_pre:n] = True
-    idx = need.reshape(-1).nonzero().squeeze(1).to(torch.int32)      # row number in [B*Hkv*max_ctx)
+    idx = need.reshape(-1).nonzero().squeeze(1)                      # row number in [B*Hkv*max_ctx)
+    if bt is not None:      # paged pools [n_pages][Hkv][page][128]: the row a (b, g, key) triple lives in
+        key, bg = idx % w.max_ctx, idx // w.max_ctx
+        page = bt.view(B, -1).long()[bg // Hkv, key // w.page_size]
+        idx = (page * Hkv + bg % Hkv) * w.page_size + key % w.page_size
+    idx = idx.to(torch.int32)
     check = torch.empty((idx.numel() + 63) // 64, dtype=torch.int32, device=sel.device)
-    kc, vc = inp["k_cache"].view(-1, w.head_dim), inp["v_cache"].view(-1, w.head_dim)
+    kc, vc = k_store.view(-1, w.head_dim), v_store.view(-1, w.head_dim)
     for _ in range(3):
         binding.csa_probe_row_gather(kc, vc, idx, check)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
