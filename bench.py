@@ -335,7 +335,7 @@ def cluster_bench(args, w):
                    "C": C, "iters": iters, "points_per_problem": n_pool},
         "seeding_s": round(t_seed, 4), "lloyd_s": round(t_lloyd, 4),
         "mean_cos_first_last": [round(float(mc[0]), 4), round(float(mc[-1]), 4)],
-        "roofline": {"kernel": "k_km_assign (+ k_km_finish)", "bound": "mfma",
+        "roofline": {"kernel": "k_km_assign (+ member sums, k_km_finish)", "bound": "mfma",
                      "achieved": round(flops / t_lloyd / 1e12, 2), "peak": peak, "unit": "TFLOP/s",
                      "frac": round(flops / t_lloyd / 1e12 / peak, 4), "traffic": None,
                      "measured": "wall clock over all Lloyd steps of all problems, synchronised"},

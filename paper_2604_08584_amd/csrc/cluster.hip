@@ -194,76 +194,125 @@ __global__ __launch_bounds__(1024) void k_km_seed_pick(const float *__restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// Lloyd step, first half: cosine assignment and accumulation.  A workgroup takes 128 points, a
-// wave 32 of them; the centroids pass through LDS 32 at a time and each tile is one 32x32 block
-// of inner products on the matrix cores (centroids as rows, points as columns, so a lane ends up
-// with 16 centroid scores of ONE point and keeps a running arg-max in registers; the two lanes
-// that share a point are merged at the end).  Ties go to the lower centroid.  Positive scaling of
-// a point does not change its arg-max, so the raw bf16 sub-vector is the B operand and the
-// normalisation only enters the sums.  Each point then adds its normalised sub-vector to the sum
-// of its centroid (fp32 atomics: the order of these additions is not fixed).  When all C * d_b sums
-// fit in LDS (few, short centroids: the paper's default geometry) the workgroup adds there first and
-// flushes once - otherwise a few thousand addresses would take millions of global atomics.
+// Lloyd step, first half: cosine assignment.  A workgroup takes 128 points, a wave 32 of them,
+// held as the B operand for the whole kernel; the centroids pass through LDS 64 at a time (two
+// buffers: the next tile is fetched while this one is used, one barrier per tile) and each 32 of
+// them are one 32x32 block of inner products on the matrix cores (32x32x16 bf16: centroids as
+// rows, points as columns, so a lane ends up with 16 centroid scores of ONE point and keeps a
+// running arg-max in registers; the two lanes that share a point are merged at the end).  The
+// arg-max first takes the block's maximum per lane and walks the 16 scores only when some lane's
+// maximum beats its best so far - rare once a few tiles are done.  Ties go to the lower centroid.
+// Positive scaling of a point does not change its arg-max, so the raw bf16 sub-vector is the B
+// operand and the normalisation only enters the sums.
+// What follows the assignment depends on the size of the sums.  When all C * d_b of them fit in
+// LDS (few, short centroids: the paper's default geometry) every point adds its normalised
+// sub-vector to its centroid's sum there and the workgroup flushes once (fp32 atomics: the order
+// of these additions is not fixed).  Otherwise the kernel only records the assignment and counts
+// the members; the sums are then taken per centroid over its member list (k_km_offsets,
+// k_km_scatter, k_km_sum below) - adding 128 values per point with global atomics took three
+// times as long as the matrix products.
 // grid ceil(n_pool / 128), block 256, dynamic LDS lds_sums ? (C * DB + C) * 4 : 0 bytes.
 // ---------------------------------------------------------------------------------------------
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+union Frag8 {  // eight bf16 values: as loaded (16 bytes) and as a matrix operand
+    uint4 u;
+    v8bf v;
+};
+constexpr int kKmTile = 64;  // centroids per LDS buffer
+
 template <int DB>
 __global__ __launch_bounds__(256) void k_km_assign(Pool pool, const float *__restrict__ inv_norm,
                                                    const uint16_t *__restrict__ cent16, int C,
                                                    float *__restrict__ sums, int32_t *__restrict__ counts,
                                                    float *__restrict__ cos_sum,
-                                                   int32_t *__restrict__ assign_out, int lds_sums)
+                                                   int32_t *__restrict__ assign_out,
+                                                   int32_t *__restrict__ assign_work, int lds_sums)
 {
-    extern __shared__ float s_sum[];    // [C * DB] sums, then [C] counts (as floats), if lds_sums
-    constexpr int NK = DB / 8;          // matrix instructions per tile
-    constexpr int STRIDE = DB + 4;      // LDS row stride in elements (keeps 8-byte reads conflict-poor)
-    __shared__ __align__(16) uint16_t s_c[32 * STRIDE];
+    extern __shared__ float s_sum[];             // [C * DB] sums, then [C] counts (as floats), if lds_sums
+    constexpr int NK = (DB + 15) / 16;           // matrix instructions per 32-centroid block
+    constexpr int STRIDE = DB + 8;               // LDS row stride in elements (16-byte reads without conflicts)
+    constexpr int CH = DB / 8;                   // 16-byte chunks of a centroid
+    constexpr int PER = (kKmTile * CH + 255) / 256;  // chunks of a tile per thread
+    __shared__ __align__(16) uint16_t s_c[2][kKmTile * STRIDE];
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int col = lane & 31, half = lane >> 5;
     const int pt = blockIdx.x * 128 + wave * 32 + col;
     const bool live = pt < pool.n_pool;
-    // B operand: this lane's point, elements 8*kk + 4*half + (0..3)
-    v4s bq[NK];
+    // operand element k of instruction kk is dimension 16 * kk + k; a lane holds k = 8 * half .. + 7
+    // (zeros past d_b: only for 8-dimensional sub-vectors)
+    Frag8 bq[NK];
     {
         const uint16_t *r = pool.row(live ? pt : 0);
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) {
-            const uint2 w = *(const uint2 *)(r + 8 * kk + 4 * half);
-            bq[kk] = live ? v4s{(short)(w.x & 0xFFFF), (short)(w.x >> 16), (short)(w.y & 0xFFFF), (short)(w.y >> 16)}
-                          : v4s{0, 0, 0, 0};
+            const int e0 = 16 * kk + 8 * half;
+            bq[kk].u = make_uint4(0, 0, 0, 0);
+            if (live && e0 < DB) bq[kk].u = *(const uint4 *)(r + e0);
         }
     }
     if (lds_sums)
         for (int e = threadIdx.x; e < C * DB + C; e += 256) s_sum[e] = 0.0f;
+    uint4 pre[PER];
+    auto fetch = [&](int t0) {  // this thread's chunks of the tile that starts at centroid t0 (zeros past C)
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = u * 256 + (int)threadIdx.x, i = e / CH, c = e % CH;
+            pre[u] = make_uint4(0, 0, 0, 0);
+            if (e < kKmTile * CH && t0 + i < C) pre[u] = *(const uint4 *)(cent16 + (size_t)(t0 + i) * DB + c * 8);
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = u * 256 + (int)threadIdx.x, i = e / CH, c = e % CH;
+            if (e < kKmTile * CH) *(uint4 *)(s_c[buf] + i * STRIDE + c * 8) = pre[u];
+        }
+    };
+    fetch(0);
+    stash(0);
+    __syncthreads();
     float best = -INFINITY;
     int best_j = 0;
-    for (int t0 = 0; t0 < C; t0 += 32) {
-        __syncthreads();
-        for (int e = threadIdx.x; e < 32 * NK; e += 256) {  // 16-byte chunks of the tile
-            const int i = e / NK, c = e % NK;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (t0 + i < C) v = *(const uint4 *)(cent16 + (size_t)(t0 + i) * DB + c * 8);
-            *(uint2 *)(s_c + i * STRIDE + c * 8) = make_uint2(v.x, v.y);
-            *(uint2 *)(s_c + i * STRIDE + c * 8 + 4) = make_uint2(v.z, v.w);
-        }
-        __syncthreads();
-        v16f acc;
+    int buf = 0;
+    for (int t0 = 0; t0 < C; t0 += kKmTile, buf ^= 1) {
+        const bool more = t0 + kKmTile < C;
+        if (more) fetch(t0 + kKmTile);
+        v16f acc[2];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rt][r] = 0.0f;
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) {
-            const uint2 w = *(const uint2 *)(s_c + col * STRIDE + 8 * kk + 4 * half);
-            const v4s a = {(short)(w.x & 0xFFFF), (short)(w.x >> 16), (short)(w.y & 0xFFFF), (short)(w.y >> 16)};
-            acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, bq[kk], acc, 0, 0, 0);
-        }
-        // register r of this lane: centroid row (r % 4) + 8 * (r / 4) + 4 * half, column = its point
+            const int e0 = 16 * kk + 8 * half;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int j = t0 + (r & 3) + 8 * (r >> 2) + 4 * half;
-            if (j < C && acc[r] > best) {
-                best = acc[r];
-                best_j = j;
+            for (int rt = 0; rt < 2; ++rt) {  // (two independent accumulation chains)
+                Frag8 a;
+                a.u = make_uint4(0, 0, 0, 0);
+                if (e0 < DB) a.u = *(const uint4 *)(s_c[buf] + (rt * 32 + col) * STRIDE + e0);
+                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bq[kk].v, acc[rt], 0, 0, 0);
             }
         }
+        // register r of this lane: centroid row (r % 4) + 8 * (r / 4) + 4 * half of the block,
+        // column = its point
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            float tm = acc[rt][0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) tm = fmaxf(tm, acc[rt][r]);
+            if (__any(tm > best)) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int j = t0 + rt * 32 + (r & 3) + 8 * (r >> 2) + 4 * half;
+                    if (j < C && acc[rt][r] > best) {
+                        best = acc[rt][r];
+                        best_j = j;
+                    }
+                }
+            }
+        }
+        if (more) stash(buf ^ 1);
+        __syncthreads();
     }
     {
         const float ob = __shfl_xor(best, 32, kWave);
@@ -275,17 +324,27 @@ __global__ __launch_bounds__(256) void k_km_assign(Pool pool, const float *__res
     }
     const float inv = live ? inv_norm[pt] : 0.0f;
     if (live) {
-        float *dst = (lds_sums ? s_sum : sums) + (size_t)best_j * DB;
+        if (lds_sums) {
+            float *dst = s_sum + (size_t)best_j * DB;
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk)
+            for (int kk = 0; kk < NK; ++kk) {
+                const int e0 = 16 * kk + 8 * half;
+                if (e0 < DB) {
+                    const uint32_t w[4] = {bq[kk].u.x, bq[kk].u.y, bq[kk].u.z, bq[kk].u.w};
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const float v = __uint_as_float((uint32_t)(uint16_t)bq[kk][x] << 16) * inv;
-                atomicAdd(dst + 8 * kk + 4 * half + x, v);
+                    for (int x = 0; x < 4; ++x) {
+                        atomicAdd(dst + e0 + 2 * x, bf16_lo(w[x]) * inv);
+                        atomicAdd(dst + e0 + 2 * x + 1, bf16_hi(w[x]) * inv);
+                    }
+                }
             }
+        }
         if (half == 0) {
             if (lds_sums) atomicAdd(s_sum + C * DB + best_j, 1.0f);
-            else atomicAdd(counts + best_j, 1);
+            else {
+                atomicAdd(counts + best_j, 1);
+                assign_work[pt] = best_j;
+            }
             if (assign_out) assign_out[pt] = best_j;
         }
     }
@@ -303,6 +362,87 @@ __global__ __launch_bounds__(256) void k_km_assign(Pool pool, const float *__res
     float cs = (live && half == 0) ? best * inv : 0.0f;
     for (int o = 32; o > 0; o >>= 1) cs += __shfl_xor(cs, o, kWave);
     if (lane == 0) atomicAdd(cos_sum, cs);
+}
+
+// Member lists for the sums of a Lloyd step with many or long centroids.
+// k_km_offsets: exclusive scan of the member counts -> where each centroid's list starts (kept as
+// the running write position of the scatter, and a second copy as the start).  One workgroup.
+__global__ __launch_bounds__(1024) void k_km_offsets(const int32_t *__restrict__ counts, int C,
+                                                     int32_t *__restrict__ start, int32_t *__restrict__ cursor)
+{
+    __shared__ int s_w[1024 / kWave + 1];
+    __shared__ int s_carry;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int j0 = 0; j0 < C; j0 += 1024) {
+        const int j = j0 + threadIdx.x;
+        const int v = j < C ? counts[j] : 0;
+        int incl = v;
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int t = __shfl_up(incl, o, kWave);
+            if (lane_id() >= o) incl += t;
+        }
+        if (lane_id() == kWave - 1) s_w[threadIdx.x / kWave] = incl;
+        __syncthreads();
+        int before = s_carry;
+        for (int w = 0; w < (int)threadIdx.x / kWave; ++w) before += s_w[w];
+        if (j < C) {
+            start[j] = before + incl - v;
+            cursor[j] = before + incl - v;
+        }
+        __syncthreads();
+        if (threadIdx.x == 1023) s_carry = before + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) start[C] = s_carry;
+}
+
+// k_km_scatter: point i goes to the next free place of its centroid's list.  grid ceil(n / 256).
+__global__ void k_km_scatter(const int32_t *__restrict__ assign, int n_pool, int32_t *__restrict__ cursor,
+                             int32_t *__restrict__ member)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_pool) return;
+    member[atomicAdd(cursor + assign[i], 1)] = i;
+}
+
+// k_km_sum: sums[j][:] = sum over the members i of centroid j of x_i / ||x_i||, one wave per
+// centroid; a group of DB/8 lanes reads one member's sub-vector (16 bytes per lane), the groups of
+// the wave take members in turn and are folded at the end.  No atomics.  grid ceil(C / 4), block 256.
+template <int DB>
+__global__ __launch_bounds__(256) void k_km_sum(Pool pool, const float *__restrict__ inv_norm,
+                                                const int32_t *__restrict__ start,
+                                                const int32_t *__restrict__ member, int C,
+                                                float *__restrict__ sums)
+{
+    constexpr int LPR = DB / 8;        // lanes per member row
+    constexpr int GROUPS = kWave / LPR;  // members in flight per wave
+    const int j = blockIdx.x * 4 + threadIdx.x / kWave;
+    if (j >= C) return;  // (whole waves)
+    const int lane = lane_id(), grp = lane / LPR, c = lane % LPR;
+    const int m0 = start[j], m1 = start[j + 1];
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    for (int m = m0 + grp; m < m1; m += GROUPS) {
+        const int i = member[m];
+        const float inv = inv_norm[i];
+        const uint4 w = *(const uint4 *)(pool.row(i) + c * 8);
+        acc[0] = fmaf(bf16_lo(w.x), inv, acc[0]); acc[1] = fmaf(bf16_hi(w.x), inv, acc[1]);
+        acc[2] = fmaf(bf16_lo(w.y), inv, acc[2]); acc[3] = fmaf(bf16_hi(w.y), inv, acc[3]);
+        acc[4] = fmaf(bf16_lo(w.z), inv, acc[4]); acc[5] = fmaf(bf16_hi(w.z), inv, acc[5]);
+        acc[6] = fmaf(bf16_lo(w.w), inv, acc[6]); acc[7] = fmaf(bf16_hi(w.w), inv, acc[7]);
+    }
+    // fold the groups: lanes c, c + LPR, c + 2 LPR, ...
+#pragma unroll
+    for (int o = LPR; o < kWave; o <<= 1)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
+    if (grp == 0) {
+        float4 *dst = (float4 *)(sums + (size_t)j * DB + c * 8);
+        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
 }
 
 // Lloyd step, second half: centroid <- its sum re-normalised and rounded to bf16 (an empty cluster
@@ -352,7 +492,8 @@ size_t cluster_work_bytes(int n_pool, int C, int db)
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     const size_t n_blk = ((size_t)n_pool + kSeedPts - 1) / kSeedPts;
     return up((size_t)n_pool * 4) * 2 + up(n_blk * 4) + up((size_t)C * db * 4) + up((size_t)C * 4) +
-           up((size_t)C * db * 2) + 512;
+           up((size_t)C * db * 2) + 512 +
+           up((size_t)n_pool * 4) + 2 * up(((size_t)C + 1) * 4);  // assignments, list starts, write positions
 }
 
 template <int DB>
@@ -371,6 +512,11 @@ static hipError_t cluster_one(const uint16_t *q_group, int n_pre, int n_pool, in
     char *scal = (char *)cent16 + up((size_t)C * DB * 2);
     int32_t *pick_dev = (int32_t *)scal;
     float *cos_sum = (float *)(scal + 256);
+    // member lists of the Lloyd steps (the seeding's distance array is free by then and holds them)
+    int32_t *assign_work = (int32_t *)(scal + 512);
+    int32_t *start = (int32_t *)((char *)assign_work + up((size_t)n_pool * 4));
+    int32_t *cursor = (int32_t *)((char *)start + up(((size_t)C + 1) * 4));
+    int32_t *member = (int32_t *)dist;
     Pool pool{q_group, n_pre, n_pool, sub * DB};
     hipError_t e = hipMemsetAsync(sums, 0, (size_t)((char *)cent16 - (char *)sums), st);  // sums + counts
     if (e != hipSuccess) return e;
@@ -395,7 +541,12 @@ static hipError_t cluster_one(const uint16_t *q_group, int n_pre, int n_pool, in
     for (int it = 0; it < iters; ++it) {
         k_km_assign<DB><<<(n_pool + 127) / 128, 256, lds_bytes, st>>>(pool, inv_norm, cent16, C, sums, counts,
                                                                       cos_sum, it + 1 == iters ? assign_out : nullptr,
-                                                                      lds_sums);
+                                                                      assign_work, lds_sums);
+        if (!lds_sums) {
+            k_km_offsets<<<1, 1024, 0, st>>>(counts, C, start, cursor);
+            k_km_scatter<<<(n_pool + 255) / 256, 256, 0, st>>>(assign_work, n_pool, cursor, member);
+            k_km_sum<DB><<<(C + 3) / 4, 256, 0, st>>>(pool, inv_norm, start, member, C, sums);
+        }
         k_km_finish<DB><<<(C + 3) / 4, 256, 0, st>>>(sums, counts, cent16, C, cos_sum,
                                                      mean_cos_out ? mean_cos_out + it : nullptr, n_pool);
     }
