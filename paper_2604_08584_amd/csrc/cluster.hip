@@ -68,6 +68,9 @@ __global__ __launch_bounds__(256) void k_km_seed_update(Pool pool, const float *
     __shared__ float s_c[DB];
     __shared__ float s_red[4];
     __shared__ float s_cn2;
+    // odd rounds walk the points from the far end: what the previous round read last is what this
+    // one reads first, while it is still in the memory-side cache
+    const int blk = (j & 1) ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
     int pick = pick_host >= 0 ? pick_host : *pick_dev;
     pick = min(max(pick, 0), pool.n_pool - 1);
     if (threadIdx.x < DB) {
@@ -87,7 +90,7 @@ __global__ __launch_bounds__(256) void k_km_seed_update(Pool pool, const float *
     float local = 0.0f;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        const int i = blockIdx.x * kSeedPts + u * 256 + threadIdx.x;
+        const int i = blk * kSeedPts + u * 256 + threadIdx.x;
         if (i < pool.n_pool) {
             const uint4 *r = (const uint4 *)pool.row(i);
             float dot = 0.0f;
@@ -114,7 +117,7 @@ __global__ __launch_bounds__(256) void k_km_seed_update(Pool pool, const float *
     local = __shfl_xor(local, 32, kWave) + local;
     if (lane_id() == 0) s_red[threadIdx.x / kWave] = local;
     __syncthreads();
-    if (threadIdx.x == 0) part[blockIdx.x] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    if (threadIdx.x == 0) part[blk] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
 }
 
 // The draw: the first point whose running sum of distances exceeds u * total (the last point if
