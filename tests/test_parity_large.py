@@ -46,9 +46,10 @@ def test_cfg2_full_size_with_appends():
     case.build_on_gpu()
     _check_rows(case, 0, 5, [7, 2047])
     heads = [(0, h) for h in (0, 3, 20, 21, 22, 23)]
-    for step in range(3):
-        print("cfg2 step", step, "err", case.check_step(step, heads))
-        case.append(1)
+    for step in range(3):       # the one-call iteration bench.py times, and the two-call form
+        print("cfg2 step", step, "err", case.check_step(step, heads, fused_append=(step != 1)))
+        if step == 1:
+            case.append(1)
 
 
 def test_cfg3_paged_batch():
@@ -69,9 +70,8 @@ def test_cfg4_70b_shape():
     case.build_on_gpu()
     _check_rows(case, 7, 7, [4095])
     heads = [(0, 0), (0, 7), (3, 40), (7, 56), (7, 63)]
-    for step in range(2):
-        print("cfg4 step", step, "err", case.check_step(step, heads))
-        case.append(1)
+    for step in range(2):       # the one-call iteration (step, then append) that bench.py times
+        print("cfg4 step", step, "err", case.check_step(step, heads, fused_append=True))
 
 
 def test_paper_default_geometry_full_size():
