@@ -562,3 +562,36 @@ def test_two_contexts_interleaved_on_two_streams():
         for g in range(2):
             b.check_tables(0, g)
             b.check_tables(1, g)
+
+
+@pytest.mark.parametrize("stream", [0, 4])
+def test_a_context_is_reused_for_new_sequences(stream):
+    """A serving loop keeps one context and its buffers: after some steps on one sequence the caller
+    overwrites the K/V cache with the prefill of another (shorter, then longer) and calls
+    csa_build_tables again with new centroids.  Nothing of the earlier sequence may survive: tables,
+    context length, key ranges and the score grid all follow the new build."""
+    shape = dict(n_q_heads=8, n_kv_heads=2, C=48, L=200, m=3, k=150, steps=6)
+    first = Case(small("seq0", n_pre=9000, **shape), seed=1, F=-1, stream_window=stream)
+    first.build_on_gpu()
+    first.check_step(0, fused_append=True)
+    first.check_step(1, fused_append=True)
+    shared = first.ctx
+    for i, n_pre in enumerate((2500, 8800)):
+        nxt = Case(small(f"seq{i + 1}", n_pre=n_pre, **shape), seed=10 + i, F=-1, stream_window=stream)
+        nxt.ctx.close()
+        nxt.ctx = shared                                    # the first sequence's context and buffers
+        n_rows = nxt.w.max_ctx
+        first.inp["k_cache"][:, :, :n_rows] = nxt.inp["k_cache"]
+        first.inp["v_cache"][:, :, :n_rows] = nxt.inp["v_cache"]
+        nxt.build_on_gpu()
+        assert binding.csa_context_len(shared.ctx) == (n_pre, n_pre)
+        for g in range(2):
+            nxt.check_tables(0, g)
+        for step in range(3):
+            nxt.check_step(step, fused_append=(step != 1))
+            if step == 1:
+                nxt.append(1)
+        if stream:
+            for g in range(2):
+                nxt.check_tables(0, g)
+        nxt.ctx = None                                      # (the context belongs to `first`)
