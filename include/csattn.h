@@ -113,7 +113,9 @@ int csa_bind(csa_ctx *ctx, void *tables_dev, size_t tables_bytes, void *scratch_
  * fused-multiply-add chain over the subspace's dimensions in ascending order starting from +0,
  * bf16 inputs widened.
  *   centroids_dev: bf16 [B][Hkv][S][C][d/S], unit norm (Sec. 3.2 (1); clustering is the caller's).
- * K is read from the bound cache, rows [0, n_pre).  Sets the context length to n_pre.
+ * K is read from the bound cache, rows [0, n_pre), 1 <= n_pre <= max_ctx (CSA_ERR_ARG otherwise).
+ * Sets the context length to n_pre.  May be called again on the same context (a new sequence in
+ * the same buffers): tables, context length, key ranges and an automatic score grid start over.
  * SYNCHRONISES `stream` before returning (it reads back an overflow flag); returns
  * CSA_ERR_RANGE if some |q| * M >= 2^24 or |q| >= 2^18 (tables are then unusable).
  */
