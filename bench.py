@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the CSAttention decode step on one MI355X.
 
-A "step" is one pass of the whole hot path through the C-ABI library - csa_decode_step
-(centroid scoring, row gather + score accumulation, Top-K, gathered attention) followed by
-csa_append_kv - over one batch of synthetic input that is already resident in HBM.  Every step
+A "step" is one pass of the whole hot path through the C-ABI library - the decode step (centroid
+scoring, row gather + score accumulation, Top-K, gathered attention) followed by the append of the
+next K/V row, as the one call csa_decode_step_append (or, with --two-calls, csa_decode_step then
+csa_append_kv) - over one batch of synthetic input that is already resident in HBM.  Every step
 uses a fresh query, so the 256 MiB last-level cache cannot replay the previous step.
 
 Prints ONE JSON line.  One GPU only.
