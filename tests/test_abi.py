@@ -83,3 +83,25 @@ def test_calls_out_of_order_are_refused_on_the_host():
     binding.csa_destroy(ctx)
     assert lib.csa_strerror(binding.CSA_ERR_RANGE).decode().startswith("table score")
     assert lib.csa_stage_name(0).decode() == "score_centroids" and lib.csa_stage_name(99) is None
+
+
+def test_product_and_oracle_do_not_reach_into_each_other():
+    """The library, its binding and the input generator never import, load or call the oracle, and
+    the oracle never imports the package: parity compares two independent implementations, and a
+    missing HIP library cannot be papered over by the CPU code."""
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2604_08584_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp", ".c")):
+                text = open(os.path.join(dirpath, f), errors="replace").read()
+                assert not re.search(r"import\s+oracle|from\s+oracle|oracle\.|oracle/|csa_oracle", text), \
+                    f"{f} reaches into the oracle"
+    for f in os.listdir(os.path.join(root, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(root, "oracle", f), errors="replace").read()
+            assert "paper_2604_08584_amd" not in text and "csattn" not in text, f"oracle/{f} names the product"
+    # the binding refuses to work without the built library instead of falling back
+    src = open(os.path.join(pkg, "binding.py")).read()
+    assert "raise" in src[src.index("def lib("):src.index("def lib(") + 1500]
