@@ -63,14 +63,14 @@ __global__ __launch_bounds__(256) void k_km_seed_update(Pool pool, const float *
                                                         float *__restrict__ part,
                                                         uint16_t *__restrict__ cent16,
                                                         const int32_t *__restrict__ pick_dev,
-                                                        int pick_host, int j)
+                                                        int pick_host, int j, int snake)
 {
     __shared__ float s_c[DB];
     __shared__ float s_red[4];
     __shared__ float s_cn2;
-    // odd rounds walk the points from the far end: what the previous round read last is what this
-    // one reads first, while it is still in the memory-side cache
-    const int blk = (j & 1) ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+    // snake (pools too large for the last-level cache): odd rounds walk the points from the far end -
+    // what the previous round read last is what this one reads first, while it is still cached
+    const int blk = (snake && (j & 1)) ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
     int pick = pick_host >= 0 ? pick_host : *pick_dev;
     pick = min(max(pick, 0), pool.n_pool - 1);
     if (threadIdx.x < DB) {
@@ -197,8 +197,9 @@ __global__ __launch_bounds__(1024) void k_km_seed_pick(const float *__restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// Lloyd step, first half: cosine assignment.  A workgroup takes 128 points, a wave 32 of them,
-// held as the B operand for the whole kernel; the centroids pass through LDS 64 at a time (two
+// Lloyd step, first half: cosine assignment.  A workgroup takes 128 or 256 points, a wave one or
+// two blocks of 32 of them, held as the B operands for the whole kernel (with two blocks every A
+// operand read from LDS feeds two matrix instructions); the centroids pass through LDS 64 at a time (two
 // buffers: the next tile is fetched while this one is used, one barrier per tile) and each 32 of
 // them are one 32x32 block of inner products on the matrix cores (32x32x16 bf16: centroids as
 // rows, points as columns, so a lane ends up with 16 centroid scores of ONE point and keeps a
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(1024) void k_km_seed_pick(const float *__restrict__
 // the members; the sums are then taken per centroid over its member list (k_km_offsets,
 // k_km_scatter, k_km_sum below) - adding 128 values per point with global atomics took three
 // times as long as the matrix products.
-// grid ceil(n_pool / 128), block 256, dynamic LDS lds_sums ? (C * DB + C) * 4 : 0 bytes.
+// grid ceil(n_pool / (128 or 256)), block 256, dynamic LDS lds_sums ? (C * DB + C) * 4 : 0 bytes.
 // ---------------------------------------------------------------------------------------------
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 union Frag8 {  // eight bf16 values: as loaded (16 bytes) and as a matrix operand
@@ -222,6 +223,12 @@ union Frag8 {  // eight bf16 values: as loaded (16 bytes) and as a matrix operan
     v8bf v;
 };
 constexpr int kKmTile = 64;  // centroids per LDS buffer
+
+// blocks of 32 points per wave (one A read serves as many products): two for short sub-vectors, where
+// the sums go through LDS and half as many workgroups flush them; one for long ones, where the
+// registers of a second block cost more occupancy than the saved LDS reads bring
+template <int DB>
+constexpr int km_cols() { return DB <= 32 ? 2 : 1; }
 
 template <int DB>
 __global__ __launch_bounds__(256) void k_km_assign(Pool pool, const float *__restrict__ inv_norm,
@@ -232,25 +239,30 @@ __global__ __launch_bounds__(256) void k_km_assign(Pool pool, const float *__res
                                                    int32_t *__restrict__ assign_work, int lds_sums)
 {
     extern __shared__ float s_sum[];             // [C * DB] sums, then [C] counts (as floats), if lds_sums
-    constexpr int NK = (DB + 15) / 16;           // matrix instructions per 32-centroid block
+    constexpr int NK = (DB + 15) / 16;           // matrix instructions per 32x32 block
     constexpr int STRIDE = DB + 8;               // LDS row stride in elements (16-byte reads without conflicts)
     constexpr int CH = DB / 8;                   // 16-byte chunks of a centroid
     constexpr int PER = (kKmTile * CH + 255) / 256;  // chunks of a tile per thread
+    constexpr int CB = km_cols<DB>();
+    constexpr int kKmPts = 4 * 32 * CB;          // points per workgroup
     __shared__ __align__(16) uint16_t s_c[2][kKmTile * STRIDE];
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int col = lane & 31, half = lane >> 5;
-    const int pt = blockIdx.x * 128 + wave * 32 + col;
-    const bool live = pt < pool.n_pool;
+    int pt[CB];
+    bool live[CB];
     // operand element k of instruction kk is dimension 16 * kk + k; a lane holds k = 8 * half .. + 7
     // (zeros past d_b: only for 8-dimensional sub-vectors)
-    Frag8 bq[NK];
-    {
-        const uint16_t *r = pool.row(live ? pt : 0);
+    Frag8 bq[CB][NK];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        pt[cb] = blockIdx.x * kKmPts + (wave * CB + cb) * 32 + col;
+        live[cb] = pt[cb] < pool.n_pool;
+        const uint16_t *r = pool.row(live[cb] ? pt[cb] : 0);
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) {
             const int e0 = 16 * kk + 8 * half;
-            bq[kk].u = make_uint4(0, 0, 0, 0);
-            if (live && e0 < DB) bq[kk].u = *(const uint4 *)(r + e0);
+            bq[cb][kk].u = make_uint4(0, 0, 0, 0);
+            if (live[cb] && e0 < DB) bq[cb][kk].u = *(const uint4 *)(r + e0);
         }
     }
     if (lds_sums)
@@ -274,82 +286,98 @@ __global__ __launch_bounds__(256) void k_km_assign(Pool pool, const float *__res
     fetch(0);
     stash(0);
     __syncthreads();
-    float best = -INFINITY;
-    int best_j = 0;
+    float best[CB];
+    int best_j[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        best[cb] = -INFINITY;
+        best_j[cb] = 0;
+    }
     int buf = 0;
     for (int t0 = 0; t0 < C; t0 += kKmTile, buf ^= 1) {
         const bool more = t0 + kKmTile < C;
         if (more) fetch(t0 + kKmTile);
-        v16f acc[2];
+        v16f acc[2][CB];
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[rt][r] = 0.0f;
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[rt][cb][r] = 0.0f;
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) {
             const int e0 = 16 * kk + 8 * half;
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt) {  // (two independent accumulation chains)
+            for (int rt = 0; rt < 2; ++rt) {  // (independent accumulation chains)
                 Frag8 a;
                 a.u = make_uint4(0, 0, 0, 0);
                 if (e0 < DB) a.u = *(const uint4 *)(s_c[buf] + (rt * 32 + col) * STRIDE + e0);
-                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bq[kk].v, acc[rt], 0, 0, 0);
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[rt][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bq[cb][kk].v, acc[rt][cb], 0, 0, 0);
             }
         }
         // register r of this lane: centroid row (r % 4) + 8 * (r / 4) + 4 * half of the block,
         // column = its point
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt) {
-            float tm = acc[rt][0];
+        for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-            for (int r = 1; r < 16; ++r) tm = fmaxf(tm, acc[rt][r]);
-            if (__any(tm > best)) {
+            for (int cb = 0; cb < CB; ++cb) {
+                float tm = acc[rt][cb][0];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int j = t0 + rt * 32 + (r & 3) + 8 * (r >> 2) + 4 * half;
-                    if (j < C && acc[rt][r] > best) {
-                        best = acc[rt][r];
-                        best_j = j;
+                for (int r = 1; r < 16; ++r) tm = fmaxf(tm, acc[rt][cb][r]);
+                if (__any(tm > best[cb])) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int j = t0 + rt * 32 + (r & 3) + 8 * (r >> 2) + 4 * half;
+                        if (j < C && acc[rt][cb][r] > best[cb]) {
+                            best[cb] = acc[rt][cb][r];
+                            best_j[cb] = j;
+                        }
                     }
                 }
             }
-        }
         if (more) stash(buf ^ 1);
         __syncthreads();
     }
-    {
-        const float ob = __shfl_xor(best, 32, kWave);
-        const int oj = __shfl_xor(best_j, 32, kWave);
-        if (ob > best || (ob == best && oj < best_j)) {
-            best = ob;
-            best_j = oj;
+    float cs = 0.0f;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        {
+            const float ob = __shfl_xor(best[cb], 32, kWave);
+            const int oj = __shfl_xor(best_j[cb], 32, kWave);
+            if (ob > best[cb] || (ob == best[cb] && oj < best_j[cb])) {
+                best[cb] = ob;
+                best_j[cb] = oj;
+            }
         }
-    }
-    const float inv = live ? inv_norm[pt] : 0.0f;
-    if (live) {
-        if (lds_sums) {
-            float *dst = s_sum + (size_t)best_j * DB;
+        const float inv = live[cb] ? inv_norm[pt[cb]] : 0.0f;
+        if (live[cb]) {
+            if (lds_sums) {
+                float *dst = s_sum + (size_t)best_j[cb] * DB;
 #pragma unroll
-            for (int kk = 0; kk < NK; ++kk) {
-                const int e0 = 16 * kk + 8 * half;
-                if (e0 < DB) {
-                    const uint32_t w[4] = {bq[kk].u.x, bq[kk].u.y, bq[kk].u.z, bq[kk].u.w};
+                for (int kk = 0; kk < NK; ++kk) {
+                    const int e0 = 16 * kk + 8 * half;
+                    if (e0 < DB) {
+                        const uint32_t w[4] = {bq[cb][kk].u.x, bq[cb][kk].u.y, bq[cb][kk].u.z, bq[cb][kk].u.w};
 #pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        atomicAdd(dst + e0 + 2 * x, bf16_lo(w[x]) * inv);
-                        atomicAdd(dst + e0 + 2 * x + 1, bf16_hi(w[x]) * inv);
+                        for (int x = 0; x < 4; ++x) {
+                            atomicAdd(dst + e0 + 2 * x, bf16_lo(w[x]) * inv);
+                            atomicAdd(dst + e0 + 2 * x + 1, bf16_hi(w[x]) * inv);
+                        }
                     }
                 }
             }
-        }
-        if (half == 0) {
-            if (lds_sums) atomicAdd(s_sum + C * DB + best_j, 1.0f);
-            else {
-                atomicAdd(counts + best_j, 1);
-                assign_work[pt] = best_j;
+            if (half == 0) {
+                if (lds_sums) atomicAdd(s_sum + C * DB + best_j[cb], 1.0f);
+                else {
+                    atomicAdd(counts + best_j[cb], 1);
+                    assign_work[pt[cb]] = best_j[cb];
+                }
+                if (assign_out) assign_out[pt[cb]] = best_j[cb];
             }
-            if (assign_out) assign_out[pt] = best_j;
         }
+        cs += (live[cb] && half == 0) ? best[cb] * inv : 0.0f;
     }
     if (lds_sums) {
         __syncthreads();
@@ -359,10 +387,9 @@ __global__ __launch_bounds__(256) void k_km_assign(Pool pool, const float *__res
         }
         for (int j = threadIdx.x; j < C; j += 256) {
             const float v = s_sum[C * DB + j];
-            if (v != 0.0f) atomicAdd(counts + j, (int)v);   // (<= 128 members per workgroup: exact)
+            if (v != 0.0f) atomicAdd(counts + j, (int)v);   // (<= 256 members per workgroup: exact)
         }
     }
-    float cs = (live && half == 0) ? best * inv : 0.0f;
     for (int o = 32; o > 0; o >>= 1) cs += __shfl_xor(cs, o, kWave);
     if (lane == 0) atomicAdd(cos_sum, cs);
 }
@@ -530,11 +557,12 @@ static hipError_t cluster_one(const uint16_t *q_group, int n_pre, int n_pool, in
         e = hipMemcpyAsync(cent16, init, (size_t)C * DB * 2, hipMemcpyDeviceToDevice, st);
         if (e != hipSuccess) return e;
     } else {
+        const int snake = (size_t)n_pool * DB * 2 > ((size_t)64 << 20) ? 1 : 0;
         int first = (int)((double)u_seed[0] * (double)n_pool);
         if (first >= n_pool) first = n_pool - 1;
         for (int j = 0; j < C; ++j) {
             k_km_seed_update<DB><<<n_blk, 256, 0, st>>>(pool, inv_norm, dist, part, cent16, pick_dev,
-                                                        j == 0 ? first : -1, j);
+                                                        j == 0 ? first : -1, j, snake);
             if (j + 1 < C)
                 k_km_seed_pick<<<1, 1024, 0, st>>>(dist, part, n_blk, n_pool, u_seed[j + 1], pick_dev);
         }
@@ -542,7 +570,7 @@ static hipError_t cluster_one(const uint16_t *q_group, int n_pre, int n_pool, in
     const int lds_sums = (size_t)C * DB + C <= 8192 ? 1 : 0;  // up to 32 KiB of LDS sums
     const size_t lds_bytes = lds_sums ? ((size_t)C * DB + C) * 4 : 0;
     for (int it = 0; it < iters; ++it) {
-        k_km_assign<DB><<<(n_pool + 127) / 128, 256, lds_bytes, st>>>(pool, inv_norm, cent16, C, sums, counts,
+        k_km_assign<DB><<<(n_pool + 128 * km_cols<DB>() - 1) / (128 * km_cols<DB>()), 256, lds_bytes, st>>>(pool, inv_norm, cent16, C, sums, counts,
                                                                       cos_sum, it + 1 == iters ? assign_out : nullptr,
                                                                       assign_work, lds_sums);
         if (!lds_sums) {
