@@ -59,7 +59,7 @@ def main():
                          "so that a counter run has a kernel of known HBM traffic to scale by")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--row-gather-floor", action="store_true",
-                    help="also time csa_probe_row_gather (bare fetches of K and V rows) over the distinct "
+                    help="also time bench_aids/row_gather_probe.hip (bare fetches of K and V rows) over the distinct "
                          "rows the last step's attention had to read, and report it as row_gather_floor")
     ap.add_argument("--two-calls", action="store_true",
                     help="csa_decode_step then csa_append_kv instead of the one-call csa_decode_step_append")
@@ -258,6 +258,7 @@ def row_gather_floor(ctx, w, k_store, v_store, bt, att_us, reps=20):
     of the last step had to read: per (sequence, KV head) the union of its query heads' selected
     keys and the appended keys, in ascending order."""
     import torch
+    from bench_aids import probe_row_gather
     from paper_2604_08584_amd import binding
     B, Hkv, G = w.batch, w.n_kv_heads, w.group
     n = binding.csa_context_len(ctx.ctx)[1]
@@ -275,11 +276,11 @@ def row_gather_floor(ctx, w, k_store, v_store, bt, att_us, reps=20):
     check = torch.empty((idx.numel() + 63) // 64, dtype=torch.int32, device=sel.device)
     kc, vc = k_store.view(-1, w.head_dim), v_store.view(-1, w.head_dim)
     for _ in range(3):
-        binding.csa_probe_row_gather(kc, vc, idx, check)
+        probe_row_gather(kc, vc, idx, check)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
-        binding.csa_probe_row_gather(kc, vc, idx, check)
+        probe_row_gather(kc, vc, idx, check)
     e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / reps
@@ -287,7 +288,7 @@ def row_gather_floor(ctx, w, k_store, v_store, bt, att_us, reps=20):
     return {"distinct_rows": int(idx.numel()), "bytes": int(nbytes), "us": round(us, 2),
             "gbps": round(nbytes / (us * 1e-6) / 1e9, 1), "attention_split_us": round(att_us, 2),
             "floor_over_attention": round(us / att_us, 4),
-            "what": "csa_probe_row_gather over the union of the selected and appended rows per KV head "
+            "what": "bench_aids.probe_row_gather over the union of the selected and appended rows per KV head "
                     "(last step), K and V, HIP events"}
 
 

@@ -90,7 +90,9 @@ void csa_destroy(csa_ctx *ctx);
 /*
  * Sizes (bytes) of the two device buffers the caller must provide to csa_bind:
  *   tables  - centroids + lookup tables in the library's private layout (persistent state)
- *   scratch - per-step temporaries (contents need not survive between calls)
+ *   scratch - per-step temporaries (contents need not survive between calls, with one exception:
+ *             the index set of the last searching step when it was called with NULL sel pointers,
+ *             see csa_decode_step_reuse)
  */
 int csa_workspace_bytes(const csa_ctx *ctx, size_t *tables_bytes, size_t *scratch_bytes);
 
@@ -253,19 +255,6 @@ int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream);
 int csa_profile_enable(csa_ctx *ctx, int32_t on);
 int csa_profile_read(csa_ctx *ctx, double *ms_sum, int64_t *launches);
 const char *csa_stage_name(int32_t stage); /* NULL if out of range */
-
-/*
- * Measurement aid (no part of the method; no context needed): reads, and only reads, the
- * 256-byte rows idx_dev[i], i < n_idx, of k_rows_dev and of v_rows_dev (device buffers of n_rows
- * rows each) the way the attention kernel fetches rows - 16 lanes per row, 16 bytes per lane, 64
- * consecutive indices per lane group, eight rows of each buffer in flight - and stores the XOR
- * of all 32-bit words read for indices [64 j, 64 j + 64) into check_dev[j] (uint32,
- * ceil(n_idx / 64) words).  Indices outside [0, n_rows) are skipped.  Timed over a step's
- * distinct selected rows it gives the floor for any kernel that has to fetch them.
- * CSA_ERR_ARG for NULL pointers or non-positive n_rows; enqueues on `stream`.
- */
-int csa_probe_row_gather(const void *k_rows_dev, const void *v_rows_dev, int64_t n_rows,
-                         const int32_t *idx_dev, int64_t n_idx, uint32_t *check_dev, void *stream);
 
 const char *csa_strerror(int status);
 /* hipError_t of the last failing HIP call on this ctx (0 if none). */

@@ -59,7 +59,6 @@ def lib() -> C.CDLL:
         "csa_set_context_len": (C.c_int, [vp, i32]),
         "csa_score_frac_bits": (C.c_int, [vp, C.POINTER(i32)]),
         "csa_last_probed_rows": (C.c_int, [vp, vp, vp]),
-        "csa_probe_row_gather": (C.c_int, [vp, vp, C.c_int64, vp, C.c_int64, vp, vp]),
         "csa_profile_enable": (C.c_int, [vp, i32]),
         "csa_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "csa_stage_name": (C.c_char_p, [i32]),
@@ -78,7 +77,7 @@ EXPORTED = ("csa_create", "csa_destroy", "csa_workspace_bytes", "csa_bind", "csa
             "csa_export_tables", "csa_import_tables", "csa_append_kv", "csa_decode_step",
             "csa_decode_step_reuse", "csa_decode_step_append", "csa_streaming_status",
             "csa_context_len", "csa_set_context_len", "csa_score_frac_bits",
-            "csa_last_probed_rows", "csa_probe_row_gather", "csa_profile_enable", "csa_profile_read", "csa_stage_name",
+            "csa_last_probed_rows", "csa_profile_enable", "csa_profile_read", "csa_stage_name",
             "csa_strerror", "csa_last_hip_error")
 
 
@@ -210,15 +209,6 @@ def csa_score_frac_bits(ctx) -> int:
 
 def csa_last_probed_rows(ctx, rows_out):
     _check(lib().csa_last_probed_rows(ctx, _ptr(rows_out), _stream()), "csa_last_probed_rows")
-
-
-def csa_probe_row_gather(k_rows, v_rows, idx, check):
-    """k_rows, v_rows: [n_rows][128] bf16; idx: int32 [n_idx]; check: int32/uint32 [ceil(n_idx / 64)]."""
-    n_rows = k_rows.numel() // 128
-    assert v_rows.numel() // 128 == n_rows and k_rows.element_size() == 2 and idx.dtype == torch.int32
-    assert check.element_size() == 4 and check.numel() >= (idx.numel() + 63) // 64
-    _check(lib().csa_probe_row_gather(_ptr(k_rows), _ptr(v_rows), n_rows, _ptr(idx), idx.numel(), _ptr(check),
-                                      _stream()), "csa_probe_row_gather")
 
 
 def csa_profile_enable(ctx, on: bool):

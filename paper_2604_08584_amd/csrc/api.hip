@@ -31,11 +31,13 @@ struct Region {
 struct Layout {
     // tables buffer
     Region cent_t, ent, part_off, row_cnt, row_min, blk_min;  // (the last three: streaming updates only)
+    Region state;  // persistent device words: [0] = a streamed score was clamped since the build
     size_t tables_bytes = 0;
-    // scratch buffer
+    // scratch buffer: what a decode step uses comes first (decode_bytes), then what only the table
+    // build and the streaming insertion use
     Region z, rows, spans, cand, bin_off, cand_cnt, seg_par, seg_run, thr, sel, sel_count, part, flags, qs;
     Region queue_n, queue;  // rows waiting for the streaming insertion
-    size_t scratch_bytes = 0;
+    size_t scratch_bytes = 0, decode_bytes = 0;
     int P_max = 0, PO_max = 0, S_max = 0, Ls = 0;
     size_t cand_keys = 0;  // candidate slots per head
 };
@@ -67,6 +69,7 @@ struct csa_ctx {
     };
     // the index set of the last searching step (reused by csa_decode_step_reuse)
     const int32_t *last_sel = nullptr, *last_sel_count = nullptr;
+    const char *last_scratch = nullptr;  // where that step kept its temporaries (probed rows)
     std::vector<Rec> recs;
     size_t n_recs = 0;
 };
@@ -104,6 +107,7 @@ Layout make_layout(const csa_config &c)
         put(l.row_min, BG * Ct * 4);
         put(l.blk_min, BG * Ct * (size_t)l.PO_max * 4);  // per block of a row: its smallest score
     }
+    put(l.state, 256);
     l.tables_bytes = off;
     off = 0;
     l.cand_keys = ((size_t)c.max_ctx + 16383) / 16384 * 16384;
@@ -119,6 +123,8 @@ Layout make_layout(const csa_config &c)
     put(l.sel, BH * (size_t)(c.budget_k > 0 ? c.budget_k : 1) * 4);
     put(l.sel_count, BH * 4);
     put(l.part, BH * (size_t)(l.S_max > 0 ? l.S_max : 1) * (c.head_dim + 2) * 4);
+    put(l.bin_off, BH * (size_t)l.P_max * 512 * 2);  // start of every coarse score bin per (head, key range)
+    l.decode_bytes = off;
     put(l.flags, 256);
     put(l.qs, (size_t)(c.n_centroids < build_chunk(c.max_ctx) ? c.n_centroids : build_chunk(c.max_ctx)) * c.max_ctx * 4);
     if (c.stream_window > 0) {
@@ -126,7 +132,6 @@ Layout make_layout(const csa_config &c)
         put(l.queue_n, BG * n_seg * 4);
         put(l.queue, BG * n_seg * 1024 * 16);
     }
-    put(l.bin_off, BH * (size_t)l.P_max * 512 * 2);  // start of every coarse score bin per (head, key range)
     l.scratch_bytes = off;
     return l;
 }
@@ -309,6 +314,7 @@ int csa_bind(csa_ctx *ctx, void *tables_dev, size_t tables_bytes, void *scratch_
     ctx->v_cache = v_cache_dev;
     ctx->block_table = block_table_dev;
     ctx->last_sel = ctx->last_sel_count = nullptr;
+    ctx->last_scratch = nullptr;
     ctx->bound = true;
     return CSA_OK;
 }
@@ -323,8 +329,10 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
     const Layout &l = ctx->lay;
     ctx->have_tables = false;
     ctx->last_sel = ctx->last_sel_count = nullptr;
+    ctx->last_scratch = nullptr;
     int32_t *flags = at<int32_t>(ctx->scratch, l.flags);
     hipError_t e = hipMemsetAsync(flags, 0, 256, st);
+    if (e == hipSuccess) e = hipMemsetAsync(at<void>(ctx->tables, l.state), 0, 256, st);
     if (e != hipSuccess) return hip_fail(ctx, e);
 
     int F = c.score_frac_bits;
@@ -435,8 +443,10 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
     const Layout &l = ctx->lay;
     ctx->have_tables = false;
     ctx->last_sel = ctx->last_sel_count = nullptr;
+    ctx->last_scratch = nullptr;
     int32_t *flags = at<int32_t>(ctx->scratch, l.flags);
     hipError_t e = hipMemsetAsync(flags, 0, 256, st);
+    if (e == hipSuccess) e = hipMemsetAsync(at<void>(ctx->tables, l.state), 0, 256, st);
     if (e != hipSuccess) return hip_fail(ctx, e);
     choose_partition(ctx, n_pre);
     if (ctx->PO > l.PO_max || ctx->P > l.P_max) return CSA_ERR_WORKSPACE;  // (cannot happen: see make_layout)
@@ -494,7 +504,7 @@ void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, hipStream_t st)
                        at<int32_t>(ctx->tables, l.part_off), at<int32_t>(ctx->tables, l.row_cnt),
                        at<int32_t>(ctx->tables, l.row_min), at<int32_t>(ctx->tables, l.blk_min),
                        at<int32_t>(ctx->scratch, l.queue_n),
-                       at<void>(ctx->scratch, l.queue), at<int32_t>(ctx->scratch, l.flags), c.batch,
+                       at<void>(ctx->scratch, l.queue), at<int32_t>(ctx->tables, l.state), c.batch,
                        c.n_kv_heads, c.n_centroids, c.n_subspaces, c.list_len, l.Ls, ctx->Q, ctx->PO, ctx->F,
                        qmax_for(c.n_probe * c.n_subspaces), ctx->n, st);
     prof.end(9);
@@ -542,7 +552,9 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
 
 namespace {
 
-int search_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
+// `scr`: the scratch memory of this step, laid out as Layout says (the bound scratch buffer, or
+// any other memory of that layout)
+int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
                 int32_t *sel_count_dev, const void *k_new_dev, const void *v_new_dev, void *stream)
 {
     if (!ctx || !q_dev || !out_dev) return CSA_ERR_ARG;
@@ -553,17 +565,17 @@ int search_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_id
     hipStream_t st = (hipStream_t)stream;
     const int BH = c.batch * c.n_q_heads, G = c.n_q_heads / c.n_kv_heads;
     const int S_sub = c.n_subspaces, Ct = S_sub * c.n_centroids, M = S_sub * c.n_probe;
-    float *z = at<float>(ctx->scratch, l.z);
-    int32_t *rows = at<int32_t>(ctx->scratch, l.rows);
-    uint32_t *cand_key = at<uint32_t>(ctx->scratch, l.cand);
-    uint16_t *bin_off = at<uint16_t>(ctx->scratch, l.bin_off);
-    int32_t *cand_cnt = at<int32_t>(ctx->scratch, l.cand_cnt);
-    void *seg_par = at<void>(ctx->scratch, l.seg_par);
-    void *seg_run = at<void>(ctx->scratch, l.seg_run);
-    uint32_t *thr = at<uint32_t>(ctx->scratch, l.thr);
-    int32_t *sel = sel_idx_dev ? sel_idx_dev : at<int32_t>(ctx->scratch, l.sel);
-    int32_t *sel_count = sel_count_dev ? sel_count_dev : at<int32_t>(ctx->scratch, l.sel_count);
-    float *part = at<float>(ctx->scratch, l.part);
+    float *z = at<float>(scr, l.z);
+    int32_t *rows = at<int32_t>(scr, l.rows);
+    uint32_t *cand_key = at<uint32_t>(scr, l.cand);
+    uint16_t *bin_off = at<uint16_t>(scr, l.bin_off);
+    int32_t *cand_cnt = at<int32_t>(scr, l.cand_cnt);
+    void *seg_par = at<void>(scr, l.seg_par);
+    void *seg_run = at<void>(scr, l.seg_run);
+    uint32_t *thr = at<uint32_t>(scr, l.thr);
+    int32_t *sel = sel_idx_dev ? sel_idx_dev : at<int32_t>(scr, l.sel);
+    int32_t *sel_count = sel_count_dev ? sel_count_dev : at<int32_t>(scr, l.sel_count);
+    float *part = at<float>(scr, l.part);
     // the always-attended recent window [ws, n): every appended key, or - with streaming updates -
     // the last stream_window positions (older appended keys compete through the tables)
     const int ws = window_start(ctx);
@@ -571,7 +583,7 @@ int search_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_id
 
     Prof prof(ctx, st);
     prof.mark(0);
-    int32_t *spans = at<int32_t>(ctx->scratch, l.spans);
+    int32_t *spans = at<int32_t>(scr, l.spans);
     if (csa::score_top_fused(c.n_centroids, S_sub, c.n_probe)) {
         // the paper's own geometry: scoring and the choice of the probed rows in one launch
         csa::launch_score_top_sub(q_dev, at<void>(ctx->tables, l.cent_t), rows, at<int32_t>(ctx->tables, l.part_off),
@@ -611,6 +623,7 @@ int search_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_id
     prof.end(5);
     finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, st);
     ctx->last_sel = sel;
+    ctx->last_scratch = scr;
     ctx->last_sel_count = sel_count;
     return check_launch(ctx);
 }
@@ -652,7 +665,7 @@ int reuse_step(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *s
 int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
                     int32_t *sel_count_dev, void *stream)
 {
-    return search_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, stream);
+    return search_step(ctx, ctx ? ctx->scratch : nullptr, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, stream);
 }
 
 int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *sel_idx_dev,
@@ -667,7 +680,7 @@ int csa_decode_step_append(csa_ctx *ctx, const void *q_dev, const void *k_new_de
 {
     if (!k_new_dev || !v_new_dev) return CSA_ERR_ARG;
     return reuse ? reuse_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev, v_new_dev, stream)
-                 : search_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev, v_new_dev, stream);
+                 : search_step(ctx, ctx ? ctx->scratch : nullptr, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev, v_new_dev, stream);
 }
 
 int csa_streaming_status(csa_ctx *ctx, void *stream)
@@ -676,7 +689,7 @@ int csa_streaming_status(csa_ctx *ctx, void *stream)
     if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
     if (ctx->cfg.stream_window <= 0) return CSA_OK;
     int32_t flag = 0;
-    hipError_t e = hipMemcpyAsync(&flag, at<int32_t>(ctx->scratch, ctx->lay.flags) + 2, 4, hipMemcpyDeviceToHost,
+    hipError_t e = hipMemcpyAsync(&flag, at<int32_t>(ctx->tables, ctx->lay.state), 4, hipMemcpyDeviceToHost,
                                   (hipStream_t)stream);
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, e);
@@ -715,18 +728,10 @@ int csa_last_probed_rows(const csa_ctx *ctx, int32_t *rows_dev, void *stream)
     if (!ctx || !rows_dev) return CSA_ERR_ARG;
     if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
     const size_t bytes = (size_t)ctx->cfg.batch * ctx->cfg.n_q_heads * ctx->cfg.n_probe * ctx->cfg.n_subspaces * 4;
-    const hipError_t e = hipMemcpyAsync(rows_dev, ctx->scratch + ctx->lay.rows.off, bytes,
+    if (!ctx->last_scratch) return CSA_ERR_STATE;  // no searching step since the tables were made
+    const hipError_t e = hipMemcpyAsync(rows_dev, ctx->last_scratch + ctx->lay.rows.off, bytes,
                                         hipMemcpyDeviceToDevice, (hipStream_t)stream);
     return e == hipSuccess ? CSA_OK : hip_fail(const_cast<csa_ctx *>(ctx), e);
-}
-
-int csa_probe_row_gather(const void *k_rows_dev, const void *v_rows_dev, int64_t n_rows,
-                         const int32_t *idx_dev, int64_t n_idx, uint32_t *check_dev, void *stream)
-{
-    if (!k_rows_dev || !v_rows_dev || !idx_dev || !check_dev) return CSA_ERR_ARG;
-    if (n_rows <= 0 || n_idx < 0 || n_idx > ((int64_t)1 << 40)) return CSA_ERR_ARG;
-    csa::launch_probe_row_gather(k_rows_dev, v_rows_dev, n_rows, idx_dev, n_idx, check_dev, (hipStream_t)stream);
-    return hipGetLastError() == hipSuccess ? CSA_OK : CSA_ERR_HIP;
 }
 
 int csa_profile_enable(csa_ctx *ctx, int32_t on)

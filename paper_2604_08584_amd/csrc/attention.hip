@@ -391,62 +391,4 @@ void launch_append(void *kc, void *vc, const int32_t *block_table, const void *k
                                                 (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx);
 }
 
-// ---------------------------------------------------------------------------------------------
-// Measurement aid: the row fetches of the attention kernel and nothing else.  A group of 16 lanes
-// owns 64 consecutive indices and reads row idx[i] (256 bytes, 16 per lane) of K and of V, eight
-// rows of each in flight; what it read is folded into one XOR word per group so that the reads are
-// real and checkable.  The duration of this launch over a step's distinct selected rows is a floor
-// for any kernel that has to fetch them.  grid ceil(n_idx / 1024), block 256.
-// ---------------------------------------------------------------------------------------------
-constexpr int kProbeRows = 64, kProbeFlight = 8;
-
-__global__ __launch_bounds__(256) void k_probe_row_gather(const uint4 *__restrict__ kr,
-                                                          const uint4 *__restrict__ vr, long long n_rows,
-                                                          const int32_t *__restrict__ idx, long long n_idx,
-                                                          uint32_t *__restrict__ check)
-{
-    const long long grp = ((long long)blockIdx.x * 256 + threadIdx.x) / 16;
-    const int l = threadIdx.x & 15;
-    const long long i0 = grp * kProbeRows;
-    uint32_t x = 0;
-    if (i0 >= n_idx) return;  // (whole lane groups; the shuffles below stay within a group)
-    // every load is unconditional (a skipped index reads row 0 and its words are dropped): no
-    // branch stands between the loads, so all of a round's rows are in flight together
-#pragma unroll 1
-    for (int r = 0; r < kProbeRows; r += kProbeFlight) {
-        long long row[kProbeFlight];
-        bool ok[kProbeFlight];
-#pragma unroll
-        for (int u = 0; u < kProbeFlight; ++u) {
-            const long long i = i0 + r + u;
-            row[u] = (long long)idx[i < n_idx ? i : n_idx - 1];
-            ok[u] = i < n_idx && row[u] >= 0 && row[u] < n_rows;
-            row[u] = ok[u] ? row[u] : 0;
-        }
-        uint4 a[kProbeFlight], b[kProbeFlight];
-#pragma unroll
-        for (int u = 0; u < kProbeFlight; ++u) {
-            a[u] = kr[row[u] * 16 + l];
-            b[u] = vr[row[u] * 16 + l];
-        }
-#pragma unroll
-        for (int u = 0; u < kProbeFlight; ++u) {
-            const uint32_t w = a[u].x ^ a[u].y ^ a[u].z ^ a[u].w ^ b[u].x ^ b[u].y ^ b[u].z ^ b[u].w;
-            x ^= ok[u] ? w : 0u;
-        }
-    }
-#pragma unroll
-    for (int d = 8; d >= 1; d >>= 1) x ^= (uint32_t)__shfl_xor((int)x, d, 16);
-    if (l == 0) check[grp] = x;
-}
-
-void launch_probe_row_gather(const void *k_rows, const void *v_rows, int64_t n_rows, const int32_t *idx,
-                             int64_t n_idx, uint32_t *check, hipStream_t st)
-{
-    const int64_t blocks = (n_idx + 16 * kProbeRows - 1) / (16 * kProbeRows);
-    if (blocks > 0)
-        k_probe_row_gather<<<(unsigned)blocks, 256, 0, st>>>((const uint4 *)k_rows, (const uint4 *)v_rows, n_rows,
-                                                             idx, n_idx, check);
-}
-
 }  // namespace csa

@@ -29,7 +29,7 @@ void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc
 void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt, int32_t *row_min, int32_t *blk_min,
                       int64_t n_rows, int Ls, int PO, hipStream_t st);
 void launch_insert(const void *k_new, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
-                   int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *flags, int B, int Hkv, int C,
+                   int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *clamped, int B, int Hkv, int C,
                    int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st);
 void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
                          int max_ctx, int n_pre, int S, hipStream_t st);
@@ -84,9 +84,5 @@ void launch_attention_merge_append(const float *part, float *out, int n_heads, i
                                    int Hkv, int n, int max_ctx, hipStream_t st);
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
                    int B, int Hkv, int n, int max_ctx, hipStream_t st);
-
-// measurement aid: reads row idx[i] (256 bytes) of both buffers, one XOR word per 64 indices
-void launch_probe_row_gather(const void *k_rows, const void *v_rows, int64_t n_rows, const int32_t *idx,
-                             int64_t n_idx, uint32_t *check, hipStream_t st);
 
 }  // namespace csa

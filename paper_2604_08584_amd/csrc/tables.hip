@@ -417,7 +417,7 @@ void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt
 // Try test: lane j of block (x, s, bg) scores the new key of KV head bg against centroid (s, j)
 // - the fma chain and grid of the table build - and, if the row has a free slot or the score beats
 // the row minimum, queues (row, q) for insertion.  A score outside the grid range is clamped and
-// reported in flags[2].  cent_t is [bg][S][db/8][C][8]; k_new is [bg][128] bf16.
+// reported in *clamped.  cent_t is [bg][S][db/8][C][8]; k_new is [bg][128] bf16.
 // Every workgroup owns a queue segment of kScanNT slots and its count (written, not added to): no
 // global atomics - on this multi-die part thousands of returning atomics on a few addresses cost
 // more than the scan itself - and nothing to clear between steps.
@@ -430,7 +430,7 @@ __global__ __launch_bounds__(kScanNT) void k_insert_scan(const uint16_t *__restr
                                                      const int32_t *__restrict__ row_min,
                                                      int32_t *__restrict__ queue_n,
                                                      int4 *__restrict__ queue,
-                                                     int32_t *__restrict__ flags, int C, int S, int L,
+                                                     int32_t *__restrict__ clamped, int C, int S, int L,
                                                      float up, int qmax)
 {
     __shared__ float s_k[kHeadDim];
@@ -463,7 +463,7 @@ __global__ __launch_bounds__(kScanNT) void k_insert_scan(const uint16_t *__restr
     }
     float qf = rintf(acc * up);
     if (!(fabsf(qf) <= (float)qmax)) {
-        atomicOr(flags + 2, 1);
+        atomicOr(clamped, 1);
         qf = qf > 0.0f ? (float)qmax : -(float)qmax;  // (a NaN cannot occur: inputs are finite)
     }
     const int q = (int)qf;
@@ -619,13 +619,13 @@ __global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ en
 }
 
 void launch_insert(const void *k_new, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
-                   int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *flags, int B, int Hkv, int C,
+                   int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *clamped, int B, int Hkv, int C,
                    int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st)
 {
     const int nx = (C + kScanNT - 1) / kScanNT, n_seg = S * nx;  // (n_seg <= 64: checked at create)
     dim3 grid(nx, S, B * Hkv);
     k_insert_scan<<<grid, kScanNT, 0, st>>>((const uint16_t *)k_new, (const uint4 *)cent_t, row_cnt, row_min, queue_n,
-                                            (int4 *)queue, flags, C, S, L, ldexpf(1.0f, F), qmax);
+                                            (int4 *)queue, clamped, C, S, L, ldexpf(1.0f, F), qmax);
     // the queue lengths are only known on the device: enough waves for one row each in the usual
     // case (a few percent of the rows take a new key), striding when there are more
     const int per_seg = C < kScanNT ? C : kScanNT;  // rows behind a segment

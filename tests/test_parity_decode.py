@@ -508,34 +508,6 @@ def test_profile_counters_cover_every_stage():
     assert all(v == (0.0, 0) for v in binding.csa_profile_read(case.ctx.ctx).values())
 
 
-def test_row_gather_probe_reads_the_rows_it_is_given():
-    """The measurement aid that times bare row fetches: its XOR words equal those of the K and V
-    rows named by the indices (numpy), indices outside the buffers are skipped, the last group
-    is ragged."""
-    g = torch.Generator().manual_seed(3)
-    n_rows, n_idx = 5000, 64 * 37 + 21
-    k = torch.randn(n_rows, 128, generator=g).to(torch.bfloat16)
-    v = torch.randn(n_rows, 128, generator=g).to(torch.bfloat16)
-    idx = torch.randint(0, n_rows, (n_idx,), generator=g, dtype=torch.int32)
-    idx[5], idx[70], idx[700], idx[-1] = -1, n_rows, 2 ** 31 - 1, -(2 ** 31)
-    n_grp = (n_idx + 63) // 64
-    check = torch.full((n_grp + 1,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
-    binding.csa_probe_row_gather(k.cuda(), v.cuda(), idx.cuda(), check)
-    torch.cuda.synchronize()
-    got = check.cpu().numpy().view(np.uint32)
-    kw = k.view(torch.int32).numpy().view(np.uint32)          # [n_rows][64]
-    vw = v.view(torch.int32).numpy().view(np.uint32)
-    rows = idx.numpy().astype(np.int64)
-    for j in range(n_grp):
-        r = rows[64 * j:64 * j + 64]
-        r = r[(r >= 0) & (r < n_rows)]
-        want = np.bitwise_xor.reduce(np.concatenate([kw[r].ravel(), vw[r].ravel()])) if len(r) else 0
-        assert got[j] == want, j
-    assert got[n_grp] == 0x5A5A5A5A                           # nothing past the last group is written
-    with pytest.raises(binding.CsaError):
-        binding._check(binding.lib().csa_probe_row_gather(None, None, 1, None, 0, None, None), "probe")
-
-
 def test_two_contexts_interleaved_on_two_streams():
     """Two contexts of different shapes take turns, each on a stream of its own: nothing in the
     library is shared between contexts, so every step still matches the oracle."""
