@@ -201,6 +201,31 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
                     int32_t *sel_count_dev, void *stream);
 
 /*
+ * csa_decode_step for callers that cannot allocate or bring a workspace to the call - code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc: the same kernels, same
+ * arguments and same results as csa_decode_step, but every per-step temporary (centroid scores,
+ * probed rows, candidate words, bin offsets, Top-K records, split partials; and the index set
+ * when sel_idx_dev / sel_count_dev are NULL) lives in a fixed array inside the library's own
+ * device image instead of the scratch buffer given to csa_bind.  The call allocates nothing and
+ * frees nothing (no hipMalloc, no hipFree, no library routine that allocates); it only launches
+ * kernels on `stream`.
+ *   Limit: the step's temporaries (csa_static_scratch_bytes reports them) must fit the array's
+ *   32 MiB - e.g. batch 1, 32 query heads at a 128K context; CSA_ERR_WORKSPACE and nothing
+ *   enqueued otherwise.  Tables and the K/V cache still come from csa_bind; inputs and outputs
+ *   are the caller's as in csa_decode_step.
+ *   Every GPU the library runs on holds its own copy of the array until the process ends.  All
+ *   calls on one GPU, from any context, share it: nothing in it needs to start at zero and nothing
+ *   is read from an earlier call, but two such calls that overlap in time on one GPU (different
+ *   streams) race.  With both sel pointers NULL the index set stays in the array, so the next
+ *   csa_decode_step_static of ANY context overwrites what csa_decode_step_reuse(NULL, NULL) would
+ *   read.
+ */
+int csa_decode_step_static(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
+                           int32_t *sel_count_dev, void *stream);
+/* Bytes of temporaries a step of this context needs, and the capacity of the static array. */
+int csa_static_scratch_bytes(const csa_ctx *ctx, size_t *needed, size_t *capacity);
+
+/*
  * A decode step inside a search period (App. "Schedules evaluation" and the complexity appendix:
  * with search period P the index set of the last searching step is reused for the next P-1
  * steps, e.g. the schedules 0.15-step-4 and 0.20-step-8): no centroid scoring, no table access,

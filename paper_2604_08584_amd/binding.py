@@ -52,6 +52,8 @@ def lib() -> C.CDLL:
         "csa_import_tables": (C.c_int, [vp, vp, vp, vp, i32, vp]),
         "csa_append_kv": (C.c_int, [vp, vp, vp, vp]),
         "csa_decode_step": (C.c_int, [vp, vp, vp, vp, vp, vp]),
+        "csa_decode_step_static": (C.c_int, [vp, vp, vp, vp, vp, vp]),
+        "csa_static_scratch_bytes": (C.c_int, [vp, C.POINTER(sz), C.POINTER(sz)]),
         "csa_decode_step_reuse": (C.c_int, [vp, vp, vp, vp, vp, vp]),
         "csa_decode_step_append": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, i32, vp]),
         "csa_streaming_status": (C.c_int, [vp, vp]),
@@ -75,6 +77,7 @@ def lib() -> C.CDLL:
 EXPORTED = ("csa_create", "csa_destroy", "csa_workspace_bytes", "csa_bind", "csa_build_tables",
             "csa_cluster_workspace_bytes", "csa_cluster_queries",
             "csa_export_tables", "csa_import_tables", "csa_append_kv", "csa_decode_step",
+            "csa_decode_step_static", "csa_static_scratch_bytes",
             "csa_decode_step_reuse", "csa_decode_step_append", "csa_streaming_status",
             "csa_context_len", "csa_set_context_len", "csa_score_frac_bits",
             "csa_last_probed_rows", "csa_profile_enable", "csa_profile_read", "csa_stage_name",
@@ -174,6 +177,17 @@ def csa_append_kv(ctx, k_new, v_new):
 def csa_decode_step(ctx, q, out, sel_idx=None, sel_count=None):
     _check(lib().csa_decode_step(ctx, _ptr(q), _ptr(out), _ptr(sel_idx), _ptr(sel_count), _stream()),
            "csa_decode_step")
+
+
+def csa_decode_step_static(ctx, q, out, sel_idx=None, sel_count=None):
+    _check(lib().csa_decode_step_static(ctx, _ptr(q), _ptr(out), _ptr(sel_idx), _ptr(sel_count), _stream()),
+           "csa_decode_step_static")
+
+
+def csa_static_scratch_bytes(ctx):
+    a, b = C.c_size_t(), C.c_size_t()
+    _check(lib().csa_static_scratch_bytes(ctx, C.byref(a), C.byref(b)), "csa_static_scratch_bytes")
+    return a.value, b.value
 
 
 def csa_decode_step_reuse(ctx, q, out, sel_idx=None, sel_count=None):

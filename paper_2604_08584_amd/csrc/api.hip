@@ -3,11 +3,18 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "../../include/csattn.h"
 #include "kernels.h"
+
+// Scratch memory of csa_decode_step_static: one array per GPU, part of the loaded code object (it
+// exists on every device the library runs on until the process ends).  Host code never uses this
+// name as an address: the device address is looked up once per device (static_scratch below).
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -204,6 +211,29 @@ void choose_partition(csa_ctx *ctx, int n_pre)
 
 template <class T>
 T *at(char *base, const Region &r) { return reinterpret_cast<T *>(base + r.off); }
+
+// device address of g_static_scratch on the current device (every GPU holds its own copy at its
+// own address), looked up on the first call on that device
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+char *g_static_ptr[kMaxDevices] = {};
+
+int static_scratch(csa_ctx *ctx, char **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    if (dev < 0 || dev >= kMaxDevices) return CSA_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+        if (e != hipSuccess || !p) return hip_fail(ctx, e != hipSuccess ? e : hipErrorInvalidSymbol);
+        g_static_ptr[dev] = (char *)p;
+    }
+    *out = g_static_ptr[dev];
+    return CSA_OK;
+}
 
 // largest admissible |q|: m sums stay below 2^24 and q fits its field of a packed entry
 int qmax_for(int m)
@@ -553,7 +583,7 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
 namespace {
 
 // `scr`: the scratch memory of this step, laid out as Layout says (the bound scratch buffer, or
-// any other memory of that layout)
+// the library's own static array)
 int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
                 int32_t *sel_count_dev, const void *k_new_dev, const void *v_new_dev, void *stream)
 {
@@ -666,6 +696,25 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
                     int32_t *sel_count_dev, void *stream)
 {
     return search_step(ctx, ctx ? ctx->scratch : nullptr, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, stream);
+}
+
+int csa_decode_step_static(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
+                           int32_t *sel_count_dev, void *stream)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    if (ctx->lay.decode_bytes > kStaticScratchBytes) return CSA_ERR_WORKSPACE;
+    char *scr = nullptr;
+    const int rc = static_scratch(ctx, &scr);
+    if (rc != CSA_OK) return rc;
+    return search_step(ctx, scr, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, stream);
+}
+
+int csa_static_scratch_bytes(const csa_ctx *ctx, size_t *needed, size_t *capacity)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    if (needed) *needed = ctx->lay.decode_bytes;
+    if (capacity) *capacity = kStaticScratchBytes;
+    return CSA_OK;
 }
 
 int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *sel_idx_dev,
