@@ -271,12 +271,11 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
 // lower index (Sec. 3.3 (1) with the top-tau back-off of Sec. 4.4), on the order-preserving
 // integer image of z; they become table rows sub*C + j, slots [sub*tau, (sub+1)*tau) of the head's
 // M = S*tau probed rows.
-// Fast path (m small against C): every thread takes the maximum of its own slice; the m-th
-// largest of the 256 thread maxima is a lower bound on the m-th largest overall, so only the few
-// values >= that bound are candidates; they are ranked against each other by (z desc, j asc) and
-// ranks < m are written in rank order.  If there are too many candidates (many equal values) a
-// radix threshold search with an ordered tie pick does the job instead.  With C <= 256 every
-// thread holds one value and simply counts the values that beat it.
+// Fast path (m small against C): every thread takes the maximum of its own slice; a lower bound
+// on the m-th largest overall follows from the thread maxima, so only the few values >= that
+// bound are candidates; they are ranked against each other by (z desc, j asc) and ranks < m are
+// kept.  If there are too many candidates (many equal values) a radix threshold search with an
+// ordered tie pick does the job instead.  With C <= 256 every value is a candidate.
 // Also looks up, for every key range p, the
 // nsub + 1 offsets that cut the slice of each probed row into its blocks, so that the
 // accumulation kernel starts with one coalesced read.
@@ -284,6 +283,141 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
 // ---------------------------------------------------------------------------------------------
 constexpr int kTopReg = 16;     // keys per thread held in registers
 constexpr int kTopCand = 1024;  // candidate capacity of the fast path
+
+template <int NT>
+struct TopSmem {
+    int32_t rows[64];  // the result: the m chosen centroids (valid after the barrier that follows select_top)
+    alignas(16) uint32_t hist[256 + NT / kWave + 4];
+    int scan[NT / kWave + 1];
+    alignas(16) uint64_t ck[kTopCand + 2];  // (key << 32) | ~j : larger = better, distinct
+    int slot;
+    uint32_t bound;
+};
+
+// The m centroids of zh[0..C) with the largest score, ties to the lower index, into sm.rows (in
+// no particular order on the fast path).  All NT threads of the workgroup must call; the caller
+// puts a barrier between this call and its reads of sm.rows; sm may hold anything on entry.
+template <int NT>
+__device__ __forceinline__ void select_top(const float *__restrict__ zh, int C, int m, TopSmem<NT> &sm)
+{
+    if (threadIdx.x == 0) sm.slot = 0;
+    // rank the nc candidates in sm.ck[0..nc) (distinct words, larger = better) against each other and
+    // keep ranks < m.  A candidate is shared by tpc adjacent lanes, each counting over a slice of the
+    // others, so that the chain of LDS reads is short however many threads the workgroup has.
+    auto rank_candidates = [&](int nc) {
+        if (threadIdx.x == 0) sm.ck[nc] = 0;  // pad to an even count (0 beats nothing)
+        __syncthreads();
+        int sh = 0;
+        while (sh < 4 && ((nc * 2) << sh) <= NT) ++sh;  // tpc = 2^sh lanes per candidate (uniform)
+        const int tpc = 1 << sh, part = (int)threadIdx.x & (tpc - 1);
+        const int n2 = (nc + 1) / 2, per = (n2 + tpc - 1) >> sh;
+        const int t_lo = part * per, t_hi = min(n2, t_lo + per);
+        const ulonglong2 *c2 = (const ulonglong2 *)sm.ck;
+        for (int a0 = 0; a0 < nc; a0 += NT >> sh) {  // (uniform trip count)
+            const int a = a0 + ((int)threadIdx.x >> sh);
+            const uint64_t mine = a < nc ? sm.ck[a] : ~0ull;
+            int r = 0;
+#pragma unroll 4
+            for (int t2 = t_lo; t2 < t_hi; ++t2) {
+                const ulonglong2 o = c2[t2];
+                r += (o.x > mine) + (o.y > mine);
+            }
+            for (int x = 1; x < tpc; x <<= 1) r += __shfl_xor(r, x, kWave);
+            if (a < nc && part == 0 && r < m) sm.rows[r] = (int32_t)~(uint32_t)mine;
+        }
+    };
+    if (C <= 256) {
+        // ---- few centroids: every value is a candidate
+        for (int j = threadIdx.x; j < C; j += NT)
+            sm.ck[j] = ((uint64_t)orderable(zh[j]) << 32) | (uint32_t)~(uint32_t)j;
+        rank_candidates(C);
+        return;
+    }
+    const bool in_regs = C <= NT * kTopReg;
+    uint32_t kreg[kTopReg];
+    if (in_regs) {
+#pragma unroll
+        for (int u = 0; u < kTopReg; ++u) {
+            const int j = u * NT + threadIdx.x;
+            kreg[u] = j < C ? orderable(zh[j]) : 0u;
+        }
+    }
+    const int rounds = (C + NT - 1) / NT;
+    // visit(fn): fn(j, key, valid) for every centroid slot of this thread, uniformly per wave
+    auto visit = [&](auto fn) {
+        if (in_regs) {
+#pragma unroll
+            for (int u = 0; u < kTopReg; ++u)
+                if (u < rounds) {
+                    const int j = u * NT + threadIdx.x;
+                    fn(j, kreg[u], j < C);
+                }
+        } else {
+            for (int u = 0; u < rounds; ++u) {
+                const int j = u * NT + threadIdx.x;
+                fn(j, j < C ? orderable(zh[j]) : 0u, j < C);
+            }
+        }
+    };
+    if (m <= NT / 4 && C >= NT) {  // every lane holds at least one value
+        // ---- fast path
+        uint32_t best = 0;  // orderable(z) of a finite z is never 0
+        visit([&](int, uint32_t key, bool valid) { if (valid && key > best) best = key; });
+        // a lower bound on the m-th largest value overall: in each wave the r-th largest of the
+        // 64 lane maxima, r = ceil(m / waves) (found by r rounds of max-and-remove); the smallest
+        // of these over the waves has at least m values at or above it
+        {
+            constexpr int NWT = NT / kWave;
+            const int r = (m + NWT - 1) / NWT;  // <= 16 of the 64 lane maxima; NWT * r >= m
+            uint32_t cur = best, wmax = 0u;
+            for (int round = 0; round < r; ++round) {
+                wmax = wave_max(cur);
+                const uint64_t holders = __ballot(cur == wmax);
+                if (lane_id() == __ffsll((unsigned long long)holders) - 1) cur = 0u;  // remove one winner
+            }
+            if (lane_id() == 0) sm.hist[threadIdx.x / kWave] = wmax;
+            __syncthreads();
+            if (threadIdx.x < kWave) {
+                uint32_t bnd = (int)threadIdx.x < NWT ? sm.hist[threadIdx.x] : 0xFFFFFFFFu;
+                bnd = ~wave_max(~bnd);  // the smallest
+                if (threadIdx.x == 0) sm.bound = bnd;
+            }
+        }
+        __syncthreads();
+        const uint32_t bound = sm.bound;
+        visit([&](int j, uint32_t key, bool valid) {
+            if (valid && key >= bound) {
+                const int slot = atomicAdd(&sm.slot, 1);
+                if (slot < kTopCand) sm.ck[slot] = ((uint64_t)key << 32) | (uint32_t)~j;
+            }
+        });
+        __syncthreads();
+        const int nc = sm.slot;
+        if (nc <= kTopCand && nc >= m) {  // (nc >= m always holds; checked so that no row is ever left unset)
+            rank_candidates(nc);
+            return;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) sm.slot = 0;
+    }
+    // ---- general path: radix threshold, winners above it take any slot, ties in index order
+    int need = 0;
+    const uint32_t T = block_radix_threshold<NT, 8, 4>(
+        [&](auto fn) { visit([&](int, uint32_t key, bool valid) { fn(key, valid); }); }, m, sm.hist,
+        need);
+    visit([&](int j, uint32_t key, bool valid) {
+        if (valid && key > T) sm.rows[atomicAdd(&sm.slot, 1)] = j;
+    });
+    int ties_taken = 0;
+    const int base = m - need;
+    visit([&](int j, uint32_t key, bool valid) {
+        const int is_tie = (valid && key == T) ? 1 : 0;
+        int round_total;
+        const int rank = block_excl_scan<NT>(is_tie, sm.scan, round_total) + ties_taken;
+        if (is_tie && rank < need) sm.rows[base + rank] = j;
+        ties_taken += round_total;
+    });
+}
 
 template <int kTopNT>
 __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restrict__ z,
@@ -294,134 +428,12 @@ __global__ __launch_bounds__(kTopNT) void k_top_centroids(const float *__restric
 {
     const int head = blockIdx.x / S, sub = blockIdx.x - head * S;
     const int M = S * m;
-    __shared__ int32_t s_rows[64];
-    __shared__ __align__(16) uint32_t s_hist[256 + kTopNT / kWave + 4];
-    __shared__ int s_scan[kTopNT / kWave + 1];
-    __shared__ __align__(16) uint64_t s_ck[kTopCand + 2];  // (key << 32) | ~j : larger = better, distinct
-    __shared__ int s_slot;
-    __shared__ uint32_t s_bound;
-    const float *zh = z + (size_t)blockIdx.x * C;
+    __shared__ TopSmem<kTopNT> sm;
     int32_t *out = rows + (size_t)head * M + sub * m;
-    if (threadIdx.x == 0) s_slot = 0;
-    const bool in_regs = C <= kTopNT * kTopReg;
-    uint32_t kreg[kTopReg];
-    if (in_regs) {
-#pragma unroll
-        for (int u = 0; u < kTopReg; ++u) {
-            const int j = u * kTopNT + threadIdx.x;
-            kreg[u] = j < C ? orderable(zh[j]) : 0u;
-        }
-    }
-    const int rounds = (C + kTopNT - 1) / kTopNT;
-    // visit(fn): fn(j, key, valid) for every centroid slot of this thread, uniformly per wave
-    auto visit = [&](auto fn) {
-        if (in_regs) {
-#pragma unroll
-            for (int u = 0; u < kTopReg; ++u)
-                if (u < rounds) {
-                    const int j = u * kTopNT + threadIdx.x;
-                    fn(j, kreg[u], j < C);
-                }
-        } else {
-            for (int u = 0; u < rounds; ++u) {
-                const int j = u * kTopNT + threadIdx.x;
-                fn(j, j < C ? orderable(zh[j]) : 0u, j < C);
-            }
-        }
-    };
-    if (C <= kTopNT && C <= 256) {
-        // ---- few centroids: one value per thread, rank = number of values that beat it (quadratic
-        // work: not for the 1024 values a wide workgroup could hold this way)
-        const uint64_t mine = (int)threadIdx.x < C ? (((uint64_t)kreg[0] << 32) | (uint32_t)~threadIdx.x) : 0ull;
-        s_ck[threadIdx.x] = mine;  // (key << 32) | ~j: larger = better, distinct; 0 beats nothing
-        __syncthreads();
-        if ((int)threadIdx.x < C) {
-            const ulonglong2 *c2 = (const ulonglong2 *)s_ck;
-            int r = 0;
-#pragma unroll 4
-            for (int t2 = 0; t2 < kTopNT / 2; ++t2) {
-                const ulonglong2 o = c2[t2];
-                r += (o.x > mine) + (o.y > mine);
-            }
-            if (r < m) s_rows[r] = (int32_t)threadIdx.x;
-        }
-        goto publish;
-    }
-    if (m <= kTopNT / 4 && C >= kTopNT) {  // every lane holds at least one value
-        // ---- fast path
-        uint32_t best = 0;  // orderable(z) of a finite z is never 0
-        visit([&](int, uint32_t key, bool valid) { if (valid && key > best) best = key; });
-        // a lower bound on the m-th largest value overall: in each wave the r-th largest of the
-        // 64 lane maxima, r = ceil(m / waves) (found by r rounds of max-and-remove); the smallest
-        // of these over the waves has at least m values at or above it
-        {
-            constexpr int NWT = kTopNT / kWave;
-            const int r = (m + NWT - 1) / NWT;  // <= 16 of the 64 lane maxima; NWT * r >= m
-            uint32_t cur = best, wmax = 0u;
-            for (int round = 0; round < r; ++round) {
-                wmax = wave_max(cur);
-                const uint64_t holders = __ballot(cur == wmax);
-                if (lane_id() == __ffsll((unsigned long long)holders) - 1) cur = 0u;  // remove one winner
-            }
-            if (lane_id() == 0) s_hist[threadIdx.x / kWave] = wmax;
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                uint32_t bnd = 0xFFFFFFFFu;
-                for (int w = 0; w < NWT; ++w) bnd = min(bnd, s_hist[w]);
-                s_bound = bnd;
-            }
-        }
-        __syncthreads();
-        const uint32_t bound = s_bound;
-        visit([&](int j, uint32_t key, bool valid) {
-            if (valid && key >= bound) {
-                const int slot = atomicAdd(&s_slot, 1);
-                if (slot < kTopCand) s_ck[slot] = ((uint64_t)key << 32) | (uint32_t)~j;
-            }
-        });
-        __syncthreads();
-        const int nc = s_slot;
-        if (nc <= kTopCand && nc >= m) {  // (nc >= m always holds; checked so that no row is ever left unset)
-            if (threadIdx.x == 0) s_ck[nc] = 0;  // pad to an even count (0 beats nothing)
-            __syncthreads();
-            const ulonglong2 *c2 = (const ulonglong2 *)s_ck;
-            for (int a = threadIdx.x; a < nc; a += kTopNT) {
-                const uint64_t mine = s_ck[a];
-                int r = 0;
-#pragma unroll 4
-                for (int t2 = 0; t2 < (nc + 1) / 2; ++t2) {
-                    const ulonglong2 o = c2[t2];
-                    r += (o.x > mine) + (o.y > mine);
-                }
-                if (r < m) s_rows[r] = (int32_t)~(uint32_t)mine;
-            }
-            goto publish;
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) s_slot = 0;
-    }
-    {
-    // ---- general path: radix threshold, winners above it take any slot, ties in index order
-    int need = 0;
-    const uint32_t T = block_radix_threshold<kTopNT, 8, 4>(
-        [&](auto fn) { visit([&](int, uint32_t key, bool valid) { fn(key, valid); }); }, m, s_hist,
-        need);
-    visit([&](int j, uint32_t key, bool valid) {
-        if (valid && key > T) s_rows[atomicAdd(&s_slot, 1)] = j;
-    });
-    int ties_taken = 0;
-    const int base = m - need;
-    visit([&](int j, uint32_t key, bool valid) {
-        const int is_tie = (valid && key == T) ? 1 : 0;
-        int round_total;
-        const int rank = block_excl_scan<kTopNT>(is_tie, s_scan, round_total) + ties_taken;
-        if (is_tie && rank < need) s_rows[base + rank] = j;
-        ties_taken += round_total;
-    });
-    }
-publish:
+    select_top<kTopNT>(z + (size_t)blockIdx.x * C, C, m, sm);
     // the probed rows, and for every key range p the nsub + 1 block offsets of each probed row
     __syncthreads();
+    const int32_t *s_rows = sm.rows;
     if ((int)threadIdx.x < m) out[threadIdx.x] = sub * C + s_rows[threadIdx.x];
     const int bg = head / G;
     const int nb = nsub + 1;
@@ -472,15 +484,21 @@ void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off
 // ---------------------------------------------------------------------------------------------
 constexpr int kAccRows = 4;  // rows in flight per wave
 
-template <int NT>
+// SELF_TOP (one subspace, small launches): no launch of k_top_centroids came before - the workgroup
+// first picks the head's m best centroids from the scores z itself (every range's workgroup repeats
+// that choice; with few workgroups the repeated work is cheaper than a launch in the chain) and
+// looks up its block offsets in part_off; the workgroup of range 0 publishes the probed rows.
+template <int NT, bool SELF_TOP>
 __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ ent,
-                                                   const int32_t *__restrict__ rows,
+                                                   int32_t *__restrict__ rows,
                                                    const int32_t *__restrict__ spans,
                                                    uint32_t *__restrict__ cand_key,
                                                    uint16_t *__restrict__ bin_off,
                                                    int32_t *__restrict__ seg_cnt, int C, int Ls,
                                                    int m, int G, int P, size_t cand_stride,
-                                                   uint32_t key_lo, int key_sh, int excl_from)
+                                                   uint32_t key_lo, int key_sh, int excl_from,
+                                                   const float *__restrict__ z,
+                                                   const int32_t *__restrict__ part_off, int PO)
 {
     constexpr int NW = NT / kWave;
     constexpr int R = NT * 16;
@@ -493,10 +511,35 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     const int p = blockIdx.x, head = blockIdx.y;
     const int bg = head / G;
     const int wave = threadIdx.x / kWave, lane = lane_id();
+    if (SELF_TOP) {
+        static_assert(!SELF_TOP || sizeof(TopSmem<NT>) <= (size_t)R * 4, "the choice borrows the accumulators' memory");
+        static_assert(!SELF_TOP || 2 * NT >= 64 * NB, "two offsets per thread cover m * NB");
+        TopSmem<NT> &sm = *reinterpret_cast<TopSmem<NT> *>(s_acc);  // (the accumulators are not in use yet)
+        select_top<NT>(z + (size_t)head * C, C, m, sm);
+        __syncthreads();
+        const int my_row = (int)threadIdx.x < m ? sm.rows[threadIdx.x] : 0;
+        int32_t off[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int e = u * NT + (int)threadIdx.x;
+            const int r = e / NB, x = e - r * NB;
+            off[u] = e < m * NB ? part_off[((size_t)bg * C + sm.rows[r]) * PO + p * NSUB + x] : 0;
+        }
+        __syncthreads();  // (every thread has read the choice: the memory may be zeroed now)
+        if ((int)threadIdx.x < m) {
+            s_row[threadIdx.x] = my_row;
+            if (p == 0) rows[(size_t)head * m + threadIdx.x] = my_row;
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            if (u * NT + (int)threadIdx.x < m * NB) s_b[u * NT + threadIdx.x] = off[u];
+    }
     {
-        const int32_t *sp = spans + ((size_t)head * P + p) * m * NB;
-        for (int e = threadIdx.x; e < m * NB; e += NT) s_b[e] = sp[e];
-        if ((int)threadIdx.x < m) s_row[threadIdx.x] = rows[(size_t)head * m + threadIdx.x];
+        if (!SELF_TOP) {
+            const int32_t *sp = spans + ((size_t)head * P + p) * m * NB;
+            for (int e = threadIdx.x; e < m * NB; e += NT) s_b[e] = sp[e];
+            if ((int)threadIdx.x < m) s_row[threadIdx.x] = rows[(size_t)head * m + threadIdx.x];
+        }
         int4 *z4 = (int4 *)s_acc;
 #pragma unroll
         for (int u = 0; u < 4; ++u) z4[u * NT + threadIdx.x] = make_int4(0, 0, 0, 0);
@@ -644,28 +687,45 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     if (threadIdx.x == 0) seg_cnt[(size_t)head * P + p] = total;
 }
 
-void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *spans, uint32_t *cand_key,
+// does the accumulation launch choose the probed rows itself (no k_top_centroids launch)?
+bool accumulate_self_top(int n_heads, int S, int C, int tau, int R, int P)
+{
+    return S == 1 && R >= 4096 && (int64_t)n_heads * P <= 1024;
+}
+
+void launch_accumulate(const void *ent, int32_t *rows, const int32_t *spans, uint32_t *cand_key,
                        uint16_t *bin_off, int32_t *seg_cnt, int n_heads, int C,
                        int Ls, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
-                       int key_sh, int excl_from, hipStream_t st)
+                       int key_sh, int excl_from, const float *z, const int32_t *part_off, int PO,
+                       bool self_top, hipStream_t st)
 {
     dim3 grid(P, n_heads);
     static bool attr = false;
     if (!attr) {
-        (void)hipFuncSetAttribute((const void *)k_accumulate<1024>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        (void)hipFuncSetAttribute((const void *)k_accumulate<1024, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  16384 * 4);
+        (void)hipFuncSetAttribute((const void *)k_accumulate<1024, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   16384 * 4);
         attr = true;
     }
-#define CSA_ACC(NT_)                                                                              \
-    k_accumulate<NT_><<<grid, NT_, (size_t)R * 4, st>>>((const uint32_t *)ent, rows, spans, cand_key, \
-                                                        bin_off, seg_cnt, C, Ls, m, G, P,  \
-                                                        cand_stride, key_lo, key_sh, excl_from)
+#define CSA_ACC(NT_, SELF_)                                                                                \
+    k_accumulate<NT_, SELF_><<<grid, NT_, (size_t)R * 4, st>>>((const uint32_t *)ent, rows, spans, cand_key, \
+                                                               bin_off, seg_cnt, C, Ls, m, G, P, cand_stride, \
+                                                               key_lo, key_sh, excl_from, z, part_off, PO)
+    if (self_top) {  // (R >= 4096: see accumulate_self_top)
+        switch (R) {
+        case 4096: CSA_ACC(256, true); break;
+        case 8192: CSA_ACC(512, true); break;
+        default: CSA_ACC(1024, true); break;  // 16384
+        }
+        return;
+    }
     switch (R) {
-    case 1024: CSA_ACC(64); break;
-    case 2048: CSA_ACC(128); break;
-    case 4096: CSA_ACC(256); break;
-    case 8192: CSA_ACC(512); break;
-    default: CSA_ACC(1024); break;  // 16384
+    case 1024: CSA_ACC(64, false); break;
+    case 2048: CSA_ACC(128, false); break;
+    case 4096: CSA_ACC(256, false); break;
+    case 8192: CSA_ACC(512, false); break;
+    default: CSA_ACC(1024, false); break;  // 16384
     }
 #undef CSA_ACC
 }

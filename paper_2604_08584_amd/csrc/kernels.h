@@ -52,10 +52,14 @@ void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off
                           int n_heads, int C, int S, int tau, int G, int P, int nsub, int PO, hipStream_t st);
 // candidates of (head, key range): cand_key (words grouped by coarse score bin, best first),
 // bin_off[.][512] (start of every bin), seg_cnt (how many)
-void launch_accumulate(const void *ent, const int32_t *rows, const int32_t *spans, uint32_t *cand_key,
+// self_top (see accumulate_self_top): the launch also chooses the probed rows from z (no
+// launch_top_centroids before it; `spans` is not read, `rows` is written)
+bool accumulate_self_top(int n_heads, int S, int C, int tau, int R, int P);
+void launch_accumulate(const void *ent, int32_t *rows, const int32_t *spans, uint32_t *cand_key,
                        uint16_t *bin_off, int32_t *seg_cnt, int n_heads, int C,
                        int Ls, int m, int G, int R, int P, size_t cand_stride, uint32_t key_lo,
-                       int key_sh, int excl_from, hipStream_t st);
+                       int key_sh, int excl_from, const float *z, const int32_t *part_off, int PO,
+                       bool self_top, hipStream_t st);
 // seg_run[head][p] = where the threshold's bin starts and ends among the candidates of range p
 void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, const uint16_t *bin_off, int32_t *sel,
                       int32_t *sel_count, uint32_t *thr, void *seg_par, void *seg_run, int n_heads, int k,
