@@ -60,6 +60,7 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
     __shared__ float s_m[kAttWaves], s_l[kAttWaves], s_o[kAttWaves][kHeadDim];
     __shared__ uint32_t s_bits[EMIT ? 2 * kAttNT : 4];  // winners' and ties' bitmaps of the key range
     __shared__ int s_scan[kAttWaves + 1];
+    __shared__ int32_t s_list[EMIT ? kSplit : 1];  // the range's first winners (what one pass attends)
     // XCD-aware order: the chip deals consecutive workgroup ids round-robin to its 8 XCDs (each
     // with its own L2).  The G workgroups that handle the same split of the same KV head get ids
     // 8 apart: same XCD, same moment.
@@ -77,9 +78,11 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
     int first, count;
     if (from_sel && EMIT) {
         count = emit_range<kAttNT>(ea.cand_key, ea.seg_run, ea.seg_cnt, ea.thr, seg_par, sel, k, ea.R, P,
-                                   ea.cand_stride, head, s, s_bits, s_scan, first);
+                                   ea.cand_stride, head, s, s_bits, s_scan, first, s_list, kSplit);
         count = max(0, min(count, k - first));
-        __syncthreads();  // the indices just written are read back below by other threads
+        // the winners are read back below by other threads: the first kSplit from LDS (no wait for
+        // the stores to `sel`), any further ones - an unusually popular range - from `sel`
+        if (count > kSplit) __syncthreads(); else lds_barrier();
     } else if (from_sel) {
         const int n_sel = min(sel_count[head], k);
         first = min(seg_par[(size_t)head * P + s].x, n_sel);
@@ -119,7 +122,12 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
             const int t = u * kWave + lane;
             const int a = ((t >> 3) * kAttWaves + wave) * 8 + (t & 7);
             int key = 0;
-            if (a < rem) key = from_sel ? sel[(size_t)head * k + first + base + a] : first + base + a;
+            if (a < rem) {
+                if (EMIT && from_sel && base == 0)
+                    key = s_list[a];
+                else
+                    key = from_sel ? sel[(size_t)head * k + first + base + a] : first + base + a;
+            }
             if ((unsigned)key >= (unsigned)n) key = 0;  // never form an address from a bad index
             if (PAGED) {
                 const int page = block_table[(size_t)b * (max_ctx >> 4) + (key >> 4)];

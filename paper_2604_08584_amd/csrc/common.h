@@ -32,6 +32,15 @@ __device__ __forceinline__ uint32_t orderable(float f)
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
+// workgroup barrier that orders LDS accesses only: outstanding global loads and stores are not
+// waited for (what __syncthreads() would do)
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // number of set bits of `mask` below this lane
 __device__ __forceinline__ int mbcnt(uint64_t mask)
 {
@@ -238,6 +247,7 @@ constexpr int kThrShift = 22;  // score bits within a bin: < 2^18
 // requested before the threshold is known: they are almost always the ones needed.
 // All NT >= R/32 threads of the workgroup must call.  s_bits: 2 * R/32 words, s_scan: NT/64 + 1.
 // Returns the number of winners written (uniform); `first` = the range's first output slot.
+// s_list (optional, LDS): also receives the first list_cap winners, in the same order.
 // Ends with every thread past the last barrier but NOT with a barrier after the global writes.
 // ---------------------------------------------------------------------------------------------
 constexpr int kEmitPre = 2;  // candidate words per thread requested up front
@@ -249,7 +259,8 @@ __device__ __forceinline__ int emit_range(const uint32_t *__restrict__ cand_key,
                                           const uint32_t *__restrict__ thr,
                                           const int2 *__restrict__ seg_par, int32_t *__restrict__ sel,
                                           int k, int R, int P, size_t cand_stride, int head, int p,
-                                          uint32_t *s_bits, int *s_scan, int &first)
+                                          uint32_t *s_bits, int *s_scan, int &first,
+                                          int32_t *s_list = nullptr, int list_cap = 0)
 {
     const uint32_t *dk = cand_key + (size_t)head * cand_stride + (size_t)p * R;
     const int W = R / 32;
@@ -306,7 +317,9 @@ __device__ __forceinline__ int emit_range(const uint32_t *__restrict__ cand_key,
     int32_t *out = sel + (size_t)head * k;
     const int kbase = p * R + (int)threadIdx.x * 32;
     for (; bits; bits &= bits - 1) {
-        if (pos < k) out[pos] = kbase + __ffs(bits) - 1;
+        const int key = kbase + __ffs(bits) - 1;
+        if (pos < k) out[pos] = key;
+        if (pos - par.x < list_cap) s_list[pos - par.x] = key;  // (the caller's copy of the first winners)
         ++pos;
     }
     return total;

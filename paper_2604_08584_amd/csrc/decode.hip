@@ -22,6 +22,10 @@ __global__ __launch_bounds__(256) void k_score_centroids(const uint16_t *__restr
     const int bg = blockIdx.y;
     const int j = blockIdx.x * 256 + threadIdx.x;
     const uint4 *ct = cent_t + (size_t)bg * (kHeadDim / 8) * C;
+    // the centroid (requested before the queries are staged: one memory round trip, not two)
+    uint4 wv[kHeadDim / 8];
+#pragma unroll
+    for (int c = 0; c < kHeadDim / 8; ++c) wv[c] = j < C ? ct[(size_t)c * C + j] : make_uint4(0, 0, 0, 0);
     for (int h0 = 0; h0 < G; h0 += GH) {
         __syncthreads();
         for (int e = threadIdx.x; e < GH * kHeadDim; e += 256) {
@@ -33,9 +37,6 @@ __global__ __launch_bounds__(256) void k_score_centroids(const uint16_t *__restr
             float acc[GH];
 #pragma unroll
             for (int hh = 0; hh < GH; ++hh) acc[hh] = 0.0f;
-            uint4 wv[kHeadDim / 8];
-#pragma unroll
-            for (int c = 0; c < kHeadDim / 8; ++c) wv[c] = ct[(size_t)c * C + j];
 #pragma unroll
             for (int c = 0; c < kHeadDim / 8; ++c) {
                 const uint4 w = wv[c];
@@ -822,13 +823,36 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
         const int B = (kCoarseBins - 1) - top_bin;  // as the accumulation kernel numbers the bins
         int in_bin = (int)s_hist[top_bin];
         int want = k - above;  // how many of bin B's candidates are selected (>= 1)
-        for (int p = threadIdx.x; p < P; p += kThrNT) {
-            const int c = s_cnt[p];
-            const int b0 = c > 0 ? (int)bo[(size_t)p * kCoarseBins + B] : 0;
-            const int b1 = c > 0 ? (B + 1 < kCoarseBins ? (int)bo[(size_t)p * kCoarseBins + B + 1] : c) : 0;
-            s_beg[p] = (uint16_t)b0;
-            s_end[p] = (uint16_t)b1;
-            s_gt[p] = b0;  // every candidate of a better bin
+        if (P <= 2 * NW) {
+            // every range's offsets are still in the registers of the wave that loaded them: the
+            // lane that holds bin B hands out the run, no second trip to memory
+            for (int it = 0; it < 2; ++it) {
+                const int p = wave + it * NW;
+                if (p >= P) break;
+                const uint4 v = it == 0 ? hpre0 : hpre1;
+                uint32_t nxt = (uint32_t)__shfl_down((int)(v.x & 0xFFFFu), 1, kWave);
+                if (lane == kWave - 1) nxt = (uint32_t)s_cnt[p];
+                if (lane == (B >> 3)) {
+                    const uint32_t o[9] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16, v.z & 0xFFFFu,
+                                           v.z >> 16, v.w & 0xFFFFu, v.w >> 16, nxt};
+                    uint32_t b0 = o[0], b1 = o[1];
+#pragma unroll
+                    for (int i = 1; i < 8; ++i)
+                        if ((B & 7) == i) { b0 = o[i]; b1 = o[i + 1]; }
+                    s_beg[p] = (uint16_t)b0;
+                    s_end[p] = (uint16_t)b1;
+                    s_gt[p] = (int)b0;  // every candidate of a better bin
+                }
+            }
+        } else {
+            for (int p = threadIdx.x; p < P; p += kThrNT) {
+                const int c = s_cnt[p];
+                const int b0 = c > 0 ? (int)bo[(size_t)p * kCoarseBins + B] : 0;
+                const int b1 = c > 0 ? (B + 1 < kCoarseBins ? (int)bo[(size_t)p * kCoarseBins + B + 1] : c) : 0;
+                s_beg[p] = (uint16_t)b0;
+                s_end[p] = (uint16_t)b1;
+                s_gt[p] = b0;  // every candidate of a better bin
+            }
         }
         __syncthreads();
         // runs(fn, seg_end): fn(score within the bin, valid, p) for the candidates of bin B of every
