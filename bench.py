@@ -61,6 +61,12 @@ def main():
     ap.add_argument("--row-gather-floor", action="store_true",
                     help="also time bench_aids/row_gather_probe.hip (bare fetches of K and V rows) over the distinct "
                          "rows the last step's attention had to read, and report it as row_gather_floor")
+    ap.add_argument("--graph-iters", type=int, default=8,
+                    help="also time the steps as replays of a captured HIP graph of this many iterations "
+                         "(csa_decode_step_append_replayable); 0 = off")
+    ap.add_argument("--also", default="auto",
+                    help="a second workload measured in the same process and reported under 'also' "
+                         "(auto = cfg2 when the main workload is cfg4; none = off)")
     ap.add_argument("--two-calls", action="store_true",
                     help="csa_decode_step then csa_append_kv instead of the one-call csa_decode_step_append")
     args = ap.parse_args()
@@ -72,15 +78,46 @@ def main():
 
     import torch
     from paper_2604_08584_amd import binding
-    from paper_2604_08584_amd.workload import (CONFIGS, algorithmic_bytes_per_head, make_inputs,
-                                                 paginate)
+    from paper_2604_08584_amd.workload import CONFIGS
     binding.lib()  # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
-    dev = "cuda"
-    base = CONFIGS[args.config]
     if args.cluster:
-        return cluster_bench(args, base)
-    K, W = args.steps, args.warmup
+        return cluster_bench(args, CONFIGS[args.config])
+    result = decode_bench(args, args.config, args.steps, args.warmup, not args.no_cpu_baseline)
+    # the other headline configuration of the metric (batch 1 at 128K next to batch 8), in the same
+    # process, after the first one's buffers are gone; config.workload stays the first one
+    also = args.also if args.also != "auto" else ("cfg2" if args.config == "cfg4" else "none")
+    plain = (args.search_period == 1 and args.keep_ratio == 0 and args.stream_window == 0)
+    if also != "none" and also != args.config and plain:
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        r2 = decode_bench(args, also, min(args.steps, CONFIGS[also].steps), args.warmup, False)
+        keep = ("value", "unit", "steps", "warmup", "ms_per_step", "config", "tokens_per_s", "step_algorithmic_bytes",
+                "step_hbm_gbps", "step_frac_of_peak", "step_us_percentiles", "host_issue_us_per_step", "graph_replay_us_per_step", "stage_us",
+                "search_us", "roofline", "footprint")
+        result["also"] = {also: {k_: r2[k_] for k_ in keep if k_ in r2}}
+    print(json.dumps(result, ensure_ascii=False), flush=True)
+
+
+def source_sha():
+    """Hash of the kernel sources: a stored counter figure is only quoted for the kernels it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2604_08584_amd", "csrc")
+    for f in ("attention.hip", "common.h"):
+        h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:12]
+
+
+def decode_bench(args, name, K, W, with_cpu):
+    """One workload: K timed steps after W warm-up steps; returns the result dictionary."""
+    import torch
+    from paper_2604_08584_amd import binding
+    from paper_2604_08584_amd.workload import (CONFIGS, algorithmic_bytes_per_head, make_inputs,
+                                                 paginate)
+    dev = "cuda"
+    base = CONFIGS[name]
     streaming = args.stream_window > 0
     # with streaming updates the tables keep the appended keys, so the context cannot be rewound
     # after the warm-up: the timed steps simply continue from there
@@ -166,6 +203,36 @@ def main():
     us_per_step = elapsed / K * 1e6
     sel_mean = float(ctx.sel_count.float().mean().item())
 
+    # ---- the same K steps as replays of a captured HIP graph of `graph_iters` iterations
+    # (csa_decode_step_append_replayable: the position lives on the device), each iteration of the
+    # graph with its own query, so the host issues one launch per graph_iters steps
+    graph_us = None
+    gi = args.graph_iters
+    if gi > 0 and period == 1 and not streaming and not args.two_calls and K >= gi:
+        reset()
+        run(1)                      # (first-use paths run outside the capture)
+        reset()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(g, stream=side):
+            for t in range(gi):
+                ctx.decode_step_append_replayable(q_steps[w.pre_appended + t], k_new[w.pre_appended + t],
+                                                  v_new[w.pre_appended + t])
+        reset()                     # (the capture advanced the host-side count only)
+        for _ in range(max(1, W // gi)):
+            g.replay()
+        reset()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K // gi):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) / (K // gi * gi) * 1e6
+        binding.csa_sync_context_len(ctx.ctx)
+        del g
+
     # ---- per-step latency spread: an event pair around every step of one more pass (the library
     # launches on torch's current stream, so torch events bracket its kernels); streaming runs,
     # which cannot replay their steps, skip it
@@ -200,20 +267,64 @@ def main():
     n_search = (K + period - 1) // period
     step_bytes = B * Hq * ((per_head["centroids"] + per_head["table_rows"]) * n_search / K
                            + per_head["kv_rows"] + per_head["io"])
-    # dominant kernel = the gathered attention: K and V rows, q, the selected indices
-    att_bytes = B * Hq * (per_head["kv_rows"] + w.head_dim * 2 + w.k * 4)
+    # dominant kernel = the gathered attention.  Its algorithmic bytes: the K and V rows it must fetch
+    # - per (sequence, KV head) the UNION of the rows its G query heads attend, counted live from the
+    # index sets of the last step (a row picked by several heads of the group has to come from HBM
+    # once) - plus q and the index lists.  The per-head sum (every head's rows counted separately, so
+    # a shared row counts G times) is reported beside it as per_head_*: it can exceed the HBM peak.
     att_us = stage_us["attention_split"]
+    n_now = binding.csa_context_len(ctx.ctx)[1]
+    ws_now = max(0, n_now - args.stream_window) if streaming else w.n_pre
+    sel_l = ctx.sel.view(B, Hkv, G * max(w.k, 1)).long()
+    need = torch.zeros(B, Hkv, w.max_ctx + 1, dtype=torch.bool, device=dev)
+    if w.k:
+        need.scatter_(2, torch.where(sel_l >= 0, sel_l, torch.full_like(sel_l, w.max_ctx)), True)
+    need[:, :, w.max_ctx] = False
+    distinct_sel = int(need.sum().item())
+    sum_sel = int(ctx.sel_count.sum().item())
+    del need, sel_l
+    # (the window of the last step is the largest of the run; scaled to the run's mean window)
+    share = distinct_sel / max(sum_sel, 1)               # distinct / per-head selected rows
+    rows_per_head = w.k * share + t_mean / G
+    att_bytes = B * Hq * (2 * rows_per_head * w.head_dim * 2 + w.head_dim * 2 + w.k * 4)
+    per_head_bytes = B * Hq * (per_head["kv_rows"] + w.head_dim * 2 + w.k * 4)
     achieved = att_bytes / (att_us * 1e-6) / 1e9
-    traffic = None
+    traffic = traffic_src = None
     tf = os.path.join(ROOT, "profiles", f"attention_split_{w.name}_hbm_traffic.txt")
-    if os.path.exists(tf) and period == 1 and args.keep_ratio == 0:
-        mt = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(tf).read())
-        traffic = float(mt.group(1)) if mt else None
+    if os.path.exists(tf) and period == 1 and args.keep_ratio == 0 and not streaming:
+        txt = open(tf).read()
+        mt = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", txt)
+        ms = re.search(r"kernel_source_sha:\s*([0-9a-f]+)", txt)
+        if mt and ms and ms.group(1) == source_sha():
+            traffic = float(mt.group(1))
+            traffic_src = f"profiles/{os.path.basename(tf)} (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; kernel sources {ms.group(1)})"
+        else:
+            traffic_src = (f"profiles/{os.path.basename(tf)} was taken on other kernel sources "
+                           f"({ms.group(1) if ms else 'unstamped'} != {source_sha()}): not quoted")
     roofline = dict(kernel="k_attention_split", bound="hbm", achieved=round(achieved, 1),
                     peak=PEAK_HBM_GBPS, unit="GB/s", frac=round(achieved / PEAK_HBM_GBPS, 4),
-                    traffic=traffic, algorithmic_bytes_per_launch=int(att_bytes),
+                    traffic=traffic, traffic_source=traffic_src,
+                    algorithmic_bytes_per_launch=int(att_bytes),
+                    algorithmic_bytes_are="K/V rows of the union of the G heads' index sets per KV head "
+                                          "(counted from the last step's sel) + window rows + q + index lists",
+                    distinct_over_per_head_rows=round(share, 4),
+                    per_head_bytes_per_launch=int(per_head_bytes),
+                    per_head_gbps=round(per_head_bytes / (att_us * 1e-6) / 1e9, 1),
                     avg_launch_us=round(att_us, 2),
                     measured="HIP events around each launch, second pass over the same steps")
+    if traffic:
+        roofline["traffic_gbps"] = round(traffic / (att_us * 1e-6) / 1e9, 1)
+        roofline["traffic_frac"] = round(traffic / (att_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4)
+    search = ("score_centroids", "top_centroids", "accumulate", "select_threshold", "select_emit")
+    # table footprint against the K/V cache (the paper's memory-footprint appendix: 3 S C alpha / (2 d)
+    # with 6-byte entries; the device entry here is 4 bytes, the canonical export 8)
+    tb, _ = binding.csa_workspace_bytes(ctx.ctx)
+    kv_bytes = 2 * B * Hkv * w.n_pre * w.head_dim * 2
+    alpha = w.L / w.n_pre
+    footprint = dict(tables_bytes=int(tb), kv_bytes_at_n_pre=int(kv_bytes), tables_over_kv=round(tb / kv_bytes, 4),
+                     paper_formula_6B=round(3 * w.n_sub * w.C * alpha / (2 * w.head_dim), 4),
+                     same_formula_4B_entries=round(2 * w.n_sub * w.C * alpha / (2 * w.head_dim), 4),
+                     note="tables_bytes also holds the centroids and the per-row block offsets")
 
     result = {
         "metric": "decode-step latency (µs) and achieved HBM GB/s at 128K ctx, 95% sparsity",
@@ -234,11 +345,15 @@ def main():
                    "calls_per_step": "csa_decode_step + csa_append_kv" if args.two_calls else "csa_decode_step_append"},
         "tokens_per_s": round(B / (us_per_step * 1e-6), 1),
         "step_algorithmic_bytes": int(step_bytes),
+        "step_algorithmic_bytes_are": "per query head (rows shared by the heads of a KV head counted per head)",
         "step_hbm_gbps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
         "step_frac_of_peak": round(step_bytes / (us_per_step * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
         "step_us_percentiles": step_pct,
         "host_issue_us_per_step": round(issued / K * 1e6, 2),
+        "graph_replay_us_per_step": None if graph_us is None else round(graph_us, 2),
         "stage_us": {k_: round(v, 2) for k_, v in stage_us.items()},
+        "search_us": round(sum(stage_us.get(k_, 0.0) for k_ in search), 2),
+        "footprint": footprint,
         "build_tables_s": round(t_build, 2),
         "roofline": roofline,
     }
@@ -248,9 +363,10 @@ def main():
     if streaming:
         result["config"]["stream_window"] = args.stream_window
         binding.csa_streaming_status(ctx.ctx)
-    if not args.no_cpu_baseline and not streaming:
+    if with_cpu and not streaming:
         result["cpu_baseline"] = cpu_baseline(ctx, w, inp, args.cpu_seconds)
-    print(json.dumps(result, ensure_ascii=False), flush=True)
+    ctx.close()
+    return result
 
 
 def row_gather_floor(ctx, w, k_store, v_store, bt, att_us, reps=20):

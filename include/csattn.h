@@ -23,10 +23,11 @@
  *   - bf16 = the upper 16 bits of an IEEE fp32.  Inputs must be finite.
  *   - A ctx is not thread-safe; calls on one ctx must be issued from one thread at a time and
  *     on streams that are ordered with respect to each other.
- *   - csa_decode_step and csa_decode_step_reuse only launch kernels on `stream` (no allocation,
- *     no synchronisation, no memset or copy nodes), so they may be captured into a HIP graph and
- *     replayed while the context length stays as captured; calls that append bake the position
- *     into their launches and are not replayable.
+ *   - csa_decode_step, csa_decode_step_static and csa_decode_step_reuse only launch kernels on
+ *     `stream` (no allocation, no synchronisation, no memset or copy nodes), so they may be captured
+ *     into a HIP graph and replayed while the context length stays as captured; csa_append_kv and
+ *     csa_decode_step_append bake the position into their launches and are not replayable -
+ *     csa_decode_step_append_replayable is the form of a whole iteration that is.
  */
 #ifndef CSATTN_H
 #define CSATTN_H
@@ -253,14 +254,39 @@ int csa_decode_step_append(csa_ctx *ctx, const void *q_dev, const void *k_new_de
                            float *out_dev, int32_t *sel_idx_dev, int32_t *sel_count_dev, int32_t reuse,
                            void *stream);
 
+/*
+ * csa_decode_step_append in a form that a HIP graph can replay, one decode iteration (Sec. 3.3
+ * (1)-(5)) per replay: no launch argument depends on the context length.  The library keeps a copy
+ * of the context length in a word of the tables buffer (every appending call advances it); these
+ * launches read the position there, attend the window [n_pre, n) it implies, write row n and
+ * advance the word themselves, and their grids are sized for a full context (max_ctx - n_pre window
+ * keys), so the same launches are right for every later position.  Same arguments and results as
+ * csa_decode_step_append; q_dev, k_new_dev, v_new_dev, out_dev and the sel buffers are read and
+ * written in place by every replay (refill the inputs between replays).  Only kernels are enqueued:
+ * no allocation, no synchronisation, no memset or copy nodes.  Not available with streaming updates
+ * (stream_window > 0: CSA_ERR_ARG).
+ * The host-side count (csa_context_len, the capacity checks of the other calls) follows the CALLS
+ * made on the context, not the replays of a graph: call csa_sync_context_len after capturing and
+ * after replaying, before any other call that depends on the position.  A replay on a full context
+ * appends nothing, leaves the count alone and is reported by csa_sync_context_len.
+ */
+int csa_decode_step_append_replayable(csa_ctx *ctx, const void *q_dev, const void *k_new_dev,
+                                      const void *v_new_dev, float *out_dev, int32_t *sel_idx_dev,
+                                      int32_t *sel_count_dev, int32_t reuse, void *stream);
+/* SYNCHRONISES `stream`, sets the host-side context length to the device's count and returns
+ * CSA_ERR_CAPACITY if a replayed append found the context full since the tables were built or the
+ * length was last set, else CSA_OK. */
+int csa_sync_context_len(csa_ctx *ctx, void *stream);
+
 /* Streaming updates only: SYNCHRONISES `stream` and returns CSA_ERR_RANGE if a streamed key's
  * score did not fit the score grid since the tables were built (it was clamped), else CSA_OK. */
 int csa_streaming_status(csa_ctx *ctx, void *stream);
 
 /* Host-side counters: prefill length and current context length. */
 int csa_context_len(const csa_ctx *ctx, int32_t *n_pre, int32_t *n);
-/* Rewind / set the context length to n in [n_pre, max_ctx] (rows >= n are simply ignored).
- * With streaming updates the tables hold the appended keys: CSA_ERR_STATE unless n is unchanged. */
+/* Rewind / set the context length to n in [n_pre, max_ctx] (rows >= n are simply ignored), on the
+ * host and - with a blocking copy - in the device's word.  With streaming updates the tables hold
+ * the appended keys: CSA_ERR_STATE unless n is unchanged. */
 int csa_set_context_len(csa_ctx *ctx, int32_t n);
 /* The grid exponent F in use (valid after build/import). */
 int csa_score_frac_bits(const csa_ctx *ctx, int32_t *frac_bits);

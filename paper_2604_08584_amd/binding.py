@@ -56,6 +56,8 @@ def lib() -> C.CDLL:
         "csa_static_scratch_bytes": (C.c_int, [vp, C.POINTER(sz), C.POINTER(sz)]),
         "csa_decode_step_reuse": (C.c_int, [vp, vp, vp, vp, vp, vp]),
         "csa_decode_step_append": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, i32, vp]),
+        "csa_decode_step_append_replayable": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, i32, vp]),
+        "csa_sync_context_len": (C.c_int, [vp, vp]),
         "csa_streaming_status": (C.c_int, [vp, vp]),
         "csa_context_len": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
         "csa_set_context_len": (C.c_int, [vp, i32]),
@@ -78,7 +80,8 @@ EXPORTED = ("csa_create", "csa_destroy", "csa_workspace_bytes", "csa_bind", "csa
             "csa_cluster_workspace_bytes", "csa_cluster_queries",
             "csa_export_tables", "csa_import_tables", "csa_append_kv", "csa_decode_step",
             "csa_decode_step_static", "csa_static_scratch_bytes",
-            "csa_decode_step_reuse", "csa_decode_step_append", "csa_streaming_status",
+            "csa_decode_step_reuse", "csa_decode_step_append", "csa_decode_step_append_replayable",
+            "csa_sync_context_len", "csa_streaming_status",
             "csa_context_len", "csa_set_context_len", "csa_score_frac_bits",
             "csa_last_probed_rows", "csa_profile_enable", "csa_profile_read", "csa_stage_name",
             "csa_strerror", "csa_last_hip_error")
@@ -201,6 +204,16 @@ def csa_decode_step_append(ctx, q, k_new, v_new, out, sel_idx=None, sel_count=No
            "csa_decode_step_append")
 
 
+def csa_decode_step_append_replayable(ctx, q, k_new, v_new, out, sel_idx=None, sel_count=None, reuse=False):
+    _check(lib().csa_decode_step_append_replayable(ctx, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _ptr(sel_idx),
+                                                   _ptr(sel_count), int(bool(reuse)), _stream()),
+           "csa_decode_step_append_replayable")
+
+
+def csa_sync_context_len(ctx):
+    _check(lib().csa_sync_context_len(ctx, _stream()), "csa_sync_context_len")
+
+
 def csa_streaming_status(ctx):
     _check(lib().csa_streaming_status(ctx, _stream()), "csa_streaming_status")
 
@@ -282,6 +295,12 @@ class Context:
     def decode_step_append(self, q, k_new, v_new):
         """decode_step followed by append_kv, in one call."""
         csa_decode_step_append(self.ctx, q, k_new, v_new, self.out, self.sel, self.sel_count, False)
+        return self.out, self.sel, self.sel_count
+
+    def decode_step_append_replayable(self, q, k_new, v_new, reuse=False):
+        """decode_step_append in the form a HIP graph can replay (position read on the device)."""
+        csa_decode_step_append_replayable(self.ctx, q, k_new, v_new, self.out,
+                                          None if reuse else self.sel, None if reuse else self.sel_count, reuse)
         return self.out, self.sel, self.sel_count
 
     def decode_step_reuse_append(self, q, k_new, v_new, sel=None, sel_count=None):

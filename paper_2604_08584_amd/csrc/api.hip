@@ -38,7 +38,8 @@ struct Region {
 struct Layout {
     // tables buffer
     Region cent_t, ent, part_off, row_cnt, row_min, blk_min;  // (the last three: streaming updates only)
-    Region state;  // persistent device words: [0] = a streamed score was clamped since the build
+    Region state;  // persistent device words: [0] = a streamed score was clamped since the build,
+                   // [1] = the context length as the device knows it, [2] = a replayed append found the context full
     size_t tables_bytes = 0;
     // scratch buffer: what a decode step uses comes first (decode_bytes), then what only the table
     // build and the streaming insertion use
@@ -256,6 +257,17 @@ void set_key_range(csa_ctx *ctx, int qabs_max)
     ctx->key_sh = sh;
 }
 
+int32_t *n_word(csa_ctx *ctx) { return at<int32_t>(ctx->tables, ctx->lay.state) + 1; }
+int32_t *full_word(csa_ctx *ctx) { return at<int32_t>(ctx->tables, ctx->lay.state) + 2; }
+
+// the device's copy of the context length (set-up paths only: the copy is synchronous)
+int set_device_count(csa_ctx *ctx, int n)
+{
+    const int32_t words[2] = {n, 0};  // (count, no refused append)
+    const hipError_t e = hipMemcpy(n_word(ctx), words, 8, hipMemcpyHostToDevice);
+    return e == hipSuccess ? CSA_OK : hip_fail(ctx, e);
+}
+
 int window_start(const csa_ctx *ctx)
 {
     if (ctx->cfg.stream_window <= 0) return ctx->n_pre;
@@ -416,6 +428,8 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
                               (int64_t)BG * S * c.n_centroids, l.Ls, ctx->PO, st);
     ctx->F = F;
     ctx->n_pre = ctx->n = n_pre;
+    rc = set_device_count(ctx, n_pre);
+    if (rc != CSA_OK) return rc;
     ctx->have_tables = true;
     return CSA_OK;
 }
@@ -502,6 +516,8 @@ int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *id
                               at<int32_t>(ctx->tables, l.blk_min), n_rows, l.Ls, ctx->PO, st);
     ctx->F = c.score_frac_bits;
     ctx->n_pre = ctx->n = n_pre;
+    rc = set_device_count(ctx, n_pre);
+    if (rc != CSA_OK) return rc;
     ctx->have_tables = true;
     return CSA_OK;
 }
@@ -543,7 +559,7 @@ void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, hipStream_t st)
 // the split merge that ends a step; with k_new/v_new also the append of row n (same launch) and,
 // with streaming updates, the try-insert
 void finish_step(csa_ctx *ctx, Prof &prof, const float *part, float *out_dev, int S, const void *k_new_dev,
-                 const void *v_new_dev, hipStream_t st)
+                 const void *v_new_dev, bool replayable, hipStream_t st)
 {
     const csa_config &c = ctx->cfg;
     const int BH = c.batch * c.n_q_heads;
@@ -554,7 +570,8 @@ void finish_step(csa_ctx *ctx, Prof &prof, const float *part, float *out_dev, in
     }
     const bool streaming = c.stream_window > 0;
     csa::launch_attention_merge_append(part, out_dev, BH, S, ctx->k_cache, ctx->v_cache, ctx->block_table,
-                                       k_new_dev, v_new_dev, c.batch, c.n_kv_heads, ctx->n, c.max_ctx, st);
+                                       k_new_dev, v_new_dev, c.batch, c.n_kv_heads, ctx->n, c.max_ctx, n_word(ctx),
+                                       full_word(ctx), replayable, st);
     prof.end(6);
     if (streaming) run_insert(ctx, prof, k_new_dev, st);
     ctx->n += 1;
@@ -573,7 +590,7 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
     const bool streaming = c.stream_window > 0;
     prof.mark(7);
     csa::launch_append(ctx->k_cache, ctx->v_cache, ctx->block_table, k_new_dev, v_new_dev, c.batch,
-                       c.n_kv_heads, ctx->n, c.max_ctx, st);
+                       c.n_kv_heads, ctx->n, c.max_ctx, n_word(ctx), st);
     prof.end(7);
     if (streaming) run_insert(ctx, prof, k_new_dev, st);
     ctx->n += 1;
@@ -584,12 +601,16 @@ namespace {
 
 // `scr`: the scratch memory of this step, laid out as Layout says (the bound scratch buffer, or
 // the library's own static array)
+// replayable: no launch argument depends on the context length - the kernels read the device's
+// count, the window splits are sized for a full context (streaming updates excluded)
 int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
-                int32_t *sel_count_dev, const void *k_new_dev, const void *v_new_dev, void *stream)
+                int32_t *sel_count_dev, const void *k_new_dev, const void *v_new_dev, bool replayable,
+                void *stream)
 {
     if (!ctx || !q_dev || !out_dev) return CSA_ERR_ARG;
     if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
     if (k_new_dev && ctx->n >= ctx->cfg.max_ctx) return CSA_ERR_CAPACITY;
+    if (replayable && ctx->cfg.stream_window > 0) return CSA_ERR_ARG;
     const csa_config &c = ctx->cfg;
     const Layout &l = ctx->lay;
     hipStream_t st = (hipStream_t)stream;
@@ -609,7 +630,8 @@ int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int3
     // the always-attended recent window [ws, n): every appended key, or - with streaming updates -
     // the last stream_window positions (older appended keys compete through the tables)
     const int ws = window_start(ctx);
-    const int S = csa::attention_splits(c.budget_k, ctx->P, ctx->n - ws);
+    const int S = csa::attention_splits(c.budget_k, ctx->P, (replayable ? c.max_ctx : ctx->n) - ws);
+    const int32_t *n_dev = replayable ? n_word(ctx) : nullptr;
 
     Prof prof(ctx, st);
     prof.mark(0);
@@ -658,9 +680,9 @@ int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int3
     csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table, sel, sel_count, seg_par,
                                 part, c.batch, c.n_q_heads, c.n_kv_heads, c.budget_k, ws, ctx->n,
                                 c.max_ctx, S, ctx->P, fused ? cand_key : nullptr, seg_run, cand_cnt, thr,
-                                ctx->R, l.cand_keys, st);
+                                ctx->R, l.cand_keys, n_dev, st);
     prof.end(5);
-    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, st);
+    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, replayable, st);
     ctx->last_sel = sel;
     ctx->last_scratch = scr;
     ctx->last_sel_count = sel_count;
@@ -668,9 +690,11 @@ int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int3
 }
 
 int reuse_step(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *sel_idx_dev,
-               const int32_t *sel_count_dev, const void *k_new_dev, const void *v_new_dev, void *stream)
+               const int32_t *sel_count_dev, const void *k_new_dev, const void *v_new_dev, bool replayable,
+               void *stream)
 {
     if (!ctx || !q_dev || !out_dev) return CSA_ERR_ARG;
+    if (replayable && ctx->cfg.stream_window > 0) return CSA_ERR_ARG;
     if ((sel_idx_dev == nullptr) != (sel_count_dev == nullptr)) return CSA_ERR_ARG;
     if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
     if (k_new_dev && ctx->n >= ctx->cfg.max_ctx) return CSA_ERR_CAPACITY;
@@ -684,7 +708,7 @@ int reuse_step(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *s
     void *seg_par = at<void>(ctx->scratch, l.seg_par);
     float *part = at<float>(ctx->scratch, l.part);
     const int ws = window_start(ctx);
-    const int S = csa::attention_splits(c.budget_k, ctx->P, ctx->n - ws);
+    const int S = csa::attention_splits(c.budget_k, ctx->P, (replayable ? c.max_ctx : ctx->n) - ws);
     Prof prof(ctx, st);
     prof.mark(8);
     csa::launch_range_offsets(sel, sel_count, seg_par, BH, c.budget_k, ctx->R, ctx->P, st);
@@ -693,9 +717,9 @@ int reuse_step(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *s
     csa::launch_attention_split(q_dev, ctx->k_cache, ctx->v_cache, ctx->block_table,
                                 const_cast<int32_t *>(sel), sel_count, seg_par, part, c.batch, c.n_q_heads,
                                 c.n_kv_heads, c.budget_k, ws, ctx->n, c.max_ctx, S, ctx->P, nullptr, nullptr,
-                                nullptr, nullptr, ctx->R, l.cand_keys, st);
+                                nullptr, nullptr, ctx->R, l.cand_keys, replayable ? n_word(ctx) : nullptr, st);
     prof.end(5);
-    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, st);
+    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, replayable, st);
     return check_launch(ctx);
 }
 
@@ -704,7 +728,7 @@ int reuse_step(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *s
 int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
                     int32_t *sel_count_dev, void *stream)
 {
-    return search_step(ctx, ctx ? ctx->scratch : nullptr, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, stream);
+    return search_step(ctx, ctx ? ctx->scratch : nullptr, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, false, stream);
 }
 
 int csa_decode_step_static(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
@@ -715,7 +739,7 @@ int csa_decode_step_static(csa_ctx *ctx, const void *q_dev, float *out_dev, int3
     char *scr = nullptr;
     const int rc = static_scratch(ctx, &scr);
     if (rc != CSA_OK) return rc;
-    return search_step(ctx, scr, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, stream);
+    return search_step(ctx, scr, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, false, stream);
 }
 
 int csa_static_scratch_bytes(const csa_ctx *ctx, size_t *needed, size_t *capacity)
@@ -729,7 +753,7 @@ int csa_static_scratch_bytes(const csa_ctx *ctx, size_t *needed, size_t *capacit
 int csa_decode_step_reuse(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *sel_idx_dev,
                           const int32_t *sel_count_dev, void *stream)
 {
-    return reuse_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, stream);
+    return reuse_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, nullptr, nullptr, false, stream);
 }
 
 int csa_decode_step_append(csa_ctx *ctx, const void *q_dev, const void *k_new_dev, const void *v_new_dev,
@@ -737,8 +761,32 @@ int csa_decode_step_append(csa_ctx *ctx, const void *q_dev, const void *k_new_de
                            void *stream)
 {
     if (!k_new_dev || !v_new_dev) return CSA_ERR_ARG;
-    return reuse ? reuse_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev, v_new_dev, stream)
-                 : search_step(ctx, ctx ? ctx->scratch : nullptr, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev, v_new_dev, stream);
+    return reuse ? reuse_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev, v_new_dev, false, stream)
+                 : search_step(ctx, ctx ? ctx->scratch : nullptr, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev,
+                               v_new_dev, false, stream);
+}
+
+int csa_decode_step_append_replayable(csa_ctx *ctx, const void *q_dev, const void *k_new_dev,
+                                      const void *v_new_dev, float *out_dev, int32_t *sel_idx_dev,
+                                      int32_t *sel_count_dev, int32_t reuse, void *stream)
+{
+    if (!k_new_dev || !v_new_dev) return CSA_ERR_ARG;
+    return reuse ? reuse_step(ctx, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev, v_new_dev, true, stream)
+                 : search_step(ctx, ctx ? ctx->scratch : nullptr, q_dev, out_dev, sel_idx_dev, sel_count_dev, k_new_dev,
+                               v_new_dev, true, stream);
+}
+
+int csa_sync_context_len(csa_ctx *ctx, void *stream)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;
+    int32_t words[2] = {0, 0};
+    hipError_t e = hipMemcpyAsync(words, n_word(ctx), 8, hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    if (words[0] < ctx->n_pre || words[0] > ctx->cfg.max_ctx) return CSA_ERR_STATE;  // (the word was overwritten)
+    ctx->n = words[0];
+    return words[1] ? CSA_ERR_CAPACITY : CSA_OK;
 }
 
 int csa_streaming_status(csa_ctx *ctx, void *stream)
@@ -770,7 +818,7 @@ int csa_set_context_len(csa_ctx *ctx, int32_t n)
     if (n < ctx->n_pre || n > ctx->cfg.max_ctx) return CSA_ERR_ARG;
     if (ctx->cfg.stream_window > 0 && n != ctx->n) return CSA_ERR_STATE;  // the tables hold the appended keys
     ctx->n = n;
-    return CSA_OK;
+    return ctx->bound ? set_device_count(ctx, n) : CSA_OK;
 }
 
 int csa_score_frac_bits(const csa_ctx *ctx, int32_t *frac_bits)

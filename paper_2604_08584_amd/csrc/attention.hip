@@ -55,8 +55,11 @@ __global__ __launch_bounds__(kAttNT) void k_attention_split(
     const int32_t *__restrict__ block_table, int32_t *__restrict__ sel,
     const int32_t *__restrict__ sel_count, const int2 *__restrict__ seg_par,
     float *__restrict__ part, int k, int n_pre, int n, int Hq, int G, int Hkv, int max_ctx, int S,
-    int P, int P_sel, int n_units, float qscale, EmitArgs ea)
+    int P, int P_sel, int n_units, float qscale, EmitArgs ea, const int32_t *__restrict__ n_dev)
 {
+    // a replayable launch has no context length among its arguments: it reads the device's count
+    // (and was sized for the longest window, so some window splits may be empty)
+    if (n_dev) n = min(*n_dev, max_ctx);
     __shared__ float s_m[kAttWaves], s_l[kAttWaves], s_o[kAttWaves][kHeadDim];
     __shared__ uint32_t s_bits[EMIT ? 2 * kAttNT : 4];  // winners' and ties' bitmaps of the key range
     __shared__ int s_scan[kAttWaves + 1];
@@ -264,19 +267,25 @@ struct AppendArgs {
     const int32_t *block_table;
     const uint16_t *kn, *vn;
     int n, Hkv, max_ctx;
+    // the context length as the device knows it (a word of the tables buffer) and the word that
+    // records an append refused on the device.  from_dev: the position is read there instead of
+    // taken from `n` (a launch that can be replayed), and n_bg rows are appended by one workgroup,
+    // which then advances the count; otherwise the count is set to n + 1.
+    int32_t *n_word, *full_word;
+    int from_dev, n_bg;
 };
 
 template <bool PAGED>
-__device__ __forceinline__ void append_row(const AppendArgs &a, int bg, int t)
+__device__ __forceinline__ void append_row(const AppendArgs &a, int n, int bg, int t)
 {
     // row n of (sequence, KV head) bg: 16 lanes copy K, 16 lanes V, 16 bytes each
     const int b = bg / a.Hkv, g = bg % a.Hkv;
     int64_t row;
     if (PAGED) {
-        const int page = a.block_table[(size_t)b * (a.max_ctx >> 4) + (a.n >> 4)];
-        row = ((int64_t)page * a.Hkv + g) * 16 + (a.n & 15);
+        const int page = a.block_table[(size_t)b * (a.max_ctx >> 4) + (n >> 4)];
+        row = ((int64_t)page * a.Hkv + g) * 16 + (n & 15);
     } else {
-        row = (int64_t)bg * a.max_ctx + a.n;
+        row = (int64_t)bg * a.max_ctx + n;
     }
     const int c = t & 15;
     const uint16_t *src = (t < 16 ? a.kn : a.vn) + (size_t)bg * kHeadDim + c * 8;
@@ -292,7 +301,21 @@ __global__ __launch_bounds__(kHeadDim) void k_attention_merge(const float *__res
     __shared__ float s_f[kHeadDim];  // per-split scale (S <= 128 per pass)
     __shared__ float s_red[2];
     if (APPEND && (int)blockIdx.x >= n_heads) {  // (uniform over the workgroup)
-        if (threadIdx.x < 32) append_row<APPEND == 2>(ap, (int)blockIdx.x - n_heads, (int)threadIdx.x);
+        if (ap.from_dev) {
+            // one workgroup appends every row at the device's own count and then advances it: nothing
+            // else in this launch reads the count.  A full context is recorded, not written to.
+            const int n = *ap.n_word;
+            if (n < ap.max_ctx)
+                for (int bg = threadIdx.x / 32; bg < ap.n_bg; bg += kHeadDim / 32)
+                    append_row<APPEND == 2>(ap, n, bg, (int)threadIdx.x & 31);
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                if (n < ap.max_ctx) *ap.n_word = n + 1; else *ap.full_word = 1;
+            }
+            return;
+        }
+        if (threadIdx.x < 32) append_row<APPEND == 2>(ap, ap.n, (int)blockIdx.x - n_heads, (int)threadIdx.x);
+        if ((int)blockIdx.x == n_heads && threadIdx.x == 0) *ap.n_word = ap.n + 1;
         return;
     }
     const float *ph = part + (size_t)blockIdx.x * S * (kHeadDim + 2);
@@ -337,7 +360,7 @@ void launch_attention_split(const void *q, const void *kc, const void *vc,
                             const void *seg_par, float *part, int B, int Hq, int Hkv, int k, int n_pre,
                             int n, int max_ctx, int S, int P, const uint32_t *cand_key,
                             const void *seg_run, const int32_t *seg_cnt, const uint32_t *thr, int R,
-                            size_t cand_stride, hipStream_t st)
+                            size_t cand_stride, const int32_t *n_dev, hipStream_t st)
 {
     if (S <= 0) return;
     const float qscale = 1.4426950408889634f / sqrtf((float)kHeadDim);
@@ -350,7 +373,7 @@ void launch_attention_split(const void *q, const void *kc, const void *vc,
 #define CSA_ATT(PAGED_, EMIT_)                                                                            \
     k_attention_split<PAGED_, EMIT_><<<grid, block, 0, st>>>(                                             \
         (const uint16_t *)q, (const uint16_t *)kc, (const uint16_t *)vc, block_table, sel, sel_count,     \
-        (const int2 *)seg_par, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, P, P_sel, n_units, qscale, ea)
+        (const int2 *)seg_par, part, k, n_pre, n, Hq, G, Hkv, max_ctx, S, P, P_sel, n_units, qscale, ea, n_dev)
     if (block_table) {
         if (emit) CSA_ATT(true, true); else CSA_ATT(true, false);
     } else {
@@ -368,35 +391,35 @@ void launch_attention_merge(const float *part, float *out, int n_heads, int S, h
 
 void launch_attention_merge_append(const float *part, float *out, int n_heads, int S, void *kc, void *vc,
                                    const int32_t *block_table, const void *kn, const void *vn, int B,
-                                   int Hkv, int n, int max_ctx, hipStream_t st)
+                                   int Hkv, int n, int max_ctx, int32_t *n_word, int32_t *full_word,
+                                   bool from_dev, hipStream_t st)
 {
     const AppendArgs ap{(uint16_t *)kc, (uint16_t *)vc, block_table, (const uint16_t *)kn,
-                        (const uint16_t *)vn, n, Hkv, max_ctx};
+                        (const uint16_t *)vn, n, Hkv, max_ctx, n_word, full_word, from_dev ? 1 : 0, B * Hkv};
+    const int grid = n_heads + (from_dev ? 1 : B * Hkv);
     if (block_table)
-        k_attention_merge<2><<<n_heads + B * Hkv, kHeadDim, 0, st>>>(part, out, S, n_heads, ap);
+        k_attention_merge<2><<<grid, kHeadDim, 0, st>>>(part, out, S, n_heads, ap);
     else
-        k_attention_merge<1><<<n_heads + B * Hkv, kHeadDim, 0, st>>>(part, out, S, n_heads, ap);
+        k_attention_merge<1><<<grid, kHeadDim, 0, st>>>(part, out, S, n_heads, ap);
 }
 
 // K/V append: row n of every (sequence, KV head).  grid B*Hkv, block 32 (16 lanes K, 16 lanes V).
 template <bool PAGED>
-__global__ void k_append(uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
-                         const int32_t *__restrict__ block_table, const uint16_t *__restrict__ kn,
-                         const uint16_t *__restrict__ vn, int n, int Hkv, int max_ctx)
+__global__ void k_append(AppendArgs ap)
 {
-    append_row<PAGED>(AppendArgs{kc, vc, block_table, kn, vn, n, Hkv, max_ctx}, (int)blockIdx.x,
-                      (int)threadIdx.x);
+    append_row<PAGED>(ap, ap.n, (int)blockIdx.x, (int)threadIdx.x);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *ap.n_word = ap.n + 1;
 }
 
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
-                   int B, int Hkv, int n, int max_ctx, hipStream_t st)
+                   int B, int Hkv, int n, int max_ctx, int32_t *n_word, hipStream_t st)
 {
+    const AppendArgs ap{(uint16_t *)kc, (uint16_t *)vc, block_table, (const uint16_t *)kn,
+                        (const uint16_t *)vn, n, Hkv, max_ctx, n_word, nullptr, 0, B * Hkv};
     if (block_table)
-        k_append<true><<<B * Hkv, 32, 0, st>>>((uint16_t *)kc, (uint16_t *)vc, block_table,
-                                               (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx);
+        k_append<true><<<B * Hkv, 32, 0, st>>>(ap);
     else
-        k_append<false><<<B * Hkv, 32, 0, st>>>((uint16_t *)kc, (uint16_t *)vc, nullptr,
-                                                (const uint16_t *)kn, (const uint16_t *)vn, n, Hkv, max_ctx);
+        k_append<false><<<B * Hkv, 32, 0, st>>>(ap);
 }
 
 }  // namespace csa

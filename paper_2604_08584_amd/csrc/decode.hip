@@ -387,9 +387,13 @@ __device__ __forceinline__ void select_top(const float *__restrict__ zh, int C, 
         __syncthreads();
         const uint32_t bound = sm.bound;
         visit([&](int j, uint32_t key, bool valid) {
-            if (valid && key >= bound) {
-                const int slot = atomicAdd(&sm.slot, 1);
-                if (slot < kTopCand) sm.ck[slot] = ((uint64_t)key << 32) | (uint32_t)~j;
+            const bool in = valid && key >= bound;
+            const uint64_t mask = __ballot(in);
+            if (mask) {  // (uniform over the wave) one counter update per wave and round
+                int base = 0;
+                if (lane_id() == 0) base = atomicAdd(&sm.slot, (int)__popcll(mask));
+                const int slot = __builtin_amdgcn_readfirstlane(base) + mbcnt(mask);
+                if (in && slot < kTopCand) sm.ck[slot] = ((uint64_t)key << 32) | (uint32_t)~j;
             }
         });
         __syncthreads();

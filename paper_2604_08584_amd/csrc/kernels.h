@@ -71,22 +71,27 @@ void launch_emit(const uint32_t *cand_key, const void *seg_run, const int32_t *s
 // ---- attention.hip
 int attention_splits(int k, int P, int n_appended);
 // cand_key != NULL: the kernel also does the second half of the Top-K for its key range (needs
-// attention_can_emit(R)); else `sel` is read as given.
+// attention_can_emit(R)); else `sel` is read as given.  n_dev != NULL: the context length is read
+// from that device word instead of `n` (a launch that can be replayed; S must then cover the
+// longest window).
 void launch_attention_split(const void *q, const void *kc, const void *vc,
                             const int32_t *block_table, int32_t *sel, const int32_t *sel_count,
                             const void *seg_par, float *part, int B, int Hq, int Hkv, int k, int n_pre,
                             int n, int max_ctx, int S, int P, const uint32_t *cand_key,
                             const void *seg_run, const int32_t *seg_cnt, const uint32_t *thr, int R,
-                            size_t cand_stride, hipStream_t st);
+                            size_t cand_stride, const int32_t *n_dev, hipStream_t st);
 bool attention_can_emit(int R);
 void launch_range_offsets(const int32_t *sel, const int32_t *sel_count, void *seg_par, int n_heads, int k,
                           int R, int P, hipStream_t st);
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st);
-// the merge, and in the same launch the append of row n (arguments as launch_append)
+// the merge, and in the same launch the append of row n; *n_word (the device's copy of the context
+// length) becomes n + 1.  from_dev: the position is *n_word itself, not `n` (replayable); an append
+// to a full context is skipped and recorded in *full_word.
 void launch_attention_merge_append(const float *part, float *out, int n_heads, int S, void *kc, void *vc,
                                    const int32_t *block_table, const void *kn, const void *vn, int B,
-                                   int Hkv, int n, int max_ctx, hipStream_t st);
+                                   int Hkv, int n, int max_ctx, int32_t *n_word, int32_t *full_word,
+                                   bool from_dev, hipStream_t st);
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
-                   int B, int Hkv, int n, int max_ctx, hipStream_t st);
+                   int B, int Hkv, int n, int max_ctx, int32_t *n_word, hipStream_t st);
 
 }  // namespace csa
