@@ -9,6 +9,7 @@ import dataclasses
 import numpy as np
 import pytest
 
+from paper_2604_08584_amd import binding
 from paper_2604_08584_amd.workload import CONFIGS
 
 from harness import Case
@@ -72,6 +73,47 @@ def test_cfg4_70b_shape():
     heads = [(0, 0), (0, 7), (3, 40), (7, 56), (7, 63)]
     for step in range(2):       # the one-call iteration (step, then append) that bench.py times
         print("cfg4 step", step, "err", case.check_step(step, heads, fused_append=True))
+
+
+def _sampled_rows(case, n_groups, per_group, seed):
+    """per_group table rows of each of n_groups (sequence, KV head) pairs, seeded; compared one export
+    per pair."""
+    w = case.w
+    rng = np.random.default_rng(seed)
+    pairs = rng.choice(w.batch * w.n_kv_heads, size=n_groups, replace=False)
+    for pr in pairs:
+        b, g = divmod(int(pr), w.n_kv_heads)
+        rows = sorted(set(rng.choice(w.n_sub * w.C, size=per_group, replace=False).tolist()) | {0, w.n_sub * w.C - 1})
+        _check_rows(case, b, g, rows)
+
+
+def test_cfg2_every_head_first_and_last_step():
+    """Config 2 as defined (batch 1, 128K, 64 steps): 34+ sampled table rows, EVERY head at the first
+    step and EVERY head at the last one (63 keys appended), in the one-call form bench.py times."""
+    w = _light("cfg2", 64)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=16 * w.C)
+    case.build_on_gpu()
+    _sampled_rows(case, 4, 8, seed=2)
+    print("cfg2 all heads, step 0: err", case.check_step(0, fused_append=True))
+    case.append(62)
+    assert case.t == 63
+    print("cfg2 all heads, step 63: err", case.check_step(63, fused_append=True))
+    assert binding.csa_context_len(case.ctx.ctx) == (w.n_pre, w.n_pre + 64)
+
+
+def test_cfg4_every_head_and_the_last_step():
+    """Config 4 as defined (batch 8, 64 query heads, 128K, 256 steps): 40 sampled table rows, EVERY
+    one of the 512 heads at the first step and at the last one (255 keys appended, context 131327);
+    the oracle builds the table rows they probe, about 16 thousand per step."""
+    w = _light("cfg4", 256)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=8 * w.C)
+    case.build_on_gpu()
+    _sampled_rows(case, 4, 8, seed=4)
+    print("cfg4 all 512 heads, step 0: err", case.check_step(0, fused_append=True))
+    case.append(254)
+    assert case.t == 255
+    print("cfg4 all 512 heads, step 255: err", case.check_step(255, fused_append=True))
+    assert binding.csa_context_len(case.ctx.ctx) == (w.n_pre, w.n_pre + 256)
 
 
 def test_paper_default_geometry_full_size():
