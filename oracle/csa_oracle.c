@@ -253,14 +253,21 @@ void oracle_kmeans(const float *x, int64_t n, int d, int C, int iters, const dou
  *   oracle_kmeans_step also returns, per point, its assignment and the gap between its best and
  *   second-best cosine (how close the decision was), and the mean best cosine.
  */
-void oracle_kmeans_seed(const float *x, int64_t n, int d, int C, const double *u_seed, uint16_t *cent)
+void oracle_kmeans_seed(const float *x, int64_t n, int d, int C, const double *u_seed, uint16_t *cent,
+                        int64_t *picks, double *margin)
 {
+    /* picks[j] (optional): the point taken as seed j.  margin[j] (optional, j >= 1): how far the
+     * draw's target u_j * total was from the nearer end of the picked point's stretch of the running
+     * sum, as a fraction of the total - a draw with a tiny margin is one that rounding may move to a
+     * neighbouring point.  margin[0] = 0. */
     double *xn = (double *)malloc(sizeof(double) * (size_t)d);
     double *dist = (double *)malloc(sizeof(double) * (size_t)n);
     for (int64_t i = 0; i < n; ++i) dist[i] = INFINITY;
     int64_t pick = (int64_t)(u_seed[0] * (double)n);
     if (pick >= n) pick = n - 1;
+    if (margin) margin[0] = 0.0;
     for (int j = 0; j < C; ++j) {
+        if (picks) picks[j] = pick;
         /* seed j = the normalised point `pick`, rounded to bf16 */
         double nn = 0.0;
         for (int t = 0; t < d; ++t) nn += (double)x[pick * d + t] * x[pick * d + t];
@@ -280,14 +287,68 @@ void oracle_kmeans_seed(const float *x, int64_t n, int d, int C, const double *u
             if (s < dist[i]) dist[i] = s;
             tot += dist[i];
         }
-        double target = u_seed[j + 1] * tot, run = 0.0;
+        double target = u_seed[j + 1] * tot, run = 0.0, before = 0.0;
         pick = n - 1;
         for (int64_t i = 0; i < n; ++i) {
+            before = run;
             run += dist[i];
             if (run > target) { pick = i; break; }
         }
+        if (margin) {
+            const double lo = target - before, hi = run - target;
+            margin[j + 1] = tot > 0.0 ? fmin(fabs(lo), fabs(hi)) / tot : 0.0;
+        }
     }
     free(xn); free(dist);
+}
+
+/*
+ * One step of the mini-batch form of the same clustering (Sec. 3.2 (1) names mini-batch k-means;
+ * the update is the per-centre running mean of the mini-batch k-means algorithm, Sculley 2010: a
+ * centre is the mean of every point ever assigned to it, the starting centre carrying no weight -
+ * here the mean direction, re-normalised and rounded to bf16).  The points of this batch are
+ * assigned to the bf16 centroids as in oracle_kmeans_step, then added to the running sums and
+ * counts, which the caller keeps between the steps (all zero before the first); a centre whose
+ * running count is still zero keeps its centroid.  With one batch holding every point and zeroed
+ * sums this is oracle_kmeans_step.
+ *   run_sum [C][d] fp64, run_cnt [C] int64: in/out.
+ */
+double oracle_kmeans_minibatch_step(const float *x, int64_t n, int d, int C, const uint16_t *cent_in,
+                                    uint16_t *cent_out, int32_t *assign, double *gap, double *run_sum,
+                                    int64_t *run_cnt)
+{
+    double *xn = (double *)malloc(sizeof(double) * (size_t)d);
+    double cos_sum = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double nn = 0.0;
+        for (int t = 0; t < d; ++t) nn += (double)x[i * d + t] * x[i * d + t];
+        nn = sqrt(nn);
+        for (int t = 0; t < d; ++t) xn[t] = nn > 0 ? x[i * d + t] / nn : 0.0;
+        int best = 0;
+        double b1 = -INFINITY, b2 = -INFINITY;
+        for (int j = 0; j < C; ++j) {
+            double s = 0.0;
+            for (int t = 0; t < d; ++t) s += xn[t] * (double)bf16_to_f32(cent_in[(int64_t)j * d + t]);
+            if (s > b1) { b2 = b1; b1 = s; best = j; }
+            else if (s > b2) b2 = s;
+        }
+        assign[i] = best;
+        if (gap) gap[i] = b1 - b2;
+        cos_sum += b1;
+        run_cnt[best]++;
+        for (int t = 0; t < d; ++t) run_sum[(int64_t)best * d + t] += xn[t];
+    }
+    for (int j = 0; j < C; ++j) {
+        double nn = 0.0;
+        for (int t = 0; t < d; ++t) nn += run_sum[(int64_t)j * d + t] * run_sum[(int64_t)j * d + t];
+        nn = sqrt(nn);
+        for (int t = 0; t < d; ++t)
+            cent_out[(int64_t)j * d + t] = (run_cnt[j] == 0 || nn == 0.0)
+                                               ? cent_in[(int64_t)j * d + t]
+                                               : f32_to_bf16((float)(run_sum[(int64_t)j * d + t] / nn));
+    }
+    free(xn);
+    return n > 0 ? cos_sum / (double)n : 0.0;
 }
 
 double oracle_kmeans_step(const float *x, int64_t n, int d, int C, const uint16_t *cent_in,

@@ -39,6 +39,7 @@ def lib():
         _lib.oracle_decode_items.restype = C.c_int
         _lib.oracle_try_insert.restype = C.c_double
         _lib.oracle_kmeans_step.restype = C.c_double
+        _lib.oracle_kmeans_minibatch_step.restype = C.c_double
     return _lib
 
 
@@ -77,15 +78,35 @@ def kmeans(x, n_centroids, iters, u_seed):
     return cent, obj
 
 
-def kmeans_seed(x, n_centroids, u_seed):
-    """k-means++ seeds (bf16 bit patterns [C][d]) of the rows of x [n][d] fp32."""
+def kmeans_seed(x, n_centroids, u_seed, with_draws=False):
+    """k-means++ seeds (bf16 bit patterns [C][d]) of the rows of x [n][d] fp32.  with_draws: also the
+    picked point of every seed and every draw's margin (see oracle_kmeans_seed)."""
     x = np.ascontiguousarray(x, np.float32)
     u_seed = np.ascontiguousarray(u_seed, np.float64)
     assert u_seed.shape[0] >= n_centroids
     n, d = x.shape
     cent = np.empty((n_centroids, d), np.uint16)
-    lib().oracle_kmeans_seed(_p(x), C.c_int64(n), C.c_int(d), C.c_int(n_centroids), _p(u_seed), _p(cent))
-    return cent
+    picks = np.empty(n_centroids, np.int64)
+    margin = np.empty(n_centroids, np.float64)
+    lib().oracle_kmeans_seed(_p(x), C.c_int64(n), C.c_int(d), C.c_int(n_centroids), _p(u_seed), _p(cent),
+                             _p(picks), _p(margin))
+    return (cent, picks, margin) if with_draws else cent
+
+
+def kmeans_minibatch_step(x, cent, run_sum, run_cnt):
+    """One mini-batch step on the batch x [n][d] from bf16 centroids; run_sum [C][d] fp64 and run_cnt [C]
+    int64 are updated in place.  Returns (new bf16 centroids, assignment [n], gap [n], mean best cosine)."""
+    x = np.ascontiguousarray(x, np.float32)
+    n, d = x.shape
+    n_c = cent.shape[0]
+    assert run_sum.dtype == np.float64 and run_sum.shape == (n_c, d) and run_sum.flags["C_CONTIGUOUS"]
+    assert run_cnt.dtype == np.int64 and run_cnt.shape == (n_c,)
+    out = np.empty((n_c, d), np.uint16)
+    asg = np.empty(n, np.int32)
+    gap = np.empty(n, np.float64)
+    mc = lib().oracle_kmeans_minibatch_step(_p(x), C.c_int64(n), C.c_int(d), C.c_int(n_c), _p(cent), _p(out),
+                                            _p(asg), _p(gap), _p(run_sum), _p(run_cnt))
+    return out, asg, gap, mc
 
 
 def kmeans_step(x, cent):

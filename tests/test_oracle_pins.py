@@ -710,3 +710,61 @@ def test_hand_worked_example():
     w = np.array(ex["weights_num"]) ; w = np.exp(w) / np.exp(w).sum()
     want0 = sum(wi * vi for wi, vi in zip(w, ex["attended_v0"]))
     assert out[0] == pytest.approx(want0, rel=1e-6)
+
+
+def test_kmeans_draw_matches_the_hand_worked_example():
+    """tests/golden/kmeans_draw_example.txt: six points, three uniforms, the picks and margins worked
+    out by hand - pins the draw to the index (first point whose running sum EXCEEDS u * total)."""
+    lines = [l for l in open(os.path.join(os.path.dirname(__file__), "golden", "kmeans_draw_example.txt"))
+             if l.strip() and not l.startswith("#")]
+    pts = np.array([[float(v) for v in l.split()] for l in lines[:6]], np.float32)
+    u = np.array([float(v) for v in lines[6].split()])
+    want_picks = [int(v) for v in lines[7].split()]
+    want_margin = [float(v) for v in lines[8].split()]
+    cent, picks, margin = oracle.kmeans_seed(pts, 3, u, with_draws=True)
+    assert picks.tolist() == want_picks
+    np.testing.assert_allclose(margin[1:], want_margin, atol=1e-7)
+    f32 = oracle.bits_to_f32
+    np.testing.assert_array_equal(f32(cent), pts[want_picks])            # exact in bf16
+    # a target that lands exactly on a running sum does not take that point ("exceeds"): after seed 0
+    # the running sums are 0 2 6 ...; u_1 = 2 / 8.8 puts the target on point 1's sum (up to rounding of
+    # the product, so test both sides of it)
+    for u1, want in ((0.22, 1), (0.2280, 2)):      # 0.22 * 8.8 = 1.936 < 2 -> point 1; 2.0064 > 2 -> point 2
+        assert oracle.kmeans_seed(pts, 2, np.array([0.0, u1]), with_draws=True)[1].tolist() == [0, want]
+
+
+def test_kmeans_minibatch_step_is_a_running_mean_direction():
+    """The mini-batch step: with one batch and zeroed sums it is the full step; the running sums are
+    the sums of every normalised point assigned so far (checked from the definition in numpy); a
+    centre that has never had a member keeps its centroid; feeding the same batch twice leaves the
+    centroids where the first pass put them when the assignments do not change."""
+    rng = np.random.default_rng(11)
+    d, n_c = 8, 5
+    dirs = rng.standard_normal((4, d))
+    x = (dirs[rng.integers(0, 4, 400)] + 0.2 * rng.standard_normal((400, d))).astype(np.float32)
+    cent0 = oracle.round_bf16((dirs / np.linalg.norm(dirs, axis=1, keepdims=True)).astype(np.float32))
+    far = -np.sum(dirs, axis=0)
+    cent0 = np.concatenate([cent0, oracle.round_bf16((far / np.linalg.norm(far)).astype(np.float32)[None])])
+    full, asg_f, _, mc_f = oracle.kmeans_step(x, cent0)
+    rs, rc = np.zeros((n_c, d)), np.zeros(n_c, np.int64)
+    one, asg_1, _, mc_1 = oracle.kmeans_minibatch_step(x, cent0, rs, rc)
+    assert np.array_equal(full, one) and np.array_equal(asg_f, asg_1) and mc_f == mc_1
+    assert rc.sum() == 400 and rc[4] == 0 and np.array_equal(one[4], cent0[4])   # the far centre stays put
+    xn = x.astype(np.float64) / np.linalg.norm(x.astype(np.float64), axis=1, keepdims=True)
+    for j in range(4):
+        np.testing.assert_allclose(rs[j], xn[asg_1 == j].sum(axis=0), rtol=1e-12)
+    # two batches: the second step's centroid is the direction of ALL members so far, not of the batch
+    rs, rc = np.zeros((n_c, d)), np.zeros(n_c, np.int64)
+    a, asg_a, _, _ = oracle.kmeans_minibatch_step(x[0::2], cent0, rs, rc)
+    b, asg_b, _, _ = oracle.kmeans_minibatch_step(x[1::2], a, rs, rc)
+    f32 = oracle.bits_to_f32
+    for j in range(4):
+        tot = xn[0::2][asg_a == j].sum(axis=0) + xn[1::2][asg_b == j].sum(axis=0)
+        np.testing.assert_allclose(rs[j], tot, rtol=1e-12)
+        np.testing.assert_allclose(f32(b[j]), tot / np.linalg.norm(tot), atol=2.0 ** -8)
+    # the same batch again: sums double, directions stay (up to the bf16 rounding already applied)
+    rs, rc = np.zeros((n_c, d)), np.zeros(n_c, np.int64)
+    c1, asg1, _, _ = oracle.kmeans_minibatch_step(x, cent0, rs, rc)
+    c2, asg2, _, _ = oracle.kmeans_minibatch_step(x, c1, rs, rc)
+    if np.array_equal(asg1, asg2):
+        assert np.array_equal(c1, c2)
