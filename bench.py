@@ -53,6 +53,9 @@ def main():
                          "the config instead of the decode step: seeding + Lloyd steps, and the "
                          "assignment kernel against the bf16 matrix-core peak")
     ap.add_argument("--cluster-iters", type=int, default=10)
+    ap.add_argument("--cluster-batches", type=int, default=1,
+                    help="mini-batch clustering: the points are dealt into this many classes, the seeding "
+                         "runs over the first and step t over class t %% batches (1 = full batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies before the timed region, "
@@ -432,16 +435,17 @@ def cluster_bench(args, w):
     useed = np.random.default_rng(args.seed).uniform(size=(1, Hkv, S, C)).astype(np.float32)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    binding.csa_cluster_queries(ctx, q, w.n_pre, 0, useed, None, cent, None, None, work)   # seeding only
+    nb = max(1, args.cluster_batches)
+    binding.csa_cluster_queries(ctx, q, w.n_pre, 0, useed, None, cent, None, None, work, n_batches=nb)   # seeding only
     torch.cuda.synchronize()
     t_seed = time.perf_counter() - t0
     seeds = cent.clone()
     t0 = time.perf_counter()
-    binding.csa_cluster_queries(ctx, q, w.n_pre, iters, None, seeds, cent, mean_cos, None, work)
+    binding.csa_cluster_queries(ctx, q, w.n_pre, iters, None, seeds, cent, mean_cos, None, work, n_batches=nb)
     torch.cuda.synchronize()
     t_lloyd = time.perf_counter() - t0
     n_pool = G * w.n_pre
-    flops = 2.0 * n_pool * C * (d // S) * Hkv * S * iters          # the assignment contraction
+    flops = 2.0 * (n_pool / nb) * C * (d // S) * Hkv * S * iters          # the assignment contraction
     mc = mean_cos.mean(dim=(0, 1, 2)).cpu().numpy()
     binding.csa_destroy(ctx)
     peak = 2500.0
@@ -450,14 +454,33 @@ def cluster_bench(args, w):
         "value": round(t_seed + t_lloyd, 4), "unit": "s", "n_gpus": 1, "higher_is_better": False,
         "dtype": "bf16 operands, fp32 accumulate", "data": "synthetic",
         "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "n_pre": w.n_pre, "subspaces": S,
-                   "C": C, "iters": iters, "points_per_problem": n_pool},
+                   "C": C, "iters": iters, "points_per_problem": n_pool, "batches": nb,
+                   "problems_side_by_side": Hkv * S},
         "seeding_s": round(t_seed, 4), "lloyd_s": round(t_lloyd, 4),
         "mean_cos_first_last": [round(float(mc[0]), 4), round(float(mc[-1]), 4)],
-        "roofline": {"kernel": "k_km_assign (+ member sums, k_km_finish)", "bound": "mfma",
-                     "achieved": round(flops / t_lloyd / 1e12, 2), "peak": peak, "unit": "TFLOP/s",
-                     "frac": round(flops / t_lloyd / 1e12 / peak, 4), "traffic": None,
-                     "measured": "wall clock over all Lloyd steps of all problems, synchronised"},
+        "roofline": lloyd_roofline(flops, t_lloyd, n_pool / nb, C, d // S, Hkv * S, iters, peak),
     }), flush=True)
+
+
+def lloyd_roofline(flops, t_lloyd, n_pts, C, db, n_prob, iters, peak):
+    """The Lloyd steps against the bound that governs them: the bf16 matrix-core peak when the
+    contraction is large against the bytes of the points (long sub-vectors, many centroids), else the
+    HBM stream of the points (every step reads each point's sub-vector once for the assignment and
+    once for the member sums: 2 * d_b * 2 bytes per point)."""
+    point_bytes = 2.0 * n_pts * db * 2 * n_prob * iters
+    t_mfma, t_hbm = flops / (peak * 1e12), point_bytes / (PEAK_HBM_GBPS * 1e9)
+    if t_mfma >= t_hbm:
+        return {"kernel": "k_km_assign (+ member sums, k_km_finish)", "bound": "mfma",
+                "achieved": round(flops / t_lloyd / 1e12, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(flops / t_lloyd / 1e12 / peak, 4), "traffic": None,
+                "measured": "wall clock over all Lloyd steps of all problems, synchronised"}
+    return {"kernel": "k_km_assign (+ member sums, k_km_finish)", "bound": "hbm",
+            "achieved": round(point_bytes / t_lloyd / 1e9, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+            "frac": round(point_bytes / t_lloyd / 1e9 / PEAK_HBM_GBPS, 4), "traffic": None,
+            "note": "the contraction is tiny against the bytes of the points (%.1f flop per byte): the steps "
+                    "are bound by the stream of the points and by their launches, not by the matrix cores"
+                    % (flops / point_bytes),
+            "measured": "wall clock over all Lloyd steps of all problems, synchronised"}
 
 
 def cpu_baseline(ctx, w, inp, budget_s):

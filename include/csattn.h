@@ -127,23 +127,34 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
 /*
  * Query-centric centroids, Sec. 3.2 (1): for every KV head and subspace, cosine k-means over the
  * l2-normalised prefill query sub-vectors of the G query heads of the group ("per KV-head group",
- * Sec. 4.4), k-means++ seeding, `iters` Lloyd steps over all points (the paper's mini-batch size is
- * not stated; the full batch is used).  Centroids are unit vectors held in bf16 between the steps:
- * each step assigns every point to the centroid of largest inner product (bf16 operands on the
- * matrix cores, fp32 accumulation; ties to the lower centroid) and replaces a centroid by the
- * re-normalised sum of its normalised members, rounded to bf16 (an empty cluster keeps its
- * centroid).  The member sums are added with fp32 atomics, so the last bit of a centroid may differ
- * between runs.
+ * Sec. 4.4), k-means++ seeding, `iters` Lloyd steps.  Centroids are unit vectors held in bf16
+ * between the steps: each step assigns its points to the centroid of largest inner product (bf16
+ * operands on the matrix cores, fp32 accumulation; ties to the lower centroid) and replaces a
+ * centroid by the re-normalised sum of its normalised members, rounded to bf16 (a cluster without a
+ * member keeps its centroid).
+ * csa_cluster_queries: every step runs over all G * n_pre points (full batch).
+ * csa_cluster_queries_minibatch: the paper names mini-batch k-means without a batch size; here the
+ *   pooled points are dealt into n_batches classes (point i belongs to class i % n_batches), the
+ *   seeding runs over class 0, step t over class t % n_batches, and a centroid is the re-normalised
+ *   sum of every point assigned to it in any step so far (the per-centre running mean of mini-batch
+ *   k-means; the starting centroid carries no weight).  n_batches = 1 is the full batch.
+ * All problems of a sequence run side by side.  The member sums are fp32: with few short centroids
+ * (C * (d/S + 1) <= 8192) they are added with atomics in an order that is not fixed; otherwise each
+ * centroid's members are listed (in an order that depends on an atomic cursor) and summed by one
+ * wave - either way the last bit of a centroid may differ between runs.
  *   q_pre_dev          bf16 [B][Hq][n_pre][d]: the prefill queries.
  *   u_seed             HOST fp32 [B][Hkv][S][C], uniforms in [0, 1) that drive the seeding: point
  *                      floor(u_0 * n) first, then each next seed is the first point whose running
- *                      sum of squared distances to the nearest seed so far exceeds u_j * total.
- *                      NULL if init_centroids_dev is given.
+ *                      sum of squared distances to the nearest seed so far exceeds u_j * total
+ *                      (n and the points: those of class 0).  It is copied to the device on
+ *                      `stream` and must stay valid until that copy has run.  NULL if
+ *                      init_centroids_dev is given.
  *   init_centroids_dev bf16 [B][Hkv][S][C][d/S] starting centroids instead of the seeding, or NULL.
  *   centroids_out_dev  bf16 [B][Hkv][S][C][d/S]: the input csa_build_tables expects.
- *   mean_cos_dev       fp32 [B][Hkv][S][max(iters,1)]: mean cosine of the points to their assigned
- *                      centroid in each step's assignment (non-decreasing up to rounding); or NULL.
- *   assign_dev         int32 [B][Hkv][S][G*n_pre]: assignments of the last step; or NULL.
+ *   mean_cos_dev       fp32 [B][Hkv][S][max(iters,1)]: mean cosine of a step's points to their
+ *                      assigned centroid (full batch: non-decreasing up to rounding); or NULL.
+ *   assign_dev         int32 [B][Hkv][S][G*n_pre]: assignments of the last step (mini-batches: -1
+ *                      for the points outside the last step's class); or NULL.
  *   work_dev           scratch of csa_cluster_workspace_bytes bytes, 256-byte aligned.
  * Needs no bound buffers and no tables.  Enqueues on `stream`; does not synchronise.
  */
@@ -152,6 +163,21 @@ int csa_cluster_queries(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int3
                         const float *u_seed, const void *init_centroids_dev, void *centroids_out_dev,
                         float *mean_cos_dev, int32_t *assign_dev, void *work_dev, size_t work_bytes,
                         void *stream);
+int csa_cluster_queries_minibatch(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters,
+                                  int32_t n_batches, const float *u_seed, const void *init_centroids_dev,
+                                  void *centroids_out_dev, float *mean_cos_dev, int32_t *assign_dev,
+                                  void *work_dev, size_t work_bytes, void *stream);
+
+/*
+ * The whole offline prefill of Sec. 3.2 in one call, from the prefill queries and the keys in the
+ * bound cache: (1) csa_cluster_queries_minibatch(q_pre_dev, n_pre, iters, n_batches, u_seed) into
+ * centroids_out_dev, then (2) csa_build_tables(centroids_out_dev, n_pre), on one stream.  Arguments
+ * as in those two calls (centroids_out_dev, bf16 [B][Hkv][S][C][d/S], also serves the caller: it is
+ * what csa_import_tables or an oracle of the build would take).  SYNCHRONISES `stream` (the table
+ * build does); errors of either part are returned.
+ */
+int csa_prefill(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters, int32_t n_batches,
+                const float *u_seed, void *centroids_out_dev, void *work_dev, size_t work_bytes, void *stream);
 
 /*
  * Tables in the canonical layout, one KV head at a time or all at once:

@@ -48,6 +48,8 @@ def lib() -> C.CDLL:
         "csa_build_tables": (C.c_int, [vp, vp, i32, vp]),
         "csa_cluster_workspace_bytes": (C.c_int, [vp, i32, C.POINTER(sz)]),
         "csa_cluster_queries": (C.c_int, [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "csa_cluster_queries_minibatch": (C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "csa_prefill": (C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]),
         "csa_export_tables": (C.c_int, [vp, i32, i32, vp, vp, vp]),
         "csa_import_tables": (C.c_int, [vp, vp, vp, vp, i32, vp]),
         "csa_append_kv": (C.c_int, [vp, vp, vp, vp]),
@@ -77,7 +79,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTED = ("csa_create", "csa_destroy", "csa_workspace_bytes", "csa_bind", "csa_build_tables",
-            "csa_cluster_workspace_bytes", "csa_cluster_queries",
+            "csa_cluster_workspace_bytes", "csa_cluster_queries", "csa_cluster_queries_minibatch", "csa_prefill",
             "csa_export_tables", "csa_import_tables", "csa_append_kv", "csa_decode_step",
             "csa_decode_step_static", "csa_static_scratch_bytes",
             "csa_decode_step_reuse", "csa_decode_step_append", "csa_decode_step_append_replayable",
@@ -148,8 +150,9 @@ def csa_cluster_workspace_bytes(ctx, n_pre) -> int:
 
 
 def csa_cluster_queries(ctx, q_pre, n_pre, iters, u_seed, init_centroids, centroids_out, mean_cos=None,
-                        assign=None, work=None):
-    """u_seed: host numpy float32 array (or None when init_centroids is given)."""
+                        assign=None, work=None, n_batches=1):
+    """u_seed: host numpy float32 array (or None when init_centroids is given).  n_batches > 1 calls
+    csa_cluster_queries_minibatch."""
     import numpy as np
     if work is None:
         work = torch.empty(csa_cluster_workspace_bytes(ctx, n_pre), dtype=torch.uint8, device=q_pre.device)
@@ -157,10 +160,26 @@ def csa_cluster_queries(ctx, q_pre, n_pre, iters, u_seed, init_centroids, centro
     if u_seed is not None:
         u_seed = np.ascontiguousarray(u_seed, np.float32)
         useed_p = u_seed.ctypes.data_as(C.c_void_p)
-    _check(lib().csa_cluster_queries(ctx, _ptr(q_pre), n_pre, iters, useed_p, _ptr(init_centroids),
-                                     _ptr(centroids_out), _ptr(mean_cos), _ptr(assign), _ptr(work),
-                                     work.numel(), _stream()), "csa_cluster_queries")
+    if n_batches == 1:
+        _check(lib().csa_cluster_queries(ctx, _ptr(q_pre), n_pre, iters, useed_p, _ptr(init_centroids),
+                                         _ptr(centroids_out), _ptr(mean_cos), _ptr(assign), _ptr(work),
+                                         work.numel(), _stream()), "csa_cluster_queries")
+    else:
+        _check(lib().csa_cluster_queries_minibatch(ctx, _ptr(q_pre), n_pre, iters, n_batches, useed_p,
+                                                   _ptr(init_centroids), _ptr(centroids_out), _ptr(mean_cos),
+                                                   _ptr(assign), _ptr(work), work.numel(), _stream()),
+               "csa_cluster_queries_minibatch")
     torch.cuda.current_stream().synchronize()   # u_seed (host memory) and work stay alive until here
+
+
+def csa_prefill(ctx, q_pre, n_pre, iters, n_batches, u_seed, centroids_out, work=None):
+    """Clustering of the prefill queries, then the table build, in one call (synchronises)."""
+    import numpy as np
+    if work is None:
+        work = torch.empty(csa_cluster_workspace_bytes(ctx, n_pre), dtype=torch.uint8, device=q_pre.device)
+    u_seed = np.ascontiguousarray(u_seed, np.float32)
+    _check(lib().csa_prefill(ctx, _ptr(q_pre), n_pre, iters, n_batches, u_seed.ctypes.data_as(C.c_void_p),
+                             _ptr(centroids_out), _ptr(work), work.numel(), _stream()), "csa_prefill")
 
 
 def csa_export_tables(ctx, b, g, idx_out, score_out):

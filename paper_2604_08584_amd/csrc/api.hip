@@ -440,14 +440,15 @@ int csa_cluster_workspace_bytes(const csa_ctx *ctx, int32_t n_pre, size_t *bytes
     const csa_config &c = ctx->cfg;
     const int64_t n_pool = (int64_t)(c.n_q_heads / c.n_kv_heads) * n_pre;
     if (n_pool > (1 << 30)) return CSA_ERR_ARG;
-    *bytes = csa::cluster_work_bytes((int)n_pool, c.n_centroids, c.head_dim / c.n_subspaces);
+    *bytes = csa::cluster_work_bytes(c.n_kv_heads * c.n_subspaces, (int)n_pool, c.n_centroids,
+                                     c.head_dim / c.n_subspaces);
     return CSA_OK;
 }
 
-int csa_cluster_queries(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters,
-                        const float *u_seed, const void *init_centroids_dev, void *centroids_out_dev,
-                        float *mean_cos_dev, int32_t *assign_dev, void *work_dev, size_t work_bytes,
-                        void *stream)
+int csa_cluster_queries_minibatch(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters,
+                                  int32_t n_batches, const float *u_seed, const void *init_centroids_dev,
+                                  void *centroids_out_dev, float *mean_cos_dev, int32_t *assign_dev,
+                                  void *work_dev, size_t work_bytes, void *stream)
 {
     if (!ctx || !q_pre_dev || !centroids_out_dev || !work_dev) return CSA_ERR_ARG;
     if (n_pre < 1 || iters < 0 || (!u_seed && !init_centroids_dev)) return CSA_ERR_ARG;
@@ -456,24 +457,43 @@ int csa_cluster_queries(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int3
     const int G = c.n_q_heads / c.n_kv_heads, S = c.n_subspaces, C = c.n_centroids, db = c.head_dim / S;
     const int64_t n_pool64 = (int64_t)G * n_pre;
     if (n_pool64 > (1 << 30)) return CSA_ERR_ARG;
-    const int n_pool = (int)n_pool64;
-    if (work_bytes < csa::cluster_work_bytes(n_pool, C, db)) return CSA_ERR_WORKSPACE;
+    const int n_pool = (int)n_pool64, n_prob = c.n_kv_heads * S;
+    if (n_batches < 1 || n_batches > n_pool) return CSA_ERR_ARG;
+    if (work_bytes < csa::cluster_work_bytes(n_prob, n_pool, C, db)) return CSA_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const uint16_t *q = (const uint16_t *)q_pre_dev;
-    for (int b = 0; b < c.batch; ++b)
-        for (int g = 0; g < c.n_kv_heads; ++g)
-            for (int sub = 0; sub < S; ++sub) {
-                const size_t prob = ((size_t)(b * c.n_kv_heads + g) * S + sub);
-                const uint16_t *q_group = q + ((size_t)b * c.n_q_heads + (size_t)g * G) * n_pre * c.head_dim;
-                const int rc = csa::cluster_problem(
-                    q_group, n_pre, n_pool, S, sub, C, iters, u_seed ? u_seed + prob * C : nullptr,
-                    init_centroids_dev ? (const uint16_t *)init_centroids_dev + prob * C * db : nullptr,
-                    (uint16_t *)centroids_out_dev + prob * C * db,
-                    mean_cos_dev ? mean_cos_dev + prob * (iters > 0 ? iters : 1) : nullptr,
-                    assign_dev ? assign_dev + prob * n_pool : nullptr, work_dev, st);
-                if (rc != 0) return hip_fail(ctx, (hipError_t)rc);
-            }
+    const int it_eff = iters > 0 ? iters : 1;
+    for (int b = 0; b < c.batch; ++b) {
+        const size_t p0 = (size_t)b * n_prob;  // the sequence's first problem
+        const int rc = csa::cluster_sequence(
+            (const uint16_t *)q_pre_dev + (size_t)b * c.n_q_heads * n_pre * c.head_dim, n_pre, G, c.n_kv_heads, S, C,
+            iters, n_batches, u_seed ? u_seed + p0 * C : nullptr,
+            init_centroids_dev ? (const uint16_t *)init_centroids_dev + p0 * C * db : nullptr,
+            (uint16_t *)centroids_out_dev + p0 * C * db, mean_cos_dev ? mean_cos_dev + p0 * it_eff : nullptr,
+            assign_dev ? assign_dev + p0 * n_pool : nullptr, work_dev, st);
+        if (rc != 0) return hip_fail(ctx, (hipError_t)rc);
+    }
     return CSA_OK;
+}
+
+int csa_cluster_queries(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters,
+                        const float *u_seed, const void *init_centroids_dev, void *centroids_out_dev,
+                        float *mean_cos_dev, int32_t *assign_dev, void *work_dev, size_t work_bytes,
+                        void *stream)
+{
+    return csa_cluster_queries_minibatch(ctx, q_pre_dev, n_pre, iters, 1, u_seed, init_centroids_dev,
+                                         centroids_out_dev, mean_cos_dev, assign_dev, work_dev, work_bytes, stream);
+}
+
+int csa_prefill(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters, int32_t n_batches,
+                const float *u_seed, void *centroids_out_dev, void *work_dev, size_t work_bytes, void *stream)
+{
+    if (!ctx) return CSA_ERR_ARG;
+    if (!ctx->bound) return CSA_ERR_STATE;
+    if (!u_seed) return CSA_ERR_ARG;
+    const int rc = csa_cluster_queries_minibatch(ctx, q_pre_dev, n_pre, iters, n_batches, u_seed, nullptr,
+                                                 centroids_out_dev, nullptr, nullptr, work_dev, work_bytes, stream);
+    if (rc != CSA_OK) return rc;
+    return csa_build_tables(ctx, centroids_out_dev, n_pre, stream);
 }
 
 int csa_import_tables(csa_ctx *ctx, const void *centroids_dev, const int32_t *idx_dev,

@@ -35,10 +35,11 @@ void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out,
                          int max_ctx, int n_pre, int S, hipStream_t st);
 
 // ---- cluster.hip
-size_t cluster_work_bytes(int n_pool, int C, int db);
-int cluster_problem(const void *q_group, int n_pre, int n_pool, int S, int sub, int C, int iters,
-                    const float *u_seed, const void *init, void *out, float *mean_cos_out,
-                    int32_t *assign_out, void *work, hipStream_t st);
+// every (KV head, subspace) problem of one sequence side by side; n_batches > 1: mini-batch steps
+size_t cluster_work_bytes(int n_prob, int n_all, int C, int db);
+int cluster_sequence(const void *q_seq, int n_pre, int G, int Hkv, int S, int C, int iters, int n_batches,
+                     const float *u_seed, const void *init, void *out, float *mean_cos_out,
+                     int32_t *assign_out, void *work, hipStream_t st);
 
 // ---- decode.hip
 void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
