@@ -38,8 +38,10 @@ def main():
                     help="benchmark configuration cfg1..cfg4, or paper_s8 (the paper's default geometry)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--partition-keys", type=int, default=0)
-    ap.add_argument("--kmeans-sample", type=int, default=0,
-                    help="cap on pooled prefill queries seen by the centroid synthesis (0 = all)")
+    ap.add_argument("--centroids", default="library", choices=("library", "sample"),
+                    help="library: the centroids come from the library's own clustering of the prefill "
+                         "queries (csa_prefill; --cluster-iters steps, --cluster-batches classes); sample: "
+                         "normalised prefill queries picked at random, then csa_build_tables")
     ap.add_argument("--search-period", type=int, default=1,
                     help="schedule 'keep ratio + search period': search every P-th step, reuse the "
                          "index set in between (csa_decode_step_reuse)")
@@ -53,7 +55,7 @@ def main():
                          "the config instead of the decode step: seeding + Lloyd steps, and the "
                          "assignment kernel against the bf16 matrix-core peak")
     ap.add_argument("--cluster-iters", type=int, default=10)
-    ap.add_argument("--cluster-batches", type=int, default=1,
+    ap.add_argument("--cluster-batches", type=int, default=8,
                     help="mini-batch clustering: the points are dealt into this many classes, the seeding "
                          "runs over the first and step t over class t %% batches (1 = full batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -134,10 +136,10 @@ def decode_bench(args, name, K, W, with_cpu):
         f"m={w.m} k={w.k} pre_appended={w.pre_appended} page={w.page_size} steps={K} warmup={W}")
 
     t0 = time.time()
-    inp = make_inputs(w, seed=args.seed, device=dev,
-                      kmeans_sample=args.kmeans_sample or None)
+    library_centroids = args.centroids == "library"
+    inp = make_inputs(w, seed=args.seed, device=dev, keep_q_pre=library_centroids)
     torch.cuda.synchronize()
-    log(f"[bench] synthetic inputs + centroids: {time.time() - t0:.1f} s")
+    log(f"[bench] synthetic inputs: {time.time() - t0:.1f} s")
     if w.page_size:
         k_store, bt = paginate(inp["k_cache"], w.page_size, args.seed, w.name)
         v_store, _ = paginate(inp["v_cache"], w.page_size, args.seed, w.name, bt)
@@ -149,10 +151,22 @@ def decode_bench(args, name, K, W, with_cpu):
                           partition_keys=args.partition_keys, n_subspaces=w.n_sub,
                           stream_window=args.stream_window)
     t0 = time.time()
-    ctx.build_tables(inp["centroids"], w.n_pre)
+    if library_centroids:
+        # the offline prefill as the library does it (Sec. 3.2): clustering of the prefill queries, then
+        # the table build, in one call
+        import numpy as np
+        S_ = w.n_sub
+        cent = torch.empty(B, Hkv, S_, w.C, w.head_dim // S_, dtype=torch.bfloat16, device=dev)
+        u_seed = np.random.default_rng(args.seed).uniform(size=(B, Hkv, S_, w.C)).astype(np.float32)
+        binding.csa_prefill(ctx.ctx, inp["q_pre"], w.n_pre, args.cluster_iters, max(1, args.cluster_batches), u_seed, cent)
+        inp["centroids"] = cent.view(B, Hkv, w.C, w.head_dim) if S_ == 1 else cent
+        del inp["q_pre"]
+    else:
+        ctx.build_tables(inp["centroids"], w.n_pre)
     torch.cuda.synchronize()
     t_build = time.time() - t0
-    log(f"[bench] csa_build_tables: {t_build:.2f} s (F = {binding.csa_score_frac_bits(ctx.ctx)})")
+    log(f"[bench] {'csa_prefill (clustering + tables)' if library_centroids else 'csa_build_tables'}: {t_build:.2f} s "
+        f"(F = {binding.csa_score_frac_bits(ctx.ctx)})")
 
     q_steps, k_new, v_new = inp["q_steps"], inp["k_new"], inp["v_new"]
 
@@ -357,7 +371,9 @@ def decode_bench(args, name, K, W, with_cpu):
         "stage_us": {k_: round(v, 2) for k_, v in stage_us.items()},
         "search_us": round(sum(stage_us.get(k_, 0.0) for k_ in search), 2),
         "footprint": footprint,
-        "build_tables_s": round(t_build, 2),
+        "centroids": ("csa_prefill: k-means++ seeding + %d steps, %d mini-batch classes" % (args.cluster_iters, max(1, args.cluster_batches)))
+                     if library_centroids else "random sample of the prefill queries",
+        "prefill_s" if library_centroids else "build_tables_s": round(t_build, 2),
         "roofline": roofline,
     }
 
@@ -417,16 +433,12 @@ def cluster_bench(args, w):
     import numpy as np
     import torch
     from paper_2604_08584_amd import binding
-    from paper_2604_08584_amd.workload import _gen, _mixture, stream_seed
+    from paper_2604_08584_amd.workload import make_inputs
     Hq, Hkv, G, S, C, d = w.n_q_heads, w.n_kv_heads, w.group, w.n_sub, w.C, w.head_dim
     iters = args.cluster_iters
-    q = torch.empty(1, Hq, w.n_pre, d, dtype=torch.bfloat16, device="cuda")
-    for g in range(Hkv):     # the workload's prefill-query recipe (same means as the keys, shifted)
-        gen = lambda st: _gen(q.device, stream_seed(args.seed, w.name, 0, g, st))
-        means = torch.randn(w.n_comp, d, generator=gen("k_means"), device="cuda")
-        u = torch.randn(d, generator=gen("offset"), device="cuda")
-        u = 3.0 * u / u.norm()
-        q[0, g * G:(g + 1) * G] = _mixture(means, G * w.n_pre, gen("Qpre"), shift=u).to(torch.bfloat16).view(G, w.n_pre, d)
+    # the prefill queries of one sequence, by the workload's own recipe
+    q = make_inputs(dataclasses.replace(w, batch=1, steps=1, pre_appended=0), seed=args.seed, device="cuda",
+                    keep_q_pre=True)["q_pre"]
     ctx = binding.csa_create(batch=1, n_q_heads=Hq, n_kv_heads=Hkv, n_centroids=C, list_len=w.L, n_probe=w.m,
                              budget_k=w.k, max_ctx=w.max_ctx, n_subspaces=S)
     work = torch.empty(binding.csa_cluster_workspace_bytes(ctx, w.n_pre), dtype=torch.uint8, device="cuda")

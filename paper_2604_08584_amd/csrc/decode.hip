@@ -22,10 +22,6 @@ __global__ __launch_bounds__(256) void k_score_centroids(const uint16_t *__restr
     const int bg = blockIdx.y;
     const int j = blockIdx.x * 256 + threadIdx.x;
     const uint4 *ct = cent_t + (size_t)bg * (kHeadDim / 8) * C;
-    // the centroid (requested before the queries are staged: one memory round trip, not two)
-    uint4 wv[kHeadDim / 8];
-#pragma unroll
-    for (int c = 0; c < kHeadDim / 8; ++c) wv[c] = j < C ? ct[(size_t)c * C + j] : make_uint4(0, 0, 0, 0);
     for (int h0 = 0; h0 < G; h0 += GH) {
         __syncthreads();
         for (int e = threadIdx.x; e < GH * kHeadDim; e += 256) {
@@ -37,6 +33,9 @@ __global__ __launch_bounds__(256) void k_score_centroids(const uint16_t *__restr
             float acc[GH];
 #pragma unroll
             for (int hh = 0; hh < GH; ++hh) acc[hh] = 0.0f;
+            uint4 wv[kHeadDim / 8];
+#pragma unroll
+            for (int c = 0; c < kHeadDim / 8; ++c) wv[c] = ct[(size_t)c * C + j];
 #pragma unroll
             for (int c = 0; c < kHeadDim / 8; ++c) {
                 const uint4 w = wv[c];

@@ -18,11 +18,11 @@ Recipe (per sequence b, KV head g), all draws from a torch.Generator seeded with
 * prefill query     q = mu_c + 0.5 * eps + u (same means as the keys)  (stream "Qpre")
 * value i           independent mixture of the same form, own means    (streams "v_means", "V")
 * decode query / appended key / appended value: fresh draws of the three forms above
-* centroids         per subspace (a uniform slice of the head dimension): spherical k-means over
-                    the pooled, l2-normalised sub-vectors of the prefill queries of the G query
-                    heads of the group; random-sample initialisation; `kmeans_iters` full-batch
-                    Lloyd iterations; an empty cluster keeps its centroid; rounded to bf16 once
-                    at the end.
+* centroids         NOT made here by default: the benchmark takes them from the library's own
+                    clustering of the prefill queries (make_inputs(keep_q_pre=True) returns those),
+                    and the tests bring a centroid synthesis of their own (`centroid_fn`).  Without
+                    either, the centroids are l2-normalised prefill query sub-vectors picked at
+                    random: plain sampling, enough for anything that only needs valid inputs.
 """
 from __future__ import annotations
 
@@ -104,41 +104,21 @@ def _mixture(means: torch.Tensor, n: int, gen: torch.Generator, shift=None) -> t
     return x
 
 
-def spherical_kmeans(x: torch.Tensor, C: int, iters: int, gen: torch.Generator,
-                     chunk: int = 1 << 16) -> torch.Tensor:
-    """Centroid synthesis: Lloyd iterations with cosine assignment on unit vectors.
-
-    x: [n, d] fp32 (any scale; normalised here).  Returns unit-norm fp32 [C, d].
-    """
-    x = x / x.norm(dim=1, keepdim=True).clamp_min(1e-20)
-    n, d = x.shape
-    if n >= C:
-        init = torch.randperm(n, generator=gen, device=x.device)[:C]
-    else:
-        init = torch.randint(0, n, (C,), generator=gen, device=x.device)
-    cent = x[init].clone()
-    for _ in range(iters):
-        sums = torch.zeros(C, d, dtype=torch.float32, device=x.device)
-        cnts = torch.zeros(C, dtype=torch.float32, device=x.device)
-        for s in range(0, n, chunk):
-            xs = x[s:s + chunk]
-            a = (xs @ cent.t()).argmax(dim=1)
-            sums.index_add_(0, a, xs)
-            cnts.index_add_(0, a, torch.ones_like(a, dtype=torch.float32))
-        norm = sums.norm(dim=1, keepdim=True)
-        ok = (cnts > 0).unsqueeze(1) & (norm > 1e-12)
-        cent = torch.where(ok, sums / norm.clamp_min(1e-12), cent)
-    return cent
-
-
 def make_inputs(cfg: Workload, seed: int = 0, device: str = "cpu",
-                kmeans_sample: Optional[int] = None) -> Dict[str, torch.Tensor]:
+                kmeans_sample: Optional[int] = None, centroid_fn=None,
+                keep_q_pre: bool = False) -> Dict[str, torch.Tensor]:
     """All tensors one run of `cfg` needs.
 
     Returns (bf16 unless noted):
       k_cache, v_cache [B][Hkv][max_ctx][d]  rows [0, n_pre) filled, the rest zero
       centroids        [B][Hkv][C][d], or [B][Hkv][S][C][d/S] when cfg.n_sub = S > 1;
-                                             unit norm before the bf16 rounding
+                                             unit norm before the bf16 rounding.  Made by
+                                             centroid_fn(x [n][d/S] fp32, C, iters, generator) ->
+                                             [C][d/S] fp32 per subspace from the pooled prefill query
+                                             sub-vectors of the group if given; else normalised
+                                             sub-vectors of randomly picked prefill queries.  Absent
+                                             with keep_q_pre (the caller clusters q_pre itself).
+      q_pre            [B][Hq][n_pre][d]     the prefill queries (only with keep_q_pre)
       q_steps          [T][B][Hq][d]         one decode query per head per step
       k_new, v_new     [T][B][Hkv][d]        the pair appended at each step
     with T = pre_appended + steps.  `kmeans_sample` caps the number of pooled prefill queries
@@ -152,7 +132,8 @@ def make_inputs(cfg: Workload, seed: int = 0, device: str = "cpu",
     v_cache = torch.zeros(B, Hkv, cfg.max_ctx, d, dtype=bf, device=dev)
     S = cfg.n_sub
     db = d // S
-    centroids = torch.empty(B, Hkv, S, cfg.C, db, dtype=bf, device=dev)
+    centroids = None if keep_q_pre else torch.empty(B, Hkv, S, cfg.C, db, dtype=bf, device=dev)
+    q_pre = torch.empty(B, Hq, cfg.n_pre, d, dtype=bf, device=dev) if keep_q_pre else None
     q_steps = torch.empty(T, B, Hq, d, dtype=bf, device=dev)
     k_new = torch.empty(T, B, Hkv, d, dtype=bf, device=dev)
     v_new = torch.empty(T, B, Hkv, d, dtype=bf, device=dev)
@@ -167,24 +148,35 @@ def make_inputs(cfg: Workload, seed: int = 0, device: str = "cpu",
             k_cache[b, g, :cfg.n_pre] = _mixture(k_means, cfg.n_pre, G_("K")).to(bf)
             v_cache[b, g, :cfg.n_pre] = _mixture(v_means, cfg.n_pre, G_("V")).to(bf)
             n_pool = G * cfg.n_pre
-            if kmeans_sample is not None:
+            if kmeans_sample is not None and not keep_q_pre:
                 n_pool = min(n_pool, kmeans_sample)
             # prefill queries are bf16 tensors in a model; round before clustering
-            qpre = _mixture(k_means, n_pool, G_("Qpre"), shift=u).to(bf).float()
-            g_init = G_("kmeans_init")
-            for sub in range(S):
-                cent = spherical_kmeans(qpre[:, sub * db:(sub + 1) * db].contiguous(), cfg.C,
-                                        cfg.kmeans_iters, g_init)
-                centroids[b, g, sub] = cent.to(bf)
+            qpre = _mixture(k_means, n_pool, G_("Qpre"), shift=u).to(bf)
+            if keep_q_pre:
+                q_pre[b, g * G:(g + 1) * G] = qpre.view(G, cfg.n_pre, d)
+            else:
+                g_init = G_("kmeans_init")
+                qf = qpre.float()
+                for sub in range(S):
+                    x = qf[:, sub * db:(sub + 1) * db].contiguous()
+                    if centroid_fn is not None:
+                        cent = centroid_fn(x, cfg.C, cfg.kmeans_iters, g_init)
+                    else:
+                        pick = torch.randint(0, x.shape[0], (cfg.C,), generator=g_init, device=dev)
+                        cent = x[pick] / x[pick].norm(dim=1, keepdim=True).clamp_min(1e-20)
+                    centroids[b, g, sub] = cent.to(bf)
+                del qf
             del qpre
             q_steps[:, b, g * G:(g + 1) * G] = _mixture(
                 k_means, T * G, G_("decode_q"), shift=u).to(bf).view(T, G, d)
             k_new[:, b, g] = _mixture(k_means, T, G_("append_k")).to(bf)
             v_new[:, b, g] = _mixture(v_means, T, G_("append_v")).to(bf)
-    if S == 1:
-        centroids = centroids.view(B, Hkv, cfg.C, d)
-    return dict(k_cache=k_cache, v_cache=v_cache, centroids=centroids,
-                q_steps=q_steps, k_new=k_new, v_new=v_new)
+    out = dict(k_cache=k_cache, v_cache=v_cache, q_steps=q_steps, k_new=k_new, v_new=v_new)
+    if keep_q_pre:
+        out["q_pre"] = q_pre
+    else:
+        out["centroids"] = centroids.view(B, Hkv, cfg.C, d) if S == 1 else centroids
+    return out
 
 
 def paginate(cache: torch.Tensor, page_size: int, seed: int, cfg_name: str,

@@ -16,6 +16,31 @@ from paper_2604_08584_amd.workload import Workload, make_inputs, paginate
 TOL_OUT = 2e-2   # max-abs tolerance on attention outputs (bf16 inputs, fp32 accumulation)
 
 
+def synth_centroids(x: torch.Tensor, C: int, iters: int, gen: torch.Generator, chunk: int = 1 << 16) -> torch.Tensor:
+    """Centroids for the parity tests (inputs handed identically to the library and to the oracle;
+    test infrastructure, not the library's clustering): Lloyd iterations with cosine assignment on
+    unit vectors from a random sample.  x: [n, d] fp32; returns unit-norm fp32 [C, d]."""
+    x = x / x.norm(dim=1, keepdim=True).clamp_min(1e-20)
+    n, d = x.shape
+    if n >= C:
+        init = torch.randperm(n, generator=gen, device=x.device)[:C]
+    else:
+        init = torch.randint(0, n, (C,), generator=gen, device=x.device)
+    cent = x[init].clone()
+    for _ in range(iters):
+        sums = torch.zeros(C, d, dtype=torch.float32, device=x.device)
+        cnts = torch.zeros(C, dtype=torch.float32, device=x.device)
+        for s in range(0, n, chunk):
+            xs = x[s:s + chunk]
+            a = (xs @ cent.t()).argmax(dim=1)
+            sums.index_add_(0, a, xs)
+            cnts.index_add_(0, a, torch.ones_like(a, dtype=torch.float32))
+        norm = sums.norm(dim=1, keepdim=True)
+        ok = (cnts > 0).unsqueeze(1) & (norm > 1e-12)
+        cent = torch.where(ok, sums / norm.clamp_min(1e-12), cent)
+    return cent
+
+
 def cfg_kwargs(w: Workload, F: int, partition_keys: int = 0, stream_window: int = 0):
     return dict(stream_window=stream_window, batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, n_centroids=w.C,
                 list_len=w.L, n_probe=w.m, budget_k=w.k, max_ctx=w.max_ctx, page_size=w.page_size,
@@ -29,7 +54,7 @@ class Case:
                  kmeans_sample=None, stream_window=0):
         self.w, self.F = w, F
         self.stream_window = stream_window   # > 0: appended keys are try-inserted into the tables
-        inp = make_inputs(w, seed=seed, device=gen_device, kmeans_sample=kmeans_sample)
+        inp = make_inputs(w, seed=seed, device=gen_device, kmeans_sample=kmeans_sample, centroid_fn=synth_centroids)
         self.inp = {k: v.cuda() for k, v in inp.items()}
         # logical (contiguous) host copies for the oracle; appended rows are filled in as we go
         self.K_host = oracle.bf16_bits(inp["k_cache"])
