@@ -143,12 +143,10 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
  * centroid's members are listed (in an order that depends on an atomic cursor) and summed by one
  * wave - either way the last bit of a centroid may differ between runs.
  *   q_pre_dev          bf16 [B][Hq][n_pre][d]: the prefill queries.
- *   u_seed             HOST fp32 [B][Hkv][S][C], uniforms in [0, 1) that drive the seeding: point
+ *   u_seed_dev         fp32 [B][Hkv][S][C], uniforms in [0, 1) that drive the seeding: point
  *                      floor(u_0 * n) first, then each next seed is the first point whose running
  *                      sum of squared distances to the nearest seed so far exceeds u_j * total
- *                      (n and the points: those of class 0).  It is copied to the device on
- *                      `stream` and must stay valid until that copy has run.  NULL if
- *                      init_centroids_dev is given.
+ *                      (n and the points: those of class 0).  NULL if init_centroids_dev is given.
  *   init_centroids_dev bf16 [B][Hkv][S][C][d/S] starting centroids instead of the seeding, or NULL.
  *   centroids_out_dev  bf16 [B][Hkv][S][C][d/S]: the input csa_build_tables expects.
  *   mean_cos_dev       fp32 [B][Hkv][S][max(iters,1)]: mean cosine of a step's points to their
@@ -160,24 +158,24 @@ int csa_build_tables(csa_ctx *ctx, const void *centroids_dev, int32_t n_pre, voi
  */
 int csa_cluster_workspace_bytes(const csa_ctx *ctx, int32_t n_pre, size_t *bytes);
 int csa_cluster_queries(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters,
-                        const float *u_seed, const void *init_centroids_dev, void *centroids_out_dev,
+                        const float *u_seed_dev, const void *init_centroids_dev, void *centroids_out_dev,
                         float *mean_cos_dev, int32_t *assign_dev, void *work_dev, size_t work_bytes,
                         void *stream);
 int csa_cluster_queries_minibatch(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters,
-                                  int32_t n_batches, const float *u_seed, const void *init_centroids_dev,
+                                  int32_t n_batches, const float *u_seed_dev, const void *init_centroids_dev,
                                   void *centroids_out_dev, float *mean_cos_dev, int32_t *assign_dev,
                                   void *work_dev, size_t work_bytes, void *stream);
 
 /*
  * The whole offline prefill of Sec. 3.2 in one call, from the prefill queries and the keys in the
- * bound cache: (1) csa_cluster_queries_minibatch(q_pre_dev, n_pre, iters, n_batches, u_seed) into
+ * bound cache: (1) csa_cluster_queries_minibatch(q_pre_dev, n_pre, iters, n_batches, u_seed_dev) into
  * centroids_out_dev, then (2) csa_build_tables(centroids_out_dev, n_pre), on one stream.  Arguments
  * as in those two calls (centroids_out_dev, bf16 [B][Hkv][S][C][d/S], also serves the caller: it is
  * what csa_import_tables or an oracle of the build would take).  SYNCHRONISES `stream` (the table
  * build does); errors of either part are returned.
  */
 int csa_prefill(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters, int32_t n_batches,
-                const float *u_seed, void *centroids_out_dev, void *work_dev, size_t work_bytes, void *stream);
+                const float *u_seed_dev, void *centroids_out_dev, void *work_dev, size_t work_bytes, void *stream);
 
 /*
  * Tables in the canonical layout, one KV head at a time or all at once:

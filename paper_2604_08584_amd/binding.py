@@ -149,36 +149,39 @@ def csa_cluster_workspace_bytes(ctx, n_pre) -> int:
     return b.value
 
 
+def _uniforms(u_seed, device):
+    """The seeding's uniforms as a device fp32 tensor (a numpy array is uploaded)."""
+    if u_seed is None or isinstance(u_seed, torch.Tensor):
+        return u_seed
+    import numpy as np
+    return torch.from_numpy(np.ascontiguousarray(u_seed, np.float32)).to(device)
+
+
 def csa_cluster_queries(ctx, q_pre, n_pre, iters, u_seed, init_centroids, centroids_out, mean_cos=None,
                         assign=None, work=None, n_batches=1):
-    """u_seed: host numpy float32 array (or None when init_centroids is given).  n_batches > 1 calls
-    csa_cluster_queries_minibatch."""
-    import numpy as np
+    """u_seed: fp32 uniforms, a device tensor or a numpy array (uploaded here), or None when
+    init_centroids is given.  n_batches > 1 calls csa_cluster_queries_minibatch."""
     if work is None:
         work = torch.empty(csa_cluster_workspace_bytes(ctx, n_pre), dtype=torch.uint8, device=q_pre.device)
-    useed_p = None
-    if u_seed is not None:
-        u_seed = np.ascontiguousarray(u_seed, np.float32)
-        useed_p = u_seed.ctypes.data_as(C.c_void_p)
+    u_dev = _uniforms(u_seed, q_pre.device)
     if n_batches == 1:
-        _check(lib().csa_cluster_queries(ctx, _ptr(q_pre), n_pre, iters, useed_p, _ptr(init_centroids),
+        _check(lib().csa_cluster_queries(ctx, _ptr(q_pre), n_pre, iters, _ptr(u_dev), _ptr(init_centroids),
                                          _ptr(centroids_out), _ptr(mean_cos), _ptr(assign), _ptr(work),
                                          work.numel(), _stream()), "csa_cluster_queries")
     else:
-        _check(lib().csa_cluster_queries_minibatch(ctx, _ptr(q_pre), n_pre, iters, n_batches, useed_p,
+        _check(lib().csa_cluster_queries_minibatch(ctx, _ptr(q_pre), n_pre, iters, n_batches, _ptr(u_dev),
                                                    _ptr(init_centroids), _ptr(centroids_out), _ptr(mean_cos),
                                                    _ptr(assign), _ptr(work), work.numel(), _stream()),
                "csa_cluster_queries_minibatch")
-    torch.cuda.current_stream().synchronize()   # u_seed (host memory) and work stay alive until here
+    torch.cuda.current_stream().synchronize()   # the uniforms and the work buffer stay alive until here
 
 
 def csa_prefill(ctx, q_pre, n_pre, iters, n_batches, u_seed, centroids_out, work=None):
     """Clustering of the prefill queries, then the table build, in one call (synchronises)."""
-    import numpy as np
     if work is None:
         work = torch.empty(csa_cluster_workspace_bytes(ctx, n_pre), dtype=torch.uint8, device=q_pre.device)
-    u_seed = np.ascontiguousarray(u_seed, np.float32)
-    _check(lib().csa_prefill(ctx, _ptr(q_pre), n_pre, iters, n_batches, u_seed.ctypes.data_as(C.c_void_p),
+    u_dev = _uniforms(u_seed, q_pre.device)
+    _check(lib().csa_prefill(ctx, _ptr(q_pre), n_pre, iters, n_batches, _ptr(u_dev),
                              _ptr(centroids_out), _ptr(work), work.numel(), _stream()), "csa_prefill")
 
 

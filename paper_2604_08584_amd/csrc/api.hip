@@ -446,12 +446,12 @@ int csa_cluster_workspace_bytes(const csa_ctx *ctx, int32_t n_pre, size_t *bytes
 }
 
 int csa_cluster_queries_minibatch(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters,
-                                  int32_t n_batches, const float *u_seed, const void *init_centroids_dev,
+                                  int32_t n_batches, const float *u_seed_dev, const void *init_centroids_dev,
                                   void *centroids_out_dev, float *mean_cos_dev, int32_t *assign_dev,
                                   void *work_dev, size_t work_bytes, void *stream)
 {
     if (!ctx || !q_pre_dev || !centroids_out_dev || !work_dev) return CSA_ERR_ARG;
-    if (n_pre < 1 || iters < 0 || (!u_seed && !init_centroids_dev)) return CSA_ERR_ARG;
+    if (n_pre < 1 || iters < 0 || (!u_seed_dev && !init_centroids_dev)) return CSA_ERR_ARG;
     if ((uintptr_t)work_dev % kAlign) return CSA_ERR_ARG;
     const csa_config &c = ctx->cfg;
     const int G = c.n_q_heads / c.n_kv_heads, S = c.n_subspaces, C = c.n_centroids, db = c.head_dim / S;
@@ -466,7 +466,7 @@ int csa_cluster_queries_minibatch(csa_ctx *ctx, const void *q_pre_dev, int32_t n
         const size_t p0 = (size_t)b * n_prob;  // the sequence's first problem
         const int rc = csa::cluster_sequence(
             (const uint16_t *)q_pre_dev + (size_t)b * c.n_q_heads * n_pre * c.head_dim, n_pre, G, c.n_kv_heads, S, C,
-            iters, n_batches, u_seed ? u_seed + p0 * C : nullptr,
+            iters, n_batches, u_seed_dev ? u_seed_dev + p0 * C : nullptr,
             init_centroids_dev ? (const uint16_t *)init_centroids_dev + p0 * C * db : nullptr,
             (uint16_t *)centroids_out_dev + p0 * C * db, mean_cos_dev ? mean_cos_dev + p0 * it_eff : nullptr,
             assign_dev ? assign_dev + p0 * n_pool : nullptr, work_dev, st);
@@ -476,21 +476,21 @@ int csa_cluster_queries_minibatch(csa_ctx *ctx, const void *q_pre_dev, int32_t n
 }
 
 int csa_cluster_queries(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters,
-                        const float *u_seed, const void *init_centroids_dev, void *centroids_out_dev,
+                        const float *u_seed_dev, const void *init_centroids_dev, void *centroids_out_dev,
                         float *mean_cos_dev, int32_t *assign_dev, void *work_dev, size_t work_bytes,
                         void *stream)
 {
-    return csa_cluster_queries_minibatch(ctx, q_pre_dev, n_pre, iters, 1, u_seed, init_centroids_dev,
+    return csa_cluster_queries_minibatch(ctx, q_pre_dev, n_pre, iters, 1, u_seed_dev, init_centroids_dev,
                                          centroids_out_dev, mean_cos_dev, assign_dev, work_dev, work_bytes, stream);
 }
 
 int csa_prefill(csa_ctx *ctx, const void *q_pre_dev, int32_t n_pre, int32_t iters, int32_t n_batches,
-                const float *u_seed, void *centroids_out_dev, void *work_dev, size_t work_bytes, void *stream)
+                const float *u_seed_dev, void *centroids_out_dev, void *work_dev, size_t work_bytes, void *stream)
 {
     if (!ctx) return CSA_ERR_ARG;
     if (!ctx->bound) return CSA_ERR_STATE;
-    if (!u_seed) return CSA_ERR_ARG;
-    const int rc = csa_cluster_queries_minibatch(ctx, q_pre_dev, n_pre, iters, n_batches, u_seed, nullptr,
+    if (!u_seed_dev) return CSA_ERR_ARG;
+    const int rc = csa_cluster_queries_minibatch(ctx, q_pre_dev, n_pre, iters, n_batches, u_seed_dev, nullptr,
                                                  centroids_out_dev, nullptr, nullptr, work_dev, work_bytes, stream);
     if (rc != CSA_OK) return rc;
     return csa_build_tables(ctx, centroids_out_dev, n_pre, stream);

@@ -591,7 +591,7 @@ namespace {
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct WorkLayout {
-    size_t inv_norm, dist, part, sums, counts, run_cnt, cent16, pick, cos_sum, assign_work, start, cursor, u, bytes;
+    size_t inv_norm, dist, part, sums, counts, run_cnt, cent16, pick, cos_sum, assign_work, start, cursor, bytes;
     int n_blk, cap;
 };
 
@@ -616,7 +616,6 @@ WorkLayout work_layout(int n_prob, int n_all, int C, int db, int n_batches)
     put(w.assign_work, P * w.cap * 4);
     put(w.start, P * (C + 1) * 4);
     put(w.cursor, P * (C + 1) * 4);
-    put(w.u, P * C * 4);
     w.bytes = off;
     return w;
 }
@@ -649,10 +648,8 @@ hipError_t cluster_sequence_db(const uint16_t *q_seq, int n_pre, int G, int Hkv,
         if (e != hipSuccess) return e;
     } else {
         // k-means++ over the first view; one launch per round serves every problem
-        e = hipMemcpyAsync(work + w.u, u_seed, (size_t)n_prob * C * 4, hipMemcpyHostToDevice, st);
-        if (e != hipSuccess) return e;
         const SeedArgs sa{inv_norm, (float *)(work + w.dist), (float *)(work + w.part), cent16,
-                          (int32_t *)(work + w.pick), (const float *)(work + w.u), w.n_blk, C};
+                          (int32_t *)(work + w.pick), u_seed, w.n_blk, C};
         const int snake = (size_t)all.n_view * DB * 2 * n_prob > ((size_t)64 << 20) ? 1 : 0;
         for (int j = 0; j < C; ++j) {
             k_km_seed_update<DB><<<dim3(w.n_blk, n_prob), 256, 0, st>>>(all, sa, j, snake);
@@ -702,7 +699,7 @@ size_t cluster_work_bytes(int n_prob, int n_all, int C, int db)
 }
 
 // All (KV head, subspace) problems of one sequence.  q_seq: [Hq][n_pre][128] bf16 of the sequence;
-// u_seed: HOST [Hkv*S][C] or NULL; init / out: device bf16 [Hkv*S][C][128/S]; mean_cos_out: device
+// u_seed: device fp32 [Hkv*S][C] or NULL; init / out: device bf16 [Hkv*S][C][128/S]; mean_cos_out: device
 // [Hkv*S][max(iters,1)] or NULL; assign_out: device [Hkv*S][G*n_pre] or NULL.
 int cluster_sequence(const void *q_seq, int n_pre, int G, int Hkv, int S, int C, int iters, int n_batches,
                      const float *u_seed, const void *init, void *out, float *mean_cos_out,

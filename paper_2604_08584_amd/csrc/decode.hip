@@ -558,17 +558,27 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
         int n_wide[kAccRows], n_tail[kAccRows];
         const uint32_t *rp[kAccRows];
         int rounds = 0;
+        // the constants of the wave's rows come out of LDS with ONE read - lane (what, j) fetches
+        // constant `what` of row j - and are handed out by lane reads; a read per constant would be a
+        // chain of two dozen LDS round trips
+        int gv = 0;
+        {
+            const int jj = lane % kAccRows, what = lane / kAccRows;  // what: lo, hi, b1, b2, b3, row
+            const int r = r0 + jj * NW;
+            const int rr = r < m ? r : r0;
+            const int within = what == 1 ? NSUB : what == 0 ? 0 : what - 1;
+            const int32_t *src = what == 5 ? s_row + rr : s_b + rr * NB + min(within, NSUB);
+            if (what <= 5) gv = *src;
+        }
 #pragma unroll
         for (int j = 0; j < kAccRows; ++j) {
-            const int r = r0 + j * NW;
-            const bool on = r < m;
-            const int rr = on ? r : r0;
-            lo[j] = __builtin_amdgcn_readfirstlane(s_b[rr * NB]);
-            hi[j] = on ? __builtin_amdgcn_readfirstlane(s_b[rr * NB + NSUB]) : lo[j];  // empty if no such row
-            b1[j] = NSUB > 1 ? __builtin_amdgcn_readfirstlane(s_b[rr * NB + 1]) : 0x7FFFFFFF;
-            b2[j] = NSUB > 2 ? __builtin_amdgcn_readfirstlane(s_b[rr * NB + 2]) : 0x7FFFFFFF;
-            b3[j] = NSUB > 2 ? __builtin_amdgcn_readfirstlane(s_b[rr * NB + 3]) : 0x7FFFFFFF;
-            rp[j] = ent + ((size_t)bg * C + __builtin_amdgcn_readfirstlane(s_row[rr])) * Ls;
+            const bool on = r0 + j * NW < m;
+            lo[j] = __builtin_amdgcn_readlane(gv, 0 * kAccRows + j);
+            hi[j] = on ? __builtin_amdgcn_readlane(gv, 1 * kAccRows + j) : lo[j];  // empty if no such row
+            b1[j] = NSUB > 1 ? __builtin_amdgcn_readlane(gv, 2 * kAccRows + j) : 0x7FFFFFFF;
+            b2[j] = NSUB > 2 ? __builtin_amdgcn_readlane(gv, 3 * kAccRows + j) : 0x7FFFFFFF;
+            b3[j] = NSUB > 2 ? __builtin_amdgcn_readlane(gv, 4 * kAccRows + j) : 0x7FFFFFFF;
+            rp[j] = ent + ((size_t)bg * C + __builtin_amdgcn_readlane(gv, 5 * kAccRows + j)) * Ls;
             lo[j] = min(lo[j], hi[j]);
             // the slice from its 16-byte boundary: rounds of 16 bytes per lane, and - when what is
             // left after them fits one entry per lane - one such round instead of a mostly idle wide
