@@ -238,6 +238,262 @@ constexpr int kIdxBits = 14;   // key index within a range of <= 16384 keys
 constexpr int kThrShift = 22;  // score bits within a bin: < 2^18
 
 // ---------------------------------------------------------------------------------------------
+// Top-K, first half (paper Sec. 3.3 (4)): the threshold of one head.  Every key range's candidates
+// are grouped by coarse score bin (best first) with the bins' start offsets, so the head's histogram
+// is a sum of offset differences, the bin B holding the k-th largest score follows from it, and
+// everything in better bins is selected without being looked at.  Only the candidates of bin B (a
+// run per key range) are read: their scores within the bin are searched for the value T such that
+// the winners are every candidate above T plus the `need` lowest-index candidates equal to T - in
+// LDS by a radix search when the bin holds few enough, else by refining the range with histogram
+// passes over the runs first.  The result is B << kThrShift | T (0xFFFFFFFF: nothing selected;
+// B = 512: every candidate) and, per range, its first output slot and the ties it may keep.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSelCap = 4096;   // contenders finished in LDS
+constexpr int kSelMaxP = 2048;  // key ranges (segments) per head
+constexpr int kSegBits = 11;    // a contender is (score within the bin) << kSegBits | p
+static_assert((1 << kSegBits) >= kSelMaxP, "segment tag too narrow");
+
+// LDS of head_threshold for workgroups of NT threads and heads of up to MAXP key ranges
+template <int NT, int MAXP>
+struct ThrSmem {
+    uint32_t hist[512 + NT / kWave + 2];
+    int scan[NT / kWave + 1];
+    uint32_t ck[kSelCap];
+    int32_t cnt[MAXP], gt[MAXP], eq[MAXP];
+    uint16_t beg[MAXP], end[MAXP];  // the run of the threshold's bin in every range
+    int n;
+};
+
+// The threshold of one head from its ranges' candidates (hk), counts (seg_cnt) and bin offsets (bo);
+// all NT threads of the workgroup call.  Returns T (see above) and k_eff = min(k, candidates); for
+// every range p, on_range(p, first output slot, ties allowed) is called by one thread, and sm.beg[p] /
+// sm.end[p] / sm.cnt[p] hold the run of the threshold's bin and the range's candidate count.  Ends
+// with the calls to on_range, not with a barrier.  P <= MAXP.
+template <int kThrNT, int MAXP, class OnRange>
+__device__ __forceinline__ uint32_t head_threshold(const uint32_t *__restrict__ hk,
+                                                   const int32_t *__restrict__ seg_cnt,
+                                                   const uint16_t *__restrict__ bo, int k, int R, int P,
+                                                   int key_sh, ThrSmem<kThrNT, MAXP> &sm, int &k_eff_out,
+                                                   OnRange on_range)
+{
+    constexpr int NW = kThrNT / kWave;
+    uint32_t *s_hist = sm.hist;
+    int *s_scan = sm.scan;
+    uint32_t *s_ck = sm.ck;
+    int32_t *s_cnt = sm.cnt, *s_gt = sm.gt, *s_eq = sm.eq;
+    uint16_t *s_beg = sm.beg, *s_end = sm.end;
+    int &s_n = sm.n;
+    static_assert(kCoarseBins == 512 && (512 % kThrNT == 0 || kThrNT % 512 == 0), "whole bins per thread");
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
+    // the head's histogram, bin j = sum over the ranges of (start of bin j+1) - (start of bin j):
+    // a wave reads a range's 512 offsets with one 16-byte load per lane (lane = eight consecutive
+    // bins); the first two ranges of every wave are requested before anything is waited for
+    static_assert(kCoarseBins == 8 * kWave, "one 16-byte load per lane covers a range's offsets");
+    auto hist_load = [&](int p) {
+        return p < P ? *(const uint4 *)(bo + (size_t)p * kCoarseBins + lane * 8) : make_uint4(0, 0, 0, 0);
+    };
+    const uint4 hpre[4] = {hist_load(wave), hist_load(wave + NW), hist_load(wave + 2 * NW), hist_load(wave + 3 * NW)};
+    int part = 0;
+    for (int p = threadIdx.x; p < MAXP; p += kThrNT) {
+        const int c = p < P ? min(seg_cnt[p], R) : 0;
+        s_cnt[p] = c;
+        s_gt[p] = 0;
+        s_eq[p] = 0;
+        part += c;
+    }
+    for (int i = threadIdx.x; i < 512; i += kThrNT) s_hist[i] = 0;  // (walked top = best by block_pick_bin)
+    if (threadIdx.x == 0) s_n = 0;
+    int n_total;
+    block_excl_scan<kThrNT>(part, s_scan, n_total);  // (its barriers also publish the LDS writes)
+    const int k_eff = n_total < k ? n_total : k;
+    k_eff_out = k_eff;
+
+    uint32_t T = 0xFFFFFFFFu;
+    int need = 0;
+    if (k_eff > 0 && n_total <= k) {
+        T = (uint32_t)kCoarseBins << kThrShift;  // every candidate wins
+        for (int p = threadIdx.x; p < P; p += kThrNT) {
+            s_gt[p] = s_cnt[p];
+            s_beg[p] = s_end[p] = (uint16_t)s_cnt[p];
+        }
+    } else if (k_eff > 0) {
+        for (int p = wave, it = 0; p < P; p += NW, ++it) {
+            const uint4 v = it < 4 ? hpre[it] : hist_load(p);
+            // start of the bin after this lane's eight: the next lane's first, or the range's count
+            uint32_t nxt = (uint32_t)__shfl_down((int)(v.x & 0xFFFFu), 1, kWave);
+            if (lane == kWave - 1) nxt = (uint32_t)s_cnt[p];
+            const uint32_t o[9] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16, v.z & 0xFFFFu,
+                                   v.z >> 16, v.w & 0xFFFFu, v.w >> 16, nxt};
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (o[i + 1] > o[i]) atomicAdd(&s_hist[(kCoarseBins - 1) - (lane * 8 + i)], o[i + 1] - o[i]);
+        }
+        __syncthreads();
+        int above;
+        const int top_bin = block_pick_bin<kThrNT, 512>(s_hist, k, s_hist + 512, above);
+        const int B = (kCoarseBins - 1) - top_bin;  // as the accumulation kernel numbers the bins
+        int in_bin = (int)s_hist[top_bin];
+        int want = k - above;  // how many of bin B's candidates are selected (>= 1)
+        if (P <= 4 * NW) {
+            // every range's offsets are still in the registers of the wave that loaded them: the
+            // lane that holds bin B hands out the run, no second trip to memory
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int p = wave + it * NW;
+                if (p >= P) break;
+                const uint4 v = hpre[it];
+                uint32_t nxt = (uint32_t)__shfl_down((int)(v.x & 0xFFFFu), 1, kWave);
+                if (lane == kWave - 1) nxt = (uint32_t)s_cnt[p];
+                if (lane == (B >> 3)) {
+                    const uint32_t o[9] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16, v.z & 0xFFFFu,
+                                           v.z >> 16, v.w & 0xFFFFu, v.w >> 16, nxt};
+                    uint32_t b0 = o[0], b1 = o[1];
+#pragma unroll
+                    for (int i = 1; i < 8; ++i)
+                        if ((B & 7) == i) { b0 = o[i]; b1 = o[i + 1]; }
+                    s_beg[p] = (uint16_t)b0;
+                    s_end[p] = (uint16_t)b1;
+                    s_gt[p] = (int)b0;  // every candidate of a better bin
+                }
+            }
+        } else {
+            for (int p = threadIdx.x; p < P; p += kThrNT) {
+                const int c = s_cnt[p];
+                const int b0 = c > 0 ? (int)bo[(size_t)p * kCoarseBins + B] : 0;
+                const int b1 = c > 0 ? (B + 1 < kCoarseBins ? (int)bo[(size_t)p * kCoarseBins + B + 1] : c) : 0;
+                s_beg[p] = (uint16_t)b0;
+                s_end[p] = (uint16_t)b1;
+                s_gt[p] = b0;  // every candidate of a better bin
+            }
+        }
+        __syncthreads();
+        // runs(fn, seg_end): fn(score within the bin, valid, p) for the candidates of bin B of every
+        // range p (a wave walks whole runs, one candidate per lane and round), then seg_end(p)
+        auto runs = [&](auto fn, auto seg_end) {
+            for (int p = wave; p < P; p += NW) {
+                const int b0 = __builtin_amdgcn_readfirstlane((int)s_beg[p]);
+                const int b1 = __builtin_amdgcn_readfirstlane((int)s_end[p]);
+                for (int e0 = b0; e0 < b1; e0 += kWave) {
+                    const bool valid = e0 + lane < b1;
+                    const uint32_t w = valid ? hk[(size_t)p * R + e0 + lane] : 0u;
+                    fn(w >> kIdxBits, valid, p);
+                }
+                seg_end(p);
+            }
+        };
+        // the live score range [lo, hi] within the bin, narrowed until few enough candidates remain
+        uint32_t lo = 0, hi = (1u << key_sh) - 1u;
+        for (;;) {
+            if (in_bin <= kSelCap) {
+                // gather the contenders, tagged with their range; candidates above the live range are
+                // sure winners of their range
+                int n_gt = 0;  // (wave-uniform)
+                runs([&](uint32_t key, bool valid, int p) {
+                         n_gt += __popcll(__ballot(valid && key > hi));
+                         const bool in = valid && key >= lo && key <= hi;
+                         const unsigned long long m = __ballot(in);
+                         if (m) {
+                             int o = 0;
+                             if (lane == 0) o = atomicAdd(&s_n, __popcll(m));
+                             o = __builtin_amdgcn_readfirstlane(o) + mbcnt(m);
+                             if (in && o < kSelCap) s_ck[o] = ((key - lo) << kSegBits) | (uint32_t)p;
+                         }
+                     },
+                     [&](int p) {
+                         if (lane == 0 && n_gt) s_gt[p] += n_gt;
+                         n_gt = 0;
+                     });
+                __syncthreads();
+                const int nc = min(s_n, kSelCap);
+                const uint32_t Tl = block_radix_threshold<kThrNT, 8, 2>(
+                    [&](auto fn) {
+                        for (int a0 = 0; a0 < nc; a0 += kThrNT) {
+                            const int a = a0 + threadIdx.x;
+                            fn(a < nc ? s_ck[a] >> kSegBits : 0u, a < nc);
+                        }
+                    },
+                    want, s_hist, need);
+                T = ((uint32_t)B << kThrShift) | (lo + Tl);
+                for (int a = threadIdx.x; a < nc; a += kThrNT) {
+                    const uint32_t c = s_ck[a];
+                    const uint32_t kk = c >> kSegBits;
+                    const int p = (int)(c & ((1u << kSegBits) - 1u));
+                    if (kk > Tl)
+                        atomicAdd(&s_gt[p], 1);
+                    else if (kk == Tl)
+                        atomicAdd(&s_eq[p], 1);
+                }
+                break;
+            }
+            if (lo == hi) {
+                // a single score value: count, per range, the candidates above and equal to it
+                T = ((uint32_t)B << kThrShift) | lo;
+                need = want;
+                int n_gt = 0, n_eq = 0;
+                runs([&](uint32_t key, bool valid, int) {
+                         n_gt += __popcll(__ballot(valid && key > lo));
+                         n_eq += __popcll(__ballot(valid && key == lo));
+                     },
+                     [&](int p) {
+                         if (lane == 0) {
+                             s_gt[p] += n_gt;
+                             s_eq[p] = n_eq;
+                         }
+                         n_gt = 0;
+                         n_eq = 0;
+                     });
+                break;
+            }
+            // too many: histogram of the live range over <= 512 equal bins, keep the bin with the
+            // want-th largest
+            int sh = 0;
+            while (((hi - lo) >> sh) >= 512u) ++sh;
+            __syncthreads();
+            for (int i = threadIdx.x; i < 512; i += kThrNT) s_hist[i] = 0;
+            __syncthreads();
+            runs([&](uint32_t key, bool valid, int) {
+                     const bool in = valid && key >= lo && key <= hi;
+                     hist_add(s_hist, in ? (key - lo) >> sh : 0u, in);
+                 },
+                 [&](int) {});
+            __syncthreads();
+            const int bin = block_pick_bin<kThrNT, 512>(s_hist, want, s_hist + 512, above);
+            in_bin = (int)s_hist[bin];
+            want -= above;
+            lo += (uint32_t)bin << sh;
+            hi = min(hi, lo + ((1u << sh) - 1u));
+        }
+    }
+    __syncthreads();
+    // per range: its share of the ties (lowest ranges first) and its first output slot; thread t
+    // owns the RPT consecutive ranges starting at t * RPT (threads past MAXP / RPT own none)
+    constexpr int RPT = MAXP >= kThrNT ? MAXP / kThrNT : 1;
+    const int p0 = RPT * (int)threadIdx.x;
+    const bool own = p0 < MAXP;
+    int e_mine = 0;
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) e_mine += own ? s_eq[p0 + i] : 0;
+    int dummy;
+    int ties_before = block_excl_scan<kThrNT>(e_mine, s_scan, dummy);
+    int al[RPT], take_mine = 0;
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const int e = own ? s_eq[p0 + i] : 0;
+        al[i] = max(0, min(e, need - ties_before));
+        ties_before += e;
+        take_mine += (own ? s_gt[p0 + i] : 0) + al[i];
+    }
+    int off = block_excl_scan<kThrNT>(take_mine, s_scan, dummy);
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        if (own && p0 + i < P) on_range(p0 + i, off, al[i]);
+        off += (own ? s_gt[p0 + i] : 0) + al[i];
+    }
+    return T;
+}
+
+
+// ---------------------------------------------------------------------------------------------
 // Top-K, second half (paper Sec. 3.3 (4)) for key range p of one head: the range writes its winners
 // - its candidates in bins better than the threshold's, those of the threshold's bin above the
 // threshold, plus its allowed number of lowest-index candidates equal to it - as ascending key
@@ -252,29 +508,29 @@ constexpr int kThrShift = 22;  // score bits within a bin: < 2^18
 // ---------------------------------------------------------------------------------------------
 constexpr int kEmitPre = 2;  // candidate words per thread requested up front
 
+// the range's first candidate words, requested before its threshold is known
 template <int NT>
-__device__ __forceinline__ int emit_range(const uint32_t *__restrict__ cand_key,
-                                          const int2 *__restrict__ seg_run,
-                                          const int32_t *__restrict__ seg_cnt,
-                                          const uint32_t *__restrict__ thr,
-                                          const int2 *__restrict__ seg_par, int32_t *__restrict__ sel,
-                                          int k, int R, int P, size_t cand_stride, int head, int p,
-                                          uint32_t *s_bits, int *s_scan, int &first,
-                                          int32_t *s_list = nullptr, int list_cap = 0)
+__device__ __forceinline__ void emit_prefetch(const uint32_t *__restrict__ dk, int R, uint32_t (&pre)[kEmitPre])
 {
-    const uint32_t *dk = cand_key + (size_t)head * cand_stride + (size_t)p * R;
-    const int W = R / 32;
-    uint32_t *s_tie = s_bits + W;
-    uint32_t pre[kEmitPre];
 #pragma unroll
     for (int u = 0; u < kEmitPre; ++u) {
         const int i = u * NT + (int)threadIdx.x;
         pre[u] = i < R ? dk[i] : 0u;  // (slots past the count hold stale words; masked below)
     }
-    const int c = min(seg_cnt[(size_t)head * P + p], R);
-    const uint32_t T = thr[head];
-    const int2 par = seg_par[(size_t)head * P + p];
-    const int2 run = seg_run[(size_t)head * P + p];  // (holds stale values when nothing is selected)
+}
+
+// dk: the range's candidate words; c: how many; T: the head's threshold; par = (first output slot,
+// ties allowed); run = (start, end) of the threshold's bin among the words (unused when T says
+// nothing is selected); pre: emit_prefetch(dk).
+template <int NT>
+__device__ __forceinline__ int emit_range_core(const uint32_t *__restrict__ dk, const uint32_t (&pre)[kEmitPre],
+                                               int c, uint32_t T, int2 par, int2 run,
+                                               int32_t *__restrict__ out, int k, int R, int p,
+                                               uint32_t *s_bits, int *s_scan, int &first,
+                                               int32_t *s_list, int list_cap)
+{
+    const int W = R / 32;
+    uint32_t *s_tie = s_bits + W;
     first = par.x;
     if (c <= 0 || T == 0xFFFFFFFFu) return 0;  // (uniform over the workgroup)
     const uint32_t Tl = T & ((1u << kThrShift) - 1u);
@@ -314,7 +570,6 @@ __device__ __forceinline__ int emit_range(const uint32_t *__restrict__ cand_key,
     }
     bits |= eq;
     int pos = par.x + block_excl_scan<NT>(__popc(bits), s_scan, total);
-    int32_t *out = sel + (size_t)head * k;
     const int kbase = p * R + (int)threadIdx.x * 32;
     for (; bits; bits &= bits - 1) {
         const int key = kbase + __ffs(bits) - 1;
@@ -323,6 +578,28 @@ __device__ __forceinline__ int emit_range(const uint32_t *__restrict__ cand_key,
         ++pos;
     }
     return total;
+}
+
+// The same with the range's records read from memory (written by k_threshold).
+template <int NT>
+__device__ __forceinline__ int emit_range(const uint32_t *__restrict__ cand_key,
+                                          const int2 *__restrict__ seg_run,
+                                          const int32_t *__restrict__ seg_cnt,
+                                          const uint32_t *__restrict__ thr,
+                                          const int2 *__restrict__ seg_par, int32_t *__restrict__ sel,
+                                          int k, int R, int P, size_t cand_stride, int head, int p,
+                                          uint32_t *s_bits, int *s_scan, int &first,
+                                          int32_t *s_list = nullptr, int list_cap = 0)
+{
+    const uint32_t *dk = cand_key + (size_t)head * cand_stride + (size_t)p * R;
+    uint32_t pre[kEmitPre];
+    emit_prefetch<NT>(dk, R, pre);
+    const int c = min(seg_cnt[(size_t)head * P + p], R);
+    const uint32_t T = thr[head];
+    const int2 par = seg_par[(size_t)head * P + p];
+    const int2 run = seg_run[(size_t)head * P + p];  // (holds stale values when nothing is selected)
+    return emit_range_core<NT>(dk, pre, c, T, par, run, sel + (size_t)head * k, k, R, p, s_bits, s_scan, first,
+                               s_list, list_cap);
 }
 
 }  // namespace csa

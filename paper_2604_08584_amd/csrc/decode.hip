@@ -757,11 +757,7 @@ void launch_accumulate(const void *ent, int32_t *rows, const int32_t *spans, uin
 //   seg_par[head][p] = (first output slot of range p, ties range p may keep).
 // grid B*Hq, block NT.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSelCap = 4096;   // contenders finished in LDS
-constexpr int kSelMaxP = 2048;  // key ranges (segments) per head
-constexpr int kSegBits = 11;    // a contender is (score within the bin) << kSegBits | p
-static_assert((1 << kSegBits) >= kSelMaxP, "segment tag too narrow");
-
+// grid B*Hq, block NT.
 template <int kThrNT>
 __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict__ cand_key,
                                                       const int32_t *__restrict__ seg_cnt,
@@ -773,227 +769,22 @@ __global__ __launch_bounds__(kThrNT) void k_threshold(const uint32_t *__restrict
                                                       int2 *__restrict__ seg_run, int k, int R, int P,
                                                       size_t cand_stride, int key_sh)
 {
-    constexpr int NW = kThrNT / kWave;
-    __shared__ uint32_t s_hist[512 + kThrNT / kWave + 2];
-    __shared__ int s_scan[kThrNT / kWave + 1];
-    __shared__ uint32_t s_ck[kSelCap];
-    __shared__ int32_t s_cnt[kSelMaxP], s_gt[kSelMaxP], s_eq[kSelMaxP];
-    __shared__ uint16_t s_beg[kSelMaxP], s_end[kSelMaxP];  // the run of bin B in every range
-    __shared__ int s_n;
-    static_assert(kCoarseBins == 512 && kCoarseBins <= kThrNT, "one bin per thread");
+    __shared__ ThrSmem<kThrNT, kSelMaxP> sm;
     const int head = blockIdx.x;
-    const uint32_t *hk = cand_key + (size_t)head * cand_stride;
-    const uint16_t *bo = bin_off + (size_t)head * P * kCoarseBins;
+    int k_eff;
+    const uint32_t T = head_threshold<kThrNT, kSelMaxP>(
+        cand_key + (size_t)head * cand_stride, seg_cnt + (size_t)head * P,
+        bin_off + (size_t)head * P * kCoarseBins, k, R, P, key_sh, sm, k_eff, [&](int p, int off, int al) {
+            seg_par[(size_t)head * P + p] = make_int2(off, al);
+            // (sm.beg / sm.end are only set when something is selected)
+            if (k_eff > 0) seg_run[(size_t)head * P + p] = make_int2((int)sm.beg[p], (int)sm.end[p]);
+        });
+    if (threadIdx.x == 0) {
+        sel_count[head] = k_eff;
+        thr[head] = T;
+    }
     int32_t *out = sel + (size_t)head * k;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
-    // the head's histogram, bin j = sum over the ranges of (start of bin j+1) - (start of bin j):
-    // a wave reads a range's 512 offsets with one 16-byte load per lane (lane = eight consecutive
-    // bins); the first two ranges of every wave are requested before anything is waited for
-    static_assert(kCoarseBins == 8 * kWave, "one 16-byte load per lane covers a range's offsets");
-    auto hist_load = [&](int p) {
-        return p < P ? *(const uint4 *)(bo + (size_t)p * kCoarseBins + lane * 8) : make_uint4(0, 0, 0, 0);
-    };
-    const uint4 hpre0 = hist_load(wave), hpre1 = hist_load(wave + NW);
-    int part = 0;
-    for (int p = threadIdx.x; p < kSelMaxP; p += kThrNT) {
-        const int c = p < P ? min(seg_cnt[(size_t)head * P + p], R) : 0;
-        s_cnt[p] = c;
-        s_gt[p] = 0;
-        s_eq[p] = 0;
-        part += c;
-    }
-    for (int i = threadIdx.x; i < 512; i += kThrNT) s_hist[i] = 0;  // (walked top = best by block_pick_bin)
-    if (threadIdx.x == 0) s_n = 0;
-    int n_total;
-    block_excl_scan<kThrNT>(part, s_scan, n_total);  // (its barriers also publish the LDS writes)
-    const int k_eff = n_total < k ? n_total : k;
-    if (threadIdx.x == 0) sel_count[head] = k_eff;
     for (int a = k_eff + threadIdx.x; a < k; a += kThrNT) out[a] = -1;
-
-    uint32_t T = 0xFFFFFFFFu;
-    int need = 0;
-    if (k_eff > 0 && n_total <= k) {
-        T = (uint32_t)kCoarseBins << kThrShift;  // every candidate wins
-        for (int p = threadIdx.x; p < P; p += kThrNT) {
-            s_gt[p] = s_cnt[p];
-            s_beg[p] = s_end[p] = (uint16_t)s_cnt[p];
-        }
-    } else if (k_eff > 0) {
-        for (int p = wave, it = 0; p < P; p += NW, ++it) {
-            const uint4 v = it == 0 ? hpre0 : it == 1 ? hpre1 : hist_load(p);
-            // start of the bin after this lane's eight: the next lane's first, or the range's count
-            uint32_t nxt = (uint32_t)__shfl_down((int)(v.x & 0xFFFFu), 1, kWave);
-            if (lane == kWave - 1) nxt = (uint32_t)s_cnt[p];
-            const uint32_t o[9] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16, v.z & 0xFFFFu,
-                                   v.z >> 16, v.w & 0xFFFFu, v.w >> 16, nxt};
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (o[i + 1] > o[i]) atomicAdd(&s_hist[(kCoarseBins - 1) - (lane * 8 + i)], o[i + 1] - o[i]);
-        }
-        __syncthreads();
-        int above;
-        const int top_bin = block_pick_bin<kThrNT, 512>(s_hist, k, s_hist + 512, above);
-        const int B = (kCoarseBins - 1) - top_bin;  // as the accumulation kernel numbers the bins
-        int in_bin = (int)s_hist[top_bin];
-        int want = k - above;  // how many of bin B's candidates are selected (>= 1)
-        if (P <= 2 * NW) {
-            // every range's offsets are still in the registers of the wave that loaded them: the
-            // lane that holds bin B hands out the run, no second trip to memory
-            for (int it = 0; it < 2; ++it) {
-                const int p = wave + it * NW;
-                if (p >= P) break;
-                const uint4 v = it == 0 ? hpre0 : hpre1;
-                uint32_t nxt = (uint32_t)__shfl_down((int)(v.x & 0xFFFFu), 1, kWave);
-                if (lane == kWave - 1) nxt = (uint32_t)s_cnt[p];
-                if (lane == (B >> 3)) {
-                    const uint32_t o[9] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16, v.z & 0xFFFFu,
-                                           v.z >> 16, v.w & 0xFFFFu, v.w >> 16, nxt};
-                    uint32_t b0 = o[0], b1 = o[1];
-#pragma unroll
-                    for (int i = 1; i < 8; ++i)
-                        if ((B & 7) == i) { b0 = o[i]; b1 = o[i + 1]; }
-                    s_beg[p] = (uint16_t)b0;
-                    s_end[p] = (uint16_t)b1;
-                    s_gt[p] = (int)b0;  // every candidate of a better bin
-                }
-            }
-        } else {
-            for (int p = threadIdx.x; p < P; p += kThrNT) {
-                const int c = s_cnt[p];
-                const int b0 = c > 0 ? (int)bo[(size_t)p * kCoarseBins + B] : 0;
-                const int b1 = c > 0 ? (B + 1 < kCoarseBins ? (int)bo[(size_t)p * kCoarseBins + B + 1] : c) : 0;
-                s_beg[p] = (uint16_t)b0;
-                s_end[p] = (uint16_t)b1;
-                s_gt[p] = b0;  // every candidate of a better bin
-            }
-        }
-        __syncthreads();
-        // runs(fn, seg_end): fn(score within the bin, valid, p) for the candidates of bin B of every
-        // range p (a wave walks whole runs, one candidate per lane and round), then seg_end(p)
-        auto runs = [&](auto fn, auto seg_end) {
-            for (int p = wave; p < P; p += NW) {
-                const int b0 = __builtin_amdgcn_readfirstlane((int)s_beg[p]);
-                const int b1 = __builtin_amdgcn_readfirstlane((int)s_end[p]);
-                for (int e0 = b0; e0 < b1; e0 += kWave) {
-                    const bool valid = e0 + lane < b1;
-                    const uint32_t w = valid ? hk[(size_t)p * R + e0 + lane] : 0u;
-                    fn(w >> kIdxBits, valid, p);
-                }
-                seg_end(p);
-            }
-        };
-        // the live score range [lo, hi] within the bin, narrowed until few enough candidates remain
-        uint32_t lo = 0, hi = (1u << key_sh) - 1u;
-        for (;;) {
-            if (in_bin <= kSelCap) {
-                // gather the contenders, tagged with their range; candidates above the live range are
-                // sure winners of their range
-                int n_gt = 0;  // (wave-uniform)
-                runs([&](uint32_t key, bool valid, int p) {
-                         n_gt += __popcll(__ballot(valid && key > hi));
-                         const bool in = valid && key >= lo && key <= hi;
-                         const unsigned long long m = __ballot(in);
-                         if (m) {
-                             int o = 0;
-                             if (lane == 0) o = atomicAdd(&s_n, __popcll(m));
-                             o = __builtin_amdgcn_readfirstlane(o) + mbcnt(m);
-                             if (in && o < kSelCap) s_ck[o] = ((key - lo) << kSegBits) | (uint32_t)p;
-                         }
-                     },
-                     [&](int p) {
-                         if (lane == 0 && n_gt) s_gt[p] += n_gt;
-                         n_gt = 0;
-                     });
-                __syncthreads();
-                const int nc = min(s_n, kSelCap);
-                const uint32_t Tl = block_radix_threshold<kThrNT, 8, 2>(
-                    [&](auto fn) {
-                        for (int a0 = 0; a0 < nc; a0 += kThrNT) {
-                            const int a = a0 + threadIdx.x;
-                            fn(a < nc ? s_ck[a] >> kSegBits : 0u, a < nc);
-                        }
-                    },
-                    want, s_hist, need);
-                T = ((uint32_t)B << kThrShift) | (lo + Tl);
-                for (int a = threadIdx.x; a < nc; a += kThrNT) {
-                    const uint32_t c = s_ck[a];
-                    const uint32_t kk = c >> kSegBits;
-                    const int p = (int)(c & ((1u << kSegBits) - 1u));
-                    if (kk > Tl)
-                        atomicAdd(&s_gt[p], 1);
-                    else if (kk == Tl)
-                        atomicAdd(&s_eq[p], 1);
-                }
-                break;
-            }
-            if (lo == hi) {
-                // a single score value: count, per range, the candidates above and equal to it
-                T = ((uint32_t)B << kThrShift) | lo;
-                need = want;
-                int n_gt = 0, n_eq = 0;
-                runs([&](uint32_t key, bool valid, int) {
-                         n_gt += __popcll(__ballot(valid && key > lo));
-                         n_eq += __popcll(__ballot(valid && key == lo));
-                     },
-                     [&](int p) {
-                         if (lane == 0) {
-                             s_gt[p] += n_gt;
-                             s_eq[p] = n_eq;
-                         }
-                         n_gt = 0;
-                         n_eq = 0;
-                     });
-                break;
-            }
-            // too many: histogram of the live range over <= 512 equal bins, keep the bin with the
-            // want-th largest
-            int sh = 0;
-            while (((hi - lo) >> sh) >= 512u) ++sh;
-            __syncthreads();
-            for (int i = threadIdx.x; i < 512; i += kThrNT) s_hist[i] = 0;
-            __syncthreads();
-            runs([&](uint32_t key, bool valid, int) {
-                     const bool in = valid && key >= lo && key <= hi;
-                     hist_add(s_hist, in ? (key - lo) >> sh : 0u, in);
-                 },
-                 [&](int) {});
-            __syncthreads();
-            const int bin = block_pick_bin<kThrNT, 512>(s_hist, want, s_hist + 512, above);
-            in_bin = (int)s_hist[bin];
-            want -= above;
-            lo += (uint32_t)bin << sh;
-            hi = min(hi, lo + ((1u << sh) - 1u));
-        }
-    }
-    __syncthreads();
-    // per range: its share of the ties (lowest ranges first) and its first output slot; thread t
-    // owns the kSelMaxP / NT consecutive ranges starting at t * kSelMaxP / NT
-    constexpr int RPT = kSelMaxP / kThrNT;
-    const int p0 = RPT * (int)threadIdx.x;
-    int e_mine = 0;
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) e_mine += s_eq[p0 + i];
-    int dummy;
-    int ties_before = block_excl_scan<kThrNT>(e_mine, s_scan, dummy);
-    int al[RPT], take_mine = 0;
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) {
-        const int e = s_eq[p0 + i];
-        al[i] = max(0, min(e, need - ties_before));
-        ties_before += e;
-        take_mine += s_gt[p0 + i] + al[i];
-    }
-    int off = block_excl_scan<kThrNT>(take_mine, s_scan, dummy);
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) {
-        if (p0 + i < P) {
-            seg_par[(size_t)head * P + p0 + i] = make_int2(off, al[i]);
-            if (T != 0xFFFFFFFFu)
-                seg_run[(size_t)head * P + p0 + i] = make_int2((int)s_beg[p0 + i], (int)s_end[p0 + i]);
-        }
-        off += s_gt[p0 + i] + al[i];
-    }
-    if (threadIdx.x == 0) thr[head] = T;
 }
 
 void launch_threshold(const uint32_t *cand_key, const int32_t *seg_cnt, const uint16_t *bin_off, int32_t *sel,
