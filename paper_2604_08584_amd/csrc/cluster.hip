@@ -77,7 +77,7 @@ struct SeedArgs {  // per-problem arrays: problem p's part starts at p * its str
     int n_blk, C;
 };
 
-template <int DB>
+template <int DB, bool STRIDED>
 __global__ __launch_bounds__(256) void k_km_seed_update(Pool pool, SeedArgs a, int j, int snake)
 {
     __shared__ float s_c[DB];
@@ -107,27 +107,68 @@ __global__ __launch_bounds__(256) void k_km_seed_update(Pool pool, SeedArgs a, i
     __syncthreads();
     const float cn2 = s_cn2;
     float local = 0.0f;
+    if (STRIDED) {
+        // a mini-batch: its rows are far apart and mostly cached - one point per thread with all of its
+        // chunks requested at once measured faster (0.34 against 0.41 s for 4096 draws)
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int i = blk * kSeedPts + u * 256 + threadIdx.x;
-        if (i < pool.n_view) {
-            const int gi = pool.gid(i);
-            const uint4 *r = (const uint4 *)pool.row(p, gi);
+        for (int u = 0; u < 4; ++u) {
+            const int i = blk * kSeedPts + u * 256 + threadIdx.x;
+            if (i < pool.n_view) {
+                const int gi = pool.gid(i);
+                const uint4 *r = (const uint4 *)pool.row(p, gi);
+                float dot = 0.0f;
+#pragma unroll
+                for (int c = 0; c < DB / 8; ++c) {
+                    const uint4 w = r[c];
+                    const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                                        bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) dot = fmaf(f[e], s_c[c * 8 + e], dot);
+                }
+                const float inv = inv_norm[gi];
+                float d = inv > 0.0f ? fmaxf(0.0f, 1.0f + cn2 - 2.0f * inv * dot) : cn2;
+                if (j > 0) d = fminf(d, dist[i]);
+                dist[i] = d;
+                local += d;
+            }
+        }
+    } else {
+    // the whole pool, streamed from HBM: LPR lanes share a point (16 bytes of its sub-vector each), so a
+    // wave instruction reads whole, consecutive rows - coalesced whatever the sub-vector's length
+    constexpr int LPR = DB / 8, RPW = kWave / LPR, PER_WAVE = kSeedPts / 4;
+    constexpr int UNR = PER_WAVE / RPW < 4 ? PER_WAVE / RPW : 4;  // rows requested ahead per lane
+    const int c = lane_id() % LPR, rsub = lane_id() / LPR;
+    float cf[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cf[e] = s_c[c * 8 + e];
+    const int base = blk * kSeedPts + (int)(threadIdx.x / kWave) * PER_WAVE + rsub;
+    for (int it0 = 0; it0 < PER_WAVE / RPW; it0 += UNR) {
+        uint4 w[UNR];
+        int idx[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            idx[u] = base + (it0 + u) * RPW;
+            w[u] = make_uint4(0, 0, 0, 0);
+            if (idx[u] < pool.n_view) w[u] = *(const uint4 *)(pool.row(p, pool.gid(idx[u])) + c * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const float f[8] = {bf16_lo(w[u].x), bf16_hi(w[u].x), bf16_lo(w[u].y), bf16_hi(w[u].y),
+                                bf16_lo(w[u].z), bf16_hi(w[u].z), bf16_lo(w[u].w), bf16_hi(w[u].w)};
             float dot = 0.0f;
 #pragma unroll
-            for (int c = 0; c < DB / 8; ++c) {
-                const uint4 w = r[c];
-                const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
-                                    bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+            for (int e = 0; e < 8; ++e) dot = fmaf(f[e], cf[e], dot);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) dot = fmaf(f[e], s_c[c * 8 + e], dot);
+            for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o, kWave);
+            if (c == 0 && idx[u] < pool.n_view) {
+                const float inv = inv_norm[pool.gid(idx[u])];
+                float d = inv > 0.0f ? fmaxf(0.0f, 1.0f + cn2 - 2.0f * inv * dot) : cn2;
+                if (j > 0) d = fminf(d, dist[idx[u]]);
+                dist[idx[u]] = d;
+                local += d;
             }
-            const float inv = inv_norm[gi];
-            float d = inv > 0.0f ? fmaxf(0.0f, 1.0f + cn2 - 2.0f * inv * dot) : cn2;
-            if (j > 0) d = fminf(d, dist[i]);
-            dist[i] = d;
-            local += d;
         }
+    }
     }
     local = __shfl_xor(local, 1, kWave) + local;
     local = __shfl_xor(local, 2, kWave) + local;
@@ -652,7 +693,10 @@ hipError_t cluster_sequence_db(const uint16_t *q_seq, int n_pre, int G, int Hkv,
                           (int32_t *)(work + w.pick), u_seed, w.n_blk, C};
         const int snake = (size_t)all.n_view * DB * 2 * n_prob > ((size_t)64 << 20) ? 1 : 0;
         for (int j = 0; j < C; ++j) {
-            k_km_seed_update<DB><<<dim3(w.n_blk, n_prob), 256, 0, st>>>(all, sa, j, snake);
+            if (all.stride > 1)
+                k_km_seed_update<DB, true><<<dim3(w.n_blk, n_prob), 256, 0, st>>>(all, sa, j, snake);
+            else
+                k_km_seed_update<DB, false><<<dim3(w.n_blk, n_prob), 256, 0, st>>>(all, sa, j, snake);
             if (j + 1 < C) k_km_seed_pick<<<n_prob, 1024, 0, st>>>(sa, all.n_view, j + 1);
         }
     }
