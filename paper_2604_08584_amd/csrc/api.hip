@@ -757,8 +757,9 @@ int csa_decode_step(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *se
 int csa_decode_step_static(csa_ctx *ctx, const void *q_dev, float *out_dev, int32_t *sel_idx_dev,
                            int32_t *sel_count_dev, void *stream)
 {
-    if (!ctx) return CSA_ERR_ARG;
+    if (!ctx || !q_dev || !out_dev) return CSA_ERR_ARG;
     if (ctx->lay.decode_bytes > kStaticScratchBytes) return CSA_ERR_WORKSPACE;
+    if (!ctx->bound || !ctx->have_tables) return CSA_ERR_STATE;  // (before the device is touched)
     char *scr = nullptr;
     const int rc = static_scratch(ctx, &scr);
     if (rc != CSA_OK) return rc;

@@ -105,3 +105,33 @@ def test_product_and_oracle_do_not_reach_into_each_other():
     # the binding refuses to work without the built library instead of falling back
     src = open(os.path.join(pkg, "binding.py")).read()
     assert "raise" in src[src.index("def lib("):src.index("def lib(") + 1500]
+
+
+def test_new_entry_points_validate_on_the_host():
+    """The static-scratch step, the replayable iteration, the count sync and the one-call prefill
+    refuse bad arguments and calls out of order before anything touches the GPU."""
+    lib = binding.lib()
+    ctx = binding.csa_create(**GOOD)
+    p = C.c_void_p(256)
+    # nothing bound yet
+    assert lib.csa_decode_step_static(ctx, p, p, None, None, None) == binding.CSA_ERR_STATE
+    assert lib.csa_decode_step_append_replayable(ctx, p, p, p, p, None, None, 0, None) == binding.CSA_ERR_STATE
+    assert lib.csa_decode_step_append_replayable(ctx, p, None, p, p, None, None, 0, None) == binding.CSA_ERR_ARG
+    assert lib.csa_sync_context_len(ctx, None) == binding.CSA_ERR_STATE
+    assert lib.csa_sync_context_len(None, None) == binding.CSA_ERR_ARG
+    assert lib.csa_prefill(ctx, p, 100, 2, 1, p, p, p, 1 << 40, None) == binding.CSA_ERR_STATE
+    assert lib.csa_prefill(None, p, 100, 2, 1, p, p, p, 1 << 40, None) == binding.CSA_ERR_ARG
+    # the clustering calls need no bound buffers, but sane arguments
+    assert lib.csa_cluster_queries_minibatch(ctx, p, 100, 2, 0, p, None, p, None, None, p, 1 << 40, None) == binding.CSA_ERR_ARG
+    assert lib.csa_cluster_queries_minibatch(ctx, p, 100, 2, 401, p, None, p, None, None, p, 1 << 40, None) == binding.CSA_ERR_ARG
+    assert lib.csa_cluster_queries_minibatch(ctx, p, 100, 2, 2, None, None, p, None, None, p, 1 << 40, None) == binding.CSA_ERR_ARG
+    assert lib.csa_cluster_queries_minibatch(ctx, p, 100, 2, 2, p, None, p, None, None, p, 16, None) == binding.CSA_ERR_WORKSPACE
+    assert lib.csa_cluster_queries(ctx, p, 100, -1, p, None, p, None, None, p, 1 << 40, None) == binding.CSA_ERR_ARG
+    need, cap = binding.csa_static_scratch_bytes(ctx)
+    assert 0 < need < cap == 32 << 20
+    binding.csa_destroy(ctx)
+    # a configuration whose step does not fit the static array is refused before anything else
+    big = binding.csa_create(**{**GOOD, 'batch': 8, 'n_q_heads': 64, 'n_kv_heads': 8, 'max_ctx': 131072 + 256,
+                                'n_centroids': 4096, 'list_len': 4096, 'n_probe': 32, 'budget_k': 6554})
+    assert lib.csa_decode_step_static(big, p, p, None, None, None) == binding.CSA_ERR_WORKSPACE
+    binding.csa_destroy(big)
