@@ -102,6 +102,39 @@ def test_captured_iteration_replays_correctly(paged):
     assert torch.isfinite(b.ctx.out).all()
 
 
+def test_replayed_search_period_schedule():
+    """A schedule with search period 2 as two captured graphs - a searching iteration and a reusing
+    one (index set of the last search, left in the caller's buffers) - replayed in turn; every step
+    equals the eager twin's csa_decode_step_append with the same reuse flag."""
+    a, b = _twin(steps=8)
+    w = a.w
+    q, kn, vn = (torch.empty_like(b.inp[x][0]) for x in ("q_steps", "k_new", "v_new"))
+    for c in (a, b):                               # step 0 eagerly (a search)
+        c.ctx.decode_step_append(c.inp["q_steps"][0], c.inp["k_new"][0], c.inp["v_new"][0])
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g_search, g_reuse = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g_reuse, stream=side):
+        b.ctx.decode_step_append_replayable(q, kn, vn, reuse=True)
+    with torch.cuda.graph(g_search, stream=side):
+        b.ctx.decode_step_append_replayable(q, kn, vn)
+    binding.csa_sync_context_len(b.ctx.ctx)
+    for step in range(1, w.steps):
+        reuse = step % 2 == 1
+        if reuse:
+            a.ctx.decode_step_reuse_append(a.inp["q_steps"][step], a.inp["k_new"][step], a.inp["v_new"][step])
+        else:
+            a.ctx.decode_step_append(a.inp["q_steps"][step], a.inp["k_new"][step], a.inp["v_new"][step])
+        q.copy_(b.inp["q_steps"][step]); kn.copy_(b.inp["k_new"][step]); vn.copy_(b.inp["v_new"][step])
+        torch.cuda.synchronize()
+        (g_reuse if reuse else g_search).replay()
+        torch.cuda.synchronize()
+        _same(f"{'reuse' if reuse else 'search'} replay at step {step}", a, b)
+    binding.csa_sync_context_len(b.ctx.ctx)
+    assert binding.csa_context_len(b.ctx.ctx)[1] == w.n_pre + w.steps
+
+
 def test_replayable_form_is_refused_with_streaming_updates():
     c = Case(small("replay_stream", steps=2), seed=2, F=13, stream_window=8)
     c.build_on_gpu()
