@@ -160,17 +160,24 @@ class Case:
         n = self.w.n_pre + self.t
         return max(0, n - self.stream_window) if self.stream_window else self.w.n_pre
 
-    def decode(self, step):
+    def decode(self, step, static=False):
+        """static: through csa_decode_step_static (the step's temporaries in the library's own array)."""
         q = self.inp["q_steps"][step]
-        out, sel, cnt = self.ctx.decode_step(q)
+        if static:
+            binding.csa_decode_step_static(self.ctx.ctx, q, self.ctx.out, self.ctx.sel, self.ctx.sel_count)
+            out, sel, cnt = self.ctx.out, self.ctx.sel, self.ctx.sel_count
+        else:
+            out, sel, cnt = self.ctx.decode_step(q)
         rows = self.ctx.probed_rows()
         torch.cuda.synchronize()
         return out.cpu().numpy(), sel.cpu().numpy(), cnt.cpu().numpy(), rows.cpu().numpy()
 
-    def decode_append(self, step):
-        """The fused call: decode step `step`, then the append of the next K/V row (one call)."""
+    def decode_append(self, step, replayable=False):
+        """The fused call: decode step `step`, then the append of the next K/V row (one call);
+        replayable: its form with the context length read on the device."""
         q = self.inp["q_steps"][step]
-        out, sel, cnt = self.ctx.decode_step_append(q, self.inp["k_new"][self.t], self.inp["v_new"][self.t])
+        call = self.ctx.decode_step_append_replayable if replayable else self.ctx.decode_step_append
+        out, sel, cnt = call(q, self.inp["k_new"][self.t], self.inp["v_new"][self.t])
         rows = self.ctx.probed_rows()
         torch.cuda.synchronize()
         return out.cpu().numpy(), sel.cpu().numpy(), cnt.cpu().numpy(), rows.cpu().numpy()
@@ -205,7 +212,7 @@ class Case:
             sel[b, h, :o_cnt[t]] = np.asarray(o_sel[t])[:o_cnt[t]]
         return sel, cnt
 
-    def check_step(self, step, heads=None, fused_append=False, groups=None):
+    def check_step(self, step, heads=None, fused_append=False, groups=None, static=False, replayable=False):
         """Decode on both sides, compare; returns the max-abs output error.  fused_append: the GPU
         side uses the one-call form that also appends the next K/V row (the oracle decodes on the
         context before that append, then the host mirrors it)."""
@@ -214,10 +221,10 @@ class Case:
             heads = [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
         o_rows, o_sel, o_cnt, o_out = self.oracle_decode(step, heads)
         if fused_append:
-            out, sel, cnt, rows = self.decode_append(step)
+            out, sel, cnt, rows = self.decode_append(step, replayable=replayable)
             self._mirror_append(groups)
         else:
-            out, sel, cnt, rows = self.decode(step)
+            out, sel, cnt, rows = self.decode(step, static=static)
         worst = 0.0
         for t, (b, h) in enumerate(heads):
             tag = f"{w.name} step {step} head ({b},{h})"
@@ -231,7 +238,7 @@ class Case:
         return worst
 
 
-    def check_reuse_step(self, step, sel, cnt, heads=None, pass_buffers=False, fused_append=False):
+    def check_reuse_step(self, step, sel, cnt, heads=None, pass_buffers=False, fused_append=False, replayable=False):
         """A search-period step: attention of step `step`'s query over the index set (sel, cnt) of
         an earlier searching step plus everything appended so far; compared with the oracle.
         fused_append: the GPU side uses the one-call form that also appends the next K/V row."""
@@ -242,7 +249,10 @@ class Case:
         bufs = (torch.from_numpy(sel).cuda(), torch.from_numpy(cnt).cuda()) if pass_buffers else ()
         n = w.n_pre + self.t                      # the context this step attends to
         start = self.window_start()
-        if fused_append:
+        if fused_append and replayable:     # (the library's copy of the index set)
+            out = self.ctx.decode_step_append_replayable(q, self.inp["k_new"][self.t], self.inp["v_new"][self.t],
+                                                         reuse=True)[0]
+        elif fused_append:
             out = self.ctx.decode_step_reuse_append(q, self.inp["k_new"][self.t], self.inp["v_new"][self.t], *bufs)
         else:
             out = self.ctx.decode_step_reuse(q, *bufs)

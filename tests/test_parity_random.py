@@ -19,11 +19,18 @@ def _check_all_tables(case):
 
 
 def _steps_with_random_call_forms(case, rng, steps):
+    """Each step through one of the forms of the call: the plain step (its temporaries in the bound
+    scratch buffer or in the library's static array) followed by an append, or the one-call iteration
+    (plain, or - without streaming updates - the replayable form with the position on the device)."""
     for step in range(steps):
-        fused = rng.random() < 0.5
-        case.check_step(step, fused_append=fused)
-        if not fused:
+        form = rng.choice(["plain", "static", "fused", "fused", "replayable"])
+        if form == "replayable" and case.stream_window:
+            form = "fused"
+        if form in ("plain", "static"):
+            case.check_step(step, static=(form == "static"))
             case.append(1)
+        else:
+            case.check_step(step, fused_append=True, replayable=(form == "replayable"))
 
 
 @pytest.mark.parametrize("seed", [11, 12])
@@ -85,8 +92,9 @@ def test_random_tiny_shapes(seed):
 
 @pytest.mark.parametrize("seed", [31, 32])
 def test_random_schedules(seed):
-    """Searching steps, search-period steps (the library's copy of the index set or the caller's,
-    with or without the append in the same call) and appends of one or two rows in random order."""
+    """Searching steps (also through the static-scratch form), search-period steps (the library's copy of
+    the index set or the caller's, with or without the append in the same call, also in the replayable
+    form) and appends of one or two rows in random order."""
     rng = random.Random(seed)
     for ci in range(20):
         S = rng.choice([1, 1, 2, 8])
@@ -107,17 +115,21 @@ def test_random_schedules(seed):
         for step in range(steps - 2):
             if case.t >= steps - 2:
                 break
-            op = rng.choice(["search", "search+append", "reuse", "reuse given", "reuse+append", "append"])
+            op = rng.choice(["search", "search static", "search+append", "search+append replayable", "reuse",
+                             "reuse given", "reuse+append", "reuse+append replayable", "append"])
             if sel is None and op.startswith("reuse"):
                 op = "search"
+            if stream and op.endswith("replayable"):
+                op = op[:-len(" replayable")]
             ops.append(op)
             print(ci, w, "stream", stream, ops, flush=True)
             if op.startswith("search"):
                 sel, cnt = case.oracle_index_set(step)
-                case.check_step(step, fused_append=op.endswith("+append"))
+                case.check_step(step, fused_append="+append" in op, static=op.endswith("static"),
+                                replayable=op.endswith("replayable"))
             elif op.startswith("reuse"):
                 case.check_reuse_step(step, sel, cnt, pass_buffers=(op == "reuse given"),
-                                      fused_append=op.endswith("+append"))
+                                      fused_append="+append" in op, replayable=op.endswith("replayable"))
             else:
                 case.append(rng.choice([1, 2]))
         if stream:
