@@ -319,6 +319,12 @@ __global__ __launch_bounds__(kHeadDim) void k_attention_merge(const float *__res
         return;
     }
     const float *ph = part + (size_t)blockIdx.x * S * (kHeadDim + 2);
+    // this thread's value of the first kMergePre splits, requested together with the splits' maxima
+    // and sums instead of after them: the launch is a chain of memory round trips, one less this way
+    constexpr int kMergePre = 32;
+    float pv[kMergePre];
+#pragma unroll
+    for (int t = 0; t < kMergePre; ++t) pv[t] = t < S ? ph[(size_t)t * (kHeadDim + 2) + 2 + threadIdx.x] : 0.0f;
     float acc = 0.0f, l = 0.0f, M = -INFINITY;
     for (int s0 = 0; s0 < S; s0 += kHeadDim) {
         const int s = s0 + threadIdx.x;
@@ -342,7 +348,14 @@ __global__ __launch_bounds__(kHeadDim) void k_attention_merge(const float *__res
         __syncthreads();
         l += s_red[0] + s_red[1];
         const int ns = min(kHeadDim, S - s0);
-        for (int t = 0; t < ns; ++t)
+        int t_first = 0;
+        if (s0 == 0) {  // (the same additions in the same order, from the values already here)
+#pragma unroll
+            for (int t = 0; t < kMergePre; ++t)
+                if (t < ns) acc += pv[t] * s_f[t];
+            t_first = kMergePre;
+        }
+        for (int t = t_first; t < ns; ++t)
             acc += ph[(size_t)(s0 + t) * (kHeadDim + 2) + 2 + threadIdx.x] * s_f[t];
     }
     out[(size_t)blockIdx.x * kHeadDim + threadIdx.x] = l > 0.0f ? acc / l : 0.0f;

@@ -1,5 +1,7 @@
 // Search half of the decode step (paper Sec. 3.3 steps 1-4): centroid scoring, choice of the
 // probed rows, row gather with per-key score accumulation, Top-K selection.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -319,9 +321,8 @@ __device__ __forceinline__ void select_top(const float *__restrict__ zh, int C, 
     // rank the nc candidates in sm.ck[0..nc) (distinct words, larger = better) against each other and
     // keep ranks < m.  A candidate is shared by tpc adjacent lanes, each counting over a slice of the
     // others, so that the chain of LDS reads is short however many threads the workgroup has.
+    // (sm.ck[nc] must be 0 - the pad to an even count, 0 beats nothing - and the candidates visible)
     auto rank_candidates = [&](int nc) {
-        if (threadIdx.x == 0) sm.ck[nc] = 0;  // pad to an even count (0 beats nothing)
-        __syncthreads();
         int sh = 0;
         while (sh < 4 && ((nc * 2) << sh) <= NT) ++sh;  // tpc = 2^sh lanes per candidate (uniform)
         const int tpc = 1 << sh, part = (int)threadIdx.x & (tpc - 1);
@@ -343,11 +344,14 @@ __device__ __forceinline__ void select_top(const float *__restrict__ zh, int C, 
     };
     if (C <= 256) {
         // ---- few centroids: every value is a candidate
-        for (int j = threadIdx.x; j < C; j += NT)
-            sm.ck[j] = ((uint64_t)orderable(zh[j]) << 32) | (uint32_t)~(uint32_t)j;
+        for (int j = threadIdx.x; j <= C; j += NT)
+            sm.ck[j] = j < C ? ((uint64_t)orderable(zh[j]) << 32) | (uint32_t)~(uint32_t)j : 0ull;
+        __syncthreads();
         rank_candidates(C);
         return;
     }
+    // (the candidate array starts out as zeros: whatever the count turns out to be, its pad is there)
+    for (int e = threadIdx.x; e < kTopCand + 2; e += NT) sm.ck[e] = 0ull;
     const bool in_regs = C <= NT * kTopReg;
     uint32_t kreg[kTopReg];
     if (in_regs) {
@@ -530,39 +534,35 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     const int p = blockIdx.x, head = blockIdx.y;
     const int bg = head / G;
     const int wave = threadIdx.x / kWave, lane = lane_id();
-    if (SELF_TOP) {
-        static_assert(!SELF_TOP || sizeof(TopSmem<NT>) <= (size_t)R * 4, "the choice borrows the accumulators' memory");
-        static_assert(!SELF_TOP || 2 * NT >= 64 * NB, "two offsets per thread cover m * NB");
-        TopSmem<NT> &sm = *reinterpret_cast<TopSmem<NT> *>(s_acc);  // (the accumulators are not in use yet)
-        select_top<NT>(z + (size_t)head * C, C, m, sm);
-        __syncthreads();
-        const int my_row = (int)threadIdx.x < m ? sm.rows[threadIdx.x] : 0;
-        int32_t off[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int e = u * NT + (int)threadIdx.x;
-            const int r = e / NB, x = e - r * NB;
-            off[u] = e < m * NB ? part_off[((size_t)bg * C + sm.rows[r]) * PO + p * NSUB + x] : 0;
-        }
-        __syncthreads();  // (every thread has read the choice: the memory may be zeroed now)
-        if ((int)threadIdx.x < m) {
-            s_row[threadIdx.x] = my_row;
-            if (p == 0) rows[(size_t)head * m + threadIdx.x] = my_row;
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-            if (u * NT + (int)threadIdx.x < m * NB) s_b[u * NT + threadIdx.x] = off[u];
-    }
     {
-        if (!SELF_TOP) {
-            const int32_t *sp = spans + ((size_t)head * P + p) * m * NB;
-            for (int e = threadIdx.x; e < m * NB; e += NT) s_b[e] = sp[e];
-            if ((int)threadIdx.x < m) s_row[threadIdx.x] = rows[(size_t)head * m + threadIdx.x];
-        }
         int4 *z4 = (int4 *)s_acc;
 #pragma unroll
         for (int u = 0; u < 4; ++u) z4[u * NT + threadIdx.x] = make_int4(0, 0, 0, 0);
         for (int e = threadIdx.x; e < kCoarseBins; e += NT) s_h[e] = 0;
+    }
+    if (SELF_TOP) {
+        static_assert(!SELF_TOP || 2 * NT >= 64 * NB, "two offsets per thread cover m * NB");
+        // (LDS of its own - 10 KiB, three workgroups per CU instead of four, which a launch this small
+        // does not fill anyway - so that the accumulators are zeroed while the scores are on their way)
+        __shared__ typename std::conditional<SELF_TOP, TopSmem<NT>, int>::type s_top;
+        TopSmem<NT> &sm = *reinterpret_cast<TopSmem<NT> *>(&s_top);
+        select_top<NT>(z + (size_t)head * C, C, m, sm);
+        __syncthreads();
+        if ((int)threadIdx.x < m) {
+            const int my_row = sm.rows[threadIdx.x];
+            s_row[threadIdx.x] = my_row;
+            if (p == 0) rows[(size_t)head * m + threadIdx.x] = my_row;
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int e = u * NT + (int)threadIdx.x;
+            const int r = e / NB, x = e - r * NB;
+            if (e < m * NB) s_b[e] = part_off[((size_t)bg * C + sm.rows[r]) * PO + p * NSUB + x];
+        }
+    } else {
+        const int32_t *sp = spans + ((size_t)head * P + p) * m * NB;
+        for (int e = threadIdx.x; e < m * NB; e += NT) s_b[e] = sp[e];
+        if ((int)threadIdx.x < m) s_row[threadIdx.x] = rows[(size_t)head * m + threadIdx.x];
     }
     __syncthreads();
     // slot of an entry = (its block within the range) * kUnit + (low index bits) - off0
