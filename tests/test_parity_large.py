@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 from paper_2604_08584_amd import binding
-from paper_2604_08584_amd.workload import CONFIGS
+from paper_2604_08584_amd.workload import CONFIGS, Workload
 
 from harness import Case
 
@@ -127,6 +127,19 @@ def test_paper_default_geometry_full_size():
     heads = [(0, 0), (0, 3), (3, 20), (7, 28), (7, 31)]
     for step in range(2):
         print("paper_s8 step", step, "err", case.check_step(step, heads))
+        case.append(1)
+
+
+def test_long_context_with_the_widest_key_ranges():
+    """A 144K context in ranges of 16384 keys (the widest the library offers: 1024-thread accumulation
+    workgroups with two blocks per range, 512-thread workgroups writing the winners); every head of
+    two KV heads, two steps."""
+    w = Workload("long144k", 1, 8, 2, 128, 147000, 64, 512, 2048, 16, 7350, 2, 0, 0, kmeans_iters=3)
+    case = Case(w, F=-1, partition_keys=16384, gen_device="cuda", kmeans_sample=16 * w.C)
+    case.build_on_gpu()
+    heads = [(0, h) for h in range(8)]
+    for step in range(2):
+        print("long144k step", step, "err", case.check_step(step, heads))
         case.append(1)
 
 
