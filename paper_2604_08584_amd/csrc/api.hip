@@ -690,7 +690,7 @@ int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int3
                           ctx->R, ctx->P, l.cand_keys, ctx->key_sh, st);
     prof.end(3);
     // the second half of the Top-K runs in the prologue of the attention workgroups when a key
-    // range has one bitmap word per attention thread and the launch is small (it then saves a
+    // range has at most one bitmap word per attention thread and the launch is small (it then saves a
     // launch, 4 us of 66 at batch 1); with thousands of workgroups the prologue's latency delays
     // every workgroup's K/V stream and a kernel of its own measured 7 us of 390 faster
     const bool fused = c.budget_k > 0 && csa::attention_can_emit(ctx->R) && (int64_t)BH * S <= 2048;

@@ -35,8 +35,8 @@ constexpr int kSplit = kAttWaves * kItemsPerWave;  // 512 attended keys per work
 // (max, sum, o[128]) per (head, split).
 // EMIT: the workgroup of a key range first finishes the Top-K for that range itself (second half of
 // Sec. 3.3 (4): compare the range's candidates with the head's threshold, write the winners'
-// indices into `sel`) and then attends what it wrote - possible when a range has one bitmap word
-// per thread (R = 8192); it saves a launch, and this latency-bound piece runs while other
+// indices into `sel`) and then attends what it wrote - possible when a range has at most one bitmap
+// word per thread (R <= 8192); it saves a launch, and this latency-bound piece runs while other
 // workgroups stream K/V.  Otherwise `sel` is read as given (Top-K done by a kernel before, or a
 // reused / caller-made index set).
 // grid ceil8(B*Hkv*S) * G workgroups (1-D, see the id mapping below), block 256.
@@ -395,7 +395,7 @@ void launch_attention_split(const void *q, const void *kc, const void *vc,
 #undef CSA_ATT
 }
 
-bool attention_can_emit(int R) { return R == 32 * kAttNT; }
+bool attention_can_emit(int R) { return R <= 32 * kAttNT; }
 
 void launch_attention_merge(const float *part, float *out, int n_heads, int S, hipStream_t st)
 {

@@ -492,8 +492,10 @@ def test_device_side_errors_are_reported():
 
 
 def test_profile_counters_cover_every_stage():
-    w = small("prof", steps=2, pre_appended=0)
-    case = Case(w, seed=11, F=12, partition_keys=2048)   # (ranges too small for the fused launches: every stage runs)
+    # 64 heads of 40 key ranges each: too many workgroups for the accumulation launch to choose the probed
+    # rows itself or for the attention launch to write the winners, so every stage is a launch of its own
+    w = small("prof", batch=4, n_q_heads=16, n_kv_heads=4, n_pre=40000, L=900, k=2000, steps=2, pre_appended=0)
+    case = Case(w, seed=11, F=12, partition_keys=1024)
     case.import_oracle_tables()
     binding.csa_profile_enable(case.ctx.ctx, True)
     case.decode(0)
