@@ -521,7 +521,7 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
                                                    int m, int G, int P, size_t cand_stride,
                                                    uint32_t key_lo, int key_sh, int excl_from,
                                                    const float *__restrict__ z,
-                                                   const int32_t *__restrict__ part_off, int PO)
+                                                   const int32_t *__restrict__ part_off, int PO, int c_sh)
 {
     constexpr int NW = NT / kWave;
     constexpr int R = NT * 16;
@@ -568,7 +568,11 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
     // slot of an entry = (its block within the range) * kUnit + (low index bits) - off0
     const int off0 = (p * R) & (kUnit - 1);  // non-zero only for ranges smaller than a block
     constexpr int kChunk = kWave * 4;  // entries of one round of 16-byte loads
-    for (int r0 = wave; r0 < m; r0 += kAccRows * NW) {
+    // With few probed rows (the paper's geometry: one long row per subspace) a row's slice is cut into
+    // 2^c_sh pieces that are walked as rows of their own, so that the workgroup still has kAccRows * NW
+    // loads in flight instead of a few waves walking long slices round after round.
+    const int mv = m << c_sh;
+    for (int r0 = wave; r0 < mv; r0 += kAccRows * NW) {
         int lo[kAccRows], hi[kAccRows], b1[kAccRows], b2[kAccRows], b3[kAccRows];
         int n_wide[kAccRows], n_tail[kAccRows];
         const uint32_t *rp[kAccRows];
@@ -580,14 +584,14 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
         {
             const int jj = lane % kAccRows, what = lane / kAccRows;  // what: lo, hi, b1, b2, b3, row
             const int r = r0 + jj * NW;
-            const int rr = r < m ? r : r0;
+            const int rr = (r < mv ? r : r0) >> c_sh;
             const int within = what == 1 ? NSUB : what == 0 ? 0 : what - 1;
             const int32_t *src = what == 5 ? s_row + rr : s_b + rr * NB + min(within, NSUB);
             if (what <= 5) gv = *src;
         }
 #pragma unroll
         for (int j = 0; j < kAccRows; ++j) {
-            const bool on = r0 + j * NW < m;
+            const bool on = r0 + j * NW < mv;
             lo[j] = __builtin_amdgcn_readlane(gv, 0 * kAccRows + j);
             hi[j] = on ? __builtin_amdgcn_readlane(gv, 1 * kAccRows + j) : lo[j];  // empty if no such row
             b1[j] = NSUB > 1 ? __builtin_amdgcn_readlane(gv, 2 * kAccRows + j) : 0x7FFFFFFF;
@@ -595,6 +599,11 @@ __global__ __launch_bounds__(NT) void k_accumulate(const uint32_t *__restrict__ 
             b3[j] = NSUB > 2 ? __builtin_amdgcn_readlane(gv, 4 * kAccRows + j) : 0x7FFFFFFF;
             rp[j] = ent + ((size_t)bg * C + __builtin_amdgcn_readlane(gv, 5 * kAccRows + j)) * Ls;
             lo[j] = min(lo[j], hi[j]);
+            if (c_sh) {  // this piece of the slice
+                const int piece = (r0 + j * NW) & ((1 << c_sh) - 1), len = hi[j] - lo[j];
+                hi[j] = lo[j] + ((len * (piece + 1)) >> c_sh);
+                lo[j] = lo[j] + ((len * piece) >> c_sh);
+            }
             // the slice from its 16-byte boundary: rounds of 16 bytes per lane, and - when what is
             // left after them fits one entry per lane - one such round instead of a mostly idle wide
             // one (a slice of a 1/P share of a row is typically a little over one wide round)
@@ -729,6 +738,14 @@ void launch_accumulate(const void *ent, int32_t *rows, const int32_t *spans, uin
                        bool self_top, hipStream_t st)
 {
     dim3 grid(P, n_heads);
+    // pieces per row slice: as many as keep every wave's row slots busy, while a piece still holds at
+    // least ~128 entries
+    int c_sh = 0;
+    {
+        const int slots = kAccRows * (R / 16 / kWave);
+        const int per_slice = Ls / (P > 0 ? P : 1);
+        while (c_sh < 5 && (m << (c_sh + 1)) <= slots && (per_slice >> (c_sh + 1)) >= 128) ++c_sh;
+    }
     static bool attr = false;
     if (!attr) {
         (void)hipFuncSetAttribute((const void *)k_accumulate<1024, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -740,7 +757,7 @@ void launch_accumulate(const void *ent, int32_t *rows, const int32_t *spans, uin
 #define CSA_ACC(NT_, SELF_)                                                                                \
     k_accumulate<NT_, SELF_><<<grid, NT_, (size_t)R * 4, st>>>((const uint32_t *)ent, rows, spans, cand_key, \
                                                                bin_off, seg_cnt, C, Ls, m, G, P, cand_stride, \
-                                                               key_lo, key_sh, excl_from, z, part_off, PO)
+                                                               key_lo, key_sh, excl_from, z, part_off, PO, c_sh)
     if (self_top) {  // (R >= 4096: see accumulate_self_top)
         switch (R) {
         case 4096: CSA_ACC(256, true); break;
