@@ -195,7 +195,7 @@ void choose_partition(csa_ctx *ctx, int n_pre)
     if (!R) {
         // the accumulation kernel runs R/16 threads per key range, so the wave count does not
         // depend on R; larger ranges amortise per-row work, but at least ~512 workgroups are wanted
-        // and 8192 keys (512 threads, four workgroups per CU) measured best on MI355X
+        // and 8192 keys (512 threads, three workgroups at a time per CU) measured best on MI355X
         // With few heads and a short context the step is a chain of small launches, and ranges of
         // at least 4096 keys keep that chain short (the accumulation launch then also chooses the
         // probed rows): 32 heads at 32K context, 43.8 us per step with 2048-key ranges, 38.8 with 4096
