@@ -107,6 +107,21 @@ def test_subspace_geometry(S, tau, C):
     case2.check_step(0)
 
 
+@pytest.mark.parametrize("S,tau,L,part", [(1, 2, 2000, 8192), (8, 1, 1800, 8192), (1, 1, 3000, 16384), (2, 3, 1100, 4096)])
+def test_few_long_rows_are_walked_in_pieces(S, tau, L, part):
+    """Few probed rows with long lists (the paper's geometry has one row of 0.1 N entries per
+    subspace): the accumulation launch walks a row's slice of a key range as 2, 4, 8 or more pieces
+    handled like rows of their own.  Selected indices and outputs must not change with that: every
+    head, two steps with an append in between, ragged last range."""
+    w = small(f"pieces{S}x{tau}", n_q_heads=4, n_kv_heads=2, n_pre=9001, C=24, L=L, m=tau, k=700,
+              steps=2, n_sub=S)
+    case = Case(w, seed=S * 100 + tau, F=13, partition_keys=part)
+    case.build_on_gpu()
+    case.check_step(0)
+    case.append(1)
+    case.check_step(1)
+
+
 def test_subspace_geometry_automatic_grid_uses_subvector_norms():
     """With S = 8 the scores are inner products of 16-dimensional sub-vectors, so the automatic
     grid is finer than the one a whole-vector norm bound would allow."""
