@@ -130,6 +130,25 @@ def test_paper_default_geometry_full_size():
         case.append(1)
 
 
+def test_cfg3_every_head_paged():
+    """All 512 (sequence, query head) pairs of config 3 (paged K/V through a scattered block table, 256
+    keys appended before the step) in one step, and 32 sampled table rows."""
+    w = _light("cfg3", 1)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=8 * w.C)
+    case.build_on_gpu()
+    _sampled_rows(case, 4, 8, seed=31)
+    case.append(w.pre_appended)
+    print("cfg3 all 512 heads err", case.check_step(w.pre_appended))
+
+
+def test_paper_geometry_every_head():
+    """All 256 (sequence, query head) pairs of the paper's default geometry at 64K context, one step."""
+    w = _light("paper_s8", 1)
+    case = Case(w, F=-1, gen_device="cuda", kmeans_sample=64 * w.C)
+    case.build_on_gpu()
+    print("paper_s8 all 256 heads err", case.check_step(0))
+
+
 def test_long_context_with_the_widest_key_ranges():
     """A 144K context in ranges of 16384 keys (the widest the library offers: 1024-thread accumulation
     workgroups with two blocks per range, 512-thread workgroups writing the winners); every head of
