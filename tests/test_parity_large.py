@@ -37,8 +37,7 @@ def test_cfg1_full_size():
     case = Case(w, F=-1, gen_device="cuda", kmeans_sample=16 * w.C)
     case.build_on_gpu()
     _check_rows(case, 0, 3, [0, 511, 1023])
-    heads = [(0, h) for h in (0, 1, 2, 3, 12, 13, 30, 31)]
-    print("cfg1 err", case.check_step(0, heads))
+    print("cfg1 all 32 heads err", case.check_step(0))
 
 
 def test_cfg2_full_size_with_appends():
