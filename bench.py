@@ -207,6 +207,15 @@ def decode_bench(args, name, K, W, with_cpu):
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- clocks: the chip has idled through the host-side set-up, and a short warm-up (a few steps are
+    # a few milliseconds) leaves it short of its sustained clock; some tens of milliseconds of the same
+    # steps first, untimed like the warm-up
+    if not streaming:
+        n_ramp = min(64, w.steps)
+        for _ in range((128 + n_ramp - 1) // n_ramp):
+            reset()
+            run(n_ramp)
+        torch.cuda.synchronize()
     # ---- warm-up, then the timed region (exactly K steps)
     reset()
     run(W)
