@@ -45,6 +45,7 @@ struct Layout {
     // build and the streaming insertion use
     Region z, rows, spans, cand, bin_off, cand_cnt, seg_par, seg_run, thr, sel, sel_count, part, flags, qs;
     Region queue_n, queue;  // rows waiting for the streaming insertion
+    Region z_key;           // centroid scores of the key a streaming one-call iteration appends
     size_t scratch_bytes = 0, decode_bytes = 0;
     int P_max = 0, PO_max = 0, S_max = 0, Ls = 0;
     size_t cand_keys = 0;  // candidate slots per head
@@ -139,6 +140,7 @@ Layout make_layout(const csa_config &c)
         const size_t n_seg = (size_t)c.n_subspaces * ((c.n_centroids + 1023) / 1024);  // queue segments per KV head
         put(l.queue_n, BG * n_seg * 4);
         put(l.queue, BG * n_seg * 1024 * 16);
+        put(l.z_key, BG * (size_t)c.n_centroids * 4);  // the appended key's centroid scores (one subspace)
     }
     l.scratch_bytes = off;
     return l;
@@ -564,12 +566,13 @@ int csa_export_tables(const csa_ctx *ctx, int32_t b, int32_t g, int32_t *idx_dev
 namespace {
 
 // streaming update of the tables with the key just appended at position ctx->n (Sec. 3.3 (5))
-void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, hipStream_t st)
+// z_key: the new key's centroid scores if the step's scoring launch computed them, else NULL
+void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, const float *z_key, hipStream_t st)
 {
     const csa_config &c = ctx->cfg;
     const Layout &l = ctx->lay;
     prof.mark(9);
-    csa::launch_insert(k_new_dev, at<void>(ctx->tables, l.cent_t), at<void>(ctx->tables, l.ent),
+    csa::launch_insert(k_new_dev, z_key, at<void>(ctx->tables, l.cent_t), at<void>(ctx->tables, l.ent),
                        at<int32_t>(ctx->tables, l.part_off), at<int32_t>(ctx->tables, l.row_cnt),
                        at<int32_t>(ctx->tables, l.row_min), at<int32_t>(ctx->tables, l.blk_min),
                        at<int32_t>(ctx->scratch, l.queue_n),
@@ -582,7 +585,7 @@ void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, hipStream_t st)
 // the split merge that ends a step; with k_new/v_new also the append of row n (same launch) and,
 // with streaming updates, the try-insert
 void finish_step(csa_ctx *ctx, Prof &prof, const float *part, float *out_dev, int S, const void *k_new_dev,
-                 const void *v_new_dev, bool replayable, hipStream_t st)
+                 const void *v_new_dev, bool replayable, const float *z_key, hipStream_t st)
 {
     const csa_config &c = ctx->cfg;
     const int BH = c.batch * c.n_q_heads;
@@ -596,7 +599,7 @@ void finish_step(csa_ctx *ctx, Prof &prof, const float *part, float *out_dev, in
                                        k_new_dev, v_new_dev, c.batch, c.n_kv_heads, ctx->n, c.max_ctx, n_word(ctx),
                                        full_word(ctx), replayable, st);
     prof.end(6);
-    if (streaming) run_insert(ctx, prof, k_new_dev, st);
+    if (streaming) run_insert(ctx, prof, k_new_dev, z_key, st);
     ctx->n += 1;
 }
 
@@ -615,7 +618,7 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
     csa::launch_append(ctx->k_cache, ctx->v_cache, ctx->block_table, k_new_dev, v_new_dev, c.batch,
                        c.n_kv_heads, ctx->n, c.max_ctx, n_word(ctx), st);
     prof.end(7);
-    if (streaming) run_insert(ctx, prof, k_new_dev, st);
+    if (streaming) run_insert(ctx, prof, k_new_dev, nullptr, st);
     ctx->n += 1;
     return check_launch(ctx);
 }
@@ -660,6 +663,7 @@ int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int3
     prof.mark(0);
     int32_t *spans = at<int32_t>(scr, l.spans);
     bool self_top = false;
+    float *z_key = nullptr;
     if (csa::score_top_fused(c.n_centroids, S_sub, c.n_probe)) {
         // the paper's own geometry: scoring and the choice of the probed rows in one launch
         csa::launch_score_top_sub(q_dev, at<void>(ctx->tables, l.cent_t), rows, at<int32_t>(ctx->tables, l.part_off),
@@ -668,8 +672,10 @@ int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int3
         prof.end(0);
         prof.mark(2);
     } else {
+        // with streaming updates the key this call appends is scored in the same pass over the centroids
+        if (c.stream_window > 0 && k_new_dev && S_sub == 1) z_key = at<float>(ctx->scratch, l.z_key);
         csa::launch_score_centroids(q_dev, at<void>(ctx->tables, l.cent_t), z, c.batch, c.n_kv_heads, G,
-                                    c.n_centroids, S_sub, st);
+                                    c.n_centroids, S_sub, k_new_dev, z_key, st);
         prof.end(0);
         // a small launch chooses the probed rows inside the accumulation launch (a kernel less in
         // the chain of dependent launches: 61 -> 57 us per step at batch 1, 128K)
@@ -705,7 +711,7 @@ int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int3
                                 c.max_ctx, S, ctx->P, fused ? cand_key : nullptr, seg_run, cand_cnt, thr,
                                 ctx->R, l.cand_keys, n_dev, st);
     prof.end(5);
-    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, replayable, st);
+    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, replayable, z_key, st);
     ctx->last_sel = sel;
     ctx->last_scratch = scr;
     ctx->last_sel_count = sel_count;
@@ -742,7 +748,7 @@ int reuse_step(csa_ctx *ctx, const void *q_dev, float *out_dev, const int32_t *s
                                 c.n_kv_heads, c.budget_k, ws, ctx->n, c.max_ctx, S, ctx->P, nullptr, nullptr,
                                 nullptr, nullptr, ctx->R, l.cand_keys, replayable ? n_word(ctx) : nullptr, st);
     prof.end(5);
-    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, replayable, st);
+    finish_step(ctx, prof, part, out_dev, S, k_new_dev, v_new_dev, replayable, nullptr, st);
     return check_launch(ctx);
 }
 

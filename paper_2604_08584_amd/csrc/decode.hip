@@ -18,12 +18,18 @@ namespace csa {
 // EARLY (a launch of few workgroups, where latency is everything): the centroid is requested before
 // the queries are staged - one memory round trip instead of two; on a full chip the early loads only
 // hold back the staging (16 -> 26 us at batch 8).
-template <int GH, bool EARLY>
+// KEY (streaming updates, one-call iteration): the key about to be appended is scored against the
+// same centroids in the same pass - z_key[bg][j] = c[bg][j] . k_new[bg], the same fma chain - so the
+// try-insert after the step need not stream the centroid matrix again.
+template <int GH, bool EARLY, bool KEY>
 __global__ __launch_bounds__(256) void k_score_centroids(const uint16_t *__restrict__ q,
                                                          const uint4 *__restrict__ cent_t,
-                                                         float *__restrict__ z, int C, int G)
+                                                         float *__restrict__ z, int C, int G,
+                                                         const uint16_t *__restrict__ k_new,
+                                                         float *__restrict__ z_key)
 {
-    __shared__ float s_q[GH][kHeadDim];
+    constexpr int NV = GH + (KEY ? 1 : 0);  // vectors scored per pass: GH queries (+ the new key, as the last)
+    __shared__ float s_q[NV][kHeadDim];
     const int bg = blockIdx.y;
     const int j = blockIdx.x * 256 + threadIdx.x;
     const uint4 *ct = cent_t + (size_t)bg * (kHeadDim / 8) * C;
@@ -38,11 +44,13 @@ __global__ __launch_bounds__(256) void k_score_centroids(const uint16_t *__restr
             const int hh = e / kHeadDim, t = e % kHeadDim;
             s_q[hh][t] = __uint_as_float((uint32_t)q[((size_t)bg * G + h0 + hh) * kHeadDim + t] << 16);
         }
+        if (KEY && threadIdx.x < kHeadDim)  // (scored again in every pass over the heads: G > 8 is rare)
+            s_q[NV - 1][threadIdx.x] = __uint_as_float((uint32_t)k_new[(size_t)bg * kHeadDim + threadIdx.x] << 16);
         __syncthreads();
         if (j < C) {
-            float acc[GH];
+            float acc[NV];
 #pragma unroll
-            for (int hh = 0; hh < GH; ++hh) acc[hh] = 0.0f;
+            for (int hh = 0; hh < NV; ++hh) acc[hh] = 0.0f;
             if (!EARLY) {
 #pragma unroll
                 for (int c = 0; c < kHeadDim / 8; ++c) wv[c] = ct[(size_t)c * C + j];
@@ -55,12 +63,13 @@ __global__ __launch_bounds__(256) void k_score_centroids(const uint16_t *__restr
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
 #pragma unroll
-                    for (int hh = 0; hh < GH; ++hh)
+                    for (int hh = 0; hh < NV; ++hh)
                         acc[hh] = __builtin_fmaf(s_q[hh][c * 8 + e], cf[e], acc[hh]);
             }
 #pragma unroll
             for (int hh = 0; hh < GH; ++hh)
                 z[((size_t)bg * G + h0 + hh) * C + j] = acc[hh] + 0.0f;  // -0 -> +0
+            if (KEY) z_key[(size_t)bg * C + j] = acc[NV - 1];
         }
     }
 }
@@ -240,7 +249,7 @@ void launch_score_top_sub(const void *q, const void *cent_t, int32_t *rows, cons
 }
 
 void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
-                            int C, int S, hipStream_t st)
+                            int C, int S, const void *k_new, float *z_key, hipStream_t st)
 {
     dim3 block(256);
     const int gh = heads_per_pass(G);
@@ -249,10 +258,12 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
         const bool early = (int64_t)grid.x * grid.y <= 256;
 #define CSA_SC(GH_)                                                                                            \
     do {                                                                                                       \
-        if (early)                                                                                             \
-            k_score_centroids<GH_, true><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G); \
+        if (z_key)  /* (S == 1 only: see score_key_fused) */                                                   \
+            k_score_centroids<GH_, false, true><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, (const uint16_t *)k_new, z_key); \
+        else if (early)                                                                                        \
+            k_score_centroids<GH_, true, false><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, nullptr, nullptr); \
         else                                                                                                   \
-            k_score_centroids<GH_, false><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G); \
+            k_score_centroids<GH_, false, false><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, nullptr, nullptr); \
     } while (0)
         switch (gh) {
         case 8: CSA_SC(8); break;

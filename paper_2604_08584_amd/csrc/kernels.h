@@ -28,7 +28,9 @@ void launch_build_select(const int32_t *qs, void *ent, int32_t *part_off, int jc
                          int Ls, int Q, int PO, hipStream_t st);
 void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt, int32_t *row_min, int32_t *blk_min,
                       int64_t n_rows, int Ls, int PO, hipStream_t st);
-void launch_insert(const void *k_new, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
+// z_key != NULL: the new key's centroid scores are already there (k_score_centroids with KEY): the
+// try test reads them instead of streaming the centroids (one subspace only)
+void launch_insert(const void *k_new, const float *z_key, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
                    int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *clamped, int B, int Hkv, int C,
                    int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st);
 void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
@@ -42,8 +44,9 @@ int cluster_sequence(const void *q_seq, int n_pre, int G, int Hkv, int S, int C,
                      int32_t *assign_out, void *work, hipStream_t st);
 
 // ---- decode.hip
+// z_key != NULL (one subspace only): also z_key[bg][j] = centroid j of KV head bg . k_new[bg]
 void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, int Hkv, int G,
-                            int C, int S, hipStream_t st);
+                            int C, int S, const void *k_new, float *z_key, hipStream_t st);
 // both of the above in one launch (several subspaces, C <= 256, few probes per subspace)
 bool score_top_fused(int C, int S, int tau);
 void launch_score_top_sub(const void *q, const void *cent_t, int32_t *rows, const int32_t *part_off,
