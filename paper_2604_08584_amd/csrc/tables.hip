@@ -560,16 +560,32 @@ __global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ en
         const int b0 = pol[ue], b1 = pol[ue + 1];
         unsigned long long best = 0ull;  // (low index bits + 1, position): larger wins
         int n_min = 0, min2 = 0x7FFFFFFF;
-        for (int p = b0 + lane; p < b1; p += kWave) {
-            const uint32_t e = re[p];
-            const int q = entry_q(e);
-            if (q == mn) {
-                ++n_min;
-                const unsigned long long cand =
-                    ((unsigned long long)((e & (uint32_t)(kUnit - 1)) + 1u) << 32) | (uint32_t)p;
-                best = cand > best ? cand : best;
-            } else {
-                min2 = min(min2, q);
+        // (eight entries per lane requested together: with long rows - the paper's geometry keeps a tenth
+        // of the context per row - a block holds hundreds of entries, and one request per round trip
+        // would make this read the longest part of the insertion)
+        constexpr int kBlkFlight = 8;
+        for (int p0 = b0 + lane; p0 < b1; p0 += kBlkFlight * kWave) {
+            uint32_t ev[kBlkFlight];
+#pragma unroll
+            for (int u = 0; u < kBlkFlight; ++u) {
+                const int p = p0 + u * kWave;
+                ev[u] = p < b1 ? re[p] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kBlkFlight; ++u) {
+                const int p = p0 + u * kWave;
+                if (p < b1) {
+                    const uint32_t e = ev[u];
+                    const int q = entry_q(e);
+                    if (q == mn) {
+                        ++n_min;
+                        const unsigned long long cand =
+                            ((unsigned long long)((e & (uint32_t)(kUnit - 1)) + 1u) << 32) | (uint32_t)p;
+                        best = cand > best ? cand : best;
+                    } else {
+                        min2 = min(min2, q);
+                    }
+                }
             }
         }
         for (int o = 32; o > 0; o >>= 1) {
