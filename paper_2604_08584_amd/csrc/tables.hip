@@ -686,8 +686,13 @@ void launch_insert(const void *k_new, const float *z_key, const void *cent_t, vo
                                                 (int4 *)queue, clamped, C, S, L, ldexpf(1.0f, F), qmax);
     // the queue lengths are only known on the device: enough waves for one row each in the usual
     // case (a few percent of the rows take a new key), striding when there are more
+    // A row takes the new key with probability about L / (context length): one wave per 8 rows covers
+    // the 3 % of 128K-context tables with lists of 4096; long lists in few rows (the paper's geometry:
+    // a tenth of the rows) get three waves per expected row, up to one per row
     const int per_seg = C < kScanNT ? C : kScanNT;  // rows behind a segment
-    const int waves = per_seg / 8 < 1 ? 1 : per_seg / 8;  // one wave per 8 rows (about 3 % take a key, unevenly)
+    int waves = per_seg / 8 < 1 ? 1 : per_seg / 8;
+    const int64_t expect3 = 3 * (int64_t)per_seg * L / (idx_new > 0 ? idx_new : 1);
+    if (expect3 > waves) waves = (int)(expect3 < per_seg ? expect3 : per_seg);
     k_insert_rows<<<dim3(waves, n_seg, B * Hkv), kWave, 0, st>>>((uint32_t *)ent, part_off, row_cnt, row_min, blk_min, queue_n,
                                                       (const int4 *)queue, n_seg, L, Ls, Q, PO, idx_new);
 }
