@@ -566,13 +566,14 @@ int csa_export_tables(const csa_ctx *ctx, int32_t b, int32_t g, int32_t *idx_dev
 namespace {
 
 // streaming update of the tables with the key just appended at position ctx->n (Sec. 3.3 (5))
-// z_key: the new key's centroid scores if the step's scoring launch computed them, else NULL
-void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, const float *z_key, hipStream_t st)
+// z_key: the new key's centroid scores if the step's scoring launch computed them, else NULL;
+// tried: the try test on those scores has run already (in the step's merge launch)
+void run_insert(csa_ctx *ctx, Prof &prof, const void *k_new_dev, const float *z_key, bool tried, hipStream_t st)
 {
     const csa_config &c = ctx->cfg;
     const Layout &l = ctx->lay;
     prof.mark(9);
-    csa::launch_insert(k_new_dev, z_key, at<void>(ctx->tables, l.cent_t), at<void>(ctx->tables, l.ent),
+    csa::launch_insert(k_new_dev, z_key, tried, at<void>(ctx->tables, l.cent_t), at<void>(ctx->tables, l.ent),
                        at<int32_t>(ctx->tables, l.part_off), at<int32_t>(ctx->tables, l.row_cnt),
                        at<int32_t>(ctx->tables, l.row_min), at<int32_t>(ctx->tables, l.blk_min),
                        at<int32_t>(ctx->scratch, l.queue_n),
@@ -595,11 +596,21 @@ void finish_step(csa_ctx *ctx, Prof &prof, const float *part, float *out_dev, in
         return;
     }
     const bool streaming = c.stream_window > 0;
+    // with the new key's centroid scores at hand its try test rides in the merge launch (it reads the
+    // tables' row states, which nothing in this launch writes)
+    const bool try_here = streaming && z_key && c.n_subspaces == 1 && !replayable;
+    const Layout &l = ctx->lay;
+    csa::TryArgs tr{};
+    if (try_here)
+        tr = csa::insert_try_args(z_key, at<int32_t>(ctx->tables, l.row_cnt), at<int32_t>(ctx->tables, l.row_min),
+                                  at<int32_t>(ctx->scratch, l.queue_n), at<void>(ctx->scratch, l.queue),
+                                  at<int32_t>(ctx->tables, l.state), c.n_centroids, c.list_len, ctx->F,
+                                  qmax_for(c.n_probe * c.n_subspaces));
     csa::launch_attention_merge_append(part, out_dev, BH, S, ctx->k_cache, ctx->v_cache, ctx->block_table,
                                        k_new_dev, v_new_dev, c.batch, c.n_kv_heads, ctx->n, c.max_ctx, n_word(ctx),
-                                       full_word(ctx), replayable, st);
+                                       full_word(ctx), replayable, try_here ? &tr : nullptr, st);
     prof.end(6);
-    if (streaming) run_insert(ctx, prof, k_new_dev, z_key, st);
+    if (streaming) run_insert(ctx, prof, k_new_dev, z_key, try_here, st);
     ctx->n += 1;
 }
 
@@ -618,7 +629,7 @@ int csa_append_kv(csa_ctx *ctx, const void *k_new_dev, const void *v_new_dev, vo
     csa::launch_append(ctx->k_cache, ctx->v_cache, ctx->block_table, k_new_dev, v_new_dev, c.batch,
                        c.n_kv_heads, ctx->n, c.max_ctx, n_word(ctx), st);
     prof.end(7);
-    if (streaming) run_insert(ctx, prof, k_new_dev, nullptr, st);
+    if (streaming) run_insert(ctx, prof, k_new_dev, nullptr, false, st);
     ctx->n += 1;
     return check_launch(ctx);
 }

@@ -273,6 +273,10 @@ struct AppendArgs {
     // which then advances the count; otherwise the count is set to n + 1.
     int32_t *n_word, *full_word;
     int from_dev, n_bg;
+    // streaming updates: n_try further workgroups (one per queue segment) run the try test of the key
+    // being appended against the tables (its centroid scores were taken by the step's scoring launch)
+    int n_try;
+    TryArgs tr;
 };
 
 template <bool PAGED>
@@ -314,8 +318,15 @@ __global__ __launch_bounds__(kHeadDim) void k_attention_merge(const float *__res
             }
             return;
         }
-        if (threadIdx.x < 32) append_row<APPEND == 2>(ap, ap.n, (int)blockIdx.x - n_heads, (int)threadIdx.x);
-        if ((int)blockIdx.x == n_heads && threadIdx.x == 0) *ap.n_word = ap.n + 1;
+        const int extra = (int)blockIdx.x - n_heads;
+        if (extra >= ap.n_bg) {  // (never in a replayable launch: streaming updates exclude it)
+            __shared__ int s_try_n;
+            const int seg = extra - ap.n_bg;
+            insert_try_segment<kHeadDim>(ap.tr, seg / ap.tr.nx, seg % ap.tr.nx, &s_try_n);
+            return;
+        }
+        if (threadIdx.x < 32) append_row<APPEND == 2>(ap, ap.n, extra, (int)threadIdx.x);
+        if (extra == 0 && threadIdx.x == 0) *ap.n_word = ap.n + 1;
         return;
     }
     const float *ph = part + (size_t)blockIdx.x * S * (kHeadDim + 2);
@@ -405,11 +416,13 @@ void launch_attention_merge(const float *part, float *out, int n_heads, int S, h
 void launch_attention_merge_append(const float *part, float *out, int n_heads, int S, void *kc, void *vc,
                                    const int32_t *block_table, const void *kn, const void *vn, int B,
                                    int Hkv, int n, int max_ctx, int32_t *n_word, int32_t *full_word,
-                                   bool from_dev, hipStream_t st)
+                                   bool from_dev, const TryArgs *tr, hipStream_t st)
 {
+    const int n_try = tr && !from_dev ? B * Hkv * tr->nx : 0;
     const AppendArgs ap{(uint16_t *)kc, (uint16_t *)vc, block_table, (const uint16_t *)kn,
-                        (const uint16_t *)vn, n, Hkv, max_ctx, n_word, full_word, from_dev ? 1 : 0, B * Hkv};
-    const int grid = n_heads + (from_dev ? 1 : B * Hkv);
+                        (const uint16_t *)vn, n, Hkv, max_ctx, n_word, full_word, from_dev ? 1 : 0, B * Hkv,
+                        n_try, n_try ? *tr : TryArgs{}};
+    const int grid = n_heads + (from_dev ? 1 : B * Hkv) + n_try;
     if (block_table)
         k_attention_merge<2><<<grid, kHeadDim, 0, st>>>(part, out, S, n_heads, ap);
     else
@@ -428,7 +441,7 @@ void launch_append(void *kc, void *vc, const int32_t *block_table, const void *k
                    int B, int Hkv, int n, int max_ctx, int32_t *n_word, hipStream_t st)
 {
     const AppendArgs ap{(uint16_t *)kc, (uint16_t *)vc, block_table, (const uint16_t *)kn,
-                        (const uint16_t *)vn, n, Hkv, max_ctx, n_word, nullptr, 0, B * Hkv};
+                        (const uint16_t *)vn, n, Hkv, max_ctx, n_word, nullptr, 0, B * Hkv, 0, TryArgs{}};
     if (block_table)
         k_append<true><<<B * Hkv, 32, 0, st>>>(ap);
     else

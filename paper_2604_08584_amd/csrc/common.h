@@ -226,6 +226,54 @@ __device__ __forceinline__ uint32_t block_radix_threshold(ForEach for_each, int 
 
 
 // ---------------------------------------------------------------------------------------------
+// Streaming updates (Sec. 3.3 (5)), the try test with the new key's centroid scores given: row j of
+// KV head bg takes the key if it has room or the key's grid score beats the row's minimum.  Rows
+// that take it are queued, with their state, in the queue segment of their 1024 rows (kScanNT);
+// the segment's count is written, not added to.  All NT threads of a workgroup call (NT divides
+// kScanNT); *s_n is an LDS word of the workgroup.  One subspace.
+// ---------------------------------------------------------------------------------------------
+template <int NT>
+__device__ __forceinline__ void insert_try_segment(const TryArgs &a, int bg, int x, int *s_n)
+{
+    constexpr int PER = kScanNT / NT;
+    if (threadIdx.x == 0) *s_n = 0;
+    __syncthreads();
+    float zk[PER];
+    int cnt[PER], mn[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {  // (every load before the first use)
+        const int j = x * kScanNT + u * NT + (int)threadIdx.x;
+        const int64_t row = (int64_t)bg * a.C + (j < a.C ? j : a.C - 1);
+        zk[u] = a.z_key[row];
+        cnt[u] = a.row_cnt[row];
+        mn[u] = a.row_min[row];
+    }
+    const size_t seg = (size_t)bg * a.nx + x;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int j = x * kScanNT + u * NT + (int)threadIdx.x;
+        const bool live = j < a.C;
+        float qf = rintf(zk[u] * a.up);
+        if (!(fabsf(qf) <= (float)a.qmax)) {
+            if (live) atomicOr(a.clamped, 1);
+            qf = qf > 0.0f ? (float)a.qmax : -(float)a.qmax;  // (a NaN cannot occur: inputs are finite)
+        }
+        const int q = (int)qf;
+        const bool take = live && (cnt[u] < a.L || q > mn[u]);
+        const uint64_t mask = __ballot(take);
+        if (mask) {  // one LDS counter update per wave
+            int base = 0;
+            if (lane_id() == __ffsll((unsigned long long)mask) - 1) base = atomicAdd(s_n, __popcll(mask));
+            base = __builtin_amdgcn_readlane(base, __ffsll((unsigned long long)mask) - 1);
+            if (take)  // (the row's state travels along)
+                a.queue[seg * kScanNT + base + mbcnt(mask)] = make_int4((int)((int64_t)bg * a.C + j), q, cnt[u], mn[u]);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) a.queue_n[seg] = *s_n;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Candidate words.  The accumulation kernel leaves the candidates of (head, key range) grouped by
 // coarse bin of their accumulated score, best bin first: word = (score bits below the bin) <<
 // kIdxBits | key index within the range, with the start offset of every bin in bin_off[.][512]

@@ -258,7 +258,9 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
         const bool early = (int64_t)grid.x * grid.y <= 256;
 #define CSA_SC(GH_)                                                                                            \
     do {                                                                                                       \
-        if (z_key)  /* (S == 1 only: see score_key_fused) */                                                   \
+        if (z_key && early)                                                                                    \
+            k_score_centroids<GH_, true, true><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, (const uint16_t *)k_new, z_key); \
+        else if (z_key)                                                                                        \
             k_score_centroids<GH_, false, true><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, (const uint16_t *)k_new, z_key); \
         else if (early)                                                                                        \
             k_score_centroids<GH_, true, false><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, z, C, G, nullptr, nullptr); \

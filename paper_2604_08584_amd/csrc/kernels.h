@@ -14,6 +14,20 @@ constexpr int kUnit = 1 << kUnitBits;
 constexpr int kQBits = 32 - kUnitBits;
 constexpr int32_t kQLimit = (1 << (kQBits - 1)) - 1;  // |q| <= kQLimit
 
+// Streaming updates: the rows that take a new key wait in queue segments of kScanNT rows each; what the
+// try test of a key whose centroid scores are given needs (insert_try_segment in common.h).
+constexpr int kScanNT = 1024;
+struct TryArgs {
+    const float *z_key;  // [B*Hkv][C]: centroid j . new key, the table build's fma chain
+    const int32_t *row_cnt, *row_min;
+    int32_t *queue_n;
+    int4 *queue;
+    int32_t *clamped;  // set when a score left the grid and was clamped
+    int C, L, nx;      // centroids per KV head, list length, segments per KV head
+    float up;          // 2^F
+    int qmax;          // largest admissible |grid score|
+};
+
 // ---- tables.hip
 void launch_pack_centroids(const void *cent, void *cent_t, int n_bg, int C, int S, hipStream_t st);
 void launch_import_rows(const int32_t *idx, const float *score, void *ent, int32_t *part_off,
@@ -30,7 +44,10 @@ void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt
                       int64_t n_rows, int Ls, int PO, hipStream_t st);
 // z_key != NULL: the new key's centroid scores are already there (k_score_centroids with KEY): the
 // try test reads them instead of streaming the centroids (one subspace only)
-void launch_insert(const void *k_new, const float *z_key, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
+// tried: that test has already run (in the merge launch of the step, see launch_attention_merge_append)
+TryArgs insert_try_args(const float *z_key, const int32_t *row_cnt, const int32_t *row_min, int32_t *queue_n,
+                        void *queue, int32_t *clamped, int C, int L, int F, int qmax);
+void launch_insert(const void *k_new, const float *z_key, bool tried, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
                    int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *clamped, int B, int Hkv, int C,
                    int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st);
 void launch_max_key_norm(const void *kc, const int32_t *block_table, float *out, int B, int Hkv,
@@ -91,10 +108,12 @@ void launch_attention_merge(const float *part, float *out, int n_heads, int S, h
 // the merge, and in the same launch the append of row n; *n_word (the device's copy of the context
 // length) becomes n + 1.  from_dev: the position is *n_word itself, not `n` (replayable); an append
 // to a full context is skipped and recorded in *full_word.
+// tr != NULL (streaming updates, the new key's centroid scores at hand): the try test of the key
+// runs in further workgroups of this launch, one per queue segment.
 void launch_attention_merge_append(const float *part, float *out, int n_heads, int S, void *kc, void *vc,
                                    const int32_t *block_table, const void *kn, const void *vn, int B,
                                    int Hkv, int n, int max_ctx, int32_t *n_word, int32_t *full_word,
-                                   bool from_dev, hipStream_t st);
+                                   bool from_dev, const TryArgs *tr, hipStream_t st);
 void launch_append(void *kc, void *vc, const int32_t *block_table, const void *kn, const void *vn,
                    int B, int Hkv, int n, int max_ctx, int32_t *n_word, hipStream_t st);
 

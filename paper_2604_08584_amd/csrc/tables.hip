@@ -422,7 +422,6 @@ void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt
 // global atomics - on this multi-die part thousands of returning atomics on a few addresses cost
 // more than the scan itself - and nothing to clear between steps.
 // grid (ceil(C/1024), S, B*Hkv), block 1024; segment id = (bg*S + s) * gridDim.x + x.
-constexpr int kScanNT = 1024;
 
 __global__ __launch_bounds__(kScanNT) void k_insert_scan(const uint16_t *__restrict__ k_new,
                                                      const uint4 *__restrict__ cent_t,
@@ -634,53 +633,31 @@ __global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ en
     }
 }
 
-// The same try test with the new key's centroid scores given (one subspace): z_key[bg][j] is the fma
-// chain the scan above computes.  grid (ceil(C / kScanNT), 1, B*Hkv), block kScanNT.
-__global__ __launch_bounds__(kScanNT) void k_insert_try(const float *__restrict__ z_key,
-                                                    const int32_t *__restrict__ row_cnt,
-                                                    const int32_t *__restrict__ row_min,
-                                                    int32_t *__restrict__ queue_n,
-                                                    int4 *__restrict__ queue,
-                                                    int32_t *__restrict__ clamped, int C, int L, float up,
-                                                    int qmax)
+// The try test with the new key's centroid scores given (insert_try_segment), as a launch of its own.
+// grid (ceil(C / kScanNT), 1, B*Hkv), block kScanNT.
+__global__ __launch_bounds__(kScanNT) void k_insert_try(TryArgs a)
 {
     __shared__ int s_n;
-    const int bg = blockIdx.z;
-    const int j = blockIdx.x * kScanNT + threadIdx.x;
-    if (threadIdx.x == 0) s_n = 0;
-    __syncthreads();
-    const bool live = j < C;
-    const int jc = live ? j : C - 1;
-    const int64_t row = (int64_t)bg * C + jc;
-    const int cnt = row_cnt[row], mn = row_min[row];
-    float qf = rintf(z_key[row] * up);
-    if (!(fabsf(qf) <= (float)qmax)) {
-        atomicOr(clamped, 1);
-        qf = qf > 0.0f ? (float)qmax : -(float)qmax;
-    }
-    const int q = (int)qf;
-    const size_t seg = (size_t)bg * gridDim.x + blockIdx.x;
-    const bool take = live && (cnt < L || q > mn);
-    const uint64_t mask = __ballot(take);
-    if (mask) {
-        int base = 0;
-        if (lane_id() == __ffsll((unsigned long long)mask) - 1) base = atomicAdd(&s_n, __popcll(mask));
-        base = __builtin_amdgcn_readlane(base, __ffsll((unsigned long long)mask) - 1);
-        if (take) queue[seg * kScanNT + base + mbcnt(mask)] = make_int4((int)row, q, cnt, mn);
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) queue_n[seg] = s_n;
+    insert_try_segment<kScanNT>(a, (int)blockIdx.z, (int)blockIdx.x, &s_n);
 }
 
-void launch_insert(const void *k_new, const float *z_key, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
+TryArgs insert_try_args(const float *z_key, const int32_t *row_cnt, const int32_t *row_min, int32_t *queue_n,
+                        void *queue, int32_t *clamped, int C, int L, int F, int qmax)
+{
+    return TryArgs{z_key, row_cnt, row_min, queue_n, (int4 *)queue, clamped, C, L, (C + kScanNT - 1) / kScanNT,
+                   ldexpf(1.0f, F), qmax};
+}
+
+void launch_insert(const void *k_new, const float *z_key, bool tried, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
                    int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *clamped, int B, int Hkv, int C,
                    int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st)
 {
     const int nx = (C + kScanNT - 1) / kScanNT, n_seg = S * nx;  // (n_seg <= 64: checked at create)
     dim3 grid(nx, S, B * Hkv);
-    if (z_key && S == 1)
-        k_insert_try<<<grid, kScanNT, 0, st>>>(z_key, row_cnt, row_min, queue_n, (int4 *)queue, clamped, C, L,
-                                               ldexpf(1.0f, F), qmax);
+    if (tried) {
+        // (the try test rode in an earlier launch of the step: the queues are filled)
+    } else if (z_key && S == 1)
+        k_insert_try<<<grid, kScanNT, 0, st>>>(insert_try_args(z_key, row_cnt, row_min, queue_n, queue, clamped, C, L, F, qmax));
     else
         k_insert_scan<<<grid, kScanNT, 0, st>>>((const uint16_t *)k_new, (const uint4 *)cent_t, row_cnt, row_min, queue_n,
                                                 (int4 *)queue, clamped, C, S, L, ldexpf(1.0f, F), qmax);
