@@ -140,7 +140,7 @@ Layout make_layout(const csa_config &c)
         const size_t n_seg = (size_t)c.n_subspaces * ((c.n_centroids + 1023) / 1024);  // queue segments per KV head
         put(l.queue_n, BG * n_seg * 4);
         put(l.queue, BG * n_seg * 1024 * 16);
-        put(l.z_key, BG * (size_t)c.n_centroids * 4);  // the appended key's centroid scores (one subspace)
+        put(l.z_key, BG * Ct * 4);  // the appended key's centroid scores
     }
     l.scratch_bytes = off;
     return l;
@@ -598,13 +598,13 @@ void finish_step(csa_ctx *ctx, Prof &prof, const float *part, float *out_dev, in
     const bool streaming = c.stream_window > 0;
     // with the new key's centroid scores at hand its try test rides in the merge launch (it reads the
     // tables' row states, which nothing in this launch writes)
-    const bool try_here = streaming && z_key && c.n_subspaces == 1 && !replayable;
+    const bool try_here = streaming && z_key && !replayable;
     const Layout &l = ctx->lay;
     csa::TryArgs tr{};
     if (try_here)
         tr = csa::insert_try_args(z_key, at<int32_t>(ctx->tables, l.row_cnt), at<int32_t>(ctx->tables, l.row_min),
                                   at<int32_t>(ctx->scratch, l.queue_n), at<void>(ctx->scratch, l.queue),
-                                  at<int32_t>(ctx->tables, l.state), c.n_centroids, c.list_len, ctx->F,
+                                  at<int32_t>(ctx->tables, l.state), c.n_centroids, c.n_subspaces, c.list_len, ctx->F,
                                   qmax_for(c.n_probe * c.n_subspaces));
     csa::launch_attention_merge_append(part, out_dev, BH, S, ctx->k_cache, ctx->v_cache, ctx->block_table,
                                        k_new_dev, v_new_dev, c.batch, c.n_kv_heads, ctx->n, c.max_ctx, n_word(ctx),
@@ -677,9 +677,11 @@ int search_step(csa_ctx *ctx, char *scr, const void *q_dev, float *out_dev, int3
     float *z_key = nullptr;
     if (csa::score_top_fused(c.n_centroids, S_sub, c.n_probe)) {
         // the paper's own geometry: scoring and the choice of the probed rows in one launch
+        // with streaming updates the key this call appends is scored in the same pass over the centroids
+        if (c.stream_window > 0 && k_new_dev) z_key = at<float>(ctx->scratch, l.z_key);
         csa::launch_score_top_sub(q_dev, at<void>(ctx->tables, l.cent_t), rows, at<int32_t>(ctx->tables, l.part_off),
                                   spans, c.batch, c.n_kv_heads, G, c.n_centroids, S_sub, c.n_probe, ctx->P,
-                                  ctx->nsub, ctx->PO, st);
+                                  ctx->nsub, ctx->PO, k_new_dev, z_key, st);
         prof.end(0);
         prof.mark(2);
     } else {

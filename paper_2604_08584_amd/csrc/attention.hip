@@ -418,7 +418,7 @@ void launch_attention_merge_append(const float *part, float *out, int n_heads, i
                                    int Hkv, int n, int max_ctx, int32_t *n_word, int32_t *full_word,
                                    bool from_dev, const TryArgs *tr, hipStream_t st)
 {
-    const int n_try = tr && !from_dev ? B * Hkv * tr->nx : 0;
+    const int n_try = tr && !from_dev ? B * Hkv * tr->S * tr->nx : 0;
     const AppendArgs ap{(uint16_t *)kc, (uint16_t *)vc, block_table, (const uint16_t *)kn,
                         (const uint16_t *)vn, n, Hkv, max_ctx, n_word, full_word, from_dev ? 1 : 0, B * Hkv,
                         n_try, n_try ? *tr : TryArgs{}};

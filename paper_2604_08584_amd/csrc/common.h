@@ -227,10 +227,10 @@ __device__ __forceinline__ uint32_t block_radix_threshold(ForEach for_each, int 
 
 // ---------------------------------------------------------------------------------------------
 // Streaming updates (Sec. 3.3 (5)), the try test with the new key's centroid scores given: row j of
-// KV head bg takes the key if it has room or the key's grid score beats the row's minimum.  Rows
+// (KV head, subspace) pair bg takes the key if it has room or the key's grid score beats the row's minimum.  Rows
 // that take it are queued, with their state, in the queue segment of their 1024 rows (kScanNT);
 // the segment's count is written, not added to.  All NT threads of a workgroup call (NT divides
-// kScanNT); *s_n is an LDS word of the workgroup.  One subspace.
+// kScanNT); *s_n is an LDS word of the workgroup.
 // ---------------------------------------------------------------------------------------------
 template <int NT>
 __device__ __forceinline__ void insert_try_segment(const TryArgs &a, int bg, int x, int *s_n)

@@ -131,15 +131,20 @@ __global__ __launch_bounds__(256) void k_score_centroids_sub(const uint16_t *__r
 // grid (1, S, B*Hkv), block 256.
 constexpr int kFusedTau = 4;
 
-template <int GH>
+template <int GH, bool KEY>
 __global__ __launch_bounds__(256) void k_score_top_sub(const uint16_t *__restrict__ q,
                                                        const uint4 *__restrict__ cent_t,
                                                        int32_t *__restrict__ rows,
                                                        const int32_t *__restrict__ part_off,
                                                        int32_t *__restrict__ spans, int C, int G, int S,
-                                                       int tau, int P, int nsub, int PO)
+                                                       int tau, int P, int nsub, int PO,
+                                                       const uint16_t *__restrict__ k_new,
+                                                       float *__restrict__ z_key)
 {
-    __shared__ float s_q[GH][kHeadDim / 2];
+    // KEY (streaming updates, one-call iteration): the key about to be appended is scored as one more
+    // vector of the pass, z_key[bg][sub][j] = centroid (sub, j) . k_new[bg] over the subspace's dimensions
+    constexpr int NV = GH + (KEY ? 1 : 0);
+    __shared__ float s_q[NV][kHeadDim / 2];
     __shared__ unsigned long long s_best[256 / kWave][GH];  // per wave and head: (key, ~centroid)
     __shared__ int32_t s_rows[GH][kFusedTau];
     const int sub = blockIdx.y, bg = blockIdx.z;
@@ -157,12 +162,14 @@ __global__ __launch_bounds__(256) void k_score_top_sub(const uint16_t *__restric
             const int hh = e / db, t = e % db;
             s_q[hh][t] = __uint_as_float((uint32_t)q[((size_t)bg * G + h0 + hh) * kHeadDim + sub * db + t] << 16);
         }
+        if (KEY && (int)threadIdx.x < db)  // (scored again in every pass over the heads: G > 8 is rare)
+            s_q[NV - 1][threadIdx.x] = __uint_as_float((uint32_t)k_new[(size_t)bg * kHeadDim + sub * db + threadIdx.x] << 16);
         __syncthreads();
         uint32_t key[GH];  // order-preserving image of z; 0 = no centroid / already taken
         {
-            float acc[GH];
+            float acc[NV];
 #pragma unroll
-            for (int hh = 0; hh < GH; ++hh) acc[hh] = 0.0f;
+            for (int hh = 0; hh < NV; ++hh) acc[hh] = 0.0f;
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 if (c < nch) {
@@ -172,12 +179,13 @@ __global__ __launch_bounds__(256) void k_score_top_sub(const uint16_t *__restric
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
 #pragma unroll
-                        for (int hh = 0; hh < GH; ++hh)
+                        for (int hh = 0; hh < NV; ++hh)
                             acc[hh] = __builtin_fmaf(s_q[hh][c * 8 + e], cf[e], acc[hh]);
                 }
             }
 #pragma unroll
             for (int hh = 0; hh < GH; ++hh) key[hh] = j < C ? orderable(acc[hh] + 0.0f) : 0u;  // -0 -> +0
+            if (KEY && j < C) z_key[((size_t)bg * S + sub) * C + j] = acc[NV - 1];
         }
         for (int r = 0; r < tau; ++r) {
 #pragma unroll
@@ -229,12 +237,18 @@ bool score_top_fused(int C, int S, int tau) { return S > 1 && C <= 256 && tau <=
 
 void launch_score_top_sub(const void *q, const void *cent_t, int32_t *rows, const int32_t *part_off,
                           int32_t *spans, int B, int Hkv, int G, int C, int S, int tau, int P, int nsub,
-                          int PO, hipStream_t st)
+                          int PO, const void *k_new, float *z_key, hipStream_t st)
 {
     dim3 grid(1, S, B * Hkv), block(256);
 #define CSA_ST(GH_)                                                                                    \
-    k_score_top_sub<GH_><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, rows, part_off, \
-                                                 spans, C, G, S, tau, P, nsub, PO)
+    do {                                                                                               \
+        if (z_key)                                                                                     \
+            k_score_top_sub<GH_, true><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, rows, part_off, \
+                                                               spans, C, G, S, tau, P, nsub, PO, (const uint16_t *)k_new, z_key); \
+        else                                                                                           \
+            k_score_top_sub<GH_, false><<<grid, block, 0, st>>>((const uint16_t *)q, (const uint4 *)cent_t, rows, part_off, \
+                                                                spans, C, G, S, tau, P, nsub, PO, nullptr, nullptr); \
+    } while (0)
     switch (heads_per_pass(G)) {
     case 8: CSA_ST(8); break;
     case 7: CSA_ST(7); break;

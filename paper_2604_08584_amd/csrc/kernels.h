@@ -18,12 +18,12 @@ constexpr int32_t kQLimit = (1 << (kQBits - 1)) - 1;  // |q| <= kQLimit
 // try test of a key whose centroid scores are given needs (insert_try_segment in common.h).
 constexpr int kScanNT = 1024;
 struct TryArgs {
-    const float *z_key;  // [B*Hkv][C]: centroid j . new key, the table build's fma chain
+    const float *z_key;  // [B*Hkv][S][C]: centroid (s, j) . new key over subspace s, the table build's fma chain
     const int32_t *row_cnt, *row_min;
     int32_t *queue_n;
     int4 *queue;
     int32_t *clamped;  // set when a score left the grid and was clamped
-    int C, L, nx;      // centroids per KV head, list length, segments per KV head
+    int C, L, nx, S;   // centroids per (KV head, subspace), list length, segments per (KV head, subspace), subspaces
     float up;          // 2^F
     int qmax;          // largest admissible |grid score|
 };
@@ -46,7 +46,7 @@ void launch_row_stats(const void *ent, const int32_t *part_off, int32_t *row_cnt
 // try test reads them instead of streaming the centroids (one subspace only)
 // tried: that test has already run (in the merge launch of the step, see launch_attention_merge_append)
 TryArgs insert_try_args(const float *z_key, const int32_t *row_cnt, const int32_t *row_min, int32_t *queue_n,
-                        void *queue, int32_t *clamped, int C, int L, int F, int qmax);
+                        void *queue, int32_t *clamped, int C, int S, int L, int F, int qmax);
 void launch_insert(const void *k_new, const float *z_key, bool tried, const void *cent_t, void *ent, int32_t *part_off, int32_t *row_cnt,
                    int32_t *row_min, int32_t *blk_min, int32_t *queue_n, void *queue, int32_t *clamped, int B, int Hkv, int C,
                    int S, int L, int Ls, int Q, int PO, int F, int qmax, int idx_new, hipStream_t st);
@@ -66,9 +66,10 @@ void launch_score_centroids(const void *q, const void *cent_t, float *z, int B, 
                             int C, int S, const void *k_new, float *z_key, hipStream_t st);
 // both of the above in one launch (several subspaces, C <= 256, few probes per subspace)
 bool score_top_fused(int C, int S, int tau);
+// z_key != NULL: also z_key[bg][s][j] = centroid (s, j) . k_new[bg] over subspace s
 void launch_score_top_sub(const void *q, const void *cent_t, int32_t *rows, const int32_t *part_off,
                           int32_t *spans, int B, int Hkv, int G, int C, int S, int tau, int P, int nsub,
-                          int PO, hipStream_t st);
+                          int PO, const void *k_new, float *z_key, hipStream_t st);
 void launch_top_centroids(const float *z, int32_t *rows, const int32_t *part_off, int32_t *spans,
                           int n_heads, int C, int S, int tau, int G, int P, int nsub, int PO, hipStream_t st);
 // candidates of (head, key range): cand_key (words grouped by coarse score bin, best first),

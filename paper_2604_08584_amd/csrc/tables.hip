@@ -634,17 +634,17 @@ __global__ __launch_bounds__(kWave) void k_insert_rows(uint32_t *__restrict__ en
 }
 
 // The try test with the new key's centroid scores given (insert_try_segment), as a launch of its own.
-// grid (ceil(C / kScanNT), 1, B*Hkv), block kScanNT.
+// grid (ceil(C / kScanNT), S, B*Hkv), block kScanNT.
 __global__ __launch_bounds__(kScanNT) void k_insert_try(TryArgs a)
 {
     __shared__ int s_n;
-    insert_try_segment<kScanNT>(a, (int)blockIdx.z, (int)blockIdx.x, &s_n);
+    insert_try_segment<kScanNT>(a, (int)(blockIdx.z * gridDim.y + blockIdx.y), (int)blockIdx.x, &s_n);
 }
 
 TryArgs insert_try_args(const float *z_key, const int32_t *row_cnt, const int32_t *row_min, int32_t *queue_n,
-                        void *queue, int32_t *clamped, int C, int L, int F, int qmax)
+                        void *queue, int32_t *clamped, int C, int S, int L, int F, int qmax)
 {
-    return TryArgs{z_key, row_cnt, row_min, queue_n, (int4 *)queue, clamped, C, L, (C + kScanNT - 1) / kScanNT,
+    return TryArgs{z_key, row_cnt, row_min, queue_n, (int4 *)queue, clamped, C, L, (C + kScanNT - 1) / kScanNT, S,
                    ldexpf(1.0f, F), qmax};
 }
 
@@ -656,8 +656,8 @@ void launch_insert(const void *k_new, const float *z_key, bool tried, const void
     dim3 grid(nx, S, B * Hkv);
     if (tried) {
         // (the try test rode in an earlier launch of the step: the queues are filled)
-    } else if (z_key && S == 1)
-        k_insert_try<<<grid, kScanNT, 0, st>>>(insert_try_args(z_key, row_cnt, row_min, queue_n, queue, clamped, C, L, F, qmax));
+    } else if (z_key)
+        k_insert_try<<<grid, kScanNT, 0, st>>>(insert_try_args(z_key, row_cnt, row_min, queue_n, queue, clamped, C, S, L, F, qmax));
     else
         k_insert_scan<<<grid, kScanNT, 0, st>>>((const uint16_t *)k_new, (const uint4 *)cent_t, row_cnt, row_min, queue_n,
                                                 (int4 *)queue, clamped, C, S, L, ldexpf(1.0f, F), qmax);

@@ -369,6 +369,26 @@ def test_streaming_updates_after_a_very_short_prefill(n_pre, S, C):
     binding.csa_streaming_status(case.ctx.ctx)
 
 
+@pytest.mark.parametrize("S,tau,C,paged", [(4, 2, 40, False), (8, 1, 128, True), (2, 3, 300, False)])
+def test_streaming_one_call_iterations_with_subspaces(S, tau, C, paged):
+    """Streaming updates through the one-call iteration with several subspaces: full lists, so every
+    accepted key evicts one; the tables of every KV head are compared with the oracle's after four
+    and after eight iterations, the steps themselves at every iteration.  (C = 300 takes the scoring
+    launch that leaves the try test its own pass over the centroids.)"""
+    w = small(f"stream_sub{S}", batch=2, n_q_heads=4, n_kv_heads=2, n_pre=2100, C=C, L=100, m=tau, k=150, steps=8,
+              n_sub=S, page_size=16 if paged else 0)
+    case = Case(w, seed=300 + S, F=12, partition_keys=2048, stream_window=5)
+    case.build_on_gpu()
+    for step in range(8):
+        case.check_step(step, fused_append=True)
+        if step % 4 == 3:
+            for b in range(2):
+                for g in range(2):
+                    case.check_tables(b, g)
+    binding.csa_streaming_status(case.ctx.ctx)
+    assert (case.oracle_rows(0, 0)[0] >= w.n_pre).any()
+
+
 def test_streaming_updates_report_scores_that_leave_the_grid():
     w = small("stream_ovf", n_q_heads=4, n_kv_heads=1, n_pre=500, C=8, L=64, m=2, k=50, steps=2)
     case = Case(w, seed=31, F=-1, stream_window=4)
